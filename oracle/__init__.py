@@ -1,0 +1,156 @@
+"""CPU oracle for the Squeezed Attention online path -- TEST INFRASTRUCTURE ONLY.
+
+Only the tests, the smoke check and the benchmark's CPU-baseline leg may import
+this package.  It is independent of the GPU library: no shared code, headers or
+helpers, and neither side imports the other.
+
+`squeezed_oracle.c` holds the step-by-step fp32/fp64 C implementation (built by
+`build()` with gcc); `literal.py` holds a second, literal fp64 NumPy evaluation
+of Eq. 1-3 used for brute-force checks and for classifying clusters whose score
+lies next to the threshold.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Optional
+
+import numpy as np
+
+_DIR = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_DIR, "squeezed_oracle.c")
+_LIB = os.path.join(_DIR, "liboracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (plain -O2, OpenMP over (sequence, head, query))."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared",
+                               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = C.CDLL(_LIB)
+        _lib.oracle_num_threads.restype = C.c_int
+    return _lib
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _f16(a) -> np.ndarray:
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.float16, a.dtype
+    return a
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _f32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def centroid_score(q, centroids, sizes, sm_scale):
+    """q [B,H,Lq,d] f16, centroids [H,C,d] f16, sizes [H,C] -> logits [B,H,Lq,C], row_max, denom [B,H,Lq]."""
+    q, centroids, sizes = _f16(q), _f16(centroids), _i32(sizes)
+    B, H, Lq, d = q.shape
+    Cn = centroids.shape[1]
+    assert centroids.shape == (H, Cn, d) and sizes.shape == (H, Cn)
+    logits = np.empty((B, H, Lq, Cn), np.float32)
+    row_max = np.empty((B, H, Lq), np.float32)
+    denom = np.empty((B, H, Lq), np.float32)
+    lib().oracle_centroid_score(B, H, Lq, Cn, d, C.c_float(sm_scale), _p(q), _p(centroids), _p(sizes),
+                                _p(logits), _p(row_max), _p(denom))
+    return logits, row_max, denom
+
+
+def select(logits, row_max, denom, thresh, sizes, offsets):
+    """-> keep_mask [B,H,Lq,ceil(C/32)] u32, ranges [B,H,Lq,C,2] i32, n_ranges, n_keys [B,H,Lq] i32."""
+    logits, row_max, denom, thresh = _f32(logits), _f32(row_max), _f32(denom), _f32(thresh)
+    sizes, offsets = _i32(sizes), _i32(offsets)
+    B, H, Lq, Cn = logits.shape
+    assert thresh.shape == (H,) and sizes.shape == (H, Cn) and offsets.shape == (H, Cn + 1)
+    W = (Cn + 31) // 32
+    mask = np.empty((B, H, Lq, W), np.uint32)
+    ranges = np.zeros((B, H, Lq, Cn, 2), np.int32)
+    n_ranges = np.empty((B, H, Lq), np.int32)
+    n_keys = np.empty((B, H, Lq), np.int32)
+    lib().oracle_select(B, H, Lq, Cn, _p(logits), _p(row_max), _p(denom), _p(thresh), _p(sizes), _p(offsets),
+                        _p(mask), _p(ranges), _p(n_ranges), _p(n_keys))
+    return mask, ranges, n_ranges, n_keys
+
+
+def hier_select(q, centroids1, sizes1, child_offsets, thresh1, centroids2, sizes2, offsets2, thresh2, sm_scale,
+                want_logits2: bool = False):
+    """Two-level lookup, q [B,H,1,d] or [B,H,d].  Returns dict(mask1, mask2, ranges, n_ranges, n_keys, stats[, logits2])."""
+    q = _f16(q)
+    if q.ndim == 4:
+        assert q.shape[2] == 1
+        q = np.ascontiguousarray(q[:, :, 0])
+    B, H, d = q.shape
+    centroids1, centroids2 = _f16(centroids1), _f16(centroids2)
+    sizes1, child_offsets, sizes2, offsets2 = _i32(sizes1), _i32(child_offsets), _i32(sizes2), _i32(offsets2)
+    thresh1, thresh2 = _f32(thresh1), _f32(thresh2)
+    C1, C2 = centroids1.shape[1], centroids2.shape[1]
+    assert child_offsets.shape == (H, C1 + 1) and offsets2.shape == (H, C2 + 1)
+    m1 = np.empty((B, H, (C1 + 31) // 32), np.uint32)
+    m2 = np.empty((B, H, (C2 + 31) // 32), np.uint32)
+    ranges = np.zeros((B, H, C2, 2), np.int32)
+    n_ranges = np.empty((B, H), np.int32)
+    n_keys = np.empty((B, H), np.int32)
+    stats = np.empty((B, H, 4), np.float32)
+    logits2 = np.empty((B, H, C2), np.float32) if want_logits2 else None
+    lib().oracle_hier_select(B, H, C1, C2, d, C.c_float(sm_scale), _p(q), _p(centroids1), _p(sizes1),
+                             _p(child_offsets), _p(thresh1), _p(centroids2), _p(sizes2), _p(offsets2), _p(thresh2),
+                             _p(m1), _p(m2), _p(ranges), _p(n_ranges), _p(n_keys), _p(logits2), _p(stats))
+    out = dict(mask1=m1, mask2=m2, ranges=ranges, n_ranges=n_ranges, n_keys=n_keys, stats=stats)
+    if want_logits2:
+        out["logits2"] = logits2
+    return out
+
+
+def sparse_attn(q, K_fixed, V_fixed, ranges, n_ranges, K_user, V_user, sm_scale, causal_user=False, row_sel=None):
+    """q [B,H,Lq,d]; ranges [B,H,Lq,cap,2]; -> out [B,H,Lq,d] f64, lse [B,H,Lq] f64.
+
+    `row_sel` ([B,H,Lq] bool) restricts the computation to sampled rows; other rows come back NaN.
+    """
+    q, K_fixed, V_fixed, K_user, V_user = _f16(q), _f16(K_fixed), _f16(V_fixed), _f16(K_user), _f16(V_user)
+    ranges, n_ranges = _i32(ranges), _i32(n_ranges)
+    B, H, Lq, d = q.shape
+    L = K_fixed.shape[1]
+    U = K_user.shape[2]
+    assert K_fixed.shape == (H, L, d) and V_fixed.shape == (H, L, d)
+    assert K_user.shape == (B, H, U, d) and V_user.shape == (B, H, U, d)
+    assert ranges.shape[:3] == (B, H, Lq) and ranges.shape[4] == 2 and n_ranges.shape == (B, H, Lq)
+    cap = ranges.shape[3]
+    out = np.full((B, H, Lq, d), np.nan, np.float64)
+    lse = np.full((B, H, Lq), np.nan, np.float64)
+    sel = None if row_sel is None else np.ascontiguousarray(row_sel, dtype=np.uint8)
+    lib().oracle_sparse_attn(B, H, Lq, L, U, d, C.c_float(sm_scale), int(bool(causal_user)), cap,
+                             _p(q), _p(K_fixed), _p(V_fixed), _p(ranges), _p(n_ranges), _p(K_user), _p(V_user),
+                             _p(sel), _p(out), _p(lse))
+    return out, lse
+
+
+def scores(q, centroids, sizes, sm_scale) -> np.ndarray:
+    """Cluster scores S [nq, C] of Eq. 1 for one head, from the C oracle's (x, m, D): S_i = exp(x_i-m)/D.
+
+    Shape contract of the workload module's `score_fn`: q [nq,d], centroids [C,d], sizes [C].
+    """
+    x, m, D = centroid_score(np.asarray(q)[None, None], np.asarray(centroids)[None], np.asarray(sizes)[None],
+                             sm_scale)
+    x, m, D = x[0, 0].astype(np.float64), m[0, 0].astype(np.float64), D[0, 0].astype(np.float64)
+    return np.exp(x - m[:, None]) / D[:, None]
