@@ -1,0 +1,184 @@
+/*
+ * squeezed_attention.h -- C ABI of the MI355X (gfx950) implementation of the online path of
+ * Squeezed Attention (arxiv 2411.09688): centroid scoring, threshold selection with key-range
+ * compaction, sparse flash attention for decode and prefill, and the two-level centroid lookup.
+ *
+ * Conventions shared by every entry point
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller, contiguous in the stated
+ *     layout, 16-byte aligned, and never retained after the call returns.
+ *   - fp16 tensors are IEEE binary16 passed as `const void*`; "f32"/"i32"/"u32" are 4-byte types.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue
+ *     work on it and never synchronise; outputs are valid once the stream reaches that point.
+ *   - The library allocates nothing.  Scratch is a caller-provided device workspace `ws` of at
+ *     least sq_workspace_bytes(shape, which) bytes, 256-byte aligned; its contents are private to
+ *     one call and may be reused afterwards.  Two calls that share a workspace must be ordered on
+ *     the same stream.
+ *   - Return value: SQ_OK or a negative sq_status; sq_last_error() gives a thread-local message.
+ *     Invalid arguments are rejected on the host before anything is enqueued.
+ *   - Empty selections, zero-size clusters and U == 0 are legal inputs and never fault.
+ *
+ * Data layout of the fixed context (Section 3.1: keys are clustered offline; here they are stored
+ * sorted by cluster id, so a cluster is a contiguous key range):
+ *   K_fixed, V_fixed  f16 [H, L, d]      keys/values of the fixed context, shared by all B sequences
+ *   centroids         f16 [H, C, d]      mean key of each cluster
+ *   sizes             i32 [H, C]         N_i, number of keys in cluster i (0 allowed)
+ *   offsets           i32 [H, C+1]       exclusive prefix sum of sizes; cluster i = keys
+ *                                        [offsets[i], offsets[i] + sizes[i])
+ *   thresh            f32 [H]            threshold T per head (a global T is a broadcast)
+ * Queries q are f16 [B, H, Lq, d]; user / generated keys K_user, V_user are f16 [B, H, U, d].
+ */
+#ifndef SQUEEZED_ATTENTION_H
+#define SQUEEZED_ATTENTION_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum sq_status {
+    SQ_OK = 0,
+    SQ_ERR_INVALID_ARG = -1, /* null pointer, misalignment, non-positive dimension, bad enum */
+    SQ_ERR_UNSUPPORTED = -2, /* d != 128, Lq != 1 where decode is required, device is not gfx950 */
+    SQ_ERR_WORKSPACE = -3,   /* ws == NULL or ws_bytes too small */
+    SQ_ERR_HIP = -4          /* a launch or runtime call failed; see sq_last_error() */
+} sq_status;
+
+typedef enum sq_call {
+    SQ_CALL_CENTROID_SCORE = 0,
+    SQ_CALL_SELECT = 1,
+    SQ_CALL_ATTN_DECODE = 2,
+    SQ_CALL_ATTN_PREFILL = 3,
+    SQ_CALL_HIER_SELECT = 4,
+    SQ_CALL_DECODE_STEP = 5,
+    SQ_CALL_HIER_DECODE_STEP = 6
+} sq_call;
+
+/*
+ * Problem shape.  B sequences, H heads, head dim d (must be 128), L fixed-context keys per head,
+ * C clusters per head (the fine level C2 for the two-level calls), Lq queries per sequence
+ * (1 in decode), U user keys per sequence.  sm_scale multiplies every logit, both q.C_i in Eq. 1
+ * and q.k_j in attention (Eq. 1 is an estimate of the attention softmax, so it takes the same
+ * scale; sm_scale = 1 gives the equation as printed).  causal_user != 0: query t sees user keys
+ * 0..t only (prefill; the user input follows the fixed context, which stays fully visible).
+ */
+typedef struct sq_shape_t {
+    int32_t B, H, d, L, C, Lq, U;
+    float sm_scale;
+    int32_t causal_user;
+} sq_shape_t;
+
+/* Bytes of workspace the given call needs for this shape (0 if none).  Host only. */
+size_t sq_workspace_bytes(const sq_shape_t *shape, int which_call);
+
+/* Message of the last error raised on the calling thread ("" if none).  Host only. */
+const char *sq_last_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int sq_version(void);
+
+/*
+ * Cluster scores of Eq. 1 (Section 3.2) in the max-subtracted form of Appendix D
+ * ("Generation Stage"): for every query row r = (b, h, t)
+ *     logits[r, i] = sm_scale * sum_u q[r, u] * centroids[h, i, u]          (fp32 accumulation)
+ *     row_max[r]   = max over clusters with sizes > 0 of logits[r, i]       (-inf if none)
+ *     denom[r]     = sum_i sizes[h, i] * exp(logits[r, i] - row_max[r])     (D of Appendix D)
+ * so that S_i = exp(logits[r,i] - row_max[r]) / denom[r].
+ * Out: logits f32 [B,H,Lq,C], row_max f32 [B,H,Lq], denom f32 [B,H,Lq].  No workspace needed
+ * (ws may be NULL).
+ */
+int sq_centroid_score(const sq_shape_t *shape, const void *q, const void *centroids, const int32_t *sizes,
+                      float *logits, float *row_max, float *denom,
+                      void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Threshold rule of Sections 3.2 / 4.1 ("load cluster i iff S_i > T", strict), evaluated without a
+ * division as exp(logits - row_max) > T * denom (Appendix D), followed by compaction of the kept
+ * clusters into key ranges (the key-index tensor of Section 4.2, as ranges because clusters are
+ * contiguous).  Clusters with sizes == 0 are never kept.
+ * Out: keep_mask u32 [B,H,Lq,ceil(C/32)]  bit (i % 32) of word (i / 32) = cluster i kept;
+ *      ranges    i32 [B,H,Lq,C,2]         (first key, key count) per kept cluster, ascending; entries
+ *                                         past n_ranges are left untouched.  May be NULL (mask only).
+ *      n_ranges  i32 [B,H,Lq]             number of kept clusters
+ *      n_keys    i32 [B,H,Lq]             total keys in kept clusters
+ * No workspace needed.
+ */
+int sq_select(const sq_shape_t *shape, const float *logits, const float *row_max, const float *denom,
+              const float *thresh, const int32_t *sizes, const int32_t *offsets,
+              uint32_t *keep_mask, int32_t *ranges, int32_t *n_ranges, int32_t *n_keys,
+              void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Decode-time sparse attention (Section 4.2, Lq must be 1): exact softmax attention of each query
+ * over the fixed-context keys listed in its ranges together with all U user keys of its sequence,
+ * one softmax over the union.  Work is split along the key dimension into equal-sized chunks of
+ * keys (the split-KV scheme of Section 4.2, so heads that keep more keys get more workgroups), each
+ * chunk producing a partial (max, sum, output), merged in a second phase.
+ * In:  ranges i32 [B,H,1,range_cap,2] (first key, count), ascending, disjoint, within [0, L);
+ *      n_ranges, n_keys i32 [B,H,1] with n_keys = sum of counts; range_cap = shape->C.
+ * Out: out f16 [B,H,1,d]; lse f32 [B,H,1] = log sum exp of the scaled logits, or NULL.
+ *      A query with no visible key gets out = 0 and lse = -inf.
+ * Workspace: sq_workspace_bytes(shape, SQ_CALL_ATTN_DECODE).
+ */
+int sq_sparse_attn_decode(const sq_shape_t *shape, const void *q, const void *K_fixed, const void *V_fixed,
+                          const int32_t *ranges, const int32_t *n_ranges, const int32_t *n_keys,
+                          const void *K_user, const void *V_user,
+                          void *out, float *lse, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Prefill-time sparse attention (Section 4.2) with PER-QUERY selection: query t of sequence b
+ * attends to the keys of the clusters set in its own keep_mask row, plus user keys 0..t
+ * (causal_user != 0) or all U user keys (causal_user == 0).
+ * In:  keep_mask u32 [B,H,Lq,ceil(C/32)], offsets i32 [H,C+1].
+ * Out: out f16 [B,H,Lq,d]; lse f32 [B,H,Lq] or NULL.
+ * Workspace: sq_workspace_bytes(shape, SQ_CALL_ATTN_PREFILL).
+ */
+int sq_sparse_attn_prefill(const sq_shape_t *shape, const void *q, const void *K_fixed, const void *V_fixed,
+                           const int32_t *offsets, const uint32_t *keep_mask,
+                           const void *K_user, const void *V_user,
+                           void *out, float *lse, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Two-level centroid lookup (Section 3.3, Eq. 2 and Eq. 3; Lq must be 1).  shape->C is the number
+ * of fine (level-2) clusters C2; C1 is the number of coarse clusters.
+ *   level 1: scores of Eq. 2 on (centroids1, sizes1) against thresh1 -> keep_mask1;
+ *   expansion: the candidates are fine clusters child_offsets[j] .. child_offsets[j+1]-1 of every
+ *            kept coarse cluster j (fine clusters are stored grouped by parent);
+ *   level 2: scores of Eq. 3 on the candidates only -- the max and the normaliser run over the
+ *            candidates, not over all fine clusters -- against thresh2 -> keep_mask2, ranges.
+ * In:  centroids1 f16 [H,C1,d], sizes1 i32 [H,C1] (keys under each coarse cluster),
+ *      child_offsets i32 [H,C1+1] (non-decreasing, child_offsets[C1] <= C2), thresh1 f32 [H],
+ *      centroids2 f16 [H,C2,d], sizes2 i32 [H,C2], offsets2 i32 [H,C2+1], thresh2 f32 [H].
+ * Out: keep_mask1 u32 [B,H,ceil(C1/32)], keep_mask2 u32 [B,H,ceil(C2/32)],
+ *      ranges i32 [B,H,1,C2,2] (may be NULL), n_ranges, n_keys i32 [B,H,1] as in sq_select.
+ * Workspace: sq_workspace_bytes(shape, SQ_CALL_HIER_SELECT) (depends on C1 only through C2 >= C1).
+ */
+int sq_hier_select(const sq_shape_t *shape, int32_t C1, const void *q,
+                   const void *centroids1, const int32_t *sizes1, const int32_t *child_offsets,
+                   const float *thresh1,
+                   const void *centroids2, const int32_t *sizes2, const int32_t *offsets2,
+                   const float *thresh2,
+                   uint32_t *keep_mask1, uint32_t *keep_mask2,
+                   int32_t *ranges, int32_t *n_ranges, int32_t *n_keys,
+                   void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * One whole decode step (Lq must be 1): sq_centroid_score + sq_select + sq_sparse_attn_decode
+ * enqueued back to back with the intermediate results kept in the workspace -- the end-to-end
+ * quantity the paper times (lookup + argument set-up + sparse attention, Appendix "Kernel
+ * Benchmarking").  Results are identical to the three separate calls.
+ * Out: out f16 [B,H,1,d]; optional (NULL to skip): lse f32 [B,H,1], keep_mask u32 [B,H,1,ceil(C/32)],
+ *      n_keys i32 [B,H,1].
+ * Workspace: sq_workspace_bytes(shape, SQ_CALL_DECODE_STEP).
+ */
+int sq_decode_step(const sq_shape_t *shape, const void *q,
+                   const void *centroids, const int32_t *sizes, const int32_t *offsets, const float *thresh,
+                   const void *K_fixed, const void *V_fixed, const void *K_user, const void *V_user,
+                   void *out, float *lse, uint32_t *keep_mask, int32_t *n_keys,
+                   void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SQUEEZED_ATTENTION_H */

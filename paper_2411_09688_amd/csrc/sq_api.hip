@@ -1,0 +1,285 @@
+// C ABI of the library: argument validation, workspace carving and kernel sequencing.  Nothing here
+// computes; every step of the path runs in the kernels of the other files.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "../../include/squeezed_attention.h"
+#include "sq_common.hpp"
+#include "sq_internal.hpp"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+#define SQ_REQUIRE_PTR(p)                                                                     \
+    do {                                                                                      \
+        if ((p) == nullptr) return fail(SQ_ERR_INVALID_ARG, "%s: %s is NULL", __func__, #p);  \
+        if (!aligned16(p)) return fail(SQ_ERR_INVALID_ARG, "%s: %s is not 16-byte aligned", __func__, #p); \
+    } while (0)
+#define SQ_OPTIONAL_PTR(p)                                                                    \
+    do {                                                                                      \
+        if ((p) != nullptr && !aligned16(p))                                                  \
+            return fail(SQ_ERR_INVALID_ARG, "%s: %s is not 16-byte aligned", __func__, #p);   \
+    } while (0)
+#define SQ_HIP(expr)                                                                          \
+    do {                                                                                      \
+        hipError_t e_ = (expr);                                                               \
+        if (e_ != hipSuccess) return fail(SQ_ERR_HIP, "%s: %s -> %s", __func__, #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+int check_shape(const sq_shape_t *sh, const char *fn, bool need_decode)
+{
+    if (!sh) return fail(SQ_ERR_INVALID_ARG, "%s: shape is NULL", fn);
+    if (sh->B <= 0 || sh->H <= 0 || sh->L <= 0 || sh->C <= 0 || sh->Lq <= 0 || sh->U < 0)
+        return fail(SQ_ERR_INVALID_ARG, "%s: non-positive dimension (B=%d H=%d L=%d C=%d Lq=%d U=%d)", fn, sh->B, sh->H,
+                    sh->L, sh->C, sh->Lq, sh->U);
+    if (!(sh->sm_scale == sh->sm_scale) || sh->sm_scale <= 0.0f)
+        return fail(SQ_ERR_INVALID_ARG, "%s: sm_scale must be positive", fn);
+    if (sh->d != sq::D) return fail(SQ_ERR_UNSUPPORTED, "%s: head dim %d not supported (d must be 128)", fn, sh->d);
+    if (need_decode && sh->Lq != 1) return fail(SQ_ERR_UNSUPPORTED, "%s: decode call needs Lq == 1 (got %d)", fn, sh->Lq);
+    const long long rows = (long long)sh->B * sh->H * sh->Lq;
+    if (rows * (long long)sh->C > (1ll << 40) || (long long)sh->H * sh->L > (1ll << 40))
+        return fail(SQ_ERR_UNSUPPORTED, "%s: problem too large", fn);
+    return SQ_OK;
+}
+
+// The kernels are gfx950 code objects: refuse any other device with a clear message.
+int check_device(const char *fn)
+{
+    static thread_local int ok_device = -1;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(SQ_ERR_HIP, "%s: hipGetDevice -> %s", fn, hipGetErrorString(e));
+    if (dev == ok_device) return SQ_OK;
+    hipDeviceProp_t prop;
+    e = hipGetDeviceProperties(&prop, dev);
+    if (e != hipSuccess) return fail(SQ_ERR_HIP, "%s: hipGetDeviceProperties -> %s", fn, hipGetErrorString(e));
+    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+        return fail(SQ_ERR_UNSUPPORTED, "%s: device %d is %s, this library is built for gfx950 only", fn, dev,
+                    prop.gcnArchName);
+    ok_device = dev;
+    return SQ_OK;
+}
+
+size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+// Carves consecutive 256-byte aligned regions out of a workspace.
+struct Carver {
+    char *base;
+    size_t off = 0;
+    explicit Carver(void *p) : base(static_cast<char *>(p)) {}
+    template <typename T>
+    T *take(size_t count)
+    {
+        T *r = base ? reinterpret_cast<T *>(base + off) : nullptr;
+        off += align256(count * sizeof(T));
+        return r;
+    }
+};
+
+struct DecodeWs {
+    sq::DecodePlan plan;
+    float *partials;
+};
+
+DecodeWs carve_decode(Carver &cv, const sq_shape_t *sh)
+{
+    const size_t rows = (size_t)sh->B * sh->H;
+    DecodeWs w;
+    w.plan.rec_cap = sh->C;
+    w.plan.chunk_cap = sq::chunk_cap_for(sh->L);
+    w.plan.rec = cv.take<int4>(rows * sh->C);
+    w.plan.chunk_first = cv.take<int>(rows * w.plan.chunk_cap);
+    w.plan.hdr = cv.take<int2>(rows);
+    w.partials = cv.take<float>(rows * (sq::user_chunks_for(sh->U) + w.plan.chunk_cap) * sq::PART_STRIDE);
+    return w;
+}
+
+struct StepWs {
+    float *logits;
+    int32_t *n_ranges, *n_keys;
+    DecodeWs dec;
+};
+
+StepWs carve_step(Carver &cv, const sq_shape_t *sh)
+{
+    const size_t rows = (size_t)sh->B * sh->H;
+    StepWs w;
+    w.logits = cv.take<float>(rows * sh->C);
+    w.n_ranges = cv.take<int32_t>(rows);
+    w.n_keys = cv.take<int32_t>(rows);
+    w.dec = carve_decode(cv, sh);
+    return w;
+}
+
+int check_ws(const char *fn, const sq_shape_t *sh, int which, void *ws, size_t ws_bytes)
+{
+    const size_t need = sq_workspace_bytes(sh, which);
+    if (need == 0) return SQ_OK;
+    if (!ws) return fail(SQ_ERR_WORKSPACE, "%s: workspace is NULL, %zu bytes needed", fn, need);
+    if (reinterpret_cast<uintptr_t>(ws) & 255u) return fail(SQ_ERR_WORKSPACE, "%s: workspace is not 256-byte aligned", fn);
+    if (ws_bytes < need) return fail(SQ_ERR_WORKSPACE, "%s: workspace has %zu bytes, %zu needed", fn, ws_bytes, need);
+    return SQ_OK;
+}
+
+sq::Shape to_shape(const sq_shape_t *sh)
+{
+    return sq::Shape{sh->B, sh->H, sh->L, sh->C, sh->Lq, sh->U, sh->sm_scale, sh->causal_user};
+}
+
+}  // namespace
+
+extern "C" {
+
+int sq_version(void) { return 100; }
+
+const char *sq_last_error(void) { return g_err; }
+
+size_t sq_workspace_bytes(const sq_shape_t *sh, int which)
+{
+    if (!sh || sh->B <= 0 || sh->H <= 0 || sh->L <= 0 || sh->C <= 0 || sh->Lq <= 0 || sh->U < 0) return 0;
+    Carver cv(nullptr);
+    switch (which) {
+    case SQ_CALL_ATTN_DECODE:
+        carve_decode(cv, sh);
+        return cv.off;
+    case SQ_CALL_DECODE_STEP:
+        carve_step(cv, sh);
+        return cv.off;
+    default:
+        return 0;
+    }
+}
+
+int sq_centroid_score(const sq_shape_t *sh, const void *q, const void *centroids, const int32_t *sizes, float *logits,
+                      float *row_max, float *denom, void *, size_t, void *stream)
+{
+    if (int rc = check_shape(sh, __func__, false)) return rc;
+    SQ_REQUIRE_PTR(q);
+    SQ_REQUIRE_PTR(centroids);
+    SQ_REQUIRE_PTR(sizes);
+    SQ_REQUIRE_PTR(logits);
+    SQ_REQUIRE_PTR(row_max);
+    SQ_REQUIRE_PTR(denom);
+    if (int rc = check_device(__func__)) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    SQ_HIP(sq::launch_score(q, centroids, logits, sh->B, sh->H, sh->Lq, sh->C, sh->sm_scale, s));
+    SQ_HIP(sq::launch_row_stats(logits, sizes, row_max, denom, sh->B * sh->H * sh->Lq, sh->H, sh->Lq, sh->C, s));
+    g_err[0] = 0;
+    return SQ_OK;
+}
+
+int sq_select(const sq_shape_t *sh, const float *logits, const float *row_max, const float *denom, const float *thresh,
+              const int32_t *sizes, const int32_t *offsets, uint32_t *keep_mask, int32_t *ranges, int32_t *n_ranges,
+              int32_t *n_keys, void *, size_t, void *stream)
+{
+    if (int rc = check_shape(sh, __func__, false)) return rc;
+    SQ_REQUIRE_PTR(logits);
+    SQ_REQUIRE_PTR(row_max);
+    SQ_REQUIRE_PTR(denom);
+    SQ_REQUIRE_PTR(thresh);
+    SQ_REQUIRE_PTR(sizes);
+    SQ_REQUIRE_PTR(offsets);
+    SQ_REQUIRE_PTR(keep_mask);
+    SQ_OPTIONAL_PTR(ranges);
+    SQ_REQUIRE_PTR(n_ranges);
+    SQ_REQUIRE_PTR(n_keys);
+    if (int rc = check_device(__func__)) return rc;
+    sq::DecodePlan none{nullptr, nullptr, nullptr, 0, 0};
+    SQ_HIP(sq::launch_select(logits, row_max, denom, true, thresh, sizes, offsets, keep_mask, ranges, n_ranges, n_keys,
+                             none, sh->B * sh->H * sh->Lq, sh->H, sh->Lq, sh->C, static_cast<hipStream_t>(stream)));
+    g_err[0] = 0;
+    return SQ_OK;
+}
+
+int sq_sparse_attn_decode(const sq_shape_t *sh, const void *q, const void *K_fixed, const void *V_fixed,
+                          const int32_t *ranges, const int32_t *n_ranges, const int32_t *n_keys, const void *K_user,
+                          const void *V_user, void *out, float *lse, void *ws, size_t ws_bytes, void *stream)
+{
+    if (int rc = check_shape(sh, __func__, true)) return rc;
+    SQ_REQUIRE_PTR(q);
+    SQ_REQUIRE_PTR(K_fixed);
+    SQ_REQUIRE_PTR(V_fixed);
+    SQ_REQUIRE_PTR(ranges);
+    SQ_REQUIRE_PTR(n_ranges);
+    SQ_REQUIRE_PTR(n_keys);
+    if (sh->U > 0) {
+        SQ_REQUIRE_PTR(K_user);
+        SQ_REQUIRE_PTR(V_user);
+    }
+    SQ_REQUIRE_PTR(out);
+    SQ_OPTIONAL_PTR(lse);
+    if (int rc = check_ws(__func__, sh, SQ_CALL_ATTN_DECODE, ws, ws_bytes)) return rc;
+    if (int rc = check_device(__func__)) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Carver cv(ws);
+    DecodeWs w = carve_decode(cv, sh);
+    SQ_HIP(sq::launch_plan_from_ranges(ranges, n_ranges, w.plan, sh->B * sh->H, sh->C, s));
+    SQ_HIP(sq::launch_decode_attn(q, K_fixed, V_fixed, K_user, V_user, w.plan, n_ranges, n_keys, w.partials, out, lse,
+                                  to_shape(sh), s));
+    g_err[0] = 0;
+    return SQ_OK;
+}
+
+int sq_decode_step(const sq_shape_t *sh, const void *q, const void *centroids, const int32_t *sizes,
+                   const int32_t *offsets, const float *thresh, const void *K_fixed, const void *V_fixed,
+                   const void *K_user, const void *V_user, void *out, float *lse, uint32_t *keep_mask, int32_t *n_keys,
+                   void *ws, size_t ws_bytes, void *stream)
+{
+    if (int rc = check_shape(sh, __func__, true)) return rc;
+    SQ_REQUIRE_PTR(q);
+    SQ_REQUIRE_PTR(centroids);
+    SQ_REQUIRE_PTR(sizes);
+    SQ_REQUIRE_PTR(offsets);
+    SQ_REQUIRE_PTR(thresh);
+    SQ_REQUIRE_PTR(K_fixed);
+    SQ_REQUIRE_PTR(V_fixed);
+    if (sh->U > 0) {
+        SQ_REQUIRE_PTR(K_user);
+        SQ_REQUIRE_PTR(V_user);
+    }
+    SQ_REQUIRE_PTR(out);
+    SQ_OPTIONAL_PTR(lse);
+    SQ_OPTIONAL_PTR(keep_mask);
+    SQ_OPTIONAL_PTR(n_keys);
+    if (int rc = check_ws(__func__, sh, SQ_CALL_DECODE_STEP, ws, ws_bytes)) return rc;
+    if (int rc = check_device(__func__)) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Carver cv(ws);
+    StepWs w = carve_step(cv, sh);
+    const int rows = sh->B * sh->H;
+    SQ_HIP(sq::launch_score(q, centroids, w.logits, sh->B, sh->H, 1, sh->C, sh->sm_scale, s));
+    SQ_HIP(sq::launch_select(w.logits, nullptr, nullptr, false, thresh, sizes, offsets, keep_mask, nullptr, w.n_ranges,
+                             n_keys ? n_keys : w.n_keys, w.dec.plan, rows, sh->H, 1, sh->C, s));
+    SQ_HIP(sq::launch_decode_attn(q, K_fixed, V_fixed, K_user, V_user, w.dec.plan, w.n_ranges, w.n_keys, w.dec.partials,
+                                  out, lse, to_shape(sh), s));
+    g_err[0] = 0;
+    return SQ_OK;
+}
+
+int sq_sparse_attn_prefill(const sq_shape_t *, const void *, const void *, const void *, const int32_t *,
+                           const uint32_t *, const void *, const void *, void *, float *, void *, size_t, void *)
+{
+    return fail(SQ_ERR_UNSUPPORTED, "sq_sparse_attn_prefill: not built yet");
+}
+
+int sq_hier_select(const sq_shape_t *, int32_t, const void *, const void *, const int32_t *, const int32_t *,
+                   const float *, const void *, const int32_t *, const int32_t *, const float *, uint32_t *, uint32_t *,
+                   int32_t *, int32_t *, int32_t *, void *, size_t, void *)
+{
+    return fail(SQ_ERR_UNSUPPORTED, "sq_hier_select: not built yet");
+}
+
+}  // extern "C"

@@ -1,0 +1,106 @@
+// Device-side helpers and compile-time constants shared by the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sq {
+
+constexpr int D = 128;            // head dimension (fp16 row = 256 B = 16 lanes x 16 B)
+constexpr int KPC = 256;          // keys per split-KV chunk = one workgroup of 4 waves x 64 keys
+constexpr int PART_STRIDE = 132;  // floats per partial result: m, l, pad, pad, o[128]
+
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef float f16v __attribute__((ext_vector_type(16)));
+
+#define SQ_NEG_INF (-__builtin_inff())
+
+// Data-parallel-primitive move: lane i receives `v` from the lane selected by CTRL inside its
+// row of 16 lanes (0x120 + n = rotate right by n).
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+}
+
+// Sum / max over each group of 16 consecutive lanes; every lane of the group gets the result.
+__device__ __forceinline__ float row16_sum(float v)
+{
+    v += dpp_f<0x128>(v);
+    v += dpp_f<0x124>(v);
+    v += dpp_f<0x122>(v);
+    v += dpp_f<0x121>(v);
+    return v;
+}
+
+// Sum / max over the four 16-lane groups (lanes l, l^16, l^32, l^48); all lanes get the result.
+__device__ __forceinline__ float cross16_sum(float v)
+{
+    v += __shfl_xor(v, 16);
+    v += __shfl_xor(v, 32);
+    return v;
+}
+__device__ __forceinline__ float cross16_max(float v)
+{
+    v = fmaxf(v, __shfl_xor(v, 16));
+    v = fmaxf(v, __shfl_xor(v, 32));
+    return v;
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave.
+__device__ __forceinline__ int wave_inclusive_scan(int v, int lane)
+{
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        int t = __shfl_up(v, o);
+        if (lane >= o) v += t;
+    }
+    return v;
+}
+
+// fp32 dot product of two 8-element fp16 vectors (exact products, fp32 accumulation).
+__device__ __forceinline__ float dot8(h8 a, h8 b, float acc)
+{
+    acc = __builtin_amdgcn_fdot2(h2{a[0], a[1]}, h2{b[0], b[1]}, acc, false);
+    acc = __builtin_amdgcn_fdot2(h2{a[2], a[3]}, h2{b[2], b[3]}, acc, false);
+    acc = __builtin_amdgcn_fdot2(h2{a[4], a[5]}, h2{b[4], b[5]}, acc, false);
+    acc = __builtin_amdgcn_fdot2(h2{a[6], a[7]}, h2{b[6], b[7]}, acc, false);
+    return acc;
+}
+
+// Row statistics of Eq. 1 in max-subtracted form, computed by ONE wave for one query row:
+//   m = max over clusters with N > 0 of x;  D = sum_i N_i * exp(x_i - m).
+// Every kernel that needs (m, D) calls this, so the values are bit-identical wherever they are
+// produced.  `x` and `N` may be indexed through `cand` (candidate list) when it is non-null.
+__device__ __forceinline__ void wave_row_stats(const float *__restrict__ x, const int32_t *__restrict__ N,
+                                               int n, int lane, float &m_out, float &D_out)
+{
+    float m = SQ_NEG_INF;
+    for (int i = lane; i < n; i += 64)
+        if (N[i] > 0) m = fmaxf(m, x[i]);
+    m = wave_max(m);
+    float Dsum = 0.0f;
+    for (int i = lane; i < n; i += 64) {
+        int Ni = N[i];
+        if (Ni > 0) Dsum += (float)Ni * expf(x[i] - m);
+    }
+    m_out = m;
+    D_out = wave_sum(Dsum);
+}
+
+}  // namespace sq

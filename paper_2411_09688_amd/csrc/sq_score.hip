@@ -1,0 +1,103 @@
+// Centroid scoring: logits[r, i] = sm_scale * q_r . C_i  (argument of exp in Eq. 1, Section 3.2) and
+// the row statistics (m, D) of the max-subtracted form (Appendix D, "Generation Stage").
+//
+// The score is a small matrix product per head -- centroids [C x 128] times queries [128 x Nq] -- so it
+// runs on the matrix cores: one 16x16x32 fp16 MFMA tile covers 16 centroid rows x 16 queries, with the
+// centroid rows streamed straight from HBM into the A operand (each lane loads 16 contiguous bytes of
+// a row, no LDS).  In decode only some of the 16 query columns are live; the kernel is bound by
+// the centroid bytes either way.
+#include "sq_common.hpp"
+#include "sq_internal.hpp"
+
+namespace sq {
+
+constexpr int SCORE_TILES_PER_WAVE = 2;                              // 16-row tiles per wave
+constexpr int SCORE_ROWS_PER_WG = 4 * 16 * SCORE_TILES_PER_WAVE;     // 4 waves
+
+__global__ __launch_bounds__(256) void score_kernel(const _Float16 *__restrict__ q,
+                                                    const _Float16 *__restrict__ cent,
+                                                    float *__restrict__ logits, int B, int H, int Lq, int C,
+                                                    float sm_scale)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane & 15, kg = lane >> 4;
+    const int h = blockIdx.y;
+    const int NQ = B * Lq;
+    const int n = blockIdx.z * 16 + col;          // query column of this lane (per head)
+    const bool n_ok = n < NQ;
+    size_t qrow = 0;
+    h8 bq[4];
+    if (n_ok) {
+        int b = n / Lq, t = n - b * Lq;
+        qrow = ((size_t)b * H + h) * Lq + t;
+        const h8 *qp = reinterpret_cast<const h8 *>(q + qrow * D);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) bq[s] = qp[s * 4 + kg];
+    } else {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) bq[s] = h8{0, 0, 0, 0, 0, 0, 0, 0};
+    }
+    const int i_base = (blockIdx.x * 4 + wave) * 16 * SCORE_TILES_PER_WAVE;
+    h8 a[SCORE_TILES_PER_WAVE][4];
+#pragma unroll
+    for (int tile = 0; tile < SCORE_TILES_PER_WAVE; ++tile) {
+        int row = i_base + tile * 16 + col;
+        row = row < C ? row : C - 1;              // clamp: rows past C are computed and discarded
+        const h8 *cp = reinterpret_cast<const h8 *>(cent + ((size_t)h * C + row) * D);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) a[tile][s] = cp[s * 4 + kg];
+    }
+#pragma unroll
+    for (int tile = 0; tile < SCORE_TILES_PER_WAVE; ++tile) {
+        const int i0 = i_base + tile * 16 + kg * 4;   // first of this lane's 4 centroid rows
+        f4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < 4; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[tile][s], bq[s], acc, 0, 0, 0);
+        if (n_ok && i0 < C) {
+            float *dst = logits + qrow * (size_t)C + i0;
+            if (i0 + 3 < C && (C & 3) == 0) {
+                *reinterpret_cast<f4 *>(dst) = acc * sm_scale;
+            } else {
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (i0 + v < C) dst[v] = acc[v] * sm_scale;
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void row_stats_kernel(const float *__restrict__ logits,
+                                                        const int32_t *__restrict__ sizes,
+                                                        float *__restrict__ row_max, float *__restrict__ denom,
+                                                        int rows, int H, int Lq, int C)
+{
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const int h = (row / Lq) % H;
+    float m, Dsum;
+    wave_row_stats(logits + (size_t)row * C, sizes + (size_t)h * C, C, lane, m, Dsum);
+    if (lane == 0) {
+        row_max[row] = m;
+        denom[row] = Dsum;
+    }
+}
+
+hipError_t launch_score(const void *q, const void *centroids, float *logits, int B, int H, int Lq, int C,
+                        float sm_scale, hipStream_t s)
+{
+    dim3 grid((C + SCORE_ROWS_PER_WG - 1) / SCORE_ROWS_PER_WG, H, (B * Lq + 15) / 16);
+    hipLaunchKernelGGL(score_kernel, grid, dim3(256), 0, s, (const _Float16 *)q, (const _Float16 *)centroids, logits, B,
+                       H, Lq, C, sm_scale);
+    return hipGetLastError();
+}
+
+hipError_t launch_row_stats(const float *logits, const int32_t *sizes, float *row_max, float *denom, int rows,
+                            int H, int Lq, int C, hipStream_t s)
+{
+    hipLaunchKernelGGL(row_stats_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, logits, sizes, row_max, denom, rows, H,
+                       Lq, C);
+    return hipGetLastError();
+}
+
+}  // namespace sq
