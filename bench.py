@@ -1,0 +1,250 @@
+#!/usr/bin/env python3
+"""Benchmark of the decode hot path on one MI355X.
+
+One step = one pass of the whole path (centroid scoring -> threshold selection / range compaction ->
+split-KV sparse attention over the kept fixed-context keys + the dense user keys -> merge) for one
+decode token, through the C ABI (`sq_decode_step`), on seeded synthetic inputs already resident in
+HBM.  Steps rotate through `--queries` different query tokens (the paper times 100 different query
+tokens per measurement, Appendix "Kernel Benchmarking") and through `--replicas` device copies of
+the fixed context, so that the bytes of a step cannot be served from the 256 MB last-level cache.
+
+Prints ONE JSON line (see the field notes in the design doc).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0       # MI355X published HBM3E bandwidth
+METRIC = "decode attn µs/token + achieved HBM GB/s, 32K fixed ctx, keep 1/8, H=32 d=128"
+
+
+def gpu_score_fn(sq, torch, device):
+    """`score_fn` for the workload calibration that runs Eq. 1 through the library (sq_centroid_score)."""
+    def fn(q, centroids, sizes, sm_scale):
+        nq, d = q.shape
+        Cn = centroids.shape[0]
+        sh = sq.make_shape(1, 1, 1, Cn, nq, 0, sm_scale)
+        tq = torch.from_numpy(np.ascontiguousarray(q)).to(device).view(1, 1, nq, d)
+        tc = torch.from_numpy(np.ascontiguousarray(centroids)).to(device).view(1, Cn, d)
+        ts = torch.from_numpy(np.ascontiguousarray(sizes, dtype=np.int32)).to(device).view(1, Cn)
+        x = torch.empty(1, 1, nq, Cn, dtype=torch.float32, device=device)
+        m = torch.empty(1, 1, nq, dtype=torch.float32, device=device)
+        D = torch.empty(1, 1, nq, dtype=torch.float32, device=device)
+        sq.sq_centroid_score(sh, tq, tc, ts, x, m, D)
+        torch.cuda.synchronize()
+        x, m, D = (a.cpu().numpy().astype(np.float64) for a in (x, m, D))
+        return np.exp(x[0, 0] - m[0, 0][:, None]) / D[0, 0][:, None]
+    return fn
+
+
+def step_bytes(w, n_keys_per_head):
+    """Algorithmic HBM bytes of one decode step for the achieved selection (bytes the method must move)."""
+    H, C, d, U, B = w.H, w.C, w.d, w.U, w.B
+    centroid = H * C * d * 2
+    meta = H * C * 4 + H * (C + 1) * 4 + H * 4
+    selected_kv = int(np.sum(n_keys_per_head)) * d * 2 * 2
+    dense_kv = B * H * U * d * 2 * 2
+    io = B * H * d * 2 * 2
+    return dict(centroid=centroid, meta=meta, selected_kv=selected_kv, dense_kv=dense_kv, io=io,
+                total=centroid + meta + selected_kv + dense_kv + io)
+
+
+def read_traffic(name):
+    """HBM bytes per launch of the dominant kernel from a committed rocprofv3 --pmc summary, if present."""
+    path = os.path.join(ROOT, "profiles", name)
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch:"):
+            return float(line.split(":", 1)[1])
+    return None
+
+
+def cpu_baseline(w_name, seed, budget_s):
+    """The CPU oracle, as it stands, timed on this host on a bounded sample of the same workload."""
+    import oracle
+    from paper_2411_09688_amd import workload as wl
+    w = wl.calibrate(wl.make_config(w_name, seed=seed), oracle.scores)
+    qs = wl.extra_queries(w, 100)
+    n, t_total, nbytes = 0, 0.0, 0
+    while n < 100 and t_total < budget_s:
+        q = np.ascontiguousarray(qs[n][None, :, None, :])
+        t0 = time.perf_counter()
+        x, m, D = oracle.centroid_score(q, w.centroids, w.sizes, w.sm_scale)
+        mask, ranges, nr, nk = oracle.select(x, m, D, w.thresh, w.sizes, w.offsets)
+        oracle.sparse_attn(q, w.K_fixed, w.V_fixed, ranges, nr, w.K_user, w.V_user, w.sm_scale)
+        t_total += time.perf_counter() - t0
+        nbytes += step_bytes(w, nk)["total"]
+        n += 1
+    return dict(value=round(nbytes / t_total / 1e9, 3), unit="GB/s", us_per_token=round(t_total / n * 1e6, 1),
+                cores=oracle.num_threads(), kind="oracle",
+                sample=f"{n} decode steps (different query tokens) of {w_name}, whole path, same byte model")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=100)
+    ap.add_argument("--workload", default="cfg2_decode_32k")
+    ap.add_argument("--queries", type=int, default=100)
+    ap.add_argument("--replicas", type=int, default=8)
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU-oracle baseline (0 = skip)")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay measurement")
+    ap.add_argument("--separate", action="store_true", help="time the three separate calls instead of sq_decode_step")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus {args.gpus} is not "
+              "supported. Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2411_09688_amd import binding as sq, workload as wl
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    sq.lib()
+
+    w = wl.make_config(args.workload, seed=args.seed, threads=16)
+    assert w.Lq == 1 and not w.C1, "bench.py times the one-level decode path"
+    wl.calibrate(w, gpu_score_fn(sq, torch, dev))
+    NQ, R = args.queries, args.replicas
+    tt = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    rep = lambda a: [tt(a) for _ in range(R)]
+    Kf, Vf, Ce, Ku, Vu = rep(w.K_fixed), rep(w.V_fixed), rep(w.centroids), rep(w.K_user), rep(w.V_user)
+    sizes, offsets, thresh = tt(w.sizes), tt(w.offsets), tt(w.thresh)
+    # queries: NQ tokens; every sequence of a batched workload gets its own rotation of them
+    qs = wl.extra_queries(w, NQ + w.B - 1)
+    Q = torch.stack([tt(np.ascontiguousarray(qs[i:i + w.B][:, :, None, :])) for i in range(NQ)])  # [NQ,B,H,1,d]
+    out = torch.zeros(NQ, w.B, w.H, 1, w.d, dtype=torch.float16, device=dev)
+    lse = torch.zeros(NQ, w.B, w.H, 1, dtype=torch.float32, device=dev)
+    nkeys = torch.zeros(NQ, w.B, w.H, 1, dtype=torch.int32, device=dev)
+    shape = sq.make_shape(w.B, w.H, w.L, w.C, 1, w.U, w.sm_scale)
+    ws = sq.workspace(shape, sq.SQ_CALL_DECODE_STEP, dev)
+    if args.separate:
+        logits = torch.empty(w.B, w.H, 1, w.C, dtype=torch.float32, device=dev)
+        rmax = torch.empty(w.B, w.H, 1, dtype=torch.float32, device=dev)
+        den = torch.empty_like(rmax)
+        mask = torch.zeros(w.B, w.H, 1, (w.C + 31) // 32, dtype=torch.int32, device=dev)
+        ranges = torch.zeros(w.B, w.H, 1, w.C, 2, dtype=torch.int32, device=dev)
+        nr = torch.zeros(w.B, w.H, 1, dtype=torch.int32, device=dev)
+        ws_a = sq.workspace(shape, sq.SQ_CALL_ATTN_DECODE, dev)
+
+    # Arguments are marshalled once per (query, replica) pair; a step is then one ctypes call.
+    import ctypes as C
+    L_ = sq.lib()
+    sp = C.byref(shape)
+    P = lambda t: C.c_void_p(t.data_ptr()) if t is not None else None
+    wsp = lambda t: (C.c_void_p(t.data_ptr()), t.numel())
+    cycle = int(np.lcm(NQ, R))
+    calls = []
+    for i in range(cycle):
+        qi, r = i % NQ, i % R
+        if args.separate:
+            calls.append((
+                (sp, P(Q[qi]), P(Ce[r]), P(sizes), P(logits), P(rmax), P(den), None, 0),
+                (sp, P(logits), P(rmax), P(den), P(thresh), P(sizes), P(offsets), P(mask), P(ranges), P(nr),
+                 P(nkeys[qi]), None, 0),
+                (sp, P(Q[qi]), P(Kf[r]), P(Vf[r]), P(ranges), P(nr), P(nkeys[qi]), P(Ku[r]), P(Vu[r]), P(out[qi]),
+                 P(lse[qi]), *wsp(ws_a))))
+        else:
+            calls.append((sp, P(Q[qi]), P(Ce[r]), P(sizes), P(offsets), P(thresh), P(Kf[r]), P(Vf[r]), P(Ku[r]),
+                          P(Vu[r]), P(out[qi]), P(lse[qi]), None, P(nkeys[qi]), *wsp(ws)))
+
+    def step(i, stream_ptr):
+        a = calls[i % cycle]
+        if args.separate:
+            rc = (L_.sq_centroid_score(*a[0], stream_ptr) or L_.sq_select(*a[1], stream_ptr)
+                  or L_.sq_sparse_attn_decode(*a[2], stream_ptr))
+        else:
+            rc = L_.sq_decode_step(*a, stream_ptr)
+        if rc:
+            raise sq.SqError(rc, L_.sq_last_error().decode())
+
+    def cur_stream():
+        return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+    # ---- eager: W warm-up steps, then exactly K timed steps between two synchronisations -------------
+    st = cur_stream()
+    for i in range(args.warmup):
+        step(i, st)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, st)
+    torch.cuda.synchronize()
+    eager_ms = (time.perf_counter() - t0) / args.steps * 1e3
+
+    # ---- the same K steps captured once into a HIP graph and replayed (no host launch cost) ----------
+    graph_ms = None
+    if not args.no_graph:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            st_cap = cur_stream()
+            for i in range(args.steps):
+                step(args.warmup + i, st_cap)
+        g.replay()                                   # untimed replay (warm-up of the graph itself)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        g.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) / args.steps * 1e3
+    ms_per_step = min(eager_ms, graph_ms) if graph_ms is not None else eager_ms
+
+    # ---- same steps again, eager, with HIP events around every launch of the dominant kernel ---------
+    sq.sq_profile_begin(args.steps)
+    for i in range(args.steps):
+        step(args.warmup + i, st)
+    torch.cuda.synchronize()
+    n_meas, k_avg_us, k_min_us, k_max_us = sq.sq_profile_end()
+
+    nk = nkeys.cpu().numpy()[:, :, :, 0]                       # [NQ, B, H]
+    used = [(args.warmup + i) % NQ for i in range(args.steps)]
+    per_step = [step_bytes(w, nk[qi]) for qi in used]
+    tot = float(np.mean([b["total"] for b in per_step]))
+    sel = float(np.mean([b["selected_kv"] for b in per_step]))
+    cen = float(per_step[0]["centroid"])
+    dense = float(per_step[0]["dense_kv"])
+    kernel_bytes = sel + dense + w.B * w.H * w.d * 2           # K/V rows read by the partial kernel + q
+    keep = float(np.mean([nk[qi].mean() for qi in used]) / w.L)
+    tokens = w.B
+
+    res = {
+        "metric": METRIC,
+        "value": round(tot / (ms_per_step * 1e-3) / 1e9, 2),
+        "unit": "GB/s",
+        "us_per_token": round(ms_per_step * 1e3 / tokens, 3),
+        "us_per_step_eager": round(eager_ms * 1e3, 3),
+        "us_per_step_graph": None if graph_ms is None else round(graph_ms * 1e3, 3),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 6),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": args.workload, "B": w.B, "H": w.H, "d": w.d, "L": w.L, "C": w.C, "U": w.U,
+                   "keep_target": w.keep_frac, "keep_achieved": round(keep, 5), "queries": NQ, "replicas": R,
+                   "entry": "3 calls" if args.separate else "sq_decode_step"},
+        "bytes_per_step": {"total": round(tot), "centroid": round(cen), "selected_kv": round(sel),
+                           "dense_kv": round(dense), "centroid_plus_selected_kv": round(cen + sel)},
+        "hbm_frac_whole_step": round(tot / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "roofline": {"bound": "hbm", "kernel": "decode_partial_kernel",
+                     "achieved": round(kernel_bytes / (k_avg_us * 1e-6) / 1e9, 2) if n_meas else None,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(kernel_bytes / (k_avg_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4) if n_meas else None,
+                     "traffic": read_traffic(f"decode_partial_kernel_{args.workload}_pmc.txt"),
+                     "bytes_per_launch": round(kernel_bytes), "avg_us": round(k_avg_us, 3),
+                     "min_us": round(k_min_us, 3), "launches": n_meas},
+    }
+    if args.cpu_seconds > 0:
+        res["cpu_baseline"] = cpu_baseline(args.workload, args.seed, args.cpu_seconds)
+    print(json.dumps(res, ensure_ascii=False))
+
+
+if __name__ == "__main__":
+    main()

@@ -178,6 +178,27 @@ int sq_decode_step(const sq_shape_t *shape, const void *q,
                    void *out, float *lse, uint32_t *keep_mask, int32_t *n_keys,
                    void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * Measurement hook for benchmarks (not part of the method; for callers that want a kernel's duration
+ * without an external profiler).  Between sq_profile_begin(n) and sq_profile_end(), every launch of
+ * the split-KV partial-attention kernel -- the kernel that reads the selected K/V rows, i.e. nearly
+ * all bytes of a decode step (Section 4.2, phase 1) -- is bracketed by a pair of HIP events recorded on
+ * the stream it is launched on, up to n launches.  sq_profile_end() waits for those events, writes the
+ * average / minimum / maximum elapsed time per launch in microseconds (any pointer may be NULL),
+ * returns the number of launches measured (or a negative sq_status), and releases the events.
+ * Host only; process-wide state, not thread-safe; creates HIP events (no device memory).
+ */
+int sq_profile_begin(int max_launches);
+int sq_profile_end(float *avg_us, float *min_us, float *max_us);
+
+/*
+ * Measurement probe: a plain streaming read of `bytes` bytes of device memory at `buf` (16-byte aligned)
+ * by `workgroups` workgroups of 256 threads, enqueued on `stream`; `sink` is >= 1 KiB of device memory
+ * that may receive a word.  Timed by the caller, it gives the read bandwidth an HBM-bound kernel can
+ * approach on the device at hand, to put beside the published peak.
+ */
+int sq_probe_stream_read(const void *buf, size_t bytes, void *sink, int workgroups, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -15,14 +15,15 @@ from typing import Optional
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libsqueezed_attention.so")
+LIB_PATH = os.environ.get("SQ_LIB_PATH") or os.path.join(_PKG, "libsqueezed_attention.so")   # override: tuning builds
 
 SQ_OK, SQ_ERR_INVALID_ARG, SQ_ERR_UNSUPPORTED, SQ_ERR_WORKSPACE, SQ_ERR_HIP = 0, -1, -2, -3, -4
 (SQ_CALL_CENTROID_SCORE, SQ_CALL_SELECT, SQ_CALL_ATTN_DECODE, SQ_CALL_ATTN_PREFILL, SQ_CALL_HIER_SELECT,
  SQ_CALL_DECODE_STEP, SQ_CALL_HIER_DECODE_STEP) = range(7)
 
 EXPORTS = ("sq_workspace_bytes", "sq_last_error", "sq_version", "sq_centroid_score", "sq_select",
-           "sq_sparse_attn_decode", "sq_sparse_attn_prefill", "sq_hier_select", "sq_decode_step")
+           "sq_sparse_attn_decode", "sq_sparse_attn_prefill", "sq_hier_select", "sq_decode_step",
+           "sq_profile_begin", "sq_profile_end", "sq_probe_stream_read")
 
 
 class SqShape(C.Structure):
@@ -59,6 +60,9 @@ def lib() -> C.CDLL:
         L.sq_sparse_attn_prefill.argtypes = [sp] + [vp] * 9 + [vp, sz, vp]
         L.sq_hier_select.argtypes = [sp, C.c_int32] + [vp] * 14 + [vp, sz, vp]
         L.sq_decode_step.argtypes = [sp] + [vp] * 13 + [vp, sz, vp]
+        L.sq_probe_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_int, C.c_void_p]
+        L.sq_profile_begin.argtypes = [C.c_int]
+        L.sq_profile_end.argtypes = [C.POINTER(C.c_float)] * 3
         for name in EXPORTS[3:]:
             getattr(L, name).restype = C.c_int
         _lib = L
@@ -170,6 +174,25 @@ def sq_decode_step(shape, q, centroids, sizes, offsets, thresh, K_fixed, V_fixed
                                 _ptr(K_user, F16, "K_user"), _ptr(V_user, F16, "V_user"), _ptr(out, F16, "out"),
                                 _ptr(lse, F32, "lse"), _ptr(keep_mask, I32, "keep_mask"), _ptr(n_keys, I32, "n_keys"),
                                 *_ws_args(ws), _stream(stream)))
+
+
+def sq_probe_stream_read(buf: torch.Tensor, sink: torch.Tensor, workgroups: int, nbytes: Optional[int] = None,
+                         stream=None):
+    n = buf.numel() * buf.element_size() if nbytes is None else int(nbytes)
+    _check(lib().sq_probe_stream_read(_ptr(buf), n, _ptr(sink), int(workgroups), _stream(stream)))
+
+
+def sq_profile_begin(max_launches: int):
+    _check(lib().sq_profile_begin(int(max_launches)))
+
+
+def sq_profile_end():
+    """-> (launches measured, avg_us, min_us, max_us) of the split-KV partial kernel."""
+    a, mn, mx = C.c_float(), C.c_float(), C.c_float()
+    n = lib().sq_profile_end(C.byref(a), C.byref(mn), C.byref(mx))
+    if n < 0:
+        _check(n)
+    return n, a.value, mn.value, mx.value
 
 
 # ------------------------------------------------------------------------------------------------

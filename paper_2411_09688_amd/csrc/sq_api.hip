@@ -50,8 +50,11 @@ int check_shape(const sq_shape_t *sh, const char *fn, bool need_decode)
     if (sh->d != sq::D) return fail(SQ_ERR_UNSUPPORTED, "%s: head dim %d not supported (d must be 128)", fn, sh->d);
     if (need_decode && sh->Lq != 1) return fail(SQ_ERR_UNSUPPORTED, "%s: decode call needs Lq == 1 (got %d)", fn, sh->Lq);
     const long long rows = (long long)sh->B * sh->H * sh->Lq;
-    if (rows * (long long)sh->C > (1ll << 40) || (long long)sh->H * sh->L > (1ll << 40))
+    if (rows * (long long)sh->C > (1ll << 40) || (long long)sh->H * sh->L > (1ll << 40) || sh->L > sq::MAX_L)
         return fail(SQ_ERR_UNSUPPORTED, "%s: problem too large", fn);
+    if (sh->C > sq::SELECT_MAX_C)
+        return fail(SQ_ERR_UNSUPPORTED, "%s: C = %d clusters per head exceeds the supported %d", fn, sh->C,
+                    sq::SELECT_MAX_C);
     return SQ_OK;
 }
 
@@ -97,16 +100,21 @@ struct DecodeWs {
 DecodeWs carve_decode(Carver &cv, const sq_shape_t *sh)
 {
     const size_t rows = (size_t)sh->B * sh->H;
+    const size_t items = rows * (sq::user_chunks_for(sh->U) + sq::chunk_cap_for(sh->L));
     DecodeWs w;
     w.plan.rec_cap = sh->C;
-    w.plan.chunk_cap = sq::chunk_cap_for(sh->L);
+    w.plan.L = sh->L;
+    w.plan.item_cap = (int)items;
     w.plan.rec = cv.take<int4>(rows * sh->C);
-    w.plan.chunk_first = cv.take<int>(rows * w.plan.chunk_cap);
     w.plan.hdr = cv.take<int2>(rows);
-    w.partials = cv.take<float>(rows * (sq::user_chunks_for(sh->U) + w.plan.chunk_cap) * sq::PART_STRIDE);
+    w.plan.row_items = cv.take<int2>(rows);
+    w.plan.total = cv.take<int>(1);
+    w.plan.item = cv.take<int2>(items * sq::ITEM_STRIDE);
+    w.partials = cv.take<float>(items * sq::PART_STRIDE);
     return w;
 }
 
+// Workspace of the whole decode step: logits, counts, plan, partials.
 struct StepWs {
     float *logits;
     int32_t *n_ranges, *n_keys;
@@ -175,7 +183,7 @@ int sq_centroid_score(const sq_shape_t *sh, const void *q, const void *centroids
     SQ_REQUIRE_PTR(denom);
     if (int rc = check_device(__func__)) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    SQ_HIP(sq::launch_score(q, centroids, logits, sh->B, sh->H, sh->Lq, sh->C, sh->sm_scale, s));
+    SQ_HIP(sq::launch_score(q, centroids, logits, nullptr, sh->B, sh->H, sh->Lq, sh->C, sh->sm_scale, s));
     SQ_HIP(sq::launch_row_stats(logits, sizes, row_max, denom, sh->B * sh->H * sh->Lq, sh->H, sh->Lq, sh->C, s));
     g_err[0] = 0;
     return SQ_OK;
@@ -197,9 +205,10 @@ int sq_select(const sq_shape_t *sh, const float *logits, const float *row_max, c
     SQ_REQUIRE_PTR(n_ranges);
     SQ_REQUIRE_PTR(n_keys);
     if (int rc = check_device(__func__)) return rc;
-    sq::DecodePlan none{nullptr, nullptr, nullptr, 0, 0};
+    sq::DecodePlan none{};
     SQ_HIP(sq::launch_select(logits, row_max, denom, true, thresh, sizes, offsets, keep_mask, ranges, n_ranges, n_keys,
-                             none, sh->B * sh->H * sh->Lq, sh->H, sh->Lq, sh->C, static_cast<hipStream_t>(stream)));
+                             none, false, 0, sh->B * sh->H * sh->Lq, sh->H, sh->Lq, sh->C,
+                             static_cast<hipStream_t>(stream)));
     g_err[0] = 0;
     return SQ_OK;
 }
@@ -226,9 +235,9 @@ int sq_sparse_attn_decode(const sq_shape_t *sh, const void *q, const void *K_fix
     hipStream_t s = static_cast<hipStream_t>(stream);
     Carver cv(ws);
     DecodeWs w = carve_decode(cv, sh);
-    SQ_HIP(sq::launch_plan_from_ranges(ranges, n_ranges, w.plan, sh->B * sh->H, sh->C, s));
-    SQ_HIP(sq::launch_decode_attn(q, K_fixed, V_fixed, K_user, V_user, w.plan, n_ranges, n_keys, w.partials, out, lse,
-                                  to_shape(sh), s));
+    SQ_HIP(sq::launch_ranges_to_rec(ranges, n_ranges, w.plan, sh->B * sh->H, sh->C, s));
+    SQ_HIP(sq::launch_schedule(w.plan, sh->B * sh->H, sh->U, s));
+    SQ_HIP(sq::launch_decode_attn(q, K_fixed, V_fixed, K_user, V_user, w.plan, w.partials, out, lse, to_shape(sh), s));
     g_err[0] = 0;
     return SQ_OK;
 }
@@ -260,11 +269,12 @@ int sq_decode_step(const sq_shape_t *sh, const void *q, const void *centroids, c
     Carver cv(ws);
     StepWs w = carve_step(cv, sh);
     const int rows = sh->B * sh->H;
-    SQ_HIP(sq::launch_score(q, centroids, w.logits, sh->B, sh->H, 1, sh->C, sh->sm_scale, s));
+    int32_t *nk = n_keys ? n_keys : w.n_keys;
+    SQ_HIP(sq::launch_score(q, centroids, w.logits, w.dec.plan.total, sh->B, sh->H, 1, sh->C, sh->sm_scale, s));
     SQ_HIP(sq::launch_select(w.logits, nullptr, nullptr, false, thresh, sizes, offsets, keep_mask, nullptr, w.n_ranges,
-                             n_keys ? n_keys : w.n_keys, w.dec.plan, rows, sh->H, 1, sh->C, s));
-    SQ_HIP(sq::launch_decode_attn(q, K_fixed, V_fixed, K_user, V_user, w.dec.plan, w.n_ranges, w.n_keys, w.dec.partials,
-                                  out, lse, to_shape(sh), s));
+                             nk, w.dec.plan, true, sh->U, rows, sh->H, 1, sh->C, s));
+    SQ_HIP(sq::launch_decode_attn(q, K_fixed, V_fixed, K_user, V_user, w.dec.plan, w.dec.partials, out, lse,
+                                  to_shape(sh), s));
     g_err[0] = 0;
     return SQ_OK;
 }

@@ -6,7 +6,10 @@
 namespace sq {
 
 constexpr int D = 128;            // head dimension (fp16 row = 256 B = 16 lanes x 16 B)
-constexpr int KPC = 256;          // keys per split-KV chunk = one workgroup of 4 waves x 64 keys
+#ifndef SQ_KPC
+#define SQ_KPC 128
+#endif
+constexpr int KPC = SQ_KPC;       // keys per split-KV chunk = one workgroup of 4 waves x KPC/4 keys
 constexpr int PART_STRIDE = 132;  // floats per partial result: m, l, pad, pad, o[128]
 
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
@@ -62,6 +65,13 @@ __device__ __forceinline__ float wave_max(float v)
     return v;
 }
 
+__device__ __forceinline__ int wave_sum_i(int v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
 // Inclusive prefix sum over the 64 lanes of a wave.
 __device__ __forceinline__ int wave_inclusive_scan(int v, int lane)
 {
@@ -85,19 +95,42 @@ __device__ __forceinline__ float dot8(h8 a, h8 b, float acc)
 
 // Row statistics of Eq. 1 in max-subtracted form, computed by ONE wave for one query row:
 //   m = max over clusters with N > 0 of x;  D = sum_i N_i * exp(x_i - m).
-// Every kernel that needs (m, D) calls this, so the values are bit-identical wherever they are
-// produced.  `x` and `N` may be indexed through `cand` (candidate list) when it is non-null.
-__device__ __forceinline__ void wave_row_stats(const float *__restrict__ x, const int32_t *__restrict__ N,
-                                               int n, int lane, float &m_out, float &D_out)
+// Lane l accumulates clusters l, l+64, l+128, ... in ascending order and the 64 lane sums are
+// combined with a butterfly.  Every kernel that needs (m, D) calls this, on global or LDS memory, so
+// the values are bit-identical wherever they are produced.  Loads are issued eight at a time ahead
+// of the arithmetic (the order of the arithmetic does not change).
+__device__ __forceinline__ void wave_row_stats(const float *x, const int32_t *N, int n, int lane, float &m_out,
+                                               float &D_out)
 {
+    constexpr int UN = 8;
     float m = SQ_NEG_INF;
-    for (int i = lane; i < n; i += 64)
-        if (N[i] > 0) m = fmaxf(m, x[i]);
+    for (int i0 = 0; i0 < n; i0 += 64 * UN) {
+        float xv[UN];
+        int nv[UN];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int i = i0 + u * 64 + lane;
+            nv[u] = i < n ? N[i] : 0;
+            xv[u] = i < n ? x[i] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u)
+            if (nv[u] > 0) m = fmaxf(m, xv[u]);
+    }
     m = wave_max(m);
     float Dsum = 0.0f;
-    for (int i = lane; i < n; i += 64) {
-        int Ni = N[i];
-        if (Ni > 0) Dsum += (float)Ni * expf(x[i] - m);
+    for (int i0 = 0; i0 < n; i0 += 64 * UN) {
+        float xv[UN];
+        int nv[UN];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int i = i0 + u * 64 + lane;
+            nv[u] = i < n ? N[i] : 0;
+            xv[u] = i < n ? x[i] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u)
+            if (nv[u] > 0) Dsum += (float)nv[u] * expf(xv[u] - m);
     }
     m_out = m;
     D_out = wave_sum(Dsum);

@@ -1,13 +1,17 @@
 // Decode-time sparse attention (Section 4.2): exact attention of one query per (sequence, head) over
-// the selected fixed-context key ranges plus the dense user keys, split along the key dimension into
-// chunks of KPC keys (the split-KV scheme: a head that keeps more keys gets more workgroups), each
-// chunk producing a partial (max, sum, output) that a second phase merges.
+// the selected fixed-context keys plus the dense user keys, split along the key dimension into
+// chunks of KPC keys (the split-KV scheme: a head that keeps more keys gets more workgroups).  Each
+// chunk produces a partial (max, sum, output); the workgroup that finishes a row last merges the
+// row's partials (phase 2 of Section 4.2 without a second launch).
 //
 // The kernel is bound by HBM: every selected K and V row (256 B each) is read exactly once.  A
-// workgroup owns one chunk; 16 lanes share a row (16 B per lane, so a wave-wide load covers four
-// whole rows), and every lane issues all of its K and V loads before any arithmetic, so a
-// workgroup keeps its whole 128 KiB chunk in flight.  Scores are reduced over the 16 lanes of a row
-// with DPP rotations; the softmax runs per wave and the four wave results are combined in LDS.
+// workgroup owns one chunk; its 256 threads fetch the chunk's range records with one coalesced load
+// and turn them into one row index per key in LDS, then 16 lanes share a row (16 B per lane, a wave-wide load covers four whole rows) and every lane
+// issues all of its K and V loads before any arithmetic, so a workgroup keeps its whole chunk in
+// flight.  Scores are reduced over the 16 lanes of a row with DPP rotations; the softmax runs per
+// wave and the four wave results are combined in LDS.
+#include <stdlib.h>
+
 #include "sq_common.hpp"
 #include "sq_internal.hpp"
 
@@ -16,168 +20,235 @@ namespace sq {
 constexpr int KW = KPC / 4;     // keys per wave
 constexpr int NI = KW / 4;      // loads per lane (4 rows per wave-wide load)
 
-__global__ __launch_bounds__(256) void decode_partial_kernel(
+// Merge of n partials of one row by a 1024-thread workgroup:
+//   out = sum_c e^{m_c - M} o_c / sum_c e^{m_c - M} l_c,   lse = M + log(sum_c e^{m_c - M} l_c).
+// 32 groups of 32 threads; group g folds partials g, g+32, ... with a running maximum (a thread owns
+// four output dimensions, 16-byte loads, four partials in flight), then the groups are folded in LDS.
+constexpr int MERGE_THREADS = 1024;
+constexpr int MERGE_GROUPS = MERGE_THREADS / 32;
+__device__ __forceinline__ void merge_row(const float *__restrict__ base, int n, _Float16 *__restrict__ out_row,
+                                          float *lse_row, float *s_red /*[MERGE_GROUPS * 130]*/, int tid)
+{
+    const int quad = tid & 31, grp = tid >> 5;
+    float M = SQ_NEG_INF, lsum = 0.0f;
+    f4 acc = {0.f, 0.f, 0.f, 0.f};
+    int c = grp;
+    for (; c + 3 * MERGE_GROUPS < n; c += 4 * MERGE_GROUPS) {
+        const float *p0 = base + (size_t)c * PART_STRIDE, *p1 = p0 + MERGE_GROUPS * PART_STRIDE,
+                    *p2 = p1 + MERGE_GROUPS * PART_STRIDE, *p3 = p2 + MERGE_GROUPS * PART_STRIDE;
+        const float2 a0 = *reinterpret_cast<const float2 *>(p0), a1 = *reinterpret_cast<const float2 *>(p1),
+                     a2 = *reinterpret_cast<const float2 *>(p2), a3 = *reinterpret_cast<const float2 *>(p3);
+        const f4 o0 = *reinterpret_cast<const f4 *>(p0 + 4 + quad * 4), o1 = *reinterpret_cast<const f4 *>(p1 + 4 + quad * 4),
+                 o2 = *reinterpret_cast<const f4 *>(p2 + 4 + quad * 4), o3 = *reinterpret_cast<const f4 *>(p3 + 4 + quad * 4);
+        const float Mn = fmaxf(fmaxf(M, fmaxf(a0.x, a1.x)), fmaxf(a2.x, a3.x));
+        const float sc = __expf(M - Mn);                 // M = -inf on the first pass: scale 0
+        const float w0 = __expf(a0.x - Mn), w1 = __expf(a1.x - Mn), w2 = __expf(a2.x - Mn), w3 = __expf(a3.x - Mn);
+        acc = acc * sc + o0 * w0 + o1 * w1 + o2 * w2 + o3 * w3;
+        lsum = lsum * sc + a0.y * w0 + a1.y * w1 + a2.y * w2 + a3.y * w3;
+        M = Mn;
+    }
+    for (; c < n; c += MERGE_GROUPS) {
+        const float *p = base + (size_t)c * PART_STRIDE;
+        const float2 a = *reinterpret_cast<const float2 *>(p);
+        const f4 o = *reinterpret_cast<const f4 *>(p + 4 + quad * 4);
+        const float Mn = fmaxf(M, a.x);
+        const float sc = __expf(M - Mn), w = __expf(a.x - Mn);
+        acc = acc * sc + o * w;
+        lsum = lsum * sc + a.y * w;
+        M = Mn;
+    }
+    // Fold the groups: s_red[g] = (M_g, l_g, o_g[128]).  A group that saw no partial has M_g = -inf.
+    float *mine = s_red + grp * 130;
+    if (quad == 0) {
+        mine[0] = M;
+        mine[1] = lsum;
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) mine[2 + quad * 4 + e] = acc[e];
+    __syncthreads();
+    if (tid < D) {
+        float Mt = SQ_NEG_INF;
+#pragma unroll
+        for (int g = 0; g < MERGE_GROUPS; ++g) Mt = fmaxf(Mt, s_red[g * 130]);
+        float a = 0.0f, l = 0.0f;
+#pragma unroll
+        for (int g = 0; g < MERGE_GROUPS; ++g) {
+            const float mg = s_red[g * 130];
+            const float w = mg == SQ_NEG_INF ? 0.0f : __expf(mg - Mt);
+            a += w * s_red[g * 130 + 2 + tid];
+            l += w * s_red[g * 130 + 1];
+        }
+        const bool empty = n == 0 || !(l > 0.0f);
+        out_row[tid] = (_Float16)(empty ? 0.0f : a / l);
+        if (lse_row && tid == 0) *lse_row = empty ? SQ_NEG_INF : Mt + logf(l);
+    }
+}
+
+// Phase 1: one work item = one chunk of up to KPC keys of one (sequence, head) row.  The grid is a fixed
+// number of workgroups; workgroup w takes items w, w + gridDim.x, ... below the item count the schedule
+// kernel left in the plan, so no workgroup is launched for chunks that do not exist.
+__global__ __launch_bounds__(256) void decode_attn_kernel(
     const _Float16 *__restrict__ q, const _Float16 *__restrict__ Kf, const _Float16 *__restrict__ Vf,
     const _Float16 *__restrict__ Ku, const _Float16 *__restrict__ Vu, DecodePlan plan,
-    float *__restrict__ partials, int H, int L, int U, int n_user_chunks, float sm_scale)
+    float *__restrict__ partials, int H, int L, int U, float sm_scale)
 {
-    __shared__ int4 s_rec[KPC];
+    __shared__ int s_pos[KPC], s_delta[KPC];
     __shared__ int s_rows[KPC];
     __shared__ float s_part[4][PART_STRIDE];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 4, p = lane & 15;
-    const int c = blockIdx.x;
-    const size_t bh = blockIdx.y;
-    const int h = (int)(bh % H);
-    const int chunks_per_row = n_user_chunks + plan.chunk_cap;
 
-    const h8 qv = *reinterpret_cast<const h8 *>(q + bh * D + p * 8);
+    // The item count, the first item's header and its records are independent loads: one round trip.
+    // (blockIdx.x < item_cap, so the speculative loads stay inside the plan.)
+    int item = blockIdx.x;
+    const int2 *it = plan.item + (size_t)item * ITEM_STRIDE;
+    int2 h0_next = it[0], h1_next = it[1], rec_next = it[2 + (tid < KPC ? tid : 0)];   // threads >= KPC idle here
+    const int total = min(*plan.total, plan.item_cap);
 
-    const _Float16 *Kbase, *Vbase;
-    int nvalid;
-    const bool user = c < n_user_chunks;
-    if (user) {
-        const int k0 = c * KPC;
-        nvalid = min(KPC, U - k0);
-        Kbase = Ku + (bh * U + k0) * D;
-        Vbase = Vu + (bh * U + k0) * D;
-    } else {
-        const int cf = c - n_user_chunks;
-        const int2 hdr = plan.hdr[bh];                 // (records, selected keys)
-        const int key0 = cf * KPC;
-        if (key0 >= hdr.y) return;                     // chunk past the selection: whole workgroup leaves
-        nvalid = min(KPC, hdr.y - key0);
-        const int first = plan.chunk_first[bh * plan.chunk_cap + cf];
-        // A chunk of KPC keys touches at most KPC records (each holds at least one of its keys).
-        {
-            const int idx = first + tid;
-            int4 r = make_int4(0, 0, 0x7fffffff, 0);
-            if (idx < hdr.x) r = plan.rec[bh * plan.rec_cap + idx];
-            s_rec[tid] = r;
+    for (; item < total; item += gridDim.x) {
+        const int2 h0 = h0_next, h1 = h1_next, rc = rec_next;   // (row, keys) (records | -1, first user key)
+        const size_t bh = (size_t)h0.x;
+        const int nvalid = h0.y;
+        const bool user = h1.x < 0;
+        const int nrec = min(h1.x, KPC);
+        const int h = (int)(bh % H);
+        const _Float16 *Kbase, *Vbase;
+        const h8 qv = *reinterpret_cast<const h8 *>(q + bh * D + p * 8);
+        if (user) {
+            Kbase = Ku + (bh * U + h1.y) * D;
+            Vbase = Vu + (bh * U + h1.y) * D;
+            if (tid < KPC) s_rows[tid] = tid < nvalid ? tid : -1;
+        } else {
+            Kbase = Kf + (size_t)h * L * D;
+            Vbase = Vf + (size_t)h * L * D;
+            if (tid < KPC) {
+                s_pos[tid] = rc.x;
+                s_delta[tid] = rc.y;
+            }
+            __syncthreads();
+            // Key slot `tid` lies in the last record whose position is <= tid (positions ascend; the
+            // first record's position is <= 0).
+            if (tid < KPC) {
+                int lo = 0;
+#pragma unroll
+                for (int step = KPC / 2; step > 0; step >>= 1)
+                    if (lo + step < nrec && s_pos[lo + step] <= tid) lo += step;
+                const int rowi = tid + s_delta[lo];
+                s_rows[tid] = tid < nvalid ? max(0, min(rowi, L - 1)) : -1;   // malformed ranges stay in the tensor
+            }
         }
         __syncthreads();
-        {
-            // Last staged record whose key prefix is <= this thread's key (records ascend in .z).
-            const int kk = key0 + min(tid, nvalid - 1);
-            int lo = 0;
+
+        // Issue every K and V load of this lane.
+        h8 kreg[NI], vreg[NI];
+        const int r_last = s_rows[nvalid - 1];
 #pragma unroll
-            for (int step = KPC / 2; step > 0; step >>= 1)
-                if (s_rec[lo + step].z <= kk) lo += step;
-            const int4 r = s_rec[lo];
-            int rowi = r.x + (kk - r.z);
-            rowi = max(0, min(rowi, L - 1));           // malformed ranges cannot leave the tensor
-            s_rows[tid] = rowi;
+        for (int i = 0; i < NI; ++i) {
+            const int kl = wave * KW + i * 4 + g;
+            int r = s_rows[kl];
+            r = r < 0 ? r_last : r;                       // slots past the chunk re-read a valid row
+            const size_t o = (size_t)r * D + p * 8;
+            kreg[i] = *reinterpret_cast<const h8 *>(Kbase + o);
+            vreg[i] = *reinterpret_cast<const h8 *>(Vbase + o);
+        }
+        // Metadata of this workgroup's next item, fetched behind the K/V stream.
+        if (item + (int)gridDim.x < total) {
+            const int2 *nx = plan.item + (size_t)(item + gridDim.x) * ITEM_STRIDE;
+            h0_next = nx[0];
+            h1_next = nx[1];
+            rec_next = nx[2 + (tid < KPC ? tid : 0)];
+        }
+
+        // Scores of this lane-group's keys and the wave-local softmax.
+        float s[NI];
+        float m_w = SQ_NEG_INF;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int kl = wave * KW + i * 4 + g;
+            const float d = row16_sum(dot8(qv, kreg[i], 0.0f)) * sm_scale;
+            s[i] = kl < nvalid ? d : SQ_NEG_INF;
+            m_w = fmaxf(m_w, s[i]);
+        }
+        m_w = cross16_max(m_w);
+        float l_w = 0.0f;
+        float o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const float pr = s[i] == SQ_NEG_INF ? 0.0f : __expf(s[i] - m_w);
+            l_w += pr;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] += pr * (float)vreg[i][e];
+        }
+        l_w = cross16_sum(l_w);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = cross16_sum(o[e]);
+        if (g == 0) {
+            if (p == 0) {
+                s_part[wave][0] = m_w;
+                s_part[wave][1] = l_w;
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s_part[wave][4 + p * 8 + e] = o[e];
         }
         __syncthreads();
-        Kbase = Kf + (size_t)h * L * D;
-        Vbase = Vf + (size_t)h * L * D;
-    }
 
-    // Issue every K and V load of this lane.
-    h8 kreg[NI], vreg[NI];
+        // Combine the four waves; threads 0..127 own one output dimension each.
+        if (tid < D) {
+            const float M = fmaxf(fmaxf(s_part[0][0], s_part[1][0]), fmaxf(s_part[2][0], s_part[3][0]));
+            float lsum = 0.0f, acc = 0.0f;
 #pragma unroll
-    for (int i = 0; i < NI; ++i) {
-        const int kl = wave * KW + i * 4 + g;
-        const int rowi = user ? min(kl, nvalid - 1) : s_rows[kl];
-        const size_t o = (size_t)rowi * D + p * 8;
-        kreg[i] = *reinterpret_cast<const h8 *>(Kbase + o);
-        vreg[i] = *reinterpret_cast<const h8 *>(Vbase + o);
-    }
-
-    // Scores of this lane-group's keys and the wave-local softmax.
-    float s[NI];
-    float m_w = SQ_NEG_INF;
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-        const int kl = wave * KW + i * 4 + g;
-        float d = row16_sum(dot8(qv, kreg[i], 0.0f)) * sm_scale;
-        s[i] = kl < nvalid ? d : SQ_NEG_INF;
-        m_w = fmaxf(m_w, s[i]);
-    }
-    m_w = cross16_max(m_w);
-    float l_w = 0.0f;
-    float o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-        const float pr = s[i] == SQ_NEG_INF ? 0.0f : __expf(s[i] - m_w);
-        l_w += pr;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] += pr * (float)vreg[i][e];
-    }
-    l_w = cross16_sum(l_w);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) o[e] = cross16_sum(o[e]);
-    if (g == 0) {
-        if (p == 0) {
-            s_part[wave][0] = m_w;
-            s_part[wave][1] = l_w;
+            for (int w = 0; w < 4; ++w) {
+                const float mw = s_part[w][0];
+                const float sc = mw == SQ_NEG_INF ? 0.0f : __expf(mw - M);
+                lsum += sc * s_part[w][1];
+                acc += sc * s_part[w][4 + tid];
+            }
+            float *dst = partials + (size_t)item * PART_STRIDE;
+            if (tid == 0) {
+                dst[0] = M;
+                dst[1] = lsum;
+            }
+            dst[4 + tid] = acc;
         }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) s_part[wave][4 + p * 8 + e] = o[e];
-    }
-    __syncthreads();
-
-    // Combine the four waves; threads 0..127 own one output dimension each.
-    if (tid < D) {
-        float M = fmaxf(fmaxf(s_part[0][0], s_part[1][0]), fmaxf(s_part[2][0], s_part[3][0]));
-        float lsum = 0.0f, acc = 0.0f;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            const float mw = s_part[w][0];
-            const float sc = mw == SQ_NEG_INF ? 0.0f : __expf(mw - M);
-            lsum += sc * s_part[w][1];
-            acc += sc * s_part[w][4 + tid];
-        }
-        float *dst = partials + (bh * chunks_per_row + c) * PART_STRIDE;
-        if (tid == 0) {
-            dst[0] = M;
-            dst[1] = lsum;
-        }
-        dst[4 + tid] = acc;
+        __syncthreads();      // LDS is reused by the next item
     }
 }
 
-// Phase 2: merge the partials of one (sequence, head):  out = sum_c e^{m_c - M} o_c / sum_c e^{m_c - M} l_c.
-__global__ __launch_bounds__(128) void decode_merge_kernel(const float *__restrict__ partials, DecodePlan plan,
-                                                           _Float16 *__restrict__ out, float *__restrict__ lse,
-                                                           int U, int n_user_chunks)
+// Phase 2 (Section 4.2): one workgroup per (sequence, head) merges the row's partials.  A separate
+// launch, so the kernel boundary makes the partials visible: a device-wide fence inside the partial
+// kernel would write back a whole L2 per workgroup and costs far more than this launch.
+__global__ __launch_bounds__(MERGE_THREADS) void decode_merge_kernel(const float *__restrict__ partials,
+                                                                     DecodePlan plan, _Float16 *__restrict__ out,
+                                                                     float *__restrict__ lse)
 {
+    __shared__ float s_red[MERGE_GROUPS * 130];
     const size_t bh = blockIdx.x;
-    const int tid = threadIdx.x;
-    const int chunks_per_row = n_user_chunks + plan.chunk_cap;
-    const int n_fixed = (plan.hdr[bh].y + KPC - 1) / KPC;
-    const float *base = partials + bh * chunks_per_row * PART_STRIDE;
-    // Valid chunks: user chunks 0..n_user_chunks-1, fixed chunks n_user_chunks..n_user_chunks+n_fixed-1.
-    const int n = n_user_chunks + n_fixed;
-    float M = SQ_NEG_INF;
-    for (int c = 0; c < n; ++c) M = fmaxf(M, base[c * PART_STRIDE]);
-    float lsum = 0.0f, acc = 0.0f;
-    for (int c = 0; c < n; ++c) {
-        const float *pc = base + c * PART_STRIDE;
-        const float sc = __expf(pc[0] - M);
-        lsum += sc * pc[1];
-        acc += sc * pc[4 + tid];
-    }
-    const bool empty = n == 0 || lsum == 0.0f;
-    out[bh * D + tid] = (_Float16)(empty ? 0.0f : acc / lsum);
-    if (lse && tid == 0) lse[bh] = empty ? SQ_NEG_INF : M + logf(lsum);
+    const int2 it = plan.row_items[bh];              // (first item, items) of this row
+    merge_row(partials + (size_t)it.x * PART_STRIDE, it.y, out + bh * D, lse ? lse + bh : nullptr, s_red,
+              threadIdx.x);
 }
+
+// Workgroups of the persistent partial kernel: enough to hold every chunk of a typical selection in one
+// pass and to fill all 256 compute units several times over.
+constexpr int ATTN_GRID = 256 * 4;
 
 hipError_t launch_decode_attn(const void *q, const void *Kf, const void *Vf, const void *Ku, const void *Vu,
-                              DecodePlan plan, const int32_t *, const int32_t *, float *partials, void *out,
-                              float *lse, const Shape &sh, hipStream_t s)
+                              DecodePlan plan, float *partials, void *out, float *lse, const Shape &sh,
+                              hipStream_t s)
 {
-    const int nuc = user_chunks_for(sh.U);
     const int rows = sh.B * sh.H;
-    dim3 grid(nuc + plan.chunk_cap, rows);
-    hipLaunchKernelGGL(decode_partial_kernel, grid, dim3(256), 0, s, (const _Float16 *)q, (const _Float16 *)Kf,
+    static const int grid_env = getenv("SQ_ATTN_GRID") ? atoi(getenv("SQ_ATTN_GRID")) : 0;   // tuning knob
+    const int want = grid_env > 0 ? grid_env : ATTN_GRID;
+    const int grid = plan.item_cap < want ? plan.item_cap : want;
+    const bool prof = profile_mark(s, true);
+    hipLaunchKernelGGL(decode_attn_kernel, dim3(grid), dim3(256), 0, s, (const _Float16 *)q, (const _Float16 *)Kf,
                        (const _Float16 *)Vf, (const _Float16 *)Ku, (const _Float16 *)Vu, plan, partials, sh.H, sh.L,
-                       sh.U, nuc, sh.sm_scale);
+                       sh.U, sh.sm_scale);
+    if (prof) profile_mark(s, false);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(decode_merge_kernel, dim3(rows), dim3(128), 0, s, partials, plan, (_Float16 *)out, lse, sh.U,
-                       nuc);
+    hipLaunchKernelGGL(decode_merge_kernel, dim3(rows), dim3(MERGE_THREADS), 0, s, partials, plan, (_Float16 *)out, lse);
     return hipGetLastError();
 }
 

@@ -13,32 +13,58 @@ struct Shape {
     int causal_user;
 };
 
-// Internal per-row plan of the split-KV decode kernel: one record per kept range with the number of
-// selected keys in front of it, and for every chunk of KPC selected keys the first record it touches.
+// Internal plan of the split-KV decode kernel, held in the workspace.
+//   rec       per row, one record per kept range: (first key, count, selected keys before it, 0)
+//   hdr       per row: (number of records, number of selected keys)
+//   row_items per row: (first work item, number of work items); items of a row are consecutive
+//   total     number of work items of the whole call
+//   item      per work item (= one chunk of up to KPC keys of one row) ITEM_STRIDE int2 slots:
+//             slot 0 = (row, keys in the chunk), slot 1 = (records in the chunk or -1 for a chunk of user
+//             keys, first user key), slots 2.. = the chunk's own copy of the range records it touches, as
+//             (position of the record's first key relative to the chunk, fixed-context row of that key
+//             minus that position): key slot t of the chunk lies in the last record whose position is
+//             <= t and reads row t + delta.  This is the key-index tensor of Section 4.2 in run-length
+//             form, stored chunk by chunk so an attention workgroup gets it with one coalesced load.
+constexpr int ITEM_STRIDE = KPC + 2;     // int2 slots per item: a chunk of KPC keys touches <= KPC records
 struct DecodePlan {
-    int4 *rec;          // [rows, rec_cap]  (first key, count, keys before, 0)
-    int *chunk_first;   // [rows, chunk_cap]
-    int2 *hdr;          // [rows] (number of records, number of selected keys)
+    int4 *rec;        // [rows, rec_cap]
+    int2 *hdr;        // [rows]
+    int2 *row_items;  // [rows]
+    int *total;       // [1]
+    int2 *item;       // [item_cap, ITEM_STRIDE]
     int rec_cap;
-    int chunk_cap;
+    int item_cap;     // rows * (user chunks + ceil(L / KPC))
+    int L;
 };
 
 inline int chunk_cap_for(int L) { return (L + KPC - 1) / KPC; }
 inline int user_chunks_for(int U) { return (U + KPC - 1) / KPC; }
 
-hipError_t launch_score(const void *q, const void *centroids, float *logits, int B, int H, int Lq, int C,
-                        float sm_scale, hipStream_t s);
-hipError_t launch_row_stats(const float *logits, const int32_t *sizes, float *row_max, float *denom,
-                            int rows, int H, int Lq, int C, hipStream_t s);
+// Row-wise selection stages a row's logits and cluster sizes in LDS.
+constexpr int SELECT_MAX_C = 16384;
+// Scheduling keeps two ints per chunk of a row in LDS (same budget as the staged logits).
+constexpr int MAX_L = SELECT_MAX_C * KPC;
+
+// zero_counter (may be null) is set to 0 by the kernel: the item counter of a decode step.
+hipError_t launch_score(const void *q, const void *centroids, float *logits, int *zero_counter, int B, int H, int Lq,
+                        int C, float sm_scale, hipStream_t s);
+hipError_t launch_row_stats(const float *logits, const int32_t *sizes, float *row_max, float *denom, int rows,
+                            int H, int Lq, int C, hipStream_t s);
 // stats_in == true: use row_max/denom; false: the kernel derives them from logits itself.
 hipError_t launch_select(const float *logits, const float *row_max, const float *denom, bool stats_in,
-                         const float *thresh, const int32_t *sizes, const int32_t *offsets,
-                         uint32_t *keep_mask, int32_t *ranges, int32_t *n_ranges, int32_t *n_keys,
-                         DecodePlan plan, int rows, int H, int Lq, int C, hipStream_t s);
-hipError_t launch_plan_from_ranges(const int32_t *ranges, const int32_t *n_ranges, DecodePlan plan, int rows,
-                                   int range_cap, hipStream_t s);
+                         const float *thresh, const int32_t *sizes, const int32_t *offsets, uint32_t *keep_mask,
+                         int32_t *ranges, int32_t *n_ranges, int32_t *n_keys, DecodePlan plan, bool schedule, int U,
+                         int rows, int H, int Lq, int C, hipStream_t s);
+// Caller-style ranges [rows, range_cap, 2] -> records + header per row.
+hipError_t launch_ranges_to_rec(const int32_t *ranges, const int32_t *n_ranges, DecodePlan plan, int rows,
+                                int range_cap, hipStream_t s);
+// Records + headers of all rows -> work items.
+hipError_t launch_schedule(DecodePlan plan, int rows, int U, hipStream_t s);
 hipError_t launch_decode_attn(const void *q, const void *Kf, const void *Vf, const void *Ku, const void *Vu,
-                              DecodePlan plan, const int32_t *n_ranges, const int32_t *n_keys, float *partials,
-                              void *out, float *lse, const Shape &sh, hipStream_t s);
+                              DecodePlan plan, float *partials, void *out, float *lse, const Shape &sh,
+                              hipStream_t s);
+
+// Measurement hook (sq_profile.hip): records an event before / after the partial kernel when enabled.
+bool profile_mark(hipStream_t s, bool begin);
 
 }  // namespace sq

@@ -16,9 +16,10 @@ constexpr int SCORE_ROWS_PER_WG = 4 * 16 * SCORE_TILES_PER_WAVE;     // 4 waves
 
 __global__ __launch_bounds__(256) void score_kernel(const _Float16 *__restrict__ q,
                                                     const _Float16 *__restrict__ cent,
-                                                    float *__restrict__ logits, int B, int H, int Lq, int C,
-                                                    float sm_scale)
+                                                    float *__restrict__ logits, int *__restrict__ zero_counter,
+                                                    int B, int H, int Lq, int C, float sm_scale)
 {
+    if (zero_counter && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) *zero_counter = 0;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & 15, kg = lane >> 4;
     const int h = blockIdx.y;
@@ -83,12 +84,12 @@ __global__ __launch_bounds__(256) void row_stats_kernel(const float *__restrict_
     }
 }
 
-hipError_t launch_score(const void *q, const void *centroids, float *logits, int B, int H, int Lq, int C,
-                        float sm_scale, hipStream_t s)
+hipError_t launch_score(const void *q, const void *centroids, float *logits, int *zero_counter, int B, int H, int Lq,
+                        int C, float sm_scale, hipStream_t s)
 {
     dim3 grid((C + SCORE_ROWS_PER_WG - 1) / SCORE_ROWS_PER_WG, H, (B * Lq + 15) / 16);
-    hipLaunchKernelGGL(score_kernel, grid, dim3(256), 0, s, (const _Float16 *)q, (const _Float16 *)centroids, logits, B,
-                       H, Lq, C, sm_scale);
+    hipLaunchKernelGGL(score_kernel, grid, dim3(256), 0, s, (const _Float16 *)q, (const _Float16 *)centroids, logits,
+                       zero_counter, B, H, Lq, C, sm_scale);
     return hipGetLastError();
 }
 

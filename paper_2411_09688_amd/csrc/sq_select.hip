@@ -3,23 +3,31 @@
 // list of key ranges -- the role the key-index tensor plays in Section 4.2; ranges suffice because
 // clusters are stored contiguously.
 //
-// One workgroup (4 waves) per query row walks the clusters 256 at a time.  Inside a wave the
-// rank of a kept cluster comes from a 64-bit ballot + population count, the number of keys in front
-// of it from a shuffle prefix scan; the four waves are stitched through LDS.  The ballot words are
-// the keep mask.  The same pass emits the decode plan: per kept range the count of selected keys
-// before it, and for each chunk of KPC selected keys the first range it touches, so the split-KV
-// attention kernel can find its keys without scanning the whole list.
+// select_kernel: one workgroup of 16 waves per query row.  The row's logits are staged in LDS and
+// replaced there by e_i = exp(x_i - m), so the comparison with T * D re-reads stored exponentials
+// instead of recomputing anything (the stored-exponential scheme of Appendix D).  Inside a wave the
+// rank of a kept cluster comes from a 64-bit ballot + population count and the number of keys in
+// front of it from a shuffle prefix scan; the waves are stitched through LDS.  The ballot words
+// are the keep mask.
+//
+// ranges_to_rec_kernel turns a caller's range list into the same records the selection emits, and
+// schedule_kernel turns the records of all rows into the work items of the split-KV attention
+// kernel: chunks of KPC selected keys (Section 4.2: a fixed number of keys per workgroup, so rows
+// that keep more keys get more workgroups), each carrying its own copy of the records it touches.
 #include "sq_common.hpp"
 #include "sq_internal.hpp"
 
 namespace sq {
 
-// Block-wide exclusive offsets of (count, keys) for one 256-wide step.  Returns this thread's
-// exclusive rank / key prefix inside the block and the block totals.
+constexpr int SEL_THREADS = 1024;
+constexpr int SEL_WAVES = SEL_THREADS / 64;
+
 struct ScanOut {
     int rank, key_prefix, total_cnt, total_keys;
 };
 
+// Block-wide exclusive rank / key prefix of the kept items of one block-wide step (NW waves).
+template <int NW>
 __device__ __forceinline__ ScanOut block_scan_kept(bool keep, int nkeys, int lane, int wave, int *s_cnt, int *s_keys,
                                                    unsigned long long &ballot_out)
 {
@@ -35,8 +43,8 @@ __device__ __forceinline__ ScanOut block_scan_kept(bool keep, int nkeys, int lan
     __syncthreads();
     ScanOut o{lane_rank, incl - kv, 0, 0};
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-        int c = s_cnt[w], k = s_keys[w];
+    for (int w = 0; w < NW; ++w) {
+        const int c = s_cnt[w], k = s_keys[w];
         if (w < wave) {
             o.rank += c;
             o.key_prefix += k;
@@ -48,27 +56,79 @@ __device__ __forceinline__ ScanOut block_scan_kept(bool keep, int nkeys, int lan
     return o;
 }
 
-// Record r of a row: (first key, count, selected keys before it); it is the first record of every
-// chunk whose first key falls inside it.
-__device__ __forceinline__ void emit_plan_record(const DecodePlan &plan, size_t row, int r, int start, int len, int cum)
+// Work items of one row, written by the calling workgroup (nthreads threads).  The row owns
+// n_user_chunks + ceil(n_sel / KPC) consecutive items starting at *s_base_ptr (read after the first
+// barrier, so the caller may still be fetching it); each record copies itself into every chunk it
+// touches.  s_first: LDS scratch, two ints per fixed-context chunk of the row.
+// REG: the caller's threads each hold at most one record (have_rec, my_r, my_rec) in registers, as they
+// do after a single selection step; otherwise the records are read back from plan.rec.
+template <bool REG>
+__device__ __forceinline__ void emit_row_items(const DecodePlan &plan, int row, const int *s_base_ptr, int n_rec,
+                                               int n_sel, int U, int n_user_chunks, int *s_first, int tid,
+                                               int nthreads, bool have_rec, int my_r, int4 my_rec)
 {
-    plan.rec[row * plan.rec_cap + r] = make_int4(start, len, cum, 0);
-    const int c_lo = (cum + KPC - 1) / KPC, c_hi = (cum + len - 1) / KPC;
-    for (int c = c_lo; c <= c_hi && c < plan.chunk_cap; ++c) plan.chunk_first[row * plan.chunk_cap + c] = r;
+    const int n_fixed = (n_sel + KPC - 1) / KPC;
+    int *s_firstz = s_first + n_fixed;                      // selected keys before the chunk's first record
+    const int4 *rec_row = plan.rec + (size_t)row * plan.rec_cap;
+    // Pass 1: the record that holds a chunk's first key is the chunk's first record.
+    for (int r = REG ? my_r : tid; REG ? have_rec : r < n_rec; r += nthreads) {
+        const int4 rc = REG ? my_rec : rec_row[r];
+        const int c_lo = (rc.z + KPC - 1) / KPC, c_hi = min((rc.z + rc.y - 1) / KPC, n_fixed - 1);
+        for (int c = c_lo; c <= c_hi; ++c) {
+            s_first[c] = r;
+            s_firstz[c] = rc.z;
+        }
+        if (REG) break;
+    }
+    __syncthreads();
+    const int base = *s_base_ptr;
+    if (tid == 0) plan.row_items[row] = make_int2(base, n_user_chunks + n_fixed);
+    for (int c = tid; c < n_user_chunks; c += nthreads) {
+        int2 *it = plan.item + (size_t)(base + c) * ITEM_STRIDE;
+        it[0] = make_int2(row, min(KPC, U - c * KPC));
+        it[1] = make_int2(-1, c * KPC);
+    }
+    // Pass 2: every record writes its (position, delta) into the chunks it touches.
+    for (int r = REG ? my_r : tid; REG ? have_rec : r < n_rec; r += nthreads) {
+        const int4 rc = REG ? my_rec : rec_row[r];
+        const int c_lo = rc.z / KPC, c_hi = min((rc.z + rc.y - 1) / KPC, n_fixed - 1);
+        for (int c = c_lo; c <= c_hi; ++c) {
+            int2 *it = plan.item + (size_t)(base + n_user_chunks + c) * ITEM_STRIDE;
+            const int pos = rc.z - c * KPC;                 // negative for a record that began in an earlier chunk
+            it[2 + r - s_first[c]] = make_int2(pos, rc.x - pos);
+        }
+        if (REG) break;
+    }
+    // Chunk headers.  The last record touching chunk c is the first record of chunk c+1 if that record
+    // began before the boundary, else the one before it.
+    for (int c = tid; c < n_fixed; c += nthreads) {
+        int2 *it = plan.item + (size_t)(base + n_user_chunks + c) * ITEM_STRIDE;
+        int last;
+        if (c + 1 < n_fixed) {
+            const int f = s_first[c + 1];
+            last = s_firstz[c + 1] == (c + 1) * KPC ? f - 1 : f;
+        } else {
+            last = n_rec - 1;
+        }
+        it[0] = make_int2(row, min(KPC, n_sel - c * KPC));
+        it[1] = make_int2(last - s_first[c] + 1, 0);
+    }
 }
 
-template <bool STATS_IN>
-__global__ __launch_bounds__(256) void select_kernel(const float *__restrict__ logits,
-                                                     const float *__restrict__ row_max,
-                                                     const float *__restrict__ denom,
-                                                     const float *__restrict__ thresh,
-                                                     const int32_t *__restrict__ sizes,
-                                                     const int32_t *__restrict__ offsets,
-                                                     uint32_t *__restrict__ keep_mask, int32_t *__restrict__ ranges,
-                                                     int32_t *__restrict__ n_ranges, int32_t *__restrict__ n_keys,
-                                                     DecodePlan plan, int H, int Lq, int C)
+template <bool STATS_IN, bool SCHEDULE>
+__global__ __launch_bounds__(SEL_THREADS) void select_kernel(
+    const float *__restrict__ logits, const float *__restrict__ row_max, const float *__restrict__ denom,
+    const float *__restrict__ thresh, const int32_t *__restrict__ sizes, const int32_t *__restrict__ offsets,
+    uint32_t *__restrict__ keep_mask, int32_t *__restrict__ ranges, int32_t *__restrict__ n_ranges,
+    int32_t *__restrict__ n_keys, DecodePlan plan, int H, int Lq, int C, int U, int n_user_chunks)
 {
-    __shared__ int s_cnt[4], s_keys[4];
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ float s_wred[SEL_WAVES];
+    __shared__ int s_base;
+    __shared__ int s_cnt[SEL_WAVES], s_keys[SEL_WAVES];
+    __shared__ float s_thr;
+    float *s_e = reinterpret_cast<float *>(smem);          // [C] logits, then e_i
+    int32_t *s_N = reinterpret_cast<int32_t *>(s_e + C);   // [C]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const size_t row = blockIdx.x;
     const int h = (int)((row / Lq) % H);
@@ -76,32 +136,70 @@ __global__ __launch_bounds__(256) void select_kernel(const float *__restrict__ l
     const int32_t *N = sizes + (size_t)h * C;
     const int32_t *off = offsets + (size_t)h * (C + 1);
     const int W = (C + 31) >> 5;
+    const float T = thresh[h];
 
-    float m, Dsum;
+    for (int i = tid; i < C; i += SEL_THREADS) {
+        s_e[i] = x[i];
+        s_N[i] = N[i];
+    }
+    int start_first = tid < C ? off[tid] : 0;               // offsets of the first step, fetched with the logits
+    float m;
     if (STATS_IN) {
         m = row_max[row];
-        Dsum = denom[row];
+        if (tid == 0) s_thr = T * denom[row];
+        __syncthreads();
+        for (int i = tid; i < C; i += SEL_THREADS) s_e[i] = s_N[i] > 0 ? expf(s_e[i] - m) : 0.0f;
     } else {
-        wave_row_stats(x, N, C, lane, m, Dsum);      // every wave derives the same (m, D)
+        __syncthreads();
+        m = SQ_NEG_INF;
+        for (int i = tid; i < C; i += SEL_THREADS)
+            if (s_N[i] > 0) m = fmaxf(m, s_e[i]);
+        m = wave_max(m);
+        if (lane == 0) s_wred[wave] = m;
+        __syncthreads();
+        m = s_wred[0];
+#pragma unroll
+        for (int w = 1; w < SEL_WAVES; ++w) m = fmaxf(m, s_wred[w]);
+        for (int i = tid; i < C; i += SEL_THREADS) s_e[i] = s_N[i] > 0 ? expf(s_e[i] - m) : 0.0f;
+        __syncthreads();
+        // D in the library's one summation order: lane l adds clusters l, l+64, ... ascending, then a
+        // butterfly over the 64 lanes (identical to wave_row_stats).
+        if (wave == 0) {
+            float Dsum = 0.0f;
+            for (int i = lane; i < C; i += 64) {
+                const int Ni = s_N[i];
+                if (Ni > 0) Dsum += (float)Ni * s_e[i];
+            }
+            Dsum = wave_sum(Dsum);
+            if (lane == 0) s_thr = T * Dsum;
+        }
     }
-    const float thr = thresh[h] * Dsum;
+    __syncthreads();
+    const float thr = s_thr;
 
     int base_r = 0, base_k = 0;
-    for (int i0 = 0; i0 < C; i0 += 256) {
+    bool have_rec = false;                                   // this thread's record of the (only) step
+    int my_r = 0;
+    int4 my_rec = make_int4(0, 0, 0, 0);
+    for (int i0 = 0; i0 < C; i0 += SEL_THREADS) {
         const int i = i0 + tid;
-        const int Ni = i < C ? N[i] : 0;
-        const bool keep = Ni > 0 && expf(x[i] - m) > thr;
+        const int Ni = i < C ? s_N[i] : 0;
+        const bool keep = Ni > 0 && s_e[i] > thr;
+        const int start = i0 == 0 ? start_first : (keep ? off[i] : 0);
         unsigned long long bal;
-        const ScanOut sc = block_scan_kept(keep, Ni, lane, wave, s_cnt, s_keys, bal);
+        const ScanOut sc = block_scan_kept<SEL_WAVES>(keep, Ni, lane, wave, s_cnt, s_keys, bal);
         if (lane == 0 && keep_mask) {
             const int w0 = (i0 >> 5) + wave * 2;
             if (w0 < W) keep_mask[row * W + w0] = (uint32_t)bal;
             if (w0 + 1 < W) keep_mask[row * W + w0 + 1] = (uint32_t)(bal >> 32);
         }
         if (keep) {
-            const int r = base_r + sc.rank, cum = base_k + sc.key_prefix, start = off[i];
+            const int r = base_r + sc.rank;
             if (ranges) *reinterpret_cast<int2 *>(ranges + (row * C + r) * 2) = make_int2(start, Ni);
-            if (plan.rec) emit_plan_record(plan, row, r, start, Ni, cum);
+            my_rec = make_int4(start, Ni, base_k + sc.key_prefix, 0);
+            my_r = r;
+            have_rec = true;
+            if (plan.rec) plan.rec[row * plan.rec_cap + r] = my_rec;
         }
         base_r += sc.total_cnt;
         base_k += sc.total_keys;
@@ -111,50 +209,136 @@ __global__ __launch_bounds__(256) void select_kernel(const float *__restrict__ l
         n_keys[row] = base_k;
         if (plan.rec) plan.hdr[row] = make_int2(base_r, base_k);
     }
+    if (SCHEDULE) {
+        // This row's work items, placed at a base taken from a device-wide counter (zeroed by the scoring
+        // kernel that ran before): rows land in arrival order, which moves chunks between workgroups but
+        // changes no result.  The records written above are read back after the barrier.
+        const int n_sel = min(base_k, plan.L);
+        if (tid == 0) s_base = atomicAdd(plan.total, n_user_chunks + (n_sel + KPC - 1) / KPC);
+        int *s_first = reinterpret_cast<int *>(smem);       // the staged logits are no longer needed
+        if (C <= SEL_THREADS) {
+            emit_row_items<true>(plan, (int)row, &s_base, base_r, n_sel, U, n_user_chunks, s_first, tid, SEL_THREADS,
+                                 have_rec, my_r, my_rec);
+        } else {
+            __syncthreads();                                // records of every step are in plan.rec
+            emit_row_items<false>(plan, (int)row, &s_base, base_r, n_sel, U, n_user_chunks, s_first, tid, SEL_THREADS,
+                                  false, 0, my_rec);
+        }
+    }
 }
 
-// Plan for ranges that came from the caller (standalone attention call): prefix-sum the counts.
-__global__ __launch_bounds__(256) void plan_from_ranges_kernel(const int32_t *__restrict__ ranges,
-                                                               const int32_t *__restrict__ n_ranges, DecodePlan plan,
-                                                               int range_cap)
+// Caller-provided ranges -> records (start, count, keys before) + header.  Empty ranges are dropped.
+__global__ __launch_bounds__(256) void ranges_to_rec_kernel(const int32_t *__restrict__ ranges,
+                                                            const int32_t *__restrict__ n_ranges, DecodePlan plan,
+                                                            int range_cap)
 {
     __shared__ int s_cnt[4], s_keys[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const size_t row = blockIdx.x;
-    const int nr = n_ranges[row];
+    const int nr = min(n_ranges[row], range_cap);
+    int4 *rec_row = plan.rec + row * plan.rec_cap;
     int base_r = 0, base_k = 0;
     for (int r0 = 0; r0 < nr; r0 += 256) {
         const int r = r0 + tid;
         int2 rg = make_int2(0, 0);
         if (r < nr) rg = *reinterpret_cast<const int2 *>(ranges + (row * range_cap + r) * 2);
-        const bool live = r < nr && rg.y > 0;          // empty ranges are dropped from the plan
+        const bool live = r < nr && rg.y > 0;
         unsigned long long bal;
-        const ScanOut sc = block_scan_kept(live, rg.y, lane, wave, s_cnt, s_keys, bal);
-        if (live) emit_plan_record(plan, row, base_r + sc.rank, rg.x, rg.y, base_k + sc.key_prefix);
+        const ScanOut sc = block_scan_kept<4>(live, rg.y, lane, wave, s_cnt, s_keys, bal);
+        if (live && base_r + sc.rank < plan.rec_cap)
+            rec_row[base_r + sc.rank] = make_int4(rg.x, rg.y, base_k + sc.key_prefix, 0);
         base_r += sc.total_cnt;
         base_k += sc.total_keys;
     }
-    if (tid == 0) plan.hdr[row] = make_int2(base_r, base_k);
+    if (tid == 0) plan.hdr[row] = make_int2(min(base_r, plan.rec_cap), base_k);
 }
 
+// Work items from the records of all rows, in row order: every workgroup derives its row's first item
+// from the headers of all rows (a few hundred integers), so the rows need no second pass.
+__global__ __launch_bounds__(256) void schedule_kernel(DecodePlan plan, int rows, int U, int n_user_chunks)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    int *s_first = reinterpret_cast<int *>(smem);
+    __shared__ int s_wsum[2][4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int row = blockIdx.x;
+    const int L = plan.L;
+    int before = 0, total = 0;
+    for (int r = tid; r < rows; r += 256) {
+        const int cnt = n_user_chunks + (min(plan.hdr[r].y, L) + KPC - 1) / KPC;
+        total += cnt;
+        if (r < row) before += cnt;
+    }
+    before = wave_sum_i(before);
+    total = wave_sum_i(total);
+    if (lane == 0) {
+        s_wsum[0][wave] = before;
+        s_wsum[1][wave] = total;
+    }
+    __syncthreads();
+    __shared__ int s_base;
+    total = s_wsum[1][0] + s_wsum[1][1] + s_wsum[1][2] + s_wsum[1][3];
+    const int2 hdr = plan.hdr[row];
+    if (tid == 0) {
+        s_base = s_wsum[0][0] + s_wsum[0][1] + s_wsum[0][2] + s_wsum[0][3];
+        if (row == 0) *plan.total = total;
+    }
+    emit_row_items<false>(plan, row, &s_base, min(hdr.x, plan.rec_cap), min(hdr.y, L), U, n_user_chunks, s_first, tid,
+                          256, false, 0, make_int4(0, 0, 0, 0));
+}
+
+// schedule == true also emits the row's work items (decode step; needs *plan.total == 0 on entry).
 hipError_t launch_select(const float *logits, const float *row_max, const float *denom, bool stats_in,
                          const float *thresh, const int32_t *sizes, const int32_t *offsets, uint32_t *keep_mask,
-                         int32_t *ranges, int32_t *n_ranges, int32_t *n_keys, DecodePlan plan, int rows, int H, int Lq,
-                         int C, hipStream_t s)
+                         int32_t *ranges, int32_t *n_ranges, int32_t *n_keys, DecodePlan plan, bool schedule, int U,
+                         int rows, int H, int Lq, int C, hipStream_t s)
 {
-    if (stats_in)
-        hipLaunchKernelGGL(select_kernel<true>, dim3(rows), dim3(256), 0, s, logits, row_max, denom, thresh, sizes,
-                           offsets, keep_mask, ranges, n_ranges, n_keys, plan, H, Lq, C);
+    // LDS: logits + sizes of the row; reused for one int per chunk when scheduling.
+    size_t smem = (size_t)C * 8;
+    if (schedule && (size_t)chunk_cap_for(plan.L) * 8 > smem) smem = (size_t)chunk_cap_for(plan.L) * 8;
+    static bool attr_set = false;   // one GPU per process in this build
+    if (!attr_set) {
+        const int lim = SELECT_MAX_C * 8;
+        const void *fns[3] = {reinterpret_cast<const void *>(select_kernel<true, false>),
+                              reinterpret_cast<const void *>(select_kernel<false, false>),
+                              reinterpret_cast<const void *>(select_kernel<false, true>)};
+        for (const void *f : fns) {
+            hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
+            if (e != hipSuccess) return e;
+        }
+        attr_set = true;
+    }
+    const int nuc = user_chunks_for(U);
+    if (schedule)
+        hipLaunchKernelGGL((select_kernel<false, true>), dim3(rows), dim3(SEL_THREADS), smem, s, logits, row_max,
+                           denom, thresh, sizes, offsets, keep_mask, ranges, n_ranges, n_keys, plan, H, Lq, C, U, nuc);
+    else if (stats_in)
+        hipLaunchKernelGGL((select_kernel<true, false>), dim3(rows), dim3(SEL_THREADS), smem, s, logits, row_max,
+                           denom, thresh, sizes, offsets, keep_mask, ranges, n_ranges, n_keys, plan, H, Lq, C, U, nuc);
     else
-        hipLaunchKernelGGL(select_kernel<false>, dim3(rows), dim3(256), 0, s, logits, row_max, denom, thresh, sizes,
-                           offsets, keep_mask, ranges, n_ranges, n_keys, plan, H, Lq, C);
+        hipLaunchKernelGGL((select_kernel<false, false>), dim3(rows), dim3(SEL_THREADS), smem, s, logits, row_max,
+                           denom, thresh, sizes, offsets, keep_mask, ranges, n_ranges, n_keys, plan, H, Lq, C, U, nuc);
     return hipGetLastError();
 }
 
-hipError_t launch_plan_from_ranges(const int32_t *ranges, const int32_t *n_ranges, DecodePlan plan, int rows,
-                                   int range_cap, hipStream_t s)
+hipError_t launch_ranges_to_rec(const int32_t *ranges, const int32_t *n_ranges, DecodePlan plan, int rows,
+                                int range_cap, hipStream_t s)
 {
-    hipLaunchKernelGGL(plan_from_ranges_kernel, dim3(rows), dim3(256), 0, s, ranges, n_ranges, plan, range_cap);
+    hipLaunchKernelGGL(ranges_to_rec_kernel, dim3(rows), dim3(256), 0, s, ranges, n_ranges, plan, range_cap);
+    return hipGetLastError();
+}
+
+hipError_t launch_schedule(DecodePlan plan, int rows, int U, hipStream_t s)
+{
+    const size_t smem = (size_t)chunk_cap_for(plan.L) * 8 + 16;
+    static bool attr_set = false;   // one GPU per process in this build
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(schedule_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, SELECT_MAX_C * 8 + 16);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(schedule_kernel, dim3(rows), dim3(256), smem, s, plan, rows, U, user_chunks_for(U));
     return hipGetLastError();
 }
 
