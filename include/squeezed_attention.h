@@ -179,6 +179,21 @@ int sq_decode_step(const sq_shape_t *shape, const void *q,
                    void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * One whole decode step with the two-level lookup (Lq must be 1): sq_hier_select followed by
+ * sq_sparse_attn_decode on its ranges, intermediates kept in the workspace.  Arguments as in those two
+ * calls; keep_mask2 and n_keys are optional outputs (NULL to skip).
+ * Workspace: sq_workspace_bytes(shape, SQ_CALL_HIER_DECODE_STEP).
+ */
+int sq_hier_decode_step(const sq_shape_t *shape, int32_t C1, const void *q,
+                        const void *centroids1, const int32_t *sizes1, const int32_t *child_offsets,
+                        const float *thresh1,
+                        const void *centroids2, const int32_t *sizes2, const int32_t *offsets2,
+                        const float *thresh2,
+                        const void *K_fixed, const void *V_fixed, const void *K_user, const void *V_user,
+                        void *out, float *lse, uint32_t *keep_mask2, int32_t *n_keys,
+                        void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Measurement hook for benchmarks (not part of the method; for callers that want a kernel's duration
  * without an external profiler).  Between sq_profile_begin(n) and sq_profile_end(), every launch of
  * the split-KV partial-attention kernel -- the kernel that reads the selected K/V rows, i.e. nearly

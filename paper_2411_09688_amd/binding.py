@@ -23,7 +23,7 @@ SQ_OK, SQ_ERR_INVALID_ARG, SQ_ERR_UNSUPPORTED, SQ_ERR_WORKSPACE, SQ_ERR_HIP = 0,
 
 EXPORTS = ("sq_workspace_bytes", "sq_last_error", "sq_version", "sq_centroid_score", "sq_select",
            "sq_sparse_attn_decode", "sq_sparse_attn_prefill", "sq_hier_select", "sq_decode_step",
-           "sq_profile_begin", "sq_profile_end", "sq_probe_stream_read")
+           "sq_hier_decode_step", "sq_profile_begin", "sq_profile_end", "sq_probe_stream_read")
 
 
 class SqShape(C.Structure):
@@ -60,6 +60,7 @@ def lib() -> C.CDLL:
         L.sq_sparse_attn_prefill.argtypes = [sp] + [vp] * 9 + [vp, sz, vp]
         L.sq_hier_select.argtypes = [sp, C.c_int32] + [vp] * 14 + [vp, sz, vp]
         L.sq_decode_step.argtypes = [sp] + [vp] * 13 + [vp, sz, vp]
+        L.sq_hier_decode_step.argtypes = [sp, C.c_int32] + [vp] * 17 + [vp, sz, vp]
         L.sq_probe_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_int, C.c_void_p]
         L.sq_profile_begin.argtypes = [C.c_int]
         L.sq_profile_end.argtypes = [C.POINTER(C.c_float)] * 3
@@ -174,6 +175,17 @@ def sq_decode_step(shape, q, centroids, sizes, offsets, thresh, K_fixed, V_fixed
                                 _ptr(K_user, F16, "K_user"), _ptr(V_user, F16, "V_user"), _ptr(out, F16, "out"),
                                 _ptr(lse, F32, "lse"), _ptr(keep_mask, I32, "keep_mask"), _ptr(n_keys, I32, "n_keys"),
                                 *_ws_args(ws), _stream(stream)))
+
+
+def sq_hier_decode_step(shape, C1, q, centroids1, sizes1, child_offsets, thresh1, centroids2, sizes2, offsets2,
+                        thresh2, K_fixed, V_fixed, K_user, V_user, out, lse, keep_mask2, n_keys, ws, stream=None):
+    _check(lib().sq_hier_decode_step(
+        C.byref(shape), int(C1), _ptr(q, F16, "q"), _ptr(centroids1, F16, "centroids1"), _ptr(sizes1, I32, "sizes1"),
+        _ptr(child_offsets, I32, "child_offsets"), _ptr(thresh1, F32, "thresh1"),
+        _ptr(centroids2, F16, "centroids2"), _ptr(sizes2, I32, "sizes2"), _ptr(offsets2, I32, "offsets2"),
+        _ptr(thresh2, F32, "thresh2"), _ptr(K_fixed, F16, "K_fixed"), _ptr(V_fixed, F16, "V_fixed"),
+        _ptr(K_user, F16, "K_user"), _ptr(V_user, F16, "V_user"), _ptr(out, F16, "out"), _ptr(lse, F32, "lse"),
+        _ptr(keep_mask2, I32, "keep_mask2"), _ptr(n_keys, I32, "n_keys"), *_ws_args(ws), _stream(stream)))
 
 
 def sq_probe_stream_read(buf: torch.Tensor, sink: torch.Tensor, workgroups: int, nbytes: Optional[int] = None,

@@ -132,6 +132,53 @@ StepWs carve_step(Carver &cv, const sq_shape_t *sh)
     return w;
 }
 
+// Workspace of the two-level lookup.  C1 <= C2 is not known to sq_workspace_bytes, so level-1 buffers
+// are sized for C2.
+struct HierWs {
+    float *logits1, *logits2;
+    int32_t *nr1, *nk1;
+    sq::DecodePlan cand;      // work items of candidate fine clusters (chunks of KPC clusters)
+};
+
+HierWs carve_hier(Carver &cv, const sq_shape_t *sh)
+{
+    const size_t rows = (size_t)sh->B * sh->H;
+    const size_t items = rows * sq::chunk_cap_for(sh->C);
+    HierWs w;
+    w.logits1 = cv.take<float>(rows * sh->C);
+    w.logits2 = cv.take<float>(rows * sh->C);
+    w.nr1 = cv.take<int32_t>(rows);
+    w.nk1 = cv.take<int32_t>(rows);
+    w.cand.rec_cap = sh->C;
+    w.cand.L = sh->C;
+    w.cand.item_cap = (int)items;
+    w.cand.rec = cv.take<int4>(rows * sh->C);
+    w.cand.hdr = cv.take<int2>(rows);
+    w.cand.row_items = cv.take<int2>(rows);
+    w.cand.total = cv.take<int>(1);
+    w.cand.item = cv.take<int2>(items * sq::ITEM_STRIDE);
+    return w;
+}
+
+struct HierStepWs {
+    HierWs hier;
+    uint32_t *mask1;
+    int32_t *n_ranges, *n_keys;
+    DecodeWs dec;
+};
+
+HierStepWs carve_hier_step(Carver &cv, const sq_shape_t *sh)
+{
+    const size_t rows = (size_t)sh->B * sh->H;
+    HierStepWs w;
+    w.hier = carve_hier(cv, sh);
+    w.mask1 = cv.take<uint32_t>(rows * ((sh->C + 31) / 32));
+    w.n_ranges = cv.take<int32_t>(rows);
+    w.n_keys = cv.take<int32_t>(rows);
+    w.dec = carve_decode(cv, sh);
+    return w;
+}
+
 int check_ws(const char *fn, const sq_shape_t *sh, int which, void *ws, size_t ws_bytes)
 {
     const size_t need = sq_workspace_bytes(sh, which);
@@ -165,6 +212,12 @@ size_t sq_workspace_bytes(const sq_shape_t *sh, int which)
         return cv.off;
     case SQ_CALL_DECODE_STEP:
         carve_step(cv, sh);
+        return cv.off;
+    case SQ_CALL_HIER_SELECT:
+        carve_hier(cv, sh);
+        return cv.off;
+    case SQ_CALL_HIER_DECODE_STEP:
+        carve_hier_step(cv, sh);
         return cv.off;
     default:
         return 0;
@@ -207,7 +260,7 @@ int sq_select(const sq_shape_t *sh, const float *logits, const float *row_max, c
     if (int rc = check_device(__func__)) return rc;
     sq::DecodePlan none{};
     SQ_HIP(sq::launch_select(logits, row_max, denom, true, thresh, sizes, offsets, keep_mask, ranges, n_ranges, n_keys,
-                             none, false, 0, sh->B * sh->H * sh->Lq, sh->H, sh->Lq, sh->C,
+                             none, false, 0, sq::SelectOpts{}, sh->B * sh->H * sh->Lq, sh->H, sh->Lq, sh->C,
                              static_cast<hipStream_t>(stream)));
     g_err[0] = 0;
     return SQ_OK;
@@ -272,7 +325,7 @@ int sq_decode_step(const sq_shape_t *sh, const void *q, const void *centroids, c
     int32_t *nk = n_keys ? n_keys : w.n_keys;
     SQ_HIP(sq::launch_score(q, centroids, w.logits, w.dec.plan.total, sh->B, sh->H, 1, sh->C, sh->sm_scale, s));
     SQ_HIP(sq::launch_select(w.logits, nullptr, nullptr, false, thresh, sizes, offsets, keep_mask, nullptr, w.n_ranges,
-                             nk, w.dec.plan, true, sh->U, rows, sh->H, 1, sh->C, s));
+                             nk, w.dec.plan, true, sh->U, sq::SelectOpts{}, rows, sh->H, 1, sh->C, s));
     SQ_HIP(sq::launch_decode_attn(q, K_fixed, V_fixed, K_user, V_user, w.dec.plan, w.dec.partials, out, lse,
                                   to_shape(sh), s));
     g_err[0] = 0;
@@ -285,11 +338,124 @@ int sq_sparse_attn_prefill(const sq_shape_t *, const void *, const void *, const
     return fail(SQ_ERR_UNSUPPORTED, "sq_sparse_attn_prefill: not built yet");
 }
 
-int sq_hier_select(const sq_shape_t *, int32_t, const void *, const void *, const int32_t *, const int32_t *,
-                   const float *, const void *, const int32_t *, const int32_t *, const float *, uint32_t *, uint32_t *,
-                   int32_t *, int32_t *, int32_t *, void *, size_t, void *)
+namespace {
+
+// Both levels of the lookup (Section 3.3).  plan2 (may be empty) receives the level-2 records and, when
+// `schedule2`, the attention work items.
+int hier_lookup(const char *fn, const sq_shape_t *sh, int32_t C1, const void *q, const void *centroids1,
+                const int32_t *sizes1, const int32_t *child_offsets, const float *thresh1, const void *centroids2,
+                const int32_t *sizes2, const int32_t *offsets2, const float *thresh2, uint32_t *keep_mask1,
+                uint32_t *keep_mask2, int32_t *ranges, int32_t *n_ranges, int32_t *n_keys, HierWs &w,
+                sq::DecodePlan plan2, bool schedule2, hipStream_t s)
 {
-    return fail(SQ_ERR_UNSUPPORTED, "sq_hier_select: not built yet");
+    const int rows = sh->B * sh->H;
+    // Level 1 (Eq. 2): scores on the coarse centroids, threshold T1; the kept clusters' child ranges
+    // become chunks of candidate fine clusters.
+    hipError_t e = sq::launch_score(q, centroids1, w.logits1, w.cand.total, sh->B, sh->H, 1, C1, sh->sm_scale, s);
+    if (e == hipSuccess) {
+        sq::SelectOpts o1{};
+        o1.len_from_offsets = 1;
+        sq::DecodePlan cand = w.cand;
+        cand.rec_cap = C1;
+        e = sq::launch_select(w.logits1, nullptr, nullptr, false, thresh1, sizes1, child_offsets, keep_mask1, nullptr,
+                              w.nr1, w.nk1, cand, true, 0, o1, rows, sh->H, 1, C1, s);
+        // Level 2 (Eq. 3): scores of the candidates only; maximum and normaliser over the candidates only.
+        if (e == hipSuccess)
+            e = sq::launch_gather_score(q, centroids2, cand, w.logits2, plan2.total, sh->H, sh->C, sh->sm_scale, s);
+    }
+    if (e == hipSuccess) {
+        sq::SelectOpts o2{};
+        o2.parent_offsets = child_offsets;
+        o2.parent_mask = keep_mask1;
+        o2.C1 = C1;
+        e = sq::launch_select(w.logits2, nullptr, nullptr, false, thresh2, sizes2, offsets2, keep_mask2, ranges,
+                              n_ranges, n_keys, plan2, schedule2, sh->U, o2, rows, sh->H, 1, sh->C, s);
+    }
+    if (e != hipSuccess) return fail(SQ_ERR_HIP, "%s: launch failed -> %s", fn, hipGetErrorString(e));
+    return SQ_OK;
+}
+
+int check_hier_args(const char *fn, const sq_shape_t *sh, int32_t C1)
+{
+    if (C1 <= 0 || C1 > sh->C) return fail(SQ_ERR_INVALID_ARG, "%s: C1 = %d must be in [1, C2 = %d]", fn, C1, sh->C);
+    return SQ_OK;
+}
+
+}  // namespace
+
+int sq_hier_select(const sq_shape_t *sh, int32_t C1, const void *q, const void *centroids1, const int32_t *sizes1,
+                   const int32_t *child_offsets, const float *thresh1, const void *centroids2, const int32_t *sizes2,
+                   const int32_t *offsets2, const float *thresh2, uint32_t *keep_mask1, uint32_t *keep_mask2,
+                   int32_t *ranges, int32_t *n_ranges, int32_t *n_keys, void *ws, size_t ws_bytes, void *stream)
+{
+    if (int rc = check_shape(sh, __func__, true)) return rc;
+    if (int rc = check_hier_args(__func__, sh, C1)) return rc;
+    SQ_REQUIRE_PTR(q);
+    SQ_REQUIRE_PTR(centroids1);
+    SQ_REQUIRE_PTR(sizes1);
+    SQ_REQUIRE_PTR(child_offsets);
+    SQ_REQUIRE_PTR(thresh1);
+    SQ_REQUIRE_PTR(centroids2);
+    SQ_REQUIRE_PTR(sizes2);
+    SQ_REQUIRE_PTR(offsets2);
+    SQ_REQUIRE_PTR(thresh2);
+    SQ_REQUIRE_PTR(keep_mask1);
+    SQ_REQUIRE_PTR(keep_mask2);
+    SQ_OPTIONAL_PTR(ranges);
+    SQ_REQUIRE_PTR(n_ranges);
+    SQ_REQUIRE_PTR(n_keys);
+    if (int rc = check_ws(__func__, sh, SQ_CALL_HIER_SELECT, ws, ws_bytes)) return rc;
+    if (int rc = check_device(__func__)) return rc;
+    Carver cv(ws);
+    HierWs w = carve_hier(cv, sh);
+    if (int rc = hier_lookup(__func__, sh, C1, q, centroids1, sizes1, child_offsets, thresh1, centroids2, sizes2,
+                             offsets2, thresh2, keep_mask1, keep_mask2, ranges, n_ranges, n_keys, w, sq::DecodePlan{},
+                             false, static_cast<hipStream_t>(stream)))
+        return rc;
+    g_err[0] = 0;
+    return SQ_OK;
+}
+
+int sq_hier_decode_step(const sq_shape_t *sh, int32_t C1, const void *q, const void *centroids1,
+                        const int32_t *sizes1, const int32_t *child_offsets, const float *thresh1,
+                        const void *centroids2, const int32_t *sizes2, const int32_t *offsets2, const float *thresh2,
+                        const void *K_fixed, const void *V_fixed, const void *K_user, const void *V_user, void *out,
+                        float *lse, uint32_t *keep_mask2, int32_t *n_keys, void *ws, size_t ws_bytes, void *stream)
+{
+    if (int rc = check_shape(sh, __func__, true)) return rc;
+    if (int rc = check_hier_args(__func__, sh, C1)) return rc;
+    SQ_REQUIRE_PTR(q);
+    SQ_REQUIRE_PTR(centroids1);
+    SQ_REQUIRE_PTR(sizes1);
+    SQ_REQUIRE_PTR(child_offsets);
+    SQ_REQUIRE_PTR(thresh1);
+    SQ_REQUIRE_PTR(centroids2);
+    SQ_REQUIRE_PTR(sizes2);
+    SQ_REQUIRE_PTR(offsets2);
+    SQ_REQUIRE_PTR(thresh2);
+    SQ_REQUIRE_PTR(K_fixed);
+    SQ_REQUIRE_PTR(V_fixed);
+    if (sh->U > 0) {
+        SQ_REQUIRE_PTR(K_user);
+        SQ_REQUIRE_PTR(V_user);
+    }
+    SQ_REQUIRE_PTR(out);
+    SQ_OPTIONAL_PTR(lse);
+    SQ_OPTIONAL_PTR(keep_mask2);
+    SQ_OPTIONAL_PTR(n_keys);
+    if (int rc = check_ws(__func__, sh, SQ_CALL_HIER_DECODE_STEP, ws, ws_bytes)) return rc;
+    if (int rc = check_device(__func__)) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Carver cv(ws);
+    HierStepWs w = carve_hier_step(cv, sh);
+    if (int rc = hier_lookup(__func__, sh, C1, q, centroids1, sizes1, child_offsets, thresh1, centroids2, sizes2,
+                             offsets2, thresh2, w.mask1, keep_mask2, nullptr, w.n_ranges, n_keys ? n_keys : w.n_keys,
+                             w.hier, w.dec.plan, true, s))
+        return rc;
+    SQ_HIP(sq::launch_decode_attn(q, K_fixed, V_fixed, K_user, V_user, w.dec.plan, w.dec.partials, out, lse,
+                                  to_shape(sh), s));
+    g_err[0] = 0;
+    return SQ_OK;
 }
 
 }  // extern "C"

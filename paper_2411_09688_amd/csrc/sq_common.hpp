@@ -93,6 +93,30 @@ __device__ __forceinline__ float dot8(h8 a, h8 b, float acc)
     return acc;
 }
 
+// Rows of one chunk from its run-length records (position of a record's first key relative to the
+// chunk, row of that key minus that position): slot t lies in the last record whose position is <= t
+// and reads row t + delta.  Positions ascend and the first is <= 0.  Called by a whole workgroup of at
+// least CH threads (contains a barrier); thread t < CH passes record t and gets s_rows[t] = its row
+// clamped to [0, limit), or -1 for slots past `nvalid`.
+template <int CH>
+__device__ __forceinline__ void chunk_rows_from_records(int rec_pos, int rec_delta, int nrec, int nvalid, int limit,
+                                                        int *s_pos, int *s_delta, int *s_rows, int tid)
+{
+    if (tid < CH) {
+        s_pos[tid] = rec_pos;
+        s_delta[tid] = rec_delta;
+    }
+    __syncthreads();
+    if (tid < CH) {
+        int lo = 0;
+#pragma unroll
+        for (int step = CH / 2; step > 0; step >>= 1)
+            if (lo + step < nrec && s_pos[lo + step] <= tid) lo += step;
+        const int r = tid + s_delta[lo];
+        s_rows[tid] = tid < nvalid ? max(0, min(r, limit - 1)) : -1;   // malformed input stays in the tensor
+    }
+}
+
 // Row statistics of Eq. 1 in max-subtracted form, computed by ONE wave for one query row:
 //   m = max over clusters with N > 0 of x;  D = sum_i N_i * exp(x_i - m).
 // Lane l accumulates clusters l, l+64, l+128, ... in ascending order and the 64 lane sums are

@@ -122,21 +122,7 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
         } else {
             Kbase = Kf + (size_t)h * L * D;
             Vbase = Vf + (size_t)h * L * D;
-            if (tid < KPC) {
-                s_pos[tid] = rc.x;
-                s_delta[tid] = rc.y;
-            }
-            __syncthreads();
-            // Key slot `tid` lies in the last record whose position is <= tid (positions ascend; the
-            // first record's position is <= 0).
-            if (tid < KPC) {
-                int lo = 0;
-#pragma unroll
-                for (int step = KPC / 2; step > 0; step >>= 1)
-                    if (lo + step < nrec && s_pos[lo + step] <= tid) lo += step;
-                const int rowi = tid + s_delta[lo];
-                s_rows[tid] = tid < nvalid ? max(0, min(rowi, L - 1)) : -1;   // malformed ranges stay in the tensor
-            }
+            chunk_rows_from_records<KPC>(rc.x, rc.y, nrec, nvalid, L, s_pos, s_delta, s_rows, tid);
         }
         __syncthreads();
 

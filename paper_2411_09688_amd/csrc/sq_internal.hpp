@@ -42,6 +42,7 @@ inline int user_chunks_for(int U) { return (U + KPC - 1) / KPC; }
 
 // Row-wise selection stages a row's logits and cluster sizes in LDS.
 constexpr int SELECT_MAX_C = 16384;
+constexpr int LDS_BYTES_MAX = 160 * 1024 - 1024;   // gfx950: 160 KB per workgroup, minus the static arrays
 // Scheduling keeps two ints per chunk of a row in LDS (same budget as the staged logits).
 constexpr int MAX_L = SELECT_MAX_C * KPC;
 
@@ -50,11 +51,23 @@ hipError_t launch_score(const void *q, const void *centroids, float *logits, int
                         int C, float sm_scale, hipStream_t s);
 hipError_t launch_row_stats(const float *logits, const int32_t *sizes, float *row_max, float *denom, int rows,
                             int H, int Lq, int C, hipStream_t s);
+// Options of the row-wise selection for the two-level lookup (all zero for the one-level path).
+struct SelectOpts {
+    const int32_t *parent_offsets;   // level 2: child_offsets [H, C1+1]; cluster i is a candidate iff its parent is kept
+    const uint32_t *parent_mask;     // level 2: keep mask of the coarse level [B*H, ceil(C1/32)]
+    int C1;
+    int len_from_offsets;            // level 1: emitted range length = offsets[i+1] - offsets[i] (child clusters)
+};
+
 // stats_in == true: use row_max/denom; false: the kernel derives them from logits itself.
 hipError_t launch_select(const float *logits, const float *row_max, const float *denom, bool stats_in,
                          const float *thresh, const int32_t *sizes, const int32_t *offsets, uint32_t *keep_mask,
                          int32_t *ranges, int32_t *n_ranges, int32_t *n_keys, DecodePlan plan, bool schedule, int U,
-                         int rows, int H, int Lq, int C, hipStream_t s);
+                         SelectOpts opt, int rows, int H, int Lq, int C, hipStream_t s);
+// Level-2 scoring of the two-level lookup: logits of the candidate fine centroids listed by the work
+// items of `cand` (chunks of candidate clusters), written at logits2[row, fine id].
+hipError_t launch_gather_score(const void *q, const void *centroids2, DecodePlan cand, float *logits2,
+                               int *zero_counter, int H, int C2, float sm_scale, hipStream_t s);
 // Caller-style ranges [rows, range_cap, 2] -> records + header per row.
 hipError_t launch_ranges_to_rec(const int32_t *ranges, const int32_t *n_ranges, DecodePlan plan, int rows,
                                 int range_cap, hipStream_t s);

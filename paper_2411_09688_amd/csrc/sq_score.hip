@@ -84,6 +84,73 @@ __global__ __launch_bounds__(256) void row_stats_kernel(const float *__restrict_
     }
 }
 
+// Level-2 scoring of the two-level lookup (Section 3.3, Eq. 3 numerator): the fine centroids to score are
+// the children of the kept coarse clusters, listed by work items of KPC candidate clusters each (built
+// by the level-1 selection: a balanced number of centroids per workgroup, Appendix D).  A persistent
+// grid walks the items; each wave scores 16-cluster MFMA tiles of its share, gathering the centroid rows
+// by cluster id, and writes logits2[row, cluster id].
+__global__ __launch_bounds__(256) void gather_score_kernel(const _Float16 *__restrict__ q,
+                                                           const _Float16 *__restrict__ cent2, DecodePlan cand,
+                                                           float *__restrict__ logits2,
+                                                           int *__restrict__ zero_counter, int H, int C2,
+                                                           float sm_scale)
+{
+    __shared__ int s_pos[KPC], s_delta[KPC], s_rows[KPC];
+    if (zero_counter && blockIdx.x == 0 && threadIdx.x == 0) *zero_counter = 0;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col = lane & 15, kg = lane >> 4;
+    constexpr int TILES = KPC / 64;                 // 16-cluster tiles per wave
+    const int total = min(*cand.total, cand.item_cap);
+    for (int item = blockIdx.x; item < total; item += gridDim.x) {
+        const int2 *it = cand.item + (size_t)item * ITEM_STRIDE;
+        const int2 h0 = it[0], h1 = it[1];          // (row, clusters in chunk) (records, -)
+        const int2 rc = it[2 + (tid < KPC ? tid : 0)];
+        const size_t bh = (size_t)h0.x;
+        const int h = (int)(bh % H);
+        chunk_rows_from_records<KPC>(rc.x, rc.y, min(h1.x, KPC), h0.y, C2, s_pos, s_delta, s_rows, tid);
+        __syncthreads();
+        h8 bq[4];
+        {
+            const h8 *qp = reinterpret_cast<const h8 *>(q + bh * D);
+#pragma unroll
+            for (int s = 0; s < 4; ++s) bq[s] = col == 0 ? qp[s * 4 + kg] : h8{0, 0, 0, 0, 0, 0, 0, 0};
+        }
+        const int r_last = s_rows[h0.y - 1];
+        h8 a[TILES][4];
+#pragma unroll
+        for (int t = 0; t < TILES; ++t) {
+            int r = s_rows[wave * (KPC / 4) + t * 16 + col];
+            r = r < 0 ? r_last : r;
+            const h8 *cp = reinterpret_cast<const h8 *>(cent2 + ((size_t)h * C2 + r) * D);
+#pragma unroll
+            for (int s = 0; s < 4; ++s) a[t][s] = cp[s * 4 + kg];
+        }
+#pragma unroll
+        for (int t = 0; t < TILES; ++t) {
+            f4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < 4; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[t][s], bq[s], acc, 0, 0, 0);
+            if (col == 0) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int r = s_rows[wave * (KPC / 4) + t * 16 + kg * 4 + v];
+                    if (r >= 0) logits2[bh * (size_t)C2 + r] = acc[v] * sm_scale;
+                }
+            }
+        }
+        __syncthreads();                            // LDS is reused by the next item
+    }
+}
+
+hipError_t launch_gather_score(const void *q, const void *centroids2, DecodePlan cand, float *logits2,
+                               int *zero_counter, int H, int C2, float sm_scale, hipStream_t s)
+{
+    const int grid = cand.item_cap < 2048 ? cand.item_cap : 2048;
+    hipLaunchKernelGGL(gather_score_kernel, dim3(grid), dim3(256), 0, s, (const _Float16 *)q,
+                       (const _Float16 *)centroids2, cand, logits2, zero_counter, H, C2, sm_scale);
+    return hipGetLastError();
+}
+
 hipError_t launch_score(const void *q, const void *centroids, float *logits, int *zero_counter, int B, int H, int Lq,
                         int C, float sm_scale, hipStream_t s)
 {

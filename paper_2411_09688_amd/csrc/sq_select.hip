@@ -120,7 +120,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     const float *__restrict__ logits, const float *__restrict__ row_max, const float *__restrict__ denom,
     const float *__restrict__ thresh, const int32_t *__restrict__ sizes, const int32_t *__restrict__ offsets,
     uint32_t *__restrict__ keep_mask, int32_t *__restrict__ ranges, int32_t *__restrict__ n_ranges,
-    int32_t *__restrict__ n_keys, DecodePlan plan, int H, int Lq, int C, int U, int n_user_chunks)
+    int32_t *__restrict__ n_keys, DecodePlan plan, SelectOpts opt, int H, int Lq, int C, int U, int n_user_chunks)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ float s_wred[SEL_WAVES];
@@ -138,11 +138,33 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     const int W = (C + 31) >> 5;
     const float T = thresh[h];
 
-    for (int i = tid; i < C; i += SEL_THREADS) {
-        s_e[i] = x[i];
-        s_N[i] = N[i];
+    if (opt.parent_mask) {
+        // Two-level lookup, level 2 (Section 3.3): only the children of kept coarse clusters are
+        // candidates; every other cluster is treated as empty, so the maximum and the normaliser of
+        // Eq. 3 run over the candidates only.  Parent of cluster i: the j with co[j] <= i < co[j+1].
+        int32_t *s_co = s_N + C;                            // [C1 + 1]
+        const int32_t *co = opt.parent_offsets + (size_t)h * (opt.C1 + 1);
+        for (int j = tid; j <= opt.C1; j += SEL_THREADS) s_co[j] = co[j];
+        __syncthreads();
+        const uint32_t *pm = opt.parent_mask + (row / Lq) * ((opt.C1 + 31) >> 5);
+        for (int i = tid; i < C; i += SEL_THREADS) {
+            int lo = 0, hi = opt.C1;                        // invariant: co[lo] <= i (if any) ; answer in [lo, hi)
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (s_co[mid] <= i) lo = mid; else hi = mid;
+            }
+            const bool cand = i >= s_co[lo] && i < s_co[lo + 1] && ((pm[lo >> 5] >> (lo & 31)) & 1u);
+            s_N[i] = cand ? N[i] : 0;
+            s_e[i] = cand ? x[i] : 0.0f;
+        }
+    } else {
+        for (int i = tid; i < C; i += SEL_THREADS) {
+            s_e[i] = x[i];
+            s_N[i] = N[i];
+        }
     }
     int start_first = tid < C ? off[tid] : 0;               // offsets of the first step, fetched with the logits
+    int next_first = (opt.len_from_offsets && tid < C) ? off[tid + 1] : 0;
     float m;
     if (STATS_IN) {
         m = row_max[row];
@@ -186,17 +208,24 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
         const int Ni = i < C ? s_N[i] : 0;
         const bool keep = Ni > 0 && s_e[i] > thr;
         const int start = i0 == 0 ? start_first : (keep ? off[i] : 0);
-        unsigned long long bal;
-        const ScanOut sc = block_scan_kept<SEL_WAVES>(keep, Ni, lane, wave, s_cnt, s_keys, bal);
+        // Length of the emitted range: the cluster's keys, or (level 1 of the two-level lookup) the
+        // number of child clusters, read from the offsets.
+        int len = Ni;
+        if (opt.len_from_offsets) len = keep ? (i0 == 0 ? next_first : off[i + 1]) - start : 0;
+        // A kept coarse cluster without children is kept (mask bit) but emits no range.
+        const bool emit = keep && len > 0;
+        unsigned long long bal_emit;
+        const ScanOut sc = block_scan_kept<SEL_WAVES>(emit, len, lane, wave, s_cnt, s_keys, bal_emit);
+        const unsigned long long bal = __ballot(keep);
         if (lane == 0 && keep_mask) {
             const int w0 = (i0 >> 5) + wave * 2;
             if (w0 < W) keep_mask[row * W + w0] = (uint32_t)bal;
             if (w0 + 1 < W) keep_mask[row * W + w0 + 1] = (uint32_t)(bal >> 32);
         }
-        if (keep) {
+        if (emit) {
             const int r = base_r + sc.rank;
-            if (ranges) *reinterpret_cast<int2 *>(ranges + (row * C + r) * 2) = make_int2(start, Ni);
-            my_rec = make_int4(start, Ni, base_k + sc.key_prefix, 0);
+            if (ranges) *reinterpret_cast<int2 *>(ranges + (row * C + r) * 2) = make_int2(start, len);
+            my_rec = make_int4(start, len, base_k + sc.key_prefix, 0);
             my_r = r;
             have_rec = true;
             if (plan.rec) plan.rec[row * plan.rec_cap + r] = my_rec;
@@ -287,21 +316,23 @@ __global__ __launch_bounds__(256) void schedule_kernel(DecodePlan plan, int rows
                           256, false, 0, make_int4(0, 0, 0, 0));
 }
 
-// schedule == true also emits the row's work items (decode step; needs *plan.total == 0 on entry).
+// schedule == true also emits the row's work items (needs *plan.total == 0 on entry).
 hipError_t launch_select(const float *logits, const float *row_max, const float *denom, bool stats_in,
                          const float *thresh, const int32_t *sizes, const int32_t *offsets, uint32_t *keep_mask,
                          int32_t *ranges, int32_t *n_ranges, int32_t *n_keys, DecodePlan plan, bool schedule, int U,
-                         int rows, int H, int Lq, int C, hipStream_t s)
+                         SelectOpts opt, int rows, int H, int Lq, int C, hipStream_t s)
 {
-    // LDS: logits + sizes of the row; reused for one int per chunk when scheduling.
-    size_t smem = (size_t)C * 8;
+    // LDS: logits + sizes of the row (+ parent offsets); reused for two ints per chunk when scheduling.
+    size_t smem = (size_t)C * 8 + (opt.parent_mask ? (size_t)(opt.C1 + 1) * 4 : 0);
     if (schedule && (size_t)chunk_cap_for(plan.L) * 8 > smem) smem = (size_t)chunk_cap_for(plan.L) * 8;
+    if (smem > (size_t)LDS_BYTES_MAX) return hipErrorInvalidValue;   // C and C1 too large together
     static bool attr_set = false;   // one GPU per process in this build
     if (!attr_set) {
-        const int lim = SELECT_MAX_C * 8;
-        const void *fns[3] = {reinterpret_cast<const void *>(select_kernel<true, false>),
+        const int lim = LDS_BYTES_MAX;
+        const void *fns[4] = {reinterpret_cast<const void *>(select_kernel<true, false>),
                               reinterpret_cast<const void *>(select_kernel<false, false>),
-                              reinterpret_cast<const void *>(select_kernel<false, true>)};
+                              reinterpret_cast<const void *>(select_kernel<false, true>),
+                              reinterpret_cast<const void *>(select_kernel<true, true>)};
         for (const void *f : fns) {
             hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
             if (e != hipSuccess) return e;
@@ -309,15 +340,14 @@ hipError_t launch_select(const float *logits, const float *row_max, const float 
         attr_set = true;
     }
     const int nuc = user_chunks_for(U);
-    if (schedule)
-        hipLaunchKernelGGL((select_kernel<false, true>), dim3(rows), dim3(SEL_THREADS), smem, s, logits, row_max,
-                           denom, thresh, sizes, offsets, keep_mask, ranges, n_ranges, n_keys, plan, H, Lq, C, U, nuc);
-    else if (stats_in)
-        hipLaunchKernelGGL((select_kernel<true, false>), dim3(rows), dim3(SEL_THREADS), smem, s, logits, row_max,
-                           denom, thresh, sizes, offsets, keep_mask, ranges, n_ranges, n_keys, plan, H, Lq, C, U, nuc);
-    else
-        hipLaunchKernelGGL((select_kernel<false, false>), dim3(rows), dim3(SEL_THREADS), smem, s, logits, row_max,
-                           denom, thresh, sizes, offsets, keep_mask, ranges, n_ranges, n_keys, plan, H, Lq, C, U, nuc);
+#define SQ_LAUNCH_SELECT(SI, SCH)                                                                               \
+    hipLaunchKernelGGL((select_kernel<SI, SCH>), dim3(rows), dim3(SEL_THREADS), smem, s, logits, row_max, denom, \
+                       thresh, sizes, offsets, keep_mask, ranges, n_ranges, n_keys, plan, opt, H, Lq, C, U, nuc)
+    if (stats_in && schedule) SQ_LAUNCH_SELECT(true, true);
+    else if (stats_in) SQ_LAUNCH_SELECT(true, false);
+    else if (schedule) SQ_LAUNCH_SELECT(false, true);
+    else SQ_LAUNCH_SELECT(false, false);
+#undef SQ_LAUNCH_SELECT
     return hipGetLastError();
 }
 
