@@ -48,14 +48,8 @@ def gpu_score_fn(sq, torch, device):
 
 def step_bytes(w, n_keys_per_head):
     """Algorithmic HBM bytes of one decode step for the achieved selection (bytes the method must move)."""
-    H, C, d, U, B = w.H, w.C, w.d, w.U, w.B
-    centroid = H * C * d * 2
-    meta = H * C * 4 + H * (C + 1) * 4 + H * 4
-    selected_kv = int(np.sum(n_keys_per_head)) * d * 2 * 2
-    dense_kv = B * H * U * d * 2 * 2
-    io = B * H * d * 2 * 2
-    return dict(centroid=centroid, meta=meta, selected_kv=selected_kv, dense_kv=dense_kv, io=io,
-                total=centroid + meta + selected_kv + dense_kv + io)
+    from paper_2411_09688_amd.bytes_model import decode_step_bytes
+    return decode_step_bytes(w.H, w.C, w.d, w.U, w.B, n_keys_per_head)
 
 
 def read_traffic(name):
@@ -101,6 +95,9 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU-oracle baseline (0 = skip)")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay measurement")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="only run a 256 MiB streaming read and a 256 MiB device copy (known sizes) a few times: "
+                         "the reference dispatches that scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
     ap.add_argument("--separate", action="store_true", help="time the three separate calls instead of sq_decode_step")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -113,6 +110,16 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     sq.lib()
+    if args.pmc_calibration:
+        src = torch.ones(1 << 28, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        sink = torch.zeros(1024, dtype=torch.int32, device=dev)
+        for _ in range(5):
+            sq.sq_probe_stream_read(src, sink, 512)
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"pmc_calibration": {"stream_read_bytes": 1 << 28, "copy_bytes_each_way": 1 << 28}}))
+        return
 
     w = wl.make_config(args.workload, seed=args.seed, threads=16)
     assert w.Lq == 1 and not w.C1, "bench.py times the one-level decode path"
@@ -233,11 +240,11 @@ def main():
         "bytes_per_step": {"total": round(tot), "centroid": round(cen), "selected_kv": round(sel),
                            "dense_kv": round(dense), "centroid_plus_selected_kv": round(cen + sel)},
         "hbm_frac_whole_step": round(tot / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-        "roofline": {"bound": "hbm", "kernel": "decode_partial_kernel",
+        "roofline": {"bound": "hbm", "kernel": "decode_attn_kernel",
                      "achieved": round(kernel_bytes / (k_avg_us * 1e-6) / 1e9, 2) if n_meas else None,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(kernel_bytes / (k_avg_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4) if n_meas else None,
-                     "traffic": read_traffic(f"decode_partial_kernel_{args.workload}_pmc.txt"),
+                     "traffic": read_traffic(f"decode_attn_kernel_{args.workload}_pmc.txt"),
                      "bytes_per_launch": round(kernel_bytes), "avg_us": round(k_avg_us, 3),
                      "min_us": round(k_min_us, 3), "launches": n_meas},
     }
