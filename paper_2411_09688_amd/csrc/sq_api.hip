@@ -213,6 +213,9 @@ size_t sq_workspace_bytes(const sq_shape_t *sh, int which)
     case SQ_CALL_DECODE_STEP:
         carve_step(cv, sh);
         return cv.off;
+    case SQ_CALL_ATTN_PREFILL:
+        cv.take<int32_t>((size_t)sh->H * sh->L);
+        return cv.off;
     case SQ_CALL_HIER_SELECT:
         carve_hier(cv, sh);
         return cv.off;
@@ -332,10 +335,30 @@ int sq_decode_step(const sq_shape_t *sh, const void *q, const void *centroids, c
     return SQ_OK;
 }
 
-int sq_sparse_attn_prefill(const sq_shape_t *, const void *, const void *, const void *, const int32_t *,
-                           const uint32_t *, const void *, const void *, void *, float *, void *, size_t, void *)
+int sq_sparse_attn_prefill(const sq_shape_t *sh, const void *q, const void *K_fixed, const void *V_fixed,
+                           const int32_t *offsets, const uint32_t *keep_mask, const void *K_user, const void *V_user,
+                           void *out, float *lse, void *ws, size_t ws_bytes, void *stream)
 {
-    return fail(SQ_ERR_UNSUPPORTED, "sq_sparse_attn_prefill: not built yet");
+    if (int rc = check_shape(sh, __func__, false)) return rc;
+    SQ_REQUIRE_PTR(q);
+    SQ_REQUIRE_PTR(K_fixed);
+    SQ_REQUIRE_PTR(V_fixed);
+    SQ_REQUIRE_PTR(offsets);
+    SQ_REQUIRE_PTR(keep_mask);
+    if (sh->U > 0) {
+        SQ_REQUIRE_PTR(K_user);
+        SQ_REQUIRE_PTR(V_user);
+    }
+    SQ_REQUIRE_PTR(out);
+    SQ_OPTIONAL_PTR(lse);
+    if (int rc = check_ws(__func__, sh, SQ_CALL_ATTN_PREFILL, ws, ws_bytes)) return rc;
+    if (int rc = check_device(__func__)) return rc;
+    Carver cv(ws);
+    int32_t *key_cid = cv.take<int32_t>((size_t)sh->H * sh->L);
+    SQ_HIP(sq::launch_prefill_attn(q, K_fixed, V_fixed, K_user, V_user, keep_mask, offsets, key_cid, out, lse,
+                                   to_shape(sh), static_cast<hipStream_t>(stream)));
+    g_err[0] = 0;
+    return SQ_OK;
 }
 
 namespace {
