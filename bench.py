@@ -24,6 +24,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0       # MI355X published HBM3E bandwidth
+MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X published dense fp16 matrix rate
 METRIC = "decode attn µs/token + achieved HBM GB/s, 32K fixed ctx, keep 1/8, H=32 d=128"
 
 
@@ -84,6 +85,170 @@ def cpu_baseline(w_name, seed, budget_s):
                 sample=f"{n} decode steps (different query tokens) of {w_name}, whole path, same byte model")
 
 
+def time_steps(step, args, torch, sq):
+    """W warm-up steps, K timed eager steps, the same K steps as one HIP-graph replay, then K steps with the
+    library's event hook around the dominant kernel.  step(i, stream_ptr) enqueues step i."""
+    import ctypes as C
+
+    def cur_stream():
+        return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+    st = cur_stream()
+    for i in range(args.warmup):
+        step(i, st)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, st)
+    torch.cuda.synchronize()
+    eager_ms = (time.perf_counter() - t0) / args.steps * 1e3
+
+    graph_ms = None
+    if not args.no_graph:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            st_cap = cur_stream()
+            for i in range(args.steps):
+                step(args.warmup + i, st_cap)
+        g.replay()                                   # untimed replay (warm-up of the graph itself)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        g.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) / args.steps * 1e3
+    ms_per_step = min(eager_ms, graph_ms) if graph_ms is not None else eager_ms
+
+    sq.sq_profile_begin(args.steps)
+    for i in range(args.steps):
+        step(args.warmup + i, st)
+    torch.cuda.synchronize()
+    return eager_ms, graph_ms, ms_per_step, sq.sq_profile_end()
+
+
+def base_result(args, metric, value, unit, ms_per_step, eager_ms, graph_ms, tokens):
+    return {
+        "metric": metric, "value": value, "unit": unit,
+        "us_per_token": round(ms_per_step * 1e3 / tokens, 3),
+        "us_per_step_eager": round(eager_ms * 1e3, 3),
+        "us_per_step_graph": None if graph_ms is None else round(graph_ms * 1e3, 3),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 6),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+    }
+
+
+def bench_prefill(args, torch, sq, wl, dev):
+    """Config 4: scores -> per-query masks -> sparse prefill attention; dominant kernel prefill_attn_kernel (MFMA)."""
+    import ctypes as C
+    w = wl.make_config(args.workload, seed=args.seed, threads=16)
+    wl.calibrate(w, gpu_score_fn(sq, torch, dev))
+    R = max(1, min(args.replicas, 2))
+    Ps = [sq.upload(w, dev) for _ in range(R)]
+    shape = Ps[0].shape
+    ws = sq.workspace(shape, sq.SQ_CALL_ATTN_PREFILL, dev)
+
+    def step(i, stream_ptr):
+        P = Ps[i % R]
+        sq.sq_centroid_score(shape, P.q, P.centroids, P.sizes, P.logits, P.row_max, P.denom)
+        sq.sq_select(shape, P.logits, P.row_max, P.denom, P.thresh, P.sizes, P.offsets, P.keep_mask, None,
+                     P.n_ranges, P.n_keys)
+        sq.sq_sparse_attn_prefill(shape, P.q, P.K_fixed, P.V_fixed, P.offsets, P.keep_mask, P.K_user, P.V_user,
+                                  P.out, P.lse, ws)
+
+    eager_ms, graph_ms, ms, (n_meas, k_avg, k_min, k_max) = time_steps(step, args, torch, sq)
+    nk = Ps[0].n_keys.cpu().numpy().astype(np.float64)            # [B,H,Lq]
+    t = np.arange(w.Lq)
+    user_vis = np.minimum(t + 1, w.U) if w.causal_user else np.full(w.Lq, w.U)
+    useful_attn = float((nk.sum() + w.B * w.H * user_vis.sum()) * 4 * w.d)
+    score_flops = 2.0 * w.B * w.H * w.Lq * w.C * w.d
+    # executed by the attention kernel: every 64-key block of the fixed context and of the visible user keys,
+    # for every query of a 64-query workgroup (wave-level skips not subtracted)
+    nb_fixed = -(-w.L // 64)
+    q0 = np.arange(0, w.Lq, 64)
+    nb_user = -(-np.minimum(w.U, q0 + 64) // 64) if w.causal_user else np.full(len(q0), -(-w.U // 64))
+    executed = float(w.B * w.H * ((nb_fixed * len(q0) + nb_user.sum()) * 64 * 64) * 4 * w.d)
+    tokens = w.B * w.Lq
+    res = base_result(args, "sparse prefill attn: useful TFLOP/s (per-query selection), 32K fixed ctx, keep 1/8",
+                      round((useful_attn + score_flops) / (ms * 1e-3) / 1e12, 3), "TFLOP/s", ms, eager_ms, graph_ms,
+                      tokens)
+    res["config"] = {"workload": args.workload, "B": w.B, "H": w.H, "d": w.d, "L": w.L, "C": w.C, "Lq": w.Lq,
+                     "U": w.U, "keep_achieved": round(float(nk.mean() / w.L), 5), "replicas": R,
+                     "entry": "sq_centroid_score + sq_select + sq_sparse_attn_prefill"}
+    res["flops_per_step"] = {"useful_attention": useful_attn, "scoring": score_flops,
+                             "executed_attention_upper_bound": executed}
+    res["roofline"] = {"bound": "mfma", "kernel": "prefill_attn_kernel",
+                       "achieved": round(useful_attn / (k_avg * 1e-6) / 1e12, 2) if n_meas else None,
+                       "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                       "frac": round(useful_attn / (k_avg * 1e-6) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4) if n_meas else None,
+                       "executed_TFLOPs": round(executed / (k_avg * 1e-6) / 1e12, 2) if n_meas else None,
+                       "executed_frac": round(executed / (k_avg * 1e-6) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4) if n_meas else None,
+                       "traffic": read_traffic(f"prefill_attn_kernel_{args.workload}_pmc.txt"),
+                       "flops_per_launch": useful_attn, "avg_us": round(k_avg, 2), "min_us": round(k_min, 2),
+                       "launches": n_meas}
+    print(json.dumps(res, ensure_ascii=False))
+
+
+def bench_hier(args, torch, sq, wl, dev):
+    """Config 5: two-level lookup + sparse decode attention (sq_hier_decode_step)."""
+    w = wl.make_config(args.workload, seed=args.seed, threads=16)
+    wl.calibrate(w, gpu_score_fn(sq, torch, dev))
+    NQ = args.queries
+    P = sq.upload(w, dev)
+    shape = P.shape
+    qs = wl.extra_queries(w, NQ)
+    Q = torch.from_numpy(np.ascontiguousarray(qs[:, None, :, None, :])).to(dev)      # [NQ,1,H,1,d]
+    out = torch.zeros(NQ, 1, w.H, 1, w.d, dtype=torch.float16, device=dev)
+    lse = torch.zeros(NQ, 1, w.H, 1, dtype=torch.float32, device=dev)
+    nkeys = torch.zeros(NQ, 1, w.H, 1, dtype=torch.int32, device=dev)
+    ws = sq.workspace(shape, sq.SQ_CALL_HIER_DECODE_STEP, dev)
+
+    def step(i, stream_ptr):
+        qi = i % NQ
+        sq.sq_hier_decode_step(shape, w.C1, Q[qi], P.centroids1, P.sizes1, P.child_offsets, P.thresh1, P.centroids,
+                               P.sizes, P.offsets, P.thresh2, P.K_fixed, P.V_fixed, P.K_user, P.V_user, out[qi],
+                               lse[qi], None, nkeys[qi], ws)
+
+    eager_ms, graph_ms, ms, (n_meas, k_avg, k_min, k_max) = time_steps(step, args, torch, sq)
+    # candidates per query (for the byte count): one untimed sq_hier_select per query
+    m1 = torch.zeros(1, w.H, (w.C1 + 31) // 32, dtype=torch.int32, device=dev)
+    m2 = torch.zeros(1, w.H, (w.C + 31) // 32, dtype=torch.int32, device=dev)
+    nr = torch.zeros(1, w.H, 1, dtype=torch.int32, device=dev)
+    nk1 = torch.zeros(1, w.H, 1, dtype=torch.int32, device=dev)
+    ws_h = sq.workspace(shape, sq.SQ_CALL_HIER_SELECT, dev)
+    used = sorted({(args.warmup + i) % NQ for i in range(args.steps)})
+    fan = np.diff(w.child_offsets, axis=1)
+    ncand = {}
+    for qi in used:
+        sq.sq_hier_select(shape, w.C1, Q[qi], P.centroids1, P.sizes1, P.child_offsets, P.thresh1, P.centroids,
+                          P.sizes, P.offsets, P.thresh2, m1, m2, None, nr, nk1, ws_h)
+        bits = m1.cpu().numpy().view(np.uint32)[0]
+        keep1 = ((bits[:, :, None] >> np.arange(32, dtype=np.uint32)) & 1).reshape(w.H, -1)[:, :w.C1].astype(bool)
+        ncand[qi] = int((keep1 * fan).sum())
+    nk = nkeys.cpu().numpy()[:, 0, :, 0]
+    steps_q = [(args.warmup + i) % NQ for i in range(args.steps)]
+    sel = float(np.mean([nk[qi].sum() for qi in steps_q])) * w.d * 4
+    cand = float(np.mean([ncand[qi] for qi in steps_q])) * w.d * 2
+    coarse = w.H * w.C1 * w.d * 2
+    dense = w.H * w.U * w.d * 4
+    tot = sel + cand + coarse + dense
+    kernel_bytes = sel + dense + w.H * w.d * 2
+    res = base_result(args, "hierarchical decode attn µs/token + achieved HBM GB/s, 512K fixed ctx, keep 1/16",
+                      round(tot / (ms * 1e-3) / 1e9, 2), "GB/s", ms, eager_ms, graph_ms, 1)
+    res["config"] = {"workload": args.workload, "H": w.H, "d": w.d, "L": w.L, "C1": w.C1, "C2": w.C, "U": w.U,
+                     "keep_achieved": round(float(np.mean([nk[qi].mean() for qi in steps_q]) / w.L), 5),
+                     "queries": NQ, "entry": "sq_hier_decode_step"}
+    res["bytes_per_step"] = {"total": round(tot), "coarse_centroids": coarse, "candidate_fine_centroids": round(cand),
+                             "selected_kv": round(sel), "dense_kv": dense}
+    res["hbm_frac_whole_step"] = round(tot / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)
+    res["roofline"] = {"bound": "hbm", "kernel": "decode_attn_kernel",
+                       "achieved": round(kernel_bytes / (k_avg * 1e-6) / 1e9, 2) if n_meas else None,
+                       "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                       "frac": round(kernel_bytes / (k_avg * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4) if n_meas else None,
+                       "traffic": read_traffic(f"decode_attn_kernel_{args.workload}_pmc.txt"),
+                       "bytes_per_launch": round(kernel_bytes), "avg_us": round(k_avg, 3), "min_us": round(k_min, 3),
+                       "launches": n_meas}
+    print(json.dumps(res, ensure_ascii=False))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -121,8 +286,12 @@ def main():
         print(json.dumps({"pmc_calibration": {"stream_read_bytes": 1 << 28, "copy_bytes_each_way": 1 << 28}}))
         return
 
+    cfg = wl.CONFIGS[args.workload]
+    if cfg.get("Lq", 1) > 1:
+        return bench_prefill(args, torch, sq, wl, dev)
+    if cfg.get("C1", 0):
+        return bench_hier(args, torch, sq, wl, dev)
     w = wl.make_config(args.workload, seed=args.seed, threads=16)
-    assert w.Lq == 1 and not w.C1, "bench.py times the one-level decode path"
     wl.calibrate(w, gpu_score_fn(sq, torch, dev))
     NQ, R = args.queries, args.replicas
     tt = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
@@ -177,42 +346,7 @@ def main():
         if rc:
             raise sq.SqError(rc, L_.sq_last_error().decode())
 
-    def cur_stream():
-        return C.c_void_p(torch.cuda.current_stream().cuda_stream)
-
-    # ---- eager: W warm-up steps, then exactly K timed steps between two synchronisations -------------
-    st = cur_stream()
-    for i in range(args.warmup):
-        step(i, st)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + i, st)
-    torch.cuda.synchronize()
-    eager_ms = (time.perf_counter() - t0) / args.steps * 1e3
-
-    # ---- the same K steps captured once into a HIP graph and replayed (no host launch cost) ----------
-    graph_ms = None
-    if not args.no_graph:
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g):
-            st_cap = cur_stream()
-            for i in range(args.steps):
-                step(args.warmup + i, st_cap)
-        g.replay()                                   # untimed replay (warm-up of the graph itself)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        g.replay()
-        torch.cuda.synchronize()
-        graph_ms = (time.perf_counter() - t0) / args.steps * 1e3
-    ms_per_step = min(eager_ms, graph_ms) if graph_ms is not None else eager_ms
-
-    # ---- same steps again, eager, with HIP events around every launch of the dominant kernel ---------
-    sq.sq_profile_begin(args.steps)
-    for i in range(args.steps):
-        step(args.warmup + i, st)
-    torch.cuda.synchronize()
-    n_meas, k_avg_us, k_min_us, k_max_us = sq.sq_profile_end()
+    eager_ms, graph_ms, ms_per_step, (n_meas, k_avg_us, k_min_us, k_max_us) = time_steps(step, args, torch, sq)
 
     nk = nkeys.cpu().numpy()[:, :, :, 0]                       # [NQ, B, H]
     used = [(args.warmup + i) % NQ for i in range(args.steps)]

@@ -167,7 +167,8 @@ int sq_hier_select(const sq_shape_t *shape, int32_t C1, const void *q,
  * One whole decode step (Lq must be 1): sq_centroid_score + sq_select + sq_sparse_attn_decode
  * enqueued back to back with the intermediate results kept in the workspace -- the end-to-end
  * quantity the paper times (lookup + argument set-up + sparse attention, Appendix "Kernel
- * Benchmarking").  Results are identical to the three separate calls.
+ * Benchmarking").  The selection is bit-identical to the three separate calls; the attention output
+ * agrees up to fp32 rounding (the keys are split over workgroups differently).
  * Out: out f16 [B,H,1,d]; optional (NULL to skip): lse f32 [B,H,1], keep_mask u32 [B,H,1,ceil(C/32)],
  *      n_keys i32 [B,H,1].
  * Workspace: sq_workspace_bytes(shape, SQ_CALL_DECODE_STEP).

@@ -119,10 +119,11 @@ __device__ __forceinline__ void chunk_rows_from_records(int rec_pos, int rec_del
 
 // Row statistics of Eq. 1 in max-subtracted form, computed by ONE wave for one query row:
 //   m = max over clusters with N > 0 of x;  D = sum_i N_i * exp(x_i - m).
-// Lane l accumulates clusters l, l+64, l+128, ... in ascending order and the 64 lane sums are
-// combined with a butterfly.  Every kernel that needs (m, D) calls this, on global or LDS memory, so
-// the values are bit-identical wherever they are produced.  Loads are issued eight at a time ahead
-// of the arithmetic (the order of the arithmetic does not change).
+// The library has ONE summation order for D, chosen so that a 1024-thread workgroup can produce it in
+// parallel: virtual thread v (0..1023) adds clusters v, v+1024, ... in ascending order; the 64 threads of
+// each of the 16 groups are combined with an xor butterfly; the 16 group sums are added in ascending
+// order.  This function walks the 16 groups one after the other, the selection kernel computes them
+// side by side: the results are bit-identical.
 __device__ __forceinline__ void wave_row_stats(const float *x, const int32_t *N, int n, int lane, float &m_out,
                                                float &D_out)
 {
@@ -143,21 +144,25 @@ __device__ __forceinline__ void wave_row_stats(const float *x, const int32_t *N,
     }
     m = wave_max(m);
     float Dsum = 0.0f;
-    for (int i0 = 0; i0 < n; i0 += 64 * UN) {
-        float xv[UN];
-        int nv[UN];
+    for (int grp = 0; grp < 16; ++grp) {
+        float local = 0.0f;
+        for (int i0 = grp * 64 + lane; i0 < n; i0 += 1024 * 4) {     // four loads in flight
+            float xv[4];
+            int nv[4];
 #pragma unroll
-        for (int u = 0; u < UN; ++u) {
-            const int i = i0 + u * 64 + lane;
-            nv[u] = i < n ? N[i] : 0;
-            xv[u] = i < n ? x[i] : 0.0f;
+            for (int u = 0; u < 4; ++u) {
+                const int i = i0 + u * 1024;
+                nv[u] = i < n ? N[i] : 0;
+                xv[u] = i < n ? x[i] : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (nv[u] > 0) local += (float)nv[u] * expf(xv[u] - m);
         }
-#pragma unroll
-        for (int u = 0; u < UN; ++u)
-            if (nv[u] > 0) Dsum += (float)nv[u] * expf(xv[u] - m);
+        Dsum += wave_sum(local);
     }
     m_out = m;
-    D_out = wave_sum(Dsum);
+    D_out = Dsum;
 }
 
 }  // namespace sq

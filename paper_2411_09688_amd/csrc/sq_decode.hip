@@ -26,16 +26,21 @@ constexpr int NI = KW / 4;      // loads per lane (4 rows per wave-wide load)
 // four output dimensions, 16-byte loads, four partials in flight), then the groups are folded in LDS.
 constexpr int MERGE_THREADS = 1024;
 constexpr int MERGE_GROUPS = MERGE_THREADS / 32;
-__device__ __forceinline__ void merge_row(const float *__restrict__ base, int n, _Float16 *__restrict__ out_row,
-                                          float *lse_row, float *s_red /*[MERGE_GROUPS * 130]*/, int tid)
+// The row's partials sit at item indices `first` and every multiple of `k` inside (first, first + items):
+// partial c is at slot (c == 0 ? first : (first / k + c) * k), n of them.
+__device__ __forceinline__ void merge_row(const float *__restrict__ partials, int first, int k, int n,
+                                          _Float16 *__restrict__ out_row, float *lse_row,
+                                          float *s_red /*[MERGE_GROUPS * 130]*/, int tid)
 {
+    const int fk = first / k;
+    auto slot_ptr = [&](int c) { return partials + (size_t)(c == 0 ? first : (fk + c) * k) * PART_STRIDE; };
     const int quad = tid & 31, grp = tid >> 5;
     float M = SQ_NEG_INF, lsum = 0.0f;
     f4 acc = {0.f, 0.f, 0.f, 0.f};
     int c = grp;
     for (; c + 3 * MERGE_GROUPS < n; c += 4 * MERGE_GROUPS) {
-        const float *p0 = base + (size_t)c * PART_STRIDE, *p1 = p0 + MERGE_GROUPS * PART_STRIDE,
-                    *p2 = p1 + MERGE_GROUPS * PART_STRIDE, *p3 = p2 + MERGE_GROUPS * PART_STRIDE;
+        const float *p0 = slot_ptr(c), *p1 = slot_ptr(c + MERGE_GROUPS), *p2 = slot_ptr(c + 2 * MERGE_GROUPS),
+                    *p3 = slot_ptr(c + 3 * MERGE_GROUPS);
         const float2 a0 = *reinterpret_cast<const float2 *>(p0), a1 = *reinterpret_cast<const float2 *>(p1),
                      a2 = *reinterpret_cast<const float2 *>(p2), a3 = *reinterpret_cast<const float2 *>(p3);
         const f4 o0 = *reinterpret_cast<const f4 *>(p0 + 4 + quad * 4), o1 = *reinterpret_cast<const f4 *>(p1 + 4 + quad * 4),
@@ -48,7 +53,7 @@ __device__ __forceinline__ void merge_row(const float *__restrict__ base, int n,
         M = Mn;
     }
     for (; c < n; c += MERGE_GROUPS) {
-        const float *p = base + (size_t)c * PART_STRIDE;
+        const float *p = slot_ptr(c);
         const float2 a = *reinterpret_cast<const float2 *>(p);
         const f4 o = *reinterpret_cast<const f4 *>(p + 4 + quad * 4);
         const float Mn = fmaxf(M, a.x);
@@ -85,8 +90,11 @@ __device__ __forceinline__ void merge_row(const float *__restrict__ base, int n,
 }
 
 // Phase 1: one work item = one chunk of up to KPC keys of one (sequence, head) row.  The grid is a fixed
-// number of workgroups; workgroup w takes items w, w + gridDim.x, ... below the item count the schedule
-// kernel left in the plan, so no workgroup is launched for chunks that do not exist.
+// number of workgroups; workgroup w takes the k consecutive items [w*k, (w+1)*k), k = ceil(items / grid),
+// so every workgroup streams the same number of keys whatever the selection looks like and no workgroup
+// is launched for chunks that do not exist.  Consecutive items of the same row are folded into one
+// running (max, sum, output) per lane, so a partial result is written once per (workgroup, row) segment,
+// at the index of the segment's first item.
 __global__ __launch_bounds__(256) void decode_attn_kernel(
     const _Float16 *__restrict__ q, const _Float16 *__restrict__ Kf, const _Float16 *__restrict__ Vf,
     const _Float16 *__restrict__ Ku, const _Float16 *__restrict__ Vu, DecodePlan plan,
@@ -99,15 +107,68 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 4, p = lane & 15;
 
-    // The item count, the first item's header and its records are independent loads: one round trip.
-    // (blockIdx.x < item_cap, so the speculative loads stay inside the plan.)
-    int item = blockIdx.x;
+    const int total = min(*plan.total, plan.item_cap);
+    const int k = (total + (int)gridDim.x - 1) / (int)gridDim.x;
+    int item = blockIdx.x * k;
+    const int item_end = min(item + k, total);
+    if (item >= item_end) return;                          // whole workgroup
+
     const int2 *it = plan.item + (size_t)item * ITEM_STRIDE;
     int2 h0_next = it[0], h1_next = it[1], rec_next = it[2 + (tid < KPC ? tid : 0)];   // threads >= KPC idle here
-    const int total = min(*plan.total, plan.item_cap);
 
-    for (; item < total; item += gridDim.x) {
+    // Running state of the current (workgroup, row) segment.  m is wave-uniform; l and o are this lane's
+    // share (its 16-lane group's keys), summed over the four groups only when the segment is flushed.
+    float m_run = SQ_NEG_INF, l_run = 0.0f;
+    float o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    int seg_first = item;
+    int cur_row = h0_next.x;
+
+    auto flush = [&](int slot) {
+        const float l_w = cross16_sum(l_run);
+        float ow[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ow[e] = cross16_sum(o[e]);
+        if (g == 0) {
+            if (p == 0) {
+                s_part[wave][0] = m_run;
+                s_part[wave][1] = l_w;
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s_part[wave][4 + p * 8 + e] = ow[e];
+        }
+        __syncthreads();
+        // Combine the four waves; threads 0..127 own one output dimension each.
+        if (tid < D) {
+            const float M = fmaxf(fmaxf(s_part[0][0], s_part[1][0]), fmaxf(s_part[2][0], s_part[3][0]));
+            float lsum = 0.0f, acc = 0.0f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float mw = s_part[w][0];
+                const float sc = mw == SQ_NEG_INF ? 0.0f : __expf(mw - M);
+                lsum += sc * s_part[w][1];
+                acc += sc * s_part[w][4 + tid];
+            }
+            float *dst = partials + (size_t)slot * PART_STRIDE;
+            if (tid == 0) {
+                dst[0] = M;
+                dst[1] = lsum;
+            }
+            dst[4 + tid] = acc;
+        }
+        __syncthreads();
+    };
+
+    for (; item < item_end; ++item) {
         const int2 h0 = h0_next, h1 = h1_next, rc = rec_next;   // (row, keys) (records | -1, first user key)
+        if (h0.x != cur_row) {                             // workgroup-uniform: the segment of the previous row ends
+            flush(seg_first);
+            m_run = SQ_NEG_INF;
+            l_run = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = 0.0f;
+            seg_first = item;
+            cur_row = h0.x;
+        }
         const size_t bh = (size_t)h0.x;
         const int nvalid = h0.y;
         const bool user = h1.x < 0;
@@ -134,71 +195,45 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
             const int kl = wave * KW + i * 4 + g;
             int r = s_rows[kl];
             r = r < 0 ? r_last : r;                       // slots past the chunk re-read a valid row
-            const size_t o = (size_t)r * D + p * 8;
-            kreg[i] = *reinterpret_cast<const h8 *>(Kbase + o);
-            vreg[i] = *reinterpret_cast<const h8 *>(Vbase + o);
+            const size_t off = (size_t)r * D + p * 8;
+            kreg[i] = *reinterpret_cast<const h8 *>(Kbase + off);
+            vreg[i] = *reinterpret_cast<const h8 *>(Vbase + off);
         }
-        // Metadata of this workgroup's next item, fetched behind the K/V stream.
-        if (item + (int)gridDim.x < total) {
-            const int2 *nx = plan.item + (size_t)(item + gridDim.x) * ITEM_STRIDE;
+        // Metadata of the next item, fetched behind the K/V stream.
+        if (item + 1 < item_end) {
+            const int2 *nx = plan.item + (size_t)(item + 1) * ITEM_STRIDE;
             h0_next = nx[0];
             h1_next = nx[1];
             rec_next = nx[2 + (tid < KPC ? tid : 0)];
         }
 
-        // Scores of this lane-group's keys and the wave-local softmax.
+        // Scores of this lane-group's keys, folded into the running softmax.
         float s[NI];
-        float m_w = SQ_NEG_INF;
+        float m_it = SQ_NEG_INF;
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const int kl = wave * KW + i * 4 + g;
             const float d = row16_sum(dot8(qv, kreg[i], 0.0f)) * sm_scale;
             s[i] = kl < nvalid ? d : SQ_NEG_INF;
-            m_w = fmaxf(m_w, s[i]);
+            m_it = fmaxf(m_it, s[i]);
         }
-        m_w = cross16_max(m_w);
-        float l_w = 0.0f;
-        float o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        m_it = cross16_max(m_it);
+        const float m_new = fmaxf(m_run, m_it);
+        const float alpha = m_new == SQ_NEG_INF ? 1.0f : __expf(m_run - m_new);   // exp(-inf) = 0 on the first item
+        l_run *= alpha;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] *= alpha;
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
-            const float pr = s[i] == SQ_NEG_INF ? 0.0f : __expf(s[i] - m_w);
-            l_w += pr;
+            const float pr = s[i] == SQ_NEG_INF ? 0.0f : __expf(s[i] - m_new);
+            l_run += pr;
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[e] += pr * (float)vreg[i][e];
         }
-        l_w = cross16_sum(l_w);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = cross16_sum(o[e]);
-        if (g == 0) {
-            if (p == 0) {
-                s_part[wave][0] = m_w;
-                s_part[wave][1] = l_w;
-            }
-#pragma unroll
-            for (int e = 0; e < 8; ++e) s_part[wave][4 + p * 8 + e] = o[e];
-        }
-        __syncthreads();
-
-        // Combine the four waves; threads 0..127 own one output dimension each.
-        if (tid < D) {
-            const float M = fmaxf(fmaxf(s_part[0][0], s_part[1][0]), fmaxf(s_part[2][0], s_part[3][0]));
-            float lsum = 0.0f, acc = 0.0f;
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                const float mw = s_part[w][0];
-                const float sc = mw == SQ_NEG_INF ? 0.0f : __expf(mw - M);
-                lsum += sc * s_part[w][1];
-                acc += sc * s_part[w][4 + tid];
-            }
-            float *dst = partials + (size_t)item * PART_STRIDE;
-            if (tid == 0) {
-                dst[0] = M;
-                dst[1] = lsum;
-            }
-            dst[4 + tid] = acc;
-        }
-        __syncthreads();      // LDS is reused by the next item
+        m_run = m_new;
+        __syncthreads();      // s_rows is rewritten by the next item
     }
+    flush(seg_first);
 }
 
 // Phase 2 (Section 4.2): one workgroup per (sequence, head) merges the row's partials.  A separate
@@ -206,17 +241,18 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
 // kernel would write back a whole L2 per workgroup and costs far more than this launch.
 __global__ __launch_bounds__(MERGE_THREADS) void decode_merge_kernel(const float *__restrict__ partials,
                                                                      DecodePlan plan, _Float16 *__restrict__ out,
-                                                                     float *__restrict__ lse)
+                                                                     float *__restrict__ lse, int attn_grid)
 {
     __shared__ float s_red[MERGE_GROUPS * 130];
     const size_t bh = blockIdx.x;
     const int2 it = plan.row_items[bh];              // (first item, items) of this row
-    merge_row(partials + (size_t)it.x * PART_STRIDE, it.y, out + bh * D, lse ? lse + bh : nullptr, s_red,
-              threadIdx.x);
+    const int total = min(*plan.total, plan.item_cap);
+    const int k = max(1, (total + attn_grid - 1) / attn_grid);     // items per attention workgroup
+    const int n = it.y == 0 ? 0 : 1 + (it.x + it.y - 1) / k - it.x / k;
+    merge_row(partials, it.x, k, n, out + bh * D, lse ? lse + bh : nullptr, s_red, threadIdx.x);
 }
 
-// Workgroups of the persistent partial kernel: enough to hold every chunk of a typical selection in one
-// pass and to fill all 256 compute units several times over.
+// Workgroups of the persistent partial kernel: four per compute unit.
 constexpr int ATTN_GRID = 256 * 4;
 
 hipError_t launch_decode_attn(const void *q, const void *Kf, const void *Vf, const void *Ku, const void *Vu,
@@ -234,7 +270,8 @@ hipError_t launch_decode_attn(const void *q, const void *Kf, const void *Vf, con
     if (prof) profile_mark(s, false);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(decode_merge_kernel, dim3(rows), dim3(MERGE_THREADS), 0, s, partials, plan, (_Float16 *)out, lse);
+    hipLaunchKernelGGL(decode_merge_kernel, dim3(rows), dim3(MERGE_THREADS), 0, s, partials, plan, (_Float16 *)out, lse,
+                       grid);
     return hipGetLastError();
 }
 

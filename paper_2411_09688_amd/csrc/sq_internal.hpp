@@ -42,7 +42,7 @@ inline int user_chunks_for(int U) { return (U + KPC - 1) / KPC; }
 
 // Row-wise selection stages a row's logits and cluster sizes in LDS.
 constexpr int SELECT_MAX_C = 16384;
-constexpr int LDS_BYTES_MAX = 160 * 1024 - 1024;   // gfx950: 160 KB per workgroup, minus the static arrays
+constexpr int LDS_BYTES_MAX = 160 * 1024 - 4096;   // gfx950: 160 KB per workgroup, minus the static arrays
 // Scheduling keeps two ints per chunk of a row in LDS (same budget as the staged logits).
 constexpr int MAX_L = SELECT_MAX_C * KPC;
 

@@ -125,7 +125,6 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ float s_wred[SEL_WAVES];
     __shared__ int s_base;
-    __shared__ int s_cnt[SEL_WAVES], s_keys[SEL_WAVES];
     __shared__ float s_thr;
     float *s_e = reinterpret_cast<float *>(smem);          // [C] logits, then e_i
     int32_t *s_N = reinterpret_cast<int32_t *>(s_e + C);   // [C]
@@ -163,8 +162,6 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
             s_N[i] = N[i];
         }
     }
-    int start_first = tid < C ? off[tid] : 0;               // offsets of the first step, fetched with the logits
-    int next_first = (opt.len_from_offsets && tid < C) ? off[tid + 1] : 0;
     float m;
     if (STATS_IN) {
         m = row_max[row];
@@ -184,54 +181,110 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
         for (int w = 1; w < SEL_WAVES; ++w) m = fmaxf(m, s_wred[w]);
         for (int i = tid; i < C; i += SEL_THREADS) s_e[i] = s_N[i] > 0 ? expf(s_e[i] - m) : 0.0f;
         __syncthreads();
-        // D in the library's one summation order: lane l adds clusters l, l+64, ... ascending, then a
-        // butterfly over the 64 lanes (identical to wave_row_stats).
-        if (wave == 0) {
+        // D in the library's one summation order (see wave_row_stats): thread v adds clusters v, v+1024, ...
+        // ascending, butterfly inside each wave, then the 16 wave sums in ascending order.
+        float local = 0.0f;
+        for (int i = tid; i < C; i += SEL_THREADS) {
+            const int Ni = s_N[i];
+            if (Ni > 0) local += (float)Ni * s_e[i];
+        }
+        local = wave_sum(local);
+        if (lane == 0) s_wred[wave] = local;
+        __syncthreads();
+        if (tid == 0) {
             float Dsum = 0.0f;
-            for (int i = lane; i < C; i += 64) {
-                const int Ni = s_N[i];
-                if (Ni > 0) Dsum += (float)Ni * s_e[i];
-            }
-            Dsum = wave_sum(Dsum);
-            if (lane == 0) s_thr = T * Dsum;
+#pragma unroll
+            for (int w = 0; w < SEL_WAVES; ++w) Dsum += s_wred[w];
+            s_thr = T * Dsum;
         }
     }
     __syncthreads();
     const float thr = s_thr;
 
-    int base_r = 0, base_k = 0;
+    // Compaction in two passes over the (up to 16) block-wide steps, with one barrier between them.
+    // Pass 1: every wave counts the ranges it will emit and their keys, step by step, into a small LDS
+    // table, and writes the mask words.  The table's exclusive prefix in (step, wave) order gives every
+    // wave of every step its first record index and key prefix.  Pass 2 repeats the cheap ballot and
+    // lane scan and emits.
+    __shared__ int s_tcnt[16 * SEL_WAVES + 1], s_tkeys[16 * SEL_WAVES + 1];
+    const int n_steps = (C + SEL_THREADS - 1) / SEL_THREADS;
+    const int start_first = (tid < C) ? off[tid] : 0;       // offsets of the first step, fetched early
+    const int next_first = (opt.len_from_offsets && tid < C) ? off[tid + 1] : 0;
+    for (int st = 0; st < n_steps; ++st) {
+        const int i = st * SEL_THREADS + tid;
+        const int Ni = i < C ? s_N[i] : 0;
+        const bool keep = Ni > 0 && s_e[i] > thr;
+        int len = Ni;
+        if (opt.len_from_offsets) len = keep ? (st == 0 ? next_first - start_first : off[i + 1] - off[i]) : 0;
+        const bool emit = keep && len > 0;              // a kept coarse cluster without children emits nothing
+        const unsigned long long bal = __ballot(keep), bal_emit = __ballot(emit);
+        const int wkeys = wave_sum_i(emit ? len : 0);
+        if (lane == 0) {
+            s_tcnt[st * SEL_WAVES + wave] = __popcll(bal_emit);
+            s_tkeys[st * SEL_WAVES + wave] = wkeys;
+            if (keep_mask) {
+                const int w0 = (i >> 5);
+                if (w0 < W) keep_mask[row * W + w0] = (uint32_t)bal;
+                if (w0 + 1 < W) keep_mask[row * W + w0 + 1] = (uint32_t)(bal >> 32);
+            }
+        }
+    }
+    __syncthreads();
+    if (wave == 0) {                                     // exclusive prefix of the n_steps*16 (<= 256) entries
+        const int n_ent = n_steps * SEL_WAVES;
+        int c4[4], k4[4], cs = 0, ks = 0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = lane * 4 + u;
+            c4[u] = e < n_ent ? s_tcnt[e] : 0;
+            k4[u] = e < n_ent ? s_tkeys[e] : 0;
+            cs += c4[u];
+            ks += k4[u];
+        }
+        int cpre = wave_inclusive_scan(cs, lane) - cs, kpre = wave_inclusive_scan(ks, lane) - ks;
+        const int ctot = __shfl(cpre + cs, 63), ktot = __shfl(kpre + ks, 63);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = lane * 4 + u;
+            if (e < n_ent) {
+                s_tcnt[e] = cpre;
+                s_tkeys[e] = kpre;
+            }
+            cpre += c4[u];
+            kpre += k4[u];
+        }
+        if (lane == 0) {
+            s_tcnt[16 * SEL_WAVES] = ctot;
+            s_tkeys[16 * SEL_WAVES] = ktot;
+        }
+    }
+    __syncthreads();
+    const int base_r = s_tcnt[16 * SEL_WAVES], base_k = s_tkeys[16 * SEL_WAVES];   // totals of the row
     bool have_rec = false;                                   // this thread's record of the (only) step
     int my_r = 0;
     int4 my_rec = make_int4(0, 0, 0, 0);
-    for (int i0 = 0; i0 < C; i0 += SEL_THREADS) {
-        const int i = i0 + tid;
+    for (int st = 0; st < n_steps; ++st) {
+        const int i = st * SEL_THREADS + tid;
         const int Ni = i < C ? s_N[i] : 0;
         const bool keep = Ni > 0 && s_e[i] > thr;
-        const int start = i0 == 0 ? start_first : (keep ? off[i] : 0);
-        // Length of the emitted range: the cluster's keys, or (level 1 of the two-level lookup) the
-        // number of child clusters, read from the offsets.
+        const int start = st == 0 ? start_first : (keep ? off[i] : 0);
         int len = Ni;
-        if (opt.len_from_offsets) len = keep ? (i0 == 0 ? next_first : off[i + 1]) - start : 0;
-        // A kept coarse cluster without children is kept (mask bit) but emits no range.
+        if (opt.len_from_offsets) len = keep ? (st == 0 ? next_first : off[i + 1]) - start : 0;
         const bool emit = keep && len > 0;
-        unsigned long long bal_emit;
-        const ScanOut sc = block_scan_kept<SEL_WAVES>(emit, len, lane, wave, s_cnt, s_keys, bal_emit);
-        const unsigned long long bal = __ballot(keep);
-        if (lane == 0 && keep_mask) {
-            const int w0 = (i0 >> 5) + wave * 2;
-            if (w0 < W) keep_mask[row * W + w0] = (uint32_t)bal;
-            if (w0 + 1 < W) keep_mask[row * W + w0 + 1] = (uint32_t)(bal >> 32);
-        }
+        const unsigned long long bal_emit = __ballot(emit);
+        if (bal_emit == 0ull) continue;                  // wave-uniform
+        const int rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(bal_emit >> 32),
+                                                   __builtin_amdgcn_mbcnt_lo((uint32_t)bal_emit, 0));
+        const int kv = emit ? len : 0;
+        const int incl = wave_inclusive_scan(kv, lane);
         if (emit) {
-            const int r = base_r + sc.rank;
+            const int r = s_tcnt[st * SEL_WAVES + wave] + rank;
             if (ranges) *reinterpret_cast<int2 *>(ranges + (row * C + r) * 2) = make_int2(start, len);
-            my_rec = make_int4(start, len, base_k + sc.key_prefix, 0);
+            my_rec = make_int4(start, len, s_tkeys[st * SEL_WAVES + wave] + incl - kv, 0);
             my_r = r;
             have_rec = true;
             if (plan.rec) plan.rec[row * plan.rec_cap + r] = my_rec;
         }
-        base_r += sc.total_cnt;
-        base_k += sc.total_keys;
     }
     if (tid == 0) {
         n_ranges[row] = base_r;
