@@ -215,6 +215,7 @@ size_t sq_workspace_bytes(const sq_shape_t *sh, int which)
         return cv.off;
     case SQ_CALL_ATTN_PREFILL:
         cv.take<int32_t>((size_t)sh->H * sh->L);
+        cv.take<int32_t>((size_t)sh->H * ((sh->L + 63) / 64));
         return cv.off;
     case SQ_CALL_HIER_SELECT:
         carve_hier(cv, sh);
@@ -355,7 +356,8 @@ int sq_sparse_attn_prefill(const sq_shape_t *sh, const void *q, const void *K_fi
     if (int rc = check_device(__func__)) return rc;
     Carver cv(ws);
     int32_t *key_cid = cv.take<int32_t>((size_t)sh->H * sh->L);
-    SQ_HIP(sq::launch_prefill_attn(q, K_fixed, V_fixed, K_user, V_user, keep_mask, offsets, key_cid, out, lse,
+    int32_t *blk_info = cv.take<int32_t>((size_t)sh->H * ((sh->L + 63) / 64));
+    SQ_HIP(sq::launch_prefill_attn(q, K_fixed, V_fixed, K_user, V_user, keep_mask, offsets, key_cid, blk_info, out, lse,
                                    to_shape(sh), static_cast<hipStream_t>(stream)));
     g_err[0] = 0;
     return SQ_OK;

@@ -79,8 +79,8 @@ hipError_t launch_decode_attn(const void *q, const void *Kf, const void *Vf, con
 
 // Prefill attention with per-query keep masks; key_cid [H, L] is workspace for the key -> cluster map.
 hipError_t launch_prefill_attn(const void *q, const void *Kf, const void *Vf, const void *Ku, const void *Vu,
-                               const uint32_t *keep_mask, const int32_t *offsets, int32_t *key_cid, void *out,
-                               float *lse, const Shape &sh, hipStream_t s);
+                               const uint32_t *keep_mask, const int32_t *offsets, int32_t *key_cid, int32_t *blk_info,
+                               void *out, float *lse, const Shape &sh, hipStream_t s);
 
 // Measurement hook (sq_profile.hip): records an event before / after the partial kernel when enabled.
 bool profile_mark(hipStream_t s, bool begin);

@@ -3,8 +3,9 @@
 //
 // Layout of the computation (FlashAttention-2 style: grid over heads x query blocks, loop over key blocks,
 // online softmax), written for CDNA4 matrix cores:
-//   * a workgroup = 4 waves x 16*QT queries; all waves walk the same 64-key blocks, whose K tile and
-//     transposed V tile are staged in LDS once per workgroup;
+//   * a workgroup = 4 waves x 32 queries; all waves walk the same 64-key blocks, whose K tile and transposed
+//     V tile are staged in LDS once per workgroup (two LDS buffers; the next block's global loads are issued
+//     before the current block's arithmetic and land in registers meanwhile);
 //   * scores are computed TRANSPOSED, S^T = K Q^T, with 16x16x32 fp16 MFMA tiles (A = 16 keys, B = 16
 //     queries).  In the accumulator layout a lane then owns ONE query column for the whole kernel (and four
 //     keys per tile), so the running maximum, the running sum and the rescaling of the output are per-lane
@@ -39,9 +40,17 @@ __global__ __launch_bounds__(256) void key_cluster_kernel(const int32_t *__restr
     }
 }
 
-__device__ __forceinline__ int s_cid_first(const int32_t *key_cid, int h, int L, int j0, int C)
+// Per 64-key block: first mask word its clusters can touch, and whether they span more than three words
+// (possible only across runs of empty clusters).  blk_info[h, blk] = (w0 << 1) | wide.
+__global__ __launch_bounds__(256) void block_info_kernel(const int32_t *__restrict__ cid, int32_t *__restrict__ blk_info,
+                                                         int C, int L, int nblk)
 {
-    return min(key_cid[(size_t)h * L + j0], C - 1);
+    const int h = blockIdx.y;
+    const int blk = blockIdx.x * 256 + threadIdx.x;
+    if (blk >= nblk) return;
+    const int first = min(cid[(size_t)h * L + blk * PF_BN], C - 1);
+    const int last = min(cid[(size_t)h * L + min(L, (blk + 1) * PF_BN) - 1], C - 1);
+    blk_info[(size_t)h * nblk + blk] = ((first >> 5) << 1) | (((last >> 5) - (first >> 5)) > 2 ? 1 : 0);
 }
 
 // Position of key kappa (0..63) of a block inside a V^T row: within each 32-key group, key (t*16 + g*4 + j)
@@ -52,26 +61,41 @@ __device__ __forceinline__ int vt_pos(int kappa)
     return ks * 32 + g * 8 + t * 4 + j;
 }
 
-template <int QT>
+constexpr int PF_QT = 2;                  // 16-query tiles per wave
+constexpr int PF_BM = 64 * PF_QT;         // queries per workgroup (4 waves)
+constexpr int PF_MW = PF_BM * 3;          // mask words staged per block
+
+struct PfStage {                          // one LDS buffer of a key block
+    _Float16 K[PF_BN * PF_KS_STRIDE];
+    _Float16 Vt[D * PF_VT_STRIDE];
+    int cid[PF_BN];
+    uint32_t mw[PF_BM * 4];
+};
+
 __global__ __launch_bounds__(256) void prefill_attn_kernel(
     const _Float16 *__restrict__ q, const _Float16 *__restrict__ Kf, const _Float16 *__restrict__ Vf,
     const _Float16 *__restrict__ Ku, const _Float16 *__restrict__ Vu, const uint32_t *__restrict__ keep_mask,
-    const int32_t *__restrict__ key_cid, _Float16 *__restrict__ out, float *__restrict__ lse, int H, int L, int C,
-    int Lq, int U, int causal_user, float sm_scale)
+    const int32_t *__restrict__ key_cid, const int32_t *__restrict__ blk_info, _Float16 *__restrict__ out,
+    float *__restrict__ lse, int B, int H, int L, int C, int Lq, int U, int causal_user, float sm_scale)
 {
-    constexpr int BM = 64 * QT;           // queries per workgroup
-    __shared__ __align__(16) _Float16 s_K[PF_BN * PF_KS_STRIDE];
-    __shared__ __align__(16) _Float16 s_Vt[D * PF_VT_STRIDE];
-    __shared__ __align__(16) int s_cid[PF_BN];
-    __shared__ __align__(16) uint32_t s_mw[BM * 4];       // up to 3 mask words per query for the current block
-    __shared__ int s_w0, s_wide;
+    constexpr int QT = PF_QT, BM = PF_BM;
+    extern __shared__ __align__(16) unsigned char smem[];
+    PfStage *stage = reinterpret_cast<PfStage *>(smem);   // [2]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 15, kg = lane >> 4;
-    const int h = blockIdx.y, b = blockIdx.z;
-    const int q0 = blockIdx.x * BM;                       // first query of the workgroup
+    // Workgroup -> (head, sequence, query block).  Workgroups are dealt to the 8 XCDs round-robin by their
+    // linear id; units that share a head (and so stream the same K/V) are made to land on the same XCD, so
+    // one L2 fetches a head's keys once for all of its query blocks.
+    const int nqb = (Lq + BM - 1) / BM;
+    const int per_xcd = gridDim.x >> 3;                   // grid is a multiple of 8
+    const int unit = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (unit >= nqb * B * H) return;
+    const int h = unit / (nqb * B), b = (unit / nqb) % B;
+    const int q0 = (unit % nqb) * BM;                     // first query of the workgroup
     const int W = (C + 31) >> 5;
     const size_t row0 = ((size_t)b * H + h) * Lq;         // query-row index of query 0 of this (b, h)
+    const float c2 = sm_scale * 1.44269504088896341f;     // scores are kept in units of log2(e): exp2 below
 
     // Queries of this lane: n[qt] = q0 + wave*16*QT + qt*16 + col; B operand of S^T = K Q^T.
     h8 bq[QT][4];
@@ -100,76 +124,121 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(
     const int nblk_fixed = (L + PF_BN - 1) / PF_BN;
     // Causal user block: queries of this workgroup see user keys 0 .. min(U, q0 + BM) - 1 at most.
     const int u_vis = causal_user ? min(U, q0 + BM) : U;
-    const int nblk_user = (u_vis + PF_BN - 1) / PF_BN;
+    const int nblk = nblk_fixed + (u_vis + PF_BN - 1) / PF_BN;
+    const int32_t *binfo = blk_info + (size_t)h * nblk_fixed;
 
-    for (int blk = 0; blk < nblk_fixed + nblk_user; ++blk) {
+    // Registers that carry the next block from global memory to LDS.
+    h8 pk[4], pv[4];
+    int pcid = 0;
+    uint32_t pmw[2] = {0u, 0u};
+    int pinfo = 0;
+    auto fetch = [&](int blk) {           // issue the global loads of block `blk`
         const bool user = blk >= nblk_fixed;
-        const int j0 = (user ? blk - nblk_fixed : blk) * PF_BN;       // first key of the block
+        const int j0 = (user ? blk - nblk_fixed : blk) * PF_BN;
         const int nkeys = user ? U : L;
         const _Float16 *Kb = user ? Kuh : Kfh, *Vb = user ? Vuh : Vfh;
-
-        // ---- stage the block: K rows, V transposed, cluster ids, mask words --------------------------------
-        __syncthreads();                                   // previous block's LDS reads are done
-        if (!user) {
-            if (tid < PF_BN) {
-                const int j = j0 + tid;
-                const int c = j < L ? key_cid[(size_t)h * L + j] : 0x7fffffff;
-                s_cid[tid] = c;
-                if (tid == 0) s_w0 = min(c, C - 1) >> 5;
-                // Last real key of the block: if its cluster lies more than two mask words past the first
-                // key's (empty clusters in between), the staged words do not cover the block.
-                if (j == min(j0 + PF_BN, L) - 1) s_wide = (c >> 5) - (s_cid_first(key_cid, h, L, j0, C) >> 5) > 2;
-            }
-        }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int key = i * 16 + (tid >> 4), chunk = tid & 15;
             const int j = min(j0 + key, nkeys - 1);
-            const h8 kv = *reinterpret_cast<const h8 *>(Kb + (size_t)j * D + chunk * 8);
-            const h8 vv = *reinterpret_cast<const h8 *>(Vb + (size_t)j * D + chunk * 8);
-            *reinterpret_cast<h8 *>(s_K + key * PF_KS_STRIDE + chunk * 8) = kv;
-            const int pos = vt_pos(key);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) s_Vt[(chunk * 8 + e) * PF_VT_STRIDE + pos] = vv[e];
+            pk[i] = *reinterpret_cast<const h8 *>(Kb + (size_t)j * D + chunk * 8);
         }
-        __syncthreads();
+        {
+            // V: a lane takes ONE key and four 8-dim chunks (wave w: dims 32w .. 32w+31), so that the
+            // transposed LDS stores of a wave go to 64 different keys of one V^T row (no bank conflicts).
+            const int j = min(j0 + lane, nkeys - 1);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                pv[i] = *reinterpret_cast<const h8 *>(Vb + (size_t)j * D + (wave * 4 + i) * 8);
+        }
         if (!user) {
-            // Mask words w0 .. w0+2 of every query of the workgroup (64 consecutive clusters span <= 3 words).
-            const int w0 = s_w0;
-            for (int t = tid; t < BM * 3; t += 256) {
+            pinfo = binfo[blk];
+            if (tid < PF_BN) pcid = j0 + tid < L ? key_cid[(size_t)h * L + j0 + tid] : 0x7fffffff;
+            const int w0 = pinfo >> 1;
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int t = tid + u * 256;
                 const int ql = t / 3, wi = t - ql * 3;
                 const int n = min(q0 + ql, Lq - 1);
-                const int w = w0 + wi;
-                s_mw[ql * 4 + wi] = w < W ? keep_mask[(row0 + n) * W + w] : 0u;
+                pmw[u] = (t < PF_MW && w0 + wi < W) ? keep_mask[(row0 + n) * W + w0 + wi] : 0u;
             }
-            __syncthreads();
         }
+    };
+    auto commit = [&](int blk, PfStage &st) {   // registers -> LDS (K rows, V transposed, ids, mask words)
+        const bool user = blk >= nblk_fixed;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int key = i * 16 + (tid >> 4), chunk = tid & 15;
+            *reinterpret_cast<h8 *>(st.K + key * PF_KS_STRIDE + chunk * 8) = pk[i];
+        }
+        {
+            const int pos = vt_pos(lane);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) st.Vt[((wave * 4 + i) * 8 + e) * PF_VT_STRIDE + pos] = pv[i][e];
+        }
+        if (!user) {
+            if (tid < PF_BN) st.cid[tid] = pcid;
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int t = tid + u * 256;
+                if (t < PF_MW) {
+                    const int ql = t / 3;
+                    st.mw[ql * 4 + (t - ql * 3)] = pmw[u];
+                }
+            }
+        }
+    };
+
+    int info_cur = 0;
+    fetch(0);
+    info_cur = pinfo;
+    commit(0, stage[0]);
+    __syncthreads();
+
+    for (int blk = 0; blk < nblk; ++blk) {
+        PfStage &st = stage[blk & 1];
+        const bool user = blk >= nblk_fixed;
+        const int j0 = (user ? blk - nblk_fixed : blk) * PF_BN;
+        const int info = info_cur;
+        if (blk + 1 < nblk) fetch(blk + 1);                 // global loads of the next block run under this one
 
         // ---- visibility of this lane's (query, key) pairs --------------------------------------------------
         // vis[qt] bit (kt*4 + v): key kt*16 + kg*4 + v of the block is visible to query nq[qt].
         uint32_t vis[QT];
         bool any = false;
+        if (!user) {
+            const int w0 = info >> 1;
+            const bool wide = info & 1;                     // workgroup-uniform, rare
+            int cc[16];
 #pragma unroll
-        for (int qt = 0; qt < QT; ++qt) {
-            uint32_t bits = 0;
-            if (!user) {
-                const int w0 = s_w0;
-                const bool wide = s_wide != 0;                     // workgroup-uniform, rare
-                const uint4 mw = *reinterpret_cast<const uint4 *>(s_mw + (wave * 16 * QT + qt * 16 + col) * 4);
+            for (int kt = 0; kt < 4; ++kt) {
+                const int4 c4 = *reinterpret_cast<const int4 *>(st.cid + kt * 16 + kg * 4);
+                cc[kt * 4 + 0] = c4.x;
+                cc[kt * 4 + 1] = c4.y;
+                cc[kt * 4 + 2] = c4.z;
+                cc[kt * 4 + 3] = c4.w;
+            }
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt) {
+                const uint4 mw = *reinterpret_cast<const uint4 *>(st.mw + (wave * 16 * QT + qt * 16 + col) * 4);
                 const uint32_t *mrow = keep_mask + (row0 + min(nq[qt], Lq - 1)) * W;
+                uint32_t bits = 0;
 #pragma unroll
-                for (int kt = 0; kt < 4; ++kt) {
-                    const int4 c4 = *reinterpret_cast<const int4 *>(s_cid + kt * 16 + kg * 4);
-                    const int cc[4] = {c4.x, c4.y, c4.z, c4.w};
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int wi = (cc[v] >> 5) - w0;          // 0..2 for real keys, huge for padding
-                        uint32_t word = wi == 0 ? mw.x : (wi == 1 ? mw.y : (wi == 2 ? mw.z : 0u));
-                        if (wide && cc[v] < C) word = mrow[cc[v] >> 5];   // block spans > 3 mask words
-                        bits |= ((word >> (cc[v] & 31)) & 1u) << (kt * 4 + v);
-                    }
+                for (int e = 0; e < 16; ++e) {
+                    const int wi = (cc[e] >> 5) - w0;          // 0..2 for real keys, huge for padding
+                    uint32_t word = wi == 0 ? mw.x : (wi == 1 ? mw.y : (wi == 2 ? mw.z : 0u));
+                    if (wide && cc[e] < C) word = mrow[cc[e] >> 5];   // block spans > 3 mask words
+                    bits |= ((word >> (cc[e] & 31)) & 1u) << e;
                 }
-            } else {
+                vis[qt] = nq[qt] < Lq ? bits : 0u;
+                any |= vis[qt] != 0;
+            }
+        } else {
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt) {
+                uint32_t bits = 0;
 #pragma unroll
                 for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
@@ -178,85 +247,90 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(
                         const bool ok = j < U && (!causal_user || j <= nq[qt]);
                         bits |= (ok ? 1u : 0u) << (kt * 4 + v);
                     }
-            }
-            if (nq[qt] >= Lq) bits = 0;
-            vis[qt] = bits;
-            any |= bits != 0;
-        }
-        if (__ballot(any) == 0ull) continue;                // none of this wave's queries sees the block
-
-        // ---- S^T = K Q^T -----------------------------------------------------------------------------------
-        f4 st[QT][4];
-#pragma unroll
-        for (int qt = 0; qt < QT; ++qt)
-#pragma unroll
-            for (int kt = 0; kt < 4; ++kt) st[qt][kt] = f4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kt = 0; kt < 4; ++kt) {
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const h8 a = *reinterpret_cast<const h8 *>(s_K + (kt * 16 + col) * PF_KS_STRIDE + s * 32 + kg * 8);
-#pragma unroll
-                for (int qt = 0; qt < QT; ++qt)
-                    st[qt][kt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bq[qt][s], st[qt][kt], 0, 0, 0);
+                vis[qt] = nq[qt] < Lq ? bits : 0u;
+                any |= vis[qt] != 0;
             }
         }
 
-        // ---- online softmax per query column; P^T packed as the B operand of the next product ---------------
-        h8 bp[QT][2];
+        if (__ballot(any) != 0ull) {                        // else: none of this wave's queries sees the block
+            // ---- S^T = K Q^T ---------------------------------------------------------------------------------
+            f4 sacc[QT][4];
 #pragma unroll
-        for (int qt = 0; qt < QT; ++qt) {
-            float mx = SQ_NEG_INF;
+            for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
-            for (int kt = 0; kt < 4; ++kt)
+                for (int kt = 0; kt < 4; ++kt) sacc[qt][kt] = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const bool ok = (vis[qt] >> (kt * 4 + v)) & 1u;
-                    const float sv = ok ? st[qt][kt][v] * sm_scale : SQ_NEG_INF;
-                    st[qt][kt][v] = sv;
-                    mx = fmaxf(mx, sv);
+            for (int kt = 0; kt < 4; ++kt) {
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const h8 a = *reinterpret_cast<const h8 *>(st.K + (kt * 16 + col) * PF_KS_STRIDE + s * 32 + kg * 8);
+#pragma unroll
+                    for (int qt = 0; qt < QT; ++qt)
+                        sacc[qt][kt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bq[qt][s], sacc[qt][kt], 0, 0, 0);
                 }
-            mx = cross16_max(mx);                           // the 4 lane groups hold the other keys of the column
-            const float m_new = fmaxf(m_run[qt], mx);
-            const float alpha = m_new == SQ_NEG_INF ? 1.0f : __expf(m_run[qt] - m_new);
-            float psum = 0.0f;
-            float pv[16];
+            }
+
+            // ---- online softmax per query column (base 2); P^T packed as the B operand of the next product -----
+            h8 bp[QT][2];
 #pragma unroll
-            for (int kt = 0; kt < 4; ++kt)
+            for (int qt = 0; qt < QT; ++qt) {
+                float mx = SQ_NEG_INF;
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const float sv = st[qt][kt][v];
-                    const float p = sv == SQ_NEG_INF ? 0.0f : __expf(sv - m_new);
-                    pv[kt * 4 + v] = p;
-                    psum += p;
+                for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const bool ok = (vis[qt] >> (kt * 4 + v)) & 1u;
+                        const float sv = ok ? sacc[qt][kt][v] * c2 : SQ_NEG_INF;
+                        sacc[qt][kt][v] = sv;
+                        mx = fmaxf(mx, sv);
+                    }
+                mx = cross16_max(mx);                       // the 4 lane groups hold the other keys of the column
+                const float m_new = fmaxf(m_run[qt], mx);
+                const float m_use = m_new == SQ_NEG_INF ? 0.0f : m_new;    // all masked so far: exp2(-inf - 0) = 0
+                const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_use);
+                float psum = 0.0f;
+                float pvv[16];
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const float pe = __builtin_amdgcn_exp2f(sacc[qt][e >> 2][e & 3] - m_use);
+                    pvv[e] = pe;
+                    psum += pe;
                 }
-            m_run[qt] = m_new;
-            l_run[qt] = l_run[qt] * alpha + psum;           // per-lane partial; groups are summed at the end
+                m_run[qt] = m_new;
+                l_run[qt] = l_run[qt] * alpha + psum;       // per-lane partial; groups are summed at the end
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt) o[qt][dt] *= alpha;
+                for (int dt = 0; dt < 8; ++dt) o[qt][dt] *= alpha;
 #pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                h8 bv;
+                for (int ks = 0; ks < 2; ++ks) {
+                    h8 bv;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    bv[j] = (_Float16)pv[(2 * ks) * 4 + j];
-                    bv[4 + j] = (_Float16)pv[(2 * ks + 1) * 4 + j];
+                    for (int j = 0; j < 4; ++j) {
+                        bv[j] = (_Float16)pvv[(2 * ks) * 4 + j];
+                        bv[4 + j] = (_Float16)pvv[(2 * ks + 1) * 4 + j];
+                    }
+                    bp[qt][ks] = bv;
                 }
-                bp[qt][ks] = bv;
+            }
+
+            // ---- O^T += V^T P^T ------------------------------------------------------------------------------
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) {
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) {
+                    const h8 a = *reinterpret_cast<const h8 *>(st.Vt + (dt * 16 + col) * PF_VT_STRIDE + ks * 32 + kg * 8);
+#pragma unroll
+                    for (int qt = 0; qt < QT; ++qt)
+                        o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bp[qt][ks], o[qt][dt], 0, 0, 0);
+                }
             }
         }
 
-        // ---- O^T += V^T P^T --------------------------------------------------------------------------------
-#pragma unroll
-        for (int dt = 0; dt < 8; ++dt) {
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                const h8 a = *reinterpret_cast<const h8 *>(s_Vt + (dt * 16 + col) * PF_VT_STRIDE + ks * 32 + kg * 8);
-#pragma unroll
-                for (int qt = 0; qt < QT; ++qt)
-                    o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bp[qt][ks], o[qt][dt], 0, 0, 0);
-            }
+        // ---- next block: registers -> the other LDS buffer; one barrier per block --------------------------
+        if (blk + 1 < nblk) {
+            commit(blk + 1, stage[(blk + 1) & 1]);
+            info_cur = pinfo;
         }
+        __syncthreads();
     }
 
     // ---- normalise and store: lane holds query column nq[qt], dims dt*16 + kg*4 + v ---------------------------
@@ -274,23 +348,35 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(
             for (int v = 0; v < 4; ++v) hv[v] = (_Float16)(o[qt][dt][v] * inv);
             *reinterpret_cast<h4 *>(orow + dt * 16 + kg * 4) = hv;
         }
-        if (lse && kg == 0) lse[row0 + nq[qt]] = empty ? SQ_NEG_INF : m_run[qt] + logf(lt);
+        // m_run is in log2 units: lse = m * ln 2 + ln l
+        if (lse && kg == 0) lse[row0 + nq[qt]] = empty ? SQ_NEG_INF : m_run[qt] * 0.69314718055994531f + logf(lt);
     }
 }
 
 hipError_t launch_prefill_attn(const void *q, const void *Kf, const void *Vf, const void *Ku, const void *Vu,
-                               const uint32_t *keep_mask, const int32_t *offsets, int32_t *key_cid, void *out,
-                               float *lse, const Shape &sh, hipStream_t s)
+                               const uint32_t *keep_mask, const int32_t *offsets, int32_t *key_cid, int32_t *blk_info,
+                               void *out, float *lse, const Shape &sh, hipStream_t s)
 {
+    const int nblk = (sh.L + PF_BN - 1) / PF_BN;
     hipLaunchKernelGGL(key_cluster_kernel, dim3(64, sh.H), dim3(256), 0, s, offsets, key_cid, sh.C, sh.L);
+    hipLaunchKernelGGL(block_info_kernel, dim3((nblk + 255) / 256, sh.H), dim3(256), 0, s, key_cid, blk_info, sh.C,
+                       sh.L, nblk);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    constexpr int QT = 1;
-    dim3 grid((sh.Lq + 64 * QT - 1) / (64 * QT), sh.H, sh.B);
+    const size_t smem = 2 * sizeof(PfStage);
+    static bool attr_set = false;   // one GPU per process in this build
+    if (!attr_set) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(prefill_attn_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int units = ((sh.Lq + PF_BM - 1) / PF_BM) * sh.H * sh.B;
+    dim3 grid((units + 7) / 8 * 8);
     const bool prof = profile_mark(s, true);
-    hipLaunchKernelGGL(prefill_attn_kernel<QT>, grid, dim3(256), 0, s, (const _Float16 *)q, (const _Float16 *)Kf,
-                       (const _Float16 *)Vf, (const _Float16 *)Ku, (const _Float16 *)Vu, keep_mask, key_cid,
-                       (_Float16 *)out, lse, sh.H, sh.L, sh.C, sh.Lq, sh.U, sh.causal_user, sh.sm_scale);
+    hipLaunchKernelGGL(prefill_attn_kernel, grid, dim3(256), smem, s, (const _Float16 *)q, (const _Float16 *)Kf,
+                       (const _Float16 *)Vf, (const _Float16 *)Ku, (const _Float16 *)Vu, keep_mask, key_cid, blk_info,
+                       (_Float16 *)out, lse, sh.B, sh.H, sh.L, sh.C, sh.Lq, sh.U, sh.causal_user, sh.sm_scale);
     if (prof) profile_mark(s, false);
     return hipGetLastError();
 }
