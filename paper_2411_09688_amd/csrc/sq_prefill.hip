@@ -14,8 +14,9 @@
 //   * O^T = V^T P^T uses A = V^T tiles read from an LDS copy of V that was transposed on the way in, with
 //     the keys of each 32-key group permuted so that the eight keys a lane needs are 16 contiguous bytes;
 //   * the per-query keep masks are applied per (query, key): a small pre-kernel expands the cluster offsets
-//     into a key -> cluster map, each key block brings the (at most three) mask words that can cover its
-//     clusters for every query of the workgroup, and a wave skips the products of a block none of its
+//     into a key -> cluster map, each key block brings, for every query of the workgroup, the window of mask
+//     bits that covers its clusters, the bit of a (query, key) pair is moved to the sign with one shift and
+//     blended into the score with one bit-select, and a wave skips the products of a block none of its
 //     queries kept.
 // The user block is causal when causal_user is set (query t sees user keys 0..t); the fixed context is
 // always fully visible.
@@ -40,8 +41,9 @@ __global__ __launch_bounds__(256) void key_cluster_kernel(const int32_t *__restr
     }
 }
 
-// Per 64-key block: first mask word its clusters can touch, and whether they span more than three words
-// (possible only across runs of empty clusters).  blk_info[h, blk] = (w0 << 1) | wide.
+// Per 64-key block of the fixed context: the cluster of its first key, how many cluster ids it spans, and
+// whether that span fits the 31-bit window of mask bits staged per query (it always does unless the block
+// crosses a long run of empty clusters).  blk_info[h, blk] = first | span << 16 | wide << 31.
 __global__ __launch_bounds__(256) void block_info_kernel(const int32_t *__restrict__ cid, int32_t *__restrict__ blk_info,
                                                          int C, int L, int nblk)
 {
@@ -50,7 +52,8 @@ __global__ __launch_bounds__(256) void block_info_kernel(const int32_t *__restri
     if (blk >= nblk) return;
     const int first = min(cid[(size_t)h * L + blk * PF_BN], C - 1);
     const int last = min(cid[(size_t)h * L + min(L, (blk + 1) * PF_BN) - 1], C - 1);
-    blk_info[(size_t)h * nblk + blk] = ((first >> 5) << 1) | (((last >> 5) - (first >> 5)) > 2 ? 1 : 0);
+    const int span = last - first;
+    blk_info[(size_t)h * nblk + blk] = first | (min(span, 30) << 16) | (span >= 31 ? (int)0x80000000 : 0);
 }
 
 // Position of key kappa (0..63) of a block inside a V^T row: within each 32-key group, key (t*16 + g*4 + j)
@@ -63,14 +66,20 @@ __device__ __forceinline__ int vt_pos(int kappa)
 
 constexpr int PF_QT = 2;                  // 16-query tiles per wave
 constexpr int PF_BM = 64 * PF_QT;         // queries per workgroup (4 waves)
-constexpr int PF_MW = PF_BM * 3;          // mask words staged per block
 
 struct PfStage {                          // one LDS buffer of a key block
     _Float16 K[PF_BN * PF_KS_STRIDE];
     _Float16 Vt[D * PF_VT_STRIDE];
-    int cid[PF_BN];
-    uint32_t mw[PF_BM * 4];
+    int cid[PF_BN];                       // cluster of each key (0x7fffffff past the end)
+    int sh[PF_BN];                        // 31 - (cluster - first cluster of the block); 0 for keys past the end
+    uint32_t qbits[PF_BM];                // per query: mask bits of clusters first .. first+30, bit 31 clear
 };
+
+// (mask & a) | (~mask & b) on the bit patterns of floats: one v_bfi_b32.
+__device__ __forceinline__ float select_bits(uint32_t mask, float a, float b)
+{
+    return __builtin_bit_cast(float, (mask & __builtin_bit_cast(uint32_t, a)) | (~mask & __builtin_bit_cast(uint32_t, b)));
+}
 
 __global__ __launch_bounds__(256) void prefill_attn_kernel(
     const _Float16 *__restrict__ q, const _Float16 *__restrict__ Kf, const _Float16 *__restrict__ Vf,
@@ -95,7 +104,7 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(
     const int q0 = (unit % nqb) * BM;                     // first query of the workgroup
     const int W = (C + 31) >> 5;
     const size_t row0 = ((size_t)b * H + h) * Lq;         // query-row index of query 0 of this (b, h)
-    const float c2 = sm_scale * 1.44269504088896341f;     // scores are kept in units of log2(e): exp2 below
+    const float c2 = sm_scale * 1.44269504088896341f;     // exp(sm_scale * s) = exp2(c2 * s)
 
     // Queries of this lane: n[qt] = q0 + wave*16*QT + qt*16 + col; B operand of S^T = K Q^T.
     h8 bq[QT][4];
@@ -109,7 +118,7 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(
         for (int s = 0; s < 4; ++s) bq[qt][s] = qp[s * 4 + kg];
     }
 
-    float m_run[QT], l_run[QT];
+    float m_run[QT], l_run[QT];                           // running max (raw logit units) and sum per query column
     f4 o[QT][8];
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
@@ -126,12 +135,15 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(
     const int u_vis = causal_user ? min(U, q0 + BM) : U;
     const int nblk = nblk_fixed + (u_vis + PF_BN - 1) / PF_BN;
     const int32_t *binfo = blk_info + (size_t)h * nblk_fixed;
+    const int32_t *cid_h = key_cid + (size_t)h * L;
+    // Mask row of the query this thread stages bits for (threads 0..BM-1).
+    const int my_q = q0 + tid;
+    const uint32_t *my_mrow = keep_mask + (row0 + min(my_q, Lq - 1)) * W;
 
     // Registers that carry the next block from global memory to LDS.
     h8 pk[4], pv[4];
-    int pcid = 0;
-    uint32_t pmw[2] = {0u, 0u};
-    int pinfo = 0;
+    int pcid = 0, pinfo = 0;
+    uint32_t pw_lo = 0u, pw_hi = 0u;
     auto fetch = [&](int blk) {           // issue the global loads of block `blk`
         const bool user = blk >= nblk_fixed;
         const int j0 = (user ? blk - nblk_fixed : blk) * PF_BN;
@@ -153,18 +165,15 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(
         }
         if (!user) {
             pinfo = binfo[blk];
-            if (tid < PF_BN) pcid = j0 + tid < L ? key_cid[(size_t)h * L + j0 + tid] : 0x7fffffff;
-            const int w0 = pinfo >> 1;
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const int t = tid + u * 256;
-                const int ql = t / 3, wi = t - ql * 3;
-                const int n = min(q0 + ql, Lq - 1);
-                pmw[u] = (t < PF_MW && w0 + wi < W) ? keep_mask[(row0 + n) * W + w0 + wi] : 0u;
+            if (tid < PF_BN) pcid = j0 + tid < L ? cid_h[j0 + tid] : 0x7fffffff;
+            if (tid < BM) {
+                const int w0 = (pinfo & 0xffff) >> 5;
+                pw_lo = my_mrow[w0];
+                pw_hi = w0 + 1 < W ? my_mrow[w0 + 1] : 0u;
             }
         }
     };
-    auto commit = [&](int blk, PfStage &st) {   // registers -> LDS (K rows, V transposed, ids, mask words)
+    auto commit = [&](int blk, PfStage &st) {   // registers -> LDS (K rows, V transposed, ids, mask bits)
         const bool user = blk >= nblk_fixed;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -179,14 +188,14 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(
                 for (int e = 0; e < 8; ++e) st.Vt[((wave * 4 + i) * 8 + e) * PF_VT_STRIDE + pos] = pv[i][e];
         }
         if (!user) {
-            if (tid < PF_BN) st.cid[tid] = pcid;
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const int t = tid + u * 256;
-                if (t < PF_MW) {
-                    const int ql = t / 3;
-                    st.mw[ql * 4 + (t - ql * 3)] = pmw[u];
-                }
+            const int first = pinfo & 0xffff;
+            if (tid < PF_BN) {
+                st.cid[tid] = pcid;
+                st.sh[tid] = pcid == 0x7fffffff ? 0 : 31 - min(pcid - first, 31);
+            }
+            if (tid < BM) {
+                const unsigned long long two = ((unsigned long long)pw_hi << 32) | pw_lo;
+                st.qbits[tid] = my_q < Lq ? ((uint32_t)(two >> (first & 31)) & 0x7fffffffu) : 0u;
             }
         }
     };
@@ -204,52 +213,54 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(
         const int info = info_cur;
         if (blk + 1 < nblk) fetch(blk + 1);                 // global loads of the next block run under this one
 
-        // ---- visibility of this lane's (query, key) pairs --------------------------------------------------
-        // vis[qt] bit (kt*4 + v): key kt*16 + kg*4 + v of the block is visible to query nq[qt].
-        uint32_t vis[QT];
-        bool any = false;
-        if (!user) {
-            const int w0 = info >> 1;
-            const bool wide = info & 1;                     // workgroup-uniform, rare
-            int cc[16];
+        // ---- visibility of this lane's (query, key) pairs: msk = all ones (visible) or zero ------------------
+        // element e = kt*4 + v  <->  key kt*16 + kg*4 + v of the block, query nq[qt].
+        uint32_t msk[QT][16];
+        bool any;
+        if (!user && info >= 0) {
+            // Fixed context, usual case: bit (cluster - first) of the query's staged window, moved to the sign.
+            const uint32_t present = (2u << ((info >> 16) & 31)) - 1u;       // local clusters that occur in the block
+            int sh[16];
 #pragma unroll
             for (int kt = 0; kt < 4; ++kt) {
-                const int4 c4 = *reinterpret_cast<const int4 *>(st.cid + kt * 16 + kg * 4);
-                cc[kt * 4 + 0] = c4.x;
-                cc[kt * 4 + 1] = c4.y;
-                cc[kt * 4 + 2] = c4.z;
-                cc[kt * 4 + 3] = c4.w;
+                const int4 s4 = *reinterpret_cast<const int4 *>(st.sh + kt * 16 + kg * 4);
+                sh[kt * 4 + 0] = s4.x;
+                sh[kt * 4 + 1] = s4.y;
+                sh[kt * 4 + 2] = s4.z;
+                sh[kt * 4 + 3] = s4.w;
             }
+            any = false;
 #pragma unroll
             for (int qt = 0; qt < QT; ++qt) {
-                const uint4 mw = *reinterpret_cast<const uint4 *>(st.mw + (wave * 16 * QT + qt * 16 + col) * 4);
+                const uint32_t qb = st.qbits[wave * 16 * QT + qt * 16 + col];
+                any |= (qb & present) != 0u;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) msk[qt][e] = (uint32_t)((int)(qb << sh[e]) >> 31);
+            }
+        } else if (!user) {
+            // Fixed context, block spanning more than 31 cluster ids: look every bit up in the mask itself.
+            any = false;
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt) {
                 const uint32_t *mrow = keep_mask + (row0 + min(nq[qt], Lq - 1)) * W;
-                uint32_t bits = 0;
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    const int wi = (cc[e] >> 5) - w0;          // 0..2 for real keys, huge for padding
-                    uint32_t word = wi == 0 ? mw.x : (wi == 1 ? mw.y : (wi == 2 ? mw.z : 0u));
-                    if (wide && cc[e] < C) word = mrow[cc[e] >> 5];   // block spans > 3 mask words
-                    bits |= ((word >> (cc[e] & 31)) & 1u) << e;
+                    const int c = st.cid[(e >> 2) * 16 + kg * 4 + (e & 3)];
+                    const bool ok = c < C && nq[qt] < Lq && ((mrow[c >> 5] >> (c & 31)) & 1u);
+                    msk[qt][e] = ok ? 0xffffffffu : 0u;
+                    any |= ok;
                 }
-                vis[qt] = nq[qt] < Lq ? bits : 0u;
-                any |= vis[qt] != 0;
             }
         } else {
+            any = !causal_user || j0 <= q0 + wave * 16 * QT + 16 * QT - 1;
 #pragma unroll
-            for (int qt = 0; qt < QT; ++qt) {
-                uint32_t bits = 0;
+            for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
-                for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int j = j0 + kt * 16 + kg * 4 + v;
-                        const bool ok = j < U && (!causal_user || j <= nq[qt]);
-                        bits |= (ok ? 1u : 0u) << (kt * 4 + v);
-                    }
-                vis[qt] = nq[qt] < Lq ? bits : 0u;
-                any |= vis[qt] != 0;
-            }
+                for (int e = 0; e < 16; ++e) {
+                    const int j = j0 + (e >> 2) * 16 + kg * 4 + (e & 3);
+                    const bool ok = j < U && nq[qt] < Lq && (!causal_user || j <= nq[qt]);
+                    msk[qt][e] = ok ? 0xffffffffu : 0u;
+                }
         }
 
         if (__ballot(any) != 0ull) {                        // else: none of this wave's queries sees the block
@@ -270,43 +281,40 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(
                 }
             }
 
-            // ---- online softmax per query column (base 2); P^T packed as the B operand of the next product -----
+            // ---- online softmax per query column; P^T packed as the B operand of the next product ------------
             h8 bp[QT][2];
 #pragma unroll
             for (int qt = 0; qt < QT; ++qt) {
+                float sv[16];
                 float mx = SQ_NEG_INF;
 #pragma unroll
-                for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const bool ok = (vis[qt] >> (kt * 4 + v)) & 1u;
-                        const float sv = ok ? sacc[qt][kt][v] * c2 : SQ_NEG_INF;
-                        sacc[qt][kt][v] = sv;
-                        mx = fmaxf(mx, sv);
-                    }
+                for (int e = 0; e < 16; ++e) {
+                    sv[e] = select_bits(msk[qt][e], sacc[qt][e >> 2][e & 3], SQ_NEG_INF);
+                    mx = fmaxf(mx, sv[e]);
+                }
                 mx = cross16_max(mx);                       // the 4 lane groups hold the other keys of the column
                 const float m_new = fmaxf(m_run[qt], mx);
-                const float m_use = m_new == SQ_NEG_INF ? 0.0f : m_new;    // all masked so far: exp2(-inf - 0) = 0
-                const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_use);
+                const float mneg = m_new == SQ_NEG_INF ? 0.0f : -m_new * c2;   // nothing seen yet: exp2(-inf) = 0
+                const float alpha = __builtin_amdgcn_exp2f(fmaf(m_run[qt], c2, mneg));
                 float psum = 0.0f;
-                float pvv[16];
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    const float pe = __builtin_amdgcn_exp2f(sacc[qt][e >> 2][e & 3] - m_use);
-                    pvv[e] = pe;
-                    psum += pe;
+                    sv[e] = __builtin_amdgcn_exp2f(fmaf(sv[e], c2, mneg));
+                    psum += sv[e];
                 }
                 m_run[qt] = m_new;
                 l_run[qt] = l_run[qt] * alpha + psum;       // per-lane partial; groups are summed at the end
+                if (__ballot(alpha != 1.0f) != 0ull) {      // the maximum rarely moves once a strong key is seen
 #pragma unroll
-                for (int dt = 0; dt < 8; ++dt) o[qt][dt] *= alpha;
+                    for (int dt = 0; dt < 8; ++dt) o[qt][dt] *= alpha;
+                }
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
                     h8 bv;
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        bv[j] = (_Float16)pvv[(2 * ks) * 4 + j];
-                        bv[4 + j] = (_Float16)pvv[(2 * ks + 1) * 4 + j];
+                        bv[j] = (_Float16)sv[(2 * ks) * 4 + j];
+                        bv[4 + j] = (_Float16)sv[(2 * ks + 1) * 4 + j];
                     }
                     bp[qt][ks] = bv;
                 }
@@ -348,8 +356,7 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(
             for (int v = 0; v < 4; ++v) hv[v] = (_Float16)(o[qt][dt][v] * inv);
             *reinterpret_cast<h4 *>(orow + dt * 16 + kg * 4) = hv;
         }
-        // m_run is in log2 units: lse = m * ln 2 + ln l
-        if (lse && kg == 0) lse[row0 + nq[qt]] = empty ? SQ_NEG_INF : m_run[qt] * 0.69314718055994531f + logf(lt);
+        if (lse && kg == 0) lse[row0 + nq[qt]] = empty ? SQ_NEG_INF : m_run[qt] * sm_scale + logf(lt);
     }
 }
 
