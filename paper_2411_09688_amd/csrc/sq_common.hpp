@@ -143,24 +143,26 @@ __device__ __forceinline__ void wave_row_stats(const float *x, const int32_t *N,
             if (nv[u] > 0) m = fmaxf(m, xv[u]);
     }
     m = wave_max(m);
-    float Dsum = 0.0f;
-    for (int grp = 0; grp < 16; ++grp) {
-        float local = 0.0f;
-        for (int i0 = grp * 64 + lane; i0 < n; i0 += 1024 * 4) {     // four loads in flight
-            float xv[4];
-            int nv[4];
+    // One accumulator per group; a pass over 1024 clusters issues its 16 loads together.
+    float loc[16];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int i = i0 + u * 1024;
-                nv[u] = i < n ? N[i] : 0;
-                xv[u] = i < n ? x[i] : 0.0f;
-            }
+    for (int g = 0; g < 16; ++g) loc[g] = 0.0f;
+    for (int i0 = 0; i0 < n; i0 += 1024) {
+        float xv[16];
+        int nv[16];
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
-                if (nv[u] > 0) local += (float)nv[u] * expf(xv[u] - m);
+        for (int g = 0; g < 16; ++g) {
+            const int i = i0 + g * 64 + lane;
+            nv[g] = i < n ? N[i] : 0;
+            xv[g] = i < n ? x[i] : 0.0f;
         }
-        Dsum += wave_sum(local);
+#pragma unroll
+        for (int g = 0; g < 16; ++g)
+            if (nv[g] > 0) loc[g] += (float)nv[g] * expf(xv[g] - m);
     }
+    float Dsum = 0.0f;
+#pragma unroll
+    for (int g = 0; g < 16; ++g) Dsum += wave_sum(loc[g]);
     m_out = m;
     D_out = Dsum;
 }

@@ -64,7 +64,7 @@ __device__ __forceinline__ int vt_pos(int kappa)
     return ks * 32 + g * 8 + t * 4 + j;
 }
 
-constexpr int PF_QT = 2;                  // 16-query tiles per wave
+constexpr int PF_QT = 1;                  // 16-query tiles per wave
 constexpr int PF_BM = 64 * PF_QT;         // queries per workgroup (4 waves)
 
 struct PfStage {                          // one LDS buffer of a key block
@@ -180,6 +180,7 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(
             const int key = i * 16 + (tid >> 4), chunk = tid & 15;
             *reinterpret_cast<h8 *>(st.K + key * PF_KS_STRIDE + chunk * 8) = pk[i];
         }
+#ifndef SQX_NO_VT
         {
             const int pos = vt_pos(lane);
 #pragma unroll
@@ -187,6 +188,9 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(
 #pragma unroll
                 for (int e = 0; e < 8; ++e) st.Vt[((wave * 4 + i) * 8 + e) * PF_VT_STRIDE + pos] = pv[i][e];
         }
+#else
+        if (blk < 0) st.Vt[tid] = pv[0][0] + pv[1][1] + pv[2][2] + pv[3][3];
+#endif
         if (!user) {
             const int first = pinfo & 0xffff;
             if (tid < PF_BN) {
@@ -211,7 +215,9 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(
         const bool user = blk >= nblk_fixed;
         const int j0 = (user ? blk - nblk_fixed : blk) * PF_BN;
         const int info = info_cur;
+#ifndef SQX_NO_FETCH
         if (blk + 1 < nblk) fetch(blk + 1);                 // global loads of the next block run under this one
+#endif
 
         // ---- visibility of this lane's (query, key) pairs: msk = all ones (visible) or zero ------------------
         // element e = kt*4 + v  <->  key kt*16 + kg*4 + v of the block, query nq[qt].
@@ -235,7 +241,11 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(
                 const uint32_t qb = st.qbits[wave * 16 * QT + qt * 16 + col];
                 any |= (qb & present) != 0u;
 #pragma unroll
+#ifndef SQX_NO_MASK
                 for (int e = 0; e < 16; ++e) msk[qt][e] = (uint32_t)((int)(qb << sh[e]) >> 31);
+#else
+                for (int e = 0; e < 16; ++e) msk[qt][e] = qb | 0xffffffffu | (uint32_t)sh[0];
+#endif
             }
         } else if (!user) {
             // Fixed context, block spanning more than 31 cluster ids: look every bit up in the mask itself.
@@ -299,7 +309,11 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(
                 float psum = 0.0f;
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
+#ifndef SQX_NO_EXP
                     sv[e] = __builtin_amdgcn_exp2f(fmaf(sv[e], c2, mneg));
+#else
+                    sv[e] = fmaf(sv[e], c2, mneg);
+#endif
                     psum += sv[e];
                 }
                 m_run[qt] = m_new;

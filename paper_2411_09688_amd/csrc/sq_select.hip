@@ -309,6 +309,65 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     }
 }
 
+// Mask-only selection, one wave per query row and no LDS: the form prefill uses, where tens of thousands
+// of rows each need only their keep mask and counts (no ranges).  Same keep rule, same statistics.
+template <bool STATS_IN>
+__global__ __launch_bounds__(256) void select_mask_kernel(const float *__restrict__ logits,
+                                                          const float *__restrict__ row_max,
+                                                          const float *__restrict__ denom,
+                                                          const float *__restrict__ thresh,
+                                                          const int32_t *__restrict__ sizes,
+                                                          uint32_t *__restrict__ keep_mask,
+                                                          int32_t *__restrict__ n_ranges, int32_t *__restrict__ n_keys,
+                                                          int rows, int H, int Lq, int C)
+{
+    const int lane = threadIdx.x & 63;
+    const size_t row = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= (size_t)rows) return;
+    const int h = (int)((row / Lq) % H);
+    const float *x = logits + row * C;
+    const int32_t *N = sizes + (size_t)h * C;
+    const int W = (C + 31) >> 5;
+    float m, Dsum;
+    if (STATS_IN) {
+        m = row_max[row];
+        Dsum = denom[row];
+    } else {
+        wave_row_stats(x, N, C, lane, m, Dsum);
+    }
+    const float thr = thresh[h] * Dsum;
+    int cnt = 0, keys = 0;
+    for (int i0 = 0; i0 < C; i0 += 64 * 4) {                 // four loads in flight
+        float xv[4];
+        int nv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = i0 + u * 64 + lane;
+            nv[u] = i < C ? N[i] : 0;
+            xv[u] = i < C ? x[i] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = i0 + u * 64;                       // first cluster of this 64-wide step
+            if (i >= C) break;
+            const bool keep = nv[u] > 0 && expf(xv[u] - m) > thr;
+            const unsigned long long bal = __ballot(keep);
+            if (lane == 0) {
+                const int w0 = i >> 5;
+                keep_mask[row * W + w0] = (uint32_t)bal;
+                if (w0 + 1 < W) keep_mask[row * W + w0 + 1] = (uint32_t)(bal >> 32);
+            }
+            cnt += __popcll(bal);
+            keys += keep ? nv[u] : 0;
+        }
+    }
+    keys = wave_sum_i(keys);
+    if (lane == 0) {
+        n_ranges[row] = cnt;
+        n_keys[row] = keys;
+    }
+}
+
 // Caller-provided ranges -> records (start, count, keys before) + header.  Empty ranges are dropped.
 __global__ __launch_bounds__(256) void ranges_to_rec_kernel(const int32_t *__restrict__ ranges,
                                                             const int32_t *__restrict__ n_ranges, DecodePlan plan,
@@ -375,6 +434,16 @@ hipError_t launch_select(const float *logits, const float *row_max, const float 
                          int32_t *ranges, int32_t *n_ranges, int32_t *n_keys, DecodePlan plan, bool schedule, int U,
                          SelectOpts opt, int rows, int H, int Lq, int C, hipStream_t s)
 {
+    if (!ranges && !plan.rec && !schedule && !opt.parent_mask && !opt.len_from_offsets && keep_mask) {
+        // mask and counts only (prefill): one wave per row
+        if (stats_in)
+            hipLaunchKernelGGL(select_mask_kernel<true>, dim3((rows + 3) / 4), dim3(256), 0, s, logits, row_max, denom,
+                               thresh, sizes, keep_mask, n_ranges, n_keys, rows, H, Lq, C);
+        else
+            hipLaunchKernelGGL(select_mask_kernel<false>, dim3((rows + 3) / 4), dim3(256), 0, s, logits, row_max, denom,
+                               thresh, sizes, keep_mask, n_ranges, n_keys, rows, H, Lq, C);
+        return hipGetLastError();
+    }
     // LDS: logits + sizes of the row (+ parent offsets); reused for two ints per chunk when scheduling.
     size_t smem = (size_t)C * 8 + (opt.parent_mask ? (size_t)(opt.C1 + 1) * 4 : 0);
     if (schedule && (size_t)chunk_cap_for(plan.L) * 8 > smem) smem = (size_t)chunk_cap_for(plan.L) * 8;
