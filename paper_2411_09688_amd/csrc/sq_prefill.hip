@@ -3,7 +3,7 @@
 //
 // Layout of the computation (FlashAttention-2 style: grid over heads x query blocks, loop over key blocks,
 // online softmax), written for CDNA4 matrix cores:
-//   * a workgroup = 4 waves x 32 queries; all waves walk the same 64-key blocks, whose K tile and transposed
+//   * a workgroup = 4 waves x 16 queries (two workgroups per compute unit); all waves walk the same 64-key blocks, whose K tile and transposed
 //     V tile are staged in LDS once per workgroup (two LDS buffers; the next block's global loads are issued
 //     before the current block's arithmetic and land in registers meanwhile);
 //   * scores are computed TRANSPOSED, S^T = K Q^T, with 16x16x32 fp16 MFMA tiles (A = 16 keys, B = 16
@@ -81,7 +81,7 @@ __device__ __forceinline__ float select_bits(uint32_t mask, float a, float b)
     return __builtin_bit_cast(float, (mask & __builtin_bit_cast(uint32_t, a)) | (~mask & __builtin_bit_cast(uint32_t, b)));
 }
 
-__global__ __launch_bounds__(256) void prefill_attn_kernel(
+__global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
     const _Float16 *__restrict__ q, const _Float16 *__restrict__ Kf, const _Float16 *__restrict__ Vf,
     const _Float16 *__restrict__ Ku, const _Float16 *__restrict__ Vu, const uint32_t *__restrict__ keep_mask,
     const int32_t *__restrict__ key_cid, const int32_t *__restrict__ blk_info, _Float16 *__restrict__ out,
@@ -144,24 +144,32 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(
     h8 pk[4], pv[4];
     int pcid = 0, pinfo = 0;
     uint32_t pw_lo = 0u, pw_hi = 0u;
+    // Byte offsets of this thread's pieces inside a 64-key block (rows of 256 B): K piece i = key
+    // i*16 + tid/16, 16-byte chunk tid%16; V = key `lane`, four chunks starting at wave*4.
+    const uint32_t k_off = (uint32_t)(tid >> 4) * 256u + (uint32_t)(tid & 15) * 16u;
+    const uint32_t v_off = (uint32_t)lane * 256u + (uint32_t)wave * 64u;
     auto fetch = [&](int blk) {           // issue the global loads of block `blk`
         const bool user = blk >= nblk_fixed;
         const int j0 = (user ? blk - nblk_fixed : blk) * PF_BN;
         const int nkeys = user ? U : L;
-        const _Float16 *Kb = user ? Kuh : Kfh, *Vb = user ? Vuh : Vfh;
+        const char *Kb = reinterpret_cast<const char *>(user ? Kuh : Kfh) + (size_t)j0 * 256;
+        const char *Vb = reinterpret_cast<const char *>(user ? Vuh : Vfh) + (size_t)j0 * 256;
+        if (j0 + PF_BN <= nkeys) {        // full block: uniform base + 32-bit per-thread offsets
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int key = i * 16 + (tid >> 4), chunk = tid & 15;
-            const int j = min(j0 + key, nkeys - 1);
-            pk[i] = *reinterpret_cast<const h8 *>(Kb + (size_t)j * D + chunk * 8);
-        }
-        {
-            // V: a lane takes ONE key and four 8-dim chunks (wave w: dims 32w .. 32w+31), so that the
-            // transposed LDS stores of a wave go to 64 different keys of one V^T row (no bank conflicts).
-            const int j = min(j0 + lane, nkeys - 1);
+            for (int i = 0; i < 4; ++i) pk[i] = *reinterpret_cast<const h8 *>(Kb + (k_off + (uint32_t)i * 4096u));
+#pragma unroll
+            for (int i = 0; i < 4; ++i) pv[i] = *reinterpret_cast<const h8 *>(Vb + (v_off + (uint32_t)i * 16u));
+        } else {                          // last block of a tensor: rows past the end re-read the last row
+            const int last = nkeys - 1 - j0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int key = min(i * 16 + (tid >> 4), last);
+                pk[i] = *reinterpret_cast<const h8 *>(Kb + (uint32_t)key * 256u + (uint32_t)(tid & 15) * 16u);
+            }
+            const int keyv = min(lane, last);
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                pv[i] = *reinterpret_cast<const h8 *>(Vb + (size_t)j * D + (wave * 4 + i) * 8);
+                pv[i] = *reinterpret_cast<const h8 *>(Vb + (uint32_t)keyv * 256u + (uint32_t)(wave * 4 + i) * 16u);
         }
         if (!user) {
             pinfo = binfo[blk];
@@ -180,7 +188,6 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(
             const int key = i * 16 + (tid >> 4), chunk = tid & 15;
             *reinterpret_cast<h8 *>(st.K + key * PF_KS_STRIDE + chunk * 8) = pk[i];
         }
-#ifndef SQX_NO_VT
         {
             const int pos = vt_pos(lane);
 #pragma unroll
@@ -188,9 +195,6 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(
 #pragma unroll
                 for (int e = 0; e < 8; ++e) st.Vt[((wave * 4 + i) * 8 + e) * PF_VT_STRIDE + pos] = pv[i][e];
         }
-#else
-        if (blk < 0) st.Vt[tid] = pv[0][0] + pv[1][1] + pv[2][2] + pv[3][3];
-#endif
         if (!user) {
             const int first = pinfo & 0xffff;
             if (tid < PF_BN) {
@@ -215,9 +219,7 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(
         const bool user = blk >= nblk_fixed;
         const int j0 = (user ? blk - nblk_fixed : blk) * PF_BN;
         const int info = info_cur;
-#ifndef SQX_NO_FETCH
         if (blk + 1 < nblk) fetch(blk + 1);                 // global loads of the next block run under this one
-#endif
 
         // ---- visibility of this lane's (query, key) pairs: msk = all ones (visible) or zero ------------------
         // element e = kt*4 + v  <->  key kt*16 + kg*4 + v of the block, query nq[qt].
@@ -241,11 +243,7 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(
                 const uint32_t qb = st.qbits[wave * 16 * QT + qt * 16 + col];
                 any |= (qb & present) != 0u;
 #pragma unroll
-#ifndef SQX_NO_MASK
                 for (int e = 0; e < 16; ++e) msk[qt][e] = (uint32_t)((int)(qb << sh[e]) >> 31);
-#else
-                for (int e = 0; e < 16; ++e) msk[qt][e] = qb | 0xffffffffu | (uint32_t)sh[0];
-#endif
             }
         } else if (!user) {
             // Fixed context, block spanning more than 31 cluster ids: look every bit up in the mask itself.
@@ -309,11 +307,7 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(
                 float psum = 0.0f;
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-#ifndef SQX_NO_EXP
                     sv[e] = __builtin_amdgcn_exp2f(fmaf(sv[e], c2, mneg));
-#else
-                    sv[e] = fmaf(sv[e], c2, mneg);
-#endif
                     psum += sv[e];
                 }
                 m_run[qt] = m_new;
