@@ -304,6 +304,8 @@ def main():
     out = torch.zeros(NQ, w.B, w.H, 1, w.d, dtype=torch.float16, device=dev)
     lse = torch.zeros(NQ, w.B, w.H, 1, dtype=torch.float32, device=dev)
     nkeys = torch.zeros(NQ, w.B, w.H, 1, dtype=torch.int32, device=dev)
+    # keep-masks are only requested for a batch: they give the union of the sequences' selections
+    kmask = torch.zeros(NQ, w.B, w.H, 1, (w.C + 31) // 32, dtype=torch.int32, device=dev) if w.B > 1 else None
     shape = sq.make_shape(w.B, w.H, w.L, w.C, 1, w.U, w.sm_scale)
     ws = sq.workspace(shape, sq.SQ_CALL_DECODE_STEP, dev)
     if args.separate:
@@ -334,7 +336,8 @@ def main():
                  P(lse[qi]), *wsp(ws_a))))
         else:
             calls.append((sp, P(Q[qi]), P(Ce[r]), P(sizes), P(offsets), P(thresh), P(Kf[r]), P(Vf[r]), P(Ku[r]),
-                          P(Vu[r]), P(out[qi]), P(lse[qi]), None, P(nkeys[qi]), *wsp(ws)))
+                          P(Vu[r]), P(out[qi]), P(lse[qi]), P(kmask[qi]) if kmask is not None else None,
+                          P(nkeys[qi]), *wsp(ws)))
 
     def step(i, stream_ptr):
         a = calls[i % cycle]
@@ -355,6 +358,16 @@ def main():
     sel = float(np.mean([b["selected_kv"] for b in per_step]))
     cen = float(per_step[0]["centroid"])
     dense = float(per_step[0]["dense_kv"])
+    sel_requested = sel
+    if kmask is not None and not args.separate:
+        # The sequences of a batch share the fixed context: a key kept by several of them has to leave HBM
+        # once.  Unique selected bytes = keys of the union of the sequences' kept clusters, per head.
+        km = kmask.cpu().numpy()[:, :, :, 0, :].view(np.uint32)                      # [NQ, B, H, W]
+        union = np.bitwise_or.reduce(km, axis=1)                                        # [NQ, H, W]
+        bits = ((union[..., None] >> np.arange(32, dtype=np.uint32)) & 1).reshape(NQ, w.H, -1)[:, :, :w.C]
+        uniq_keys = (bits * w.sizes[None]).sum(axis=(1, 2))                            # [NQ]
+        sel = float(np.mean([uniq_keys[qi] for qi in used])) * w.d * 2 * 2
+        tot = tot - sel_requested + sel
     kernel_bytes = sel + dense + w.B * w.H * w.d * 2           # K/V rows read by the partial kernel + q
     keep = float(np.mean([nk[qi].mean() for qi in used]) / w.L)
     tokens = w.B
@@ -372,6 +385,7 @@ def main():
                    "keep_target": w.keep_frac, "keep_achieved": round(keep, 5), "queries": NQ, "replicas": R,
                    "entry": "3 calls" if args.separate else "sq_decode_step"},
         "bytes_per_step": {"total": round(tot), "centroid": round(cen), "selected_kv": round(sel),
+                           "selected_kv_requested": round(sel_requested),
                            "dense_kv": round(dense), "centroid_plus_selected_kv": round(cen + sel)},
         "hbm_frac_whole_step": round(tot / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         "roofline": {"bound": "hbm", "kernel": "decode_attn_kernel",

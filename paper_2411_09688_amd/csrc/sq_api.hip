@@ -101,14 +101,14 @@ DecodeWs carve_decode(Carver &cv, const sq_shape_t *sh)
 {
     const size_t rows = (size_t)sh->B * sh->H;
     const size_t items = rows * (sq::user_chunks_for(sh->U) + sq::chunk_cap_for(sh->L));
-    DecodeWs w;
+    DecodeWs w{};
     w.plan.rec_cap = sh->C;
     w.plan.L = sh->L;
     w.plan.item_cap = (int)items;
     w.plan.rec = cv.take<int4>(rows * sh->C);
     w.plan.hdr = cv.take<int2>(rows);
     w.plan.row_items = cv.take<int2>(rows);
-    w.plan.total = cv.take<int>(1);
+    w.plan.total = cv.take<int>(2);
     w.plan.item = cv.take<int2>(items * sq::ITEM_STRIDE);
     w.partials = cv.take<float>(items * sq::PART_STRIDE);
     return w;
@@ -124,13 +124,51 @@ struct StepWs {
 StepWs carve_step(Carver &cv, const sq_shape_t *sh)
 {
     const size_t rows = (size_t)sh->B * sh->H;
-    StepWs w;
+    StepWs w{};
     w.logits = cv.take<float>(rows * sh->C);
     w.n_ranges = cv.take<int32_t>(rows);
     w.n_keys = cv.take<int32_t>(rows);
     w.dec = carve_decode(cv, sh);
     return w;
 }
+
+// Workspace of a decode step over a shared context (B >= 2): per-sequence selection outputs, then the union
+// rows' plan and the partials of the shared-context kernel.
+struct SharedStepWs {
+    float *logits;
+    int32_t *n_ranges, *n_keys, *n_ranges_u, *n_keys_u;
+    uint32_t *mask;
+    sq::DecodePlan plan;
+    float *partials;
+};
+
+SharedStepWs carve_step_shared(Carver &cv, const sq_shape_t *sh)
+{
+    const size_t rows = (size_t)sh->B * sh->H;
+    const size_t urows = (size_t)sq::seq_groups_for(sh->B) * sh->H;
+    const size_t items = urows * ((size_t)sq::SG * sq::user_chunks_for(sh->U) + sq::chunk_cap_for(sh->L));
+    SharedStepWs w{};
+    w.logits = cv.take<float>(rows * sh->C);
+    w.n_ranges = cv.take<int32_t>(rows);
+    w.n_keys = cv.take<int32_t>(rows);
+    w.n_ranges_u = cv.take<int32_t>(urows);
+    w.n_keys_u = cv.take<int32_t>(urows);
+    w.mask = cv.take<uint32_t>(rows * ((sh->C + 31) / 32));
+    w.plan.rec_cap = sh->C;
+    w.plan.L = sh->L;
+    w.plan.item_cap = (int)items;
+    w.plan.rec = cv.take<int4>(urows * sh->C);
+    w.plan.hdr = cv.take<int2>(urows);
+    w.plan.row_items = cv.take<int2>(urows);
+    w.plan.row_rank = cv.take<int>(urows);
+    w.plan.total = cv.take<int>(2);
+    w.plan.item = cv.take<int2>(items * sq::ITEM_STRIDE);
+    w.partials = cv.take<float>(((size_t)sq::SHARED_ATTN_WAVES + urows) * sq::SG * sq::PART_STRIDE);
+    return w;
+}
+
+// A decode step with two or more sequences runs the shared-context kernels.
+bool step_is_shared(const sq_shape_t *sh) { return sh->B >= 2; }
 
 // Workspace of the two-level lookup.  C1 <= C2 is not known to sq_workspace_bytes, so level-1 buffers
 // are sized for C2.
@@ -144,7 +182,7 @@ HierWs carve_hier(Carver &cv, const sq_shape_t *sh)
 {
     const size_t rows = (size_t)sh->B * sh->H;
     const size_t items = rows * sq::chunk_cap_for(sh->C);
-    HierWs w;
+    HierWs w{};
     w.logits1 = cv.take<float>(rows * sh->C);
     w.logits2 = cv.take<float>(rows * sh->C);
     w.nr1 = cv.take<int32_t>(rows);
@@ -155,7 +193,7 @@ HierWs carve_hier(Carver &cv, const sq_shape_t *sh)
     w.cand.rec = cv.take<int4>(rows * sh->C);
     w.cand.hdr = cv.take<int2>(rows);
     w.cand.row_items = cv.take<int2>(rows);
-    w.cand.total = cv.take<int>(1);
+    w.cand.total = cv.take<int>(2);
     w.cand.item = cv.take<int2>(items * sq::ITEM_STRIDE);
     return w;
 }
@@ -170,7 +208,7 @@ struct HierStepWs {
 HierStepWs carve_hier_step(Carver &cv, const sq_shape_t *sh)
 {
     const size_t rows = (size_t)sh->B * sh->H;
-    HierStepWs w;
+    HierStepWs w{};
     w.hier = carve_hier(cv, sh);
     w.mask1 = cv.take<uint32_t>(rows * ((sh->C + 31) / 32));
     w.n_ranges = cv.take<int32_t>(rows);
@@ -211,7 +249,8 @@ size_t sq_workspace_bytes(const sq_shape_t *sh, int which)
         carve_decode(cv, sh);
         return cv.off;
     case SQ_CALL_DECODE_STEP:
-        carve_step(cv, sh);
+        if (step_is_shared(sh)) carve_step_shared(cv, sh);
+        else carve_step(cv, sh);
         return cv.off;
     case SQ_CALL_ATTN_PREFILL:
         cv.take<int32_t>((size_t)sh->H * sh->L);
@@ -324,8 +363,24 @@ int sq_decode_step(const sq_shape_t *sh, const void *q, const void *centroids, c
     if (int rc = check_device(__func__)) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     Carver cv(ws);
-    StepWs w = carve_step(cv, sh);
     const int rows = sh->B * sh->H;
+    if (step_is_shared(sh)) {
+        // Every sequence selects on its own; the work items are built from the union of the selections of each
+        // group of sequences, so a cluster kept by several sequences is streamed once.
+        SharedStepWs w = carve_step_shared(cv, sh);
+        uint32_t *mask = keep_mask ? keep_mask : w.mask;
+        SQ_HIP(sq::launch_score(q, centroids, w.logits, w.plan.total, sh->B, sh->H, 1, sh->C, sh->sm_scale, s));
+        SQ_HIP(sq::launch_select(w.logits, nullptr, nullptr, false, thresh, sizes, offsets, mask, nullptr, w.n_ranges,
+                                 n_keys ? n_keys : w.n_keys, sq::DecodePlan{}, false, 0, sq::SelectOpts{}, rows, sh->H,
+                                 1, sh->C, s));
+        SQ_HIP(sq::launch_union_schedule(mask, sizes, offsets, w.plan, w.n_ranges_u, w.n_keys_u, sh->U, sh->B, sh->H,
+                                         sh->C, s));
+        SQ_HIP(sq::launch_decode_attn_shared(q, K_fixed, V_fixed, K_user, V_user, w.plan, w.partials, out, lse,
+                                             to_shape(sh), s));
+        g_err[0] = 0;
+        return SQ_OK;
+    }
+    StepWs w = carve_step(cv, sh);
     int32_t *nk = n_keys ? n_keys : w.n_keys;
     SQ_HIP(sq::launch_score(q, centroids, w.logits, w.dec.plan.total, sh->B, sh->H, 1, sh->C, sh->sm_scale, s));
     SQ_HIP(sq::launch_select(w.logits, nullptr, nullptr, false, thresh, sizes, offsets, keep_mask, nullptr, w.n_ranges,

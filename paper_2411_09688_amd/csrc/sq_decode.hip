@@ -1,8 +1,8 @@
 // Decode-time sparse attention (Section 4.2): exact attention of one query per (sequence, head) over
 // the selected fixed-context keys plus the dense user keys, split along the key dimension into
-// chunks of KPC keys (the split-KV scheme: a head that keeps more keys gets more workgroups).  Each
-// chunk produces a partial (max, sum, output); the workgroup that finishes a row last merges the
-// row's partials (phase 2 of Section 4.2 without a second launch).
+// chunks of KPC keys (the split-KV scheme: a head that keeps more keys gets more workgroups).  A
+// workgroup folds the consecutive chunks it owns into one partial (max, sum, output) per row; a second
+// kernel merges the partials of every row (phase 2 of Section 4.2).
 //
 // The kernel is bound by HBM: every selected K and V row (256 B each) is read exactly once.  A
 // workgroup owns one chunk; its 256 threads fetch the chunk's range records with one coalesced load
@@ -14,80 +14,12 @@
 
 #include "sq_common.hpp"
 #include "sq_internal.hpp"
+#include "sq_merge.hpp"
 
 namespace sq {
 
 constexpr int KW = KPC / 4;     // keys per wave
 constexpr int NI = KW / 4;      // loads per lane (4 rows per wave-wide load)
-
-// Merge of n partials of one row by a 1024-thread workgroup:
-//   out = sum_c e^{m_c - M} o_c / sum_c e^{m_c - M} l_c,   lse = M + log(sum_c e^{m_c - M} l_c).
-// 32 groups of 32 threads; group g folds partials g, g+32, ... with a running maximum (a thread owns
-// four output dimensions, 16-byte loads, four partials in flight), then the groups are folded in LDS.
-constexpr int MERGE_THREADS = 1024;
-constexpr int MERGE_GROUPS = MERGE_THREADS / 32;
-// The row's partials sit at item indices `first` and every multiple of `k` inside (first, first + items):
-// partial c is at slot (c == 0 ? first : (first / k + c) * k), n of them.
-__device__ __forceinline__ void merge_row(const float *__restrict__ partials, int first, int k, int n,
-                                          _Float16 *__restrict__ out_row, float *lse_row,
-                                          float *s_red /*[MERGE_GROUPS * 130]*/, int tid)
-{
-    const int fk = first / k;
-    auto slot_ptr = [&](int c) { return partials + (size_t)(c == 0 ? first : (fk + c) * k) * PART_STRIDE; };
-    const int quad = tid & 31, grp = tid >> 5;
-    float M = SQ_NEG_INF, lsum = 0.0f;
-    f4 acc = {0.f, 0.f, 0.f, 0.f};
-    int c = grp;
-    for (; c + 3 * MERGE_GROUPS < n; c += 4 * MERGE_GROUPS) {
-        const float *p0 = slot_ptr(c), *p1 = slot_ptr(c + MERGE_GROUPS), *p2 = slot_ptr(c + 2 * MERGE_GROUPS),
-                    *p3 = slot_ptr(c + 3 * MERGE_GROUPS);
-        const float2 a0 = *reinterpret_cast<const float2 *>(p0), a1 = *reinterpret_cast<const float2 *>(p1),
-                     a2 = *reinterpret_cast<const float2 *>(p2), a3 = *reinterpret_cast<const float2 *>(p3);
-        const f4 o0 = *reinterpret_cast<const f4 *>(p0 + 4 + quad * 4), o1 = *reinterpret_cast<const f4 *>(p1 + 4 + quad * 4),
-                 o2 = *reinterpret_cast<const f4 *>(p2 + 4 + quad * 4), o3 = *reinterpret_cast<const f4 *>(p3 + 4 + quad * 4);
-        const float Mn = fmaxf(fmaxf(M, fmaxf(a0.x, a1.x)), fmaxf(a2.x, a3.x));
-        const float sc = __expf(M - Mn);                 // M = -inf on the first pass: scale 0
-        const float w0 = __expf(a0.x - Mn), w1 = __expf(a1.x - Mn), w2 = __expf(a2.x - Mn), w3 = __expf(a3.x - Mn);
-        acc = acc * sc + o0 * w0 + o1 * w1 + o2 * w2 + o3 * w3;
-        lsum = lsum * sc + a0.y * w0 + a1.y * w1 + a2.y * w2 + a3.y * w3;
-        M = Mn;
-    }
-    for (; c < n; c += MERGE_GROUPS) {
-        const float *p = slot_ptr(c);
-        const float2 a = *reinterpret_cast<const float2 *>(p);
-        const f4 o = *reinterpret_cast<const f4 *>(p + 4 + quad * 4);
-        const float Mn = fmaxf(M, a.x);
-        const float sc = __expf(M - Mn), w = __expf(a.x - Mn);
-        acc = acc * sc + o * w;
-        lsum = lsum * sc + a.y * w;
-        M = Mn;
-    }
-    // Fold the groups: s_red[g] = (M_g, l_g, o_g[128]).  A group that saw no partial has M_g = -inf.
-    float *mine = s_red + grp * 130;
-    if (quad == 0) {
-        mine[0] = M;
-        mine[1] = lsum;
-    }
-#pragma unroll
-    for (int e = 0; e < 4; ++e) mine[2 + quad * 4 + e] = acc[e];
-    __syncthreads();
-    if (tid < D) {
-        float Mt = SQ_NEG_INF;
-#pragma unroll
-        for (int g = 0; g < MERGE_GROUPS; ++g) Mt = fmaxf(Mt, s_red[g * 130]);
-        float a = 0.0f, l = 0.0f;
-#pragma unroll
-        for (int g = 0; g < MERGE_GROUPS; ++g) {
-            const float mg = s_red[g * 130];
-            const float w = mg == SQ_NEG_INF ? 0.0f : __expf(mg - Mt);
-            a += w * s_red[g * 130 + 2 + tid];
-            l += w * s_red[g * 130 + 1];
-        }
-        const bool empty = n == 0 || !(l > 0.0f);
-        out_row[tid] = (_Float16)(empty ? 0.0f : a / l);
-        if (lse_row && tid == 0) *lse_row = empty ? SQ_NEG_INF : Mt + logf(l);
-    }
-}
 
 // Phase 1: one work item = one chunk of up to KPC keys of one (sequence, head) row.  The grid is a fixed
 // number of workgroups; workgroup w takes the k consecutive items [w*k, (w+1)*k), k = ceil(items / grid),
@@ -249,7 +181,10 @@ __global__ __launch_bounds__(MERGE_THREADS) void decode_merge_kernel(const float
     const int total = min(*plan.total, plan.item_cap);
     const int k = max(1, (total + attn_grid - 1) / attn_grid);     // items per attention workgroup
     const int n = it.y == 0 ? 0 : 1 + (it.x + it.y - 1) / k - it.x / k;
-    merge_row(partials, it.x, k, n, out + bh * D, lse ? lse + bh : nullptr, s_red, threadIdx.x);
+    // The row's partials sit at item indices `first` and every multiple of k inside (first, first + items).
+    const int first = it.x, fk = first / k;
+    auto slot_ptr = [&](int c) { return partials + (size_t)(c == 0 ? first : (fk + c) * k) * PART_STRIDE; };
+    merge_row<false>(slot_ptr, n, out + bh * D, lse ? lse + bh : nullptr, s_red, threadIdx.x);
 }
 
 // Workgroups of the persistent partial kernel: four per compute unit.

@@ -1,0 +1,302 @@
+// Decode-time sparse attention for a batch of sequences over ONE shared fixed context (Section 4.2 applied
+// to the shared-prefix setting of Section 1): each sequence selects its own clusters, but a cluster kept by
+// several sequences is read from HBM once.  Sequences are handled in groups of SG = 16; the work items of a
+// (group, head) "union row" are chunks of KPC keys drawn from the clusters kept by ANY sequence of the group,
+// every key carrying the set of sequences that kept it.  The user keys of a sequence are chunks owned by that
+// one sequence.
+//
+// With 16 sequences per group the scores of a chunk form a 16-column matrix, which is the shape of a CDNA4
+// matrix-core tile, so the arithmetic runs on MFMA and the kernel stays bound by the K/V stream:
+//   * every WAVE works alone (no workgroup barrier anywhere): it takes a run of consecutive work items and
+//     walks each in four steps of 32 keys;
+//   * K rows are loaded from global memory directly in the A-operand layout of S^T = K Q^T (16x16x32 fp16
+//     tiles: A = 16 keys, B = the 16 queries of the group, kept in registers per head), so K never touches LDS;
+//   * in the accumulator layout a lane owns ONE sequence (column) and a few keys, so the per-(key, sequence)
+//     ownership bit, the running maximum, the running sum and the output rescaling are per-lane scalars;
+//   * V rows are transposed through a wave-private LDS tile on the way in (keys of the 32-key step permuted so
+//     that the eight keys a lane needs are 16 contiguous bytes) and O^T += V^T P^T runs on MFMA with P^T taken
+//     from the score accumulators in place;
+//   * a lane's output accumulators hold its sequence's 128 dimensions spread over the four lane groups: 32
+//     registers of state for all 16 sequences.
+//
+// Partial results and merge follow the single-sequence kernel: per (wave, union row) segment the wave writes
+// SG partial results (one per sequence of the group; those of sequences that owned no key in the segment are
+// marked empty), and a second kernel merges the partials of every (sequence, head) row.  Rows are placed in the
+// item list in the order they arrive and a row's rank in that order is recorded with it; segment (wave w, row)
+// writes slot w + rank(row), which is unique because both w and the rank never decrease along the item list
+// and one of them increases from one segment to the next.
+#include <stdlib.h>
+
+#include "sq_common.hpp"
+#include "sq_internal.hpp"
+#include "sq_merge.hpp"
+
+namespace sq {
+
+static_assert(KPC == 128 && SG == 16, "the shared-context kernel is written for 128-key chunks and 16 sequences");
+constexpr int SV_STRIDE = 40;    // halves per V^T row in LDS: 32 keys + 8 of padding (80 B)
+
+struct WaveLds {                 // private to one wave
+    int pos[KPC], delta[KPC];    // run-length records of the current item
+    uint32_t rset[KPC];          // set of sequences per record
+    int rows[KPC];               // K/V row of every key slot (-1 past the end)
+    uint32_t kset[KPC];          // set of sequences per key slot (0 past the end)
+    _Float16 Vt[D * SV_STRIDE];  // V^T of the current 32-key step
+};
+
+// LDS traffic inside a wave needs no hardware barrier (a wave's LDS operations complete in order), only a point
+// the compiler does not move LDS accesses across.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Position of key kappa (0..31) of a step inside a V^T row: key (t*16 + g*4 + j) goes to g*8 + t*4 + j, so
+// the B operand's keys of lane group g (two accumulator tiles x 4 keys) are contiguous.
+__device__ __forceinline__ int sv_pos(int kappa)
+{
+    const int t = kappa >> 4, g = (kappa & 15) >> 2, j = kappa & 3;
+    return g * 8 + t * 4 + j;
+}
+
+__global__ __launch_bounds__(256, 3) void decode_attn_shared_kernel(
+    const _Float16 *__restrict__ q, const _Float16 *__restrict__ Kf, const _Float16 *__restrict__ Vf,
+    const _Float16 *__restrict__ Ku, const _Float16 *__restrict__ Vu, DecodePlan plan,
+    float *__restrict__ partials, int B, int H, int L, int U, float sm_scale)
+{
+    __shared__ __align__(16) WaveLds s_w[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    WaveLds &S = s_w[wave];
+    const int col = lane & 15, kg = lane >> 4;             // sequence of this lane; lane group
+    const int gw = blockIdx.x * 4 + wave, n_waves = gridDim.x * 4;
+
+    const int total = min(plan.total[0], plan.item_cap);
+    const int ki = (total + n_waves - 1) / n_waves;        // items per wave
+    int item = gw * ki;
+    const int item_end = min(item + ki, total);
+    if (item >= item_end) return;                          // this wave only: the kernel has no workgroup barrier
+
+    const float c2 = sm_scale * 1.44269504088896341f;      // exp(sm_scale * s) = exp2(c2 * s)
+    float m_run = SQ_NEG_INF, l_run = 0.0f;                // of sequence `col`; raw logit units; l is this lane's share
+    f4 o[8];
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) o[dt] = f4{0.f, 0.f, 0.f, 0.f};
+    h8 bq[4] = {};                                         // Q^T operand: sequence col, dims s*32 + kg*8 .. +8
+    int cur_row = -1;
+
+    // Partials of the segment that ends here: slot (gw + rank(row)) * SG + sequence.
+    auto flush = [&](int row) {
+        const float lt = cross16_sum(l_run);
+        float *dst = partials + ((size_t)(gw + plan.row_rank[row]) * SG + col) * PART_STRIDE;
+        const bool empty = m_run == SQ_NEG_INF;            // the sequence owned no key of this segment
+        if (kg == 0) {
+            dst[0] = empty ? SQ_NEG_INF : m_run * sm_scale;
+            dst[1] = lt;
+        }
+        if (!empty) {
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) *reinterpret_cast<f4 *>(dst + 4 + dt * 16 + kg * 4) = o[dt];
+        }
+    };
+
+    for (; item < item_end; ++item) {
+        const int2 *it = plan.item + (size_t)item * ITEM_STRIDE;
+        const int2 h0 = it[0], h1 = it[1];                 // (union row, keys) (records | -1 - sequence, first user key)
+        const int row = h0.x, h = row % H, grp = row / H;
+        if (row != cur_row) {                              // wave-uniform
+            if (cur_row >= 0) {
+                flush(cur_row);
+                m_run = SQ_NEG_INF;
+                l_run = 0.0f;
+#pragma unroll
+                for (int dt = 0; dt < 8; ++dt) o[dt] = f4{0.f, 0.f, 0.f, 0.f};
+            }
+            cur_row = row;
+            const int b = grp * SG + col;
+            if (b < B) {
+                const h8 *qp = reinterpret_cast<const h8 *>(q + ((size_t)b * H + h) * D);
+#pragma unroll
+                for (int s = 0; s < 4; ++s) bq[s] = qp[s * 4 + kg];
+            } else {
+#pragma unroll
+                for (int s = 0; s < 4; ++s) bq[s] = h8{0, 0, 0, 0, 0, 0, 0, 0};
+            }
+        }
+        const int nvalid = h0.y;
+        const bool user = h1.x < 0;
+        const char *Kbase, *Vbase;                         // byte pointers; a row is 256 B
+        wave_lds_sync();                                   // the previous item's readers are done
+        if (user) {
+            const int sq_ = -1 - h1.x;                     // sequence within the group
+            const size_t bh = (size_t)(grp * SG + sq_) * H + h;
+            Kbase = reinterpret_cast<const char *>(Ku + (bh * U + h1.y) * D);
+            Vbase = reinterpret_cast<const char *>(Vu + (bh * U + h1.y) * D);
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int t = lane + 64 * u;
+                S.rows[t] = t < nvalid ? t : -1;
+                S.kset[t] = t < nvalid ? (1u << sq_) : 0u;
+            }
+        } else {
+            Kbase = reinterpret_cast<const char *>(Kf + (size_t)h * L * D);
+            Vbase = reinterpret_cast<const char *>(Vf + (size_t)h * L * D);
+            const int nrec = min(h1.x, KPC);
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int t = lane + 64 * u;
+                const int2 rc = it[2 + (t < nrec ? t : 0)];
+                S.pos[t] = rc.x & 0xffff;
+                S.rset[t] = (uint32_t)rc.x >> 16;
+                S.delta[t] = rc.y;
+            }
+            wave_lds_sync();
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int t = lane + 64 * u;
+                int lo = 0;
+#pragma unroll
+                for (int step = KPC / 2; step > 0; step >>= 1)
+                    if (lo + step < nrec && S.pos[lo + step] <= t) lo += step;
+                const int r = t + S.delta[lo];
+                S.rows[t] = t < nvalid ? max(0, min(r, L - 1)) : -1;   // malformed input stays in the tensor
+                S.kset[t] = t < nvalid ? S.rset[lo] : 0u;
+            }
+        }
+        wave_lds_sync();
+        const int r_last = S.rows[nvalid - 1];
+
+        for (int j0 = 0; j0 < nvalid; j0 += 32) {          // 32 keys per step
+            // ---- loads: K in A-operand layout (tile t: key t*16 + col, dims s*32 + kg*8 .. +8); V by key ------------
+            h8 ka[2][4], vr[8];
+            {
+                int rk[2];
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const int r = S.rows[j0 + t * 16 + col];
+                    rk[t] = r < 0 ? r_last : r;           // slots past the end re-read a valid row
+                }
+                const int rvv = S.rows[j0 + (lane & 31)];
+                const int rv = rvv < 0 ? r_last : rvv;
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int s = 0; s < 4; ++s)
+                        ka[t][s] = *reinterpret_cast<const h8 *>(Kbase + (size_t)rk[t] * 256 + s * 64 + kg * 16);
+                const char *vp = Vbase + (size_t)rv * 256 + (lane >> 5) * 128;
+#pragma unroll
+                for (int c = 0; c < 8; ++c) vr[c] = *reinterpret_cast<const h8 *>(vp + c * 16);
+            }
+            // ownership bits of this lane's (key, sequence) pairs: element e = t*4 + v <-> key t*16 + kg*4 + v
+            uint32_t msk[8];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const uint4 ks = *reinterpret_cast<const uint4 *>(&S.kset[j0 + t * 16 + kg * 4]);
+                msk[t * 4 + 0] = (uint32_t)__builtin_amdgcn_sbfe((int)ks.x, col, 1);
+                msk[t * 4 + 1] = (uint32_t)__builtin_amdgcn_sbfe((int)ks.y, col, 1);
+                msk[t * 4 + 2] = (uint32_t)__builtin_amdgcn_sbfe((int)ks.z, col, 1);
+                msk[t * 4 + 3] = (uint32_t)__builtin_amdgcn_sbfe((int)ks.w, col, 1);
+            }
+
+            // ---- S^T = K Q^T -----------------------------------------------------------------------------------------
+            f4 sacc[2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                sacc[t] = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int s = 0; s < 4; ++s)
+                    sacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][s], bq[s], sacc[t], 0, 0, 0);
+            }
+
+            // ---- V -> wave-private LDS, transposed: lane = key (lane % 32), dims (lane / 32) * 64 + c*8 + e --------
+            {
+                _Float16 *vt = S.Vt + (lane >> 5) * 64 * SV_STRIDE + sv_pos(lane & 31);
+#pragma unroll
+                for (int c = 0; c < 8; ++c)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) vt[(c * 8 + e) * SV_STRIDE] = vr[c][e];
+            }
+
+            // ---- online softmax of column `col` -------------------------------------------------------------------
+            float sv[8];
+            float mx = SQ_NEG_INF;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float sraw = sacc[e >> 2][e & 3];    // (a copy: the bit cast below must not see a vector element)
+                const uint32_t bits = __builtin_bit_cast(uint32_t, sraw);
+                sv[e] = __builtin_bit_cast(float, (msk[e] & bits) | (~msk[e] & 0xff800000u));   // not owned: -inf
+                mx = fmaxf(mx, sv[e]);
+            }
+            mx = cross16_max(mx);                          // the 4 lane groups hold the other keys of the column
+            const float m_new = fmaxf(m_run, mx);
+            const float mneg = m_new == SQ_NEG_INF ? 0.0f : -m_new * c2;   // nothing seen yet: exp2(-inf) = 0
+            const float alpha = __builtin_amdgcn_exp2f(fmaf(m_run, c2, mneg));
+            float psum = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                sv[e] = __builtin_amdgcn_exp2f(fmaf(sv[e], c2, mneg));
+                psum += sv[e];
+            }
+            m_run = m_new;
+            l_run = l_run * alpha + psum;
+            if (__ballot(alpha != 1.0f) != 0ull) {
+#pragma unroll
+                for (int dt = 0; dt < 8; ++dt) o[dt] *= alpha;
+            }
+            h8 bp;                                         // P^T operand: sequence col, keys at positions kg*8 .. +8
+#pragma unroll
+            for (int e = 0; e < 8; ++e) bp[e] = (_Float16)sv[e];
+
+            // ---- O^T += V^T P^T -------------------------------------------------------------------------------------
+            wave_lds_sync();                               // V^T is written
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) {
+                const h8 a = *reinterpret_cast<const h8 *>(S.Vt + (dt * 16 + col) * SV_STRIDE + kg * 8);
+                o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bp, o[dt], 0, 0, 0);
+            }
+            wave_lds_sync();                               // V^T is read before the next step overwrites it
+        }
+    }
+    flush(cur_row);
+}
+
+// Phase 2: one workgroup per (sequence, head) row merges the partials its union row's segments wrote for
+// that sequence.
+__global__ __launch_bounds__(MERGE_THREADS) void decode_merge_shared_kernel(const float *__restrict__ partials,
+                                                                            DecodePlan plan, _Float16 *__restrict__ out,
+                                                                            float *__restrict__ lse, int H, int n_waves)
+{
+    __shared__ float s_red[MERGE_GROUPS * 130];
+    const size_t bh = blockIdx.x;
+    const int b = (int)(bh / H), h = (int)(bh % H);
+    const int urow = (b / SG) * H + h, sq_ = b % SG;
+    const int2 it = plan.row_items[urow];            // (first item, items) of the union row
+    const int rank = plan.row_rank[urow];
+    const int total = min(plan.total[0], plan.item_cap);
+    const int ki = max(1, (total + n_waves - 1) / n_waves);        // items per attention wave
+    const int w_lo = it.x / ki;
+    const int n = it.y == 0 ? 0 : (it.x + it.y - 1) / ki - w_lo + 1;
+    auto slot_ptr = [&](int c) { return partials + ((size_t)(w_lo + c + rank) * SG + sq_) * PART_STRIDE; };
+    merge_row<true>(slot_ptr, n, out + bh * D, lse ? lse + bh : nullptr, s_red, threadIdx.x);
+}
+
+hipError_t launch_decode_attn_shared(const void *q, const void *Kf, const void *Vf, const void *Ku, const void *Vu,
+                                     DecodePlan plan, float *partials, void *out, float *lse, const Shape &sh,
+                                     hipStream_t s)
+{
+    const int rows = sh.B * sh.H;
+    static_assert(SHARED_ATTN_WAVES % 4 == 0, "four waves per workgroup");
+    const bool prof = profile_mark(s, true);
+    hipLaunchKernelGGL(decode_attn_shared_kernel, dim3(SHARED_ATTN_WAVES / 4), dim3(256), 0, s, (const _Float16 *)q,
+                       (const _Float16 *)Kf, (const _Float16 *)Vf, (const _Float16 *)Ku, (const _Float16 *)Vu, plan,
+                       partials, sh.B, sh.H, sh.L, sh.U, sh.sm_scale);
+    if (prof) profile_mark(s, false);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(decode_merge_shared_kernel, dim3(rows), dim3(MERGE_THREADS), 0, s, partials, plan,
+                       (_Float16 *)out, lse, sh.H, SHARED_ATTN_WAVES);
+    return hipGetLastError();
+}
+
+}  // namespace sq

@@ -17,7 +17,8 @@ struct Shape {
 //   rec       per row, one record per kept range: (first key, count, selected keys before it, 0)
 //   hdr       per row: (number of records, number of selected keys)
 //   row_items per row: (first work item, number of work items); items of a row are consecutive
-//   total     number of work items of the whole call
+//   total     two ints: work items of the whole call, rows that have placed their items
+//   row_rank  per row (may be null): how many rows had placed their items before this one
 //   item      per work item (= one chunk of up to KPC keys of one row) ITEM_STRIDE int2 slots:
 //             slot 0 = (row, keys in the chunk), slot 1 = (records in the chunk or -1 for a chunk of user
 //             keys, first user key), slots 2.. = the chunk's own copy of the range records it touches, as
@@ -30,7 +31,8 @@ struct DecodePlan {
     int4 *rec;        // [rows, rec_cap]
     int2 *hdr;        // [rows]
     int2 *row_items;  // [rows]
-    int *total;       // [1]
+    int *total;       // [2], 8-byte aligned (both words are advanced by one 64-bit atomic)
+    int *row_rank;    // [rows] or null
     int2 *item;       // [item_cap, ITEM_STRIDE]
     int rec_cap;
     int item_cap;     // rows * (user chunks + ceil(L / KPC))
@@ -46,7 +48,7 @@ constexpr int LDS_BYTES_MAX = 160 * 1024 - 4096;   // gfx950: 160 KB per workgro
 // Scheduling keeps two ints per chunk of a row in LDS (same budget as the staged logits).
 constexpr int MAX_L = SELECT_MAX_C * KPC;
 
-// zero_counter (may be null) is set to 0 by the kernel: the item counter of a decode step.
+// zero_counter (may be null) points at the two counters of a decode step's work list; the kernel zeroes them.
 hipError_t launch_score(const void *q, const void *centroids, float *logits, int *zero_counter, int B, int H, int Lq,
                         int C, float sm_scale, hipStream_t s);
 hipError_t launch_row_stats(const float *logits, const int32_t *sizes, float *row_max, float *denom, int rows,
@@ -57,7 +59,20 @@ struct SelectOpts {
     const uint32_t *parent_mask;     // level 2: keep mask of the coarse level [B*H, ceil(C1/32)]
     int C1;
     int len_from_offsets;            // level 1: emitted range length = offsets[i+1] - offsets[i] (child clusters)
+    const uint32_t *union_masks;     // shared-context scheduling: keep masks of all sequences [B*H, ceil(C/32)]
+    int B;                           // shared-context scheduling: number of sequences
 };
+
+// Batched decode over a shared fixed context: sequences are handled in groups of SG; a "union row" is one
+// (group, head) pair and its work items cover the clusters kept by ANY sequence of the group, each key
+// carrying the set of sequences that kept it, so a key leaves HBM once per group instead of once per sequence.
+// Items of a union row use the layout above with these differences: slot 0.x is the union row; slot 1.x of a
+// user chunk is -1 - (sequence within the group); a record's x packs (position clamped to >= 0) | (set of
+// sequences << 16).
+constexpr int SG = 16;
+inline int seq_groups_for(int B) { return (B + SG - 1) / SG; }
+// Waves of the shared-context partial kernel (each works alone): three workgroups of four per compute unit.
+constexpr int SHARED_ATTN_WAVES = 256 * 12;
 
 // stats_in == true: use row_max/denom; false: the kernel derives them from logits itself.
 hipError_t launch_select(const float *logits, const float *row_max, const float *denom, bool stats_in,
@@ -76,6 +91,16 @@ hipError_t launch_schedule(DecodePlan plan, int rows, int U, hipStream_t s);
 hipError_t launch_decode_attn(const void *q, const void *Kf, const void *Vf, const void *Ku, const void *Vu,
                               DecodePlan plan, float *partials, void *out, float *lse, const Shape &sh,
                               hipStream_t s);
+
+// Shared-context decode: work items of every union row from the per-sequence keep masks (needs the two
+// counters at plan.total zeroed), and the partial + merge kernels.  partials: (SHARED_ATTN_WAVES + union
+// rows) * SG slots of PART_STRIDE floats.
+hipError_t launch_union_schedule(const uint32_t *keep_masks, const int32_t *sizes, const int32_t *offsets,
+                                 DecodePlan plan, int32_t *n_ranges_u, int32_t *n_keys_u, int U, int B, int H, int C,
+                                 hipStream_t s);
+hipError_t launch_decode_attn_shared(const void *q, const void *Kf, const void *Vf, const void *Ku, const void *Vu,
+                                     DecodePlan plan, float *partials, void *out, float *lse, const Shape &sh,
+                                     hipStream_t s);
 
 // Prefill attention with per-query keep masks; key_cid [H, L] is workspace for the key -> cluster map.
 hipError_t launch_prefill_attn(const void *q, const void *Kf, const void *Vf, const void *Ku, const void *Vu,

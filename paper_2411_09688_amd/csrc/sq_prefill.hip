@@ -3,7 +3,8 @@
 //
 // Layout of the computation (FlashAttention-2 style: grid over heads x query blocks, loop over key blocks,
 // online softmax), written for CDNA4 matrix cores:
-//   * a workgroup = 4 waves x 16 queries (two workgroups per compute unit); all waves walk the same 64-key blocks, whose K tile and transposed
+//   * a workgroup = 4 waves x 16 queries (two workgroups per compute unit); all waves walk the same
+//     64-key blocks, whose K tile and transposed
 //     V tile are staged in LDS once per workgroup (two LDS buffers; the next block's global loads are issued
 //     before the current block's arithmetic and land in registers meanwhile);
 //   * scores are computed TRANSPOSED, S^T = K Q^T, with 16x16x32 fp16 MFMA tiles (A = 16 keys, B = 16

@@ -19,7 +19,8 @@ __global__ __launch_bounds__(256) void score_kernel(const _Float16 *__restrict__
                                                     float *__restrict__ logits, int *__restrict__ zero_counter,
                                                     int B, int H, int Lq, int C, float sm_scale)
 {
-    if (zero_counter && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) *zero_counter = 0;
+    if (zero_counter && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0)
+        zero_counter[0] = zero_counter[1] = 0;              // (items, rows placed) of the step's work list
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & 15, kg = lane >> 4;
     const int h = blockIdx.y;
@@ -96,7 +97,7 @@ __global__ __launch_bounds__(256) void gather_score_kernel(const _Float16 *__res
                                                            float sm_scale)
 {
     __shared__ int s_pos[KPC], s_delta[KPC], s_rows[KPC];
-    if (zero_counter && blockIdx.x == 0 && threadIdx.x == 0) *zero_counter = 0;
+    if (zero_counter && blockIdx.x == 0 && threadIdx.x == 0) zero_counter[0] = zero_counter[1] = 0;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 15, kg = lane >> 4;
     constexpr int TILES = KPC / 64;                 // 16-cluster tiles per wave

@@ -62,10 +62,13 @@ __device__ __forceinline__ ScanOut block_scan_kept(bool keep, int nkeys, int lan
 // touches.  s_first: LDS scratch, two ints per fixed-context chunk of the row.
 // REG: the caller's threads each hold at most one record (have_rec, my_r, my_rec) in registers, as they
 // do after a single selection step; otherwise the records are read back from plan.rec.
-template <bool REG>
+// SHARED: the row is a union row of a sequence group; its n_user_chunks = sequences * chunks_per_seq user
+// chunks name their sequence, and every record carries the set of sequences (rec.w) that kept its cluster.
+template <bool REG, bool SHARED = false>
 __device__ __forceinline__ void emit_row_items(const DecodePlan &plan, int row, const int *s_base_ptr, int n_rec,
                                                int n_sel, int U, int n_user_chunks, int *s_first, int tid,
-                                               int nthreads, bool have_rec, int my_r, int4 my_rec)
+                                               int nthreads, bool have_rec, int my_r, int4 my_rec,
+                                               int chunks_per_seq = 1)
 {
     const int n_fixed = (n_sel + KPC - 1) / KPC;
     int *s_firstz = s_first + n_fixed;                      // selected keys before the chunk's first record
@@ -85,8 +88,9 @@ __device__ __forceinline__ void emit_row_items(const DecodePlan &plan, int row, 
     if (tid == 0) plan.row_items[row] = make_int2(base, n_user_chunks + n_fixed);
     for (int c = tid; c < n_user_chunks; c += nthreads) {
         int2 *it = plan.item + (size_t)(base + c) * ITEM_STRIDE;
-        it[0] = make_int2(row, min(KPC, U - c * KPC));
-        it[1] = make_int2(-1, c * KPC);
+        const int seq = SHARED ? c / chunks_per_seq : 0, cu = SHARED ? c % chunks_per_seq : c;
+        it[0] = make_int2(row, min(KPC, U - cu * KPC));
+        it[1] = make_int2(-1 - seq, cu * KPC);
     }
     // Pass 2: every record writes its (position, delta) into the chunks it touches.
     for (int r = REG ? my_r : tid; REG ? have_rec : r < n_rec; r += nthreads) {
@@ -95,7 +99,7 @@ __device__ __forceinline__ void emit_row_items(const DecodePlan &plan, int row, 
         for (int c = c_lo; c <= c_hi; ++c) {
             int2 *it = plan.item + (size_t)(base + n_user_chunks + c) * ITEM_STRIDE;
             const int pos = rc.z - c * KPC;                 // negative for a record that began in an earlier chunk
-            it[2 + r - s_first[c]] = make_int2(pos, rc.x - pos);
+            it[2 + r - s_first[c]] = make_int2(SHARED ? (int)((uint32_t)max(pos, 0) | ((uint32_t)rc.w << 16)) : pos, rc.x - pos);
         }
         if (REG) break;
     }
@@ -115,7 +119,10 @@ __device__ __forceinline__ void emit_row_items(const DecodePlan &plan, int row, 
     }
 }
 
-template <bool STATS_IN, bool SCHEDULE>
+// UNION: the row is a union row (sequence group, head) of a batched decode over a shared context; there are
+// no logits: cluster i is kept iff any sequence of the group has it in its keep mask (opt.union_masks), and the
+// set of those sequences travels with the record.  Always with SCHEDULE.
+template <bool STATS_IN, bool SCHEDULE, bool UNION = false>
 __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     const float *__restrict__ logits, const float *__restrict__ row_max, const float *__restrict__ denom,
     const float *__restrict__ thresh, const int32_t *__restrict__ sizes, const int32_t *__restrict__ offsets,
@@ -135,9 +142,20 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     const int32_t *N = sizes + (size_t)h * C;
     const int32_t *off = offsets + (size_t)h * (C + 1);
     const int W = (C + 31) >> 5;
-    const float T = thresh[h];
+    const float T = UNION ? 0.0f : thresh[h];
+    uint32_t *s_set = reinterpret_cast<uint32_t *>(s_e);   // UNION: set of sequences per cluster instead of e_i
+    const int n_seq = UNION ? min(SG, opt.B - (int)(row / H) * SG) : 1;
 
-    if (opt.parent_mask) {
+    if (UNION) {
+        const uint32_t *m0 = opt.union_masks + ((size_t)(row / H) * SG * H + h) * W;   // sequence s: + s * H * W
+        for (int i = tid; i < C; i += SEL_THREADS) {
+            uint32_t set = 0u;
+            for (int sq_ = 0; sq_ < n_seq; ++sq_)
+                set |= ((m0[(size_t)sq_ * H * W + (i >> 5)] >> (i & 31)) & 1u) << sq_;
+            s_set[i] = set;
+            s_N[i] = N[i];
+        }
+    } else if (opt.parent_mask) {
         // Two-level lookup, level 2 (Section 3.3): only the children of kept coarse clusters are
         // candidates; every other cluster is treated as empty, so the maximum and the normaliser of
         // Eq. 3 run over the candidates only.  Parent of cluster i: the j with co[j] <= i < co[j+1].
@@ -163,7 +181,9 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
         }
     }
     float m;
-    if (STATS_IN) {
+    if (UNION) {
+        if (tid == 0) s_thr = 0.0f;
+    } else if (STATS_IN) {
         m = row_max[row];
         if (tid == 0) s_thr = T * denom[row];
         __syncthreads();
@@ -213,7 +233,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     for (int st = 0; st < n_steps; ++st) {
         const int i = st * SEL_THREADS + tid;
         const int Ni = i < C ? s_N[i] : 0;
-        const bool keep = Ni > 0 && s_e[i] > thr;
+        const bool keep = Ni > 0 && (UNION ? s_set[i] != 0u : s_e[i] > thr);
         int len = Ni;
         if (opt.len_from_offsets) len = keep ? (st == 0 ? next_first - start_first : off[i + 1] - off[i]) : 0;
         const bool emit = keep && len > 0;              // a kept coarse cluster without children emits nothing
@@ -266,7 +286,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     for (int st = 0; st < n_steps; ++st) {
         const int i = st * SEL_THREADS + tid;
         const int Ni = i < C ? s_N[i] : 0;
-        const bool keep = Ni > 0 && s_e[i] > thr;
+        const bool keep = Ni > 0 && (UNION ? s_set[i] != 0u : s_e[i] > thr);
         const int start = st == 0 ? start_first : (keep ? off[i] : 0);
         int len = Ni;
         if (opt.len_from_offsets) len = keep ? (st == 0 ? next_first : off[i + 1]) - start : 0;
@@ -280,7 +300,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
         if (emit) {
             const int r = s_tcnt[st * SEL_WAVES + wave] + rank;
             if (ranges) *reinterpret_cast<int2 *>(ranges + (row * C + r) * 2) = make_int2(start, len);
-            my_rec = make_int4(start, len, s_tkeys[st * SEL_WAVES + wave] + incl - kv, 0);
+            my_rec = make_int4(start, len, s_tkeys[st * SEL_WAVES + wave] + incl - kv, UNION ? (int)s_set[i] : 0);
             my_r = r;
             have_rec = true;
             if (plan.rec) plan.rec[row * plan.rec_cap + r] = my_rec;
@@ -296,15 +316,23 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
         // kernel that ran before): rows land in arrival order, which moves chunks between workgroups but
         // changes no result.  The records written above are read back after the barrier.
         const int n_sel = min(base_k, plan.L);
-        if (tid == 0) s_base = atomicAdd(plan.total, n_user_chunks + (n_sel + KPC - 1) / KPC);
+        const int n_uc = n_user_chunks * n_seq;             // every sequence of a union row has its own user keys
+        __syncthreads();                                    // every thread is done with the staged row (s_first aliases it)
+        if (tid == 0) {
+            // One 64-bit add advances (items, rows placed) together, so rows are ranked in item order.
+            const unsigned long long old =
+                atomicAdd(reinterpret_cast<unsigned long long *>(plan.total),
+                          (1ull << 32) | (unsigned long long)(unsigned)(n_uc + (n_sel + KPC - 1) / KPC));
+            s_base = (int)(old & 0xffffffffull);
+            if (plan.row_rank) plan.row_rank[row] = (int)(old >> 32);
+        }
         int *s_first = reinterpret_cast<int *>(smem);       // the staged logits are no longer needed
         if (C <= SEL_THREADS) {
-            emit_row_items<true>(plan, (int)row, &s_base, base_r, n_sel, U, n_user_chunks, s_first, tid, SEL_THREADS,
-                                 have_rec, my_r, my_rec);
+            emit_row_items<true, UNION>(plan, (int)row, &s_base, base_r, n_sel, U, n_uc, s_first, tid, SEL_THREADS,
+                                        have_rec, my_r, my_rec, n_user_chunks);
         } else {
-            __syncthreads();                                // records of every step are in plan.rec
-            emit_row_items<false>(plan, (int)row, &s_base, base_r, n_sel, U, n_user_chunks, s_first, tid, SEL_THREADS,
-                                  false, 0, my_rec);
+            emit_row_items<false, UNION>(plan, (int)row, &s_base, base_r, n_sel, U, n_uc, s_first, tid, SEL_THREADS,
+                                         false, 0, my_rec, n_user_chunks);
         }
     }
 }
@@ -451,10 +479,11 @@ hipError_t launch_select(const float *logits, const float *row_max, const float 
     static bool attr_set = false;   // one GPU per process in this build
     if (!attr_set) {
         const int lim = LDS_BYTES_MAX;
-        const void *fns[4] = {reinterpret_cast<const void *>(select_kernel<true, false>),
+        const void *fns[5] = {reinterpret_cast<const void *>(select_kernel<true, false>),
                               reinterpret_cast<const void *>(select_kernel<false, false>),
                               reinterpret_cast<const void *>(select_kernel<false, true>),
-                              reinterpret_cast<const void *>(select_kernel<true, true>)};
+                              reinterpret_cast<const void *>(select_kernel<true, true>),
+                              reinterpret_cast<const void *>(select_kernel<false, true, true>)};
         for (const void *f : fns) {
             hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
             if (e != hipSuccess) return e;
@@ -462,6 +491,13 @@ hipError_t launch_select(const float *logits, const float *row_max, const float 
         attr_set = true;
     }
     const int nuc = user_chunks_for(U);
+    if (opt.union_masks) {
+        if (!schedule) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((select_kernel<false, true, true>), dim3(rows), dim3(SEL_THREADS), smem, s, logits, row_max,
+                           denom, thresh, sizes, offsets, keep_mask, ranges, n_ranges, n_keys, plan, opt, H, Lq, C, U,
+                           nuc);
+        return hipGetLastError();
+    }
 #define SQ_LAUNCH_SELECT(SI, SCH)                                                                               \
     hipLaunchKernelGGL((select_kernel<SI, SCH>), dim3(rows), dim3(SEL_THREADS), smem, s, logits, row_max, denom, \
                        thresh, sizes, offsets, keep_mask, ranges, n_ranges, n_keys, plan, opt, H, Lq, C, U, nuc)
@@ -471,6 +507,17 @@ hipError_t launch_select(const float *logits, const float *row_max, const float 
     else SQ_LAUNCH_SELECT(false, false);
 #undef SQ_LAUNCH_SELECT
     return hipGetLastError();
+}
+
+hipError_t launch_union_schedule(const uint32_t *keep_masks, const int32_t *sizes, const int32_t *offsets,
+                                 DecodePlan plan, int32_t *n_ranges_u, int32_t *n_keys_u, int U, int B, int H, int C,
+                                 hipStream_t s)
+{
+    SelectOpts opt{};
+    opt.union_masks = keep_masks;
+    opt.B = B;
+    return launch_select(nullptr, nullptr, nullptr, false, nullptr, sizes, offsets, nullptr, nullptr, n_ranges_u,
+                         n_keys_u, plan, true, U, opt, seq_groups_for(B) * H, H, 1, C, s);
 }
 
 hipError_t launch_ranges_to_rec(const int32_t *ranges, const int32_t *n_ranges, DecodePlan plan, int rows,
