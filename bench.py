@@ -243,7 +243,8 @@ def bench_hier(args, torch, sq, wl, dev):
                        "achieved": round(kernel_bytes / (k_avg * 1e-6) / 1e9, 2) if n_meas else None,
                        "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                        "frac": round(kernel_bytes / (k_avg * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4) if n_meas else None,
-                       "traffic": read_traffic(f"decode_attn_kernel_{args.workload}_pmc.txt"),
+                       "traffic": read_traffic(("decode_attn_shared_kernel" if w.B > 1 and not args.separate
+                                              else "decode_attn_kernel") + f"_{args.workload}_pmc.txt"),
                        "bytes_per_launch": round(kernel_bytes), "avg_us": round(k_avg, 3), "min_us": round(k_min, 3),
                        "launches": n_meas}
     print(json.dumps(res, ensure_ascii=False))
@@ -388,11 +389,13 @@ def main():
                            "selected_kv_requested": round(sel_requested),
                            "dense_kv": round(dense), "centroid_plus_selected_kv": round(cen + sel)},
         "hbm_frac_whole_step": round(tot / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-        "roofline": {"bound": "hbm", "kernel": "decode_attn_kernel",
+        "roofline": {"bound": "hbm", "kernel": "decode_attn_shared_kernel" if w.B > 1 and not args.separate
+                     else "decode_attn_kernel",
                      "achieved": round(kernel_bytes / (k_avg_us * 1e-6) / 1e9, 2) if n_meas else None,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(kernel_bytes / (k_avg_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4) if n_meas else None,
-                     "traffic": read_traffic(f"decode_attn_kernel_{args.workload}_pmc.txt"),
+                     "traffic": read_traffic(("decode_attn_shared_kernel" if w.B > 1 and not args.separate
+                                              else "decode_attn_kernel") + f"_{args.workload}_pmc.txt"),
                      "bytes_per_launch": round(kernel_bytes), "avg_us": round(k_avg_us, 3),
                      "min_us": round(k_min_us, 3), "launches": n_meas},
     }

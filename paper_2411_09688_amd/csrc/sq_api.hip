@@ -163,7 +163,7 @@ SharedStepWs carve_step_shared(Carver &cv, const sq_shape_t *sh)
     w.plan.row_rank = cv.take<int>(urows);
     w.plan.total = cv.take<int>(2);
     w.plan.item = cv.take<int2>(items * sq::ITEM_STRIDE);
-    w.partials = cv.take<float>(((size_t)sq::SHARED_ATTN_WAVES + urows) * sq::SG * sq::PART_STRIDE);
+    w.partials = cv.take<float>(((size_t)sq::SHARED_ATTN_GRID + urows) * sq::SG * sq::PART_STRIDE);
     return w;
 }
 

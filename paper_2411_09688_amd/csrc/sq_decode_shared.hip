@@ -7,8 +7,8 @@
 //
 // With 16 sequences per group the scores of a chunk form a 16-column matrix, which is the shape of a CDNA4
 // matrix-core tile, so the arithmetic runs on MFMA and the kernel stays bound by the K/V stream:
-//   * every WAVE works alone (no workgroup barrier anywhere): it takes a run of consecutive work items and
-//     walks each in four steps of 32 keys;
+//   * a workgroup takes a run of consecutive work items; each of its four waves owns 32 of an item's 128 key
+//     slots and works alone between segment ends (no workgroup barrier inside a union row);
 //   * K rows are loaded from global memory directly in the A-operand layout of S^T = K Q^T (16x16x32 fp16
 //     tiles: A = 16 keys, B = the 16 queries of the group, kept in registers per head), so K never touches LDS;
 //   * in the accumulator layout a lane owns ONE sequence (column) and a few keys, so the per-(key, sequence)
@@ -19,12 +19,12 @@
 //   * a lane's output accumulators hold its sequence's 128 dimensions spread over the four lane groups: 32
 //     registers of state for all 16 sequences.
 //
-// Partial results and merge follow the single-sequence kernel: per (wave, union row) segment the wave writes
-// SG partial results (one per sequence of the group; those of sequences that owned no key in the segment are
-// marked empty), and a second kernel merges the partials of every (sequence, head) row.  Rows are placed in the
-// item list in the order they arrive and a row's rank in that order is recorded with it; segment (wave w, row)
-// writes slot w + rank(row), which is unique because both w and the rank never decrease along the item list
-// and one of them increases from one segment to the next.
+// Partial results and merge follow the single-sequence kernel: per (workgroup, union row) segment the four
+// waves' results are combined in LDS and written as SG partial results (one per sequence of the group; those of
+// sequences that owned no key in the segment are marked empty), and a second kernel merges the partials of every
+// (sequence, head) row.  Rows are placed in the item list in the order they arrive and a row's rank in that
+// order is recorded with it; segment (workgroup w, row) writes slot w + rank(row), which is unique because both
+// w and the rank never decrease along the item list and one of them increases from one segment to the next.
 #include <stdlib.h>
 
 #include "sq_common.hpp"
@@ -36,13 +36,15 @@ namespace sq {
 static_assert(KPC == 128 && SG == 16, "the shared-context kernel is written for 128-key chunks and 16 sequences");
 constexpr int SV_STRIDE = 40;    // halves per V^T row in LDS: 32 keys + 8 of padding (80 B)
 
-struct WaveLds {                 // private to one wave
+struct WaveLds {                 // private to one wave, except while a segment's results are combined
     int pos[KPC], delta[KPC];    // run-length records of the current item
     uint32_t rset[KPC];          // set of sequences per record
-    int rows[KPC];               // K/V row of every key slot (-1 past the end)
-    uint32_t kset[KPC];          // set of sequences per key slot (0 past the end)
-    _Float16 Vt[D * SV_STRIDE];  // V^T of the current 32-key step
+    int rows[32];                // K/V row of the wave's key slots (-1 past the end)
+    uint32_t kset[32];           // set of sequences per key slot (0 past the end)
+    float ml[2 * SG];            // segment end: (m, l) of every sequence
+    _Float16 Vt[D * SV_STRIDE];  // V^T of the current 32-key step; segment end: o[SG][D] as fp32
 };
+static_assert(sizeof(_Float16) * D * SV_STRIDE >= sizeof(float) * SG * D, "the V^T tile doubles as the output staging");
 
 // LDS traffic inside a wave needs no hardware barrier (a wave's LDS operations complete in order), only a point
 // the compiler does not move LDS accesses across.
@@ -67,16 +69,16 @@ __global__ __launch_bounds__(256, 3) void decode_attn_shared_kernel(
     float *__restrict__ partials, int B, int H, int L, int U, float sm_scale)
 {
     __shared__ __align__(16) WaveLds s_w[4];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     WaveLds &S = s_w[wave];
     const int col = lane & 15, kg = lane >> 4;             // sequence of this lane; lane group
-    const int gw = blockIdx.x * 4 + wave, n_waves = gridDim.x * 4;
+    const int j0 = wave * 32;                              // this wave's 32 key slots of every item
 
     const int total = min(plan.total[0], plan.item_cap);
-    const int ki = (total + n_waves - 1) / n_waves;        // items per wave
-    int item = gw * ki;
+    const int ki = (total + (int)gridDim.x - 1) / (int)gridDim.x;   // items per workgroup
+    int item = blockIdx.x * ki;
     const int item_end = min(item + ki, total);
-    if (item >= item_end) return;                          // this wave only: the kernel has no workgroup barrier
+    if (item >= item_end) return;                          // whole workgroup
 
     const float c2 = sm_scale * 1.44269504088896341f;      // exp(sm_scale * s) = exp2(c2 * s)
     float m_run = SQ_NEG_INF, l_run = 0.0f;                // of sequence `col`; raw logit units; l is this lane's share
@@ -86,26 +88,61 @@ __global__ __launch_bounds__(256, 3) void decode_attn_shared_kernel(
     h8 bq[4] = {};                                         // Q^T operand: sequence col, dims s*32 + kg*8 .. +8
     int cur_row = -1;
 
-    // Partials of the segment that ends here: slot (gw + rank(row)) * SG + sequence.
+    // End of a (workgroup, union row) segment: the four waves' running results are combined in LDS and written
+    // as SG partials at slots (blockIdx.x + rank(row)) * SG + sequence.  Contains workgroup barriers.
     auto flush = [&](int row) {
         const float lt = cross16_sum(l_run);
-        float *dst = partials + ((size_t)(gw + plan.row_rank[row]) * SG + col) * PART_STRIDE;
-        const bool empty = m_run == SQ_NEG_INF;            // the sequence owned no key of this segment
+        float *so = reinterpret_cast<float *>(S.Vt);       // [SG][D]
+        wave_lds_sync();                                   // the last step's readers of V^T are done
         if (kg == 0) {
-            dst[0] = empty ? SQ_NEG_INF : m_run * sm_scale;
-            dst[1] = lt;
+            S.ml[col * 2] = m_run;
+            S.ml[col * 2 + 1] = lt;
         }
-        if (!empty) {
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt) *reinterpret_cast<f4 *>(dst + 4 + dt * 16 + kg * 4) = o[dt];
+        for (int dt = 0; dt < 8; ++dt) *reinterpret_cast<f4 *>(so + col * D + dt * 16 + kg * 4) = o[dt];
+        __syncthreads();
+        const int slot0 = ((int)blockIdx.x + plan.row_rank[row]) * SG;
+        // thread t: dimension t % 128 of sequences t / 128, t / 128 + 2, ...
+        const int dim = tid & (D - 1);
+        for (int sq_ = tid >> 7; sq_ < SG; sq_ += 2) {
+            float mw[4];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) mw[w] = s_w[w].ml[sq_ * 2];
+            const float M = fmaxf(fmaxf(mw[0], mw[1]), fmaxf(mw[2], mw[3]));
+            float lsum = 0.0f, acc = 0.0f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float sc = mw[w] == SQ_NEG_INF ? 0.0f : __builtin_amdgcn_exp2f((mw[w] - M) * c2);
+                lsum += sc * s_w[w].ml[sq_ * 2 + 1];
+                acc += sc * reinterpret_cast<const float *>(s_w[w].Vt)[sq_ * D + dim];
+            }
+            float *dst = partials + (size_t)(slot0 + sq_) * PART_STRIDE;
+            const bool empty = M == SQ_NEG_INF;            // the sequence owned no key of this segment
+            if (dim == 0) {
+                dst[0] = empty ? SQ_NEG_INF : M * sm_scale;
+                dst[1] = lsum;
+            }
+            if (!empty) dst[4 + dim] = acc;
         }
+        __syncthreads();
     };
 
+    // Header and this lane's two records of the next item travel in registers behind the K/V stream.
+    int2 h0n, h1n, rcn[2];
+    auto prefetch = [&](int i) {
+        const int2 *it = plan.item + (size_t)i * ITEM_STRIDE;
+        h0n = it[0];
+        h1n = it[1];
+        rcn[0] = it[2 + lane];
+        rcn[1] = it[2 + 64 + lane];                        // inside the item's ITEM_STRIDE slots whatever its record count
+    };
+    prefetch(item);
+
     for (; item < item_end; ++item) {
-        const int2 *it = plan.item + (size_t)item * ITEM_STRIDE;
-        const int2 h0 = it[0], h1 = it[1];                 // (union row, keys) (records | -1 - sequence, first user key)
+        const int2 h0 = h0n, h1 = h1n;                     // (union row, keys) (records | -1 - sequence, first user key)
+        const int2 rc[2] = {rcn[0], rcn[1]};
         const int row = h0.x, h = row % H, grp = row / H;
-        if (row != cur_row) {                              // wave-uniform
+        if (row != cur_row) {                              // workgroup-uniform
             if (cur_row >= 0) {
                 flush(cur_row);
                 m_run = SQ_NEG_INF;
@@ -125,19 +162,22 @@ __global__ __launch_bounds__(256, 3) void decode_attn_shared_kernel(
             }
         }
         const int nvalid = h0.y;
+        if (j0 >= nvalid) {                                // wave-uniform: a short chunk has no keys for this wave
+            if (item + 1 < item_end) prefetch(item + 1);
+            continue;
+        }
         const bool user = h1.x < 0;
         const char *Kbase, *Vbase;                         // byte pointers; a row is 256 B
+        const int t_my = j0 + (lane & 31);                 // key slot this lane resolves (both halves of the wave agree)
         wave_lds_sync();                                   // the previous item's readers are done
         if (user) {
             const int sq_ = -1 - h1.x;                     // sequence within the group
             const size_t bh = (size_t)(grp * SG + sq_) * H + h;
             Kbase = reinterpret_cast<const char *>(Ku + (bh * U + h1.y) * D);
             Vbase = reinterpret_cast<const char *>(Vu + (bh * U + h1.y) * D);
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const int t = lane + 64 * u;
-                S.rows[t] = t < nvalid ? t : -1;
-                S.kset[t] = t < nvalid ? (1u << sq_) : 0u;
+            if (lane < 32) {
+                S.rows[lane] = t_my < nvalid ? t_my : -1;
+                S.kset[lane] = t_my < nvalid ? (1u << sq_) : 0u;
             }
         } else {
             Kbase = reinterpret_cast<const char *>(Kf + (size_t)h * L * D);
@@ -146,116 +186,112 @@ __global__ __launch_bounds__(256, 3) void decode_attn_shared_kernel(
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
                 const int t = lane + 64 * u;
-                const int2 rc = it[2 + (t < nrec ? t : 0)];
-                S.pos[t] = rc.x & 0xffff;
-                S.rset[t] = (uint32_t)rc.x >> 16;
-                S.delta[t] = rc.y;
+                S.pos[t] = rc[u].x & 0xffff;
+                S.rset[t] = (uint32_t)rc[u].x >> 16;
+                S.delta[t] = rc[u].y;
             }
             wave_lds_sync();
+            int lo = 0;
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const int t = lane + 64 * u;
-                int lo = 0;
-#pragma unroll
-                for (int step = KPC / 2; step > 0; step >>= 1)
-                    if (lo + step < nrec && S.pos[lo + step] <= t) lo += step;
-                const int r = t + S.delta[lo];
-                S.rows[t] = t < nvalid ? max(0, min(r, L - 1)) : -1;   // malformed input stays in the tensor
-                S.kset[t] = t < nvalid ? S.rset[lo] : 0u;
+            for (int step = KPC / 2; step > 0; step >>= 1)
+                if (lo + step < nrec && S.pos[lo + step] <= t_my) lo += step;
+            const int r = t_my + S.delta[lo];
+            const uint32_t ks = S.rset[lo];
+            if (lane < 32) {
+                S.rows[lane] = t_my < nvalid ? max(0, min(r, L - 1)) : -1;   // malformed input stays in the tensor
+                S.kset[lane] = t_my < nvalid ? ks : 0u;
             }
         }
         wave_lds_sync();
-        const int r_last = S.rows[nvalid - 1];
+        const int r_last = S.rows[min(nvalid - j0, 32) - 1];
 
-        for (int j0 = 0; j0 < nvalid; j0 += 32) {          // 32 keys per step
-            // ---- loads: K in A-operand layout (tile t: key t*16 + col, dims s*32 + kg*8 .. +8); V by key ------------
-            h8 ka[2][4], vr[8];
-            {
-                int rk[2];
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    const int r = S.rows[j0 + t * 16 + col];
-                    rk[t] = r < 0 ? r_last : r;           // slots past the end re-read a valid row
-                }
-                const int rvv = S.rows[j0 + (lane & 31)];
-                const int rv = rvv < 0 ? r_last : rvv;
-#pragma unroll
-                for (int t = 0; t < 2; ++t)
-#pragma unroll
-                    for (int s = 0; s < 4; ++s)
-                        ka[t][s] = *reinterpret_cast<const h8 *>(Kbase + (size_t)rk[t] * 256 + s * 64 + kg * 16);
-                const char *vp = Vbase + (size_t)rv * 256 + (lane >> 5) * 128;
-#pragma unroll
-                for (int c = 0; c < 8; ++c) vr[c] = *reinterpret_cast<const h8 *>(vp + c * 16);
-            }
-            // ownership bits of this lane's (key, sequence) pairs: element e = t*4 + v <-> key t*16 + kg*4 + v
-            uint32_t msk[8];
+        // ---- loads: K in A-operand layout (tile t: key t*16 + col, dims s*32 + kg*8 .. +8); V by key ----------------
+        h8 ka[2][4], vr[8];
+        {
+            int rk[2];
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
-                const uint4 ks = *reinterpret_cast<const uint4 *>(&S.kset[j0 + t * 16 + kg * 4]);
-                msk[t * 4 + 0] = (uint32_t)__builtin_amdgcn_sbfe((int)ks.x, col, 1);
-                msk[t * 4 + 1] = (uint32_t)__builtin_amdgcn_sbfe((int)ks.y, col, 1);
-                msk[t * 4 + 2] = (uint32_t)__builtin_amdgcn_sbfe((int)ks.z, col, 1);
-                msk[t * 4 + 3] = (uint32_t)__builtin_amdgcn_sbfe((int)ks.w, col, 1);
+                const int r = S.rows[t * 16 + col];
+                rk[t] = r < 0 ? r_last : r;               // slots past the end re-read a valid row
             }
-
-            // ---- S^T = K Q^T -----------------------------------------------------------------------------------------
-            f4 sacc[2];
+            const int rvv = S.rows[lane & 31];
+            const int rv = rvv < 0 ? r_last : rvv;
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                sacc[t] = f4{0.f, 0.f, 0.f, 0.f};
+            for (int t = 0; t < 2; ++t)
 #pragma unroll
                 for (int s = 0; s < 4; ++s)
-                    sacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][s], bq[s], sacc[t], 0, 0, 0);
-            }
+                    ka[t][s] = *reinterpret_cast<const h8 *>(Kbase + (size_t)rk[t] * 256 + s * 64 + kg * 16);
+            const char *vp = Vbase + (size_t)rv * 256 + (lane >> 5) * 128;
+#pragma unroll
+            for (int c = 0; c < 8; ++c) vr[c] = *reinterpret_cast<const h8 *>(vp + c * 16);
+        }
+        if (item + 1 < item_end) prefetch(item + 1);
+        // ownership bits of this lane's (key, sequence) pairs: element e = t*4 + v <-> key t*16 + kg*4 + v
+        uint32_t msk[8];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const uint4 ks = *reinterpret_cast<const uint4 *>(&S.kset[t * 16 + kg * 4]);
+            msk[t * 4 + 0] = (uint32_t)__builtin_amdgcn_sbfe((int)ks.x, col, 1);
+            msk[t * 4 + 1] = (uint32_t)__builtin_amdgcn_sbfe((int)ks.y, col, 1);
+            msk[t * 4 + 2] = (uint32_t)__builtin_amdgcn_sbfe((int)ks.z, col, 1);
+            msk[t * 4 + 3] = (uint32_t)__builtin_amdgcn_sbfe((int)ks.w, col, 1);
+        }
 
-            // ---- V -> wave-private LDS, transposed: lane = key (lane % 32), dims (lane / 32) * 64 + c*8 + e --------
-            {
-                _Float16 *vt = S.Vt + (lane >> 5) * 64 * SV_STRIDE + sv_pos(lane & 31);
+        // ---- S^T = K Q^T ---------------------------------------------------------------------------------------------
+        f4 sacc[2];
 #pragma unroll
-                for (int c = 0; c < 8; ++c)
+        for (int t = 0; t < 2; ++t) {
+            sacc[t] = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) vt[(c * 8 + e) * SV_STRIDE] = vr[c][e];
-            }
+            for (int s = 0; s < 4; ++s)
+                sacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][s], bq[s], sacc[t], 0, 0, 0);
+        }
 
-            // ---- online softmax of column `col` -------------------------------------------------------------------
-            float sv[8];
-            float mx = SQ_NEG_INF;
+        // ---- V -> wave-private LDS, transposed: lane = key (lane % 32), dims (lane / 32) * 64 + c*8 + e ------------
+        {
+            _Float16 *vt = S.Vt + (lane >> 5) * 64 * SV_STRIDE + sv_pos(lane & 31);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float sraw = sacc[e >> 2][e & 3];    // (a copy: the bit cast below must not see a vector element)
-                const uint32_t bits = __builtin_bit_cast(uint32_t, sraw);
-                sv[e] = __builtin_bit_cast(float, (msk[e] & bits) | (~msk[e] & 0xff800000u));   // not owned: -inf
-                mx = fmaxf(mx, sv[e]);
-            }
-            mx = cross16_max(mx);                          // the 4 lane groups hold the other keys of the column
-            const float m_new = fmaxf(m_run, mx);
-            const float mneg = m_new == SQ_NEG_INF ? 0.0f : -m_new * c2;   // nothing seen yet: exp2(-inf) = 0
-            const float alpha = __builtin_amdgcn_exp2f(fmaf(m_run, c2, mneg));
-            float psum = 0.0f;
+            for (int c = 0; c < 8; ++c)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                sv[e] = __builtin_amdgcn_exp2f(fmaf(sv[e], c2, mneg));
-                psum += sv[e];
-            }
-            m_run = m_new;
-            l_run = l_run * alpha + psum;
-            if (__ballot(alpha != 1.0f) != 0ull) {
-#pragma unroll
-                for (int dt = 0; dt < 8; ++dt) o[dt] *= alpha;
-            }
-            h8 bp;                                         // P^T operand: sequence col, keys at positions kg*8 .. +8
-#pragma unroll
-            for (int e = 0; e < 8; ++e) bp[e] = (_Float16)sv[e];
+                for (int e = 0; e < 8; ++e) vt[(c * 8 + e) * SV_STRIDE] = vr[c][e];
+        }
 
-            // ---- O^T += V^T P^T -------------------------------------------------------------------------------------
-            wave_lds_sync();                               // V^T is written
+        // ---- online softmax of column `col` -----------------------------------------------------------------------
+        float sv[8];
+        float mx = SQ_NEG_INF;
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt) {
-                const h8 a = *reinterpret_cast<const h8 *>(S.Vt + (dt * 16 + col) * SV_STRIDE + kg * 8);
-                o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bp, o[dt], 0, 0, 0);
-            }
-            wave_lds_sync();                               // V^T is read before the next step overwrites it
+        for (int e = 0; e < 8; ++e) {
+            const float sraw = sacc[e >> 2][e & 3];        // (a copy: the bit cast below must not see a vector element)
+            const uint32_t bits = __builtin_bit_cast(uint32_t, sraw);
+            sv[e] = __builtin_bit_cast(float, (msk[e] & bits) | (~msk[e] & 0xff800000u));   // not owned: -inf
+            mx = fmaxf(mx, sv[e]);
+        }
+        mx = cross16_max(mx);                              // the 4 lane groups hold the other keys of the column
+        const float m_new = fmaxf(m_run, mx);
+        const float mneg = m_new == SQ_NEG_INF ? 0.0f : -m_new * c2;   // nothing seen yet: exp2(-inf) = 0
+        const float alpha = __builtin_amdgcn_exp2f(fmaf(m_run, c2, mneg));
+        float psum = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            sv[e] = __builtin_amdgcn_exp2f(fmaf(sv[e], c2, mneg));
+            psum += sv[e];
+        }
+        m_run = m_new;
+        l_run = l_run * alpha + psum;
+        if (__ballot(alpha != 1.0f) != 0ull) {
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) o[dt] *= alpha;
+        }
+        h8 bp;                                             // P^T operand: sequence col, keys at positions kg*8 .. +8
+#pragma unroll
+        for (int e = 0; e < 8; ++e) bp[e] = (_Float16)sv[e];
+
+        // ---- O^T += V^T P^T -----------------------------------------------------------------------------------------
+        wave_lds_sync();                                   // V^T is written
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+            const h8 a = *reinterpret_cast<const h8 *>(S.Vt + (dt * 16 + col) * SV_STRIDE + kg * 8);
+            o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bp, o[dt], 0, 0, 0);
         }
     }
     flush(cur_row);
@@ -265,7 +301,7 @@ __global__ __launch_bounds__(256, 3) void decode_attn_shared_kernel(
 // that sequence.
 __global__ __launch_bounds__(MERGE_THREADS) void decode_merge_shared_kernel(const float *__restrict__ partials,
                                                                             DecodePlan plan, _Float16 *__restrict__ out,
-                                                                            float *__restrict__ lse, int H, int n_waves)
+                                                                            float *__restrict__ lse, int H, int attn_grid)
 {
     __shared__ float s_red[MERGE_GROUPS * 130];
     const size_t bh = blockIdx.x;
@@ -274,7 +310,7 @@ __global__ __launch_bounds__(MERGE_THREADS) void decode_merge_shared_kernel(cons
     const int2 it = plan.row_items[urow];            // (first item, items) of the union row
     const int rank = plan.row_rank[urow];
     const int total = min(plan.total[0], plan.item_cap);
-    const int ki = max(1, (total + n_waves - 1) / n_waves);        // items per attention wave
+    const int ki = max(1, (total + attn_grid - 1) / attn_grid);    // items per attention workgroup
     const int w_lo = it.x / ki;
     const int n = it.y == 0 ? 0 : (it.x + it.y - 1) / ki - w_lo + 1;
     auto slot_ptr = [&](int c) { return partials + ((size_t)(w_lo + c + rank) * SG + sq_) * PART_STRIDE; };
@@ -286,16 +322,15 @@ hipError_t launch_decode_attn_shared(const void *q, const void *Kf, const void *
                                      hipStream_t s)
 {
     const int rows = sh.B * sh.H;
-    static_assert(SHARED_ATTN_WAVES % 4 == 0, "four waves per workgroup");
     const bool prof = profile_mark(s, true);
-    hipLaunchKernelGGL(decode_attn_shared_kernel, dim3(SHARED_ATTN_WAVES / 4), dim3(256), 0, s, (const _Float16 *)q,
+    hipLaunchKernelGGL(decode_attn_shared_kernel, dim3(SHARED_ATTN_GRID), dim3(256), 0, s, (const _Float16 *)q,
                        (const _Float16 *)Kf, (const _Float16 *)Vf, (const _Float16 *)Ku, (const _Float16 *)Vu, plan,
                        partials, sh.B, sh.H, sh.L, sh.U, sh.sm_scale);
     if (prof) profile_mark(s, false);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(decode_merge_shared_kernel, dim3(rows), dim3(MERGE_THREADS), 0, s, partials, plan,
-                       (_Float16 *)out, lse, sh.H, SHARED_ATTN_WAVES);
+                       (_Float16 *)out, lse, sh.H, SHARED_ATTN_GRID);
     return hipGetLastError();
 }
 

@@ -71,8 +71,8 @@ struct SelectOpts {
 // sequences << 16).
 constexpr int SG = 16;
 inline int seq_groups_for(int B) { return (B + SG - 1) / SG; }
-// Waves of the shared-context partial kernel (each works alone): three workgroups of four per compute unit.
-constexpr int SHARED_ATTN_WAVES = 256 * 12;
+// Workgroups of the shared-context partial kernel: three per compute unit.
+constexpr int SHARED_ATTN_GRID = 256 * 3;
 
 // stats_in == true: use row_max/denom; false: the kernel derives them from logits itself.
 hipError_t launch_select(const float *logits, const float *row_max, const float *denom, bool stats_in,
@@ -93,7 +93,7 @@ hipError_t launch_decode_attn(const void *q, const void *Kf, const void *Vf, con
                               hipStream_t s);
 
 // Shared-context decode: work items of every union row from the per-sequence keep masks (needs the two
-// counters at plan.total zeroed), and the partial + merge kernels.  partials: (SHARED_ATTN_WAVES + union
+// counters at plan.total zeroed), and the partial + merge kernels.  partials: (SHARED_ATTN_GRID + union
 // rows) * SG slots of PART_STRIDE floats.
 hipError_t launch_union_schedule(const uint32_t *keep_masks, const int32_t *sizes, const int32_t *offsets,
                                  DecodePlan plan, int32_t *n_ranges_u, int32_t *n_keys_u, int U, int B, int H, int C,
