@@ -136,7 +136,7 @@ StepWs carve_step(Carver &cv, const sq_shape_t *sh)
 // rows' plan and the partials of the shared-context kernel.
 struct SharedStepWs {
     float *logits;
-    int32_t *n_ranges, *n_keys, *n_ranges_u, *n_keys_u;
+    int32_t *n_ranges, *n_keys;
     uint32_t *mask;
     sq::DecodePlan plan;
     float *partials;
@@ -151,8 +151,6 @@ SharedStepWs carve_step_shared(Carver &cv, const sq_shape_t *sh)
     w.logits = cv.take<float>(rows * sh->C);
     w.n_ranges = cv.take<int32_t>(rows);
     w.n_keys = cv.take<int32_t>(rows);
-    w.n_ranges_u = cv.take<int32_t>(urows);
-    w.n_keys_u = cv.take<int32_t>(urows);
     w.mask = cv.take<uint32_t>(rows * ((sh->C + 31) / 32));
     w.plan.rec_cap = sh->C;
     w.plan.L = sh->L;
@@ -370,11 +368,8 @@ int sq_decode_step(const sq_shape_t *sh, const void *q, const void *centroids, c
         SharedStepWs w = carve_step_shared(cv, sh);
         uint32_t *mask = keep_mask ? keep_mask : w.mask;
         SQ_HIP(sq::launch_score(q, centroids, w.logits, w.plan.total, sh->B, sh->H, 1, sh->C, sh->sm_scale, s));
-        SQ_HIP(sq::launch_select(w.logits, nullptr, nullptr, false, thresh, sizes, offsets, mask, nullptr, w.n_ranges,
-                                 n_keys ? n_keys : w.n_keys, sq::DecodePlan{}, false, 0, sq::SelectOpts{}, rows, sh->H,
-                                 1, sh->C, s));
-        SQ_HIP(sq::launch_union_schedule(mask, sizes, offsets, w.plan, w.n_ranges_u, w.n_keys_u, sh->U, sh->B, sh->H,
-                                         sh->C, s));
+        SQ_HIP(sq::launch_union_schedule(w.logits, thresh, sizes, offsets, mask, w.n_ranges,
+                                         n_keys ? n_keys : w.n_keys, w.plan, sh->U, sh->B, sh->H, sh->C, s));
         SQ_HIP(sq::launch_decode_attn_shared(q, K_fixed, V_fixed, K_user, V_user, w.plan, w.partials, out, lse,
                                              to_shape(sh), s));
         g_err[0] = 0;

@@ -59,8 +59,8 @@ struct SelectOpts {
     const uint32_t *parent_mask;     // level 2: keep mask of the coarse level [B*H, ceil(C1/32)]
     int C1;
     int len_from_offsets;            // level 1: emitted range length = offsets[i+1] - offsets[i] (child clusters)
-    const uint32_t *union_masks;     // shared-context scheduling: keep masks of all sequences [B*H, ceil(C/32)]
-    int B;                           // shared-context scheduling: number of sequences
+    int union_rows;                  // shared-context decode: rows are union rows (sequence group, head)
+    int B;                           // shared-context decode: number of sequences
 };
 
 // Batched decode over a shared fixed context: sequences are handled in groups of SG; a "union row" is one
@@ -92,12 +92,12 @@ hipError_t launch_decode_attn(const void *q, const void *Kf, const void *Vf, con
                               DecodePlan plan, float *partials, void *out, float *lse, const Shape &sh,
                               hipStream_t s);
 
-// Shared-context decode: work items of every union row from the per-sequence keep masks (needs the two
-// counters at plan.total zeroed), and the partial + merge kernels.  partials: (SHARED_ATTN_GRID + union
+// Shared-context decode: per-sequence selection (keep_masks, n_ranges, n_keys: [B*H] rows) and the work items of
+// every union row in one launch (needs the two counters at plan.total zeroed), and the partial + merge kernels.  partials: (SHARED_ATTN_GRID + union
 // rows) * SG slots of PART_STRIDE floats.
-hipError_t launch_union_schedule(const uint32_t *keep_masks, const int32_t *sizes, const int32_t *offsets,
-                                 DecodePlan plan, int32_t *n_ranges_u, int32_t *n_keys_u, int U, int B, int H, int C,
-                                 hipStream_t s);
+hipError_t launch_union_schedule(const float *logits, const float *thresh, const int32_t *sizes,
+                                 const int32_t *offsets, uint32_t *keep_masks, int32_t *n_ranges, int32_t *n_keys,
+                                 DecodePlan plan, int U, int B, int H, int C, hipStream_t s);
 hipError_t launch_decode_attn_shared(const void *q, const void *Kf, const void *Vf, const void *Ku, const void *Vu,
                                      DecodePlan plan, float *partials, void *out, float *lse, const Shape &sh,
                                      hipStream_t s);

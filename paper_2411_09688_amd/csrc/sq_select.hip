@@ -119,9 +119,96 @@ __device__ __forceinline__ void emit_row_items(const DecodePlan &plan, int row, 
     }
 }
 
-// UNION: the row is a union row (sequence group, head) of a batched decode over a shared context; there are
-// no logits: cluster i is kept iff any sequence of the group has it in its keep mask (opt.union_masks), and the
-// set of those sequences travels with the record.  Always with SCHEDULE.
+// Selection of one query row by ONE wave, mask and counts only: keep cluster i iff N_i > 0 and
+// exp(x_i - m) > T * D.  The row statistics (m, D) are given (STATS_IN) or derived here in the library's one
+// summation order (see wave_row_stats), so the decision is bit-identical to the row-wise selection kernel.
+// A row of up to 1024 clusters is held in registers after a single round of loads.
+template <bool STATS_IN>
+__device__ __forceinline__ void wave_select_mask(const float *__restrict__ x, const int32_t *__restrict__ N, int C, float T,
+                                                 float m_in, float D_in, uint32_t *__restrict__ mask_row,
+                                                 int32_t *n_ranges_out, int32_t *n_keys_out, int lane)
+{
+    const int W = (C + 31) >> 5;
+    int cnt = 0, keys = 0;
+    if (C <= 1024) {
+        float xv[16];
+        int nv[16];
+#pragma unroll
+        for (int g = 0; g < 16; ++g) {
+            const int i = g * 64 + lane;
+            nv[g] = i < C ? N[i] : 0;
+            xv[g] = i < C ? x[i] : 0.0f;
+        }
+        float m = m_in, Dsum = D_in;
+        if (!STATS_IN) {
+            m = SQ_NEG_INF;
+#pragma unroll
+            for (int g = 0; g < 16; ++g)
+                if (nv[g] > 0) m = fmaxf(m, xv[g]);
+            m = wave_max(m);
+        }
+#pragma unroll
+        for (int g = 0; g < 16; ++g) xv[g] = nv[g] > 0 ? expf(xv[g] - m) : 0.0f;   // e_i, stored (Appendix D)
+        if (!STATS_IN) {
+            Dsum = 0.0f;
+#pragma unroll
+            for (int g = 0; g < 16; ++g)                       // rounded products: nothing may be fused into the sums
+                Dsum += wave_sum(nv[g] > 0 ? __fmul_rn((float)nv[g], xv[g]) : 0.0f);
+        }
+        const float thr = T * Dsum;
+#pragma unroll
+        for (int g = 0; g < 16; ++g) {
+            if (g * 64 >= C) break;
+            const bool keep = nv[g] > 0 && xv[g] > thr;
+            const unsigned long long bal = __ballot(keep);
+            if (lane == 0) {
+                const int w0 = g * 2;
+                mask_row[w0] = (uint32_t)bal;
+                if (w0 + 1 < W) mask_row[w0 + 1] = (uint32_t)(bal >> 32);
+            }
+            cnt += __popcll(bal);
+            keys += keep ? nv[g] : 0;
+        }
+    } else {
+        float m = m_in, Dsum = D_in;
+        if (!STATS_IN) wave_row_stats(x, N, C, lane, m, Dsum);
+        const float thr = T * Dsum;
+        for (int i0 = 0; i0 < C; i0 += 64 * 4) {                 // four loads in flight
+            float xv[4];
+            int nv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = i0 + u * 64 + lane;
+                nv[u] = i < C ? N[i] : 0;
+                xv[u] = i < C ? x[i] : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = i0 + u * 64;                       // first cluster of this 64-wide step
+                if (i >= C) break;
+                const bool keep = nv[u] > 0 && expf(xv[u] - m) > thr;
+                const unsigned long long bal = __ballot(keep);
+                if (lane == 0) {
+                    const int w0 = i >> 5;
+                    mask_row[w0] = (uint32_t)bal;
+                    if (w0 + 1 < W) mask_row[w0 + 1] = (uint32_t)(bal >> 32);
+                }
+                cnt += __popcll(bal);
+                keys += keep ? nv[u] : 0;
+            }
+        }
+    }
+    keys = wave_sum_i(keys);
+    if (lane == 0) {
+        *n_ranges_out = cnt;
+        *n_keys_out = keys;
+    }
+}
+
+// UNION: the row is a union row (sequence group, head) of a batched decode over a shared context.  First every
+// sequence of the group is selected by one wave of the workgroup (logits [B*H, C]; keep_mask, n_ranges, n_keys
+// are the per-sequence outputs), then cluster i is kept for the union row iff any sequence of the group kept
+// it, and the set of those sequences travels with the record.  Always with SCHEDULE.
 template <bool STATS_IN, bool SCHEDULE, bool UNION = false>
 __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     const float *__restrict__ logits, const float *__restrict__ row_max, const float *__restrict__ denom,
@@ -143,15 +230,28 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     const int32_t *off = offsets + (size_t)h * (C + 1);
     const int W = (C + 31) >> 5;
     const float T = UNION ? 0.0f : thresh[h];
+    (void)T;
     uint32_t *s_set = reinterpret_cast<uint32_t *>(s_e);   // UNION: set of sequences per cluster instead of e_i
     const int n_seq = UNION ? min(SG, opt.B - (int)(row / H) * SG) : 1;
 
     if (UNION) {
-        const uint32_t *m0 = opt.union_masks + ((size_t)(row / H) * SG * H + h) * W;   // sequence s: + s * H * W
+        static_assert(SG == SEL_WAVES, "one wave per sequence of the group");
+        const size_t bh0 = (size_t)(row / H) * SG * H + h;           // row of sequence 0 of the group; sequence s: + s * H
+        if (wave < n_seq) {
+            const size_t bh = bh0 + (size_t)wave * H;
+            wave_select_mask<false>(logits + bh * C, N, C, thresh[h], 0.0f, 0.0f, keep_mask + bh * W, n_ranges + bh,
+                                    n_keys + bh, lane);
+        }
+        __threadfence_block();
+        __syncthreads();                                             // the group's masks are written
+        const uint32_t *m0 = keep_mask + bh0 * W;
         for (int i = tid; i < C; i += SEL_THREADS) {
             uint32_t set = 0u;
-            for (int sq_ = 0; sq_ < n_seq; ++sq_)
-                set |= ((m0[(size_t)sq_ * H * W + (i >> 5)] >> (i & 31)) & 1u) << sq_;
+#pragma unroll
+            for (int sq_ = 0; sq_ < SG; ++sq_) {                     // independent loads
+                const uint32_t word = sq_ < n_seq ? m0[(size_t)sq_ * H * W + (i >> 5)] : 0u;
+                set |= ((word >> (i & 31)) & 1u) << sq_;
+            }
             s_set[i] = set;
             s_N[i] = N[i];
         }
@@ -242,7 +342,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
         if (lane == 0) {
             s_tcnt[st * SEL_WAVES + wave] = __popcll(bal_emit);
             s_tkeys[st * SEL_WAVES + wave] = wkeys;
-            if (keep_mask) {
+            if (keep_mask && !UNION) {                   // (a union row has no mask of its own)
                 const int w0 = (i >> 5);
                 if (w0 < W) keep_mask[row * W + w0] = (uint32_t)bal;
                 if (w0 + 1 < W) keep_mask[row * W + w0 + 1] = (uint32_t)(bal >> 32);
@@ -307,8 +407,10 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
         }
     }
     if (tid == 0) {
-        n_ranges[row] = base_r;
-        n_keys[row] = base_k;
+        if (!UNION) {                                        // a union row has no outputs of its own
+            n_ranges[row] = base_r;
+            n_keys[row] = base_k;
+        }
         if (plan.rec) plan.hdr[row] = make_int2(base_r, base_k);
     }
     if (SCHEDULE) {
@@ -338,7 +440,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
 }
 
 // Mask-only selection, one wave per query row and no LDS: the form prefill uses, where tens of thousands
-// of rows each need only their keep mask and counts (no ranges).  Same keep rule, same statistics.
+// of rows each need only their keep mask and counts (no ranges).
 template <bool STATS_IN>
 __global__ __launch_bounds__(256) void select_mask_kernel(const float *__restrict__ logits,
                                                           const float *__restrict__ row_max,
@@ -353,47 +455,9 @@ __global__ __launch_bounds__(256) void select_mask_kernel(const float *__restric
     const size_t row = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= (size_t)rows) return;
     const int h = (int)((row / Lq) % H);
-    const float *x = logits + row * C;
-    const int32_t *N = sizes + (size_t)h * C;
     const int W = (C + 31) >> 5;
-    float m, Dsum;
-    if (STATS_IN) {
-        m = row_max[row];
-        Dsum = denom[row];
-    } else {
-        wave_row_stats(x, N, C, lane, m, Dsum);
-    }
-    const float thr = thresh[h] * Dsum;
-    int cnt = 0, keys = 0;
-    for (int i0 = 0; i0 < C; i0 += 64 * 4) {                 // four loads in flight
-        float xv[4];
-        int nv[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int i = i0 + u * 64 + lane;
-            nv[u] = i < C ? N[i] : 0;
-            xv[u] = i < C ? x[i] : 0.0f;
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int i = i0 + u * 64;                       // first cluster of this 64-wide step
-            if (i >= C) break;
-            const bool keep = nv[u] > 0 && expf(xv[u] - m) > thr;
-            const unsigned long long bal = __ballot(keep);
-            if (lane == 0) {
-                const int w0 = i >> 5;
-                keep_mask[row * W + w0] = (uint32_t)bal;
-                if (w0 + 1 < W) keep_mask[row * W + w0 + 1] = (uint32_t)(bal >> 32);
-            }
-            cnt += __popcll(bal);
-            keys += keep ? nv[u] : 0;
-        }
-    }
-    keys = wave_sum_i(keys);
-    if (lane == 0) {
-        n_ranges[row] = cnt;
-        n_keys[row] = keys;
-    }
+    wave_select_mask<STATS_IN>(logits + row * C, sizes + (size_t)h * C, C, thresh[h], STATS_IN ? row_max[row] : 0.0f,
+                               STATS_IN ? denom[row] : 0.0f, keep_mask + row * W, n_ranges + row, n_keys + row, lane);
 }
 
 // Caller-provided ranges -> records (start, count, keys before) + header.  Empty ranges are dropped.
@@ -491,8 +555,8 @@ hipError_t launch_select(const float *logits, const float *row_max, const float 
         attr_set = true;
     }
     const int nuc = user_chunks_for(U);
-    if (opt.union_masks) {
-        if (!schedule) return hipErrorInvalidValue;
+    if (opt.union_rows) {
+        if (!schedule || !keep_mask || !logits) return hipErrorInvalidValue;
         hipLaunchKernelGGL((select_kernel<false, true, true>), dim3(rows), dim3(SEL_THREADS), smem, s, logits, row_max,
                            denom, thresh, sizes, offsets, keep_mask, ranges, n_ranges, n_keys, plan, opt, H, Lq, C, U,
                            nuc);
@@ -509,15 +573,15 @@ hipError_t launch_select(const float *logits, const float *row_max, const float 
     return hipGetLastError();
 }
 
-hipError_t launch_union_schedule(const uint32_t *keep_masks, const int32_t *sizes, const int32_t *offsets,
-                                 DecodePlan plan, int32_t *n_ranges_u, int32_t *n_keys_u, int U, int B, int H, int C,
-                                 hipStream_t s)
+hipError_t launch_union_schedule(const float *logits, const float *thresh, const int32_t *sizes,
+                                 const int32_t *offsets, uint32_t *keep_masks, int32_t *n_ranges, int32_t *n_keys,
+                                 DecodePlan plan, int U, int B, int H, int C, hipStream_t s)
 {
     SelectOpts opt{};
-    opt.union_masks = keep_masks;
+    opt.union_rows = 1;
     opt.B = B;
-    return launch_select(nullptr, nullptr, nullptr, false, nullptr, sizes, offsets, nullptr, nullptr, n_ranges_u,
-                         n_keys_u, plan, true, U, opt, seq_groups_for(B) * H, H, 1, C, s);
+    return launch_select(logits, nullptr, nullptr, false, thresh, sizes, offsets, keep_masks, nullptr, n_ranges,
+                         n_keys, plan, true, U, opt, seq_groups_for(B) * H, H, 1, C, s);
 }
 
 hipError_t launch_ranges_to_rec(const int32_t *ranges, const int32_t *n_ranges, DecodePlan plan, int rows,
