@@ -168,7 +168,11 @@ int sq_hier_select(const sq_shape_t *shape, int32_t C1, const void *q,
  * enqueued back to back with the intermediate results kept in the workspace -- the end-to-end
  * quantity the paper times (lookup + argument set-up + sparse attention, Appendix "Kernel
  * Benchmarking").  The selection is bit-identical to the three separate calls; the attention output
- * agrees up to fp32 rounding (the keys are split over workgroups differently).
+ * agrees up to rounding (the keys are split over workgroups differently).
+ * With B >= 2 the sequences share K_fixed/V_fixed (the shared-prefix setting of Section 1): each
+ * sequence still selects on its own, but the step streams the union of the selections of every group
+ * of 16 sequences, so a key kept by several sequences is read once; the probabilities are rounded to
+ * fp16 before they multiply V (matrix-core product, fp32 accumulation), as in sq_sparse_attn_prefill.
  * Out: out f16 [B,H,1,d]; optional (NULL to skip): lse f32 [B,H,1], keep_mask u32 [B,H,1,ceil(C/32)],
  *      n_keys i32 [B,H,1].
  * Workspace: sq_workspace_bytes(shape, SQ_CALL_DECODE_STEP).

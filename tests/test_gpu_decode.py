@@ -158,6 +158,73 @@ def test_empty_selection_and_no_user_keys(sq, oracle):
     compare_decode(oracle, w2, P2, oracle_one_level(oracle, w2), "user-only")
 
 
+def step_against_oracle(sq, oracle, w, label, keep_mask=True):
+    """sq_decode_step alone, compared with the oracle directly (selection, counts, attention)."""
+    P = sq.upload(w)
+    sh = P.shape
+    ws = sq.workspace(sh, sq.SQ_CALL_DECODE_STEP, P.q.device)
+    P.out.fill_(7.0)
+    sq.sq_decode_step(sh, P.q, P.centroids, P.sizes, P.offsets, P.thresh, P.K_fixed, P.V_fixed, P.K_user, P.V_user,
+                      P.out, P.lse, P.keep_mask if keep_mask else None, P.n_keys, ws)
+    torch.cuda.synchronize()
+    ref = oracle_one_level(oracle, w)
+    ok = unpack_mask(ref["mask"], w.C)
+    if keep_mask:
+        gk = unpack_mask(P.keep_mask.cpu().numpy(), w.C)
+        listed = check_selection(w, gk, ok, w.thresh, label=label)
+    else:
+        gk, listed = ok, []
+    np.testing.assert_array_equal(P.n_keys.cpu().numpy(), (gk * w.sizes[None, :, None, :]).sum(-1))
+    ranges = np.zeros_like(ref["ranges"]); n_r = np.zeros_like(ref["n_ranges"])
+    for b in range(w.B):
+        for h in range(w.H):
+            ranges[b, h, 0], n_r[b, h, 0] = ranges_from_keep(gk[b, h, 0], w.offsets[h], w.sizes[h], w.C)
+    out, lse = oracle.sparse_attn(w.q, w.K_fixed, w.V_fixed, ranges, n_r, w.K_user, w.V_user, w.sm_scale)
+    err = np.abs(P.out.cpu().numpy().astype(np.float64) - out).max()
+    assert err <= ATTN_ATOL, f"{label}: attention max-abs error {err}"
+    got = P.lse.cpu().numpy()
+    fin = np.isfinite(lse)
+    assert (np.isneginf(got) == ~fin).all()
+    np.testing.assert_allclose(got[fin], lse[fin], atol=1e-4, rtol=1e-5)
+    return listed
+
+
+@pytest.mark.parametrize("case", [
+    dict(B=2, H=2, L=900, C=30, U=5, keep_frac=0.3),               # smallest batch that takes the shared-context kernels
+    dict(B=5, H=3, L=3000, C=100, U=300, keep_frac=0.5),           # partial group; user chunks with a ragged tail
+    dict(B=16, H=2, L=2000, C=50, U=0, keep_frac=0.2),             # one full group, no user keys
+    dict(B=33, H=1, L=1500, C=65, U=40, keep_frac=0.25),           # three groups, the last with one sequence
+    dict(B=3, H=2, L=4096, C=2048, U=17, keep_frac=0.2),           # more clusters than one selection step holds
+    dict(B=4, H=1, L=70000, C=300, U=130, keep_frac=0.6),          # several workgroups per union row, long clusters
+])
+def test_shared_context_step_against_oracle(sq, oracle, case):
+    w = wl.calibrate(wl.make_workload("shared", Lq=1, seed=11, threads=4, **case), oracle.scores)
+    step_against_oracle(sq, oracle, w, f"shared{case}")
+
+
+def test_shared_context_step_extremes(sq, oracle):
+    base = dict(B=6, H=2, L=1024, C=32, Lq=1, U=33, keep_frac=0.5, seed=12, threads=2)
+    # every sequence keeps everything: each key is owned by all sequences of the group
+    w = wl.make_workload("shared_all", **base)
+    w.thresh = np.full(w.H, -1.0, np.float32)
+    step_against_oracle(sq, oracle, w, "shared keep-all")
+    # nothing kept: user keys only; and without the optional mask output
+    w = wl.make_workload("shared_none", **base)
+    w.thresh = np.full(w.H, 2.0, np.float32)
+    step_against_oracle(sq, oracle, w, "shared keep-none", keep_mask=False)
+    # nothing at all to attend to
+    w = wl.make_workload("shared_empty", **dict(base, U=0))
+    w.thresh = np.full(w.H, 2.0, np.float32)
+    P = sq.upload(w)
+    P.out.fill_(7.0)
+    ws = sq.workspace(P.shape, sq.SQ_CALL_DECODE_STEP, P.q.device)
+    sq.sq_decode_step(P.shape, P.q, P.centroids, P.sizes, P.offsets, P.thresh, P.K_fixed, P.V_fixed, P.K_user,
+                      P.V_user, P.out, P.lse, P.keep_mask, P.n_keys, ws)
+    torch.cuda.synchronize()
+    assert (P.out.cpu().numpy() == 0).all() and np.isneginf(P.lse.cpu().numpy()).all()
+    assert (P.n_keys.cpu().numpy() == 0).all() and (P.keep_mask.cpu().numpy() == 0).all()
+
+
 def test_caller_ranges_with_gaps_and_empty_entries(sq, oracle, cfg1):
     # sq_sparse_attn_decode on ranges that did not come from sq_select: merged, with zero-length entries.
     w = cfg1
