@@ -93,6 +93,24 @@ def select(logits, row_max, denom, thresh, sizes, offsets):
     return mask, ranges, n_ranges, n_keys
 
 
+def select_mean(logits, row_max, denom, thresh, sizes, offsets, want_scores: bool = False):
+    """Prefill selection on scores averaged over the Lq query tokens (Appendix D).
+    -> keep_mask [B,H,ceil(C/32)] u32, ranges [B,H,C,2] i32, n_ranges, n_keys [B,H] i32 [, mean scores [B,H,C] f64]."""
+    logits, row_max, denom, thresh = _f32(logits), _f32(row_max), _f32(denom), _f32(thresh)
+    sizes, offsets = _i32(sizes), _i32(offsets)
+    B, H, Lq, Cn = logits.shape
+    assert thresh.shape == (H,) and sizes.shape == (H, Cn) and offsets.shape == (H, Cn + 1)
+    W = (Cn + 31) // 32
+    mask = np.empty((B, H, W), np.uint32)
+    ranges = np.zeros((B, H, Cn, 2), np.int32)
+    n_ranges = np.empty((B, H), np.int32)
+    n_keys = np.empty((B, H), np.int32)
+    sbar = np.empty((B, H, Cn), np.float64) if want_scores else None
+    lib().oracle_select_mean(B, H, Lq, Cn, _p(logits), _p(row_max), _p(denom), _p(thresh), _p(sizes), _p(offsets),
+                             _p(mask), _p(ranges), _p(n_ranges), _p(n_keys), _p(sbar))
+    return (mask, ranges, n_ranges, n_keys, sbar) if want_scores else (mask, ranges, n_ranges, n_keys)
+
+
 def hier_select(q, centroids1, sizes1, child_offsets, thresh1, centroids2, sizes2, offsets2, thresh2, sm_scale,
                 want_logits2: bool = False):
     """Two-level lookup, q [B,H,1,d] or [B,H,d].  Returns dict(mask1, mask2, ranges, n_ranges, n_keys, stats[, logits2])."""

@@ -30,6 +30,13 @@ def select(q, centroids, sizes, thresh, sm_scale):
     return (S > np.float64(thresh)) & (np.asarray(sizes)[None, :] > 0), S
 
 
+def select_mean(q, centroids, sizes, thresh, sm_scale):
+    """Prefill rule of Appendix D for one head: Eq. 1 per query token, averaged over the tokens, then > T.
+    q [Lq,d] -> (kept [C] bool, mean scores [C])."""
+    Sbar = scores(q, centroids, sizes, sm_scale).mean(axis=0)
+    return (Sbar > np.float64(thresh)) & (np.asarray(sizes) > 0), Sbar
+
+
 def near_threshold(S, thresh, band: float = NEAR_BAND) -> np.ndarray:
     """Clusters whose score is within `band` of the threshold in the log domain."""
     S = np.asarray(S, dtype=np.float64)

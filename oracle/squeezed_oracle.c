@@ -16,6 +16,10 @@
  *                           and the kept clusters' key ranges (the key-index
  *                           tensor of Section 4.2, as ranges because keys are
  *                           stored sorted by cluster).
+ *   oracle_select_mean      the prefill rule of Appendix D "Prefill Stage": the scores
+ *                           of Eq. 1 are averaged over all query tokens of a
+ *                           (sequence, head) and the average is compared with T,
+ *                           giving one kept set shared by the query tokens.
  *   oracle_hier_select      Eq. 2 and Eq. 3 (Section 3.3): level 1 on the coarse
  *                           centroids, level 2 on the children of the kept
  *                           coarse clusters with the normaliser over those
@@ -164,6 +168,54 @@ void oracle_select(int B, int H, int Lq, int C,
                 n_ranges[r] = nr;
                 n_keys[r] = nk;
             }
+}
+
+/*
+ * Prefill selection with averaged scores (Appendix D, "Prefill Stage"): for every (b,h),
+ *   Sbar_i = (1/Lq) * sum_t S_i(t),   S_i(t) = exp(x_i(t) - m(t)) / D(t)   (Eq. 1 per query token, fp32),
+ * and cluster i is kept iff N_i > 0 and Sbar_i > T (strict).  The average is accumulated in fp64 over t in
+ * ascending order.  keep_mask [B,H,ceil(C/32)], ranges [B,H,C,2], n_ranges, n_keys [B,H];
+ * mean_scores (may be NULL) [B,H,C] receives Sbar.
+ */
+void oracle_select_mean(int B, int H, int Lq, int C,
+                        const float *logits, const float *row_max, const float *denom,
+                        const float *thresh, const int32_t *sizes, const int32_t *offsets,
+                        uint32_t *keep_mask, int32_t *ranges, int32_t *n_ranges, int32_t *n_keys,
+                        double *mean_scores)
+{
+    int W = (C + 31) / 32;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < H; ++h) {
+            size_t bh = (size_t)b * H + h;
+            const int32_t *N = sizes + (size_t)h * C;
+            const int32_t *off = offsets + (size_t)h * (C + 1);
+            uint32_t *mask = keep_mask + bh * W;
+            int32_t *rg = ranges + bh * (size_t)C * 2;
+            memset(mask, 0, sizeof(uint32_t) * W);
+            int nr = 0, nk = 0;
+            for (int i = 0; i < C; ++i) {
+                double acc = 0.0;
+                if (N[i] > 0)
+                    for (int t = 0; t < Lq; ++t) {
+                        size_t r = bh * Lq + t;
+                        float S = expf(logits[r * C + i] - row_max[r]) / denom[r];
+                        acc += (double)S;
+                    }
+                double Sbar = acc / (double)Lq;
+                if (mean_scores)
+                    mean_scores[bh * C + i] = Sbar;
+                if (N[i] > 0 && Sbar > (double)thresh[h]) {
+                    mask[i >> 5] |= 1u << (i & 31);
+                    rg[2 * nr] = off[i];
+                    rg[2 * nr + 1] = N[i];
+                    ++nr;
+                    nk += N[i];
+                }
+            }
+            n_ranges[bh] = nr;
+            n_keys[bh] = nk;
+        }
 }
 
 /*
