@@ -154,6 +154,8 @@ def bench_prefill(args, torch, sq, wl, dev):
         sq.sq_sparse_attn_prefill(shape, P.q, P.K_fixed, P.V_fixed, P.offsets, P.keep_mask, P.K_user, P.V_user,
                                   P.out, P.lse, ws)
 
+    if args.selection == "mean":
+        return bench_prefill_mean(args, torch, sq, wl, dev, w, Ps)
     eager_ms, graph_ms, ms, (n_meas, k_avg, k_min, k_max) = time_steps(step, args, torch, sq)
     nk = Ps[0].n_keys.cpu().numpy().astype(np.float64)            # [B,H,Lq]
     t = np.arange(w.Lq)
@@ -184,6 +186,67 @@ def bench_prefill(args, torch, sq, wl, dev):
                        "traffic": read_traffic(f"prefill_attn_kernel_{args.workload}_pmc.txt"),
                        "flops_per_launch": useful_attn, "avg_us": round(k_avg, 2), "min_us": round(k_min, 2),
                        "launches": n_meas}
+    print(json.dumps(res, ensure_ascii=False))
+
+
+def bench_prefill_mean(args, torch, sq, wl, dev, w, Ps):
+    """Config 4's shape with the paper's own prefill rule (Appendix D): scores averaged over the query tokens ->
+    one kept set per (sequence, head) -> attention that gathers only the kept keys."""
+    R = len(Ps)
+    shape = Ps[0].shape
+    W = (w.C + 31) // 32
+    mask = torch.zeros(w.B, w.H, W, dtype=torch.int32, device=dev)
+    ranges = torch.zeros(w.B, w.H, w.C, 2, dtype=torch.int32, device=dev)
+    nr = torch.zeros(w.B, w.H, dtype=torch.int32, device=dev)
+    nk = torch.zeros(w.B, w.H, dtype=torch.int32, device=dev)
+    ws_s = sq.workspace(shape, sq.SQ_CALL_SELECT_MEAN, dev)
+    ws_a = sq.workspace(shape, sq.SQ_CALL_ATTN_PREFILL_SHARED, dev)
+    # Thresholds on the averaged scores that keep w.keep_frac of the keys per head: bisection on the library's own
+    # counts (log domain), untimed.
+    P = Ps[0]
+    sq.sq_centroid_score(shape, P.q, P.centroids, P.sizes, P.logits, P.row_max, P.denom)
+    lo, hi = np.full(w.H, -40.0), np.full(w.H, 0.0)
+    thr = torch.zeros(w.H, dtype=torch.float32, device=dev)
+    for _ in range(40):
+        mid = 0.5 * (lo + hi)
+        thr.copy_(torch.from_numpy(np.exp(mid).astype(np.float32)))
+        sq.sq_select_mean(shape, P.logits, P.row_max, P.denom, thr, P.sizes, P.offsets, mask, ranges, nr, nk, ws_s)
+        kept = nk.cpu().numpy().mean(axis=0)                      # per head
+        too_many = kept > w.keep_frac * w.L
+        lo = np.where(too_many, mid, lo)
+        hi = np.where(too_many, hi, mid)
+    thr.copy_(torch.from_numpy(np.exp(hi).astype(np.float32)))
+
+    def step(i, stream_ptr):
+        P = Ps[i % R]
+        sq.sq_centroid_score(shape, P.q, P.centroids, P.sizes, P.logits, P.row_max, P.denom)
+        sq.sq_select_mean(shape, P.logits, P.row_max, P.denom, thr, P.sizes, P.offsets, mask, ranges, nr, nk, ws_s)
+        sq.sq_sparse_attn_prefill_shared(shape, P.q, P.K_fixed, P.V_fixed, ranges, nr, nk, P.K_user, P.V_user, P.out,
+                                         P.lse, ws_a)
+
+    eager_ms, graph_ms, ms, (n_meas, k_avg, k_min, k_max) = time_steps(step, args, torch, sq)
+    nkh = nk.cpu().numpy().astype(np.float64)                     # [B,H]
+    t = np.arange(w.Lq)
+    user_vis = np.minimum(t + 1, w.U) if w.causal_user else np.full(w.Lq, w.U)
+    useful_attn = float((nkh.sum() * w.Lq + w.B * w.H * user_vis.sum()) * 4 * w.d)
+    score_flops = 2.0 * w.B * w.H * w.Lq * w.C * w.d
+    q0 = np.arange(0, w.Lq, 64)
+    nb_user = -(-np.minimum(w.U, q0 + 64) // 64) if w.causal_user else np.full(len(q0), -(-w.U // 64))
+    executed = float(((np.ceil(nkh / 64).sum() * len(q0)) + w.B * w.H * nb_user.sum()) * 64 * 64 * 4 * w.d)
+    res = base_result(args, "sparse prefill attn: useful TFLOP/s (selection on averaged scores), 32K fixed ctx, keep 1/8",
+                      round((useful_attn + score_flops) / (ms * 1e-3) / 1e12, 3), "TFLOP/s", ms, eager_ms, graph_ms,
+                      w.B * w.Lq)
+    res["config"] = {"workload": args.workload, "selection": "mean", "B": w.B, "H": w.H, "d": w.d, "L": w.L,
+                     "C": w.C, "Lq": w.Lq, "U": w.U, "keep_achieved": round(float(nkh.mean() / w.L), 5), "replicas": R,
+                     "entry": "sq_centroid_score + sq_select_mean + sq_sparse_attn_prefill_shared"}
+    res["flops_per_step"] = {"useful_attention": useful_attn, "scoring": score_flops, "executed_attention": executed}
+    res["roofline"] = {"bound": "mfma", "kernel": "prefill_attn_kernel<shared>",
+                       "achieved": round(useful_attn / (k_avg * 1e-6) / 1e12, 2) if n_meas else None,
+                       "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                       "frac": round(useful_attn / (k_avg * 1e-6) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4) if n_meas else None,
+                       "executed_TFLOPs": round(executed / (k_avg * 1e-6) / 1e12, 2) if n_meas else None,
+                       "traffic": None, "flops_per_launch": useful_attn, "avg_us": round(k_avg, 2),
+                       "min_us": round(k_min, 2), "launches": n_meas}
     print(json.dumps(res, ensure_ascii=False))
 
 
@@ -264,6 +327,8 @@ def main():
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="only run a 256 MiB streaming read and a 256 MiB device copy (known sizes) a few times: "
                          "the reference dispatches that scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
+    ap.add_argument("--selection", choices=("per_query", "mean"), default="per_query",
+                    help="prefill workloads: per-query selection, or the paper's selection on averaged scores")
     ap.add_argument("--separate", action="store_true", help="time the three separate calls instead of sq_decode_step")
     args = ap.parse_args()
     if args.gpus != 1:

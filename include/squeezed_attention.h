@@ -52,7 +52,9 @@ typedef enum sq_call {
     SQ_CALL_ATTN_PREFILL = 3,
     SQ_CALL_HIER_SELECT = 4,
     SQ_CALL_DECODE_STEP = 5,
-    SQ_CALL_HIER_DECODE_STEP = 6
+    SQ_CALL_HIER_DECODE_STEP = 6,
+    SQ_CALL_SELECT_MEAN = 7,
+    SQ_CALL_ATTN_PREFILL_SHARED = 8
 } sq_call;
 
 /*
@@ -138,6 +140,36 @@ int sq_sparse_attn_prefill(const sq_shape_t *shape, const void *q, const void *K
                            const int32_t *offsets, const uint32_t *keep_mask,
                            const void *K_user, const void *V_user,
                            void *out, float *lse, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Prefill selection as the paper does it (Appendix D, "Prefill Stage"): the cluster scores of Eq. 1,
+ * S_i(t) = exp(x_i(t) - m(t)) / D(t), are averaged over the Lq query tokens of a (sequence, head) and
+ * cluster i is kept iff N_i > 0 and the average is > thresh[h] (strict): ONE kept set for all query
+ * tokens of that sequence and head.  fp32 throughout (per-token scores, a fixed-order sum, one division).
+ * In:  logits, row_max, denom as written by sq_centroid_score.
+ * Out: keep_mask u32 [B,H,ceil(C/32)]; ranges i32 [B,H,C,2] (may be NULL) = (first key, count) of the
+ *      kept clusters in ascending order; n_ranges, n_keys i32 [B,H].
+ * Workspace: sq_workspace_bytes(shape, SQ_CALL_SELECT_MEAN).
+ */
+int sq_select_mean(const sq_shape_t *shape, const float *logits, const float *row_max, const float *denom,
+                   const float *thresh, const int32_t *sizes, const int32_t *offsets,
+                   uint32_t *keep_mask, int32_t *ranges, int32_t *n_ranges, int32_t *n_keys,
+                   void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Prefill-time sparse attention (Section 4.2) with ONE kept set per (sequence, head), as produced by
+ * sq_select_mean: every query token t of sequence b attends to the keys of ranges[b,h,0..n_ranges) plus
+ * user keys 0..t (causal_user != 0) or all U user keys.  The ranges are expanded into a list of key rows
+ * (the key-index tensor of Section 4.2) that the attention kernel gathers; there are no per-query masks.
+ * In:  ranges i32 [B,H,C,2], n_ranges i32 [B,H] (entries with count 0 are skipped; at most L keys per
+ *      row are used), n_keys i32 [B,H] (informational; the kernels recount).
+ * Out: out f16 [B,H,Lq,d]; lse f32 [B,H,Lq] or NULL.
+ * Workspace: sq_workspace_bytes(shape, SQ_CALL_ATTN_PREFILL_SHARED).
+ */
+int sq_sparse_attn_prefill_shared(const sq_shape_t *shape, const void *q, const void *K_fixed, const void *V_fixed,
+                                  const int32_t *ranges, const int32_t *n_ranges, const int32_t *n_keys,
+                                  const void *K_user, const void *V_user,
+                                  void *out, float *lse, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Two-level centroid lookup (Section 3.3, Eq. 2 and Eq. 3; Lq must be 1).  shape->C is the number

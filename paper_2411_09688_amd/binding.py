@@ -19,11 +19,12 @@ LIB_PATH = os.environ.get("SQ_LIB_PATH") or os.path.join(_PKG, "libsqueezed_atte
 
 SQ_OK, SQ_ERR_INVALID_ARG, SQ_ERR_UNSUPPORTED, SQ_ERR_WORKSPACE, SQ_ERR_HIP = 0, -1, -2, -3, -4
 (SQ_CALL_CENTROID_SCORE, SQ_CALL_SELECT, SQ_CALL_ATTN_DECODE, SQ_CALL_ATTN_PREFILL, SQ_CALL_HIER_SELECT,
- SQ_CALL_DECODE_STEP, SQ_CALL_HIER_DECODE_STEP) = range(7)
+ SQ_CALL_DECODE_STEP, SQ_CALL_HIER_DECODE_STEP, SQ_CALL_SELECT_MEAN, SQ_CALL_ATTN_PREFILL_SHARED) = range(9)
 
 EXPORTS = ("sq_workspace_bytes", "sq_last_error", "sq_version", "sq_centroid_score", "sq_select",
            "sq_sparse_attn_decode", "sq_sparse_attn_prefill", "sq_hier_select", "sq_decode_step",
-           "sq_hier_decode_step", "sq_profile_begin", "sq_profile_end", "sq_probe_stream_read")
+           "sq_hier_decode_step", "sq_select_mean", "sq_sparse_attn_prefill_shared", "sq_profile_begin",
+           "sq_profile_end", "sq_probe_stream_read")
 
 
 class SqShape(C.Structure):
@@ -153,6 +154,25 @@ def sq_sparse_attn_prefill(shape, q, K_fixed, V_fixed, offsets, keep_mask, K_use
                                         _ptr(keep_mask, I32, "keep_mask"), _ptr(K_user, F16, "K_user"),
                                         _ptr(V_user, F16, "V_user"), _ptr(out, F16, "out"), _ptr(lse, F32, "lse"),
                                         *_ws_args(ws), _stream(stream)))
+
+
+def sq_select_mean(shape, logits, row_max, denom, thresh, sizes, offsets, keep_mask, ranges, n_ranges, n_keys, ws,
+                   stream=None):
+    _check(lib().sq_select_mean(C.byref(shape), _ptr(logits, F32, "logits"), _ptr(row_max, F32, "row_max"),
+                                _ptr(denom, F32, "denom"), _ptr(thresh, F32, "thresh"), _ptr(sizes, I32, "sizes"),
+                                _ptr(offsets, I32, "offsets"), _ptr(keep_mask, I32, "keep_mask"),
+                                _ptr(ranges, I32, "ranges"), _ptr(n_ranges, I32, "n_ranges"),
+                                _ptr(n_keys, I32, "n_keys"), *_ws_args(ws), _stream(stream)))
+
+
+def sq_sparse_attn_prefill_shared(shape, q, K_fixed, V_fixed, ranges, n_ranges, n_keys, K_user, V_user, out, lse, ws,
+                                  stream=None):
+    _check(lib().sq_sparse_attn_prefill_shared(C.byref(shape), _ptr(q, F16, "q"), _ptr(K_fixed, F16, "K_fixed"),
+                                               _ptr(V_fixed, F16, "V_fixed"), _ptr(ranges, I32, "ranges"),
+                                               _ptr(n_ranges, I32, "n_ranges"), _ptr(n_keys, I32, "n_keys"),
+                                               _ptr(K_user, F16, "K_user"), _ptr(V_user, F16, "V_user"),
+                                               _ptr(out, F16, "out"), _ptr(lse, F32, "lse"), *_ws_args(ws),
+                                               _stream(stream)))
 
 
 def sq_hier_select(shape, C1, q, centroids1, sizes1, child_offsets, thresh1, centroids2, sizes2, offsets2, thresh2,

@@ -215,6 +215,24 @@ HierStepWs carve_hier_step(Carver &cv, const sq_shape_t *sh)
     return w;
 }
 
+// Workspace of the shared-set prefill attention: records of the kept ranges and the list of kept key rows.
+struct PrefillSharedWs {
+    sq::DecodePlan plan;
+    int32_t *key_idx;
+};
+
+PrefillSharedWs carve_prefill_shared(Carver &cv, const sq_shape_t *sh)
+{
+    const size_t rows = (size_t)sh->B * sh->H;
+    PrefillSharedWs w{};
+    w.plan.rec_cap = sh->C;
+    w.plan.L = sh->L;
+    w.plan.rec = cv.take<int4>(rows * sh->C);
+    w.plan.hdr = cv.take<int2>(rows);
+    w.key_idx = cv.take<int32_t>(rows * sh->L);
+    return w;
+}
+
 int check_ws(const char *fn, const sq_shape_t *sh, int which, void *ws, size_t ws_bytes)
 {
     const size_t need = sq_workspace_bytes(sh, which);
@@ -253,6 +271,12 @@ size_t sq_workspace_bytes(const sq_shape_t *sh, int which)
     case SQ_CALL_ATTN_PREFILL:
         cv.take<int32_t>((size_t)sh->H * sh->L);
         cv.take<int32_t>((size_t)sh->H * ((sh->L + 63) / 64));
+        return cv.off;
+    case SQ_CALL_SELECT_MEAN:
+        cv.take<float>((size_t)sh->B * sh->H * sq::mean_parts_for(sh->Lq) * sh->C);
+        return cv.off;
+    case SQ_CALL_ATTN_PREFILL_SHARED:
+        carve_prefill_shared(cv, sh);
         return cv.off;
     case SQ_CALL_HIER_SELECT:
         carve_hier(cv, sh);
@@ -409,6 +433,67 @@ int sq_sparse_attn_prefill(const sq_shape_t *sh, const void *q, const void *K_fi
     int32_t *blk_info = cv.take<int32_t>((size_t)sh->H * ((sh->L + 63) / 64));
     SQ_HIP(sq::launch_prefill_attn(q, K_fixed, V_fixed, K_user, V_user, keep_mask, offsets, key_cid, blk_info, out, lse,
                                    to_shape(sh), static_cast<hipStream_t>(stream)));
+    g_err[0] = 0;
+    return SQ_OK;
+}
+
+int sq_select_mean(const sq_shape_t *sh, const float *logits, const float *row_max, const float *denom,
+                   const float *thresh, const int32_t *sizes, const int32_t *offsets, uint32_t *keep_mask,
+                   int32_t *ranges, int32_t *n_ranges, int32_t *n_keys, void *ws, size_t ws_bytes, void *stream)
+{
+    if (int rc = check_shape(sh, __func__, false)) return rc;
+    SQ_REQUIRE_PTR(logits);
+    SQ_REQUIRE_PTR(row_max);
+    SQ_REQUIRE_PTR(denom);
+    SQ_REQUIRE_PTR(thresh);
+    SQ_REQUIRE_PTR(sizes);
+    SQ_REQUIRE_PTR(offsets);
+    SQ_REQUIRE_PTR(keep_mask);
+    SQ_OPTIONAL_PTR(ranges);
+    SQ_REQUIRE_PTR(n_ranges);
+    SQ_REQUIRE_PTR(n_keys);
+    if (int rc = check_ws(__func__, sh, SQ_CALL_SELECT_MEAN, ws, ws_bytes)) return rc;
+    if (int rc = check_device(__func__)) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Carver cv(ws);
+    const int rows = sh->B * sh->H;
+    float *part_sum = cv.take<float>((size_t)rows * sq::mean_parts_for(sh->Lq) * sh->C);
+    SQ_HIP(sq::launch_mean_score(logits, row_max, denom, part_sum, rows, sh->Lq, sh->C, s));
+    sq::SelectOpts opt{};
+    opt.mean_parts = sq::mean_parts_for(sh->Lq);
+    opt.mean_div = (float)sh->Lq;
+    SQ_HIP(sq::launch_select(part_sum, nullptr, nullptr, true, thresh, sizes, offsets, keep_mask, ranges, n_ranges,
+                             n_keys, sq::DecodePlan{}, false, 0, opt, rows, sh->H, 1, sh->C, s));
+    g_err[0] = 0;
+    return SQ_OK;
+}
+
+int sq_sparse_attn_prefill_shared(const sq_shape_t *sh, const void *q, const void *K_fixed, const void *V_fixed,
+                                  const int32_t *ranges, const int32_t *n_ranges, const int32_t *n_keys,
+                                  const void *K_user, const void *V_user, void *out, float *lse, void *ws,
+                                  size_t ws_bytes, void *stream)
+{
+    if (int rc = check_shape(sh, __func__, false)) return rc;
+    SQ_REQUIRE_PTR(q);
+    SQ_REQUIRE_PTR(K_fixed);
+    SQ_REQUIRE_PTR(V_fixed);
+    SQ_REQUIRE_PTR(ranges);
+    SQ_REQUIRE_PTR(n_ranges);
+    SQ_REQUIRE_PTR(n_keys);
+    if (sh->U > 0) {
+        SQ_REQUIRE_PTR(K_user);
+        SQ_REQUIRE_PTR(V_user);
+    }
+    SQ_REQUIRE_PTR(out);
+    SQ_OPTIONAL_PTR(lse);
+    if (int rc = check_ws(__func__, sh, SQ_CALL_ATTN_PREFILL_SHARED, ws, ws_bytes)) return rc;
+    if (int rc = check_device(__func__)) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Carver cv(ws);
+    PrefillSharedWs w = carve_prefill_shared(cv, sh);
+    SQ_HIP(sq::launch_ranges_to_rec(ranges, n_ranges, w.plan, sh->B * sh->H, sh->C, s));
+    SQ_HIP(sq::launch_prefill_attn_shared(q, K_fixed, V_fixed, K_user, V_user, w.plan, w.key_idx, out, lse,
+                                          to_shape(sh), s));
     g_err[0] = 0;
     return SQ_OK;
 }

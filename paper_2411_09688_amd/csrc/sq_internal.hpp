@@ -53,12 +53,20 @@ hipError_t launch_score(const void *q, const void *centroids, float *logits, int
                         int C, float sm_scale, hipStream_t s);
 hipError_t launch_row_stats(const float *logits, const int32_t *sizes, float *row_max, float *denom, int rows,
                             int H, int Lq, int C, hipStream_t s);
+// Averaged-score prefill selection: partial sums of the per-token scores over blocks of MEAN_ROWS query tokens,
+// part_sum [B*H, mean_parts_for(Lq), C].
+constexpr int MEAN_ROWS = 64;
+inline int mean_parts_for(int Lq) { return (Lq + MEAN_ROWS - 1) / MEAN_ROWS; }
+hipError_t launch_mean_score(const float *logits, const float *row_max, const float *denom, float *part_sum, int BH,
+                             int Lq, int C, hipStream_t s);
 // Options of the row-wise selection for the two-level lookup (all zero for the one-level path).
 struct SelectOpts {
     const int32_t *parent_offsets;   // level 2: child_offsets [H, C1+1]; cluster i is a candidate iff its parent is kept
     const uint32_t *parent_mask;     // level 2: keep mask of the coarse level [B*H, ceil(C1/32)]
     int C1;
     int len_from_offsets;            // level 1: emitted range length = offsets[i+1] - offsets[i] (child clusters)
+    int mean_parts;                  // averaged-score selection: `logits` holds this many partial score sums per
+    float mean_div;                  //   row, [rows, mean_parts, C]; their sum / mean_div is compared with T
     int union_rows;                  // shared-context decode: rows are union rows (sequence group, head)
     int B;                           // shared-context decode: number of sequences
 };
@@ -106,6 +114,12 @@ hipError_t launch_decode_attn_shared(const void *q, const void *Kf, const void *
 hipError_t launch_prefill_attn(const void *q, const void *Kf, const void *Vf, const void *Ku, const void *Vu,
                                const uint32_t *keep_mask, const int32_t *offsets, int32_t *key_cid, int32_t *blk_info,
                                void *out, float *lse, const Shape &sh, hipStream_t s);
+
+// Prefill attention with ONE kept set per (sequence, head): plan.rec / plan.hdr hold the kept ranges' records
+// (from launch_ranges_to_rec); key_idx [B*H, L] is workspace for the list of kept key rows.
+hipError_t launch_prefill_attn_shared(const void *q, const void *Kf, const void *Vf, const void *Ku, const void *Vu,
+                                      DecodePlan plan, int32_t *key_idx, void *out, float *lse, const Shape &sh,
+                                      hipStream_t s);
 
 // Measurement hook (sq_profile.hip): records an event before / after the partial kernel when enabled.
 bool profile_mark(hipStream_t s, bool begin);

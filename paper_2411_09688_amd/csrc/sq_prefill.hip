@@ -21,6 +21,12 @@
 //     queries kept.
 // The user block is causal when causal_user is set (query t sees user keys 0..t); the fixed context is
 // always fully visible.
+//
+// SHARED variant (selection on averaged scores, Appendix D "Prefill Stage"): all query tokens of a (sequence,
+// head) attend to ONE kept set.  The kept ranges are expanded into a list of key rows (the key-index tensor of
+// Section 4.2); the kernel walks that list 64 keys at a time, gathering K and V rows by index (the indices of
+// the block after next travel in registers ahead of the rows), with no per-query masks: only the tail of the
+// last block and the causal user keys are masked, so every executed tile is useful work.
 #include "sq_common.hpp"
 #include "sq_internal.hpp"
 
@@ -65,6 +71,20 @@ __device__ __forceinline__ int vt_pos(int kappa)
     return ks * 32 + g * 8 + t * 4 + j;
 }
 
+// Kept ranges of every (sequence, head) row -> list of key rows: record (first key, count, keys before) writes
+// key_idx[row, before + j] = first + j, clamped into the tensor.  One wave per record at a time.
+__global__ __launch_bounds__(256) void expand_ranges_kernel(DecodePlan plan, int32_t *__restrict__ key_idx, int L)
+{
+    const size_t row = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nrec = min(plan.hdr[row].x, plan.rec_cap);
+    int32_t *dst = key_idx + row * (size_t)L;
+    for (int r = wave; r < nrec; r += 4) {
+        const int4 rc = plan.rec[row * plan.rec_cap + r];
+        for (int j = lane; j < rc.y && rc.z + j < L; j += 64) dst[rc.z + j] = max(0, min(rc.x + j, L - 1));
+    }
+}
+
 constexpr int PF_QT = 1;                  // 16-query tiles per wave
 constexpr int PF_BM = 64 * PF_QT;         // queries per workgroup (4 waves)
 
@@ -82,6 +102,9 @@ __device__ __forceinline__ float select_bits(uint32_t mask, float a, float b)
     return __builtin_bit_cast(float, (mask & __builtin_bit_cast(uint32_t, a)) | (~mask & __builtin_bit_cast(uint32_t, b)));
 }
 
+// SHARED: key_cid is the key-row list [B*H, L] and blk_info the per-row (records, kept keys) headers; keep_mask is
+// not used.
+template <bool SHARED>
 __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
     const _Float16 *__restrict__ q, const _Float16 *__restrict__ Kf, const _Float16 *__restrict__ Vf,
     const _Float16 *__restrict__ Ku, const _Float16 *__restrict__ Vu, const uint32_t *__restrict__ keep_mask,
@@ -131,11 +154,14 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
 
     const _Float16 *Kfh = Kf + (size_t)h * L * D, *Vfh = Vf + (size_t)h * L * D;
     const _Float16 *Kuh = Ku + ((size_t)b * H + h) * (size_t)U * D, *Vuh = Vu + ((size_t)b * H + h) * (size_t)U * D;
-    const int nblk_fixed = (L + PF_BN - 1) / PF_BN;
+    // keys of the fixed context this (sequence, head) walks: all of them, or the kept ones through the row list
+    const int n_fixed = SHARED ? min(blk_info[2 * ((size_t)b * H + h) + 1], L) : L;
+    const int32_t *idx_bh = key_cid + ((size_t)b * H + h) * (size_t)L;   // SHARED only
+    const int nblk_fixed = (n_fixed + PF_BN - 1) / PF_BN;
     // Causal user block: queries of this workgroup see user keys 0 .. min(U, q0 + BM) - 1 at most.
     const int u_vis = causal_user ? min(U, q0 + BM) : U;
     const int nblk = nblk_fixed + (u_vis + PF_BN - 1) / PF_BN;
-    const int32_t *binfo = blk_info + (size_t)h * nblk_fixed;
+    const int32_t *binfo = blk_info + (size_t)h * ((L + PF_BN - 1) / PF_BN);
     const int32_t *cid_h = key_cid + (size_t)h * L;
     // Mask row of the query this thread stages bits for (threads 0..BM-1).
     const int my_q = q0 + tid;
@@ -149,10 +175,30 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
     // i*16 + tid/16, 16-byte chunk tid%16; V = key `lane`, four chunks starting at wave*4.
     const uint32_t k_off = (uint32_t)(tid >> 4) * 256u + (uint32_t)(tid & 15) * 16u;
     const uint32_t v_off = (uint32_t)lane * 256u + (uint32_t)wave * 64u;
+    // SHARED: rows of this thread's K pieces (keys i*16 + tid/16) and V piece (key `lane`) of a fixed block; the
+    // indices of block b+2 are loaded while block b is computed and used when block b+1's rows are fetched.
+    int ik_n[4] = {0, 0, 0, 0}, iv_n = 0, ik_c[4] = {0, 0, 0, 0}, iv_c = 0;
+    auto fetch_idx = [&](int blk) {
+        if (!SHARED || blk >= nblk_fixed) return;
+        const int j0 = blk * PF_BN, last = n_fixed - 1;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) ik_n[i] = idx_bh[min(j0 + i * 16 + (tid >> 4), last)];
+        iv_n = idx_bh[min(j0 + lane, last)];
+    };
     auto fetch = [&](int blk) {           // issue the global loads of block `blk`
         const bool user = blk >= nblk_fixed;
         const int j0 = (user ? blk - nblk_fixed : blk) * PF_BN;
         const int nkeys = user ? U : L;
+        if (SHARED && !user) {            // gathered rows (slots past the kept keys repeat the last kept row)
+            const char *Kb = reinterpret_cast<const char *>(Kfh), *Vb = reinterpret_cast<const char *>(Vfh);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                pk[i] = *reinterpret_cast<const h8 *>(Kb + (size_t)ik_c[i] * 256 + (uint32_t)(tid & 15) * 16u);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                pv[i] = *reinterpret_cast<const h8 *>(Vb + (size_t)iv_c * 256 + (uint32_t)(wave * 4 + i) * 16u);
+            return;
+        }
         const char *Kb = reinterpret_cast<const char *>(user ? Kuh : Kfh) + (size_t)j0 * 256;
         const char *Vb = reinterpret_cast<const char *>(user ? Vuh : Vfh) + (size_t)j0 * 256;
         if (j0 + PF_BN <= nkeys) {        // full block: uniform base + 32-bit per-thread offsets
@@ -172,7 +218,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
             for (int i = 0; i < 4; ++i)
                 pv[i] = *reinterpret_cast<const h8 *>(Vb + (uint32_t)keyv * 256u + (uint32_t)(wave * 4 + i) * 16u);
         }
-        if (!user) {
+        if (!user && !SHARED) {
             pinfo = binfo[blk];
             if (tid < PF_BN) pcid = j0 + tid < L ? cid_h[j0 + tid] : 0x7fffffff;
             if (tid < BM) {
@@ -196,7 +242,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
 #pragma unroll
                 for (int e = 0; e < 8; ++e) st.Vt[((wave * 4 + i) * 8 + e) * PF_VT_STRIDE + pos] = pv[i][e];
         }
-        if (!user) {
+        if (!user && !SHARED) {
             const int first = pinfo & 0xffff;
             if (tid < PF_BN) {
                 st.cid[tid] = pcid;
@@ -209,10 +255,20 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
         }
     };
 
+    auto take_idx = [&]() {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) ik_c[i] = ik_n[i];
+        iv_c = iv_n;
+    };
     int info_cur = 0;
-    fetch(0);
-    info_cur = pinfo;
-    commit(0, stage[0]);
+    if (nblk > 0) {                                       // (no kept key and no user key: nothing to stage)
+        fetch_idx(0);
+        take_idx();
+        fetch_idx(1);
+        fetch(0);
+        info_cur = pinfo;
+        commit(0, stage[0]);
+    }
     __syncthreads();
 
     for (int blk = 0; blk < nblk; ++blk) {
@@ -220,13 +276,27 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
         const bool user = blk >= nblk_fixed;
         const int j0 = (user ? blk - nblk_fixed : blk) * PF_BN;
         const int info = info_cur;
-        if (blk + 1 < nblk) fetch(blk + 1);                 // global loads of the next block run under this one
+        if (blk + 1 < nblk) {                               // global loads of the next block run under this one
+            take_idx();
+            fetch(blk + 1);
+            if (blk + 2 < nblk) fetch_idx(blk + 2);
+        }
 
         // ---- visibility of this lane's (query, key) pairs: msk = all ones (visible) or zero ------------------
         // element e = kt*4 + v  <->  key kt*16 + kg*4 + v of the block, query nq[qt].
         uint32_t msk[QT][16];
         bool any;
-        if (!user && info >= 0) {
+        if (SHARED && !user) {
+            // One kept set for every query: only slots past the kept keys (last block) are hidden.
+            any = true;
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int j = j0 + (e >> 2) * 16 + kg * 4 + (e & 3);
+                    msk[qt][e] = (j < n_fixed && nq[qt] < Lq) ? 0xffffffffu : 0u;
+                }
+        } else if (!user && info >= 0) {
             // Fixed context, usual case: bit (cluster - first) of the query's staged window, moved to the sign.
             const uint32_t present = (2u << ((info >> 16) & 31)) - 1u;       // local clusters that occur in the block
             int sh[16];
@@ -369,6 +439,34 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
     }
 }
 
+namespace {
+
+template <bool SHARED>
+hipError_t launch_prefill_kernel(const void *q, const void *Kf, const void *Vf, const void *Ku, const void *Vu,
+                                 const uint32_t *keep_mask, const int32_t *key_cid, const int32_t *blk_info, void *out,
+                                 float *lse, const Shape &sh, hipStream_t s)
+{
+    const size_t smem = 2 * sizeof(PfStage);
+    static bool attr_set = false;   // one GPU per process in this build
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(prefill_attn_kernel<SHARED>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int units = ((sh.Lq + PF_BM - 1) / PF_BM) * sh.H * sh.B;
+    dim3 grid((units + 7) / 8 * 8);
+    const bool prof = profile_mark(s, true);
+    hipLaunchKernelGGL(prefill_attn_kernel<SHARED>, grid, dim3(256), smem, s, (const _Float16 *)q,
+                       (const _Float16 *)Kf, (const _Float16 *)Vf, (const _Float16 *)Ku, (const _Float16 *)Vu, keep_mask,
+                       key_cid, blk_info, (_Float16 *)out, lse, sh.B, sh.H, sh.L, sh.C, sh.Lq, sh.U, sh.causal_user,
+                       sh.sm_scale);
+    if (prof) profile_mark(s, false);
+    return hipGetLastError();
+}
+
+}  // namespace
+
 hipError_t launch_prefill_attn(const void *q, const void *Kf, const void *Vf, const void *Ku, const void *Vu,
                                const uint32_t *keep_mask, const int32_t *offsets, int32_t *key_cid, int32_t *blk_info,
                                void *out, float *lse, const Shape &sh, hipStream_t s)
@@ -379,22 +477,18 @@ hipError_t launch_prefill_attn(const void *q, const void *Kf, const void *Vf, co
                        sh.L, nblk);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const size_t smem = 2 * sizeof(PfStage);
-    static bool attr_set = false;   // one GPU per process in this build
-    if (!attr_set) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(prefill_attn_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    const int units = ((sh.Lq + PF_BM - 1) / PF_BM) * sh.H * sh.B;
-    dim3 grid((units + 7) / 8 * 8);
-    const bool prof = profile_mark(s, true);
-    hipLaunchKernelGGL(prefill_attn_kernel, grid, dim3(256), smem, s, (const _Float16 *)q, (const _Float16 *)Kf,
-                       (const _Float16 *)Vf, (const _Float16 *)Ku, (const _Float16 *)Vu, keep_mask, key_cid, blk_info,
-                       (_Float16 *)out, lse, sh.B, sh.H, sh.L, sh.C, sh.Lq, sh.U, sh.causal_user, sh.sm_scale);
-    if (prof) profile_mark(s, false);
-    return hipGetLastError();
+    return launch_prefill_kernel<false>(q, Kf, Vf, Ku, Vu, keep_mask, key_cid, blk_info, out, lse, sh, s);
+}
+
+hipError_t launch_prefill_attn_shared(const void *q, const void *Kf, const void *Vf, const void *Ku, const void *Vu,
+                                      DecodePlan plan, int32_t *key_idx, void *out, float *lse, const Shape &sh,
+                                      hipStream_t s)
+{
+    hipLaunchKernelGGL(expand_ranges_kernel, dim3(sh.B * sh.H), dim3(256), 0, s, plan, key_idx, sh.L);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_prefill_kernel<true>(q, Kf, Vf, Ku, Vu, nullptr, key_idx, reinterpret_cast<const int32_t *>(plan.hdr),
+                                       out, lse, sh, s);
 }
 
 }  // namespace sq

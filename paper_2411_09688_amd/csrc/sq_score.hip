@@ -85,6 +85,40 @@ __global__ __launch_bounds__(256) void row_stats_kernel(const float *__restrict_
     }
 }
 
+// Prefill selection on averaged scores (Appendix D, "Prefill Stage"), first half: the per-token scores
+// S_i(t) = exp(x_i(t) - m(t)) / D(t) of Eq. 1 summed over a block of MEAN_ROWS query tokens of one
+// (sequence, head), t ascending, one thread per cluster (coalesced along i).  The selection kernel adds the
+// blocks' sums in ascending order and divides by Lq.
+__global__ __launch_bounds__(256) void mean_score_kernel(const float *__restrict__ logits,
+                                                         const float *__restrict__ row_max,
+                                                         const float *__restrict__ denom, float *__restrict__ part_sum,
+                                                         int Lq, int C, int n_part)
+{
+    __shared__ float s_m[MEAN_ROWS], s_D[MEAN_ROWS];
+    const int bh = blockIdx.y, part = blockIdx.x;
+    const int t0 = part * MEAN_ROWS, nt = min(MEAN_ROWS, Lq - t0);
+    const size_t row0 = (size_t)bh * Lq + t0;
+    if ((int)threadIdx.x < nt) {
+        s_m[threadIdx.x] = row_max[row0 + threadIdx.x];
+        s_D[threadIdx.x] = denom[row0 + threadIdx.x];
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < C; i += 256) {
+        const float *x = logits + row0 * C + i;
+        float acc = 0.0f;
+        int t = 0;
+        for (; t + 8 <= nt; t += 8) {                      // eight loads in flight
+            float xv[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) xv[u] = x[(size_t)(t + u) * C];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc += expf(xv[u] - s_m[t + u]) / s_D[t + u];
+        }
+        for (; t < nt; ++t) acc += expf(x[(size_t)t * C] - s_m[t]) / s_D[t];
+        part_sum[((size_t)bh * n_part + part) * C + i] = acc;
+    }
+}
+
 // Level-2 scoring of the two-level lookup (Section 3.3, Eq. 3 numerator): the fine centroids to score are
 // the children of the kept coarse clusters, listed by work items of KPC candidate clusters each (built
 // by the level-1 selection: a balanced number of centroids per workgroup, Appendix D).  A persistent
@@ -158,6 +192,15 @@ hipError_t launch_score(const void *q, const void *centroids, float *logits, int
     dim3 grid((C + SCORE_ROWS_PER_WG - 1) / SCORE_ROWS_PER_WG, H, (B * Lq + 15) / 16);
     hipLaunchKernelGGL(score_kernel, grid, dim3(256), 0, s, (const _Float16 *)q, (const _Float16 *)centroids, logits,
                        zero_counter, B, H, Lq, C, sm_scale);
+    return hipGetLastError();
+}
+
+hipError_t launch_mean_score(const float *logits, const float *row_max, const float *denom, float *part_sum, int BH,
+                             int Lq, int C, hipStream_t s)
+{
+    const int n_part = mean_parts_for(Lq);
+    hipLaunchKernelGGL(mean_score_kernel, dim3(n_part, BH), dim3(256), 0, s, logits, row_max, denom, part_sum, Lq, C,
+                       n_part);
     return hipGetLastError();
 }
 

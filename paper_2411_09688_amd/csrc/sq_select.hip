@@ -274,6 +274,15 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
             s_N[i] = cand ? N[i] : 0;
             s_e[i] = cand ? x[i] : 0.0f;
         }
+    } else if (opt.mean_parts) {
+        // Averaged-score selection (Appendix D, prefill): the staged value is the mean score itself.
+        const float *ps = logits + row * (size_t)opt.mean_parts * C;
+        for (int i = tid; i < C; i += SEL_THREADS) {
+            float sum = 0.0f;
+            for (int p = 0; p < opt.mean_parts; ++p) sum += ps[(size_t)p * C + i];
+            s_e[i] = sum / opt.mean_div;
+            s_N[i] = N[i];
+        }
     } else {
         for (int i = tid; i < C; i += SEL_THREADS) {
             s_e[i] = x[i];
@@ -283,6 +292,10 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     float m;
     if (UNION) {
         if (tid == 0) s_thr = 0.0f;
+    } else if (STATS_IN && opt.mean_parts) {
+        if (tid == 0) s_thr = T;                            // keep iff mean score > T
+        __syncthreads();
+        for (int i = tid; i < C; i += SEL_THREADS) s_e[i] = s_N[i] > 0 ? s_e[i] : 0.0f;
     } else if (STATS_IN) {
         m = row_max[row];
         if (tid == 0) s_thr = T * denom[row];
@@ -526,7 +539,7 @@ hipError_t launch_select(const float *logits, const float *row_max, const float 
                          int32_t *ranges, int32_t *n_ranges, int32_t *n_keys, DecodePlan plan, bool schedule, int U,
                          SelectOpts opt, int rows, int H, int Lq, int C, hipStream_t s)
 {
-    if (!ranges && !plan.rec && !schedule && !opt.parent_mask && !opt.len_from_offsets && keep_mask) {
+    if (!ranges && !plan.rec && !schedule && !opt.parent_mask && !opt.len_from_offsets && !opt.mean_parts && keep_mask) {
         // mask and counts only (prefill): one wave per row
         if (stats_in)
             hipLaunchKernelGGL(select_mask_kernel<true>, dim3((rows + 3) / 4), dim3(256), 0, s, logits, row_max, denom,

@@ -99,3 +99,122 @@ def test_cfg4_sparse_prefill_32k(sq, oracle):
     print("cfg4: comparing (selection on all 32768 rows, attention on 512 sampled rows)", flush=True)
     err = compare_prefill(oracle, w, P, "cfg4", sample=512, rng=np.random.default_rng(4))
     print("cfg4 attention max-abs err", err, "mean keep", P.n_keys.float().mean().item() / w.L, flush=True)
+
+
+# ---- selection on averaged scores + attention over one shared kept set (Appendix D, "Prefill Stage") ----------
+
+def mean_thresholds(oracle, w):
+    """Per-head thresholds on the AVERAGED scores that keep about w.keep_frac of the keys (oracle scores)."""
+    x, m, D = oracle.centroid_score(w.q, w.centroids, w.sizes, w.sm_scale)
+    sbar = oracle.select_mean(x, m, D, np.zeros(w.H, np.float32), w.sizes, w.offsets, want_scores=True)[4]
+    thr = np.empty(w.H, np.float32)
+    for h in range(w.H):
+        live = np.tile(w.sizes[h] > 0, w.B)
+        thr[h] = wl._cut(sbar[:, h].ravel()[live], np.tile(w.sizes[h], w.B)[live], w.keep_frac * w.L * w.B)
+    return thr, (x, m, D)
+
+
+def run_prefill_mean(sq, w, P):
+    sh = P.shape
+    d = P.q.device
+    W = (w.C + 31) // 32
+    mask = torch.zeros(w.B, w.H, W, dtype=torch.int32, device=d)
+    ranges = torch.zeros(w.B, w.H, w.C, 2, dtype=torch.int32, device=d)
+    nr = torch.zeros(w.B, w.H, dtype=torch.int32, device=d)
+    nk = torch.zeros(w.B, w.H, dtype=torch.int32, device=d)
+    sq.sq_centroid_score(sh, P.q, P.centroids, P.sizes, P.logits, P.row_max, P.denom)
+    sq.sq_select_mean(sh, P.logits, P.row_max, P.denom, P.thresh, P.sizes, P.offsets, mask, ranges, nr, nk,
+                      sq.workspace(sh, sq.SQ_CALL_SELECT_MEAN, d))
+    sq.sq_sparse_attn_prefill_shared(sh, P.q, P.K_fixed, P.V_fixed, ranges, nr, nk, P.K_user, P.V_user, P.out, P.lse,
+                                     sq.workspace(sh, sq.SQ_CALL_ATTN_PREFILL_SHARED, d))
+    torch.cuda.synchronize()
+    return mask.cpu().numpy(), ranges.cpu().numpy(), nr.cpu().numpy(), nk.cpu().numpy()
+
+
+def compare_prefill_mean(oracle, w, P, got, stats, label, sample=None, rng=None):
+    from oracle import literal
+    mask, ranges, nr, nk = got
+    x, m, D = stats
+    omask = oracle.select_mean(x, m, D, w.thresh, w.sizes, w.offsets)[0]
+    gk, ok = unpack_mask(mask, w.C), unpack_mask(omask, w.C)
+    listed = []
+    for b, h, c in np.argwhere(gk != ok):                  # disagreements must sit next to the threshold
+        sbar = literal.select_mean(w.q[b, h], w.centroids[h], w.sizes[h], w.thresh[h], w.sm_scale)[1]
+        assert literal.near_threshold(sbar[c], w.thresh[h]), (
+            f"{label} cluster {(b, h, c)}: gpu={gk[b, h, c]} oracle={ok[b, h, c]} mean score {sbar[c]:.9e} "
+            f"T={w.thresh[h]:.9e}")
+        listed.append((int(b), int(h), int(c), float(sbar[c]), float(w.thresh[h])))
+    if listed:
+        print(f"[near-threshold clusters {label}]", listed)
+    np.testing.assert_array_equal(nk, (gk * w.sizes[None]).sum(-1))
+    np.testing.assert_array_equal(nr, gk.sum(-1))
+    for b in range(w.B):
+        for h in range(w.H):
+            ids = np.flatnonzero(gk[b, h])
+            np.testing.assert_array_equal(ranges[b, h, :len(ids)], np.stack([w.offsets[h, ids], w.sizes[h, ids]], 1)
+                                          if len(ids) else np.zeros((0, 2), np.int32))
+    # attention over the GPU's own (validated) set, the same ranges for every query token of a (b, h)
+    R = (w.B, w.H, w.Lq)
+    sel = np.ones(R, bool)
+    if sample is not None:
+        sel = np.zeros(R, bool)
+        sel.ravel()[rng.choice(sel.size, size=sample, replace=False)] = True
+        sel[:, :, 0] = True; sel[:, :, -1] = True
+    cap = max(1, int(nr.max()))
+    rr = np.ascontiguousarray(np.broadcast_to(ranges[:, :, None, :cap], (*R, cap, 2)))
+    nn = np.ascontiguousarray(np.broadcast_to(nr[:, :, None], R))
+    out, lse = oracle.sparse_attn(w.q, w.K_fixed, w.V_fixed, rr, nn, w.K_user, w.V_user, w.sm_scale,
+                                  causal_user=w.causal_user, row_sel=sel)
+    err = np.abs(P.out.cpu().numpy().astype(np.float64)[sel] - out[sel]).max()
+    assert err <= ATTN_ATOL, f"{label}: attention max-abs error {err} over {sel.sum()} rows"
+    glse = P.lse.cpu().numpy()[sel]
+    fin = np.isfinite(lse[sel])
+    assert (np.isneginf(glse) == ~fin).all()
+    np.testing.assert_allclose(glse[fin], lse[sel][fin], atol=2e-4, rtol=1e-5)
+    return err
+
+
+@pytest.mark.parametrize("case", [
+    dict(B=1, H=2, L=512, C=16, Lq=64, U=64, keep_frac=0.3, causal_user=True),
+    dict(B=2, H=3, L=1000, C=37, Lq=70, U=70, keep_frac=0.25, causal_user=True),     # ragged everything
+    dict(B=1, H=2, L=2048, C=2048, Lq=33, U=10, keep_frac=0.3, causal_user=False),   # more clusters than one step
+    dict(B=1, H=1, L=300, C=8, Lq=5, U=0, keep_frac=0.5, causal_user=False),         # no user keys
+    dict(B=1, H=2, L=4096, C=128, Lq=200, U=200, keep_frac=0.125, causal_user=True),
+    dict(B=1, H=1, L=5000, C=50, Lq=130, U=3, keep_frac=0.6, causal_user=True),      # long kept list with a ragged tail
+])
+def test_prefill_mean_selection_small(sq, oracle, case):
+    w = wl.make_workload("prefill_mean", seed=23, threads=2, **case)
+    w.thresh, stats = mean_thresholds(oracle, w)
+    P = sq.upload(w)
+    got = run_prefill_mean(sq, w, P)
+    compare_prefill_mean(oracle, w, P, got, stats, f"prefill-mean{case}")
+
+
+def test_prefill_mean_selection_extremes(sq, oracle):
+    base = dict(B=1, H=2, L=700, C=20, Lq=40, U=40, keep_frac=0.5, causal_user=True, seed=24, threads=1)
+    for T, label in [(2.0, "nothing kept"), (-1.0, "everything kept")]:
+        w = wl.make_workload("prefill_mean_edge", **base)
+        w.thresh = np.full(w.H, T, np.float32)
+        stats = oracle.centroid_score(w.q, w.centroids, w.sizes, w.sm_scale)
+        P = sq.upload(w)
+        got = run_prefill_mean(sq, w, P)
+        assert (got[3] == (0 if T > 0 else w.L)).all()
+        compare_prefill_mean(oracle, w, P, got, stats, f"prefill-mean {label}")
+    # nothing kept and no user keys: zero output, lse = -inf
+    w = wl.make_workload("prefill_mean_void", **dict(base, U=0))
+    w.thresh = np.full(w.H, 2.0, np.float32)
+    P = sq.upload(w)
+    P.out.fill_(7.0)
+    run_prefill_mean(sq, w, P)
+    assert (P.out.cpu().numpy() == 0).all() and np.isneginf(P.lse.cpu().numpy()).all()
+
+
+def test_cfg4_shape_prefill_mean_selection(sq, oracle):
+    print("cfg4 (averaged selection): generating", flush=True)
+    w = wl.make_config("cfg4_prefill_32k", threads=16)
+    w.thresh, stats = mean_thresholds(oracle, w)
+    P = sq.upload(w)
+    print("cfg4 (averaged selection): running", flush=True)
+    got = run_prefill_mean(sq, w, P)
+    err = compare_prefill_mean(oracle, w, P, got, stats, "cfg4-mean", sample=512, rng=np.random.default_rng(5))
+    print("cfg4-mean attention max-abs err", err, "keep", got[3].mean() / w.L, flush=True)
