@@ -145,14 +145,19 @@ def bench_prefill(args, torch, sq, wl, dev):
     Ps = [sq.upload(w, dev) for _ in range(R)]
     shape = Ps[0].shape
     ws = sq.workspace(shape, sq.SQ_CALL_ATTN_PREFILL, dev)
+    ws_step = sq.workspace(shape, sq.SQ_CALL_PREFILL_STEP, dev)
 
     def step(i, stream_ptr):
         P = Ps[i % R]
-        sq.sq_centroid_score(shape, P.q, P.centroids, P.sizes, P.logits, P.row_max, P.denom)
-        sq.sq_select(shape, P.logits, P.row_max, P.denom, P.thresh, P.sizes, P.offsets, P.keep_mask, None,
-                     P.n_ranges, P.n_keys)
-        sq.sq_sparse_attn_prefill(shape, P.q, P.K_fixed, P.V_fixed, P.offsets, P.keep_mask, P.K_user, P.V_user,
-                                  P.out, P.lse, ws)
+        if args.separate:
+            sq.sq_centroid_score(shape, P.q, P.centroids, P.sizes, P.logits, P.row_max, P.denom)
+            sq.sq_select(shape, P.logits, P.row_max, P.denom, P.thresh, P.sizes, P.offsets, P.keep_mask, None,
+                         P.n_ranges, P.n_keys)
+            sq.sq_sparse_attn_prefill(shape, P.q, P.K_fixed, P.V_fixed, P.offsets, P.keep_mask, P.K_user, P.V_user,
+                                      P.out, P.lse, ws)
+        else:
+            sq.sq_prefill_step(shape, P.q, P.centroids, P.sizes, P.offsets, P.thresh, P.K_fixed, P.V_fixed, P.K_user,
+                               P.V_user, P.out, P.lse, None, P.n_keys, ws_step)
 
     if args.selection == "mean":
         return bench_prefill_mean(args, torch, sq, wl, dev, w, Ps)
@@ -174,7 +179,8 @@ def bench_prefill(args, torch, sq, wl, dev):
                       tokens)
     res["config"] = {"workload": args.workload, "B": w.B, "H": w.H, "d": w.d, "L": w.L, "C": w.C, "Lq": w.Lq,
                      "U": w.U, "keep_achieved": round(float(nk.mean() / w.L), 5), "replicas": R,
-                     "entry": "sq_centroid_score + sq_select + sq_sparse_attn_prefill"}
+                     "entry": "sq_centroid_score + sq_select + sq_sparse_attn_prefill" if args.separate
+                     else "sq_prefill_step"}
     res["flops_per_step"] = {"useful_attention": useful_attn, "scoring": score_flops,
                              "executed_attention_upper_bound": executed}
     res["roofline"] = {"bound": "mfma", "kernel": "prefill_attn_kernel",
@@ -201,6 +207,8 @@ def bench_prefill_mean(args, torch, sq, wl, dev, w, Ps):
     nk = torch.zeros(w.B, w.H, dtype=torch.int32, device=dev)
     ws_s = sq.workspace(shape, sq.SQ_CALL_SELECT_MEAN, dev)
     ws_a = sq.workspace(shape, sq.SQ_CALL_ATTN_PREFILL_SHARED, dev)
+    ws_step = sq.workspace(shape, sq.SQ_CALL_PREFILL_MEAN_STEP, dev)
+    nk_step = torch.zeros(w.B, w.H, dtype=torch.int32, device=dev)
     # Thresholds on the averaged scores that keep w.keep_frac of the keys per head: bisection on the library's own
     # counts (log domain), untimed.
     P = Ps[0]
@@ -219,13 +227,17 @@ def bench_prefill_mean(args, torch, sq, wl, dev, w, Ps):
 
     def step(i, stream_ptr):
         P = Ps[i % R]
-        sq.sq_centroid_score(shape, P.q, P.centroids, P.sizes, P.logits, P.row_max, P.denom)
-        sq.sq_select_mean(shape, P.logits, P.row_max, P.denom, thr, P.sizes, P.offsets, mask, ranges, nr, nk, ws_s)
-        sq.sq_sparse_attn_prefill_shared(shape, P.q, P.K_fixed, P.V_fixed, ranges, nr, nk, P.K_user, P.V_user, P.out,
-                                         P.lse, ws_a)
+        if args.separate:
+            sq.sq_centroid_score(shape, P.q, P.centroids, P.sizes, P.logits, P.row_max, P.denom)
+            sq.sq_select_mean(shape, P.logits, P.row_max, P.denom, thr, P.sizes, P.offsets, mask, ranges, nr, nk, ws_s)
+            sq.sq_sparse_attn_prefill_shared(shape, P.q, P.K_fixed, P.V_fixed, ranges, nr, nk, P.K_user, P.V_user,
+                                             P.out, P.lse, ws_a)
+        else:
+            sq.sq_prefill_mean_step(shape, P.q, P.centroids, P.sizes, P.offsets, thr, P.K_fixed, P.V_fixed, P.K_user,
+                                    P.V_user, P.out, P.lse, None, nk_step, ws_step)
 
     eager_ms, graph_ms, ms, (n_meas, k_avg, k_min, k_max) = time_steps(step, args, torch, sq)
-    nkh = nk.cpu().numpy().astype(np.float64)                     # [B,H]
+    nkh = (nk if args.separate else nk_step).cpu().numpy().astype(np.float64)   # [B,H]
     t = np.arange(w.Lq)
     user_vis = np.minimum(t + 1, w.U) if w.causal_user else np.full(w.Lq, w.U)
     useful_attn = float((nkh.sum() * w.Lq + w.B * w.H * user_vis.sum()) * 4 * w.d)
@@ -238,7 +250,8 @@ def bench_prefill_mean(args, torch, sq, wl, dev, w, Ps):
                       w.B * w.Lq)
     res["config"] = {"workload": args.workload, "selection": "mean", "B": w.B, "H": w.H, "d": w.d, "L": w.L,
                      "C": w.C, "Lq": w.Lq, "U": w.U, "keep_achieved": round(float(nkh.mean() / w.L), 5), "replicas": R,
-                     "entry": "sq_centroid_score + sq_select_mean + sq_sparse_attn_prefill_shared"}
+                     "entry": "sq_centroid_score + sq_select_mean + sq_sparse_attn_prefill_shared" if args.separate
+                     else "sq_prefill_mean_step"}
     res["flops_per_step"] = {"useful_attention": useful_attn, "scoring": score_flops, "executed_attention": executed}
     res["roofline"] = {"bound": "mfma", "kernel": "prefill_attn_kernel<shared>",
                        "achieved": round(useful_attn / (k_avg * 1e-6) / 1e12, 2) if n_meas else None,

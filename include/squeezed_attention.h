@@ -54,7 +54,9 @@ typedef enum sq_call {
     SQ_CALL_DECODE_STEP = 5,
     SQ_CALL_HIER_DECODE_STEP = 6,
     SQ_CALL_SELECT_MEAN = 7,
-    SQ_CALL_ATTN_PREFILL_SHARED = 8
+    SQ_CALL_ATTN_PREFILL_SHARED = 8,
+    SQ_CALL_PREFILL_STEP = 9,
+    SQ_CALL_PREFILL_MEAN_STEP = 10
 } sq_call;
 
 /*
@@ -214,6 +216,36 @@ int sq_decode_step(const sq_shape_t *shape, const void *q,
                    const void *K_fixed, const void *V_fixed, const void *K_user, const void *V_user,
                    void *out, float *lse, uint32_t *keep_mask, int32_t *n_keys,
                    void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * One whole prefill step with PER-QUERY selection: the lookup of sq_centroid_score + sq_select for every
+ * query token, then sq_sparse_attn_prefill.  The lookup makes two passes over the centroids (normaliser,
+ * then scores; Section 4.1) and writes no [queries x clusters] intermediate.  Its normaliser is summed in
+ * a different order than sq_centroid_score's, so a cluster whose score is within rounding of the threshold
+ * may be decided differently from the separate calls; everything else is identical.
+ * Out: out f16 [B,H,Lq,d]; optional (NULL to skip): lse f32 [B,H,Lq], keep_mask u32 [B,H,Lq,ceil(C/32)],
+ *      n_keys i32 [B,H,Lq].
+ * Workspace: sq_workspace_bytes(shape, SQ_CALL_PREFILL_STEP).
+ */
+int sq_prefill_step(const sq_shape_t *shape, const void *q,
+                    const void *centroids, const int32_t *sizes, const int32_t *offsets, const float *thresh,
+                    const void *K_fixed, const void *V_fixed, const void *K_user, const void *V_user,
+                    void *out, float *lse, uint32_t *keep_mask, int32_t *n_keys,
+                    void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * One whole prefill step with the selection on AVERAGED scores (Appendix D, "Prefill Stage"): the same
+ * two-pass lookup, the scores of Eq. 1 averaged over the Lq query tokens, one kept set per (sequence, head)
+ * as in sq_select_mean, then sq_sparse_attn_prefill_shared on it.  The same remark on rounding applies.
+ * Out: out f16 [B,H,Lq,d]; optional (NULL to skip): lse f32 [B,H,Lq], keep_mask u32 [B,H,ceil(C/32)],
+ *      n_keys i32 [B,H].
+ * Workspace: sq_workspace_bytes(shape, SQ_CALL_PREFILL_MEAN_STEP).
+ */
+int sq_prefill_mean_step(const sq_shape_t *shape, const void *q,
+                         const void *centroids, const int32_t *sizes, const int32_t *offsets, const float *thresh,
+                         const void *K_fixed, const void *V_fixed, const void *K_user, const void *V_user,
+                         void *out, float *lse, uint32_t *keep_mask, int32_t *n_keys,
+                         void *ws, size_t ws_bytes, void *stream);
 
 /*
  * One whole decode step with the two-level lookup (Lq must be 1): sq_hier_select followed by

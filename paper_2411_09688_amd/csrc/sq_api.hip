@@ -233,6 +233,41 @@ PrefillSharedWs carve_prefill_shared(Carver &cv, const sq_shape_t *sh)
     return w;
 }
 
+// Workspace of the whole prefill steps.
+struct PrefillStepWs {
+    uint32_t *mask;
+    int32_t *n_ranges, *n_keys, *key_cid, *blk_info;
+};
+
+PrefillStepWs carve_prefill_step(Carver &cv, const sq_shape_t *sh)
+{
+    const size_t rows = (size_t)sh->B * sh->H * sh->Lq;
+    PrefillStepWs w{};
+    w.mask = cv.take<uint32_t>(rows * ((sh->C + 31) / 32));
+    w.n_ranges = cv.take<int32_t>(rows);
+    w.n_keys = cv.take<int32_t>(rows);
+    w.key_cid = cv.take<int32_t>((size_t)sh->H * sh->L);
+    w.blk_info = cv.take<int32_t>((size_t)sh->H * ((sh->L + 63) / 64));
+    return w;
+}
+
+struct PrefillMeanStepWs {
+    float *part_sum;
+    int32_t *n_ranges, *n_keys;
+    PrefillSharedWs att;
+};
+
+PrefillMeanStepWs carve_prefill_mean_step(Carver &cv, const sq_shape_t *sh)
+{
+    const size_t rows = (size_t)sh->B * sh->H;
+    PrefillMeanStepWs w{};
+    w.part_sum = cv.take<float>(rows * sq::lookup_parts_for(sh->Lq) * sh->C);
+    w.n_ranges = cv.take<int32_t>(rows);
+    w.n_keys = cv.take<int32_t>(rows);
+    w.att = carve_prefill_shared(cv, sh);
+    return w;
+}
+
 int check_ws(const char *fn, const sq_shape_t *sh, int which, void *ws, size_t ws_bytes)
 {
     const size_t need = sq_workspace_bytes(sh, which);
@@ -277,6 +312,12 @@ size_t sq_workspace_bytes(const sq_shape_t *sh, int which)
         return cv.off;
     case SQ_CALL_ATTN_PREFILL_SHARED:
         carve_prefill_shared(cv, sh);
+        return cv.off;
+    case SQ_CALL_PREFILL_STEP:
+        carve_prefill_step(cv, sh);
+        return cv.off;
+    case SQ_CALL_PREFILL_MEAN_STEP:
+        carve_prefill_mean_step(cv, sh);
         return cv.off;
     case SQ_CALL_HIER_SELECT:
         carve_hier(cv, sh);
@@ -493,6 +534,72 @@ int sq_sparse_attn_prefill_shared(const sq_shape_t *sh, const void *q, const voi
     PrefillSharedWs w = carve_prefill_shared(cv, sh);
     SQ_HIP(sq::launch_ranges_to_rec(ranges, n_ranges, w.plan, sh->B * sh->H, sh->C, s));
     SQ_HIP(sq::launch_prefill_attn_shared(q, K_fixed, V_fixed, K_user, V_user, w.plan, w.key_idx, out, lse,
+                                          to_shape(sh), s));
+    g_err[0] = 0;
+    return SQ_OK;
+}
+
+// Pointer checks shared by the two whole prefill steps (same argument list).
+#define SQ_PREFILL_STEP_PTRS()      \
+    SQ_REQUIRE_PTR(q);              \
+    SQ_REQUIRE_PTR(centroids);      \
+    SQ_REQUIRE_PTR(sizes);          \
+    SQ_REQUIRE_PTR(offsets);        \
+    SQ_REQUIRE_PTR(thresh);         \
+    SQ_REQUIRE_PTR(K_fixed);        \
+    SQ_REQUIRE_PTR(V_fixed);        \
+    if (sh->U > 0) {                \
+        SQ_REQUIRE_PTR(K_user);     \
+        SQ_REQUIRE_PTR(V_user);     \
+    }                               \
+    SQ_REQUIRE_PTR(out);            \
+    SQ_OPTIONAL_PTR(lse);           \
+    SQ_OPTIONAL_PTR(keep_mask);     \
+    SQ_OPTIONAL_PTR(n_keys)
+
+int sq_prefill_step(const sq_shape_t *sh, const void *q, const void *centroids, const int32_t *sizes,
+                    const int32_t *offsets, const float *thresh, const void *K_fixed, const void *V_fixed,
+                    const void *K_user, const void *V_user, void *out, float *lse, uint32_t *keep_mask, int32_t *n_keys,
+                    void *ws, size_t ws_bytes, void *stream)
+{
+    if (int rc = check_shape(sh, __func__, false)) return rc;
+    SQ_PREFILL_STEP_PTRS();
+    if (int rc = check_ws(__func__, sh, SQ_CALL_PREFILL_STEP, ws, ws_bytes)) return rc;
+    if (int rc = check_device(__func__)) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Carver cv(ws);
+    PrefillStepWs w = carve_prefill_step(cv, sh);
+    uint32_t *mask = keep_mask ? keep_mask : w.mask;
+    SQ_HIP(sq::launch_prefill_lookup(q, centroids, sizes, thresh, mask, w.n_ranges, n_keys ? n_keys : w.n_keys, nullptr,
+                                     false, sh->B, sh->H, sh->Lq, sh->C, sh->sm_scale, s));
+    SQ_HIP(sq::launch_prefill_attn(q, K_fixed, V_fixed, K_user, V_user, mask, offsets, w.key_cid, w.blk_info, out, lse,
+                                   to_shape(sh), s));
+    g_err[0] = 0;
+    return SQ_OK;
+}
+
+int sq_prefill_mean_step(const sq_shape_t *sh, const void *q, const void *centroids, const int32_t *sizes,
+                         const int32_t *offsets, const float *thresh, const void *K_fixed, const void *V_fixed,
+                         const void *K_user, const void *V_user, void *out, float *lse, uint32_t *keep_mask,
+                         int32_t *n_keys, void *ws, size_t ws_bytes, void *stream)
+{
+    if (int rc = check_shape(sh, __func__, false)) return rc;
+    SQ_PREFILL_STEP_PTRS();
+    if (int rc = check_ws(__func__, sh, SQ_CALL_PREFILL_MEAN_STEP, ws, ws_bytes)) return rc;
+    if (int rc = check_device(__func__)) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Carver cv(ws);
+    PrefillMeanStepWs w = carve_prefill_mean_step(cv, sh);
+    const int rows = sh->B * sh->H;
+    SQ_HIP(sq::launch_prefill_lookup(q, centroids, sizes, thresh, nullptr, nullptr, nullptr, w.part_sum, true, sh->B,
+                                     sh->H, sh->Lq, sh->C, sh->sm_scale, s));
+    sq::SelectOpts opt{};
+    opt.mean_parts = sq::lookup_parts_for(sh->Lq);
+    opt.mean_div = (float)sh->Lq;
+    // the selection writes the kept ranges' records straight into the attention's plan
+    SQ_HIP(sq::launch_select(w.part_sum, nullptr, nullptr, true, thresh, sizes, offsets, keep_mask, nullptr, w.n_ranges,
+                             n_keys ? n_keys : w.n_keys, w.att.plan, false, 0, opt, rows, sh->H, 1, sh->C, s));
+    SQ_HIP(sq::launch_prefill_attn_shared(q, K_fixed, V_fixed, K_user, V_user, w.att.plan, w.att.key_idx, out, lse,
                                           to_shape(sh), s));
     g_err[0] = 0;
     return SQ_OK;

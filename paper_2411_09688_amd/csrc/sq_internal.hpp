@@ -59,6 +59,14 @@ constexpr int MEAN_ROWS = 64;
 inline int mean_parts_for(int Lq) { return (Lq + MEAN_ROWS - 1) / MEAN_ROWS; }
 hipError_t launch_mean_score(const float *logits, const float *row_max, const float *denom, float *part_sum, int BH,
                              int Lq, int C, hipStream_t s);
+// Fused prefill lookup (scores, statistics and the per-token decision in one kernel, nothing materialised): one
+// wave handles LOOKUP_ROWS query tokens.  mean == false writes keep_mask [B*H*Lq, ceil(C/32)] and the per-token
+// counts; mean == true writes part_sum [B*H, lookup_parts_for(Lq), C] for the selection on averaged scores.
+constexpr int LOOKUP_ROWS = 16;
+__host__ __device__ inline int lookup_parts_for(int Lq) { return (Lq + LOOKUP_ROWS - 1) / LOOKUP_ROWS; }
+hipError_t launch_prefill_lookup(const void *q, const void *centroids, const int32_t *sizes, const float *thresh,
+                                 uint32_t *keep_mask, int32_t *n_ranges, int32_t *n_keys, float *part_sum, bool mean,
+                                 int B, int H, int Lq, int C, float sm_scale, hipStream_t s);
 // Options of the row-wise selection for the two-level lookup (all zero for the one-level path).
 struct SelectOpts {
     const int32_t *parent_offsets;   // level 2: child_offsets [H, C1+1]; cluster i is a candidate iff its parent is kept

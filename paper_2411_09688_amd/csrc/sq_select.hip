@@ -278,8 +278,16 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
         // Averaged-score selection (Appendix D, prefill): the staged value is the mean score itself.
         const float *ps = logits + row * (size_t)opt.mean_parts * C;
         for (int i = tid; i < C; i += SEL_THREADS) {
-            float sum = 0.0f;
-            for (int p = 0; p < opt.mean_parts; ++p) sum += ps[(size_t)p * C + i];
+            float sum = 0.0f;                               // parts added in ascending order
+            int p = 0;
+            for (; p + 8 <= opt.mean_parts; p += 8) {       // eight loads in flight
+                float v8[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v8[u] = ps[(size_t)(p + u) * C + i];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) sum += v8[u];
+            }
+            for (; p < opt.mean_parts; ++p) sum += ps[(size_t)p * C + i];
             s_e[i] = sum / opt.mean_div;
             s_N[i] = N[i];
         }

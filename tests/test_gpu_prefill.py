@@ -27,12 +27,13 @@ def run_prefill(sq, w, P):
     torch.cuda.synchronize()
 
 
-def compare_prefill(oracle, w, P, label, sample=None, rng=None):
+def compare_prefill(oracle, w, P, label, sample=None, rng=None, logits=True):
     """Selection of every row against the oracle; attention on all rows or on `sample` random rows."""
     C = w.C
     x, m, D = oracle.centroid_score(w.q, w.centroids, w.sizes, w.sm_scale)
     mask, _, nr, nk = oracle.select(x, m, D, w.thresh, w.sizes, w.offsets)
-    np.testing.assert_allclose(P.logits.cpu().numpy(), x, atol=LOGIT_ATOL, rtol=0)
+    if logits:
+        np.testing.assert_allclose(P.logits.cpu().numpy(), x, atol=LOGIT_ATOL, rtol=0)
     gk = unpack_mask(P.keep_mask.cpu().numpy(), C)
     check_selection(w, gk, unpack_mask(mask, C), w.thresh, label=label)
     np.testing.assert_array_equal(P.n_keys.cpu().numpy(), (gk * w.sizes[None, :, None, :]).sum(-1))
@@ -147,6 +148,12 @@ def compare_prefill_mean(oracle, w, P, got, stats, label, sample=None, rng=None)
     if listed:
         print(f"[near-threshold clusters {label}]", listed)
     np.testing.assert_array_equal(nk, (gk * w.sizes[None]).sum(-1))
+    if ranges is None:                                    # (the whole-step call returns mask and counts only)
+        nr = gk.sum(-1).astype(np.int32)
+        ranges = np.zeros((w.B, w.H, w.C, 2), np.int32)
+        for b in range(w.B):
+            for h in range(w.H):
+                ranges[b, h], _ = ranges_from_keep(gk[b, h], w.offsets[h], w.sizes[h], w.C)
     np.testing.assert_array_equal(nr, gk.sum(-1))
     for b in range(w.B):
         for h in range(w.H):
@@ -218,3 +225,90 @@ def test_cfg4_shape_prefill_mean_selection(sq, oracle):
     got = run_prefill_mean(sq, w, P)
     err = compare_prefill_mean(oracle, w, P, got, stats, "cfg4-mean", sample=512, rng=np.random.default_rng(5))
     print("cfg4-mean attention max-abs err", err, "keep", got[3].mean() / w.L, flush=True)
+
+
+# ---- whole prefill steps (two-pass lookup with nothing materialised + attention) ---------------------------------
+
+STEP_CASES = [
+    dict(B=1, H=2, L=512, C=16, Lq=64, U=64, keep_frac=0.3, causal_user=True),
+    dict(B=2, H=3, L=1000, C=37, Lq=70, U=70, keep_frac=0.25, causal_user=True),     # ragged: C % 16, Lq % 16, words
+    dict(B=1, H=2, L=2048, C=2048, Lq=33, U=10, keep_frac=0.3, causal_user=False),   # many empty clusters
+    dict(B=1, H=1, L=300, C=8, Lq=5, U=0, keep_frac=0.5, causal_user=False),         # fewer clusters than a tile
+    dict(B=1, H=2, L=4096, C=128, Lq=200, U=200, keep_frac=0.125, causal_user=True),
+]
+
+
+def run_prefill_step(sq, w, P):
+    sh = P.shape
+    sq.sq_prefill_step(sh, P.q, P.centroids, P.sizes, P.offsets, P.thresh, P.K_fixed, P.V_fixed, P.K_user, P.V_user,
+                       P.out, P.lse, P.keep_mask, P.n_keys, sq.workspace(sh, sq.SQ_CALL_PREFILL_STEP, P.q.device))
+    torch.cuda.synchronize()
+
+
+def run_prefill_mean_step(sq, w, P):
+    sh, d = P.shape, P.q.device
+    mask = torch.zeros(w.B, w.H, (w.C + 31) // 32, dtype=torch.int32, device=d)
+    nk = torch.zeros(w.B, w.H, dtype=torch.int32, device=d)
+    sq.sq_prefill_mean_step(sh, P.q, P.centroids, P.sizes, P.offsets, P.thresh, P.K_fixed, P.V_fixed, P.K_user,
+                            P.V_user, P.out, P.lse, mask, nk, sq.workspace(sh, sq.SQ_CALL_PREFILL_MEAN_STEP, d))
+    torch.cuda.synchronize()
+    return mask.cpu().numpy(), None, None, nk.cpu().numpy()
+
+
+@pytest.mark.parametrize("case", STEP_CASES)
+def test_prefill_step_small(sq, oracle, case):
+    w = wl.calibrate(wl.make_workload("prefill_step", seed=25, threads=2, **case), oracle.scores)
+    P = sq.upload(w)
+    run_prefill_step(sq, w, P)
+    compare_prefill(oracle, w, P, f"prefill-step{case}", logits=False)
+
+
+@pytest.mark.parametrize("case", STEP_CASES)
+def test_prefill_mean_step_small(sq, oracle, case):
+    w = wl.make_workload("prefill_mean_step", seed=26, threads=2, **case)
+    w.thresh, stats = mean_thresholds(oracle, w)
+    P = sq.upload(w)
+    got = run_prefill_mean_step(sq, w, P)
+    compare_prefill_mean(oracle, w, P, got, stats, f"prefill-mean-step{case}")
+
+
+def test_prefill_steps_extremes_and_optional_outputs(sq, oracle):
+    base = dict(B=1, H=2, L=700, C=20, Lq=40, U=40, keep_frac=0.5, causal_user=True, seed=27, threads=1)
+    for T in (2.0, -1.0):                                  # nothing kept / everything kept
+        w = wl.make_workload("prefill_step_edge", **base)
+        w.thresh = np.full(w.H, T, np.float32)
+        P = sq.upload(w)
+        run_prefill_step(sq, w, P)
+        assert (P.n_keys.cpu().numpy() == (0 if T > 0 else w.L)).all()
+        compare_prefill(oracle, w, P, f"prefill-step T={T}", logits=False)
+        ref = P.out.clone()
+        stats = oracle.centroid_score(w.q, w.centroids, w.sizes, w.sm_scale)
+        got = run_prefill_mean_step(sq, w, P)
+        assert (got[3] == (0 if T > 0 else w.L)).all()
+        compare_prefill_mean(oracle, w, P, got, stats, f"prefill-mean-step T={T}")
+        # with one kept set for all tokens (all or nothing) the two rules select the same keys
+        assert (P.out.float() - ref.float()).abs().max().item() <= 1e-3
+    # optional outputs left out
+    w = wl.calibrate(wl.make_workload("prefill_step_opt", **base), oracle.scores)
+    P = sq.upload(w)
+    run_prefill_step(sq, w, P)
+    ref = P.out.clone()
+    P.out.zero_()
+    sq.sq_prefill_step(P.shape, P.q, P.centroids, P.sizes, P.offsets, P.thresh, P.K_fixed, P.V_fixed, P.K_user,
+                       P.V_user, P.out, None, None, None, sq.workspace(P.shape, sq.SQ_CALL_PREFILL_STEP, P.q.device))
+    torch.cuda.synchronize()
+    assert torch.equal(P.out, ref)
+
+
+def test_cfg4_prefill_steps(sq, oracle):
+    print("cfg4 (whole steps): generating", flush=True)
+    w = wl.calibrate(wl.make_config("cfg4_prefill_32k", threads=16), oracle.scores)
+    P = sq.upload(w)
+    run_prefill_step(sq, w, P)
+    err = compare_prefill(oracle, w, P, "cfg4-step", sample=256, rng=np.random.default_rng(6), logits=False)
+    print("cfg4 sq_prefill_step attention max-abs err", err, flush=True)
+    w.thresh, stats = mean_thresholds(oracle, w)
+    P = sq.upload(w)
+    got = run_prefill_mean_step(sq, w, P)
+    err = compare_prefill_mean(oracle, w, P, got, stats, "cfg4-mean-step", sample=256, rng=np.random.default_rng(7))
+    print("cfg4 sq_prefill_mean_step attention max-abs err", err, "keep", got[3].mean() / w.L, flush=True)
