@@ -3,10 +3,11 @@
 // normaliser of Eq. 1; pass 2 recomputes the same logits and turns them into scores, so no [queries x clusters]
 // intermediate is ever written to memory (the centroids are read twice instead, from L2).
 //
-// Scores run on the matrix cores as S^T = C Q^T (16x16x32 fp16 tiles: A = 16 centroids, loaded from global
-// memory directly in the operand layout, B = the wave's 16 query tokens, kept in registers), so a lane owns ONE
-// query token (column) and four centroids per tile: maximum, normaliser and threshold test are per-lane scalars,
-// combined over the four lane groups once per pass.  Waves never synchronise.
+// Scores run on the matrix cores as S^T = C Q^T (16x16x32 fp16 tiles: A = 16 centroids, B = a wave's 16 query
+// tokens, kept in registers), so a lane owns ONE query token (column) and four centroids per tile: maximum,
+// normaliser and threshold test are per-lane scalars, combined over the four lane groups once per pass.  The
+// four waves of a workgroup (64 tokens) share the centroid stream: groups of 64 centroids travel global memory ->
+// registers (issued two groups ahead) -> one of two LDS stages -> A operands, one barrier per group.
 //
 //   MEAN == false  per-query selection: keep cluster i for token t iff N_i > 0 and exp(x_i - m) > T * D; the
 //                  keep bits of two tiles are gathered into one mask word per token.
@@ -18,7 +19,14 @@
 
 namespace sq {
 
-constexpr int LK_TU = 4;         // centroid tiles in flight per step
+constexpr int LK_TU = 4;                     // centroid tiles per group
+constexpr int LK_G = LK_TU * 16;             // centroids per group
+constexpr int LK_STRIDE = D + 8;             // halves per centroid row in LDS (272 B: conflict-free 16-B reads)
+
+struct LkStage {
+    _Float16 Ct[LK_G * LK_STRIDE];
+    int N[LK_G];
+};
 
 template <bool MEAN>
 __global__ __launch_bounds__(256) void prefill_lookup_kernel(
@@ -26,16 +34,16 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
     const float *__restrict__ thresh, uint32_t *__restrict__ keep_mask, int32_t *__restrict__ n_ranges,
     int32_t *__restrict__ n_keys, float *__restrict__ part_sum, int H, int Lq, int C, float sm_scale)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __shared__ __align__(16) LkStage stage[2];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 15, kg = lane >> 4;
     const int bh = blockIdx.y, h = bh % H;
-    const int q0 = (blockIdx.x * 4 + wave) * LOOKUP_ROWS;   // first token of this wave
-    if (q0 >= Lq) return;                                   // this wave only: the kernel has no barrier
+    const int q0 = (blockIdx.x * 4 + wave) * LOOKUP_ROWS;   // first token of this wave (may lie past the end)
     const int nq = q0 + col;
     const bool valid = nq < Lq;
     const size_t row = (size_t)bh * Lq + min(nq, Lq - 1);
     const int W = (C + 31) >> 5;
-    const int nt = (C + 15) >> 4;
+    const int nt = (C + 15) >> 4, ng = (C + LK_G - 1) / LK_G;
 
     h8 bq[4];
     {
@@ -46,105 +54,129 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
     const char *ch = reinterpret_cast<const char *>(cent + (size_t)h * C * D);
     const int32_t *Nh = sizes + (size_t)h * C;
 
-    // Logits of LK_TU tiles starting at tile t0: x[u][v] = sm_scale * q . C_c, c = (t0+u)*16 + kg*4 + v, with
-    // the cluster sizes nv[u][v] (0 past the last cluster).
-    auto tiles = [&](int t0, float (&x)[LK_TU][4], int (&nv)[LK_TU][4]) {
-        h8 a[LK_TU][4];
+    // This thread's share of a group: rows i*16 + tid/16 (i = 0..3), 16-byte chunk tid%16; size of cluster tid.
+    h8 pk[4];
+    int pn = 0;
+    auto fetch = [&](int g) {
 #pragma unroll
-        for (int u = 0; u < LK_TU; ++u) {
-            const int c_row = min((t0 + u) * 16 + col, C - 1);              // rows past the end repeat the last one
-            const char *p = ch + (size_t)c_row * 256 + kg * 16;
-#pragma unroll
-            for (int s = 0; s < 4; ++s) a[u][s] = *reinterpret_cast<const h8 *>(p + s * 64);
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int c = (t0 + u) * 16 + kg * 4 + v;
-                nv[u][v] = c < C ? Nh[c] : 0;
-            }
+        for (int i = 0; i < 4; ++i) {
+            const int c_row = min(g * LK_G + i * 16 + (tid >> 4), C - 1);    // rows past the end repeat the last one
+            pk[i] = *reinterpret_cast<const h8 *>(ch + (size_t)c_row * 256 + (tid & 15) * 16);
         }
+        if (tid < LK_G) pn = g * LK_G + tid < C ? Nh[g * LK_G + tid] : 0;   // 0 past the last cluster
+    };
+    auto commit = [&](LkStage &st) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            *reinterpret_cast<h8 *>(st.Ct + (i * 16 + (tid >> 4)) * LK_STRIDE + (tid & 15) * 8) = pk[i];
+        if (tid < LK_G) st.N[tid] = pn;
+    };
+    // Logits of the staged group: x[u][v] = sm_scale * q . C_c, c = g*64 + u*16 + kg*4 + v, and the cluster sizes.
+    auto scores = [&](const LkStage &st, float (&x)[LK_TU][4], int (&nv)[LK_TU][4]) {
 #pragma unroll
         for (int u = 0; u < LK_TU; ++u) {
             f4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int s = 0; s < 4; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[u][s], bq[s], acc, 0, 0, 0);
+            for (int s = 0; s < 4; ++s) {
+                const h8 a = *reinterpret_cast<const h8 *>(st.Ct + (u * 16 + col) * LK_STRIDE + s * 32 + kg * 8);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bq[s], acc, 0, 0, 0);
+            }
+            const int4 n4 = *reinterpret_cast<const int4 *>(st.N + u * 16 + kg * 4);
+            nv[u][0] = n4.x;
+            nv[u][1] = n4.y;
+            nv[u][2] = n4.z;
+            nv[u][3] = n4.w;
 #pragma unroll
             for (int v = 0; v < 4; ++v) x[u][v] = acc[v] * sm_scale;
         }
     };
 
-    // ---- pass 1: m = max over clusters with keys, D = sum N_i exp(x_i - m), per token ---------------------------
-    float m = SQ_NEG_INF, Dsum = 0.0f;
-    for (int t0 = 0; t0 < nt; t0 += LK_TU) {
+    float m = SQ_NEG_INF, Dsum = 0.0f, thr = 0.0f;
+    uint32_t word = 0u;
+    int cnt = 0, keys = 0;
+    const int part = q0 / LOOKUP_ROWS, n_part = lookup_parts_for(Lq);
+
+    // One loop over both passes: iteration it handles group it % ng; the stream of groups never drains in between.
+    fetch(0);
+    commit(stage[0]);
+    if (2 * ng > 1) fetch(1 % ng);
+    __syncthreads();
+    for (int it = 0; it < 2 * ng; ++it) {
+        const int g = it % ng;
+        if (it + 1 < 2 * ng) {
+            commit(stage[(it + 1) & 1]);                    // group it+1 (in registers since the last iteration)
+            if (it + 2 < 2 * ng) fetch((it + 2) % ng);
+        }
         float x[LK_TU][4];
         int nv[LK_TU][4];
-        tiles(t0, x, nv);
-        float mt = m;
-#pragma unroll
-        for (int u = 0; u < LK_TU; ++u)
-#pragma unroll
-            for (int v = 0; v < 4; ++v)
-                if (nv[u][v] > 0) mt = fmaxf(mt, x[u][v]);
-        if (mt != SQ_NEG_INF) {
-            Dsum *= __expf(m - mt);                          // m = -inf: Dsum is 0 and stays 0
+        scores(stage[it & 1], x, nv);
+        if (it < ng) {
+            // ---- pass 1: m = max over clusters with keys, D = sum N_i exp(x_i - m), per token ---------------------
+            float mt = m;
 #pragma unroll
             for (int u = 0; u < LK_TU; ++u)
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
-                    if (nv[u][v] > 0) Dsum += (float)nv[u][v] * __expf(x[u][v] - mt);
-            m = mt;
-        }
-    }
+                    if (nv[u][v] > 0) mt = fmaxf(mt, x[u][v]);
+            if (mt != SQ_NEG_INF) {
+                Dsum *= __expf(m - mt);                      // m = -inf: Dsum is 0 and stays 0
 #pragma unroll
-    for (int off = 16; off <= 32; off <<= 1) {              // the four lane groups hold the other clusters of the token
-        const float mo = __shfl_xor(m, off), Do = __shfl_xor(Dsum, off);
-        const float M = fmaxf(m, mo);
-        const float wa = m == SQ_NEG_INF ? 0.0f : __expf(m - M), wb = mo == SQ_NEG_INF ? 0.0f : __expf(mo - M);
-        Dsum = Dsum * wa + Do * wb;
-        m = M;
-    }
-    const float thr = thresh[h] * Dsum;
-
-    // ---- pass 2: the same logits again, now as scores ---------------------------------------------------------------
-    uint32_t word = 0u;
-    int cnt = 0, keys = 0;
-    const int part = q0 / LOOKUP_ROWS, n_part = lookup_parts_for(Lq);
-    for (int t0 = 0; t0 < nt; t0 += LK_TU) {
-        float x[LK_TU][4];
-        int nv[LK_TU][4];
-        tiles(t0, x, nv);
-#pragma unroll
-        for (int u = 0; u < LK_TU; ++u) {
-            const int t = t0 + u;
-            if (t >= nt) break;                              // wave-uniform
-            float e[4];
-#pragma unroll
-            for (int v = 0; v < 4; ++v) e[v] = nv[u][v] > 0 ? __expf(x[u][v] - m) : 0.0f;
-            if (!MEAN) {
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const bool keep = nv[u][v] > 0 && e[v] > thr;
-                    word |= (uint32_t)keep << ((t & 1) * 16 + kg * 4 + v);
-                    cnt += keep;
-                    keys += keep ? nv[u][v] : 0;
-                }
-                if ((t & 1) || t == nt - 1) {                // a mask word is complete
-                    word |= __shfl_xor(word, 16);
-                    word |= __shfl_xor(word, 32);
-                    if (kg == 0 && valid) keep_mask[row * W + (t >> 1)] = word;
-                    word = 0u;
-                }
-            } else {
-                float sums[4];
-#pragma unroll
-                for (int v = 0; v < 4; ++v) sums[v] = row16_sum(valid && Dsum > 0.0f ? e[v] / Dsum : 0.0f);   // over the wave's tokens
-                if (col == 0) {
-                    float *dst = part_sum + ((size_t)bh * n_part + part) * C + t * 16 + kg * 4;
+                for (int u = 0; u < LK_TU; ++u)
 #pragma unroll
                     for (int v = 0; v < 4; ++v)
-                        if (t * 16 + kg * 4 + v < C) dst[v] = sums[v];
+                        if (nv[u][v] > 0) Dsum += (float)nv[u][v] * __expf(x[u][v] - mt);
+                m = mt;
+            }
+            if (it == ng - 1) {                              // the four lane groups hold the other clusters of the token
+#pragma unroll
+                for (int off = 16; off <= 32; off <<= 1) {
+                    const float mo = __shfl_xor(m, off), Do = __shfl_xor(Dsum, off);
+                    const float M = fmaxf(m, mo);
+                    const float wa = m == SQ_NEG_INF ? 0.0f : __expf(m - M);
+                    const float wb = mo == SQ_NEG_INF ? 0.0f : __expf(mo - M);
+                    Dsum = Dsum * wa + Do * wb;
+                    m = M;
+                }
+                thr = thresh[h] * Dsum;
+            }
+        } else {
+            // ---- pass 2: the same logits again, now as scores ---------------------------------------------------------
+#pragma unroll
+            for (int u = 0; u < LK_TU; ++u) {
+                const int t = g * LK_TU + u;
+                if (t >= nt) break;                          // workgroup-uniform
+                float e[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) e[v] = nv[u][v] > 0 ? __expf(x[u][v] - m) : 0.0f;
+                if (!MEAN) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const bool keep = nv[u][v] > 0 && e[v] > thr;
+                        word |= (uint32_t)keep << ((t & 1) * 16 + kg * 4 + v);
+                        cnt += keep;
+                        keys += keep ? nv[u][v] : 0;
+                    }
+                    if ((t & 1) || t == nt - 1) {            // a mask word is complete
+                        word |= __shfl_xor(word, 16);
+                        word |= __shfl_xor(word, 32);
+                        if (kg == 0 && valid) keep_mask[row * W + (t >> 1)] = word;
+                        word = 0u;
+                    }
+                } else {
+                    float sums[4];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)             // over the wave's tokens
+                        sums[v] = row16_sum(valid && Dsum > 0.0f ? e[v] / Dsum : 0.0f);
+                    if (col == 0 && part < n_part) {
+                        float *dst = part_sum + ((size_t)bh * n_part + part) * C + t * 16 + kg * 4;
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+                            if (t * 16 + kg * 4 + v < C) dst[v] = sums[v];
+                    }
                 }
             }
         }
+        __syncthreads();                                     // stage it & 1 may be overwritten; stage (it+1) & 1 is complete
     }
     if (!MEAN) {
         cnt += __shfl_xor(cnt, 16);
