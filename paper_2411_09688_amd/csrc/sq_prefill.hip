@@ -12,8 +12,8 @@
 //     keys per tile), so the running maximum, the running sum and the rescaling of the output are per-lane
 //     scalars, and P^T is repacked into the B operand of the next product in registers, with no
 //     cross-lane traffic;
-//   * O^T = V^T P^T uses A = V^T tiles read from an LDS copy of V that was transposed on the way in, with
-//     the keys of each 32-key group permuted so that the eight keys a lane needs are 16 contiguous bytes;
+//   * O^T = V^T P^T uses A = V^T tiles read from the row-major V tile with the transposing LDS read
+//     (ds_read_b64_tr_b16), so V goes to LDS with plain 16-byte stores;
 //   * the per-query keep masks are applied per (query, key): a small pre-kernel expands the cluster offsets
 //     into a key -> cluster map, each key block brings, for every query of the workgroup, the window of mask
 //     bits that covers its clusters, the bit of a (query, key) pair is moved to the sign with one shift and
@@ -34,7 +34,7 @@ namespace sq {
 
 constexpr int PF_BN = 64;                 // keys per block
 constexpr int PF_KS_STRIDE = D + 8;       // halves per K row in LDS (272 B: conflict-free 16-B reads)
-constexpr int PF_VT_STRIDE = PF_BN + 8;   // halves per V^T row in LDS (144 B)
+constexpr int PF_V_STRIDE = D + 16;       // halves per V row in LDS (288 B: the transposing reads below hit 32 distinct banks)
 
 // key -> cluster id map of every head (clusters are contiguous key ranges).
 __global__ __launch_bounds__(256) void key_cluster_kernel(const int32_t *__restrict__ offsets, int32_t *__restrict__ cid,
@@ -63,12 +63,15 @@ __global__ __launch_bounds__(256) void block_info_kernel(const int32_t *__restri
     blk_info[(size_t)h * nblk + blk] = first | (min(span, 30) << 16) | (span >= 31 ? (int)0x80000000 : 0);
 }
 
-// Position of key kappa (0..63) of a block inside a V^T row: within each 32-key group, key (t*16 + g*4 + j)
-// goes to g*8 + t*4 + j, so that the B operand's keys (two accumulator tiles x 4 keys) are contiguous.
-__device__ __forceinline__ int vt_pos(int kappa)
+// A-operand of O^T += V^T P^T from a ROW-MAJOR V tile in LDS, with the CDNA4 transposing LDS read: within each
+// group of 16 lanes, lane i receives element i % 4 of the four halves addressed by lanes i/4, 4 + i/4, 8 + i/4 and
+// 12 + i/4.  With lane 4r + c of a group pointing at V[key0 + r][d0 + 4c .. +4], lane i gets V[key0 + 0..3][d0 + i]:
+// four consecutive keys of one dimension, which is what the operand wants, and no transposed copy is ever written.
+typedef __fp16 tr_h4 __attribute__((__vector_size__(4 * sizeof(__fp16))));
+__device__ __forceinline__ h4 lds_read_tr16(const _Float16 *p)
 {
-    const int ks = kappa >> 5, k2 = kappa & 31, t = k2 >> 4, g = (k2 & 15) >> 2, j = k2 & 3;
-    return ks * 32 + g * 8 + t * 4 + j;
+    typedef __attribute__((address_space(3))) tr_h4 *lds_ptr_t;
+    return __builtin_bit_cast(h4, __builtin_amdgcn_ds_read_tr16_b64_v4f16((lds_ptr_t)(p)));
 }
 
 // Kept ranges of every (sequence, head) row -> list of key rows: record (first key, count, keys before) writes
@@ -90,7 +93,7 @@ constexpr int PF_BM = 64 * PF_QT;         // queries per workgroup (4 waves)
 
 struct PfStage {                          // one LDS buffer of a key block
     _Float16 K[PF_BN * PF_KS_STRIDE];
-    _Float16 Vt[D * PF_VT_STRIDE];
+    _Float16 V[PF_BN * PF_V_STRIDE];
     int cid[PF_BN];                       // cluster of each key (0x7fffffff past the end)
     int sh[PF_BN];                        // 31 - (cluster - first cluster of the block); 0 for keys past the end
     uint32_t qbits[PF_BM];                // per query: mask bits of clusters first .. first+30, bit 31 clear
@@ -171,19 +174,17 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
     h8 pk[4], pv[4];
     int pcid = 0, pinfo = 0;
     uint32_t pw_lo = 0u, pw_hi = 0u;
-    // Byte offsets of this thread's pieces inside a 64-key block (rows of 256 B): K piece i = key
-    // i*16 + tid/16, 16-byte chunk tid%16; V = key `lane`, four chunks starting at wave*4.
+    // Byte offset of this thread's pieces inside a 64-key block (rows of 256 B), the same for K and V: piece i =
+    // key i*16 + tid/16, 16-byte chunk tid%16.
     const uint32_t k_off = (uint32_t)(tid >> 4) * 256u + (uint32_t)(tid & 15) * 16u;
-    const uint32_t v_off = (uint32_t)lane * 256u + (uint32_t)wave * 64u;
-    // SHARED: rows of this thread's K pieces (keys i*16 + tid/16) and V piece (key `lane`) of a fixed block; the
-    // indices of block b+2 are loaded while block b is computed and used when block b+1's rows are fetched.
-    int ik_n[4] = {0, 0, 0, 0}, iv_n = 0, ik_c[4] = {0, 0, 0, 0}, iv_c = 0;
+    // SHARED: rows of this thread's pieces (keys i*16 + tid/16) of a fixed block; the indices of block b+2 are
+    // loaded while block b is computed and used when block b+1's rows are fetched.
+    int ik_n[4] = {0, 0, 0, 0}, ik_c[4] = {0, 0, 0, 0};
     auto fetch_idx = [&](int blk) {
         if (!SHARED || blk >= nblk_fixed) return;
         const int j0 = blk * PF_BN, last = n_fixed - 1;
 #pragma unroll
         for (int i = 0; i < 4; ++i) ik_n[i] = idx_bh[min(j0 + i * 16 + (tid >> 4), last)];
-        iv_n = idx_bh[min(j0 + lane, last)];
     };
     auto fetch = [&](int blk) {           // issue the global loads of block `blk`
         const bool user = blk >= nblk_fixed;
@@ -196,7 +197,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
                 pk[i] = *reinterpret_cast<const h8 *>(Kb + (size_t)ik_c[i] * 256 + (uint32_t)(tid & 15) * 16u);
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                pv[i] = *reinterpret_cast<const h8 *>(Vb + (size_t)iv_c * 256 + (uint32_t)(wave * 4 + i) * 16u);
+                pv[i] = *reinterpret_cast<const h8 *>(Vb + (size_t)ik_c[i] * 256 + (uint32_t)(tid & 15) * 16u);
             return;
         }
         const char *Kb = reinterpret_cast<const char *>(user ? Kuh : Kfh) + (size_t)j0 * 256;
@@ -205,18 +206,15 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
 #pragma unroll
             for (int i = 0; i < 4; ++i) pk[i] = *reinterpret_cast<const h8 *>(Kb + (k_off + (uint32_t)i * 4096u));
 #pragma unroll
-            for (int i = 0; i < 4; ++i) pv[i] = *reinterpret_cast<const h8 *>(Vb + (v_off + (uint32_t)i * 16u));
+            for (int i = 0; i < 4; ++i) pv[i] = *reinterpret_cast<const h8 *>(Vb + (k_off + (uint32_t)i * 4096u));
         } else {                          // last block of a tensor: rows past the end re-read the last row
             const int last = nkeys - 1 - j0;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int key = min(i * 16 + (tid >> 4), last);
                 pk[i] = *reinterpret_cast<const h8 *>(Kb + (uint32_t)key * 256u + (uint32_t)(tid & 15) * 16u);
+                pv[i] = *reinterpret_cast<const h8 *>(Vb + (uint32_t)key * 256u + (uint32_t)(tid & 15) * 16u);
             }
-            const int keyv = min(lane, last);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                pv[i] = *reinterpret_cast<const h8 *>(Vb + (uint32_t)keyv * 256u + (uint32_t)(wave * 4 + i) * 16u);
         }
         if (!user && !SHARED) {
             pinfo = binfo[blk];
@@ -228,19 +226,13 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
             }
         }
     };
-    auto commit = [&](int blk, PfStage &st) {   // registers -> LDS (K rows, V transposed, ids, mask bits)
+    auto commit = [&](int blk, PfStage &st) {   // registers -> LDS (K rows, V rows, ids, mask bits)
         const bool user = blk >= nblk_fixed;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int key = i * 16 + (tid >> 4), chunk = tid & 15;
             *reinterpret_cast<h8 *>(st.K + key * PF_KS_STRIDE + chunk * 8) = pk[i];
-        }
-        {
-            const int pos = vt_pos(lane);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) st.Vt[((wave * 4 + i) * 8 + e) * PF_VT_STRIDE + pos] = pv[i][e];
+            *reinterpret_cast<h8 *>(st.V + key * PF_V_STRIDE + chunk * 8) = pv[i];
         }
         if (!user && !SHARED) {
             const int first = pinfo & 0xffff;
@@ -258,7 +250,6 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
     auto take_idx = [&]() {
 #pragma unroll
         for (int i = 0; i < 4; ++i) ik_c[i] = ik_n[i];
-        iv_c = iv_n;
     };
     int info_cur = 0;
     if (nblk > 0) {                                       // (no kept key and no user key: nothing to stage)
@@ -404,7 +395,10 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
             for (int dt = 0; dt < 8; ++dt) {
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
-                    const h8 a = *reinterpret_cast<const h8 *>(st.Vt + (dt * 16 + col) * PF_VT_STRIDE + ks * 32 + kg * 8);
+                    // keys ks*32 + t*16 + kg*4 + (0..3) for t = 0, 1: the order P^T was packed in
+                    const _Float16 *vp = st.V + (ks * 32 + kg * 4 + (col >> 2)) * PF_V_STRIDE + dt * 16 + (col & 3) * 4;
+                    const h4 a0 = lds_read_tr16(vp), a1 = lds_read_tr16(vp + 16 * PF_V_STRIDE);
+                    const h8 a = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
 #pragma unroll
                     for (int qt = 0; qt < QT; ++qt)
                         o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bp[qt][ks], o[qt][dt], 0, 0, 0);
