@@ -16,9 +16,10 @@
 //     (ds_read_b64_tr_b16), so V goes to LDS with plain 16-byte stores;
 //   * the per-query keep masks are applied per (query, key): a small pre-kernel expands the cluster offsets
 //     into a key -> cluster map, each key block brings, for every query of the workgroup, the window of mask
-//     bits that covers its clusters, the bit of a (query, key) pair is moved to the sign with one shift and
-//     blended into the score with one bit-select, and a wave skips the products of a block none of its
-//     queries kept.
+//     bits that covers its clusters, the bit of a (query, key) pair is spread over a word with one signed
+//     bit-field extract and blended into the score with one bit-select, and a wave skips the products of a
+//     block none of its queries kept.  The mask arithmetic is issued behind the S^T products, in the same
+//     straight-line block, so the vector ALU works while the matrix cores do.
 // The user block is causal when causal_user is set (query t sees user keys 0..t); the fixed context is
 // always fully visible.
 //
@@ -95,7 +96,8 @@ struct PfStage {                          // one LDS buffer of a key block
     _Float16 K[PF_BN * PF_KS_STRIDE];
     _Float16 V[PF_BN * PF_V_STRIDE];
     int cid[PF_BN];                       // cluster of each key (0x7fffffff past the end)
-    int sh[PF_BN];                        // 31 - (cluster - first cluster of the block); 0 for keys past the end
+    int sh[PF_BN];                        // bit of the key's cluster in the staged window: cluster - first cluster of
+                                          // the block (31, a bit that is never set, for keys past the end)
     uint32_t qbits[PF_BM];                // per query: mask bits of clusters first .. first+30, bit 31 clear
 };
 
@@ -238,7 +240,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
             const int first = pinfo & 0xffff;
             if (tid < PF_BN) {
                 st.cid[tid] = pcid;
-                st.sh[tid] = pcid == 0x7fffffff ? 0 : 31 - min(pcid - first, 31);
+                st.sh[tid] = pcid == 0x7fffffff ? 31 : min(pcid - first, 31);
             }
             if (tid < BM) {
                 const unsigned long long two = ((unsigned long long)pw_hi << 32) | pw_lo;
@@ -275,65 +277,11 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
 
         // ---- visibility of this lane's (query, key) pairs: msk = all ones (visible) or zero ------------------
         // element e = kt*4 + v  <->  key kt*16 + kg*4 + v of the block, query nq[qt].
-        uint32_t msk[QT][16];
-        bool any;
-        if (SHARED && !user) {
-            // One kept set for every query: only slots past the kept keys (last block) are hidden.
-            any = true;
-#pragma unroll
-            for (int qt = 0; qt < QT; ++qt)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int j = j0 + (e >> 2) * 16 + kg * 4 + (e & 3);
-                    msk[qt][e] = (j < n_fixed && nq[qt] < Lq) ? 0xffffffffu : 0u;
-                }
-        } else if (!user && info >= 0) {
-            // Fixed context, usual case: bit (cluster - first) of the query's staged window, moved to the sign.
-            const uint32_t present = (2u << ((info >> 16) & 31)) - 1u;       // local clusters that occur in the block
-            int sh[16];
-#pragma unroll
-            for (int kt = 0; kt < 4; ++kt) {
-                const int4 s4 = *reinterpret_cast<const int4 *>(st.sh + kt * 16 + kg * 4);
-                sh[kt * 4 + 0] = s4.x;
-                sh[kt * 4 + 1] = s4.y;
-                sh[kt * 4 + 2] = s4.z;
-                sh[kt * 4 + 3] = s4.w;
-            }
-            any = false;
-#pragma unroll
-            for (int qt = 0; qt < QT; ++qt) {
-                const uint32_t qb = st.qbits[wave * 16 * QT + qt * 16 + col];
-                any |= (qb & present) != 0u;
-#pragma unroll
-                for (int e = 0; e < 16; ++e) msk[qt][e] = (uint32_t)((int)(qb << sh[e]) >> 31);
-            }
-        } else if (!user) {
-            // Fixed context, block spanning more than 31 cluster ids: look every bit up in the mask itself.
-            any = false;
-#pragma unroll
-            for (int qt = 0; qt < QT; ++qt) {
-                const uint32_t *mrow = keep_mask + (row0 + min(nq[qt], Lq - 1)) * W;
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int c = st.cid[(e >> 2) * 16 + kg * 4 + (e & 3)];
-                    const bool ok = c < C && nq[qt] < Lq && ((mrow[c >> 5] >> (c & 31)) & 1u);
-                    msk[qt][e] = ok ? 0xffffffffu : 0u;
-                    any |= ok;
-                }
-            }
-        } else {
-            any = !causal_user || j0 <= q0 + wave * 16 * QT + 16 * QT - 1;
-#pragma unroll
-            for (int qt = 0; qt < QT; ++qt)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int j = j0 + (e >> 2) * 16 + kg * 4 + (e & 3);
-                    const bool ok = j < U && nq[qt] < Lq && (!causal_user || j <= nq[qt]);
-                    msk[qt][e] = ok ? 0xffffffffu : 0u;
-                }
-        }
-
-        if (__ballot(any) != 0ull) {                        // else: none of this wave's queries sees the block
+        // One block for the queries of this wave: the products S^T = K Q^T are issued first, so that the matrix
+        // cores work while `make_masks` (inlined, branch-free in the common cases) expands the visibility of this
+        // lane's (query, key) pairs: msk = all ones (visible) or zero; element e = kt*4 + v <-> key kt*16 + kg*4 + v
+        // of the block, query nq[qt].
+        auto block = [&](auto make_masks) {
             // ---- S^T = K Q^T ---------------------------------------------------------------------------------
             f4 sacc[QT][4];
 #pragma unroll
@@ -341,15 +289,17 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
 #pragma unroll
                 for (int kt = 0; kt < 4; ++kt) sacc[qt][kt] = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int kt = 0; kt < 4; ++kt) {
+            for (int s = 0; s < 4; ++s) {
 #pragma unroll
-                for (int s = 0; s < 4; ++s) {
+                for (int kt = 0; kt < 4; ++kt) {            // four independent accumulators in turn
                     const h8 a = *reinterpret_cast<const h8 *>(st.K + (kt * 16 + col) * PF_KS_STRIDE + s * 32 + kg * 8);
 #pragma unroll
                     for (int qt = 0; qt < QT; ++qt)
                         sacc[qt][kt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bq[qt][s], sacc[qt][kt], 0, 0, 0);
                 }
             }
+            uint32_t msk[QT][16];
+            make_masks(msk);
 
             // ---- online softmax per query column; P^T packed as the B operand of the next product ------------
             h8 bp[QT][2];
@@ -392,9 +342,9 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
 
             // ---- O^T += V^T P^T ------------------------------------------------------------------------------
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt) {
+            for (int ks = 0; ks < 2; ++ks) {
 #pragma unroll
-                for (int ks = 0; ks < 2; ++ks) {
+                for (int dt = 0; dt < 8; ++dt) {
                     // keys ks*32 + t*16 + kg*4 + (0..3) for t = 0, 1: the order P^T was packed in
                     const _Float16 *vp = st.V + (ks * 32 + kg * 4 + (col >> 2)) * PF_V_STRIDE + dt * 16 + (col & 3) * 4;
                     const h4 a0 = lds_read_tr16(vp), a1 = lds_read_tr16(vp + 16 * PF_V_STRIDE);
@@ -404,6 +354,72 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
                         o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bp[qt][ks], o[qt][dt], 0, 0, 0);
                 }
             }
+        };
+
+        if (SHARED && !user) {
+            // One kept set for every query: only slots past the kept keys (last block) are hidden.
+            block([&](uint32_t (&msk)[QT][16]) {
+#pragma unroll
+                for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int j = j0 + (e >> 2) * 16 + kg * 4 + (e & 3);
+                        msk[qt][e] = (j < n_fixed && nq[qt] < Lq) ? 0xffffffffu : 0u;
+                    }
+            });
+        } else if (!user && info >= 0) {
+            // Fixed context, usual case: bit (cluster - first cluster of the block) of the query's staged window.
+            const uint32_t present = (2u << ((info >> 16) & 31)) - 1u;       // local clusters that occur in the block
+            uint32_t qb[QT];
+            bool any = false;
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt) {
+                qb[qt] = st.qbits[wave * 16 * QT + qt * 16 + col];
+                any |= (qb[qt] & present) != 0u;
+            }
+            if (__ballot(any) != 0ull) {                    // else: none of this wave's queries kept a cluster of the block
+                block([&](uint32_t (&msk)[QT][16]) {
+                    int bit[16];
+#pragma unroll
+                    for (int kt = 0; kt < 4; ++kt) {
+                        const int4 b4 = *reinterpret_cast<const int4 *>(st.sh + kt * 16 + kg * 4);
+                        bit[kt * 4 + 0] = b4.x;
+                        bit[kt * 4 + 1] = b4.y;
+                        bit[kt * 4 + 2] = b4.z;
+                        bit[kt * 4 + 3] = b4.w;
+                    }
+#pragma unroll
+                    for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e)
+                            msk[qt][e] = (uint32_t)__builtin_amdgcn_sbfe((int)qb[qt], (uint32_t)bit[e], 1u);
+                });
+            }
+        } else if (!user) {
+            // Fixed context, block spanning more than 31 cluster ids: look every bit up in the mask itself.
+            block([&](uint32_t (&msk)[QT][16]) {
+#pragma unroll
+                for (int qt = 0; qt < QT; ++qt) {
+                    const uint32_t *mrow = keep_mask + (row0 + min(nq[qt], Lq - 1)) * W;
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int c = st.cid[(e >> 2) * 16 + kg * 4 + (e & 3)];
+                        const bool ok = c < C && nq[qt] < Lq && ((mrow[c >> 5] >> (c & 31)) & 1u);
+                        msk[qt][e] = ok ? 0xffffffffu : 0u;
+                    }
+                }
+            });
+        } else if (!causal_user || j0 <= q0 + wave * 16 * QT + 16 * QT - 1) {   // else: the block lies in every query's future
+            block([&](uint32_t (&msk)[QT][16]) {
+#pragma unroll
+                for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int j = j0 + (e >> 2) * 16 + kg * 4 + (e & 3);
+                        const bool ok = j < U && nq[qt] < Lq && (!causal_user || j <= nq[qt]);
+                        msk[qt][e] = ok ? 0xffffffffu : 0u;
+                    }
+            });
         }
 
         // ---- next block: registers -> the other LDS buffer; one barrier per block --------------------------
