@@ -297,7 +297,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
             s_N[i] = N[i];
         }
     }
-    float m;
+    float m, thr = 0.0f;
     if (UNION) {
         if (tid == 0) s_thr = 0.0f;
     } else if (STATS_IN && opt.mean_parts) {
@@ -321,7 +321,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
 #pragma unroll
         for (int w = 1; w < SEL_WAVES; ++w) m = fmaxf(m, s_wred[w]);
         for (int i = tid; i < C; i += SEL_THREADS) s_e[i] = s_N[i] > 0 ? expf(s_e[i] - m) : 0.0f;
-        __syncthreads();
+        __syncthreads();                                     // every wave has read the maxima: s_wred is reused below
         // D in the library's one summation order (see wave_row_stats): thread v adds clusters v, v+1024, ...
         // ascending, butterfly inside each wave, then the 16 wave sums in ascending order.
         float local = 0.0f;
@@ -332,15 +332,15 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
         local = wave_sum(local);
         if (lane == 0) s_wred[wave] = local;
         __syncthreads();
-        if (tid == 0) {
-            float Dsum = 0.0f;
+        float Dsum = 0.0f;                                   // every thread adds the 16 wave sums, in the same order
 #pragma unroll
-            for (int w = 0; w < SEL_WAVES; ++w) Dsum += s_wred[w];
-            s_thr = T * Dsum;
-        }
+        for (int w = 0; w < SEL_WAVES; ++w) Dsum += s_wred[w];
+        thr = T * Dsum;
     }
-    __syncthreads();
-    const float thr = s_thr;
+    if (UNION || STATS_IN) {
+        __syncthreads();
+        thr = s_thr;
+    }
 
     // Compaction in two passes over the (up to 16) block-wide steps, with one barrier between them.
     // Pass 1: every wave counts the ranges it will emit and their keys, step by step, into a small LDS
@@ -371,36 +371,68 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
         }
     }
     __syncthreads();
-    if (wave == 0) {                                     // exclusive prefix of the n_steps*16 (<= 256) entries
-        const int n_ent = n_steps * SEL_WAVES;
-        int c4[4], k4[4], cs = 0, ks = 0;
+    // Work items of the row are placed at a base taken from a device-wide counter (zeroed by the scoring kernel
+    // that ran before): rows land in arrival order, which moves chunks between workgroups but changes no result.
+    // The add is issued as soon as the row's totals are known, so its round trip runs under the second pass.
+    auto take_items = [&](int total_keys) {
+        const int n_items = n_user_chunks * n_seq + (min(total_keys, plan.L) + KPC - 1) / KPC;
+        // One 64-bit add advances (items, rows placed) together, so rows are ranked in item order.
+        const unsigned long long old = atomicAdd(reinterpret_cast<unsigned long long *>(plan.total),
+                                                 (1ull << 32) | (unsigned long long)(unsigned)n_items);
+        s_base = (int)(old & 0xffffffffull);
+        if (plan.row_rank) plan.row_rank[row] = (int)(old >> 32);
+    };
+    int base_r, base_k;                                      // totals of the row
+    int pre_r = 0, pre_k = 0;                                // single step: records / keys of the waves before this one
+    if (n_steps == 1) {
+        // One step: every thread adds the 16 per-wave counts itself (no second barrier).
+        base_r = 0;
+        base_k = 0;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int e = lane * 4 + u;
-            c4[u] = e < n_ent ? s_tcnt[e] : 0;
-            k4[u] = e < n_ent ? s_tkeys[e] : 0;
-            cs += c4[u];
-            ks += k4[u];
-        }
-        int cpre = wave_inclusive_scan(cs, lane) - cs, kpre = wave_inclusive_scan(ks, lane) - ks;
-        const int ctot = __shfl(cpre + cs, 63), ktot = __shfl(kpre + ks, 63);
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int e = lane * 4 + u;
-            if (e < n_ent) {
-                s_tcnt[e] = cpre;
-                s_tkeys[e] = kpre;
+        for (int w = 0; w < SEL_WAVES; ++w) {
+            const int c = s_tcnt[w], k = s_tkeys[w];
+            if (w < wave) {
+                pre_r += c;
+                pre_k += k;
             }
-            cpre += c4[u];
-            kpre += k4[u];
+            base_r += c;
+            base_k += k;
         }
-        if (lane == 0) {
-            s_tcnt[16 * SEL_WAVES] = ctot;
-            s_tkeys[16 * SEL_WAVES] = ktot;
+        if (SCHEDULE && tid == 0) take_items(base_k);
+    } else {
+        if (wave == 0) {                                     // exclusive prefix of the n_steps*16 (<= 256) entries
+            const int n_ent = n_steps * SEL_WAVES;
+            int c4[4], k4[4], cs = 0, ks = 0;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int e = lane * 4 + u;
+                c4[u] = e < n_ent ? s_tcnt[e] : 0;
+                k4[u] = e < n_ent ? s_tkeys[e] : 0;
+                cs += c4[u];
+                ks += k4[u];
+            }
+            int cpre = wave_inclusive_scan(cs, lane) - cs, kpre = wave_inclusive_scan(ks, lane) - ks;
+            const int ctot = __shfl(cpre + cs, 63), ktot = __shfl(kpre + ks, 63);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int e = lane * 4 + u;
+                if (e < n_ent) {
+                    s_tcnt[e] = cpre;
+                    s_tkeys[e] = kpre;
+                }
+                cpre += c4[u];
+                kpre += k4[u];
+            }
+            if (lane == 0) {
+                s_tcnt[16 * SEL_WAVES] = ctot;
+                s_tkeys[16 * SEL_WAVES] = ktot;
+                if (SCHEDULE) take_items(ktot);
+            }
         }
+        __syncthreads();
+        base_r = s_tcnt[16 * SEL_WAVES];
+        base_k = s_tkeys[16 * SEL_WAVES];
     }
-    __syncthreads();
-    const int base_r = s_tcnt[16 * SEL_WAVES], base_k = s_tkeys[16 * SEL_WAVES];   // totals of the row
     bool have_rec = false;                                   // this thread's record of the (only) step
     int my_r = 0;
     int4 my_rec = make_int4(0, 0, 0, 0);
@@ -419,9 +451,10 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
         const int kv = emit ? len : 0;
         const int incl = wave_inclusive_scan(kv, lane);
         if (emit) {
-            const int r = s_tcnt[st * SEL_WAVES + wave] + rank;
+            const int r = (n_steps == 1 ? pre_r : s_tcnt[st * SEL_WAVES + wave]) + rank;
+            const int kbefore = (n_steps == 1 ? pre_k : s_tkeys[st * SEL_WAVES + wave]) + incl - kv;
             if (ranges) *reinterpret_cast<int2 *>(ranges + (row * C + r) * 2) = make_int2(start, len);
-            my_rec = make_int4(start, len, s_tkeys[st * SEL_WAVES + wave] + incl - kv, UNION ? (int)s_set[i] : 0);
+            my_rec = make_int4(start, len, kbefore, UNION ? (int)s_set[i] : 0);
             my_r = r;
             have_rec = true;
             if (plan.rec) plan.rec[row * plan.rec_cap + r] = my_rec;
@@ -435,20 +468,11 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
         if (plan.rec) plan.hdr[row] = make_int2(base_r, base_k);
     }
     if (SCHEDULE) {
-        // This row's work items, placed at a base taken from a device-wide counter (zeroed by the scoring
-        // kernel that ran before): rows land in arrival order, which moves chunks between workgroups but
-        // changes no result.  The records written above are read back after the barrier.
+        // This row's work items (their base was taken above).  The records written above are read back after
+        // the barrier.
         const int n_sel = min(base_k, plan.L);
         const int n_uc = n_user_chunks * n_seq;             // every sequence of a union row has its own user keys
         __syncthreads();                                    // every thread is done with the staged row (s_first aliases it)
-        if (tid == 0) {
-            // One 64-bit add advances (items, rows placed) together, so rows are ranked in item order.
-            const unsigned long long old =
-                atomicAdd(reinterpret_cast<unsigned long long *>(plan.total),
-                          (1ull << 32) | (unsigned long long)(unsigned)(n_uc + (n_sel + KPC - 1) / KPC));
-            s_base = (int)(old & 0xffffffffull);
-            if (plan.row_rank) plan.row_rank[row] = (int)(old >> 32);
-        }
         int *s_first = reinterpret_cast<int *>(smem);       // the staged logits are no longer needed
         if (C <= SEL_THREADS) {
             emit_row_items<true, UNION>(plan, (int)row, &s_base, base_r, n_sel, U, n_uc, s_first, tid, SEL_THREADS,
