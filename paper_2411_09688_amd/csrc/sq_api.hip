@@ -171,7 +171,8 @@ bool step_is_shared(const sq_shape_t *sh) { return sh->B >= 2; }
 // Workspace of the two-level lookup.  C1 <= C2 is not known to sq_workspace_bytes, so level-1 buffers
 // are sized for C2.
 struct HierWs {
-    float *logits1, *logits2;
+    float *logits1, *logits2;   // logits2 and cand_id are in candidate order: [rows, C2] with the row's candidates first
+    int32_t *cand_id;
     int32_t *nr1, *nk1;
     sq::DecodePlan cand;      // work items of candidate fine clusters (chunks of KPC clusters)
 };
@@ -183,6 +184,7 @@ HierWs carve_hier(Carver &cv, const sq_shape_t *sh)
     HierWs w{};
     w.logits1 = cv.take<float>(rows * sh->C);
     w.logits2 = cv.take<float>(rows * sh->C);
+    w.cand_id = cv.take<int32_t>(rows * sh->C);
     w.nr1 = cv.take<int32_t>(rows);
     w.nk1 = cv.take<int32_t>(rows);
     w.cand.rec_cap = sh->C;
@@ -628,13 +630,13 @@ int hier_lookup(const char *fn, const sq_shape_t *sh, int32_t C1, const void *q,
                               w.nr1, w.nk1, cand, true, 0, o1, rows, sh->H, 1, C1, s);
         // Level 2 (Eq. 3): scores of the candidates only; maximum and normaliser over the candidates only.
         if (e == hipSuccess)
-            e = sq::launch_gather_score(q, centroids2, cand, w.logits2, plan2.total, sh->H, sh->C, sh->sm_scale, s);
+            e = sq::launch_gather_score(q, centroids2, cand, w.logits2, w.cand_id, plan2.total, sh->H, sh->C,
+                                        sh->sm_scale, s);
     }
     if (e == hipSuccess) {
         sq::SelectOpts o2{};
-        o2.parent_offsets = child_offsets;
-        o2.parent_mask = keep_mask1;
-        o2.C1 = C1;
+        o2.cand_id = w.cand_id;
+        o2.cand_hdr = w.cand.hdr;
         e = sq::launch_select(w.logits2, nullptr, nullptr, false, thresh2, sizes2, offsets2, keep_mask2, ranges,
                               n_ranges, n_keys, plan2, schedule2, sh->U, o2, rows, sh->H, 1, sh->C, s);
     }

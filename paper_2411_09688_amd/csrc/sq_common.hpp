@@ -65,22 +65,32 @@ __device__ __forceinline__ float wave_max(float v)
     return v;
 }
 
-__device__ __forceinline__ int wave_sum_i(int v)
+// Integer data-parallel-primitive move for scans: lanes whose source lies outside their row of 16, and rows not
+// named in ROW_MASK, receive 0.
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ int dpp_i0(int v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xf, false);
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave, entirely in the vector ALU: four shifted adds inside each
+// row of 16 lanes (row_shr 1, 2, 4, 8), then lane 15 of a row is added to the following row (rows 1 and 3), then
+// lane 31 to rows 2 and 3.  Must be called with all 64 lanes active.
+__device__ __forceinline__ int wave_inclusive_scan(int v, int /*lane*/)
+{
+    v += dpp_i0<0x111>(v);
+    v += dpp_i0<0x112>(v);
+    v += dpp_i0<0x114>(v);
+    v += dpp_i0<0x118>(v);
+    v += dpp_i0<0x142, 0xa>(v);   // row_bcast:15
+    v += dpp_i0<0x143, 0xc>(v);   // row_bcast:31
     return v;
 }
 
-// Inclusive prefix sum over the 64 lanes of a wave.
-__device__ __forceinline__ int wave_inclusive_scan(int v, int lane)
+// Sum over the wave (all 64 lanes active); every lane gets the result.
+__device__ __forceinline__ int wave_sum_i(int v)
 {
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        int t = __shfl_up(v, o);
-        if (lane >= o) v += t;
-    }
-    return v;
+    return __builtin_amdgcn_readlane(wave_inclusive_scan(v, 0), 63);
 }
 
 // fp32 dot product of two 8-element fp16 vectors (exact products, fp32 accumulation).

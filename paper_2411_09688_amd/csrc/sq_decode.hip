@@ -21,12 +21,24 @@ namespace sq {
 constexpr int KW = KPC / 4;     // keys per wave
 constexpr int NI = KW / 4;      // loads per lane (4 rows per wave-wide load)
 
+// Items per batch: the work list is cut into batches of this many consecutive items, ATTN_OVERSUB batches per
+// workgroup.  The partial kernel and the merge kernel derive it from the same two numbers.  Measured: more
+// than one batch per workgroup buys no better balance (a step of config 2 stays within 1 %) and costs more
+// partial results to write and merge (config 5: merge 6.7 -> 14.2 us), so it is 1.
+constexpr int ATTN_OVERSUB = 1;
+__device__ __forceinline__ int items_per_batch(int total, int grid)
+{
+    return max(1, (total + grid * ATTN_OVERSUB - 1) / (grid * ATTN_OVERSUB));
+}
+
 // Phase 1: one work item = one chunk of up to KPC keys of one (sequence, head) row.  The grid is a fixed
-// number of workgroups; workgroup w takes the k consecutive items [w*k, (w+1)*k), k = ceil(items / grid),
-// so every workgroup streams the same number of keys whatever the selection looks like and no workgroup
-// is launched for chunks that do not exist.  Consecutive items of the same row are folded into one
-// running (max, sum, output) per lane, so a partial result is written once per (workgroup, row) segment,
-// at the index of the segment's first item.
+// number G of workgroups; the work list is cut into batches of kb consecutive items and workgroup w takes
+// batches w, w + G, w + 2G, ... (one batch with ATTN_OVERSUB = 1).  Every workgroup streams the same number of
+// keys whatever the selection looks like, and no workgroup is launched for chunks that do not exist.  (Handing
+// the batches out through a device-wide counter was measured too: a thousand increments of one address
+// serialise, and the step got 4 us slower.)
+// Consecutive items of one row inside a batch are folded into one running (max, sum, output) per lane, so a
+// partial result is written once per (batch, row) segment, at the index of the segment's first item.
 __global__ __launch_bounds__(256) void decode_attn_kernel(
     const _Float16 *__restrict__ q, const _Float16 *__restrict__ Kf, const _Float16 *__restrict__ Vf,
     const _Float16 *__restrict__ Ku, const _Float16 *__restrict__ Vu, DecodePlan plan,
@@ -39,21 +51,28 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 4, p = lane & 15;
 
-    const int total = min(*plan.total, plan.item_cap);
-    const int k = (total + (int)gridDim.x - 1) / (int)gridDim.x;
-    int item = blockIdx.x * k;
-    const int item_end = min(item + k, total);
-    if (item >= item_end) return;                          // whole workgroup
-
-    const int2 *it = plan.item + (size_t)item * ITEM_STRIDE;
+    // The work list is read with as few dependent round trips as possible: the item this workgroup starts with
+    // when a batch is one item is fetched together with the item count; only a longer list costs a second
+    // fetch.  (The grid never exceeds item_cap, so the speculative read stays inside the item array; slots
+    // past the count hold stale data that is not used.)
+    const int2 *it = plan.item + (size_t)blockIdx.x * ITEM_STRIDE;
     int2 h0_next = it[0], h1_next = it[1], rec_next = it[2 + (tid < KPC ? tid : 0)];   // threads >= KPC idle here
+    const int total = min(*plan.total, plan.item_cap);
+    const int kb = items_per_batch(total, (int)gridDim.x);
+    const int n_batches = (total + kb - 1) / kb;
+    int batch = blockIdx.x;
+    if (batch >= n_batches) return;                        // whole workgroup
+    if (kb != 1) {
+        it = plan.item + (size_t)batch * kb * ITEM_STRIDE;
+        h0_next = it[0];
+        h1_next = it[1];
+        rec_next = it[2 + (tid < KPC ? tid : 0)];
+    }
 
-    // Running state of the current (workgroup, row) segment.  m is wave-uniform; l and o are this lane's
+    // Running state of the current (batch, row) segment.  m is wave-uniform; l and o are this lane's
     // share (its 16-lane group's keys), summed over the four groups only when the segment is flushed.
-    float m_run = SQ_NEG_INF, l_run = 0.0f;
-    float o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    int seg_first = item;
-    int cur_row = h0_next.x;
+    float m_run, l_run;
+    float o[8];
 
     auto flush = [&](int slot) {
         const float l_w = cross16_sum(l_run);
@@ -90,82 +109,96 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
         __syncthreads();
     };
 
-    for (; item < item_end; ++item) {
-        const int2 h0 = h0_next, h1 = h1_next, rc = rec_next;   // (row, keys) (records | -1, first user key)
-        if (h0.x != cur_row) {                             // workgroup-uniform: the segment of the previous row ends
-            flush(seg_first);
-            m_run = SQ_NEG_INF;
-            l_run = 0.0f;
+    for (;;) {                                             // one batch per trip
+        int item = batch * kb;
+        const int item_end = min(item + kb, total);
+        m_run = SQ_NEG_INF;
+        l_run = 0.0f;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = 0.0f;
-            seg_first = item;
-            cur_row = h0.x;
-        }
-        const size_t bh = (size_t)h0.x;
-        const int nvalid = h0.y;
-        const bool user = h1.x < 0;
-        const int nrec = min(h1.x, KPC);
-        const int h = (int)(bh % H);
-        const _Float16 *Kbase, *Vbase;
-        const h8 qv = *reinterpret_cast<const h8 *>(q + bh * D + p * 8);
-        if (user) {
-            Kbase = Ku + (bh * U + h1.y) * D;
-            Vbase = Vu + (bh * U + h1.y) * D;
-            if (tid < KPC) s_rows[tid] = tid < nvalid ? tid : -1;
-        } else {
-            Kbase = Kf + (size_t)h * L * D;
-            Vbase = Vf + (size_t)h * L * D;
-            chunk_rows_from_records<KPC>(rc.x, rc.y, nrec, nvalid, L, s_pos, s_delta, s_rows, tid);
-        }
-        __syncthreads();
+        for (int e = 0; e < 8; ++e) o[e] = 0.0f;
+        int seg_first = item;
+        int cur_row = h0_next.x;
+        for (; item < item_end; ++item) {
+            const int2 h0 = h0_next, h1 = h1_next, rc = rec_next;   // (row, keys) (records | -1, first user key)
+            if (h0.x != cur_row) {                         // workgroup-uniform: the segment of the previous row ends
+                flush(seg_first);
+                m_run = SQ_NEG_INF;
+                l_run = 0.0f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = 0.0f;
+                seg_first = item;
+                cur_row = h0.x;
+            }
+            const size_t bh = (size_t)h0.x;
+            const int nvalid = h0.y;
+            const bool user = h1.x < 0;
+            const int nrec = min(h1.x, KPC);
+            const int h = (int)(bh % H);
+            const _Float16 *Kbase, *Vbase;
+            const h8 qv = *reinterpret_cast<const h8 *>(q + bh * D + p * 8);
+            if (user) {
+                Kbase = Ku + (bh * U + h1.y) * D;
+                Vbase = Vu + (bh * U + h1.y) * D;
+                if (tid < KPC) s_rows[tid] = tid < nvalid ? tid : -1;
+            } else {
+                Kbase = Kf + (size_t)h * L * D;
+                Vbase = Vf + (size_t)h * L * D;
+                chunk_rows_from_records<KPC>(rc.x, rc.y, nrec, nvalid, L, s_pos, s_delta, s_rows, tid);
+            }
+            __syncthreads();
 
-        // Issue every K and V load of this lane.
-        h8 kreg[NI], vreg[NI];
-        const int r_last = s_rows[nvalid - 1];
+            // Issue every K and V load of this lane.
+            h8 kreg[NI], vreg[NI];
+            const int r_last = s_rows[nvalid - 1];
 #pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const int kl = wave * KW + i * 4 + g;
-            int r = s_rows[kl];
-            r = r < 0 ? r_last : r;                       // slots past the chunk re-read a valid row
-            const size_t off = (size_t)r * D + p * 8;
-            kreg[i] = *reinterpret_cast<const h8 *>(Kbase + off);
-            vreg[i] = *reinterpret_cast<const h8 *>(Vbase + off);
-        }
-        // Metadata of the next item, fetched behind the K/V stream.
-        if (item + 1 < item_end) {
-            const int2 *nx = plan.item + (size_t)(item + 1) * ITEM_STRIDE;
-            h0_next = nx[0];
-            h1_next = nx[1];
-            rec_next = nx[2 + (tid < KPC ? tid : 0)];
-        }
+            for (int i = 0; i < NI; ++i) {
+                const int kl = wave * KW + i * 4 + g;
+                int r = s_rows[kl];
+                r = r < 0 ? r_last : r;                       // slots past the chunk re-read a valid row
+                const size_t off = (size_t)r * D + p * 8;
+                kreg[i] = *reinterpret_cast<const h8 *>(Kbase + off);
+                vreg[i] = *reinterpret_cast<const h8 *>(Vbase + off);
+            }
+            // Metadata of the next item (the batch's next one, or the first of this workgroup's next batch),
+            // fetched behind the K/V stream.
+            const int item_nx = item + 1 < item_end ? item + 1 : (batch + (int)gridDim.x) * kb;
+            if (item_nx < total) {
+                const int2 *nx = plan.item + (size_t)item_nx * ITEM_STRIDE;
+                h0_next = nx[0];
+                h1_next = nx[1];
+                rec_next = nx[2 + (tid < KPC ? tid : 0)];
+            }
 
-        // Scores of this lane-group's keys, folded into the running softmax.
-        float s[NI];
-        float m_it = SQ_NEG_INF;
+            // Scores of this lane-group's keys, folded into the running softmax.
+            float s[NI];
+            float m_it = SQ_NEG_INF;
 #pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const int kl = wave * KW + i * 4 + g;
-            const float d = row16_sum(dot8(qv, kreg[i], 0.0f)) * sm_scale;
-            s[i] = kl < nvalid ? d : SQ_NEG_INF;
-            m_it = fmaxf(m_it, s[i]);
+            for (int i = 0; i < NI; ++i) {
+                const int kl = wave * KW + i * 4 + g;
+                const float d = row16_sum(dot8(qv, kreg[i], 0.0f)) * sm_scale;
+                s[i] = kl < nvalid ? d : SQ_NEG_INF;
+                m_it = fmaxf(m_it, s[i]);
+            }
+            m_it = cross16_max(m_it);
+            const float m_new = fmaxf(m_run, m_it);
+            const float alpha = m_new == SQ_NEG_INF ? 1.0f : __expf(m_run - m_new);   // exp(-inf) = 0 on the first item
+            l_run *= alpha;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] *= alpha;
+#pragma unroll
+            for (int i = 0; i < NI; ++i) {
+                const float pr = s[i] == SQ_NEG_INF ? 0.0f : __expf(s[i] - m_new);
+                l_run += pr;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] += pr * (float)vreg[i][e];
+            }
+            m_run = m_new;
+            __syncthreads();      // s_rows is rewritten by the next item
         }
-        m_it = cross16_max(m_it);
-        const float m_new = fmaxf(m_run, m_it);
-        const float alpha = m_new == SQ_NEG_INF ? 1.0f : __expf(m_run - m_new);   // exp(-inf) = 0 on the first item
-        l_run *= alpha;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] *= alpha;
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const float pr = s[i] == SQ_NEG_INF ? 0.0f : __expf(s[i] - m_new);
-            l_run += pr;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] += pr * (float)vreg[i][e];
-        }
-        m_run = m_new;
-        __syncthreads();      // s_rows is rewritten by the next item
+        flush(seg_first);
+        batch += (int)gridDim.x;
+        if (batch >= n_batches) break;
     }
-    flush(seg_first);
 }
 
 // Phase 2 (Section 4.2): one workgroup per (sequence, head) merges the row's partials.  A separate
@@ -179,7 +212,7 @@ __global__ __launch_bounds__(MERGE_THREADS) void decode_merge_kernel(const float
     const size_t bh = blockIdx.x;
     const int2 it = plan.row_items[bh];              // (first item, items) of this row
     const int total = min(*plan.total, plan.item_cap);
-    const int k = max(1, (total + attn_grid - 1) / attn_grid);     // items per attention workgroup
+    const int k = items_per_batch(total, attn_grid);               // items per batch of the partial kernel
     const int n = it.y == 0 ? 0 : 1 + (it.x + it.y - 1) / k - it.x / k;
     // The row's partials sit at item indices `first` and every multiple of k inside (first, first + items).
     const int first = it.x, fk = first / k;

@@ -44,7 +44,7 @@ inline int user_chunks_for(int U) { return (U + KPC - 1) / KPC; }
 
 // Row-wise selection stages a row's logits and cluster sizes in LDS.
 constexpr int SELECT_MAX_C = 16384;
-constexpr int LDS_BYTES_MAX = 160 * 1024 - 4096;   // gfx950: 160 KB per workgroup, minus the static arrays
+constexpr int LDS_BYTES_MAX = 160 * 1024 - 8192;   // gfx950: 160 KB per workgroup, minus the static arrays
 // Scheduling keeps two ints per chunk of a row in LDS (same budget as the staged logits).
 constexpr int MAX_L = SELECT_MAX_C * KPC;
 
@@ -69,9 +69,8 @@ hipError_t launch_prefill_lookup(const void *q, const void *centroids, const int
                                  int B, int H, int Lq, int C, float sm_scale, hipStream_t s);
 // Options of the row-wise selection for the two-level lookup (all zero for the one-level path).
 struct SelectOpts {
-    const int32_t *parent_offsets;   // level 2: child_offsets [H, C1+1]; cluster i is a candidate iff its parent is kept
-    const uint32_t *parent_mask;     // level 2: keep mask of the coarse level [B*H, ceil(C1/32)]
-    int C1;
+    const int32_t *cand_id;          // level 2: `logits` is [rows, C] in candidate order, cand_id [rows, C] the
+    const int2 *cand_hdr;            //   candidates' cluster ids (ascending), cand_hdr[row].y their number
     int len_from_offsets;            // level 1: emitted range length = offsets[i+1] - offsets[i] (child clusters)
     int mean_parts;                  // averaged-score selection: `logits` holds this many partial score sums per
     float mean_div;                  //   row, [rows, mean_parts, C]; their sum / mean_div is compared with T
@@ -96,9 +95,9 @@ hipError_t launch_select(const float *logits, const float *row_max, const float 
                          int32_t *ranges, int32_t *n_ranges, int32_t *n_keys, DecodePlan plan, bool schedule, int U,
                          SelectOpts opt, int rows, int H, int Lq, int C, hipStream_t s);
 // Level-2 scoring of the two-level lookup: logits of the candidate fine centroids listed by the work
-// items of `cand` (chunks of candidate clusters), written at logits2[row, fine id].
+// items of `cand` (chunks of candidate clusters), written in candidate order: logits2[row, j], cand_id[row, j].
 hipError_t launch_gather_score(const void *q, const void *centroids2, DecodePlan cand, float *logits2,
-                               int *zero_counter, int H, int C2, float sm_scale, hipStream_t s);
+                               int32_t *cand_id, int *zero_counter, int H, int C2, float sm_scale, hipStream_t s);
 // Caller-style ranges [rows, range_cap, 2] -> records + header per row.
 hipError_t launch_ranges_to_rec(const int32_t *ranges, const int32_t *n_ranges, DecodePlan plan, int rows,
                                 int range_cap, hipStream_t s);

@@ -127,6 +127,7 @@ __global__ __launch_bounds__(256) void mean_score_kernel(const float *__restrict
 __global__ __launch_bounds__(256) void gather_score_kernel(const _Float16 *__restrict__ q,
                                                            const _Float16 *__restrict__ cent2, DecodePlan cand,
                                                            float *__restrict__ logits2,
+                                                           int32_t *__restrict__ cand_id,
                                                            int *__restrict__ zero_counter, int H, int C2,
                                                            float sm_scale)
 {
@@ -142,6 +143,7 @@ __global__ __launch_bounds__(256) void gather_score_kernel(const _Float16 *__res
         const int2 rc = it[2 + (tid < KPC ? tid : 0)];
         const size_t bh = (size_t)h0.x;
         const int h = (int)(bh % H);
+        const int j0 = (item - cand.row_items[bh].x) * KPC;   // this chunk's first candidate within its row
         chunk_rows_from_records<KPC>(rc.x, rc.y, min(h1.x, KPC), h0.y, C2, s_pos, s_delta, s_rows, tid);
         __syncthreads();
         h8 bq[4];
@@ -168,8 +170,12 @@ __global__ __launch_bounds__(256) void gather_score_kernel(const _Float16 *__res
             if (col == 0) {
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    const int r = s_rows[wave * (KPC / 4) + t * 16 + kg * 4 + v];
-                    if (r >= 0) logits2[bh * (size_t)C2 + r] = acc[v] * sm_scale;
+                    const int slot = wave * (KPC / 4) + t * 16 + kg * 4 + v;
+                    const int r = s_rows[slot];
+                    if (r >= 0 && j0 + slot < C2) {
+                        logits2[bh * (size_t)C2 + j0 + slot] = acc[v] * sm_scale;
+                        cand_id[bh * (size_t)C2 + j0 + slot] = r;
+                    }
                 }
             }
         }
@@ -178,11 +184,11 @@ __global__ __launch_bounds__(256) void gather_score_kernel(const _Float16 *__res
 }
 
 hipError_t launch_gather_score(const void *q, const void *centroids2, DecodePlan cand, float *logits2,
-                               int *zero_counter, int H, int C2, float sm_scale, hipStream_t s)
+                               int32_t *cand_id, int *zero_counter, int H, int C2, float sm_scale, hipStream_t s)
 {
     const int grid = cand.item_cap < 2048 ? cand.item_cap : 2048;
     hipLaunchKernelGGL(gather_score_kernel, dim3(grid), dim3(256), 0, s, (const _Float16 *)q,
-                       (const _Float16 *)centroids2, cand, logits2, zero_counter, H, C2, sm_scale);
+                       (const _Float16 *)centroids2, cand, logits2, cand_id, zero_counter, H, C2, sm_scale);
     return hipGetLastError();
 }
 

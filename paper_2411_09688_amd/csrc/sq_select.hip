@@ -7,8 +7,8 @@
 // replaced there by e_i = exp(x_i - m), so the comparison with T * D re-reads stored exponentials
 // instead of recomputing anything (the stored-exponential scheme of Appendix D).  Inside a wave the
 // rank of a kept cluster comes from a 64-bit ballot + population count and the number of keys in
-// front of it from a shuffle prefix scan; the waves are stitched through LDS.  The ballot words
-// are the keep mask.
+// front of it from a prefix scan in the vector ALU (data-parallel-primitive row shifts); the waves
+// are stitched through LDS.  The ballot words are the keep mask.
 //
 // ranges_to_rec_kernel turns a caller's range list into the same records the selection emits, and
 // schedule_kernel turns the records of all rows into the work items of the split-KV attention
@@ -74,14 +74,25 @@ __device__ __forceinline__ void emit_row_items(const DecodePlan &plan, int row, 
     int *s_firstz = s_first + n_fixed;                      // selected keys before the chunk's first record
     const int4 *rec_row = plan.rec + (size_t)row * plan.rec_cap;
     // Pass 1: the record that holds a chunk's first key is the chunk's first record.
-    for (int r = REG ? my_r : tid; REG ? have_rec : r < n_rec; r += nthreads) {
-        const int4 rc = REG ? my_rec : rec_row[r];
+    auto first_of = [&](int r, const int4 rc) {
         const int c_lo = (rc.z + KPC - 1) / KPC, c_hi = min((rc.z + rc.y - 1) / KPC, n_fixed - 1);
         for (int c = c_lo; c <= c_hi; ++c) {
             s_first[c] = r;
             s_firstz[c] = rc.z;
         }
-        if (REG) break;
+    };
+    constexpr int RB = 8;                                   // records fetched together (all loads in flight)
+    if (REG) {
+        if (have_rec) first_of(my_r, my_rec);
+    } else {
+        for (int r0 = tid; r0 < n_rec; r0 += nthreads * RB) {
+            int4 rc[RB];
+#pragma unroll
+            for (int u = 0; u < RB; ++u) rc[u] = r0 + u * nthreads < n_rec ? rec_row[r0 + u * nthreads] : make_int4(0, 0, 0, 0);
+#pragma unroll
+            for (int u = 0; u < RB; ++u)
+                if (r0 + u * nthreads < n_rec) first_of(r0 + u * nthreads, rc[u]);
+        }
     }
     __syncthreads();
     const int base = *s_base_ptr;
@@ -93,15 +104,25 @@ __device__ __forceinline__ void emit_row_items(const DecodePlan &plan, int row, 
         it[1] = make_int2(-1 - seq, cu * KPC);
     }
     // Pass 2: every record writes its (position, delta) into the chunks it touches.
-    for (int r = REG ? my_r : tid; REG ? have_rec : r < n_rec; r += nthreads) {
-        const int4 rc = REG ? my_rec : rec_row[r];
+    auto place = [&](int r, const int4 rc) {
         const int c_lo = rc.z / KPC, c_hi = min((rc.z + rc.y - 1) / KPC, n_fixed - 1);
         for (int c = c_lo; c <= c_hi; ++c) {
             int2 *it = plan.item + (size_t)(base + n_user_chunks + c) * ITEM_STRIDE;
             const int pos = rc.z - c * KPC;                 // negative for a record that began in an earlier chunk
             it[2 + r - s_first[c]] = make_int2(SHARED ? (int)((uint32_t)max(pos, 0) | ((uint32_t)rc.w << 16)) : pos, rc.x - pos);
         }
-        if (REG) break;
+    };
+    if (REG) {
+        if (have_rec) place(my_r, my_rec);
+    } else {
+        for (int r0 = tid; r0 < n_rec; r0 += nthreads * RB) {
+            int4 rc[RB];
+#pragma unroll
+            for (int u = 0; u < RB; ++u) rc[u] = r0 + u * nthreads < n_rec ? rec_row[r0 + u * nthreads] : make_int4(0, 0, 0, 0);
+#pragma unroll
+            for (int u = 0; u < RB; ++u)
+                if (r0 + u * nthreads < n_rec) place(r0 + u * nthreads, rc[u]);
+        }
     }
     // Chunk headers.  The last record touching chunk c is the first record of chunk c+1 if that record
     // began before the boundary, else the one before it.
@@ -209,7 +230,10 @@ __device__ __forceinline__ void wave_select_mask(const float *__restrict__ x, co
 // sequence of the group is selected by one wave of the workgroup (logits [B*H, C]; keep_mask, n_ranges, n_keys
 // are the per-sequence outputs), then cluster i is kept for the union row iff any sequence of the group kept
 // it, and the set of those sequences travels with the record.  Always with SCHEDULE.
-template <bool STATS_IN, bool SCHEDULE, bool UNION = false>
+// CAND: level 2 of the two-level lookup (Section 3.3, Eq. 3).  The row's entries are its candidates j = 0..n-1 (the
+// children of the kept coarse clusters, ascending), logits[row, j] is the logit of fine cluster opt.cand_id[row, j],
+// and the maximum, the normaliser and the compaction run over those n entries only; mask bits are set by cluster id.
+template <bool STATS_IN, bool SCHEDULE, bool UNION = false, bool CAND = false>
 __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     const float *__restrict__ logits, const float *__restrict__ row_max, const float *__restrict__ denom,
     const float *__restrict__ thresh, const int32_t *__restrict__ sizes, const int32_t *__restrict__ offsets,
@@ -231,6 +255,11 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     const int W = (C + 31) >> 5;
     const float T = UNION ? 0.0f : thresh[h];
     (void)T;
+    // Entries of the row: all C clusters, or (CAND) the row's candidates; entry i is cluster id_of(i).
+    const int32_t *cid = CAND ? opt.cand_id + row * C : nullptr;
+    const int n = CAND ? min(opt.cand_hdr[row].y, C) : C;
+    auto id_of = [&](int i) { return CAND ? cid[i] : i; };
+    __shared__ uint32_t s_mask[CAND ? SELECT_MAX_C / 32 : 1];
     uint32_t *s_set = reinterpret_cast<uint32_t *>(s_e);   // UNION: set of sequences per cluster instead of e_i
     const int n_seq = UNION ? min(SG, opt.B - (int)(row / H) * SG) : 1;
 
@@ -255,24 +284,25 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
             s_set[i] = set;
             s_N[i] = N[i];
         }
-    } else if (opt.parent_mask) {
-        // Two-level lookup, level 2 (Section 3.3): only the children of kept coarse clusters are
-        // candidates; every other cluster is treated as empty, so the maximum and the normaliser of
-        // Eq. 3 run over the candidates only.  Parent of cluster i: the j with co[j] <= i < co[j+1].
-        int32_t *s_co = s_N + C;                            // [C1 + 1]
-        const int32_t *co = opt.parent_offsets + (size_t)h * (opt.C1 + 1);
-        for (int j = tid; j <= opt.C1; j += SEL_THREADS) s_co[j] = co[j];
-        __syncthreads();
-        const uint32_t *pm = opt.parent_mask + (row / Lq) * ((opt.C1 + 31) >> 5);
-        for (int i = tid; i < C; i += SEL_THREADS) {
-            int lo = 0, hi = opt.C1;                        // invariant: co[lo] <= i (if any) ; answer in [lo, hi)
-            while (hi - lo > 1) {
-                const int mid = (lo + hi) >> 1;
-                if (s_co[mid] <= i) lo = mid; else hi = mid;
+    } else if (CAND) {
+        for (int w = tid; w < W; w += SEL_THREADS) s_mask[w] = 0u;
+        int idv[16], nv[16];                                // all loads of the (up to 16) steps in flight together
+        float xv[16];
+#pragma unroll
+        for (int st = 0; st < 16; ++st) {
+            const int i = st * SEL_THREADS + tid;
+            idv[st] = i < n ? cid[i] : 0;
+            xv[st] = i < n ? x[i] : 0.0f;
+        }
+#pragma unroll
+        for (int st = 0; st < 16; ++st) nv[st] = st * SEL_THREADS + tid < n ? N[idv[st]] : 0;
+#pragma unroll
+        for (int st = 0; st < 16; ++st) {
+            const int i = st * SEL_THREADS + tid;
+            if (i < n) {
+                s_e[i] = xv[st];
+                s_N[i] = nv[st];
             }
-            const bool cand = i >= s_co[lo] && i < s_co[lo + 1] && ((pm[lo >> 5] >> (lo & 31)) & 1u);
-            s_N[i] = cand ? N[i] : 0;
-            s_e[i] = cand ? x[i] : 0.0f;
         }
     } else if (opt.mean_parts) {
         // Averaged-score selection (Appendix D, prefill): the staged value is the mean score itself.
@@ -292,6 +322,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
             s_N[i] = N[i];
         }
     } else {
+#pragma unroll 4
         for (int i = tid; i < C; i += SEL_THREADS) {
             s_e[i] = x[i];
             s_N[i] = N[i];
@@ -303,16 +334,16 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     } else if (STATS_IN && opt.mean_parts) {
         if (tid == 0) s_thr = T;                            // keep iff mean score > T
         __syncthreads();
-        for (int i = tid; i < C; i += SEL_THREADS) s_e[i] = s_N[i] > 0 ? s_e[i] : 0.0f;
+        for (int i = tid; i < n; i += SEL_THREADS) s_e[i] = s_N[i] > 0 ? s_e[i] : 0.0f;
     } else if (STATS_IN) {
         m = row_max[row];
         if (tid == 0) s_thr = T * denom[row];
         __syncthreads();
-        for (int i = tid; i < C; i += SEL_THREADS) s_e[i] = s_N[i] > 0 ? expf(s_e[i] - m) : 0.0f;
+        for (int i = tid; i < n; i += SEL_THREADS) s_e[i] = s_N[i] > 0 ? expf(s_e[i] - m) : 0.0f;
     } else {
         __syncthreads();
         m = SQ_NEG_INF;
-        for (int i = tid; i < C; i += SEL_THREADS)
+        for (int i = tid; i < n; i += SEL_THREADS)
             if (s_N[i] > 0) m = fmaxf(m, s_e[i]);
         m = wave_max(m);
         if (lane == 0) s_wred[wave] = m;
@@ -320,12 +351,12 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
         m = s_wred[0];
 #pragma unroll
         for (int w = 1; w < SEL_WAVES; ++w) m = fmaxf(m, s_wred[w]);
-        for (int i = tid; i < C; i += SEL_THREADS) s_e[i] = s_N[i] > 0 ? expf(s_e[i] - m) : 0.0f;
+        for (int i = tid; i < n; i += SEL_THREADS) s_e[i] = s_N[i] > 0 ? expf(s_e[i] - m) : 0.0f;
         __syncthreads();                                     // every wave has read the maxima: s_wred is reused below
         // D in the library's one summation order (see wave_row_stats): thread v adds clusters v, v+1024, ...
         // ascending, butterfly inside each wave, then the 16 wave sums in ascending order.
         float local = 0.0f;
-        for (int i = tid; i < C; i += SEL_THREADS) {
+        for (int i = tid; i < n; i += SEL_THREADS) {
             const int Ni = s_N[i];
             if (Ni > 0) local += (float)Ni * s_e[i];
         }
@@ -348,29 +379,72 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     // wave of every step its first record index and key prefix.  Pass 2 repeats the cheap ballot and
     // lane scan and emits.
     __shared__ int s_tcnt[16 * SEL_WAVES + 1], s_tkeys[16 * SEL_WAVES + 1];
-    const int n_steps = (C + SEL_THREADS - 1) / SEL_THREADS;
-    const int start_first = (tid < C) ? off[tid] : 0;       // offsets of the first step, fetched early
-    const int next_first = (opt.len_from_offsets && tid < C) ? off[tid + 1] : 0;
+    const int n_steps = (n + SEL_THREADS - 1) / SEL_THREADS;
+    const int id_first = tid < n ? id_of(tid) : 0;
+    const int start_first = (tid < n) ? off[id_first] : 0;  // offsets of the first step, fetched early
+    const int next_first = (opt.len_from_offsets && tid < n) ? off[id_first + 1] : 0;
+    // Rows of more than one step: every global load of the compaction is issued here, for all (up to 16) steps at
+    // once, so that no step below waits on memory.  The staged value of entry i becomes the first key of its range
+    // (-1 if the cluster is dropped) and s_N[i] the range's length; a thread re-reads only entries it wrote itself.
+    const bool staged_ranges = !UNION && n_steps > 1;
+    if (staged_ranges) {
+        int idv[16], sv[16], lv[16];
+#pragma unroll
+        for (int st = 0; st < 16; ++st) {
+            const int i = st * SEL_THREADS + tid;
+            const bool k = i < n && s_N[i] > 0 && s_e[i] > thr;
+            idv[st] = k ? id_of(i) : -1;
+        }
+#pragma unroll
+        for (int st = 0; st < 16; ++st) {
+            sv[st] = idv[st] >= 0 ? off[idv[st]] : -1;
+            lv[st] = (opt.len_from_offsets && idv[st] >= 0) ? off[idv[st] + 1] : 0;
+        }
+#pragma unroll
+        for (int st = 0; st < 16; ++st) {
+            const int i = st * SEL_THREADS + tid;
+            if (i < n) {
+                s_e[i] = __int_as_float(sv[st]);
+                if (opt.len_from_offsets) s_N[i] = idv[st] >= 0 ? lv[st] - sv[st] : 0;
+                if (CAND && idv[st] >= 0) atomicOr(&s_mask[idv[st] >> 5], 1u << (idv[st] & 31));   // mask bit by cluster id
+            }
+        }
+    }
+    // Entry i of step st: kept?, first key and length of its range.
+    auto entry = [&](int st, int i, bool &keep, int &start, int &len) {
+        if (staged_ranges) {
+            start = i < n ? __float_as_int(s_e[i]) : -1;
+            keep = start >= 0;
+            len = keep ? s_N[i] : 0;
+        } else {
+            const int Ni = i < n ? s_N[i] : 0;
+            keep = Ni > 0 && (UNION ? s_set[i] != 0u : s_e[i] > thr);
+            start = st == 0 ? start_first : (keep ? off[i] : 0);    // later steps: union rows only
+            len = opt.len_from_offsets ? (keep ? next_first - start_first : 0) : Ni;
+        }
+    };
     for (int st = 0; st < n_steps; ++st) {
         const int i = st * SEL_THREADS + tid;
-        const int Ni = i < C ? s_N[i] : 0;
-        const bool keep = Ni > 0 && (UNION ? s_set[i] != 0u : s_e[i] > thr);
-        int len = Ni;
-        if (opt.len_from_offsets) len = keep ? (st == 0 ? next_first - start_first : off[i + 1] - off[i]) : 0;
+        bool keep;
+        int start, len;
+        entry(st, i, keep, start, len);
         const bool emit = keep && len > 0;              // a kept coarse cluster without children emits nothing
         const unsigned long long bal = __ballot(keep), bal_emit = __ballot(emit);
         const int wkeys = wave_sum_i(emit ? len : 0);
         if (lane == 0) {
             s_tcnt[st * SEL_WAVES + wave] = __popcll(bal_emit);
             s_tkeys[st * SEL_WAVES + wave] = wkeys;
-            if (keep_mask && !UNION) {                   // (a union row has no mask of its own)
+            if (keep_mask && !UNION && !CAND) {          // (a union row has no mask of its own)
                 const int w0 = (i >> 5);
                 if (w0 < W) keep_mask[row * W + w0] = (uint32_t)bal;
                 if (w0 + 1 < W) keep_mask[row * W + w0 + 1] = (uint32_t)(bal >> 32);
             }
         }
+        if (CAND && !staged_ranges && keep) atomicOr(&s_mask[id_first >> 5], 1u << (id_first & 31));
     }
     __syncthreads();
+    if (CAND && keep_mask)
+        for (int w = tid; w < W; w += SEL_THREADS) keep_mask[row * W + w] = s_mask[w];
     // Work items of the row are placed at a base taken from a device-wide counter (zeroed by the scoring kernel
     // that ran before): rows land in arrival order, which moves chunks between workgroups but changes no result.
     // The add is issued as soon as the row's totals are known, so its round trip runs under the second pass.
@@ -438,11 +512,9 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     int4 my_rec = make_int4(0, 0, 0, 0);
     for (int st = 0; st < n_steps; ++st) {
         const int i = st * SEL_THREADS + tid;
-        const int Ni = i < C ? s_N[i] : 0;
-        const bool keep = Ni > 0 && (UNION ? s_set[i] != 0u : s_e[i] > thr);
-        const int start = st == 0 ? start_first : (keep ? off[i] : 0);
-        int len = Ni;
-        if (opt.len_from_offsets) len = keep ? (st == 0 ? next_first : off[i + 1]) - start : 0;
+        bool keep;
+        int start, len;
+        entry(st, i, keep, start, len);
         const bool emit = keep && len > 0;
         const unsigned long long bal_emit = __ballot(emit);
         if (bal_emit == 0ull) continue;                  // wave-uniform
@@ -571,7 +643,7 @@ hipError_t launch_select(const float *logits, const float *row_max, const float 
                          int32_t *ranges, int32_t *n_ranges, int32_t *n_keys, DecodePlan plan, bool schedule, int U,
                          SelectOpts opt, int rows, int H, int Lq, int C, hipStream_t s)
 {
-    if (!ranges && !plan.rec && !schedule && !opt.parent_mask && !opt.len_from_offsets && !opt.mean_parts && keep_mask) {
+    if (!ranges && !plan.rec && !schedule && !opt.cand_id && !opt.len_from_offsets && !opt.mean_parts && keep_mask) {
         // mask and counts only (prefill): one wave per row
         if (stats_in)
             hipLaunchKernelGGL(select_mask_kernel<true>, dim3((rows + 3) / 4), dim3(256), 0, s, logits, row_max, denom,
@@ -581,18 +653,20 @@ hipError_t launch_select(const float *logits, const float *row_max, const float 
                                thresh, sizes, keep_mask, n_ranges, n_keys, rows, H, Lq, C);
         return hipGetLastError();
     }
-    // LDS: logits + sizes of the row (+ parent offsets); reused for two ints per chunk when scheduling.
-    size_t smem = (size_t)C * 8 + (opt.parent_mask ? (size_t)(opt.C1 + 1) * 4 : 0);
+    // LDS: logits + sizes of the row; reused for two ints per chunk when scheduling.
+    size_t smem = (size_t)C * 8;
     if (schedule && (size_t)chunk_cap_for(plan.L) * 8 > smem) smem = (size_t)chunk_cap_for(plan.L) * 8;
-    if (smem > (size_t)LDS_BYTES_MAX) return hipErrorInvalidValue;   // C and C1 too large together
+    if (smem > (size_t)LDS_BYTES_MAX) return hipErrorInvalidValue;
     static bool attr_set = false;   // one GPU per process in this build
     if (!attr_set) {
         const int lim = LDS_BYTES_MAX;
-        const void *fns[5] = {reinterpret_cast<const void *>(select_kernel<true, false>),
+        const void *fns[7] = {reinterpret_cast<const void *>(select_kernel<true, false>),
                               reinterpret_cast<const void *>(select_kernel<false, false>),
                               reinterpret_cast<const void *>(select_kernel<false, true>),
                               reinterpret_cast<const void *>(select_kernel<true, true>),
-                              reinterpret_cast<const void *>(select_kernel<false, true, true>)};
+                              reinterpret_cast<const void *>(select_kernel<false, true, true>),
+                              reinterpret_cast<const void *>(select_kernel<false, false, false, true>),
+                              reinterpret_cast<const void *>(select_kernel<false, true, false, true>)};
         for (const void *f : fns) {
             hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
             if (e != hipSuccess) return e;
@@ -605,6 +679,18 @@ hipError_t launch_select(const float *logits, const float *row_max, const float 
         hipLaunchKernelGGL((select_kernel<false, true, true>), dim3(rows), dim3(SEL_THREADS), smem, s, logits, row_max,
                            denom, thresh, sizes, offsets, keep_mask, ranges, n_ranges, n_keys, plan, opt, H, Lq, C, U,
                            nuc);
+        return hipGetLastError();
+    }
+    if (opt.cand_id) {
+        if (stats_in || !opt.cand_hdr) return hipErrorInvalidValue;
+        if (schedule)
+            hipLaunchKernelGGL((select_kernel<false, true, false, true>), dim3(rows), dim3(SEL_THREADS), smem, s, logits,
+                               row_max, denom, thresh, sizes, offsets, keep_mask, ranges, n_ranges, n_keys, plan, opt, H,
+                               Lq, C, U, nuc);
+        else
+            hipLaunchKernelGGL((select_kernel<false, false, false, true>), dim3(rows), dim3(SEL_THREADS), smem, s, logits,
+                               row_max, denom, thresh, sizes, offsets, keep_mask, ranges, n_ranges, n_keys, plan, opt, H,
+                               Lq, C, U, nuc);
         return hipGetLastError();
     }
 #define SQ_LAUNCH_SELECT(SI, SCH)                                                                               \
