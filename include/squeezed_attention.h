@@ -56,7 +56,8 @@ typedef enum sq_call {
     SQ_CALL_SELECT_MEAN = 7,
     SQ_CALL_ATTN_PREFILL_SHARED = 8,
     SQ_CALL_PREFILL_STEP = 9,
-    SQ_CALL_PREFILL_MEAN_STEP = 10
+    SQ_CALL_PREFILL_MEAN_STEP = 10,
+    SQ_CALL_GQA_DECODE_STEP = 11
 } sq_call;
 
 /*
@@ -216,6 +217,27 @@ int sq_decode_step(const sq_shape_t *shape, const void *q,
                    const void *K_fixed, const void *V_fixed, const void *K_user, const void *V_user,
                    void *out, float *lse, uint32_t *keep_mask, int32_t *n_keys,
                    void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * One whole decode step with GROUPED-QUERY attention (Lq must be 1): G query heads of a sequence share one K/V
+ * head -- its fixed-context keys, centroids, threshold and the sequence's user keys -- and every query head
+ * selects its clusters independently (the setting of the appendix "Additional Longbench Evaluation": keys and
+ * values shared amongst a subset of the heads, each head selecting on its own).  shape->H is the number of K/V
+ * heads; query head hq = h * G + g uses K/V head h.  The B * G (sequence, query head) pairs of a K/V head are
+ * handled like B * G sequences over a shared context: the union of the selections of every group of 16 of them is
+ * streamed once, so a key kept by several query heads leaves HBM once (same kernels, arithmetic and rounding as
+ * sq_decode_step with B >= 2; G = 1 is that call).  G must be 1, 2, 4, 8 or 16.
+ * In:  q f16 [B, H*G, 1, d]; centroids, sizes, offsets, thresh, K_fixed, V_fixed per K/V head as everywhere;
+ *      K_user, V_user f16 [B, H, U, d].
+ * Out: out f16 [B, H*G, 1, d]; optional (NULL to skip): lse f32 [B, H*G, 1], keep_mask u32 [B, H*G, 1, ceil(C/32)],
+ *      n_keys i32 [B, H*G, 1].
+ * Workspace: sq_workspace_bytes(shape, SQ_CALL_GQA_DECODE_STEP) (sized for G = 16).
+ */
+int sq_gqa_decode_step(const sq_shape_t *shape, int32_t G, const void *q,
+                       const void *centroids, const int32_t *sizes, const int32_t *offsets, const float *thresh,
+                       const void *K_fixed, const void *V_fixed, const void *K_user, const void *V_user,
+                       void *out, float *lse, uint32_t *keep_mask, int32_t *n_keys,
+                       void *ws, size_t ws_bytes, void *stream);
 
 /*
  * One whole prefill step with PER-QUERY selection: the lookup of sq_centroid_score + sq_select for every

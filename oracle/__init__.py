@@ -172,3 +172,36 @@ def scores(q, centroids, sizes, sm_scale) -> np.ndarray:
                              sm_scale)
     x, m, D = x[0, 0].astype(np.float64), m[0, 0].astype(np.float64), D[0, 0].astype(np.float64)
     return np.exp(x - m[:, None]) / D[:, None]
+
+
+def gqa_decode(q, centroids, sizes, offsets, thresh, K_fixed, V_fixed, K_user, V_user, sm_scale, G):
+    """Decode step with grouped-query attention (appendix "Additional Longbench Evaluation": keys and values are
+    shared amongst a subset of the heads, and every head selects its clusters independently).
+
+    q [B, Hq, d] f16 with Hq = H * G; query head hq uses K/V head hq // G -- its centroids, sizes, threshold,
+    fixed-context keys and the sequence's user keys [B, H, U, d].  Each (sequence, query head) is one independent
+    instance of the one-level method: scores (Eq. 1), threshold rule, exact attention over its kept keys plus all
+    user keys.  Written as that definition: one call of the one-level functions per query head, on the K/V head's
+    arrays.  -> dict(mask [B,Hq,W] u32, n_keys [B,Hq] i32, out [B,Hq,d] f64, lse [B,Hq] f64).
+    """
+    q = _f16(q)
+    B, Hq, d = q.shape
+    H = centroids.shape[0]
+    assert Hq == H * G
+    Cn = centroids.shape[1]
+    W = (Cn + 31) // 32
+    res = dict(mask=np.zeros((B, Hq, W), np.uint32), n_keys=np.zeros((B, Hq), np.int32),
+               out=np.zeros((B, Hq, d), np.float64), lse=np.zeros((B, Hq), np.float64))
+    for hq in range(Hq):
+        h = hq // G
+        qh = np.ascontiguousarray(q[:, hq][:, None, None, :])                       # [B, 1, 1, d]
+        x, m, D = centroid_score(qh, centroids[h:h + 1], sizes[h:h + 1], sm_scale)
+        mask, ranges, n_r, n_k = select(x, m, D, np.asarray(thresh)[h:h + 1], sizes[h:h + 1], offsets[h:h + 1])
+        out, lse = sparse_attn(qh, K_fixed[h:h + 1], V_fixed[h:h + 1], ranges, n_r,
+                               np.ascontiguousarray(K_user[:, h:h + 1]), np.ascontiguousarray(V_user[:, h:h + 1]),
+                               sm_scale)
+        res["mask"][:, hq] = mask[:, 0, 0]
+        res["n_keys"][:, hq] = n_k[:, 0, 0]
+        res["out"][:, hq] = out[:, 0, 0]
+        res["lse"][:, hq] = lse[:, 0, 0]
+    return res

@@ -142,10 +142,11 @@ struct SharedStepWs {
     float *partials;
 };
 
-SharedStepWs carve_step_shared(Carver &cv, const sq_shape_t *sh)
+// G: query rows per (sequence, head) that share the head's K/V (1, or the group size of grouped-query attention).
+SharedStepWs carve_step_shared(Carver &cv, const sq_shape_t *sh, int G = 1)
 {
-    const size_t rows = (size_t)sh->B * sh->H;
-    const size_t urows = (size_t)sq::seq_groups_for(sh->B) * sh->H;
+    const size_t rows = (size_t)sh->B * sh->H * G;
+    const size_t urows = (size_t)sq::seq_groups_for(sh->B * G) * sh->H;
     const size_t items = urows * ((size_t)sq::SG * sq::user_chunks_for(sh->U) + sq::chunk_cap_for(sh->L));
     SharedStepWs w{};
     w.logits = cv.take<float>(rows * sh->C);
@@ -318,6 +319,9 @@ size_t sq_workspace_bytes(const sq_shape_t *sh, int which)
     case SQ_CALL_PREFILL_STEP:
         carve_prefill_step(cv, sh);
         return cv.off;
+    case SQ_CALL_GQA_DECODE_STEP:                       // sized for the largest group (16 query heads per K/V head)
+        carve_step_shared(cv, sh, sq::SG);
+        return cv.off;
     case SQ_CALL_PREFILL_MEAN_STEP:
         carve_prefill_mean_step(cv, sh);
         return cv.off;
@@ -403,6 +407,61 @@ int sq_sparse_attn_decode(const sq_shape_t *sh, const void *q, const void *K_fix
     return SQ_OK;
 }
 
+namespace {
+// Decode step over K/V shared by several query rows: B sequences over one fixed context, times G query heads per
+// K/V head.  Every (sequence, query head) selects on its own; the work items are built from the union of the
+// selections of each group of 16 of them, so a cluster kept by several is streamed once.
+int decode_step_shared(const sq_shape_t *sh, int G, const void *q, const void *centroids, const int32_t *sizes,
+                       const int32_t *offsets, const float *thresh, const void *K_fixed, const void *V_fixed,
+                       const void *K_user, const void *V_user, void *out, float *lse, uint32_t *keep_mask,
+                       int32_t *n_keys, Carver &cv, hipStream_t s)
+{
+    SharedStepWs w = carve_step_shared(cv, sh, G);
+    uint32_t *mask = keep_mask ? keep_mask : w.mask;
+    // the G query heads of a (sequence, K/V head) are G query rows of that head: logits [B, H, G, C]
+    SQ_HIP(sq::launch_score(q, centroids, w.logits, w.plan.total, sh->B, sh->H, G, sh->C, sh->sm_scale, s));
+    SQ_HIP(sq::launch_union_schedule(w.logits, thresh, sizes, offsets, mask, w.n_ranges, n_keys ? n_keys : w.n_keys,
+                                     w.plan, sh->U, sh->B, G, sh->H, sh->C, s));
+    sq::Shape shp = to_shape(sh);
+    shp.Lq = G;
+    SQ_HIP(sq::launch_decode_attn_shared(q, K_fixed, V_fixed, K_user, V_user, w.plan, w.partials, out, lse, shp, s));
+    return SQ_OK;
+}
+}  // namespace
+
+int sq_gqa_decode_step(const sq_shape_t *sh, int32_t G, const void *q, const void *centroids, const int32_t *sizes,
+                       const int32_t *offsets, const float *thresh, const void *K_fixed, const void *V_fixed,
+                       const void *K_user, const void *V_user, void *out, float *lse, uint32_t *keep_mask,
+                       int32_t *n_keys, void *ws, size_t ws_bytes, void *stream)
+{
+    if (int rc = check_shape(sh, __func__, true)) return rc;
+    if (G != 1 && G != 2 && G != 4 && G != 8 && G != 16)
+        return fail(SQ_ERR_UNSUPPORTED, "%s: G = %d query heads per K/V head; supported: 1, 2, 4, 8, 16", __func__, G);
+    SQ_REQUIRE_PTR(q);
+    SQ_REQUIRE_PTR(centroids);
+    SQ_REQUIRE_PTR(sizes);
+    SQ_REQUIRE_PTR(offsets);
+    SQ_REQUIRE_PTR(thresh);
+    SQ_REQUIRE_PTR(K_fixed);
+    SQ_REQUIRE_PTR(V_fixed);
+    if (sh->U > 0) {
+        SQ_REQUIRE_PTR(K_user);
+        SQ_REQUIRE_PTR(V_user);
+    }
+    SQ_REQUIRE_PTR(out);
+    SQ_OPTIONAL_PTR(lse);
+    SQ_OPTIONAL_PTR(keep_mask);
+    SQ_OPTIONAL_PTR(n_keys);
+    if (int rc = check_ws(__func__, sh, SQ_CALL_GQA_DECODE_STEP, ws, ws_bytes)) return rc;
+    if (int rc = check_device(__func__)) return rc;
+    Carver cv(ws);
+    if (int rc = decode_step_shared(sh, G, q, centroids, sizes, offsets, thresh, K_fixed, V_fixed, K_user, V_user, out,
+                                    lse, keep_mask, n_keys, cv, static_cast<hipStream_t>(stream)))
+        return rc;
+    g_err[0] = 0;
+    return SQ_OK;
+}
+
 int sq_decode_step(const sq_shape_t *sh, const void *q, const void *centroids, const int32_t *sizes,
                    const int32_t *offsets, const float *thresh, const void *K_fixed, const void *V_fixed,
                    const void *K_user, const void *V_user, void *out, float *lse, uint32_t *keep_mask, int32_t *n_keys,
@@ -430,15 +489,9 @@ int sq_decode_step(const sq_shape_t *sh, const void *q, const void *centroids, c
     Carver cv(ws);
     const int rows = sh->B * sh->H;
     if (step_is_shared(sh)) {
-        // Every sequence selects on its own; the work items are built from the union of the selections of each
-        // group of sequences, so a cluster kept by several sequences is streamed once.
-        SharedStepWs w = carve_step_shared(cv, sh);
-        uint32_t *mask = keep_mask ? keep_mask : w.mask;
-        SQ_HIP(sq::launch_score(q, centroids, w.logits, w.plan.total, sh->B, sh->H, 1, sh->C, sh->sm_scale, s));
-        SQ_HIP(sq::launch_union_schedule(w.logits, thresh, sizes, offsets, mask, w.n_ranges,
-                                         n_keys ? n_keys : w.n_keys, w.plan, sh->U, sh->B, sh->H, sh->C, s));
-        SQ_HIP(sq::launch_decode_attn_shared(q, K_fixed, V_fixed, K_user, V_user, w.plan, w.partials, out, lse,
-                                             to_shape(sh), s));
+        if (int rc = decode_step_shared(sh, 1, q, centroids, sizes, offsets, thresh, K_fixed, V_fixed, K_user, V_user,
+                                        out, lse, keep_mask, n_keys, cv, s))
+            return rc;
         g_err[0] = 0;
         return SQ_OK;
     }

@@ -66,7 +66,7 @@ __device__ __forceinline__ int sv_pos(int kappa)
 __global__ __launch_bounds__(256, 3) void decode_attn_shared_kernel(
     const _Float16 *__restrict__ q, const _Float16 *__restrict__ Kf, const _Float16 *__restrict__ Vf,
     const _Float16 *__restrict__ Ku, const _Float16 *__restrict__ Vu, DecodePlan plan,
-    float *__restrict__ partials, int B, int H, int L, int U, float sm_scale)
+    float *__restrict__ partials, int BV, int G, int H, int L, int U, float sm_scale)
 {
     __shared__ __align__(16) WaveLds s_w[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -151,9 +151,9 @@ __global__ __launch_bounds__(256, 3) void decode_attn_shared_kernel(
                 for (int dt = 0; dt < 8; ++dt) o[dt] = f4{0.f, 0.f, 0.f, 0.f};
             }
             cur_row = row;
-            const int b = grp * SG + col;
-            if (b < B) {
-                const h8 *qp = reinterpret_cast<const h8 *>(q + ((size_t)b * H + h) * D);
+            const int vs = grp * SG + col;                 // virtual sequence of this lane's column
+            if (vs < BV) {
+                const h8 *qp = reinterpret_cast<const h8 *>(q + shared_row(vs, h, H, G) * D);
 #pragma unroll
                 for (int s = 0; s < 4; ++s) bq[s] = qp[s * 4 + kg];
             } else {
@@ -171,13 +171,13 @@ __global__ __launch_bounds__(256, 3) void decode_attn_shared_kernel(
         const int t_my = j0 + (lane & 31);                 // key slot this lane resolves (both halves of the wave agree)
         wave_lds_sync();                                   // the previous item's readers are done
         if (user) {
-            const int sq_ = -1 - h1.x;                     // sequence within the group
-            const size_t bh = (size_t)(grp * SG + sq_) * H + h;
+            const int jb = -1 - h1.x;                      // real sequence within the group; its G columns own the chunk
+            const size_t bh = (size_t)(grp * SG / G + jb) * H + h;
             Kbase = reinterpret_cast<const char *>(Ku + (bh * U + h1.y) * D);
             Vbase = reinterpret_cast<const char *>(Vu + (bh * U + h1.y) * D);
             if (lane < 32) {
                 S.rows[lane] = t_my < nvalid ? t_my : -1;
-                S.kset[lane] = t_my < nvalid ? (1u << sq_) : 0u;
+                S.kset[lane] = t_my < nvalid ? (((1u << G) - 1u) << (jb * G)) : 0u;
             }
         } else {
             Kbase = reinterpret_cast<const char *>(Kf + (size_t)h * L * D);
@@ -301,12 +301,13 @@ __global__ __launch_bounds__(256, 3) void decode_attn_shared_kernel(
 // that sequence.
 __global__ __launch_bounds__(MERGE_THREADS) void decode_merge_shared_kernel(const float *__restrict__ partials,
                                                                             DecodePlan plan, _Float16 *__restrict__ out,
-                                                                            float *__restrict__ lse, int H, int attn_grid)
+                                                                            float *__restrict__ lse, int H, int G,
+                                                                            int attn_grid)
 {
     __shared__ float s_red[MERGE_GROUPS * 130];
-    const size_t bh = blockIdx.x;
-    const int b = (int)(bh / H), h = (int)(bh % H);
-    const int urow = (b / SG) * H + h, sq_ = b % SG;
+    const size_t bh = blockIdx.x;                    // output row (b, h, g) of the [B, H, G] tensors
+    const int g = (int)(bh % G), h = (int)((bh / G) % H), vs = (int)(bh / ((size_t)G * H)) * G + g;
+    const int urow = (vs / SG) * H + h, sq_ = vs % SG;
     const int2 it = plan.row_items[urow];            // (first item, items) of the union row
     const int rank = plan.row_rank[urow];
     const int total = min(plan.total[0], plan.item_cap);
@@ -321,16 +322,17 @@ hipError_t launch_decode_attn_shared(const void *q, const void *Kf, const void *
                                      DecodePlan plan, float *partials, void *out, float *lse, const Shape &sh,
                                      hipStream_t s)
 {
-    const int rows = sh.B * sh.H;
+    const int G = sh.Lq;                             // query rows per (sequence, head): 1, or the GQA group size
+    const int rows = sh.B * sh.H * G;
     const bool prof = profile_mark(s, true);
     hipLaunchKernelGGL(decode_attn_shared_kernel, dim3(SHARED_ATTN_GRID), dim3(256), 0, s, (const _Float16 *)q,
                        (const _Float16 *)Kf, (const _Float16 *)Vf, (const _Float16 *)Ku, (const _Float16 *)Vu, plan,
-                       partials, sh.B, sh.H, sh.L, sh.U, sh.sm_scale);
+                       partials, sh.B * G, G, sh.H, sh.L, sh.U, sh.sm_scale);
     if (prof) profile_mark(s, false);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(decode_merge_shared_kernel, dim3(rows), dim3(MERGE_THREADS), 0, s, partials, plan,
-                       (_Float16 *)out, lse, sh.H, SHARED_ATTN_GRID);
+                       (_Float16 *)out, lse, sh.H, G, SHARED_ATTN_GRID);
     return hipGetLastError();
 }
 

@@ -75,17 +75,27 @@ struct SelectOpts {
     int mean_parts;                  // averaged-score selection: `logits` holds this many partial score sums per
     float mean_div;                  //   row, [rows, mean_parts, C]; their sum / mean_div is compared with T
     int union_rows;                  // shared-context decode: rows are union rows (sequence group, head)
-    int B;                           // shared-context decode: number of sequences
+    int B;                           // shared-context decode: number of query rows that share a head's K/V (B * G)
+    int G;                           // shared-context decode: query rows per (sequence, head), see shared_row
 };
 
 // Batched decode over a shared fixed context: sequences are handled in groups of SG; a "union row" is one
 // (group, head) pair and its work items cover the clusters kept by ANY sequence of the group, each key
 // carrying the set of sequences that kept it, so a key leaves HBM once per group instead of once per sequence.
 // Items of a union row use the layout above with these differences: slot 0.x is the union row; slot 1.x of a
-// user chunk is -1 - (sequence within the group); a record's x packs (position clamped to >= 0) | (set of
+// user chunk is -1 - (real sequence within the group: its G virtual sequences own the chunk); a record's x packs (position clamped to >= 0) | (set of
 // sequences << 16).
+// With grouped-query attention, G query heads of a sequence share one K/V head (and the sequence's user keys) and
+// select independently: the B * G (sequence, query head) pairs that share a K/V head are handled exactly like
+// B * G sequences over a shared context.  "Virtual sequence" vs = b * G + g; its query, keep mask, counts and
+// output sit at row ((b * H + h) * G + g) of the [B, H, G] tensors (H = K/V heads).  G = 1 is the plain batch.
+// G must divide SG so that the G virtual sequences of one real sequence never straddle two groups.
 constexpr int SG = 16;
-inline int seq_groups_for(int B) { return (B + SG - 1) / SG; }
+inline int seq_groups_for(int BV) { return (BV + SG - 1) / SG; }
+__host__ __device__ inline size_t shared_row(int vs, int h, int H, int G)
+{
+    return ((size_t)(vs / G) * H + h) * G + vs % G;
+}
 // Workgroups of the shared-context partial kernel: three per compute unit.
 constexpr int SHARED_ATTN_GRID = 256 * 3;
 
@@ -112,7 +122,7 @@ hipError_t launch_decode_attn(const void *q, const void *Kf, const void *Vf, con
 // rows) * SG slots of PART_STRIDE floats.
 hipError_t launch_union_schedule(const float *logits, const float *thresh, const int32_t *sizes,
                                  const int32_t *offsets, uint32_t *keep_masks, int32_t *n_ranges, int32_t *n_keys,
-                                 DecodePlan plan, int U, int B, int H, int C, hipStream_t s);
+                                 DecodePlan plan, int U, int B, int G, int H, int C, hipStream_t s);
 hipError_t launch_decode_attn_shared(const void *q, const void *Kf, const void *Vf, const void *Ku, const void *Vu,
                                      DecodePlan plan, float *partials, void *out, float *lse, const Shape &sh,
                                      hipStream_t s);

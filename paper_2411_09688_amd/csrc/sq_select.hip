@@ -261,24 +261,24 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     auto id_of = [&](int i) { return CAND ? cid[i] : i; };
     __shared__ uint32_t s_mask[CAND ? SELECT_MAX_C / 32 : 1];
     uint32_t *s_set = reinterpret_cast<uint32_t *>(s_e);   // UNION: set of sequences per cluster instead of e_i
-    const int n_seq = UNION ? min(SG, opt.B - (int)(row / H) * SG) : 1;
+    const int n_seq = UNION ? min(SG, opt.B - (int)(row / H) * SG) : 1;   // (virtual) sequences of this group
+    const int n_real = UNION ? (n_seq + opt.G - 1) / opt.G : 1;            // real sequences: owners of user keys
 
     if (UNION) {
         static_assert(SG == SEL_WAVES, "one wave per sequence of the group");
-        const size_t bh0 = (size_t)(row / H) * SG * H + h;           // row of sequence 0 of the group; sequence s: + s * H
+        const int vs0 = (int)(row / H) * SG;                         // first virtual sequence of the group
         if (wave < n_seq) {
-            const size_t bh = bh0 + (size_t)wave * H;
+            const size_t bh = shared_row(vs0 + wave, h, H, opt.G);
             wave_select_mask<false>(logits + bh * C, N, C, thresh[h], 0.0f, 0.0f, keep_mask + bh * W, n_ranges + bh,
                                     n_keys + bh, lane);
         }
         __threadfence_block();
         __syncthreads();                                             // the group's masks are written
-        const uint32_t *m0 = keep_mask + bh0 * W;
         for (int i = tid; i < C; i += SEL_THREADS) {
             uint32_t set = 0u;
 #pragma unroll
             for (int sq_ = 0; sq_ < SG; ++sq_) {                     // independent loads
-                const uint32_t word = sq_ < n_seq ? m0[(size_t)sq_ * H * W + (i >> 5)] : 0u;
+                const uint32_t word = sq_ < n_seq ? keep_mask[shared_row(vs0 + sq_, h, H, opt.G) * W + (i >> 5)] : 0u;
                 set |= ((word >> (i & 31)) & 1u) << sq_;
             }
             s_set[i] = set;
@@ -449,7 +449,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     // that ran before): rows land in arrival order, which moves chunks between workgroups but changes no result.
     // The add is issued as soon as the row's totals are known, so its round trip runs under the second pass.
     auto take_items = [&](int total_keys) {
-        const int n_items = n_user_chunks * n_seq + (min(total_keys, plan.L) + KPC - 1) / KPC;
+        const int n_items = n_user_chunks * n_real + (min(total_keys, plan.L) + KPC - 1) / KPC;
         // One 64-bit add advances (items, rows placed) together, so rows are ranked in item order.
         const unsigned long long old = atomicAdd(reinterpret_cast<unsigned long long *>(plan.total),
                                                  (1ull << 32) | (unsigned long long)(unsigned)n_items);
@@ -543,7 +543,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
         // This row's work items (their base was taken above).  The records written above are read back after
         // the barrier.
         const int n_sel = min(base_k, plan.L);
-        const int n_uc = n_user_chunks * n_seq;             // every sequence of a union row has its own user keys
+        const int n_uc = n_user_chunks * n_real;            // every real sequence of a union row has its own user keys
         __syncthreads();                                    // every thread is done with the staged row (s_first aliases it)
         int *s_first = reinterpret_cast<int *>(smem);       // the staged logits are no longer needed
         if (C <= SEL_THREADS) {
@@ -706,13 +706,14 @@ hipError_t launch_select(const float *logits, const float *row_max, const float 
 
 hipError_t launch_union_schedule(const float *logits, const float *thresh, const int32_t *sizes,
                                  const int32_t *offsets, uint32_t *keep_masks, int32_t *n_ranges, int32_t *n_keys,
-                                 DecodePlan plan, int U, int B, int H, int C, hipStream_t s)
+                                 DecodePlan plan, int U, int B, int G, int H, int C, hipStream_t s)
 {
     SelectOpts opt{};
     opt.union_rows = 1;
-    opt.B = B;
+    opt.B = B * G;
+    opt.G = G;
     return launch_select(logits, nullptr, nullptr, false, thresh, sizes, offsets, keep_masks, nullptr, n_ranges,
-                         n_keys, plan, true, U, opt, seq_groups_for(B) * H, H, 1, C, s);
+                         n_keys, plan, true, U, opt, seq_groups_for(B * G) * H, H, 1, C, s);
 }
 
 hipError_t launch_ranges_to_rec(const int32_t *ranges, const int32_t *n_ranges, DecodePlan plan, int rows,

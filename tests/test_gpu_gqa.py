@@ -1,0 +1,129 @@
+"""GPU parity of the grouped-query decode step (sq_gqa_decode_step) against the oracle: per query head the kept
+cluster set (bit-exact outside the near-threshold band), the key counts, the attention output and its lse."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2411_09688_amd import workload as wl
+from tests.gpu_util import ATTN_ATOL, check_selection, unpack_mask
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def sq():
+    from paper_2411_09688_amd import binding
+    binding.lib()
+    return binding
+
+
+def run_gqa(sq, w, G, thresh=None, optional=True):
+    """w has Lq = G query rows per (sequence, K/V head): q [B, H, G, d] is q [B, H*G, 1, d] in memory."""
+    dev = torch.device("cuda:0")
+    tt = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    Hq, W = w.H * G, (w.C + 31) // 32
+    shape = sq.make_shape(w.B, w.H, w.L, w.C, 1, w.U, w.sm_scale)
+    out = torch.full((w.B, Hq, 1, w.d), 7.0, dtype=torch.float16, device=dev)
+    lse = torch.zeros(w.B, Hq, 1, dtype=torch.float32, device=dev)
+    mask = torch.zeros(w.B, Hq, 1, W, dtype=torch.int32, device=dev)
+    nk = torch.zeros(w.B, Hq, 1, dtype=torch.int32, device=dev)
+    th = w.thresh if thresh is None else thresh
+    ws = sq.workspace(shape, sq.SQ_CALL_GQA_DECODE_STEP, dev)
+    sq.sq_gqa_decode_step(shape, G, tt(w.q.reshape(w.B, Hq, 1, w.d)), tt(w.centroids), tt(w.sizes), tt(w.offsets), tt(th),
+                          tt(w.K_fixed), tt(w.V_fixed), tt(w.K_user), tt(w.V_user), out, lse if optional else None,
+                          mask if optional else None, nk if optional else None, ws)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()[:, :, 0], lse.cpu().numpy()[:, :, 0], mask.cpu().numpy()[:, :, 0], nk.cpu().numpy()[:, :, 0]
+
+
+def against_oracle(sq, w, G, label, thresh=None):
+    th = w.thresh if thresh is None else thresh
+    out, lse, mask, nk = run_gqa(sq, w, G, thresh=th)
+    q = np.ascontiguousarray(w.q.reshape(w.B, w.H * G, w.d))
+    ref = oracle.gqa_decode(q, w.centroids, w.sizes, w.offsets, th, w.K_fixed, w.V_fixed, w.K_user, w.V_user, w.sm_scale, G)
+    gk = unpack_mask(mask.view(np.uint32), w.C).reshape(w.B, w.H, G, w.C)
+    ok = unpack_mask(ref["mask"], w.C).reshape(w.B, w.H, G, w.C)
+    listed = check_selection(w, gk, ok, th, label=label)        # (b, h, t = g): the query of head h * G + g
+    np.testing.assert_array_equal(nk.reshape(w.B, w.H, G), (gk * w.sizes[None, :, None, :]).sum(-1))
+    if listed:
+        # a near-threshold cluster decided differently: give the oracle the GPU's selection for the attention check
+        ranges = np.zeros((w.B, w.H, G, w.C, 2), np.int32)
+        n_r = np.zeros((w.B, w.H, G), np.int32)
+        for b, h, g in np.ndindex(w.B, w.H, G):
+            ids = np.flatnonzero(gk[b, h, g])
+            ranges[b, h, g, :len(ids), 0] = w.offsets[h][ids]
+            ranges[b, h, g, :len(ids), 1] = w.sizes[h][ids]
+            n_r[b, h, g] = len(ids)
+        ro, rl = oracle.sparse_attn(w.q, w.K_fixed, w.V_fixed, ranges, n_r, w.K_user, w.V_user, w.sm_scale)
+        ro, rl = ro.reshape(w.B, w.H * G, w.d), rl.reshape(w.B, w.H * G)
+    else:
+        ro, rl = ref["out"], ref["lse"]
+    err = np.abs(out.astype(np.float64) - ro).max()
+    assert err <= ATTN_ATOL, f"{label}: attention max-abs error {err}"
+    fin = np.isfinite(rl)
+    assert (np.isneginf(lse) == ~fin).all()
+    np.testing.assert_allclose(lse[fin], rl[fin], atol=1e-4, rtol=1e-5)
+    return err
+
+
+@pytest.mark.parametrize("case", [
+    dict(G=4, B=1, H=2, L=900, C=30, U=5, keep_frac=0.3),          # one sequence: the group alone shares the K/V head
+    dict(G=2, B=3, H=3, L=3000, C=100, U=300, keep_frac=0.5),      # several sequences, user chunks with a ragged tail
+    dict(G=8, B=2, H=2, L=2000, C=50, U=0, keep_frac=0.2),         # exactly one group of 16, no user keys
+    dict(G=4, B=5, H=1, L=1500, C=65, U=40, keep_frac=0.25),       # 20 (sequence, head) pairs: two groups, the second partial
+    dict(G=16, B=2, H=2, L=1200, C=40, U=130, keep_frac=0.4),      # a whole group per sequence; a second user chunk
+    dict(G=2, B=2, H=1, L=4096, C=2048, U=17, keep_frac=0.2),      # more clusters than one selection step holds
+])
+def test_gqa_step_against_oracle(sq, case):
+    case = dict(case)
+    G = case.pop("G")
+    w = wl.calibrate(wl.make_workload("gqa", Lq=G, seed=41, threads=4, **case), oracle.scores)
+    against_oracle(sq, w, G, f"gqa G={G} {case}")
+
+
+def test_gqa_extremes_and_optional_outputs(sq):
+    G = 4
+    base = dict(B=2, H=2, L=1024, C=32, Lq=G, U=33, keep_frac=0.5, seed=42, threads=2)
+    w = wl.make_workload("gqa_all", **base)
+    against_oracle(sq, w, G, "gqa keep-all", thresh=np.full(w.H, -1.0, np.float32))
+    against_oracle(sq, w, G, "gqa keep-none", thresh=np.full(w.H, 2.0, np.float32))
+    w0 = wl.make_workload("gqa_empty", **dict(base, U=0))
+    out, lse, mask, nk = run_gqa(sq, w0, G, thresh=np.full(w0.H, 2.0, np.float32))
+    assert (out == 0).all() and np.isneginf(lse).all() and (nk == 0).all() and (mask == 0).all()
+    # optional outputs left out: same attention output
+    w = wl.calibrate(wl.make_workload("gqa_opt", **base), oracle.scores)
+    a = run_gqa(sq, w, G)[0]
+    b = run_gqa(sq, w, G, optional=False)[0]
+    np.testing.assert_array_equal(a, b)
+
+
+def test_group_of_one_is_sq_decode_step(sq):
+    w = wl.calibrate(wl.make_workload("gqa_g1", B=3, H=2, L=2000, C=64, Lq=1, U=70, keep_frac=0.3, seed=43, threads=2),
+                     oracle.scores)
+    out, lse, mask, nk = run_gqa(sq, w, 1)
+    P = sq.upload(w)
+    sq.sq_decode_step(P.shape, P.q, P.centroids, P.sizes, P.offsets, P.thresh, P.K_fixed, P.V_fixed, P.K_user, P.V_user,
+                      P.out, P.lse, P.keep_mask, P.n_keys, sq.workspace(P.shape, sq.SQ_CALL_DECODE_STEP, P.q.device))
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(mask, P.keep_mask.cpu().numpy()[:, :, 0])
+    np.testing.assert_array_equal(nk, P.n_keys.cpu().numpy()[:, :, 0])
+    assert np.abs(out.astype(np.float32) - P.out.cpu().numpy()[:, :, 0].astype(np.float32)).max() <= 1e-3
+
+
+def test_unsupported_group_size_is_an_error(sq):
+    w = wl.make_workload("gqa_bad", B=1, H=1, L=256, C=8, Lq=3, U=0, keep_frac=0.5, seed=44, threads=1)
+    w.thresh = np.full(w.H, 0.5, np.float32)
+    with pytest.raises(sq.SqError) as e:
+        run_gqa(sq, w, 3)
+    assert e.value.code == sq.SQ_ERR_UNSUPPORTED
+
+
+def test_llama3_shape_gqa_decode_32k(sq):
+    # Llama-3.1-8B attention shape: 32 query heads over 8 K/V heads (G = 4), 32K fixed context, keep 1/8.
+    print("gqa 32k: generating", flush=True)
+    G = 4
+    w = wl.calibrate(wl.make_workload("gqa_decode_32k", B=1, H=8, L=32768, C=1024, Lq=G, U=512, keep_frac=1 / 8, seed=0,
+                                      threads=16), oracle.scores)
+    err = against_oracle(sq, w, G, "gqa-32k")
+    print("gqa 32k attention max-abs err", err, flush=True)
