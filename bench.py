@@ -326,6 +326,65 @@ def bench_hier(args, torch, sq, wl, dev):
     print(json.dumps(res, ensure_ascii=False))
 
 
+def bench_gqa(args, torch, sq, wl, dev):
+    """Grouped-query decode (sq_gqa_decode_step): G query heads per K/V head select independently; one step = one
+    token; the union of a group's selections is streamed once."""
+    w = wl.make_config(args.workload, seed=args.seed, threads=16)
+    wl.calibrate(w, gpu_score_fn(sq, torch, dev))
+    G, NQ, R = w.Lq, args.queries, args.replicas
+    Hq, W = w.H * G, (w.C + 31) // 32
+    tt = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    rep = lambda a: [tt(a) for _ in range(R)]
+    Kf, Vf, Ce, Ku, Vu = rep(w.K_fixed), rep(w.V_fixed), rep(w.centroids), rep(w.K_user), rep(w.V_user)
+    sizes, offsets, thresh = tt(w.sizes), tt(w.offsets), tt(w.thresh)
+    qs = wl.extra_queries(w, NQ + G - 1)                                            # [n, H, d]
+    # token i: query head h*G + g of K/V head h is query i + g of that head's stream
+    Q = torch.stack([tt(np.ascontiguousarray(qs[i:i + G].transpose(1, 0, 2).reshape(1, Hq, 1, w.d))) for i in range(NQ)])
+    out = torch.zeros(NQ, w.B, Hq, 1, w.d, dtype=torch.float16, device=dev)
+    lse = torch.zeros(NQ, w.B, Hq, 1, dtype=torch.float32, device=dev)
+    nkeys = torch.zeros(NQ, w.B, Hq, 1, dtype=torch.int32, device=dev)
+    kmask = torch.zeros(NQ, w.B, Hq, 1, W, dtype=torch.int32, device=dev)
+    shape = sq.make_shape(w.B, w.H, w.L, w.C, 1, w.U, w.sm_scale)
+    ws = sq.workspace(shape, sq.SQ_CALL_GQA_DECODE_STEP, dev)
+
+    def step(i, stream_ptr):
+        qi, r = i % NQ, i % R
+        sq.sq_gqa_decode_step(shape, G, Q[qi], Ce[r], sizes, offsets, thresh, Kf[r], Vf[r], Ku[r], Vu[r], out[qi],
+                              lse[qi], kmask[qi], nkeys[qi], ws)
+
+    eager_ms, graph_ms, ms, (n_meas, k_avg, k_min, k_max) = time_steps(step, args, torch, sq)
+    used = [(args.warmup + i) % NQ for i in range(args.steps)]
+    nk = nkeys.cpu().numpy()[:, 0, :, 0]                                            # [NQ, Hq]
+    km = kmask.cpu().numpy()[:, 0, :, 0, :].view(np.uint32).reshape(NQ, w.H, G, W)
+    union = np.bitwise_or.reduce(km, axis=2)                                        # [NQ, H, W]
+    bits = ((union[..., None] >> np.arange(32, dtype=np.uint32)) & 1).reshape(NQ, w.H, -1)[:, :, :w.C]
+    uniq = (bits * w.sizes[None]).sum(axis=(1, 2))                                  # keys of the union, per token
+    sel = float(np.mean([uniq[qi] for qi in used])) * w.d * 4                       # K + V rows, read once
+    sel_req = float(np.mean([nk[qi].sum() for qi in used])) * w.d * 4
+    cen = w.H * w.C * w.d * 2
+    dense = w.B * w.H * w.U * w.d * 4
+    meta = w.H * (2 * w.C + 1) * 4
+    tot = sel + cen + dense + meta + 2 * w.B * Hq * w.d * 2
+    kernel_bytes = sel + dense + w.B * Hq * w.d * 2
+    res = base_result(args, "grouped-query decode attn µs/token + achieved HBM GB/s, 32K fixed ctx, keep 1/8, "
+                      "32 query heads over 8 K/V heads, d=128", round(tot / (ms * 1e-3) / 1e9, 2), "GB/s", ms, eager_ms,
+                      graph_ms, w.B)
+    res["config"] = {"workload": args.workload, "B": w.B, "H_kv": w.H, "G": G, "d": w.d, "L": w.L, "C": w.C, "U": w.U,
+                     "keep_target": w.keep_frac, "keep_achieved": round(float(np.mean([nk[qi].mean() for qi in used])) / w.L, 5),
+                     "queries": NQ, "replicas": R, "entry": "sq_gqa_decode_step"}
+    res["bytes_per_step"] = {"total": round(tot), "centroid": cen, "selected_kv": round(sel),
+                             "selected_kv_requested": round(sel_req), "dense_kv": dense}
+    res["hbm_frac_whole_step"] = round(tot / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)
+    res["roofline"] = {"bound": "hbm", "kernel": "decode_attn_shared_kernel",
+                       "achieved": round(kernel_bytes / (k_avg * 1e-6) / 1e9, 2) if n_meas else None,
+                       "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                       "frac": round(kernel_bytes / (k_avg * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4) if n_meas else None,
+                       "traffic": read_traffic(f"decode_attn_shared_kernel_{args.workload}_pmc.txt"),
+                       "bytes_per_launch": round(kernel_bytes), "avg_us": round(k_avg, 3), "min_us": round(k_min, 3),
+                       "launches": n_meas}
+    print(json.dumps(res, ensure_ascii=False))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -365,6 +424,8 @@ def main():
         print(json.dumps({"pmc_calibration": {"stream_read_bytes": 1 << 28, "copy_bytes_each_way": 1 << 28}}))
         return
 
+    if args.workload in wl.GQA_CONFIGS:
+        return bench_gqa(args, torch, sq, wl, dev)
     cfg = wl.CONFIGS[args.workload]
     if cfg.get("Lq", 1) > 1:
         return bench_prefill(args, torch, sq, wl, dev)

@@ -52,17 +52,35 @@ __device__ __forceinline__ float cross16_max(float v)
     return v;
 }
 
+// Sum over the 64 lanes of a wave as an xor butterfly (partners 1, 2, 4, 8, 16, 32 lanes away, in that order);
+// every lane gets the same bits.  Entirely in the vector ALU: the first two steps are quad permutes; after them
+// the four lanes of a quad agree, so mirroring a half row (lane i <-> 7 - i) pairs the same values as xor 4, and
+// mirroring a row (i <-> 15 - i) the same as xor 8; the last two steps add the four row sums, read with
+// v_readlane, as (r0 + r1) + (r2 + r3), which is what every row's butterfly computes.  Must be called with all
+// 64 lanes active.  This is the one summation order of the library for sums over a wave.
 __device__ __forceinline__ float wave_sum(float v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
+    v += dpp_f<0xb1>(v);          // quad_perm [1,0,3,2]
+    v += dpp_f<0x4e>(v);          // quad_perm [2,3,0,1]
+    v += dpp_f<0x141>(v);         // row_half_mirror
+    v += dpp_f<0x140>(v);         // row_mirror
+    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 0));
+    const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 16));
+    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 32));
+    const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 48));
+    return (r0 + r1) + (r2 + r3);
 }
 __device__ __forceinline__ float wave_max(float v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-    return v;
+    v = fmaxf(v, dpp_f<0xb1>(v));
+    v = fmaxf(v, dpp_f<0x4e>(v));
+    v = fmaxf(v, dpp_f<0x141>(v));
+    v = fmaxf(v, dpp_f<0x140>(v));
+    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 0));
+    const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 16));
+    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 32));
+    const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 48));
+    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
 }
 
 // Integer data-parallel-primitive move for scans: lanes whose source lies outside their row of 16, and rows not

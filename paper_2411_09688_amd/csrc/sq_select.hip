@@ -147,7 +147,8 @@ __device__ __forceinline__ void emit_row_items(const DecodePlan &plan, int row, 
 template <bool STATS_IN>
 __device__ __forceinline__ void wave_select_mask(const float *__restrict__ x, const int32_t *__restrict__ N, int C, float T,
                                                  float m_in, float D_in, uint32_t *__restrict__ mask_row,
-                                                 int32_t *n_ranges_out, int32_t *n_keys_out, int lane)
+                                                 int32_t *n_ranges_out, int32_t *n_keys_out, int lane,
+                                                 uint32_t *lds_row = nullptr)   // optional second copy of the mask words
 {
     const int W = (C + 31) >> 5;
     int cnt = 0, keys = 0;
@@ -186,6 +187,10 @@ __device__ __forceinline__ void wave_select_mask(const float *__restrict__ x, co
                 const int w0 = g * 2;
                 mask_row[w0] = (uint32_t)bal;
                 if (w0 + 1 < W) mask_row[w0 + 1] = (uint32_t)(bal >> 32);
+                if (lds_row) {
+                    lds_row[w0] = (uint32_t)bal;
+                    if (w0 + 1 < W) lds_row[w0 + 1] = (uint32_t)(bal >> 32);
+                }
             }
             cnt += __popcll(bal);
             keys += keep ? nv[g] : 0;
@@ -213,6 +218,10 @@ __device__ __forceinline__ void wave_select_mask(const float *__restrict__ x, co
                     const int w0 = i >> 5;
                     mask_row[w0] = (uint32_t)bal;
                     if (w0 + 1 < W) mask_row[w0 + 1] = (uint32_t)(bal >> 32);
+                    if (lds_row) {
+                        lds_row[w0] = (uint32_t)bal;
+                        if (w0 + 1 < W) lds_row[w0 + 1] = (uint32_t)(bal >> 32);
+                    }
                 }
                 cnt += __popcll(bal);
                 keys += keep ? nv[u] : 0;
@@ -269,20 +278,33 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
         const int vs0 = (int)(row / H) * SG;                         // first virtual sequence of the group
         if (wave < n_seq) {
             const size_t bh = shared_row(vs0 + wave, h, H, opt.G);
+            // the mask words also go to LDS ([SG][W] words at the start of the staging area: W * 32 <= C + 31)
             wave_select_mask<false>(logits + bh * C, N, C, thresh[h], 0.0f, 0.0f, keep_mask + bh * W, n_ranges + bh,
-                                    n_keys + bh, lane);
+                                    n_keys + bh, lane, s_set + wave * W);
         }
-        __threadfence_block();
-        __syncthreads();                                             // the group's masks are written
-        for (int i = tid; i < C; i += SEL_THREADS) {
-            uint32_t set = 0u;
+        __syncthreads();                                             // the group's masks are in LDS
+        uint32_t setv[16];                                           // C <= 16 * SEL_THREADS
 #pragma unroll
-            for (int sq_ = 0; sq_ < SG; ++sq_) {                     // independent loads
-                const uint32_t word = sq_ < n_seq ? keep_mask[shared_row(vs0 + sq_, h, H, opt.G) * W + (i >> 5)] : 0u;
-                set |= ((word >> (i & 31)) & 1u) << sq_;
+        for (int k = 0; k < 16; ++k) {
+            const int i = k * SEL_THREADS + tid;
+            uint32_t set = 0u;
+            if (i < C) {
+#pragma unroll
+                for (int sq_ = 0; sq_ < SG; ++sq_) {
+                    const uint32_t word = sq_ < n_seq ? s_set[sq_ * W + (i >> 5)] : 0u;
+                    set |= ((word >> (i & 31)) & 1u) << sq_;
+                }
             }
-            s_set[i] = set;
-            s_N[i] = N[i];
+            setv[k] = set;
+        }
+        __syncthreads();                                             // the mask words are consumed: the area is reused
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const int i = k * SEL_THREADS + tid;
+            if (i < C) {
+                s_set[i] = setv[k];
+                s_N[i] = N[i];
+            }
         }
     } else if (CAND) {
         for (int w = tid; w < W; w += SEL_THREADS) s_mask[w] = 0u;
@@ -656,6 +678,7 @@ hipError_t launch_select(const float *logits, const float *row_max, const float 
     // LDS: logits + sizes of the row; reused for two ints per chunk when scheduling.
     size_t smem = (size_t)C * 8;
     if (schedule && (size_t)chunk_cap_for(plan.L) * 8 > smem) smem = (size_t)chunk_cap_for(plan.L) * 8;
+    if (opt.union_rows && (size_t)SG * ((C + 31) / 32) * 4 > smem) smem = (size_t)SG * ((C + 31) / 32) * 4;   // the group's masks
     if (smem > (size_t)LDS_BYTES_MAX) return hipErrorInvalidValue;
     static bool attr_set = false;   // one GPU per process in this build
     if (!attr_set) {

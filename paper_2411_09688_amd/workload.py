@@ -200,9 +200,16 @@ CONFIGS = {
                                   C1=256, coarse_keep_frac=1 / 8),
 }
 
+# Grouped-query decode at a Llama-3.1-8B attention shape (32 query heads over 8 K/V heads, 32K fixed context): not
+# one of the five configurations above; the "next" row for models whose heads share keys and values.  Lq holds
+# the group size G: the G query heads of a K/V head are its G query rows, q [B, H, G, d] = q [B, H*G, 1, d].
+GQA_CONFIGS = {
+    "gqa_decode_32k": dict(B=1, H=8, L=32768, C=1024, Lq=4, U=512, keep_frac=1 / 8),
+}
+
 
 def make_config(name: str, seed: int = 0, threads: int = 8, **override) -> Workload:
-    kw = dict(CONFIGS[name])
+    kw = dict(CONFIGS[name] if name in CONFIGS else GQA_CONFIGS[name])
     kw.update(override)
     return make_workload(name, seed=seed, threads=threads, **kw)
 
