@@ -97,9 +97,9 @@ struct DecodeWs {
     float *partials;
 };
 
-DecodeWs carve_decode(Carver &cv, const sq_shape_t *sh)
+DecodeWs carve_decode(Carver &cv, const sq_shape_t *sh, int G = 1)
 {
-    const size_t rows = (size_t)sh->B * sh->H;
+    const size_t rows = (size_t)sh->B * sh->H * G;
     const size_t items = rows * (sq::user_chunks_for(sh->U) + sq::chunk_cap_for(sh->L));
     DecodeWs w{};
     w.plan.rec_cap = sh->C;
@@ -121,14 +121,15 @@ struct StepWs {
     DecodeWs dec;
 };
 
-StepWs carve_step(Carver &cv, const sq_shape_t *sh)
+// G: query heads per K/V head (rows = B * H * G; 1 without grouped-query attention).
+StepWs carve_step(Carver &cv, const sq_shape_t *sh, int G = 1)
 {
-    const size_t rows = (size_t)sh->B * sh->H;
+    const size_t rows = (size_t)sh->B * sh->H * G;
     StepWs w{};
     w.logits = cv.take<float>(rows * sh->C);
     w.n_ranges = cv.take<int32_t>(rows);
     w.n_keys = cv.take<int32_t>(rows);
-    w.dec = carve_decode(cv, sh);
+    w.dec = carve_decode(cv, sh, G);
     return w;
 }
 
@@ -319,9 +320,12 @@ size_t sq_workspace_bytes(const sq_shape_t *sh, int which)
     case SQ_CALL_PREFILL_STEP:
         carve_prefill_step(cv, sh);
         return cv.off;
-    case SQ_CALL_GQA_DECODE_STEP:                       // sized for the largest group (16 query heads per K/V head)
+    case SQ_CALL_GQA_DECODE_STEP: {                     // sized for the largest group (16 query heads per K/V head)
         carve_step_shared(cv, sh, sq::SG);
-        return cv.off;
+        Carver cv2(nullptr);                            // ... on either kernel family
+        carve_step(cv2, sh, sq::SG);
+        return cv.off > cv2.off ? cv.off : cv2.off;
+    }
     case SQ_CALL_PREFILL_MEAN_STEP:
         carve_prefill_mean_step(cv, sh);
         return cv.off;
@@ -408,6 +412,11 @@ int sq_sparse_attn_decode(const sq_shape_t *sh, const void *q, const void *K_fix
 }
 
 namespace {
+// With at least this many (sequence, query head) pairs per K/V head the grouped-query step streams the union of
+// their selections (shared-context kernels); with fewer, the overlap of the selections saves less than the union
+// kernels cost and the per-row kernels run (measured at B = 1, G = 4, 32K context: 43 us against 32 us per token).
+constexpr int GQA_SHARED_MIN = 8;
+
 // Decode step over K/V shared by several query rows: B sequences over one fixed context, times G query heads per
 // K/V head.  Every (sequence, query head) selects on its own; the work items are built from the union of the
 // selections of each group of 16 of them, so a cluster kept by several is streamed once.
@@ -455,9 +464,25 @@ int sq_gqa_decode_step(const sq_shape_t *sh, int32_t G, const void *q, const voi
     if (int rc = check_ws(__func__, sh, SQ_CALL_GQA_DECODE_STEP, ws, ws_bytes)) return rc;
     if (int rc = check_device(__func__)) return rc;
     Carver cv(ws);
-    if (int rc = decode_step_shared(sh, G, q, centroids, sizes, offsets, thresh, K_fixed, V_fixed, K_user, V_user, out,
-                                    lse, keep_mask, n_keys, cv, static_cast<hipStream_t>(stream)))
-        return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (sh->B * G >= GQA_SHARED_MIN) {
+        if (int rc = decode_step_shared(sh, G, q, centroids, sizes, offsets, thresh, K_fixed, V_fixed, K_user, V_user, out,
+                                        lse, keep_mask, n_keys, cv, s))
+            return rc;
+        g_err[0] = 0;
+        return SQ_OK;
+    }
+    // Few query rows per K/V head: every (sequence, query head) is a row of the per-row kernels, which read the K/V
+    // head once per query head (the rows are [B, H, G]: K/V head = (row / G) % H).
+    StepWs w = carve_step(cv, sh, G);
+    int32_t *nk = n_keys ? n_keys : w.n_keys;
+    const int rows = sh->B * sh->H * G;
+    SQ_HIP(sq::launch_score(q, centroids, w.logits, w.dec.plan.total, sh->B, sh->H, G, sh->C, sh->sm_scale, s));
+    SQ_HIP(sq::launch_select(w.logits, nullptr, nullptr, false, thresh, sizes, offsets, keep_mask, nullptr, w.n_ranges,
+                             nk, w.dec.plan, true, sh->U, sq::SelectOpts{}, rows, sh->H, G, sh->C, s));
+    sq::Shape shp = to_shape(sh);
+    shp.Lq = G;
+    SQ_HIP(sq::launch_decode_attn(q, K_fixed, V_fixed, K_user, V_user, w.dec.plan, w.dec.partials, out, lse, shp, s));
     g_err[0] = 0;
     return SQ_OK;
 }

@@ -42,7 +42,7 @@ __device__ __forceinline__ int items_per_batch(int total, int grid)
 __global__ __launch_bounds__(256) void decode_attn_kernel(
     const _Float16 *__restrict__ q, const _Float16 *__restrict__ Kf, const _Float16 *__restrict__ Vf,
     const _Float16 *__restrict__ Ku, const _Float16 *__restrict__ Vu, DecodePlan plan,
-    float *__restrict__ partials, int H, int L, int U, float sm_scale)
+    float *__restrict__ partials, int H, int G, int L, int U, float sm_scale)
 {
     __shared__ int s_pos[KPC], s_delta[KPC];
     __shared__ int s_rows[KPC];
@@ -133,12 +133,15 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
             const int nvalid = h0.y;
             const bool user = h1.x < 0;
             const int nrec = min(h1.x, KPC);
-            const int h = (int)(bh % H);
+            // Row bh = (sequence, K/V head, query head of the group): G query heads share the K/V head and the
+            // sequence's user keys (G = 1 without grouped-query attention).
+            const size_t bkv = bh / G;                     // (sequence, K/V head)
+            const int h = (int)(bkv % H);
             const _Float16 *Kbase, *Vbase;
             const h8 qv = *reinterpret_cast<const h8 *>(q + bh * D + p * 8);
             if (user) {
-                Kbase = Ku + (bh * U + h1.y) * D;
-                Vbase = Vu + (bh * U + h1.y) * D;
+                Kbase = Ku + (bkv * U + h1.y) * D;
+                Vbase = Vu + (bkv * U + h1.y) * D;
                 if (tid < KPC) s_rows[tid] = tid < nvalid ? tid : -1;
             } else {
                 Kbase = Kf + (size_t)h * L * D;
@@ -227,13 +230,14 @@ hipError_t launch_decode_attn(const void *q, const void *Kf, const void *Vf, con
                               DecodePlan plan, float *partials, void *out, float *lse, const Shape &sh,
                               hipStream_t s)
 {
-    const int rows = sh.B * sh.H;
+    const int G = sh.Lq;                             // query heads per K/V head (1, or the group size)
+    const int rows = sh.B * sh.H * G;
     static const int grid_env = getenv("SQ_ATTN_GRID") ? atoi(getenv("SQ_ATTN_GRID")) : 0;   // tuning knob
     const int want = grid_env > 0 ? grid_env : ATTN_GRID;
     const int grid = plan.item_cap < want ? plan.item_cap : want;
     const bool prof = profile_mark(s, true);
     hipLaunchKernelGGL(decode_attn_kernel, dim3(grid), dim3(256), 0, s, (const _Float16 *)q, (const _Float16 *)Kf,
-                       (const _Float16 *)Vf, (const _Float16 *)Ku, (const _Float16 *)Vu, plan, partials, sh.H, sh.L,
+                       (const _Float16 *)Vf, (const _Float16 *)Ku, (const _Float16 *)Vu, plan, partials, sh.H, G, sh.L,
                        sh.U, sh.sm_scale);
     if (prof) profile_mark(s, false);
     hipError_t e = hipGetLastError();
