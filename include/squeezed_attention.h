@@ -204,10 +204,11 @@ int sq_hier_select(const sq_shape_t *shape, int32_t C1, const void *q,
  * quantity the paper times (lookup + argument set-up + sparse attention, Appendix "Kernel
  * Benchmarking").  The selection is bit-identical to the three separate calls; the attention output
  * agrees up to rounding (the keys are split over workgroups differently).
- * With B >= 2 the sequences share K_fixed/V_fixed (the shared-prefix setting of Section 1): each
- * sequence still selects on its own, but the step streams the union of the selections of every group
- * of 16 sequences, so a key kept by several sequences is read once; the probabilities are rounded to
- * fp16 before they multiply V (matrix-core product, fp32 accumulation), as in sq_sparse_attn_prefill.
+ * With B >= 2 the sequences share K_fixed/V_fixed (the shared-prefix setting of Section 1) and each
+ * sequence still selects on its own.  From B = 8 on, the step streams the union of the selections of every
+ * group of 16 sequences, so a key kept by several sequences is read once; the probabilities are then rounded
+ * to fp16 before they multiply V (matrix-core product, fp32 accumulation), as in sq_sparse_attn_prefill.
+ * Below that the selections overlap too little to pay for the union and every sequence is handled by itself.
  * Out: out f16 [B,H,1,d]; optional (NULL to skip): lse f32 [B,H,1], keep_mask u32 [B,H,1,ceil(C/32)],
  *      n_keys i32 [B,H,1].
  * Workspace: sq_workspace_bytes(shape, SQ_CALL_DECODE_STEP).
@@ -224,9 +225,10 @@ int sq_decode_step(const sq_shape_t *shape, const void *q,
  * selects its clusters independently (the setting of the appendix "Additional Longbench Evaluation": keys and
  * values shared amongst a subset of the heads, each head selecting on its own).  shape->H is the number of K/V
  * heads; query head hq = h * G + g uses K/V head h.  The B * G (sequence, query head) pairs of a K/V head are
- * handled like B * G sequences over a shared context: the union of the selections of every group of 16 of them is
- * streamed once, so a key kept by several query heads leaves HBM once (same kernels, arithmetic and rounding as
- * sq_decode_step with B >= 2; G = 1 is that call).  G must be 1, 2, 4, 8 or 16.
+ * handled like B * G sequences over a shared context: from B * G = 8 on, the union of the selections of every group
+ * of 16 of them is streamed once, so a key kept by several query heads leaves HBM once; below that every pair is a
+ * row of the per-sequence kernels, which read the K/V head once per query head (same kernels, arithmetic and
+ * rounding as sq_decode_step; G = 1 is that call).  G must be 1, 2, 4, 8 or 16.
  * In:  q f16 [B, H*G, 1, d]; centroids, sizes, offsets, thresh, K_fixed, V_fixed per K/V head as everywhere;
  *      K_user, V_user f16 [B, H, U, d].
  * Out: out f16 [B, H*G, 1, d]; optional (NULL to skip): lse f32 [B, H*G, 1], keep_mask u32 [B, H*G, 1, ceil(C/32)],

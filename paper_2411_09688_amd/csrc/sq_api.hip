@@ -167,8 +167,13 @@ SharedStepWs carve_step_shared(Carver &cv, const sq_shape_t *sh, int G = 1)
     return w;
 }
 
-// A decode step with two or more sequences runs the shared-context kernels.
-bool step_is_shared(const sq_shape_t *sh) { return sh->B >= 2; }
+// With at least this many query rows per K/V head -- sequences over a shared context, times the query heads of a
+// grouped-query group -- a decode step streams the union of their selections (shared-context kernels); with
+// fewer, the overlap of the selections saves less than the union kernels cost and the per-row kernels run
+// (measured at 32K context, keep 1/8: 2 sequences 65 us against 50 us per step, 6 sequences 94 against 87,
+// even from 8 on; one sequence with 4 query heads per K/V head 43 us against 31 us).
+constexpr int SHARED_MIN_ROWS = 8;
+bool step_is_shared(const sq_shape_t *sh, int G = 1) { return sh->B * G >= SHARED_MIN_ROWS; }
 
 // Workspace of the two-level lookup.  C1 <= C2 is not known to sq_workspace_bytes, so level-1 buffers
 // are sized for C2.
@@ -412,11 +417,6 @@ int sq_sparse_attn_decode(const sq_shape_t *sh, const void *q, const void *K_fix
 }
 
 namespace {
-// With at least this many (sequence, query head) pairs per K/V head the grouped-query step streams the union of
-// their selections (shared-context kernels); with fewer, the overlap of the selections saves less than the union
-// kernels cost and the per-row kernels run (measured at B = 1, G = 4, 32K context: 43 us against 32 us per token).
-constexpr int GQA_SHARED_MIN = 8;
-
 // Decode step over K/V shared by several query rows: B sequences over one fixed context, times G query heads per
 // K/V head.  Every (sequence, query head) selects on its own; the work items are built from the union of the
 // selections of each group of 16 of them, so a cluster kept by several is streamed once.
@@ -465,7 +465,7 @@ int sq_gqa_decode_step(const sq_shape_t *sh, int32_t G, const void *q, const voi
     if (int rc = check_device(__func__)) return rc;
     Carver cv(ws);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (sh->B * G >= GQA_SHARED_MIN) {
+    if (step_is_shared(sh, G)) {
         if (int rc = decode_step_shared(sh, G, q, centroids, sizes, offsets, thresh, K_fixed, V_fixed, K_user, V_user, out,
                                         lse, keep_mask, n_keys, cv, s))
             return rc;

@@ -190,12 +190,14 @@ def step_against_oracle(sq, oracle, w, label, keep_mask=True):
 
 
 @pytest.mark.parametrize("case", [
-    dict(B=2, H=2, L=900, C=30, U=5, keep_frac=0.3),               # smallest batch that takes the shared-context kernels
-    dict(B=5, H=3, L=3000, C=100, U=300, keep_frac=0.5),           # partial group; user chunks with a ragged tail
+    dict(B=8, H=2, L=900, C=30, U=5, keep_frac=0.3),               # smallest batch that takes the shared-context kernels
+    dict(B=11, H=3, L=3000, C=100, U=300, keep_frac=0.5),          # partial group; user chunks with a ragged tail
     dict(B=16, H=2, L=2000, C=50, U=0, keep_frac=0.2),             # one full group, no user keys
     dict(B=33, H=1, L=1500, C=65, U=40, keep_frac=0.25),           # three groups, the last with one sequence
-    dict(B=3, H=2, L=4096, C=2048, U=17, keep_frac=0.2),           # more clusters than one selection step holds
-    dict(B=4, H=1, L=70000, C=300, U=130, keep_frac=0.6),          # several workgroups per union row, long clusters
+    dict(B=9, H=2, L=4096, C=2048, U=17, keep_frac=0.2),           # more clusters than one selection step holds
+    dict(B=8, H=1, L=70000, C=300, U=130, keep_frac=0.6),          # several workgroups per union row, long clusters
+    dict(B=2, H=2, L=900, C=30, U=5, keep_frac=0.3),               # below the shared-context threshold: per-row kernels
+    dict(B=7, H=2, L=2500, C=80, U=140, keep_frac=0.4),            # the largest batch on the per-row kernels
 ])
 def test_shared_context_step_against_oracle(sq, oracle, case):
     w = wl.calibrate(wl.make_workload("shared", Lq=1, seed=11, threads=4, **case), oracle.scores)
@@ -203,7 +205,7 @@ def test_shared_context_step_against_oracle(sq, oracle, case):
 
 
 def test_shared_context_step_extremes(sq, oracle):
-    base = dict(B=6, H=2, L=1024, C=32, Lq=1, U=33, keep_frac=0.5, seed=12, threads=2)
+    base = dict(B=10, H=2, L=1024, C=32, Lq=1, U=33, keep_frac=0.5, seed=12, threads=2)
     # every sequence keeps everything: each key is owned by all sequences of the group
     w = wl.make_workload("shared_all", **base)
     w.thresh = np.full(w.H, -1.0, np.float32)
