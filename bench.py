@@ -8,7 +8,9 @@ HBM.  Steps rotate through `--queries` different query tokens (the paper times 1
 tokens per measurement, Appendix "Kernel Benchmarking") and through `--replicas` device copies of
 the fixed context, so that the bytes of a step cannot be served from the 256 MB last-level cache.
 
-Prints ONE JSON line (see the field notes in the design doc).
+Prints ONE JSON line: `value` = algorithmic bytes of the whole step / time per step; `roofline` = the dominant
+kernel (bytes it has to read / its event-timed duration, against the published 8 TB/s); `cpu_baseline` = the CPU
+oracle timed on this host on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
