@@ -140,6 +140,33 @@ def hier_select(q, centroids1, sizes1, child_offsets, thresh1, centroids2, sizes
     return out
 
 
+def multilevel_select(q, levels, sm_scale):
+    """Lookup through n >= 1 levels of centroids, coarsest first (Section 3.3, level after level).
+
+    q [B,H,d] f16; levels = list of dicts(centroids [H,C,d] f16, sizes [H,C] i32, child_offsets [H,C+1] i32 --
+    children in the next level, or key offsets at the last level --, thresh [H] f32).
+    -> dict(masks = [keep mask of every level, [B,H,ceil(C/32)] u32], ranges [B,H,C_last,2], n_ranges, n_keys [B,H]).
+    """
+    q = _f16(q)
+    B, H, d = q.shape
+    n = len(levels)
+    cen = [_f16(l["centroids"]) for l in levels]
+    siz = [_i32(l["sizes"]) for l in levels]
+    cof = [_i32(l["child_offsets"]) for l in levels]
+    thr = [_f32(l["thresh"]) for l in levels]
+    Cs = np.array([c.shape[1] for c in cen], np.int32)
+    for k in range(n):
+        assert cen[k].shape == (H, Cs[k], d) and siz[k].shape == (H, Cs[k]) and cof[k].shape == (H, Cs[k] + 1)
+    masks = [np.zeros((B, H, (int(c) + 31) // 32), np.uint32) for c in Cs]
+    ranges = np.zeros((B, H, int(Cs[-1]), 2), np.int32)
+    n_ranges = np.empty((B, H), np.int32)
+    n_keys = np.empty((B, H), np.int32)
+    vp = lambda arrs: (C.c_void_p * n)(*[a.ctypes.data for a in arrs])
+    lib().oracle_multilevel_select(B, H, n, _p(Cs), d, C.c_float(sm_scale), _p(q), vp(cen), vp(siz), vp(cof), vp(thr),
+                                   vp(masks), _p(ranges), _p(n_ranges), _p(n_keys))
+    return dict(masks=masks, ranges=ranges, n_ranges=n_ranges, n_keys=n_keys)
+
+
 def sparse_attn(q, K_fixed, V_fixed, ranges, n_ranges, K_user, V_user, sm_scale, causal_user=False, row_sel=None):
     """q [B,H,Lq,d]; ranges [B,H,Lq,cap,2]; -> out [B,H,Lq,d] f64, lse [B,H,Lq] f64.
 

@@ -79,3 +79,30 @@ def dense_attention(q, K, V, sm_scale):
     p = np.exp(s - M)
     z = p.sum(axis=1, keepdims=True)
     return (p / z) @ V, (M + np.log(z))[:, 0]
+
+
+def multilevel_select(q, levels, sm_scale):
+    """Section 3.3 level after level for ONE query q [d] of one head, any number of levels, coarsest first.
+
+    levels = list of (centroids [C,d], sizes [C], child_offsets [C+1], T).  Returns per level (keep [C] bool,
+    S [C] with NaN outside the level's candidates): at level 0 every cluster is a candidate, below it the children
+    of the clusters kept one level up, and Eq. 3's normaliser runs over the candidates only.
+    """
+    q = np.asarray(q, dtype=np.float64)[None]
+    out = []
+    cand = np.ones(len(levels[0][1]), dtype=bool)
+    for k, (cent, sizes, child_offsets, T) in enumerate(levels):
+        Ck = len(sizes)
+        S = np.full(Ck, np.nan)
+        keep = np.zeros(Ck, dtype=bool)
+        idx = np.flatnonzero(cand)
+        if len(idx):
+            kk, ss = select(q, np.asarray(cent)[idx], np.asarray(sizes)[idx], T, sm_scale)
+            S[idx] = ss[0]
+            keep[idx] = kk[0]
+        out.append((keep, S))
+        if k + 1 < len(levels):
+            cand = np.zeros(len(levels[k + 1][1]), dtype=bool)
+            for j in np.flatnonzero(keep):
+                cand[child_offsets[j]:child_offsets[j + 1]] = True
+    return out

@@ -24,6 +24,8 @@
  *                           centroids, level 2 on the children of the kept
  *                           coarse clusters with the normaliser over those
  *                           children only.
+ *   oracle_multilevel_select  the same, level after level, for any number of
+ *                           levels (Section 3.3 notes the extension).
  *   oracle_sparse_attn      exact softmax attention over the kept fixed-context
  *                           keys together with the user keys (Section 3.2,
  *                           Section 4.2), one softmax over the union.
@@ -293,6 +295,82 @@ void oracle_hier_select(int B, int H, int C1, int C2, int d, float sm_scale,
             free(x1);
             free(x2);
             free(cand);
+        }
+}
+
+/*
+ * Lookup through a hierarchy of n_levels >= 1 levels of centroids, coarsest first (Section 3.3: Eq. 2 and
+ * Eq. 3 applied level after level; the section notes that the two-level scheme extends to more levels).
+ *   level 0: scores on all C[0] clusters, keep S > T[0];
+ *   level k > 0: candidates = children of the clusters kept at level k-1 (child_offsets[k-1][j] ..
+ *   child_offsets[k-1][j+1]-1 for kept j, ascending); scores with the maximum and the normaliser over the
+ *   candidates only; keep S > T[k].
+ * The last level's child_offsets are key offsets: kept cluster l covers keys [off[l], off[l] + sizes[l]).
+ * Per level k: centroids[k] [H, C[k], d] f16, sizes[k] [H, C[k]] (keys under each cluster),
+ * child_offsets[k] [H, C[k]+1], thresh[k] [H].  keep_masks[k] (may be NULL) [B, H, ceil(C[k]/32)].
+ * ranges [B, H, C[n-1], 2], n_ranges, n_keys [B, H].
+ */
+void oracle_multilevel_select(int B, int H, int n_levels, const int32_t *C, int d, float sm_scale,
+                              const uint16_t *q, const uint16_t *const *centroids, const int32_t *const *sizes,
+                              const int32_t *const *child_offsets, const float *const *thresh,
+                              uint32_t *const *keep_masks, int32_t *ranges, int32_t *n_ranges, int32_t *n_keys)
+{
+    int Cmax = 0;
+    for (int k = 0; k < n_levels; ++k)
+        if (C[k] > Cmax)
+            Cmax = C[k];
+    const int Cl = C[n_levels - 1];
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < H; ++h) {
+            size_t r = (size_t)b * H + h;
+            const uint16_t *qv = q + r * d;
+            float *x = (float *)malloc(sizeof(float) * (size_t)Cmax);
+            int32_t *cand = (int32_t *)malloc(sizeof(int32_t) * (size_t)Cmax);
+            int32_t *next = (int32_t *)malloc(sizeof(int32_t) * (size_t)Cmax);
+            int nc = C[0];                       /* level 0: every cluster is a candidate */
+            for (int i = 0; i < nc; ++i)
+                cand[i] = i;
+            int nr = 0, nk = 0;
+            int32_t *rg = ranges + r * (size_t)Cl * 2;
+            for (int k = 0; k < n_levels; ++k) {
+                const int Ck = C[k], Wk = (Ck + 31) / 32;
+                const int32_t *Nk = sizes[k] + (size_t)h * Ck;
+                const int32_t *co = child_offsets[k] + (size_t)h * (Ck + 1);
+                uint32_t *mk = keep_masks && keep_masks[k] ? keep_masks[k] + r * Wk : NULL;
+                if (mk)
+                    memset(mk, 0, sizeof(uint32_t) * Wk);
+                int nn = 0;
+                if (nc > 0) {
+                    float m, D;
+                    score_one(qv, centroids[k] + (size_t)h * Ck * d, Nk, cand, nc, d, sm_scale, x, &m, &D);
+                    for (int i = 0; i < nc; ++i) {
+                        int j = cand[i];
+                        if (!keep_rule(x[i], m, D, thresh[k][h], Nk[j]))
+                            continue;
+                        if (mk)
+                            mk[j >> 5] |= 1u << (j & 31);
+                        if (k + 1 < n_levels) {
+                            for (int l = co[j]; l < co[j + 1]; ++l)
+                                next[nn++] = l;
+                        } else {
+                            rg[2 * nr] = co[j];
+                            rg[2 * nr + 1] = Nk[j];
+                            ++nr;
+                            nk += Nk[j];
+                        }
+                    }
+                }
+                int32_t *t = cand;
+                cand = next;
+                next = t;
+                nc = nn;
+            }
+            n_ranges[r] = nr;
+            n_keys[r] = nk;
+            free(x);
+            free(cand);
+            free(next);
         }
 }
 
