@@ -67,8 +67,8 @@ def test_a_level_that_keeps_everything_drops_out(oracle, seed):
     np.testing.assert_array_equal(a["masks"][2], b["masks"][1])
     np.testing.assert_array_equal(a["ranges"], b["ranges"])
     # levels 0 and 1 keep all: one-level selection on the finest level
-    c = oracle.multilevel_select(q1, with_thresholds(levels, (-1.0, -1.0, 0.03)), 0.3)
-    e = oracle.multilevel_select(q1, with_thresholds(levels[2:], (0.03,)), 0.3)
+    c = oracle.multilevel_select(q1, with_thresholds(levels, (-1.0, -1.0, 0.009)), 0.3)
+    e = oracle.multilevel_select(q1, with_thresholds(levels[2:], (0.009,)), 0.3)
     np.testing.assert_array_equal(c["masks"][2], e["masks"][0])
     np.testing.assert_array_equal(c["n_keys"], e["n_keys"])
     assert a["n_keys"].sum() > 0 and c["n_keys"].sum() > 0
