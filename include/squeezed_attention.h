@@ -57,7 +57,9 @@ typedef enum sq_call {
     SQ_CALL_ATTN_PREFILL_SHARED = 8,
     SQ_CALL_PREFILL_STEP = 9,
     SQ_CALL_PREFILL_MEAN_STEP = 10,
-    SQ_CALL_GQA_DECODE_STEP = 11
+    SQ_CALL_GQA_DECODE_STEP = 11,
+    SQ_CALL_MULTILEVEL_SELECT = 12,
+    SQ_CALL_MULTILEVEL_DECODE_STEP = 13
 } sq_call;
 
 /*
@@ -285,6 +287,45 @@ int sq_hier_decode_step(const sq_shape_t *shape, int32_t C1, const void *q,
                         const void *K_fixed, const void *V_fixed, const void *K_user, const void *V_user,
                         void *out, float *lse, uint32_t *keep_mask2, int32_t *n_keys,
                         void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Centroid lookup through a hierarchy of n_levels levels (1 .. SQ_MAX_LEVELS), coarsest first: Section 3.3's Eq. 2
+ * and Eq. 3 applied level after level (the section notes that the two-level scheme extends to more levels).
+ * Level 0 scores all of its clusters against its threshold; at every further level the candidates are the
+ * children of the clusters kept one level up, and the maximum and the normaliser of the scores run over those
+ * candidates only.  n_levels = 2 is sq_hier_select, n_levels = 1 the one-level selection.
+ * One level: centroids f16 [H, C, d]; sizes i32 [H, C] (keys under each cluster of this level); child_offsets
+ * i32 [H, C+1] -- cluster j's children at the next level are child_offsets[j] .. child_offsets[j+1]-1 (clusters of
+ * a level are stored grouped by parent), and at the LAST level child_offsets are the key offsets of the clusters
+ * (cluster j = keys [child_offsets[j], child_offsets[j] + sizes[j])); thresh f32 [H].  All device pointers; the
+ * `levels` array itself is host memory read during the call.  C must not exceed shape->C, and the last level's C
+ * must equal shape->C.
+ * Out: keep_masks (host array of n_levels device pointers, or NULL; entries may be NULL): level k's mask
+ *      u32 [B,H,ceil(C_k/32)]; ranges i32 [B,H,1,C,2] (may be NULL), n_ranges, n_keys i32 [B,H,1] of the last level.
+ * Workspace: sq_workspace_bytes(shape, SQ_CALL_MULTILEVEL_SELECT).  Lq must be 1.
+ */
+#define SQ_MAX_LEVELS 4
+typedef struct sq_level_t {
+    int32_t C;
+    const void *centroids;
+    const int32_t *sizes;
+    const int32_t *child_offsets;
+    const float *thresh;
+} sq_level_t;
+
+int sq_multilevel_select(const sq_shape_t *shape, int32_t n_levels, const sq_level_t *levels, const void *q,
+                         uint32_t *const *keep_masks, int32_t *ranges, int32_t *n_ranges, int32_t *n_keys,
+                         void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * One whole decode step with the lookup of sq_multilevel_select followed by sq_sparse_attn_decode on its ranges,
+ * intermediates kept in the workspace.  keep_mask (last level) and n_keys are optional outputs (NULL to skip).
+ * Workspace: sq_workspace_bytes(shape, SQ_CALL_MULTILEVEL_DECODE_STEP).
+ */
+int sq_multilevel_decode_step(const sq_shape_t *shape, int32_t n_levels, const sq_level_t *levels, const void *q,
+                              const void *K_fixed, const void *V_fixed, const void *K_user, const void *V_user,
+                              void *out, float *lse, uint32_t *keep_mask, int32_t *n_keys,
+                              void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Measurement hook for benchmarks (not part of the method; for callers that want a kernel's duration

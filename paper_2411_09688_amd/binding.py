@@ -20,18 +20,26 @@ LIB_PATH = os.environ.get("SQ_LIB_PATH") or os.path.join(_PKG, "libsqueezed_atte
 SQ_OK, SQ_ERR_INVALID_ARG, SQ_ERR_UNSUPPORTED, SQ_ERR_WORKSPACE, SQ_ERR_HIP = 0, -1, -2, -3, -4
 (SQ_CALL_CENTROID_SCORE, SQ_CALL_SELECT, SQ_CALL_ATTN_DECODE, SQ_CALL_ATTN_PREFILL, SQ_CALL_HIER_SELECT,
  SQ_CALL_DECODE_STEP, SQ_CALL_HIER_DECODE_STEP, SQ_CALL_SELECT_MEAN, SQ_CALL_ATTN_PREFILL_SHARED,
- SQ_CALL_PREFILL_STEP, SQ_CALL_PREFILL_MEAN_STEP, SQ_CALL_GQA_DECODE_STEP) = range(12)
+ SQ_CALL_PREFILL_STEP, SQ_CALL_PREFILL_MEAN_STEP, SQ_CALL_GQA_DECODE_STEP, SQ_CALL_MULTILEVEL_SELECT,
+ SQ_CALL_MULTILEVEL_DECODE_STEP) = range(14)
+SQ_MAX_LEVELS = 4
 
 EXPORTS = ("sq_workspace_bytes", "sq_last_error", "sq_version", "sq_centroid_score", "sq_select",
            "sq_sparse_attn_decode", "sq_sparse_attn_prefill", "sq_hier_select", "sq_decode_step",
            "sq_hier_decode_step", "sq_select_mean", "sq_sparse_attn_prefill_shared", "sq_prefill_step",
-           "sq_prefill_mean_step", "sq_gqa_decode_step", "sq_profile_begin",
+           "sq_prefill_mean_step", "sq_gqa_decode_step", "sq_multilevel_select", "sq_multilevel_decode_step",
+           "sq_profile_begin",
            "sq_profile_end", "sq_probe_stream_read")
 
 
 class SqShape(C.Structure):
     _fields_ = [("B", C.c_int32), ("H", C.c_int32), ("d", C.c_int32), ("L", C.c_int32), ("C", C.c_int32),
                 ("Lq", C.c_int32), ("U", C.c_int32), ("sm_scale", C.c_float), ("causal_user", C.c_int32)]
+
+
+class SqLevel(C.Structure):
+    _fields_ = [("C", C.c_int32), ("centroids", C.c_void_p), ("sizes", C.c_void_p), ("child_offsets", C.c_void_p),
+                ("thresh", C.c_void_p)]
 
 
 class SqError(RuntimeError):
@@ -65,6 +73,9 @@ def lib() -> C.CDLL:
         L.sq_decode_step.argtypes = [sp] + [vp] * 13 + [vp, sz, vp]
         L.sq_hier_decode_step.argtypes = [sp, C.c_int32] + [vp] * 17 + [vp, sz, vp]
         L.sq_gqa_decode_step.argtypes = [sp, C.c_int32] + [vp] * 13 + [vp, sz, vp]
+        lp = C.POINTER(SqLevel)
+        L.sq_multilevel_select.argtypes = [sp, C.c_int32, lp, vp, C.POINTER(vp)] + [vp] * 3 + [vp, sz, vp]
+        L.sq_multilevel_decode_step.argtypes = [sp, C.c_int32, lp] + [vp] * 9 + [vp, sz, vp]
         L.sq_probe_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_int, C.c_void_p]
         L.sq_profile_begin.argtypes = [C.c_int]
         L.sq_profile_end.argtypes = [C.POINTER(C.c_float)] * 3
@@ -230,6 +241,37 @@ def sq_gqa_decode_step(shape, G, q, centroids, sizes, offsets, thresh, K_fixed, 
                                     _ptr(V_user, F16, "V_user"), _ptr(out, F16, "out"), _ptr(lse, F32, "lse"),
                                     _ptr(keep_mask, I32, "keep_mask"), _ptr(n_keys, I32, "n_keys"), *_ws_args(ws),
                                     _stream(stream)))
+
+
+def _levels(levels):
+    """levels: list of (centroids f16 [H,C,d], sizes i32 [H,C], child_offsets i32 [H,C+1], thresh f32 [H]) tensors."""
+    arr = (SqLevel * len(levels))()
+    for k, (cen, siz, cof, thr) in enumerate(levels):
+        arr[k] = SqLevel(int(cen.shape[1]), _ptr(cen, F16, "centroids"), _ptr(siz, I32, "sizes"),
+                         _ptr(cof, I32, "child_offsets"), _ptr(thr, F32, "thresh"))
+    return arr
+
+
+def sq_multilevel_select(shape, levels, q, keep_masks, ranges, n_ranges, n_keys, ws, stream=None):
+    """keep_masks: None, or a list (one entry per level) of int32 tensors / None."""
+    arr = _levels(levels)
+    masks = None
+    if keep_masks is not None:
+        masks = (C.c_void_p * len(levels))(*[_ptr(m, I32, "keep_mask") for m in keep_masks])
+    _check(lib().sq_multilevel_select(C.byref(shape), len(levels), arr, _ptr(q, F16, "q"), masks,
+                                      _ptr(ranges, I32, "ranges"), _ptr(n_ranges, I32, "n_ranges"),
+                                      _ptr(n_keys, I32, "n_keys"), *_ws_args(ws), _stream(stream)))
+
+
+def sq_multilevel_decode_step(shape, levels, q, K_fixed, V_fixed, K_user, V_user, out, lse, keep_mask, n_keys, ws,
+                              stream=None):
+    arr = _levels(levels)
+    _check(lib().sq_multilevel_decode_step(C.byref(shape), len(levels), arr, _ptr(q, F16, "q"),
+                                           _ptr(K_fixed, F16, "K_fixed"), _ptr(V_fixed, F16, "V_fixed"),
+                                           _ptr(K_user, F16, "K_user"), _ptr(V_user, F16, "V_user"),
+                                           _ptr(out, F16, "out"), _ptr(lse, F32, "lse"),
+                                           _ptr(keep_mask, I32, "keep_mask"), _ptr(n_keys, I32, "n_keys"),
+                                           *_ws_args(ws), _stream(stream)))
 
 
 def sq_hier_decode_step(shape, C1, q, centroids1, sizes1, child_offsets, thresh1, centroids2, sizes2, offsets2,

@@ -205,6 +205,23 @@ HierWs carve_hier(Carver &cv, const sq_shape_t *sh)
     return w;
 }
 
+// Second candidate work list, for lookups of more than two levels.
+sq::DecodePlan carve_cand_plan(Carver &cv, const sq_shape_t *sh)
+{
+    const size_t rows = (size_t)sh->B * sh->H;
+    const size_t items = rows * sq::chunk_cap_for(sh->C);
+    sq::DecodePlan p{};
+    p.rec_cap = sh->C;
+    p.L = sh->C;
+    p.item_cap = (int)items;
+    p.rec = cv.take<int4>(rows * sh->C);
+    p.hdr = cv.take<int2>(rows);
+    p.row_items = cv.take<int2>(rows);
+    p.total = cv.take<int>(2);
+    p.item = cv.take<int2>(items * sq::ITEM_STRIDE);
+    return p;
+}
+
 struct HierStepWs {
     HierWs hier;
     uint32_t *mask1;
@@ -331,6 +348,14 @@ size_t sq_workspace_bytes(const sq_shape_t *sh, int which)
         carve_step(cv2, sh, sq::SG);
         return cv.off > cv2.off ? cv.off : cv2.off;
     }
+    case SQ_CALL_MULTILEVEL_SELECT:
+        carve_hier(cv, sh);
+        carve_cand_plan(cv, sh);
+        return cv.off;
+    case SQ_CALL_MULTILEVEL_DECODE_STEP:
+        carve_hier_step(cv, sh);
+        carve_cand_plan(cv, sh);
+        return cv.off;
     case SQ_CALL_PREFILL_MEAN_STEP:
         carve_prefill_mean_step(cv, sh);
         return cv.off;
@@ -689,36 +714,102 @@ namespace {
 
 // Both levels of the lookup (Section 3.3).  plan2 (may be empty) receives the level-2 records and, when
 // `schedule2`, the attention work items.
+// One level of a centroid hierarchy as the lookup sees it (mask: optional output of the level).
+struct Level {
+    int C;
+    const void *centroids;
+    const int32_t *sizes, *child_offsets;
+    const float *thresh;
+    uint32_t *mask;
+};
+
+// Lookup through n >= 1 levels, coarsest first (Section 3.3, Eq. 2 then Eq. 3 level after level).  Level 0 scores
+// all of its clusters; a kept cluster's child range becomes chunks of candidate clusters of the next level (a
+// balanced number of centroids per workgroup, Appendix D); every further level scores its candidates only
+// (logits in candidate order) and selects over that list, so its maximum and normaliser run over the candidates
+// only.  The candidate work lists of consecutive levels alternate between w.cand and cand_b (a level reads one
+// while it fills the other).  The last level writes ranges / counts and, when `schedule_last`, the attention
+// work items into plan_last.
+int multilevel_lookup(const char *fn, const sq_shape_t *sh, int n, const Level *lv, const void *q, int32_t *ranges,
+                      int32_t *n_ranges, int32_t *n_keys, HierWs &w, sq::DecodePlan cand_b, sq::DecodePlan plan_last,
+                      bool schedule_last, hipStream_t s)
+{
+    const int rows = sh->B * sh->H;
+    hipError_t e;
+    if (n == 1) {
+        e = sq::launch_score(q, lv[0].centroids, w.logits1, plan_last.total, sh->B, sh->H, 1, lv[0].C, sh->sm_scale, s);
+        if (e == hipSuccess)
+            e = sq::launch_select(w.logits1, nullptr, nullptr, false, lv[0].thresh, lv[0].sizes, lv[0].child_offsets,
+                                  lv[0].mask, ranges, n_ranges, n_keys, plan_last, schedule_last, sh->U, sq::SelectOpts{},
+                                  rows, sh->H, 1, lv[0].C, s);
+        if (e != hipSuccess) return fail(SQ_ERR_HIP, "%s: launch failed -> %s", fn, hipGetErrorString(e));
+        return SQ_OK;
+    }
+    sq::DecodePlan cur = w.cand, nxt = cand_b;
+    e = sq::launch_score(q, lv[0].centroids, w.logits1, cur.total, sh->B, sh->H, 1, lv[0].C, sh->sm_scale, s);
+    if (e == hipSuccess) {
+        sq::SelectOpts o{};
+        o.len_from_offsets = 1;
+        cur.rec_cap = lv[0].C;
+        e = sq::launch_select(w.logits1, nullptr, nullptr, false, lv[0].thresh, lv[0].sizes, lv[0].child_offsets,
+                              lv[0].mask, nullptr, w.nr1, w.nk1, cur, true, 0, o, rows, sh->H, 1, lv[0].C, s);
+    }
+    for (int k = 1; k < n && e == hipSuccess; ++k) {
+        const bool last = k == n - 1;
+        sq::DecodePlan dst = last ? plan_last : nxt;
+        e = sq::launch_gather_score(q, lv[k].centroids, cur, w.logits2, w.cand_id, dst.total, sh->H, lv[k].C,
+                                    sh->sm_scale, s);
+        if (e != hipSuccess) break;
+        sq::SelectOpts o{};
+        o.cand_id = w.cand_id;
+        o.cand_hdr = cur.hdr;
+        if (last) {
+            e = sq::launch_select(w.logits2, nullptr, nullptr, false, lv[k].thresh, lv[k].sizes, lv[k].child_offsets,
+                                  lv[k].mask, ranges, n_ranges, n_keys, plan_last, schedule_last, sh->U, o, rows, sh->H, 1,
+                                  lv[k].C, s);
+        } else {
+            o.len_from_offsets = 1;
+            dst.rec_cap = lv[k].C;
+            e = sq::launch_select(w.logits2, nullptr, nullptr, false, lv[k].thresh, lv[k].sizes, lv[k].child_offsets,
+                                  lv[k].mask, nullptr, w.nr1, w.nk1, dst, true, 0, o, rows, sh->H, 1, lv[k].C, s);
+            nxt = cur;
+            cur = dst;
+        }
+    }
+    if (e != hipSuccess) return fail(SQ_ERR_HIP, "%s: launch failed -> %s", fn, hipGetErrorString(e));
+    return SQ_OK;
+}
+
 int hier_lookup(const char *fn, const sq_shape_t *sh, int32_t C1, const void *q, const void *centroids1,
                 const int32_t *sizes1, const int32_t *child_offsets, const float *thresh1, const void *centroids2,
                 const int32_t *sizes2, const int32_t *offsets2, const float *thresh2, uint32_t *keep_mask1,
                 uint32_t *keep_mask2, int32_t *ranges, int32_t *n_ranges, int32_t *n_keys, HierWs &w,
                 sq::DecodePlan plan2, bool schedule2, hipStream_t s)
 {
-    const int rows = sh->B * sh->H;
-    // Level 1 (Eq. 2): scores on the coarse centroids, threshold T1; the kept clusters' child ranges
-    // become chunks of candidate fine clusters.
-    hipError_t e = sq::launch_score(q, centroids1, w.logits1, w.cand.total, sh->B, sh->H, 1, C1, sh->sm_scale, s);
-    if (e == hipSuccess) {
-        sq::SelectOpts o1{};
-        o1.len_from_offsets = 1;
-        sq::DecodePlan cand = w.cand;
-        cand.rec_cap = C1;
-        e = sq::launch_select(w.logits1, nullptr, nullptr, false, thresh1, sizes1, child_offsets, keep_mask1, nullptr,
-                              w.nr1, w.nk1, cand, true, 0, o1, rows, sh->H, 1, C1, s);
-        // Level 2 (Eq. 3): scores of the candidates only; maximum and normaliser over the candidates only.
-        if (e == hipSuccess)
-            e = sq::launch_gather_score(q, centroids2, cand, w.logits2, w.cand_id, plan2.total, sh->H, sh->C,
-                                        sh->sm_scale, s);
+    const Level lv[2] = {{C1, centroids1, sizes1, child_offsets, thresh1, keep_mask1},
+                         {sh->C, centroids2, sizes2, offsets2, thresh2, keep_mask2}};
+    return multilevel_lookup(fn, sh, 2, lv, q, ranges, n_ranges, n_keys, w, sq::DecodePlan{}, plan2, schedule2, s);
+}
+
+// Validates a caller's level array and copies it (masks: optional host array of per-level outputs).
+int read_levels(const char *fn, const sq_shape_t *sh, int32_t n, const sq_level_t *levels, uint32_t *const *masks,
+                Level *lv)
+{
+    if (n < 1 || n > SQ_MAX_LEVELS) return fail(SQ_ERR_INVALID_ARG, "%s: n_levels = %d must be in [1, %d]", fn, n, SQ_MAX_LEVELS);
+    if (!levels) return fail(SQ_ERR_INVALID_ARG, "%s: levels is NULL", fn);
+    for (int k = 0; k < n; ++k) {
+        const sq_level_t &l = levels[k];
+        if (l.C <= 0 || l.C > sh->C)
+            return fail(SQ_ERR_INVALID_ARG, "%s: levels[%d].C = %d must be in [1, shape->C = %d]", fn, k, l.C, sh->C);
+        const void *ptrs[4] = {l.centroids, l.sizes, l.child_offsets, l.thresh};
+        for (const void *p : ptrs)
+            if (!p || !aligned16(p)) return fail(SQ_ERR_INVALID_ARG, "%s: a pointer of levels[%d] is NULL or not 16-byte aligned", fn, k);
+        uint32_t *m = masks ? masks[k] : nullptr;
+        if (m && !aligned16(m)) return fail(SQ_ERR_INVALID_ARG, "%s: keep_masks[%d] is not 16-byte aligned", fn, k);
+        lv[k] = Level{l.C, l.centroids, l.sizes, l.child_offsets, l.thresh, m};
     }
-    if (e == hipSuccess) {
-        sq::SelectOpts o2{};
-        o2.cand_id = w.cand_id;
-        o2.cand_hdr = w.cand.hdr;
-        e = sq::launch_select(w.logits2, nullptr, nullptr, false, thresh2, sizes2, offsets2, keep_mask2, ranges,
-                              n_ranges, n_keys, plan2, schedule2, sh->U, o2, rows, sh->H, 1, sh->C, s);
-    }
-    if (e != hipSuccess) return fail(SQ_ERR_HIP, "%s: launch failed -> %s", fn, hipGetErrorString(e));
+    if (levels[n - 1].C != sh->C)
+        return fail(SQ_ERR_INVALID_ARG, "%s: the last level has %d clusters, shape->C is %d", fn, levels[n - 1].C, sh->C);
     return SQ_OK;
 }
 
@@ -798,6 +889,64 @@ int sq_hier_decode_step(const sq_shape_t *sh, int32_t C1, const void *q, const v
     if (int rc = hier_lookup(__func__, sh, C1, q, centroids1, sizes1, child_offsets, thresh1, centroids2, sizes2,
                              offsets2, thresh2, w.mask1, keep_mask2, nullptr, w.n_ranges, n_keys ? n_keys : w.n_keys,
                              w.hier, w.dec.plan, true, s))
+        return rc;
+    SQ_HIP(sq::launch_decode_attn(q, K_fixed, V_fixed, K_user, V_user, w.dec.plan, w.dec.partials, out, lse,
+                                  to_shape(sh), s));
+    g_err[0] = 0;
+    return SQ_OK;
+}
+
+int sq_multilevel_select(const sq_shape_t *sh, int32_t n_levels, const sq_level_t *levels, const void *q,
+                         uint32_t *const *keep_masks, int32_t *ranges, int32_t *n_ranges, int32_t *n_keys, void *ws,
+                         size_t ws_bytes, void *stream)
+{
+    if (int rc = check_shape(sh, __func__, true)) return rc;
+    Level lv[SQ_MAX_LEVELS];
+    if (int rc = read_levels(__func__, sh, n_levels, levels, keep_masks, lv)) return rc;
+    SQ_REQUIRE_PTR(q);
+    SQ_OPTIONAL_PTR(ranges);
+    SQ_REQUIRE_PTR(n_ranges);
+    SQ_REQUIRE_PTR(n_keys);
+    if (int rc = check_ws(__func__, sh, SQ_CALL_MULTILEVEL_SELECT, ws, ws_bytes)) return rc;
+    if (int rc = check_device(__func__)) return rc;
+    Carver cv(ws);
+    HierWs w = carve_hier(cv, sh);
+    sq::DecodePlan cand_b = carve_cand_plan(cv, sh);
+    if (int rc = multilevel_lookup(__func__, sh, n_levels, lv, q, ranges, n_ranges, n_keys, w, cand_b, sq::DecodePlan{},
+                                   false, static_cast<hipStream_t>(stream)))
+        return rc;
+    g_err[0] = 0;
+    return SQ_OK;
+}
+
+int sq_multilevel_decode_step(const sq_shape_t *sh, int32_t n_levels, const sq_level_t *levels, const void *q,
+                              const void *K_fixed, const void *V_fixed, const void *K_user, const void *V_user,
+                              void *out, float *lse, uint32_t *keep_mask, int32_t *n_keys, void *ws, size_t ws_bytes,
+                              void *stream)
+{
+    if (int rc = check_shape(sh, __func__, true)) return rc;
+    Level lv[SQ_MAX_LEVELS];
+    if (int rc = read_levels(__func__, sh, n_levels, levels, nullptr, lv)) return rc;
+    SQ_REQUIRE_PTR(q);
+    SQ_REQUIRE_PTR(K_fixed);
+    SQ_REQUIRE_PTR(V_fixed);
+    if (sh->U > 0) {
+        SQ_REQUIRE_PTR(K_user);
+        SQ_REQUIRE_PTR(V_user);
+    }
+    SQ_REQUIRE_PTR(out);
+    SQ_OPTIONAL_PTR(lse);
+    SQ_OPTIONAL_PTR(keep_mask);
+    SQ_OPTIONAL_PTR(n_keys);
+    if (int rc = check_ws(__func__, sh, SQ_CALL_MULTILEVEL_DECODE_STEP, ws, ws_bytes)) return rc;
+    if (int rc = check_device(__func__)) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Carver cv(ws);
+    HierStepWs w = carve_hier_step(cv, sh);
+    sq::DecodePlan cand_b = carve_cand_plan(cv, sh);
+    lv[n_levels - 1].mask = keep_mask;
+    if (int rc = multilevel_lookup(__func__, sh, n_levels, lv, q, nullptr, w.n_ranges, n_keys ? n_keys : w.n_keys, w.hier,
+                                   cand_b, w.dec.plan, true, s))
         return rc;
     SQ_HIP(sq::launch_decode_attn(q, K_fixed, V_fixed, K_user, V_user, w.dec.plan, w.dec.partials, out, lse,
                                   to_shape(sh), s));
