@@ -330,12 +330,14 @@ int sq_multilevel_decode_step(const sq_shape_t *shape, int32_t n_levels, const s
 /*
  * Measurement hook for benchmarks (not part of the method; for callers that want a kernel's duration
  * without an external profiler).  Between sq_profile_begin(n) and sq_profile_end(), every launch of
- * the split-KV partial-attention kernel -- the kernel that reads the selected K/V rows, i.e. nearly
- * all bytes of a decode step (Section 4.2, phase 1) -- is bracketed by a pair of HIP events recorded on
- * the stream it is launched on, up to n launches.  sq_profile_end() waits for those events, writes the
+ * the dominant kernel of a step -- the split-KV partial-attention kernel, which reads the selected K/V rows,
+ * i.e. nearly all bytes of a decode step (Section 4.2, phase 1); the attention kernel of a prefill step --
+ * carries a pair of HIP events attached to its dispatch on the stream it is launched on (start and end of the
+ * kernel itself), up to n launches.  sq_profile_end() waits for those events, writes the
  * average / minimum / maximum elapsed time per launch in microseconds (any pointer may be NULL),
  * returns the number of launches measured (or a negative sq_status), and releases the events.
- * Host only; process-wide state, not thread-safe; creates HIP events (no device memory).
+ * Host only; process-wide state, not thread-safe; creates HIP events (no device memory).  Not to be used while
+ * the stream is being captured into a graph.
  */
 int sq_profile_begin(int max_launches);
 int sq_profile_end(float *avg_us, float *min_us, float *max_us);

@@ -235,11 +235,15 @@ hipError_t launch_decode_attn(const void *q, const void *Kf, const void *Vf, con
     static const int grid_env = getenv("SQ_ATTN_GRID") ? atoi(getenv("SQ_ATTN_GRID")) : 0;   // tuning knob
     const int want = grid_env > 0 ? grid_env : ATTN_GRID;
     const int grid = plan.item_cap < want ? plan.item_cap : want;
-    const bool prof = profile_mark(s, true);
-    hipLaunchKernelGGL(decode_attn_kernel, dim3(grid), dim3(256), 0, s, (const _Float16 *)q, (const _Float16 *)Kf,
-                       (const _Float16 *)Vf, (const _Float16 *)Ku, (const _Float16 *)Vu, plan, partials, sh.H, G, sh.L,
-                       sh.U, sh.sm_scale);
-    if (prof) profile_mark(s, false);
+    hipEvent_t ev0, ev1;
+    if (profile_pair(&ev0, &ev1))
+        hipExtLaunchKernelGGL(decode_attn_kernel, dim3(grid), dim3(256), 0, s, ev0, ev1, 0, (const _Float16 *)q,
+                              (const _Float16 *)Kf, (const _Float16 *)Vf, (const _Float16 *)Ku, (const _Float16 *)Vu, plan,
+                              partials, sh.H, G, sh.L, sh.U, sh.sm_scale);
+    else
+        hipLaunchKernelGGL(decode_attn_kernel, dim3(grid), dim3(256), 0, s, (const _Float16 *)q, (const _Float16 *)Kf,
+                           (const _Float16 *)Vf, (const _Float16 *)Ku, (const _Float16 *)Vu, plan, partials, sh.H, G,
+                           sh.L, sh.U, sh.sm_scale);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(decode_merge_kernel, dim3(rows), dim3(MERGE_THREADS), 0, s, partials, plan, (_Float16 *)out, lse,

@@ -324,11 +324,15 @@ hipError_t launch_decode_attn_shared(const void *q, const void *Kf, const void *
 {
     const int G = sh.Lq;                             // query rows per (sequence, head): 1, or the GQA group size
     const int rows = sh.B * sh.H * G;
-    const bool prof = profile_mark(s, true);
-    hipLaunchKernelGGL(decode_attn_shared_kernel, dim3(SHARED_ATTN_GRID), dim3(256), 0, s, (const _Float16 *)q,
-                       (const _Float16 *)Kf, (const _Float16 *)Vf, (const _Float16 *)Ku, (const _Float16 *)Vu, plan,
-                       partials, sh.B * G, G, sh.H, sh.L, sh.U, sh.sm_scale);
-    if (prof) profile_mark(s, false);
+    hipEvent_t ev0, ev1;
+    if (profile_pair(&ev0, &ev1))
+        hipExtLaunchKernelGGL(decode_attn_shared_kernel, dim3(SHARED_ATTN_GRID), dim3(256), 0, s, ev0, ev1, 0,
+                              (const _Float16 *)q, (const _Float16 *)Kf, (const _Float16 *)Vf, (const _Float16 *)Ku,
+                              (const _Float16 *)Vu, plan, partials, sh.B * G, G, sh.H, sh.L, sh.U, sh.sm_scale);
+    else
+        hipLaunchKernelGGL(decode_attn_shared_kernel, dim3(SHARED_ATTN_GRID), dim3(256), 0, s, (const _Float16 *)q,
+                           (const _Float16 *)Kf, (const _Float16 *)Vf, (const _Float16 *)Ku, (const _Float16 *)Vu, plan,
+                           partials, sh.B * G, G, sh.H, sh.L, sh.U, sh.sm_scale);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(decode_merge_shared_kernel, dim3(rows), dim3(MERGE_THREADS), 0, s, partials, plan,

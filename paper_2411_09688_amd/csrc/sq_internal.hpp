@@ -1,5 +1,6 @@
 // Host-side launcher declarations shared between the kernel files and the C-ABI file.
 #pragma once
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -138,7 +139,9 @@ hipError_t launch_prefill_attn_shared(const void *q, const void *Kf, const void 
                                       DecodePlan plan, int32_t *key_idx, void *out, float *lse, const Shape &sh,
                                       hipStream_t s);
 
-// Measurement hook (sq_profile.hip): records an event before / after the partial kernel when enabled.
-bool profile_mark(hipStream_t s, bool begin);
+// Measurement hook (sq_profile.hip): when enabled, hands out the next pair of events; the caller attaches them to
+// the dominant kernel's dispatch (hipExtLaunchKernelGGL), so they carry the start and end time of that kernel
+// itself rather than of marker packets around it.
+bool profile_pair(hipEvent_t *start, hipEvent_t *stop);
 
 }  // namespace sq

@@ -466,12 +466,17 @@ hipError_t launch_prefill_kernel(const void *q, const void *Kf, const void *Vf, 
     }
     const int units = ((sh.Lq + PF_BM - 1) / PF_BM) * sh.H * sh.B;
     dim3 grid((units + 7) / 8 * 8);
-    const bool prof = profile_mark(s, true);
-    hipLaunchKernelGGL(prefill_attn_kernel<SHARED>, grid, dim3(256), smem, s, (const _Float16 *)q,
-                       (const _Float16 *)Kf, (const _Float16 *)Vf, (const _Float16 *)Ku, (const _Float16 *)Vu, keep_mask,
-                       key_cid, blk_info, (_Float16 *)out, lse, sh.B, sh.H, sh.L, sh.C, sh.Lq, sh.U, sh.causal_user,
-                       sh.sm_scale);
-    if (prof) profile_mark(s, false);
+    hipEvent_t ev0, ev1;
+    if (profile_pair(&ev0, &ev1))
+        hipExtLaunchKernelGGL(prefill_attn_kernel<SHARED>, grid, dim3(256), (uint32_t)smem, s, ev0, ev1, 0,
+                              (const _Float16 *)q, (const _Float16 *)Kf, (const _Float16 *)Vf, (const _Float16 *)Ku,
+                              (const _Float16 *)Vu, keep_mask, key_cid, blk_info, (_Float16 *)out, lse, sh.B, sh.H, sh.L,
+                              sh.C, sh.Lq, sh.U, sh.causal_user, sh.sm_scale);
+    else
+        hipLaunchKernelGGL(prefill_attn_kernel<SHARED>, grid, dim3(256), smem, s, (const _Float16 *)q,
+                           (const _Float16 *)Kf, (const _Float16 *)Vf, (const _Float16 *)Ku, (const _Float16 *)Vu,
+                           keep_mask, key_cid, blk_info, (_Float16 *)out, lse, sh.B, sh.H, sh.L, sh.C, sh.Lq, sh.U,
+                           sh.causal_user, sh.sm_scale);
     return hipGetLastError();
 }
 

@@ -1,6 +1,7 @@
-// Measurement hook: brackets every launch of the split-KV partial kernel (the kernel that moves almost
-// all of the bytes of a decode step) with a pair of HIP events on the launch stream, so a benchmark can
-// read that kernel's duration from inside the process.  Off by default; not thread-safe by design.
+// Measurement hook: every launch of the dominant kernel of a step (the split-KV partial kernel, which moves
+// almost all of the bytes of a decode step; the attention kernel of a prefill step) carries a pair of HIP events
+// attached to its dispatch on the launch stream (start and end time of the kernel), so a benchmark can read that
+// kernel's duration from inside the process.  Off by default; not thread-safe by design.
 #include <vector>
 
 #include "../../include/squeezed_attention.h"
@@ -16,15 +17,11 @@ struct Profiler {
 } g_prof;
 }  // namespace
 
-bool profile_mark(hipStream_t s, bool begin)
+bool profile_pair(hipEvent_t *start, hipEvent_t *stop)
 {
-    if (!g_prof.on) return false;
-    if (begin) {
-        if (g_prof.used + 2 > g_prof.ev.size()) return false;
-        (void)hipEventRecord(g_prof.ev[g_prof.used], s);
-        return true;
-    }
-    (void)hipEventRecord(g_prof.ev[g_prof.used + 1], s);
+    if (!g_prof.on || g_prof.used + 2 > g_prof.ev.size()) return false;
+    *start = g_prof.ev[g_prof.used];
+    *stop = g_prof.ev[g_prof.used + 1];
     g_prof.used += 2;
     return true;
 }
