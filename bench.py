@@ -82,9 +82,35 @@ def cpu_baseline(w_name, seed, budget_s):
         t_total += time.perf_counter() - t0
         nbytes += step_bytes(w, nk)["total"]
         n += 1
-    return dict(value=round(nbytes / t_total / 1e9, 3), unit="GB/s", us_per_token=round(t_total / n * 1e6, 1),
-                cores=oracle.num_threads(), kind="oracle",
-                sample=f"{n} decode steps (different query tokens) of {w_name}, whole path, same byte model")
+    res = dict(value=round(nbytes / t_total / 1e9, 3), unit="GB/s", us_per_token=round(t_total / n * 1e6, 1),
+               cores=oracle.num_threads(), kind="oracle",
+               sample=f"{n} decode steps (different query tokens) of {w_name}, whole path, same byte model")
+    res["selection_quality"] = selection_quality(oracle, w, qs[:4])
+    return res
+
+
+def selection_quality(oracle, w, qs):
+    """Diagnostic (untimed, CPU, fp64): the share of the true attention mass over the fixed context that the kept keys
+    carry, next to what an ideal lookup with the same key budget would carry (the keys with the highest attention
+    scores, found by attending to every key first: the "Ideal" baseline of the paper's appendix)."""
+    got, ideal = [], []
+    for q in qs:
+        qh = np.ascontiguousarray(q[None, :, None, :])
+        x, m, D = oracle.centroid_score(qh, w.centroids, w.sizes, w.sm_scale)
+        mask, ranges, nr, nk = oracle.select(x, m, D, w.thresh, w.sizes, w.offsets)
+        for h in range(w.H):
+            s = np.float64(w.sm_scale) * (w.K_fixed[h].astype(np.float64) @ q[h].astype(np.float64))
+            p = np.exp(s - s.max())
+            p /= p.sum()
+            kept = np.zeros(w.L, bool)
+            for a, c in ranges[0, h, 0, :nr[0, h, 0]]:
+                kept[a:a + c] = True
+            k = int(kept.sum())
+            got.append(p[kept].sum())
+            ideal.append(np.sort(p)[::-1][:k].sum())
+    return dict(attention_mass_kept=round(float(np.mean(got)), 4),
+                attention_mass_ideal_same_budget=round(float(np.mean(ideal)), 4),
+                sample=f"{len(qs)} query tokens x {w.H} heads, fixed-context keys only")
 
 
 def time_steps(step, args, torch, sq):
