@@ -59,7 +59,8 @@ typedef enum sq_call {
     SQ_CALL_PREFILL_MEAN_STEP = 10,
     SQ_CALL_GQA_DECODE_STEP = 11,
     SQ_CALL_MULTILEVEL_SELECT = 12,
-    SQ_CALL_MULTILEVEL_DECODE_STEP = 13
+    SQ_CALL_MULTILEVEL_DECODE_STEP = 13,
+    SQ_CALL_KMEANS_STEP = 14
 } sq_call;
 
 /*
@@ -326,6 +327,43 @@ int sq_multilevel_decode_step(const sq_shape_t *shape, int32_t n_levels, const s
                               const void *K_fixed, const void *V_fixed, const void *K_user, const void *V_user,
                               void *out, float *lse, uint32_t *keep_mask, int32_t *n_keys,
                               void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Offline clustering of the fixed-context keys (Section 3.1: K-means on normalised key vectors; the centroid of a
+ * cluster is the mean of its vectors).  The paper fixes neither initialisation nor iteration count, so the unit
+ * here is one Lloyd iteration; the caller chooses the initial centres (e.g. normalised keys drawn at random) and
+ * how often to iterate.  Every (sequence, head) pair of the shape is clustered on its own; shape->Lq, U and
+ * sm_scale are not used (give Lq = 1, U = 0, sm_scale = 1).
+ *
+ * sq_kmeans_normalize: X[b,h,j,:] = K[b,h,j,:] / |K[b,h,j,:]| (fp32 arithmetic, rounded to f16; a zero row stays
+ *   zero).  K, X f16 [B,H,L,d]; X may alias K.  No workspace.
+ */
+int sq_kmeans_normalize(const sq_shape_t *shape, const void *K, void *X, void *stream);
+
+/*
+ * One Lloyd iteration on the rows of X (f16 [B,H,L,d]) with the centres centers_in (f16 [B,H,C,d]):
+ *   assign  i32 [B,H,L]    nearest centre of each row in squared Euclidean distance, evaluated as
+ *                          argmax_c (x.c - |c|^2/2) with fp32 accumulation; equal scores go to the lowest index
+ *   sizes   i32 [B,H,C]    members per centre;  offsets i32 [B,H,C+1] their exclusive prefix sum (last = L)
+ *   perm    i32 [B,H,L]    row indices grouped by centre, ascending inside a centre (a stable sort by centre id):
+ *                          centre c's members are perm[offsets[c] .. offsets[c] + sizes[c])
+ *   centers_out f16 [B,H,C,d]  mean of each centre's members (fp32 sum, rounded to f16); a centre without members
+ *                          keeps its value.  May alias centers_in.
+ * C <= L required.  Workspace: sq_workspace_bytes(shape, SQ_CALL_KMEANS_STEP).
+ */
+int sq_kmeans_step(const sq_shape_t *shape, const void *X, const void *centers_in, void *centers_out,
+                   int32_t *assign, int32_t *sizes, int32_t *offsets, int32_t *perm,
+                   void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * From a grouping (perm, sizes, offsets as written by sq_kmeans_step) to the inputs of the online calls above:
+ * K_sorted[b,h,i,:] = K[b,h,perm[i],:], likewise V_sorted, so that each cluster's keys are contiguous, and
+ * centroids f16 [B,H,C,d] = mean of the RAW keys of each cluster (Section 3.1; zeros for an empty cluster).
+ * K, V, K_sorted, V_sorted f16 [B,H,L,d]; the outputs must not alias the inputs.  No workspace.
+ */
+int sq_cluster_layout(const sq_shape_t *shape, const void *K, const void *V, const int32_t *perm,
+                      const int32_t *sizes, const int32_t *offsets, void *K_sorted, void *V_sorted,
+                      void *centroids, void *stream);
 
 /*
  * Measurement hook for benchmarks (not part of the method; for callers that want a kernel's duration

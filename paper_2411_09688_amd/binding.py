@@ -21,14 +21,14 @@ SQ_OK, SQ_ERR_INVALID_ARG, SQ_ERR_UNSUPPORTED, SQ_ERR_WORKSPACE, SQ_ERR_HIP = 0,
 (SQ_CALL_CENTROID_SCORE, SQ_CALL_SELECT, SQ_CALL_ATTN_DECODE, SQ_CALL_ATTN_PREFILL, SQ_CALL_HIER_SELECT,
  SQ_CALL_DECODE_STEP, SQ_CALL_HIER_DECODE_STEP, SQ_CALL_SELECT_MEAN, SQ_CALL_ATTN_PREFILL_SHARED,
  SQ_CALL_PREFILL_STEP, SQ_CALL_PREFILL_MEAN_STEP, SQ_CALL_GQA_DECODE_STEP, SQ_CALL_MULTILEVEL_SELECT,
- SQ_CALL_MULTILEVEL_DECODE_STEP) = range(14)
+ SQ_CALL_MULTILEVEL_DECODE_STEP, SQ_CALL_KMEANS_STEP) = range(15)
 SQ_MAX_LEVELS = 4
 
 EXPORTS = ("sq_workspace_bytes", "sq_last_error", "sq_version", "sq_centroid_score", "sq_select",
            "sq_sparse_attn_decode", "sq_sparse_attn_prefill", "sq_hier_select", "sq_decode_step",
            "sq_hier_decode_step", "sq_select_mean", "sq_sparse_attn_prefill_shared", "sq_prefill_step",
            "sq_prefill_mean_step", "sq_gqa_decode_step", "sq_multilevel_select", "sq_multilevel_decode_step",
-           "sq_profile_begin",
+           "sq_kmeans_normalize", "sq_kmeans_step", "sq_cluster_layout", "sq_profile_begin",
            "sq_profile_end", "sq_probe_stream_read")
 
 
@@ -76,6 +76,9 @@ def lib() -> C.CDLL:
         lp = C.POINTER(SqLevel)
         L.sq_multilevel_select.argtypes = [sp, C.c_int32, lp, vp, C.POINTER(vp)] + [vp] * 3 + [vp, sz, vp]
         L.sq_multilevel_decode_step.argtypes = [sp, C.c_int32, lp] + [vp] * 9 + [vp, sz, vp]
+        L.sq_kmeans_normalize.argtypes = [sp, vp, vp, vp]
+        L.sq_kmeans_step.argtypes = [sp] + [vp] * 7 + [vp, sz, vp]
+        L.sq_cluster_layout.argtypes = [sp] + [vp] * 8 + [vp]
         L.sq_probe_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_int, C.c_void_p]
         L.sq_profile_begin.argtypes = [C.c_int]
         L.sq_profile_end.argtypes = [C.POINTER(C.c_float)] * 3
@@ -283,6 +286,24 @@ def sq_hier_decode_step(shape, C1, q, centroids1, sizes1, child_offsets, thresh1
         _ptr(thresh2, F32, "thresh2"), _ptr(K_fixed, F16, "K_fixed"), _ptr(V_fixed, F16, "V_fixed"),
         _ptr(K_user, F16, "K_user"), _ptr(V_user, F16, "V_user"), _ptr(out, F16, "out"), _ptr(lse, F32, "lse"),
         _ptr(keep_mask2, I32, "keep_mask2"), _ptr(n_keys, I32, "n_keys"), *_ws_args(ws), _stream(stream)))
+
+
+def sq_kmeans_normalize(shape, K, X, stream=None):
+    _check(lib().sq_kmeans_normalize(C.byref(shape), _ptr(K, F16, "K"), _ptr(X, F16, "X"), _stream(stream)))
+
+
+def sq_kmeans_step(shape, X, centers_in, centers_out, assign, sizes, offsets, perm, ws, stream=None):
+    _check(lib().sq_kmeans_step(C.byref(shape), _ptr(X, F16, "X"), _ptr(centers_in, F16, "centers_in"),
+                                _ptr(centers_out, F16, "centers_out"), _ptr(assign, I32, "assign"),
+                                _ptr(sizes, I32, "sizes"), _ptr(offsets, I32, "offsets"), _ptr(perm, I32, "perm"),
+                                *_ws_args(ws), _stream(stream)))
+
+
+def sq_cluster_layout(shape, K, V, perm, sizes, offsets, K_sorted, V_sorted, centroids, stream=None):
+    _check(lib().sq_cluster_layout(C.byref(shape), _ptr(K, F16, "K"), _ptr(V, F16, "V"), _ptr(perm, I32, "perm"),
+                                   _ptr(sizes, I32, "sizes"), _ptr(offsets, I32, "offsets"),
+                                   _ptr(K_sorted, F16, "K_sorted"), _ptr(V_sorted, F16, "V_sorted"),
+                                   _ptr(centroids, F16, "centroids"), _stream(stream)))
 
 
 def sq_probe_stream_read(buf: torch.Tensor, sink: torch.Tensor, workgroups: int, nbytes: Optional[int] = None,

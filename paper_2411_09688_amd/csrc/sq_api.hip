@@ -222,6 +222,23 @@ sq::DecodePlan carve_cand_plan(Carver &cv, const sq_shape_t *sh)
     return p;
 }
 
+// Workspace of one K-means iteration: half norms of the centres and the per-part histograms of centre ids.
+struct KmeansWs {
+    float *hn;
+    int32_t *hist;
+};
+
+KmeansWs carve_kmeans(Carver &cv, const sq_shape_t *sh)
+{
+    const size_t heads = (size_t)sh->B * sh->H;
+    const int PL = sq::kmeans_part_len(sh->L);
+    const size_t parts = (size_t)(sh->L + PL - 1) / PL;
+    KmeansWs w{};
+    w.hn = cv.take<float>(heads * sh->C);
+    w.hist = cv.take<int32_t>(heads * parts * sh->C);
+    return w;
+}
+
 struct HierStepWs {
     HierWs hier;
     uint32_t *mask1;
@@ -355,6 +372,9 @@ size_t sq_workspace_bytes(const sq_shape_t *sh, int which)
     case SQ_CALL_MULTILEVEL_DECODE_STEP:
         carve_hier_step(cv, sh);
         carve_cand_plan(cv, sh);
+        return cv.off;
+    case SQ_CALL_KMEANS_STEP:
+        carve_kmeans(cv, sh);
         return cv.off;
     case SQ_CALL_PREFILL_MEAN_STEP:
         carve_prefill_mean_step(cv, sh);
@@ -950,6 +970,60 @@ int sq_multilevel_decode_step(const sq_shape_t *sh, int32_t n_levels, const sq_l
         return rc;
     SQ_HIP(sq::launch_decode_attn(q, K_fixed, V_fixed, K_user, V_user, w.dec.plan, w.dec.partials, out, lse,
                                   to_shape(sh), s));
+    g_err[0] = 0;
+    return SQ_OK;
+}
+
+int sq_kmeans_normalize(const sq_shape_t *sh, const void *K, void *X, void *stream)
+{
+    if (int rc = check_shape(sh, __func__, false)) return rc;
+    SQ_REQUIRE_PTR(K);
+    SQ_REQUIRE_PTR(X);
+    if (int rc = check_device(__func__)) return rc;
+    SQ_HIP(sq::launch_normalize_rows(K, X, (size_t)sh->B * sh->H * sh->L, static_cast<hipStream_t>(stream)));
+    g_err[0] = 0;
+    return SQ_OK;
+}
+
+int sq_kmeans_step(const sq_shape_t *sh, const void *X, const void *centers_in, void *centers_out, int32_t *assign,
+                   int32_t *sizes, int32_t *offsets, int32_t *perm, void *ws, size_t ws_bytes, void *stream)
+{
+    if (int rc = check_shape(sh, __func__, false)) return rc;
+    if (sh->C > sh->L) return fail(SQ_ERR_INVALID_ARG, "%s: more centres (%d) than keys (%d)", __func__, sh->C, sh->L);
+    SQ_REQUIRE_PTR(X);
+    SQ_REQUIRE_PTR(centers_in);
+    SQ_REQUIRE_PTR(centers_out);
+    SQ_REQUIRE_PTR(assign);
+    SQ_REQUIRE_PTR(sizes);
+    SQ_REQUIRE_PTR(offsets);
+    SQ_REQUIRE_PTR(perm);
+    if (int rc = check_ws(__func__, sh, SQ_CALL_KMEANS_STEP, ws, ws_bytes)) return rc;
+    if (int rc = check_device(__func__)) return rc;
+    Carver cv(ws);
+    KmeansWs w = carve_kmeans(cv, sh);
+    SQ_HIP(sq::launch_kmeans_step(X, centers_in, centers_out, assign, sizes, offsets, perm, w.hn, w.hist, sh->B * sh->H,
+                                  sh->L, sh->C, static_cast<hipStream_t>(stream)));
+    g_err[0] = 0;
+    return SQ_OK;
+}
+
+int sq_cluster_layout(const sq_shape_t *sh, const void *K, const void *V, const int32_t *perm, const int32_t *sizes,
+                      const int32_t *offsets, void *K_sorted, void *V_sorted, void *centroids, void *stream)
+{
+    if (int rc = check_shape(sh, __func__, false)) return rc;
+    SQ_REQUIRE_PTR(K);
+    SQ_REQUIRE_PTR(V);
+    SQ_REQUIRE_PTR(perm);
+    SQ_REQUIRE_PTR(sizes);
+    SQ_REQUIRE_PTR(offsets);
+    SQ_REQUIRE_PTR(K_sorted);
+    SQ_REQUIRE_PTR(V_sorted);
+    SQ_REQUIRE_PTR(centroids);
+    if (K_sorted == K || V_sorted == V || K_sorted == V || V_sorted == K)
+        return fail(SQ_ERR_INVALID_ARG, "%s: the reordered tensors must not alias the inputs", __func__);
+    if (int rc = check_device(__func__)) return rc;
+    SQ_HIP(sq::launch_cluster_layout(K, V, perm, sizes, offsets, K_sorted, V_sorted, centroids, sh->B * sh->H, sh->L,
+                                     sh->C, static_cast<hipStream_t>(stream)));
     g_err[0] = 0;
     return SQ_OK;
 }

@@ -139,6 +139,17 @@ hipError_t launch_prefill_attn_shared(const void *q, const void *Kf, const void 
                                       DecodePlan plan, int32_t *key_idx, void *out, float *lse, const Shape &sh,
                                       hipStream_t s);
 
+// Offline clustering (sq_kmeans.hip).  hn: [heads * C] floats; hist: [heads * parts * C] ints with
+// parts = ceil(L / kmeans_part_len(L)).
+int kmeans_part_len(int L);
+hipError_t launch_normalize_rows(const void *K, void *X, size_t rows, hipStream_t s);
+hipError_t launch_kmeans_step(const void *X, const void *centers_in, void *centers_out, int32_t *assign,
+                              int32_t *sizes, int32_t *offsets, int32_t *perm, float *hn, int32_t *hist, int heads,
+                              int L, int C, hipStream_t s);
+hipError_t launch_cluster_layout(const void *K, const void *V, const int32_t *perm, const int32_t *sizes,
+                                 const int32_t *offsets, void *K_sorted, void *V_sorted, void *centroids, int heads,
+                                 int L, int C, hipStream_t s);
+
 // Measurement hook (sq_profile.hip): when enabled, hands out the next pair of events; the caller attaches them to
 // the dominant kernel's dispatch (hipExtLaunchKernelGGL), so they carry the start and end time of that kernel
 // itself rather than of marker packets around it.

@@ -226,6 +226,27 @@ def extra_queries(w: Workload, n: int, tensor: str = "q_bench") -> np.ndarray:
     return out
 
 
+def clustering_input(seed: int, H: int, L: int, C: int, d: int = 128, mix: int = 0, name: str = "kmeans"):
+    """Input of the offline clustering step: UNSORTED keys and values of a fixed context plus a seeding.
+
+    Keys are the mixture of the configs (centre + NOISE * N(0, I), `mix` generating centres, default C) in random
+    token order, as a real context delivers them.  The seeding is the usual "C distinct keys drawn at random":
+    `init` holds their indices, so each side normalises them itself.
+    -> K [H, L, d] f16, V [H, L, d] f16, init [H, C] int32."""
+    mix = mix or C
+    K = np.empty((H, L, d), dtype=F16)
+    V = np.empty((H, L, d), dtype=F16)
+    init = np.empty((H, C), dtype=np.int32)
+    for h in range(H):
+        centres = _normal(_rng(seed, name, "centres", h), (mix, d))
+        r = _rng(seed, name, "K", h)
+        ids = r.integers(0, mix, size=L)
+        K[h] = (centres[ids] + NOISE * _normal(r, (L, d))).astype(F16)
+        V[h] = _normal(_rng(seed, name, "V", h), (L, d)).astype(F16)
+        init[h] = np.sort(_rng(seed, name, "init", h).choice(L, size=C, replace=False)).astype(np.int32)
+    return K, V, init
+
+
 # --------------------------------------------------------------------------------------------
 # Threshold calibration.  `score_fn(q[nq,d] f16, centroids[C,d] f16, sizes[C] i32, sm_scale)`
 # returns the cluster scores S[nq, C] of Eq. 1 and is supplied by the caller.
