@@ -417,6 +417,57 @@ def bench_gqa(args, torch, sq, wl, dev):
     print(json.dumps(res, ensure_ascii=False))
 
 
+MFMA_F16_PEAK_TFLOPS = 2500.0
+
+
+def bench_kmeans(args, torch, sq, wl, dev):
+    """Offline clustering (sq_kmeans_step): one step = one Lloyd iteration over every head of the fixed context --
+    assignment (the MFMA kernel, 2*L*C*d flops per head), stable grouping by centre, member means."""
+    cfg = wl.KMEANS_CONFIGS[args.workload]
+    H, L, Cn, d = cfg["H"], cfg["L"], cfg["C"], 128
+    K, _, init = wl.clustering_input(args.seed, H, L, Cn)
+    shape = sq.make_shape(1, H, L, Cn, 1, 0, 1.0)
+    Kg = torch.from_numpy(K).to(dev)
+    X = torch.empty_like(Kg)
+    sq.sq_kmeans_normalize(shape, Kg, X)
+    idx = torch.from_numpy(init).to(dev).long()
+    cent = [torch.stack([X[h][idx[h]] for h in range(H)]).contiguous(), None]
+    cent[1] = torch.empty_like(cent[0])
+    i32 = lambda *s: torch.empty(s, dtype=torch.int32, device=dev)
+    assign, sizes, offsets, perm = i32(H, L), i32(H, Cn), i32(H, Cn + 1), i32(H, L)
+    ws = sq.workspace(shape, sq.SQ_CALL_KMEANS_STEP, dev)
+
+    def step(i, stream_ptr):                         # centres ping-pong: iteration i reads what i-1 wrote
+        sq.sq_kmeans_step(shape, X, cent[i & 1], cent[(i + 1) & 1], assign, sizes, offsets, perm, ws)
+
+    eager_ms, graph_ms, ms, (n_meas, k_avg, k_min, k_max) = time_steps(step, args, torch, sq)
+    flops = 2.0 * H * L * Cn * d
+    res = base_result(args, "K-means on normalised keys: Lloyd iterations/s over 32 heads x 32K keys x 1024 centres, "
+                      "d=128", round(1e3 / ms, 2), "iterations/s", ms, eager_ms, graph_ms, 1)
+    del res["us_per_token"]
+    res["config"] = {"workload": args.workload, "H": H, "L": L, "C": Cn, "d": d, "entry": "sq_kmeans_step",
+                     "largest_cluster": int(sizes.max()), "empty_clusters": int((sizes == 0).sum())}
+    res["roofline"] = {"bound": "mfma", "kernel": "kmeans_assign_kernel",
+                       "achieved": round(flops / (k_avg * 1e-6) / 1e12, 2) if n_meas else None,
+                       "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                       "frac": round(flops / (k_avg * 1e-6) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4) if n_meas else None,
+                       "traffic": None, "flops_per_launch": flops, "avg_us": round(k_avg, 3),
+                       "min_us": round(k_min, 3), "launches": n_meas}
+    if args.cpu_seconds > 0:
+        from oracle import clustering as ocl
+        Xn, c0 = X.cpu().numpy(), cent[0].cpu().numpy()
+        n, t_total = 0, 0.0
+        while n < H and t_total < args.cpu_seconds:
+            t0 = time.perf_counter()
+            ocl.lloyd_step(Xn[n], c0[n])
+            t_total += time.perf_counter() - t0
+            n += 1
+        import os
+        res["cpu_baseline"] = dict(value=round(n / t_total / H, 4), unit="iterations/s", cores=os.cpu_count(),
+                                   kind="oracle", sample=f"one Lloyd iteration on {n} of the {H} heads, scaled to all heads")
+    print(json.dumps(res, ensure_ascii=False))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -458,6 +509,8 @@ def main():
 
     if args.workload in wl.GQA_CONFIGS:
         return bench_gqa(args, torch, sq, wl, dev)
+    if args.workload in wl.KMEANS_CONFIGS:
+        return bench_kmeans(args, torch, sq, wl, dev)
     cfg = wl.CONFIGS[args.workload]
     if cfg.get("Lq", 1) > 1:
         return bench_prefill(args, torch, sq, wl, dev)

@@ -11,8 +11,8 @@
 // cluster is contiguous, and the centroid of every cluster as the mean of its RAW keys.
 //
 // The assignment is the only dense contraction: S^T = C X^T on 16x16x32 fp16 MFMA tiles, A = 16 centres read
-// from LDS, B = 16 key vectors held in registers.  A wave holds two B sets (32 keys), so every A operand read
-// feeds two MFMAs; the four waves of a workgroup (128 keys) share the centre stream, which travels global
+// from LDS, B = 16 key vectors held in registers.  A wave holds four B sets (64 keys), so every A operand read
+// feeds four MFMAs; the four waves of a workgroup (256 keys) share the centre stream, which travels global
 // memory -> registers (two groups ahead) -> one of two LDS stages, one barrier per group of 64 centres.  A lane
 // owns one key per B set and four centres per tile, so the running (best score, best centre) is a per-lane
 // scalar pair; the four lane groups are combined once at the end.  Ties go to the lowest centre index: a lane
@@ -24,13 +24,19 @@
 namespace sq {
 
 constexpr int KM_G = 64;                     // centres per staged group
-constexpr int KM_STRIDE = D + 8;             // halves per centre row in LDS (272 B: conflict-free 16-B reads)
-constexpr int KM_RW = 2;                     // B sets (16 keys each) per wave
+#ifndef SQ_KM_PAD
+#define SQ_KM_PAD 8
+#endif
+constexpr int KM_STRIDE = D + SQ_KM_PAD;             // halves per centre row in LDS (272 B: conflict-free 16-B reads)
+#ifndef SQ_KM_RW
+#define SQ_KM_RW 4
+#endif
+constexpr int KM_RW = SQ_KM_RW;             // B sets (16 keys each) per wave
 constexpr int KM_ROWS_PER_WG = 4 * 16 * KM_RW;
 
 struct KmStage {
     _Float16 Ct[KM_G * KM_STRIDE];
-    float hn[KM_G];
+    float nhn[KM_G];                         // minus the half norm: the accumulator's starting value
 };
 
 // x / |x| per row (fp32 arithmetic), one wave per row; a zero row stays zero.
@@ -94,13 +100,13 @@ __global__ __launch_bounds__(256) void kmeans_assign_kernel(const _Float16 *__re
             const int c_row = min(g * KM_G + i * 16 + (tid >> 4), C - 1);
             pk[i] = *reinterpret_cast<const h8 *>(ch + (size_t)c_row * 256 + (tid & 15) * 16);
         }
-        if (tid < KM_G) pn = g * KM_G + tid < C ? hh[g * KM_G + tid] : __builtin_inff();   // past the end: never best
+        if (tid < KM_G) pn = g * KM_G + tid < C ? -hh[g * KM_G + tid] : SQ_NEG_INF;   // past the end: never best
     };
     auto commit = [&](KmStage &st) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             *reinterpret_cast<h8 *>(st.Ct + (i * 16 + (tid >> 4)) * KM_STRIDE + (tid & 15) * 8) = pk[i];
-        if (tid < KM_G) st.hn[tid] = pn;
+        if (tid < KM_G) st.nhn[tid] = pn;
     };
 
     float best[KM_RW];
@@ -110,6 +116,34 @@ __global__ __launch_bounds__(256) void kmeans_assign_kernel(const _Float16 *__re
         best[r] = SQ_NEG_INF;
         bi[r] = 0;
     }
+    // Scores of tile u of a staged group: acc[r][v] = x_r . c - hn_c for c = u*16 + kg*4 + v (the accumulator starts
+    // at -hn_c).
+    auto tile = [&](const KmStage &st, int u, f4 (&acc)[KM_RW]) {
+        const f4 nh = *reinterpret_cast<const f4 *>(st.nhn + u * 16 + kg * 4);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const h8 a = *reinterpret_cast<const h8 *>(st.Ct + (u * 16 + col) * KM_STRIDE + s * 32 + kg * 8);
+#pragma unroll
+            for (int r = 0; r < KM_RW; ++r)
+                acc[r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bx[r][s], s == 0 ? nh : acc[r], 0, 0, 0);
+        }
+    };
+    auto take = [&](const f4 (&acc)[KM_RW], int c0) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+#pragma unroll
+            for (int r = 0; r < KM_RW; ++r)
+                if (acc[r][v] > best[r]) {
+                    best[r] = acc[r][v];
+                    bi[r] = c0 + v;
+                }
+    };
+    // The running best is updated one tile behind the matrix cores: the compares of a tile come after the MFMAs of
+    // the next one in program order, which lets the compiler interleave the two kinds of work.
+    f4 cur[KM_RW];
+#pragma unroll
+    for (int r = 0; r < KM_RW; ++r) cur[r] = f4{SQ_NEG_INF, SQ_NEG_INF, SQ_NEG_INF, SQ_NEG_INF};
+    int cur_c0 = 0;
     fetch(0);
     commit(stage[0]);
     if (ng > 1) fetch(1);
@@ -122,30 +156,16 @@ __global__ __launch_bounds__(256) void kmeans_assign_kernel(const _Float16 *__re
         const KmStage &st = stage[g & 1];
 #pragma unroll
         for (int u = 0; u < KM_G / 16; ++u) {
-            f4 acc[KM_RW];
+            f4 nxt[KM_RW];
+            tile(st, u, nxt);
+            take(cur, cur_c0);
 #pragma unroll
-            for (int r = 0; r < KM_RW; ++r) acc[r] = f4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const h8 a = *reinterpret_cast<const h8 *>(st.Ct + (u * 16 + col) * KM_STRIDE + s * 32 + kg * 8);
-#pragma unroll
-                for (int r = 0; r < KM_RW; ++r) acc[r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bx[r][s], acc[r], 0, 0, 0);
-            }
-            const f4 hv = *reinterpret_cast<const f4 *>(st.hn + u * 16 + kg * 4);
-            const int c0 = g * KM_G + u * 16 + kg * 4;
-#pragma unroll
-            for (int v = 0; v < 4; ++v)
-#pragma unroll
-                for (int r = 0; r < KM_RW; ++r) {
-                    const float sc = acc[r][v] - hv[v];
-                    if (sc > best[r]) {
-                        best[r] = sc;
-                        bi[r] = c0 + v;
-                    }
-                }
+            for (int r = 0; r < KM_RW; ++r) cur[r] = nxt[r];
+            cur_c0 = g * KM_G + u * 16 + kg * 4;
         }
         __syncthreads();                                      // stage g & 1 may be overwritten; the other is complete
     }
+    take(cur, cur_c0);
 #pragma unroll
     for (int r = 0; r < KM_RW; ++r) {
 #pragma unroll
@@ -214,9 +234,10 @@ __global__ __launch_bounds__(1024) void kmeans_scan_kernel(int32_t *__restrict__
 }
 
 // Grouping, step 3: one WAVE per part walks the part's keys in index order, 64 at a time.  The lanes that hold the
-// same centre id are found by electing the first unplaced lane and matching the others against its id; a lane's
-// slot is the cluster's cursor plus the number of matching lanes below it, so members appear in ascending key
-// order inside every cluster (a stable sort).  A single wave touches the cursors, in program order: no atomics.
+// same centre id are found in registers by electing the first unplaced lane and matching the others against its
+// id; a lane's slot is the cluster's cursor plus the number of matching lanes below it, so members appear in
+// ascending key order inside every cluster (a stable sort).  The cursors live in LDS and are touched by this one
+// wave only, in program order (all lanes of a group read the cursor, then its last lane advances it): no atomics.
 __global__ __launch_bounds__(64) void kmeans_scatter_kernel(const int32_t *__restrict__ assign,
                                                             const int32_t *__restrict__ hist,
                                                             const int32_t *__restrict__ offsets,
@@ -229,23 +250,27 @@ __global__ __launch_bounds__(64) void kmeans_scatter_kernel(const int32_t *__res
     for (int c = lane; c < C; c += 64) s_cur[c] = op[c] + hp[c];
     __syncthreads();
     const int k_end = min(L, (p + 1) * PL);
-    const uint64_t below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
     for (int k0 = p * PL; k0 < k_end; k0 += 64) {
         const int k = k0 + lane;
         const bool valid = k < k_end;
         const int c = valid ? assign[(size_t)h * L + k] : -1;
         uint64_t todo = __ballot(valid);
-        int pos = 0;
+        int rank = 0, cnt = 0;
         while (todo) {
             const int leader = __ffsll((long long)todo) - 1;
-            const int cl = __shfl(c, leader);
+            const int cl = __builtin_amdgcn_readlane(c, leader);
             const uint64_t m = __ballot(c == cl);
-            if (c == cl) pos = s_cur[cl] + __popcll(m & below);
-            __builtin_amdgcn_wave_barrier();                 // every member has read the cursor before it moves
-            if (lane == leader) s_cur[cl] += __popcll(m);
+            if (c == cl) {
+                rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+                cnt = __popcll(m);
+            }
             todo &= ~m;
         }
-        if (valid) perm[(size_t)h * L + pos] = k;
+        if (valid) {
+            const int cur = s_cur[c];
+            if (rank == cnt - 1) s_cur[c] = cur + cnt;
+            perm[(size_t)h * L + cur + rank] = k;
+        }
     }
 }
 

@@ -208,6 +208,12 @@ GQA_CONFIGS = {
 }
 
 
+# Offline clustering of the headline config's fixed context: 32 heads x 32768 keys into 1024 clusters (Section 3.1).
+KMEANS_CONFIGS = {
+    "kmeans_32k": dict(H=32, L=32768, C=1024),
+}
+
+
 def make_config(name: str, seed: int = 0, threads: int = 8, **override) -> Workload:
     kw = dict(CONFIGS[name] if name in CONFIGS else GQA_CONFIGS[name])
     kw.update(override)
