@@ -204,3 +204,39 @@ def test_layout_feeds_the_online_path(sq, oracle):
     np.testing.assert_array_equal(unpack_mask(mask.cpu().numpy(), C), unpack_mask(rmask, C))
     np.testing.assert_array_equal(nk.cpu().numpy(), rnk)
     assert np.abs(out.cpu().numpy().astype(np.float64) - ro).max() <= 2e-3
+
+
+def test_full_size_iteration_on_sampled_keys_and_centres(sq):
+    """The shape the benchmark times (32 heads x 32768 keys x 1024 centres), in the same launch configuration: sampled
+    keys against the oracle's assignment, whole-array properties of the grouping, sampled centres against their
+    members' means."""
+    cfg = wl.KMEANS_CONFIGS["kmeans_32k"]
+    H, L, C = cfg["H"], cfg["L"], cfg["C"]
+    K, _, init = wl.clustering_input(0, H, L, C)
+    sh = sq.make_shape(1, H, L, C, 1, 0, 1.0)
+    Kg = t(K)
+    Xg = torch.empty_like(Kg)
+    sq.sq_kmeans_normalize(sh, Kg, Xg)
+    cg = torch.stack([Xg[h][t(init[h]).long()] for h in range(H)]).contiguous()
+    out = torch.empty_like(cg)
+    i32 = lambda *s: torch.empty(s, dtype=torch.int32, device=DEV)
+    a, n, o, p = i32(H, L), i32(H, C), i32(H, C + 1), i32(H, L)
+    sq.sq_kmeans_step(sh, Xg, cg, out, a, n, o, p, sq.workspace(sh, sq.SQ_CALL_KMEANS_STEP, DEV))
+    torch.cuda.synchronize()
+    X, cent, an, nn, on, pn, cn = (x.cpu().numpy() for x in (Xg, cg, a, n, o, p, out))
+    rng = np.random.default_rng(5)
+    for h in range(H):
+        ks = rng.integers(0, L, 64)
+        ks[:2] = (0, L - 1)
+        a_ref, margin = ocl.assign(X[h][ks], cent[h])
+        clear = margin > MARGIN
+        np.testing.assert_array_equal(an[h][ks][clear], a_ref[clear], err_msg=f"head {h}")
+        assert clear.mean() > 0.9
+        # grouping: exact bookkeeping of the whole head
+        np.testing.assert_array_equal(nn[h], np.bincount(an[h], minlength=C))
+        np.testing.assert_array_equal(on[h], np.concatenate([[0], np.cumsum(nn[h])]))
+        np.testing.assert_array_equal(pn[h], np.argsort(an[h], kind="stable"))
+        for c in rng.integers(0, C, 8):
+            mem = pn[h][on[h][c]:on[h][c + 1]]
+            ref = X[h][mem].astype(np.float64).mean(0) if len(mem) else cent[h][c].astype(np.float64)
+            assert np.abs(cn[h][c].astype(np.float64) - ref).max() <= UNIT_ATOL
