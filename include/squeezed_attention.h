@@ -60,7 +60,8 @@ typedef enum sq_call {
     SQ_CALL_GQA_DECODE_STEP = 11,
     SQ_CALL_MULTILEVEL_SELECT = 12,
     SQ_CALL_MULTILEVEL_DECODE_STEP = 13,
-    SQ_CALL_KMEANS_STEP = 14
+    SQ_CALL_KMEANS_STEP = 14,
+    SQ_CALL_CALIBRATE = 15
 } sq_call;
 
 /*
@@ -364,6 +365,23 @@ int sq_kmeans_step(const sq_shape_t *shape, const void *X, const void *centers_i
 int sq_cluster_layout(const sq_shape_t *shape, const void *K, const void *V, const int32_t *perm,
                       const int32_t *sizes, const int32_t *offsets, void *K_sorted, void *V_sorted,
                       void *centroids, void *stream);
+
+/*
+ * Threshold calibration (Appendix C: the threshold is set so that a target share of the keys is retrieved on
+ * calibration queries; the paper states the goal, the procedure is this library's).  The B * Lq rows of each head are
+ * its calibration queries: their cluster scores S_i = exp(logits - row_max) / denom (Eq. 1, fp32, as written by
+ * sq_centroid_score) are pooled, each weighing sizes[i] keys, and walked from the highest score down until
+ * target_keys keys are covered (clamped to what the head's queries can retrieve at all); thresh[h] is the geometric
+ * mean of the last score needed and the highest score strictly below it (half the last score if there is none, or
+ * if it is 0), so that the strict rule S > thresh keeps exactly the walked scores, ties included.
+ * In:  logits f32 [B,H,Lq,C], row_max, denom f32 [B,H,Lq], sizes i32 [H,C]; target_keys = pooled key budget per head
+ *      (e.g. keep_fraction * B * Lq * L).  B * Lq * L must stay below 2^31.
+ * Out: thresh f32 [H].
+ * Workspace: sq_workspace_bytes(shape, SQ_CALL_CALIBRATE).
+ */
+int sq_calibrate_threshold(const sq_shape_t *shape, const float *logits, const float *row_max, const float *denom,
+                           const int32_t *sizes, int64_t target_keys, float *thresh,
+                           void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Measurement hook for benchmarks (not part of the method; for callers that want a kernel's duration

@@ -3,7 +3,8 @@ calibration queries) -- TEST INFRASTRUCTURE ONLY, plain NumPy.
 
 The paper states the goal (hit a target sparsity on calibration tokens), not the procedure.  Reading taken, per
 head: pool the cluster scores S_i of Eq. 1 of all calibration queries, each weighing N_i keys; walk them from the
-highest score down until `target_keys` keys are covered (s_k = the last score needed); the threshold is the
+highest score down until `target_keys` keys are covered (s_k = the last score needed; a budget beyond what the
+queries can retrieve at all is clamped to that); the threshold is the
 geometric mean of s_k and the highest score strictly below it (half of s_k if there is none, or if that score is 0),
 so that the strict rule S > T keeps exactly the walked prefix.  Scores are formed in fp32 from the fp32
 (logit, maximum, normaliser) triple, the precision the selection itself works in; clusters without keys weigh nothing.
@@ -31,8 +32,7 @@ def calibrate_threshold(S, sizes, target_keys: int) -> float:
     s = S.ravel()
     order = np.argsort(-s, kind="stable")
     ss, cum = s[order], np.cumsum(w[order])
-    k = int(np.searchsorted(cum, target_keys, side="left"))
-    k = min(k, len(ss) - 1)
+    k = int(np.searchsorted(cum, min(int(target_keys), int(cum[-1])), side="left"))
     s_k = float(ss[k])
     below = ss[ss < ss[k]]
     s_below = float(below.max()) if len(below) else 0.0

@@ -21,14 +21,14 @@ SQ_OK, SQ_ERR_INVALID_ARG, SQ_ERR_UNSUPPORTED, SQ_ERR_WORKSPACE, SQ_ERR_HIP = 0,
 (SQ_CALL_CENTROID_SCORE, SQ_CALL_SELECT, SQ_CALL_ATTN_DECODE, SQ_CALL_ATTN_PREFILL, SQ_CALL_HIER_SELECT,
  SQ_CALL_DECODE_STEP, SQ_CALL_HIER_DECODE_STEP, SQ_CALL_SELECT_MEAN, SQ_CALL_ATTN_PREFILL_SHARED,
  SQ_CALL_PREFILL_STEP, SQ_CALL_PREFILL_MEAN_STEP, SQ_CALL_GQA_DECODE_STEP, SQ_CALL_MULTILEVEL_SELECT,
- SQ_CALL_MULTILEVEL_DECODE_STEP, SQ_CALL_KMEANS_STEP) = range(15)
+ SQ_CALL_MULTILEVEL_DECODE_STEP, SQ_CALL_KMEANS_STEP, SQ_CALL_CALIBRATE) = range(16)
 SQ_MAX_LEVELS = 4
 
 EXPORTS = ("sq_workspace_bytes", "sq_last_error", "sq_version", "sq_centroid_score", "sq_select",
            "sq_sparse_attn_decode", "sq_sparse_attn_prefill", "sq_hier_select", "sq_decode_step",
            "sq_hier_decode_step", "sq_select_mean", "sq_sparse_attn_prefill_shared", "sq_prefill_step",
            "sq_prefill_mean_step", "sq_gqa_decode_step", "sq_multilevel_select", "sq_multilevel_decode_step",
-           "sq_kmeans_normalize", "sq_kmeans_step", "sq_cluster_layout", "sq_profile_begin",
+           "sq_kmeans_normalize", "sq_kmeans_step", "sq_cluster_layout", "sq_calibrate_threshold", "sq_profile_begin",
            "sq_profile_end", "sq_probe_stream_read")
 
 
@@ -79,6 +79,7 @@ def lib() -> C.CDLL:
         L.sq_kmeans_normalize.argtypes = [sp, vp, vp, vp]
         L.sq_kmeans_step.argtypes = [sp] + [vp] * 7 + [vp, sz, vp]
         L.sq_cluster_layout.argtypes = [sp] + [vp] * 8 + [vp]
+        L.sq_calibrate_threshold.argtypes = [sp] + [vp] * 4 + [C.c_int64, vp] + [vp, sz, vp]
         L.sq_probe_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_int, C.c_void_p]
         L.sq_profile_begin.argtypes = [C.c_int]
         L.sq_profile_end.argtypes = [C.POINTER(C.c_float)] * 3
@@ -304,6 +305,12 @@ def sq_cluster_layout(shape, K, V, perm, sizes, offsets, K_sorted, V_sorted, cen
                                    _ptr(sizes, I32, "sizes"), _ptr(offsets, I32, "offsets"),
                                    _ptr(K_sorted, F16, "K_sorted"), _ptr(V_sorted, F16, "V_sorted"),
                                    _ptr(centroids, F16, "centroids"), _stream(stream)))
+
+
+def sq_calibrate_threshold(shape, logits, row_max, denom, sizes, target_keys, thresh, ws, stream=None):
+    _check(lib().sq_calibrate_threshold(C.byref(shape), _ptr(logits, F32, "logits"), _ptr(row_max, F32, "row_max"),
+                                        _ptr(denom, F32, "denom"), _ptr(sizes, I32, "sizes"), int(target_keys),
+                                        _ptr(thresh, F32, "thresh"), *_ws_args(ws), _stream(stream)))
 
 
 def sq_probe_stream_read(buf: torch.Tensor, sink: torch.Tensor, workgroups: int, nbytes: Optional[int] = None,

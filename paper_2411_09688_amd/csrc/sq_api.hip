@@ -376,6 +376,9 @@ size_t sq_workspace_bytes(const sq_shape_t *sh, int which)
     case SQ_CALL_KMEANS_STEP:
         carve_kmeans(cv, sh);
         return cv.off;
+    case SQ_CALL_CALIBRATE:
+        cv.take<float>((size_t)sh->B * sh->H * sh->Lq * sh->C);
+        return cv.off;
     case SQ_CALL_PREFILL_MEAN_STEP:
         carve_prefill_mean_step(cv, sh);
         return cv.off;
@@ -1024,6 +1027,30 @@ int sq_cluster_layout(const sq_shape_t *sh, const void *K, const void *V, const 
     if (int rc = check_device(__func__)) return rc;
     SQ_HIP(sq::launch_cluster_layout(K, V, perm, sizes, offsets, K_sorted, V_sorted, centroids, sh->B * sh->H, sh->L,
                                      sh->C, static_cast<hipStream_t>(stream)));
+    g_err[0] = 0;
+    return SQ_OK;
+}
+
+int sq_calibrate_threshold(const sq_shape_t *sh, const float *logits, const float *row_max, const float *denom,
+                           const int32_t *sizes, int64_t target_keys, float *thresh, void *ws, size_t ws_bytes,
+                           void *stream)
+{
+    if (int rc = check_shape(sh, __func__, false)) return rc;
+    if (target_keys < 0) return fail(SQ_ERR_INVALID_ARG, "%s: target_keys is negative", __func__);
+    if ((long long)sh->B * sh->Lq * sh->L >= (1ll << 31) || (long long)sh->B * sh->Lq * sh->C >= (1ll << 30))
+        return fail(SQ_ERR_UNSUPPORTED, "%s: too many calibration queries (B * Lq * L must stay below 2^31)", __func__);
+    SQ_REQUIRE_PTR(logits);
+    SQ_REQUIRE_PTR(row_max);
+    SQ_REQUIRE_PTR(denom);
+    SQ_REQUIRE_PTR(sizes);
+    SQ_REQUIRE_PTR(thresh);
+    if (int rc = check_ws(__func__, sh, SQ_CALL_CALIBRATE, ws, ws_bytes)) return rc;
+    if (int rc = check_device(__func__)) return rc;
+    Carver cv(ws);
+    float *S = cv.take<float>((size_t)sh->B * sh->H * sh->Lq * sh->C);
+    const long long cap = (long long)sh->B * sh->Lq * sh->L;
+    SQ_HIP(sq::launch_calibrate(logits, row_max, denom, sizes, S, thresh, (int)(target_keys < cap ? target_keys : cap),
+                                sh->B, sh->H, sh->Lq, sh->C, static_cast<hipStream_t>(stream)));
     g_err[0] = 0;
     return SQ_OK;
 }

@@ -150,6 +150,10 @@ hipError_t launch_cluster_layout(const void *K, const void *V, const int32_t *pe
                                  const int32_t *offsets, void *K_sorted, void *V_sorted, void *centroids, int heads,
                                  int L, int C, hipStream_t s);
 
+// Threshold calibration (sq_calibrate.hip).  S: [H, B * Lq, C] floats of workspace.
+hipError_t launch_calibrate(const float *logits, const float *row_max, const float *denom, const int32_t *sizes,
+                            float *S, float *thresh, int target, int B, int H, int Lq, int C, hipStream_t s);
+
 // Measurement hook (sq_profile.hip): when enabled, hands out the next pair of events; the caller attaches them to
 // the dominant kernel's dispatch (hipExtLaunchKernelGGL), so they carry the start and end time of that kernel
 // itself rather than of marker packets around it.

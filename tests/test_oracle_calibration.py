@@ -56,3 +56,10 @@ def test_pooled_scores_follow_eq1():
     S = cal.pooled_scores(x, m, D, sizes)
     np.testing.assert_allclose((S.astype(np.float64) * sizes[None]).sum(1), 1.0, rtol=1e-5)   # sum_i N_i S_i = 1
     assert (S[:, ~live] == 0).all()
+
+
+def test_budget_beyond_reach_keeps_every_cluster_with_keys():
+    S = np.array([[0.5, 0.0, 0.25, 0.125]], np.float32)          # cluster 1 has no keys (score forced to 0)
+    sizes = np.array([2, 0, 2, 2])
+    T = cal.calibrate_threshold(S, sizes, 100)                   # clamped to 6: the last score needed is 0.125
+    assert T == pytest.approx(0.5 * 0.125) and cal.kept_keys(S, sizes, T) == 6
