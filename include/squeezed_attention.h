@@ -360,11 +360,32 @@ int sq_kmeans_step(const sq_shape_t *shape, const void *X, const void *centers_i
  * From a grouping (perm, sizes, offsets as written by sq_kmeans_step) to the inputs of the online calls above:
  * K_sorted[b,h,i,:] = K[b,h,perm[i],:], likewise V_sorted, so that each cluster's keys are contiguous, and
  * centroids f16 [B,H,C,d] = mean of the RAW keys of each cluster (Section 3.1; zeros for an empty cluster).
- * K, V, K_sorted, V_sorted f16 [B,H,L,d]; the outputs must not alias the inputs.  No workspace.
+ * K, V, K_sorted, V_sorted f16 [B,H,L,d]; the outputs must not alias the inputs.  V and V_sorted may be NULL (keys
+ * only); K_sorted may be NULL too (centroids only), and then perm may be NULL: cluster c is rows
+ * offsets[c] .. offsets[c] + sizes[c] of K as they stand.  No workspace.
  */
 int sq_cluster_layout(const sq_shape_t *shape, const void *K, const void *V, const int32_t *perm,
                       const int32_t *sizes, const int32_t *offsets, void *K_sorted, void *V_sorted,
                       void *centroids, void *stream);
+
+/*
+ * Nesting for the hierarchical lookup (Section 3.3: the coarse level is a clustering of the fine centroids).  After
+ * the keys were clustered into shape->C fine clusters (assign_fine i32 [B,H,L], from sq_kmeans_step) and the fine
+ * centroids into C1 coarse clusters (a second sq_kmeans_step run on the centroids, with L = C and C = C1: its perm
+ * is perm_coarse i32 [B,H,C], its offsets are child_offsets i32 [B,H,C1+1]), this call renumbers the fine clusters
+ * in perm_coarse order, so that the children of a coarse cluster are the consecutive fine clusters
+ * child_offsets[j] .. child_offsets[j+1]-1, and groups the keys again:
+ *   assign_new i32 [B,H,L]   new fine cluster id of each key
+ *   sizes i32 [B,H,C], offsets i32 [B,H,C+1], perm i32 [B,H,L]   the keys grouped by new id (as sq_kmeans_step)
+ *   sizes_coarse i32 [B,H,C1]   keys under each coarse cluster
+ * Then sq_cluster_layout on (perm, sizes, offsets) gives K/V and the fine centroids in the new order, and
+ * sq_cluster_layout with L = C, C = C1 on those centroids (perm NULL, sizes = the coarse run's sizes, offsets =
+ * child_offsets) gives the coarse centroids as the unweighted mean of their children.
+ * Workspace: sq_workspace_bytes(shape, SQ_CALL_KMEANS_STEP).
+ */
+int sq_cluster_nest(const sq_shape_t *shape, int32_t C1, const int32_t *assign_fine, const int32_t *perm_coarse,
+                    const int32_t *child_offsets, int32_t *assign_new, int32_t *sizes, int32_t *offsets,
+                    int32_t *perm, int32_t *sizes_coarse, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Threshold calibration (Appendix C: the threshold is set so that a target share of the keys is retrieved on

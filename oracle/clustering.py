@@ -77,3 +77,21 @@ def layout(K, a, C):
     nz = sizes > 0
     cent[nz] /= sizes[nz, None]
     return perm, sizes, offsets, cent.astype(np.float16)
+
+
+def nest(assign_fine, perm_coarse, child_offsets, C2):
+    """Fine clusters nested under coarse ones (Section 3.3: the coarse level clusters the fine centroids).
+    perm_coarse [C2]: fine ids grouped by coarse cluster; child_offsets [C1+1].  The fine clusters are renumbered in
+    perm_coarse order and the keys grouped again.
+    -> (assign_new [L], sizes [C2], offsets [C2+1], perm [L], sizes_coarse [C1] keys under each coarse cluster)."""
+    perm_coarse = np.asarray(perm_coarse)
+    inv = np.empty(C2, np.int64)
+    inv[perm_coarse] = np.arange(C2)
+    assign_new = inv[np.asarray(assign_fine)].astype(np.int32)
+    perm = np.argsort(assign_new, kind="stable").astype(np.int32)
+    sizes = np.bincount(assign_new, minlength=C2).astype(np.int32)
+    offsets = np.zeros(C2 + 1, np.int32)
+    offsets[1:] = np.cumsum(sizes)
+    co = np.asarray(child_offsets)
+    sizes_coarse = (offsets[co[1:]] - offsets[co[:-1]]).astype(np.int32)
+    return assign_new, sizes, offsets, perm, sizes_coarse

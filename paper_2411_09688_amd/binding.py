@@ -28,7 +28,7 @@ EXPORTS = ("sq_workspace_bytes", "sq_last_error", "sq_version", "sq_centroid_sco
            "sq_sparse_attn_decode", "sq_sparse_attn_prefill", "sq_hier_select", "sq_decode_step",
            "sq_hier_decode_step", "sq_select_mean", "sq_sparse_attn_prefill_shared", "sq_prefill_step",
            "sq_prefill_mean_step", "sq_gqa_decode_step", "sq_multilevel_select", "sq_multilevel_decode_step",
-           "sq_kmeans_normalize", "sq_kmeans_step", "sq_cluster_layout", "sq_calibrate_threshold", "sq_profile_begin",
+           "sq_kmeans_normalize", "sq_kmeans_step", "sq_cluster_layout", "sq_cluster_nest", "sq_calibrate_threshold", "sq_profile_begin",
            "sq_profile_end", "sq_probe_stream_read")
 
 
@@ -79,6 +79,7 @@ def lib() -> C.CDLL:
         L.sq_kmeans_normalize.argtypes = [sp, vp, vp, vp]
         L.sq_kmeans_step.argtypes = [sp] + [vp] * 7 + [vp, sz, vp]
         L.sq_cluster_layout.argtypes = [sp] + [vp] * 8 + [vp]
+        L.sq_cluster_nest.argtypes = [sp, C.c_int32] + [vp] * 8 + [vp, sz, vp]
         L.sq_calibrate_threshold.argtypes = [sp] + [vp] * 4 + [C.c_int64, vp] + [vp, sz, vp]
         L.sq_probe_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_int, C.c_void_p]
         L.sq_profile_begin.argtypes = [C.c_int]
@@ -305,6 +306,15 @@ def sq_cluster_layout(shape, K, V, perm, sizes, offsets, K_sorted, V_sorted, cen
                                    _ptr(sizes, I32, "sizes"), _ptr(offsets, I32, "offsets"),
                                    _ptr(K_sorted, F16, "K_sorted"), _ptr(V_sorted, F16, "V_sorted"),
                                    _ptr(centroids, F16, "centroids"), _stream(stream)))
+
+
+def sq_cluster_nest(shape, C1, assign_fine, perm_coarse, child_offsets, assign_new, sizes, offsets, perm, sizes_coarse,
+                    ws, stream=None):
+    _check(lib().sq_cluster_nest(C.byref(shape), int(C1), _ptr(assign_fine, I32, "assign_fine"),
+                                 _ptr(perm_coarse, I32, "perm_coarse"), _ptr(child_offsets, I32, "child_offsets"),
+                                 _ptr(assign_new, I32, "assign_new"), _ptr(sizes, I32, "sizes"),
+                                 _ptr(offsets, I32, "offsets"), _ptr(perm, I32, "perm"),
+                                 _ptr(sizes_coarse, I32, "sizes_coarse"), *_ws_args(ws), _stream(stream)))
 
 
 def sq_calibrate_threshold(shape, logits, row_max, denom, sizes, target_keys, thresh, ws, stream=None):

@@ -1015,18 +1015,46 @@ int sq_cluster_layout(const sq_shape_t *sh, const void *K, const void *V, const 
 {
     if (int rc = check_shape(sh, __func__, false)) return rc;
     SQ_REQUIRE_PTR(K);
-    SQ_REQUIRE_PTR(V);
-    SQ_REQUIRE_PTR(perm);
+    SQ_OPTIONAL_PTR(V);
+    SQ_OPTIONAL_PTR(perm);
     SQ_REQUIRE_PTR(sizes);
     SQ_REQUIRE_PTR(offsets);
-    SQ_REQUIRE_PTR(K_sorted);
-    SQ_REQUIRE_PTR(V_sorted);
+    SQ_OPTIONAL_PTR(K_sorted);
+    SQ_OPTIONAL_PTR(V_sorted);
     SQ_REQUIRE_PTR(centroids);
-    if (K_sorted == K || V_sorted == V || K_sorted == V || V_sorted == K)
+    if (V_sorted && (!V || !K_sorted))
+        return fail(SQ_ERR_INVALID_ARG, "%s: V_sorted needs V and K_sorted", __func__);
+    if (K_sorted && !perm) return fail(SQ_ERR_INVALID_ARG, "%s: reordering needs perm", __func__);
+    if (K_sorted && (K_sorted == K || K_sorted == V || (V_sorted && (V_sorted == V || V_sorted == K))))
         return fail(SQ_ERR_INVALID_ARG, "%s: the reordered tensors must not alias the inputs", __func__);
     if (int rc = check_device(__func__)) return rc;
     SQ_HIP(sq::launch_cluster_layout(K, V, perm, sizes, offsets, K_sorted, V_sorted, centroids, sh->B * sh->H, sh->L,
                                      sh->C, static_cast<hipStream_t>(stream)));
+    g_err[0] = 0;
+    return SQ_OK;
+}
+
+int sq_cluster_nest(const sq_shape_t *sh, int32_t C1, const int32_t *assign_fine, const int32_t *perm_coarse,
+                    const int32_t *child_offsets, int32_t *assign_new, int32_t *sizes, int32_t *offsets, int32_t *perm,
+                    int32_t *sizes_coarse, void *ws, size_t ws_bytes, void *stream)
+{
+    if (int rc = check_shape(sh, __func__, false)) return rc;
+    if (C1 <= 0 || C1 > sh->C) return fail(SQ_ERR_INVALID_ARG, "%s: C1 = %d must be in [1, C = %d]", __func__, C1, sh->C);
+    SQ_REQUIRE_PTR(assign_fine);
+    SQ_REQUIRE_PTR(perm_coarse);
+    SQ_REQUIRE_PTR(child_offsets);
+    SQ_REQUIRE_PTR(assign_new);
+    SQ_REQUIRE_PTR(sizes);
+    SQ_REQUIRE_PTR(offsets);
+    SQ_REQUIRE_PTR(perm);
+    SQ_REQUIRE_PTR(sizes_coarse);
+    if (int rc = check_ws(__func__, sh, SQ_CALL_KMEANS_STEP, ws, ws_bytes)) return rc;
+    if (int rc = check_device(__func__)) return rc;
+    Carver cv(ws);
+    KmeansWs w = carve_kmeans(cv, sh);
+    SQ_HIP(sq::launch_cluster_nest(assign_fine, perm_coarse, child_offsets, assign_new, sizes, offsets, perm, sizes_coarse,
+                                   reinterpret_cast<int32_t *>(w.hn), w.hist, sh->B * sh->H, sh->L, sh->C, C1,
+                                   static_cast<hipStream_t>(stream)));
     g_err[0] = 0;
     return SQ_OK;
 }

@@ -146,6 +146,10 @@ hipError_t launch_normalize_rows(const void *K, void *X, size_t rows, hipStream_
 hipError_t launch_kmeans_step(const void *X, const void *centers_in, void *centers_out, int32_t *assign,
                               int32_t *sizes, int32_t *offsets, int32_t *perm, float *hn, int32_t *hist, int heads,
                               int L, int C, hipStream_t s);
+hipError_t launch_cluster_nest(const int32_t *assign_fine, const int32_t *perm_coarse, const int32_t *child_offsets,
+                               int32_t *assign_new, int32_t *sizes, int32_t *offsets, int32_t *perm,
+                               int32_t *sizes_coarse, int32_t *inv, int32_t *hist, int heads, int L, int C2, int C1,
+                               hipStream_t s);
 hipError_t launch_cluster_layout(const void *K, const void *V, const int32_t *perm, const int32_t *sizes,
                                  const int32_t *offsets, void *K_sorted, void *V_sorted, void *centroids, int heads,
                                  int L, int C, hipStream_t s);

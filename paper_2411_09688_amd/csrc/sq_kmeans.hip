@@ -276,9 +276,10 @@ __global__ __launch_bounds__(64) void kmeans_scatter_kernel(const int32_t *__res
 
 // Mean of the rows of `src` listed for one cluster (members perm[off .. off + n) of head h), fp32 accumulation in
 // a fixed order: 16 member slots x 16 sixteen-byte pieces of a row, then the slots are added in ascending order.
-// An empty cluster copies prev (the centre it had) or, with prev == NULL, writes zeros.
+// An empty cluster copies prev (the centre it had) or, with prev == NULL, writes zeros.  perm == NULL: the members of
+// a cluster are the rows off .. off + n themselves.
 __global__ __launch_bounds__(256) void cluster_mean_kernel(const _Float16 *__restrict__ src,
-                                                           const int32_t *__restrict__ perm,
+                                                           const int32_t *perm,
                                                            const int32_t *__restrict__ sizes,
                                                            const int32_t *__restrict__ offsets,
                                                            const _Float16 *prev, _Float16 *out, int L, int C)
@@ -286,20 +287,22 @@ __global__ __launch_bounds__(256) void cluster_mean_kernel(const _Float16 *__res
     __shared__ float s_acc[16][D + 4];
     const int c = blockIdx.x, h = blockIdx.y, tid = threadIdx.x;
     const int slot = tid >> 4, piece = tid & 15;
-    const int n = sizes[(size_t)h * C + c], off = offsets[(size_t)h * (C + 1) + c];
+    const int off = min(max(offsets[(size_t)h * (C + 1) + c], 0), L);
+    const int n = min(max(sizes[(size_t)h * C + c], 0), L - off);
     _Float16 *dst = out + ((size_t)h * C + c) * D;
     if (n == 0) {
         if (tid < D) dst[tid] = prev ? prev[((size_t)h * C + c) * D + tid] : (_Float16)0.0f;
         return;
     }
-    const int32_t *mem = perm + (size_t)h * L + off;
+    const int32_t *mem = perm ? perm + (size_t)h * L + off : nullptr;
+    auto member = [&](int m) { return mem ? min(max(mem[m], 0), L - 1) : off + m; };
     const _Float16 *rows = src + (size_t)h * L * D;
     float acc[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
     int m = slot;
     for (; m + 16 < n; m += 32) {                             // two rows in flight
-        const int i0 = mem[m], i1 = mem[m + 16];
+        const int i0 = member(m), i1 = member(m + 16);
         const h8 a = *reinterpret_cast<const h8 *>(rows + (size_t)i0 * D + piece * 8);
         const h8 b = *reinterpret_cast<const h8 *>(rows + (size_t)i1 * D + piece * 8);
 #pragma unroll
@@ -308,7 +311,7 @@ __global__ __launch_bounds__(256) void cluster_mean_kernel(const _Float16 *__res
         for (int j = 0; j < 8; ++j) acc[j] += (float)b[j];
     }
     if (m < n) {
-        const h8 a = *reinterpret_cast<const h8 *>(rows + (size_t)mem[m] * D + piece * 8);
+        const h8 a = *reinterpret_cast<const h8 *>(rows + (size_t)member(m) * D + piece * 8);
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] += (float)a[j];
     }
@@ -333,7 +336,7 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const _Float16 *__rest
     if (i >= L) return;
     const _Float16 *src = blockIdx.z ? src1 : src0;
     _Float16 *dst = blockIdx.z ? dst1 : dst0;
-    const int k = perm[(size_t)h * L + i];
+    const int k = min(max(perm[(size_t)h * L + i], 0), L - 1);
     *reinterpret_cast<h8 *>(dst + ((size_t)h * L + i) * D + piece * 8) =
         *reinterpret_cast<const h8 *>(src + ((size_t)h * L + k) * D + piece * 8);
 }
@@ -352,11 +355,21 @@ hipError_t launch_normalize_rows(const void *K, void *X, size_t rows, hipStream_
     return hipGetLastError();
 }
 
+// Stable grouping of the rows by centre id: sizes, offsets and the member list of every centre.
+static void launch_group(const int32_t *assign, int32_t *sizes, int32_t *offsets, int32_t *perm, int32_t *hist, int H,
+                         int L, int C, hipStream_t s)
+{
+    const int PL = kmeans_part_len(L), P = (L + PL - 1) / PL;
+    hipLaunchKernelGGL(kmeans_hist_kernel, dim3(P, H), dim3(256), (size_t)C * 4, s, assign, hist, L, C, PL, P);
+    hipLaunchKernelGGL(kmeans_scan_kernel, dim3(H), dim3(1024), 0, s, hist, sizes, offsets, L, C, P);
+    hipLaunchKernelGGL(kmeans_scatter_kernel, dim3(P, H), dim3(64), (size_t)C * 4, s, assign, (const int32_t *)hist,
+                       (const int32_t *)offsets, perm, L, C, PL, P);
+}
+
 hipError_t launch_kmeans_step(const void *X, const void *centers_in, void *centers_out, int32_t *assign,
                               int32_t *sizes, int32_t *offsets, int32_t *perm, float *hn, int32_t *hist, int H, int L,
                               int C, hipStream_t s)
 {
-    const int PL = kmeans_part_len(L), P = (L + PL - 1) / PL;
     hipLaunchKernelGGL(half_norm_kernel, dim3((H * C + 3) / 4), dim3(256), 0, s, (const _Float16 *)centers_in, hn, H * C);
     const dim3 grid_a((L + KM_ROWS_PER_WG - 1) / KM_ROWS_PER_WG, H);
     hipEvent_t ev0, ev1;
@@ -366,14 +379,57 @@ hipError_t launch_kmeans_step(const void *X, const void *centers_in, void *cente
     else
         hipLaunchKernelGGL(kmeans_assign_kernel, grid_a, dim3(256), 0, s, (const _Float16 *)X,
                            (const _Float16 *)centers_in, (const float *)hn, assign, L, C);
-    hipLaunchKernelGGL(kmeans_hist_kernel, dim3(P, H), dim3(256), (size_t)C * 4, s, (const int32_t *)assign, hist, L, C,
-                       PL, P);
-    hipLaunchKernelGGL(kmeans_scan_kernel, dim3(H), dim3(1024), 0, s, hist, sizes, offsets, L, C, P);
-    hipLaunchKernelGGL(kmeans_scatter_kernel, dim3(P, H), dim3(64), (size_t)C * 4, s, (const int32_t *)assign,
-                       (const int32_t *)hist, (const int32_t *)offsets, perm, L, C, PL, P);
+    launch_group(assign, sizes, offsets, perm, hist, H, L, C, s);
     hipLaunchKernelGGL(cluster_mean_kernel, dim3(C, H), dim3(256), 0, s, (const _Float16 *)X, (const int32_t *)perm,
                        (const int32_t *)sizes, (const int32_t *)offsets, (const _Float16 *)centers_in,
                        (_Float16 *)centers_out, L, C);
+    return hipGetLastError();
+}
+
+// Nesting fine clusters under coarse ones (Section 3.3: the coarse level is a clustering of the fine centroids).
+// perm_coarse lists the fine cluster ids grouped by coarse cluster; the fine clusters are renumbered in that order
+// (inv[old id] = new id), every key's cluster id is translated, and the keys are grouped again.
+__global__ __launch_bounds__(256) void invert_perm_kernel(const int32_t *__restrict__ perm, int32_t *__restrict__ inv,
+                                                          int n)
+{
+    const int h = blockIdx.y, j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= n) return;
+    const int f = perm[(size_t)h * n + j];
+    if ((unsigned)f < (unsigned)n) inv[(size_t)h * n + f] = j;     // (a value out of range is ignored)
+}
+
+__global__ __launch_bounds__(256) void relabel_kernel(const int32_t *__restrict__ assign, const int32_t *__restrict__ inv,
+                                                      int32_t *__restrict__ assign_new, int L, int C)
+{
+    const int h = blockIdx.y, k = blockIdx.x * 256 + threadIdx.x;
+    if (k >= L) return;
+    const int a = min(max(assign[(size_t)h * L + k], 0), C - 1);        // ids are clamped into range, so that malformed
+    assign_new[(size_t)h * L + k] = min(max(inv[(size_t)h * C + a], 0), C - 1);   // input cannot index out of bounds later
+}
+
+// Keys under each coarse cluster: its children are fine clusters child_offsets[j] .. child_offsets[j+1]-1.
+__global__ __launch_bounds__(256) void coarse_sizes_kernel(const int32_t *__restrict__ offsets_fine,
+                                                           const int32_t *__restrict__ child_offsets,
+                                                           int32_t *__restrict__ sizes_coarse, int C1, int C2)
+{
+    const int h = blockIdx.y, j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= C1) return;
+    const int32_t *co = child_offsets + (size_t)h * (C1 + 1), *of = offsets_fine + (size_t)h * (C2 + 1);
+    const int lo = min(max(co[j], 0), C2), hi = min(max(co[j + 1], lo), C2);
+    sizes_coarse[(size_t)h * C1 + j] = of[hi] - of[lo];
+}
+
+hipError_t launch_cluster_nest(const int32_t *assign_fine, const int32_t *perm_coarse, const int32_t *child_offsets,
+                               int32_t *assign_new, int32_t *sizes, int32_t *offsets, int32_t *perm,
+                               int32_t *sizes_coarse, int32_t *inv, int32_t *hist, int H, int L, int C2, int C1,
+                               hipStream_t s)
+{
+    hipLaunchKernelGGL(invert_perm_kernel, dim3((C2 + 255) / 256, H), dim3(256), 0, s, perm_coarse, inv, C2);
+    hipLaunchKernelGGL(relabel_kernel, dim3((L + 255) / 256, H), dim3(256), 0, s, assign_fine, (const int32_t *)inv,
+                       assign_new, L, C2);
+    launch_group(assign_new, sizes, offsets, perm, hist, H, L, C2, s);
+    hipLaunchKernelGGL(coarse_sizes_kernel, dim3((C1 + 255) / 256, H), dim3(256), 0, s, (const int32_t *)offsets,
+                       child_offsets, sizes_coarse, C1, C2);
     return hipGetLastError();
 }
 
@@ -381,8 +437,9 @@ hipError_t launch_cluster_layout(const void *K, const void *V, const int32_t *pe
                                  const int32_t *offsets, void *K_sorted, void *V_sorted, void *centroids, int H, int L,
                                  int C, hipStream_t s)
 {
-    hipLaunchKernelGGL(gather_rows_kernel, dim3((L + 15) / 16, H, 2), dim3(256), 0, s, (const _Float16 *)K,
-                       (_Float16 *)K_sorted, (const _Float16 *)V, (_Float16 *)V_sorted, perm, L);
+    if (K_sorted)                                             // (V_sorted == NULL: keys only)
+        hipLaunchKernelGGL(gather_rows_kernel, dim3((L + 15) / 16, H, V_sorted ? 2 : 1), dim3(256), 0, s,
+                           (const _Float16 *)K, (_Float16 *)K_sorted, (const _Float16 *)V, (_Float16 *)V_sorted, perm, L);
     hipLaunchKernelGGL(cluster_mean_kernel, dim3(C, H), dim3(256), 0, s, (const _Float16 *)K, perm, sizes, offsets,
                        (const _Float16 *)nullptr, (_Float16 *)centroids, L, C);
     return hipGetLastError();

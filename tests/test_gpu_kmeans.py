@@ -240,3 +240,88 @@ def test_full_size_iteration_on_sampled_keys_and_centres(sq):
             mem = pn[h][on[h][c]:on[h][c + 1]]
             ref = X[h][mem].astype(np.float64).mean(0) if len(mem) else cent[h][c].astype(np.float64)
             assert np.abs(cn[h][c].astype(np.float64) - ref).max() <= UNIT_ATOL
+
+
+def test_two_level_hierarchy_built_on_the_gpu_feeds_the_hierarchical_lookup(sq, oracle):
+    """Keys -> fine K-means -> K-means of the fine centroids -> nesting -> layouts, all through the C ABI; every array
+    against the oracle's composition of the same steps, then sq_hier_decode_step on the result against the oracle's
+    two-level lookup and sparse attention on the same arrays."""
+    from test_gpu_hier import check_hier_selection
+    from gpu_util import ranges_from_keep
+    H, L, C2, C1, U = 2, 12000, 160, 12, 40
+    K, V, init = wl.clustering_input(21, H, L, C2, mix=48)
+    _, _, init1 = wl.clustering_input(22, H, C2, C1)             # (only the seeding indices are used)
+    i32 = lambda *s: torch.empty(s, dtype=torch.int32, device=DEV)
+    f16 = lambda *s: torch.empty(s, dtype=torch.float16, device=DEV)
+    sh = sq.make_shape(1, H, L, C2, 1, U, 1.0 / np.sqrt(128))
+    ws = sq.workspace(sh, sq.SQ_CALL_KMEANS_STEP, DEV)
+    Kg, Vg = t(K), t(V)
+    Xg = torch.empty_like(Kg)
+    sq.sq_kmeans_normalize(sh, Kg, Xg)
+    cg = torch.stack([Xg[h][t(init[h]).long()] for h in range(H)]).contiguous()
+    a2, n2, o2, p2 = i32(H, L), i32(H, C2), i32(H, C2 + 1), i32(H, L)
+    for _ in range(3):
+        sq.sq_kmeans_step(sh, Xg, cg, cg, a2, n2, o2, p2, ws)
+    cent2_old = f16(H, C2, 128)
+    sq.sq_cluster_layout(sh, Kg, None, p2, n2, o2, None, None, cent2_old)
+    # coarse level: K-means of the (normalised) fine centroids
+    shc = sq.make_shape(1, H, C2, C1, 1, 0, 1.0)
+    wsc = sq.workspace(shc, sq.SQ_CALL_KMEANS_STEP, DEV)
+    X2 = torch.empty_like(cent2_old)
+    sq.sq_kmeans_normalize(shc, cent2_old, X2)
+    c1g = torch.stack([X2[h][t(init1[h]).long()] for h in range(H)]).contiguous()
+    a1, fan, co, p1 = i32(H, C2), i32(H, C1), i32(H, C1 + 1), i32(H, C2)
+    for _ in range(3):
+        sq.sq_kmeans_step(shc, X2, c1g, c1g, a1, fan, co, p1, wsc)
+    # nesting and layouts
+    an, n2n, o2n, p2n, n1 = i32(H, L), i32(H, C2), i32(H, C2 + 1), i32(H, L), i32(H, C1)
+    sq.sq_cluster_nest(sh, C1, a2, p1, co, an, n2n, o2n, p2n, n1, ws)
+    Ks, Vs, cent2 = torch.empty_like(Kg), torch.empty_like(Vg), f16(H, C2, 128)
+    sq.sq_cluster_layout(sh, Kg, Vg, p2n, n2n, o2n, Ks, Vs, cent2)
+    cent1 = f16(H, C1, 128)
+    sq.sq_cluster_layout(shc, cent2, None, None, fan, co, None, None, cent1)
+    torch.cuda.synchronize()
+    g = {k: v.cpu().numpy() for k, v in dict(a2=a2, a1=a1, p1=p1, co=co, fan=fan, an=an, n2=n2n, o2=o2n, p2=p2n, n1=n1,
+                                             Ks=Ks, Vs=Vs, c2=cent2, c1=cent1).items()}
+    for h in range(H):
+        an_ref, n2_ref, o2_ref, p2_ref, n1_ref = ocl.nest(g["a2"][h], g["p1"][h], g["co"][h], C2)
+        for name, ref in (("an", an_ref), ("n2", n2_ref), ("o2", o2_ref), ("p2", p2_ref), ("n1", n1_ref)):
+            np.testing.assert_array_equal(g[name][h], ref, err_msg=f"{name} head {h}")
+        np.testing.assert_array_equal(g["Ks"][h], K[h][p2_ref])
+        np.testing.assert_array_equal(g["Vs"][h], V[h][p2_ref])
+        _, _, _, c2_ref = ocl.layout(K[h], an_ref, C2)
+        np.testing.assert_allclose(g["c2"][h].astype(np.float64), c2_ref.astype(np.float64), rtol=1.1e-3, atol=1e-6)
+        for j in range(C1):                                      # coarse centroid = unweighted mean of its children
+            ch = g["c2"][h][g["co"][h][j]:g["co"][h][j + 1]].astype(np.float64)
+            ref = ch.mean(0) if len(ch) else np.zeros(128)
+            np.testing.assert_allclose(g["c1"][h][j].astype(np.float64), ref, rtol=1.1e-3, atol=1e-6)
+        assert g["n1"][h].sum() == L and (np.diff(g["co"][h]) == g["fan"][h]).all()
+    # the hierarchical decode step on the GPU-made arrays
+    rng = np.random.default_rng(23)
+    pick = rng.integers(0, C2, H)
+    q = (np.stack([g["c2"][h][pick[h]] for h in range(H)])[None, :, None, :].astype(np.float32)
+         + 0.3 * rng.standard_normal((1, H, 1, 128))).astype(np.float16)
+    Ku = rng.standard_normal((1, H, U, 128)).astype(np.float16)
+    Vu = rng.standard_normal((1, H, U, 128)).astype(np.float16)
+    T1 = np.full(H, 0.5 / L, np.float32)
+    T2 = np.full(H, 1.0 / L, np.float32)
+    sm = float(sh.sm_scale)
+    out, lse = f16(1, H, 1, 128), torch.empty(1, H, 1, dtype=torch.float32, device=DEV)
+    m2, nk = torch.zeros(1, H, (C2 + 31) // 32, dtype=torch.int32, device=DEV), i32(1, H, 1)
+    sq.sq_hier_decode_step(sh, C1, t(q), cent1, n1, co, t(T1), cent2, n2n, o2n, t(T2), Ks, Vs, t(Ku), t(Vu), out, lse,
+                           m2, nk, sq.workspace(sh, sq.SQ_CALL_HIER_DECODE_STEP, DEV))
+    from test_gpu_hier import run_hier_select
+    _, tt = run_hier_select(sq, 1, H, C1, C2, L, q[:, :, 0], g["c1"], g["n1"], g["co"], T1, g["c2"], g["n2"], g["o2"], T2,
+                            sm, U=U)
+    assert torch.equal(tt["m2"], m2) and torch.equal(tt["nk"], nk)
+    ref = oracle.hier_select(q[:, :, 0], g["c1"], g["n1"], g["co"], T1, g["c2"], g["n2"], g["o2"], T2, sm)
+    g2, _ = check_hier_selection(q[:, :, 0], g["c1"], g["n1"], g["co"], T1, g["c2"], g["n2"], g["o2"], T2, sm, ref, tt,
+                                 "gpu-built hierarchy")
+    assert 0 < int(nk.sum()) < H * L
+    cap = int(g2.sum(-1).max()) + 1
+    ranges = np.zeros((1, H, 1, cap, 2), np.int32)
+    nr = np.zeros((1, H, 1), np.int32)
+    for h in range(H):
+        ranges[0, h, 0], nr[0, h, 0] = ranges_from_keep(g2[0, h], g["o2"][h], g["n2"][h], cap)
+    ro, _ = oracle.sparse_attn(q, g["Ks"], g["Vs"], ranges, nr, Ku, Vu, sm)
+    assert np.abs(out.cpu().numpy().astype(np.float64) - ro).max() <= 2e-3

@@ -74,3 +74,30 @@ def test_layout_groups_keys_by_cluster_and_averages_raw_keys():
         if len(seg):
             np.testing.assert_allclose(cent[c].astype(np.float64), K[seg].astype(np.float64).mean(0), atol=4e-3)
     assert (cent[7] == 0).all()
+
+
+def test_nesting_keeps_every_key_under_the_coarse_cluster_of_its_fine_cluster():
+    rng = np.random.default_rng(930)
+    L, C2, C1 = 3000, 60, 7
+    a_fine = rng.integers(0, C2, L).astype(np.int32)
+    a_coarse = rng.integers(0, C1, C2).astype(np.int32)          # coarse cluster of each fine cluster
+    a_coarse[a_coarse == 4] = 3                                  # coarse cluster 4 has no children
+    perm_c, fan, co, _ = cl.layout(np.zeros((C2, 2), np.float16), a_coarse, C1)
+    a_new, sizes, offsets, perm, sizes_c = cl.nest(a_fine, perm_c, co, C2)
+    parent_new = np.searchsorted(co, a_new, side="right") - 1    # coarse cluster whose child range holds the new id
+    np.testing.assert_array_equal(parent_new, a_coarse[a_fine])
+    np.testing.assert_array_equal(sizes_c, np.bincount(a_coarse[a_fine], minlength=C1))
+    assert sizes_c[4] == 0 and sizes_c.sum() == L
+    np.testing.assert_array_equal(sizes[a_new[:50]], np.bincount(a_fine, minlength=C2)[a_fine[:50]])   # same clusters, renamed
+    for c in range(C2):
+        seg = perm[offsets[c]:offsets[c + 1]]
+        assert (a_new[seg] == c).all() and (np.diff(seg) > 0).all()
+
+
+def test_nesting_by_hand():
+    # 4 fine clusters; coarse 0 = {fine 2, fine 0}, coarse 1 = {fine 3, fine 1} (perm_coarse order)
+    a_new, sizes, offsets, perm, sizes_c = cl.nest(np.array([0, 1, 2, 3, 3, 0]), np.array([2, 0, 3, 1]),
+                                                   np.array([0, 2, 4]), 4)
+    assert a_new.tolist() == [1, 3, 0, 2, 2, 1]
+    assert sizes.tolist() == [1, 2, 2, 1] and offsets.tolist() == [0, 1, 3, 5, 6]
+    assert perm.tolist() == [2, 0, 5, 3, 4, 1] and sizes_c.tolist() == [3, 3]
