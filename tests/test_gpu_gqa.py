@@ -127,3 +127,21 @@ def test_llama3_shape_gqa_decode_32k(sq):
                                       threads=16), oracle.scores)
     err = against_oracle(sq, w, G, "gqa-32k")
     print("gqa 32k attention max-abs err", err, flush=True)
+
+
+def test_group_averaged_selection_llama3_shape(sq):
+    """The aggregation the paper leaves as future work for grouped-query attention: ONE kept set per K/V head from the
+    scores averaged over its query heads.  That is the selection on averaged scores with the group's query heads in
+    the place of the query tokens (non-causal user keys), so it runs through sq_prefill_mean_step unchanged:
+    q [B, H_kv, G, d].  Llama-3.1-8B shape, 32 query heads over 8 K/V heads, 32K fixed context, keep 1/8."""
+    from tests.test_gpu_prefill import compare_prefill_mean, mean_thresholds, run_prefill_mean_step
+    print("gqa group-averaged 32k: generating", flush=True)
+    w = wl.make_workload("gqa_avg_32k", B=1, H=8, L=32768, C=1024, Lq=4, U=512, keep_frac=1 / 8, seed=1, threads=16,
+                         causal_user=False)
+    w.thresh, stats = mean_thresholds(oracle, w)
+    P = sq.upload(w)
+    got = run_prefill_mean_step(sq, w, P)
+    err = compare_prefill_mean(oracle, w, P, got, stats, "gqa-avg-32k")
+    keep = got[3].mean() / w.L
+    print("gqa group-averaged attention max-abs err", err, "keep", keep, flush=True)
+    assert 0.02 < keep < 0.6
