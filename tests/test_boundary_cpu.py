@@ -68,3 +68,30 @@ def test_host_side_validation(sq):
     assert rc == sq.SQ_ERR_WORKSPACE
     rc = L.sq_decode_step(C.byref(sh), *([aligned] * 13), aligned, 16, None)
     assert rc == sq.SQ_ERR_WORKSPACE and b"needed" in L.sq_last_error()
+
+
+def test_host_side_validation_of_the_offline_calls(sq):
+    L = sq.lib()
+    buf = (C.c_char * 4096)()
+    aligned = C.c_void_p((C.cast(buf, C.c_void_p).value + 255) & ~255)
+    sh = sq.make_shape(1, 2, 64, 4, 1, 0, 1.0)
+    assert sq.workspace_bytes(sh, sq.SQ_CALL_KMEANS_STEP) > 0 and sq.workspace_bytes(sh, sq.SQ_CALL_CALIBRATE) > 0
+    rc = L.sq_kmeans_step(C.byref(sh), None, *([aligned] * 6), aligned, 1 << 30, None)
+    assert rc == sq.SQ_ERR_INVALID_ARG and b"X is NULL" in L.sq_last_error()
+    more = sq.make_shape(1, 2, 3, 4, 1, 0, 1.0)                  # more centres than keys
+    rc = L.sq_kmeans_step(C.byref(more), *([aligned] * 7), aligned, 1 << 30, None)
+    assert rc == sq.SQ_ERR_INVALID_ARG and b"more centres" in L.sq_last_error()
+    rc = L.sq_kmeans_step(C.byref(sh), *([aligned] * 7), aligned, 16, None)
+    assert rc == sq.SQ_ERR_WORKSPACE
+    rc = L.sq_cluster_layout(C.byref(sh), aligned, aligned, aligned, aligned, aligned, aligned, aligned, aligned, None)
+    assert rc == sq.SQ_ERR_INVALID_ARG and b"alias" in L.sq_last_error()
+    other = C.c_void_p(aligned.value + 1024)
+    rc = L.sq_cluster_layout(C.byref(sh), aligned, None, None, aligned, aligned, other, None, aligned, None)
+    assert rc == sq.SQ_ERR_INVALID_ARG and b"needs perm" in L.sq_last_error()
+    rc = L.sq_cluster_nest(C.byref(sh), 9, *([aligned] * 8), aligned, 1 << 30, None)
+    assert rc == sq.SQ_ERR_INVALID_ARG and b"C1" in L.sq_last_error()
+    rc = L.sq_calibrate_threshold(C.byref(sh), *([aligned] * 4), -1, aligned, aligned, 1 << 30, None)
+    assert rc == sq.SQ_ERR_INVALID_ARG and b"negative" in L.sq_last_error()
+    big = sq.make_shape(64, 2, 1 << 19, 4, 64, 0, 1.0)           # B * Lq * L = 2^31 pooled keys
+    rc = L.sq_calibrate_threshold(C.byref(big), *([aligned] * 4), 5, aligned, aligned, 1 << 40, None)
+    assert rc == sq.SQ_ERR_UNSUPPORTED and b"calibration queries" in L.sq_last_error()
