@@ -140,6 +140,48 @@ def hier_select(q, centroids1, sizes1, child_offsets, thresh1, centroids2, sizes
     return out
 
 
+def hier_select_mean(q, centroids1, sizes1, child_offsets, thresh1, centroids2, sizes2, offsets2, thresh2, sm_scale):
+    """Two-level lookup with the prefill rule (Appendix D: scores averaged over the Lq query tokens) at both levels
+    (Section 3.3): level 1 keeps coarse clusters by their averaged Eq. 2 scores; level 2 scores the children of the
+    kept coarse clusters per token with the normaliser over those children only (Eq. 3), averages over the tokens and
+    keeps by T2.  Composed from centroid_score and select_mean, the candidates' arrays being cut out per (b, h).
+    q [B,H,Lq,d] -> dict(mask1 [B,H,C1] bool, mask2 [B,H,C2] bool, ranges [B,H,C2,2], n_ranges, n_keys [B,H])."""
+    q = _f16(q)
+    B, H, Lq, d = q.shape
+    centroids1, centroids2 = _f16(centroids1), _f16(centroids2)
+    sizes1, child_offsets, sizes2, offsets2 = _i32(sizes1), _i32(child_offsets), _i32(sizes2), _i32(offsets2)
+    thresh1, thresh2 = _f32(thresh1), _f32(thresh2)
+    C1, C2 = centroids1.shape[1], centroids2.shape[1]
+    x1, m1, D1 = centroid_score(q, centroids1, sizes1, sm_scale)
+    fan = np.diff(child_offsets, axis=1).astype(np.int32)
+    # level 1: only the mask matters (clusters with no keys underneath are never kept)
+    mk1 = select_mean(x1, m1, D1, thresh1, sizes1, child_offsets)[0]
+    mask1 = ((mk1[..., :, None] >> np.arange(32, dtype=np.uint32)) & 1).reshape(B, H, -1)[..., :C1].astype(bool)
+    mask2 = np.zeros((B, H, C2), bool)
+    ranges = np.zeros((B, H, C2, 2), np.int32)
+    n_ranges = np.zeros((B, H), np.int32)
+    n_keys = np.zeros((B, H), np.int32)
+    for b in range(B):
+        for h in range(H):
+            cand = np.concatenate([np.arange(child_offsets[h, j], child_offsets[h, j + 1])
+                                   for j in np.flatnonzero(mask1[b, h])] + [np.zeros(0, np.int64)]).astype(np.int64)
+            if len(cand) == 0:
+                continue
+            cc, cs = np.ascontiguousarray(centroids2[h][cand][None]), np.ascontiguousarray(sizes2[h][cand][None])
+            x2, m2, D2 = centroid_score(q[b:b + 1, h:h + 1], cc, cs, sm_scale)
+            co = np.zeros((1, len(cand) + 1), np.int32)
+            mk2 = select_mean(x2, m2, D2, thresh2[h:h + 1], cs, co)[0]
+            kept = ((mk2[0, 0][:, None] >> np.arange(32, dtype=np.uint32)) & 1).reshape(-1)[:len(cand)].astype(bool)
+            ids = cand[kept]
+            mask2[b, h, ids] = True
+            n_ranges[b, h] = len(ids)
+            ranges[b, h, :len(ids), 0] = offsets2[h, ids]
+            ranges[b, h, :len(ids), 1] = sizes2[h, ids]
+            n_keys[b, h] = sizes2[h, ids].sum()
+    del fan
+    return dict(mask1=mask1, mask2=mask2, ranges=ranges, n_ranges=n_ranges, n_keys=n_keys)
+
+
 def multilevel_select(q, levels, sm_scale):
     """Lookup through n >= 1 levels of centroids, coarsest first (Section 3.3, level after level).
 

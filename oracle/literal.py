@@ -69,6 +69,26 @@ def hier_select(q, centroids1, sizes1, child_offsets, T1, centroids2, sizes2, T2
     return keep1, keep2, S1, S2
 
 
+def hier_select_mean(q, centroids1, sizes1, child_offsets, T1, centroids2, sizes2, T2, sm_scale):
+    """The prefill rule of Appendix D applied level by level (Section 3.3) for one head, q [Lq, d]: the coarse
+    scores of Eq. 2 averaged over the query tokens pick the coarse clusters; the fine scores of Eq. 3 -- per token,
+    normalised over the children of the kept coarse clusters only -- are averaged over the tokens and compared with T2.
+    Returns (keep1 [C1] bool, keep2 [C2] bool, mean S1 [C1], mean S2 [C2] with NaN outside the candidates)."""
+    keep1, S1 = select_mean(q, centroids1, sizes1, T1, sm_scale)
+    C2 = len(sizes2)
+    cand = np.zeros(C2, dtype=bool)
+    for j in np.flatnonzero(keep1):
+        cand[child_offsets[j]:child_offsets[j + 1]] = True
+    S2 = np.full(C2, np.nan)
+    keep2 = np.zeros(C2, dtype=bool)
+    idx = np.flatnonzero(cand)
+    if len(idx):
+        k2, s2 = select_mean(q, np.asarray(centroids2)[idx], np.asarray(sizes2)[idx], T2, sm_scale)
+        S2[idx] = s2
+        keep2[idx] = k2
+    return keep1, keep2, S1, S2
+
+
 def dense_attention(q, K, V, sm_scale):
     """Textbook softmax(sm_scale * q K^T) V for one query set: q [nq,d], K,V [n,d] -> out [nq,d], lse [nq]."""
     q = np.asarray(q, dtype=np.float64)
