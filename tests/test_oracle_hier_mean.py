@@ -32,8 +32,8 @@ def test_closed_form_two_tokens(oracle):
     r = oracle.hier_select_mean(q, c1, N1, co, T(0.26), c2, N2, off2, T(0.1), LN2)
     assert not r["mask1"][0, 0].any() and not r["mask2"][0, 0].any() and r["n_keys"][0, 0] == 0
     k1, k2, S1, S2 = literal.hier_select_mean(q[0, 0], c1[0], N1[0], co[0], 0.2, c2[0], N2[0], 0.2, LN2)
-    np.testing.assert_allclose(S1, [0.25, 0.25], rtol=1e-12)
-    np.testing.assert_allclose(S2, np.array([17, 5, 17, 5]) / 44, rtol=1e-12)
+    np.testing.assert_allclose(S1, [0.25, 0.25], rtol=1e-7)
+    np.testing.assert_allclose(S2, np.array([17, 5, 17, 5]) / 44, rtol=1e-7)     # (ln 2 is an fp32 constant here)
 
 
 @pytest.mark.parametrize("seed", range(3))
