@@ -61,7 +61,8 @@ typedef enum sq_call {
     SQ_CALL_MULTILEVEL_SELECT = 12,
     SQ_CALL_MULTILEVEL_DECODE_STEP = 13,
     SQ_CALL_KMEANS_STEP = 14,
-    SQ_CALL_CALIBRATE = 15
+    SQ_CALL_CALIBRATE = 15,
+    SQ_CALL_HIER_PREFILL_MEAN_STEP = 16
 } sq_call;
 
 /*
@@ -328,6 +329,23 @@ int sq_multilevel_decode_step(const sq_shape_t *shape, int32_t n_levels, const s
                               const void *K_fixed, const void *V_fixed, const void *K_user, const void *V_user,
                               void *out, float *lse, uint32_t *keep_mask, int32_t *n_keys,
                               void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Prefill through the two-level lookup (Section 3.3; the paper builds the hierarchy for generation only), with the
+ * paper's prefill rule (Appendix D, "Prefill Stage": scores averaged over the Lq query tokens, ONE kept set per
+ * (sequence, head)) at both levels: the coarse scores of Eq. 2 averaged over the tokens select coarse clusters by
+ * thresh1; the fine scores of Eq. 3 -- per token, normaliser over the children of the kept coarse clusters only --
+ * are averaged over the tokens and compared with thresh2; attention as in sq_sparse_attn_prefill_shared on the kept
+ * fine clusters' keys.  Arguments as sq_hier_decode_step, with q f16 [B,H,Lq,d], out f16 [B,H,Lq,d],
+ * lse f32 [B,H,Lq] (or NULL), keep_mask2 u32 [B,H,ceil(C/32)] and n_keys i32 [B,H] (optional outputs).
+ * Workspace: sq_workspace_bytes(shape, SQ_CALL_HIER_PREFILL_MEAN_STEP).
+ */
+int sq_hier_prefill_mean_step(const sq_shape_t *shape, int32_t C1, const void *q,
+                              const void *centroids1, const int32_t *sizes1, const int32_t *child_offsets,
+                              const float *thresh1, const void *centroids2, const int32_t *sizes2,
+                              const int32_t *offsets2, const float *thresh2, const void *K_fixed, const void *V_fixed,
+                              const void *K_user, const void *V_user, void *out, float *lse, uint32_t *keep_mask2,
+                              int32_t *n_keys, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Offline clustering of the fixed-context keys (Section 3.1: K-means on normalised key vectors; the centroid of a

@@ -311,6 +311,29 @@ PrefillMeanStepWs carve_prefill_mean_step(Carver &cv, const sq_shape_t *sh)
     return w;
 }
 
+// Workspace of the hierarchical prefill step on averaged scores: the one-level step's, plus the records of the kept
+// coarse clusters' child ranges and the candidate list they expand to.
+struct HierPrefillMeanWs {
+    PrefillMeanStepWs step;
+    sq::DecodePlan cand;
+    int32_t *cand_id, *nr1, *nk1;
+};
+
+HierPrefillMeanWs carve_hier_prefill_mean(Carver &cv, const sq_shape_t *sh)
+{
+    const size_t rows = (size_t)sh->B * sh->H;
+    HierPrefillMeanWs w{};
+    w.step = carve_prefill_mean_step(cv, sh);
+    w.cand.rec_cap = sh->C;
+    w.cand.L = sh->C;
+    w.cand.rec = cv.take<int4>(rows * sh->C);
+    w.cand.hdr = cv.take<int2>(rows);
+    w.cand_id = cv.take<int32_t>(rows * sh->C);
+    w.nr1 = cv.take<int32_t>(rows);
+    w.nk1 = cv.take<int32_t>(rows);
+    return w;
+}
+
 int check_ws(const char *fn, const sq_shape_t *sh, int which, void *ws, size_t ws_bytes)
 {
     const size_t need = sq_workspace_bytes(sh, which);
@@ -375,6 +398,9 @@ size_t sq_workspace_bytes(const sq_shape_t *sh, int which)
         return cv.off;
     case SQ_CALL_KMEANS_STEP:
         carve_kmeans(cv, sh);
+        return cv.off;
+    case SQ_CALL_HIER_PREFILL_MEAN_STEP:
+        carve_hier_prefill_mean(cv, sh);
         return cv.off;
     case SQ_CALL_CALIBRATE:
         cv.take<float>((size_t)sh->B * sh->H * sh->Lq * sh->C);
@@ -915,6 +941,67 @@ int sq_hier_decode_step(const sq_shape_t *sh, int32_t C1, const void *q, const v
         return rc;
     SQ_HIP(sq::launch_decode_attn(q, K_fixed, V_fixed, K_user, V_user, w.dec.plan, w.dec.partials, out, lse,
                                   to_shape(sh), s));
+    g_err[0] = 0;
+    return SQ_OK;
+}
+
+int sq_hier_prefill_mean_step(const sq_shape_t *sh, int32_t C1, const void *q, const void *centroids1,
+                              const int32_t *sizes1, const int32_t *child_offsets, const float *thresh1,
+                              const void *centroids2, const int32_t *sizes2, const int32_t *offsets2,
+                              const float *thresh2, const void *K_fixed, const void *V_fixed, const void *K_user,
+                              const void *V_user, void *out, float *lse, uint32_t *keep_mask2, int32_t *n_keys, void *ws,
+                              size_t ws_bytes, void *stream)
+{
+    if (int rc = check_shape(sh, __func__, false)) return rc;
+    if (int rc = check_hier_args(__func__, sh, C1)) return rc;
+    SQ_REQUIRE_PTR(q);
+    SQ_REQUIRE_PTR(centroids1);
+    SQ_REQUIRE_PTR(sizes1);
+    SQ_REQUIRE_PTR(child_offsets);
+    SQ_REQUIRE_PTR(thresh1);
+    SQ_REQUIRE_PTR(centroids2);
+    SQ_REQUIRE_PTR(sizes2);
+    SQ_REQUIRE_PTR(offsets2);
+    SQ_REQUIRE_PTR(thresh2);
+    SQ_REQUIRE_PTR(K_fixed);
+    SQ_REQUIRE_PTR(V_fixed);
+    if (sh->U > 0) {
+        SQ_REQUIRE_PTR(K_user);
+        SQ_REQUIRE_PTR(V_user);
+    }
+    SQ_REQUIRE_PTR(out);
+    SQ_OPTIONAL_PTR(lse);
+    SQ_OPTIONAL_PTR(keep_mask2);
+    SQ_OPTIONAL_PTR(n_keys);
+    if (int rc = check_ws(__func__, sh, SQ_CALL_HIER_PREFILL_MEAN_STEP, ws, ws_bytes)) return rc;
+    if (int rc = check_device(__func__)) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Carver cv(ws);
+    HierPrefillMeanWs w = carve_hier_prefill_mean(cv, sh);
+    const int rows = sh->B * sh->H;
+    sq::SelectOpts opt{};
+    opt.mean_parts = sq::lookup_parts_for(sh->Lq);
+    opt.mean_div = (float)sh->Lq;
+    // Level 1 (Eq. 2 averaged over the tokens): the kept coarse clusters' child ranges become records ...
+    SQ_HIP(sq::launch_prefill_lookup(q, centroids1, sizes1, thresh1, nullptr, nullptr, nullptr, w.step.part_sum, true,
+                                     sh->B, sh->H, sh->Lq, C1, sh->sm_scale, s));
+    sq::SelectOpts opt1 = opt;
+    opt1.len_from_offsets = 1;
+    SQ_HIP(sq::launch_select(w.step.part_sum, nullptr, nullptr, true, thresh1, sizes1, child_offsets, nullptr, nullptr,
+                             w.nr1, w.nk1, w.cand, false, 0, opt1, rows, sh->H, 1, C1, s));
+    // ... which expand to the list of candidate fine clusters of each (sequence, head).
+    SQ_HIP(sq::launch_expand_ranges(w.cand, w.cand_id, rows, sh->C, s));
+    // Level 2 (Eq. 3 per token over the candidates, averaged over the tokens): scores and selection in candidate order.
+    SQ_HIP(sq::launch_prefill_lookup(q, centroids2, sizes2, thresh2, nullptr, nullptr, nullptr, w.step.part_sum, true,
+                                     sh->B, sh->H, sh->Lq, sh->C, sh->sm_scale, s, w.cand_id, w.cand.hdr));
+    sq::SelectOpts opt2 = opt;
+    opt2.cand_id = w.cand_id;
+    opt2.cand_hdr = w.cand.hdr;
+    SQ_HIP(sq::launch_select(w.step.part_sum, nullptr, nullptr, true, thresh2, sizes2, offsets2, keep_mask2, nullptr,
+                             w.step.n_ranges, n_keys ? n_keys : w.step.n_keys, w.step.att.plan, false, 0, opt2, rows,
+                             sh->H, 1, sh->C, s));
+    SQ_HIP(sq::launch_prefill_attn_shared(q, K_fixed, V_fixed, K_user, V_user, w.step.att.plan, w.step.att.key_idx, out,
+                                          lse, to_shape(sh), s));
     g_err[0] = 0;
     return SQ_OK;
 }

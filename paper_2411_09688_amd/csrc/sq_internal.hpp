@@ -67,7 +67,13 @@ constexpr int LOOKUP_ROWS = 16;
 __host__ __device__ inline int lookup_parts_for(int Lq) { return (Lq + LOOKUP_ROWS - 1) / LOOKUP_ROWS; }
 hipError_t launch_prefill_lookup(const void *q, const void *centroids, const int32_t *sizes, const float *thresh,
                                  uint32_t *keep_mask, int32_t *n_ranges, int32_t *n_keys, float *part_sum, bool mean,
-                                 int B, int H, int Lq, int C, float sm_scale, hipStream_t s);
+                                 int B, int H, int Lq, int C, float sm_scale, hipStream_t s,
+                                 const int32_t *cand_id = nullptr, const int2 *cand_hdr = nullptr);
+// (cand_id [B*H, C] / cand_hdr [B*H] given, with mean: only the hdr.y candidates listed for a (sequence, head) are
+// scored, statistics over them alone, part_sum in candidate order: level 2 of a hierarchical lookup.)
+// Kept ranges (records of a plan) -> flat index lists idx [rows, L]: the key rows of the attention, or the candidate
+// clusters of the next level.
+hipError_t launch_expand_ranges(DecodePlan plan, int32_t *idx, int rows, int L, hipStream_t s);
 // Options of the row-wise selection for the two-level lookup (all zero for the one-level path).
 struct SelectOpts {
     const int32_t *cand_id;          // level 2: `logits` is [rows, C] in candidate order, cand_id [rows, C] the

@@ -495,6 +495,12 @@ hipError_t launch_prefill_attn(const void *q, const void *Kf, const void *Vf, co
     return launch_prefill_kernel<false>(q, Kf, Vf, Ku, Vu, keep_mask, key_cid, blk_info, out, lse, sh, s);
 }
 
+hipError_t launch_expand_ranges(DecodePlan plan, int32_t *idx, int rows, int L, hipStream_t s)
+{
+    hipLaunchKernelGGL(expand_ranges_kernel, dim3(rows), dim3(256), 0, s, plan, idx, L);
+    return hipGetLastError();
+}
+
 hipError_t launch_prefill_attn_shared(const void *q, const void *Kf, const void *Vf, const void *Ku, const void *Vu,
                                       DecodePlan plan, int32_t *key_idx, void *out, float *lse, const Shape &sh,
                                       hipStream_t s)

@@ -14,6 +14,10 @@
 //   MEAN == true   selection on averaged scores (Appendix D, "Prefill Stage"), first half: the scores
 //                  S_i(t) = exp(x_i - m) / D of a wave's 16 tokens are summed per cluster and written as one
 //                  part of part_sum [B*H, ceil(Lq/16), C]; the row-wise selection kernel adds the parts.
+//   CANDS == true  (with MEAN) second level of a hierarchical lookup (Section 3.3, Eq. 3): the clusters scored are the
+//                  n candidates cand_id[bh, 0..n) of the (sequence, head) -- the children of the coarse clusters kept
+//                  one level up -- so maximum and normaliser run over the candidates only; part_sum is written in
+//                  candidate order.
 #include "sq_common.hpp"
 #include "sq_internal.hpp"
 
@@ -28,16 +32,21 @@ struct LkStage {
     int N[LK_G];
 };
 
-template <bool MEAN>
+template <bool MEAN, bool CANDS = false>
 __global__ __launch_bounds__(256) void prefill_lookup_kernel(
     const _Float16 *__restrict__ q, const _Float16 *__restrict__ cent, const int32_t *__restrict__ sizes,
     const float *__restrict__ thresh, uint32_t *__restrict__ keep_mask, int32_t *__restrict__ n_ranges,
-    int32_t *__restrict__ n_keys, float *__restrict__ part_sum, int H, int Lq, int C, float sm_scale)
+    int32_t *__restrict__ n_keys, float *__restrict__ part_sum, const int32_t *__restrict__ cand_id,
+    const int2 *__restrict__ cand_hdr, int H, int Lq, int C_all, float sm_scale)
 {
     __shared__ __align__(16) LkStage stage[2];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 15, kg = lane >> 4;
     const int bh = blockIdx.y, h = bh % H;
+    // C: the clusters this workgroup scores (all of the head's, or its candidates); C_all: row length of the arrays.
+    const int C = CANDS ? min(cand_hdr[bh].y, C_all) : C_all;
+    if (CANDS && C <= 0) return;                            // no candidate: nothing to score (workgroup-uniform)
+    const int32_t *cid = CANDS ? cand_id + (size_t)bh * C_all : nullptr;
     const int q0 = (blockIdx.x * 4 + wave) * LOOKUP_ROWS;   // first token of this wave (may lie past the end)
     const int nq = q0 + col;
     const bool valid = nq < Lq;
@@ -51,8 +60,8 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
 #pragma unroll
         for (int s = 0; s < 4; ++s) bq[s] = qp[s * 4 + kg];
     }
-    const char *ch = reinterpret_cast<const char *>(cent + (size_t)h * C * D);
-    const int32_t *Nh = sizes + (size_t)h * C;
+    const char *ch = reinterpret_cast<const char *>(cent + (size_t)h * C_all * D);
+    const int32_t *Nh = sizes + (size_t)h * C_all;
 
     // This thread's share of a group: rows i*16 + tid/16 (i = 0..3), 16-byte chunk tid%16; size of cluster tid.
     h8 pk[4];
@@ -60,10 +69,14 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
     auto fetch = [&](int g) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int c_row = min(g * LK_G + i * 16 + (tid >> 4), C - 1);    // rows past the end repeat the last one
+            int c_row = min(g * LK_G + i * 16 + (tid >> 4), C - 1);          // rows past the end repeat the last one
+            if (CANDS) c_row = min(max(cid[c_row], 0), C_all - 1);
             pk[i] = *reinterpret_cast<const h8 *>(ch + (size_t)c_row * 256 + (tid & 15) * 16);
         }
-        if (tid < LK_G) pn = g * LK_G + tid < C ? Nh[g * LK_G + tid] : 0;   // 0 past the last cluster
+        if (tid < LK_G) {                                                    // 0 past the last cluster
+            const int c = g * LK_G + tid;
+            pn = c < C ? Nh[CANDS ? min(max(cid[c], 0), C_all - 1) : c] : 0;
+        }
     };
     auto commit = [&](LkStage &st) {
 #pragma unroll
@@ -168,7 +181,7 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
                     for (int v = 0; v < 4; ++v)             // over the wave's tokens
                         sums[v] = row16_sum(valid && Dsum > 0.0f ? e[v] / Dsum : 0.0f);
                     if (col == 0 && part < n_part) {
-                        float *dst = part_sum + ((size_t)bh * n_part + part) * C + t * 16 + kg * 4;
+                        float *dst = part_sum + ((size_t)bh * n_part + part) * C_all + t * 16 + kg * 4;
 #pragma unroll
                         for (int v = 0; v < 4; ++v)
                             if (t * 16 + kg * 4 + v < C) dst[v] = sums[v];
@@ -192,17 +205,23 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
 
 hipError_t launch_prefill_lookup(const void *q, const void *centroids, const int32_t *sizes, const float *thresh,
                                  uint32_t *keep_mask, int32_t *n_ranges, int32_t *n_keys, float *part_sum, bool mean,
-                                 int B, int H, int Lq, int C, float sm_scale, hipStream_t s)
+                                 int B, int H, int Lq, int C, float sm_scale, hipStream_t s, const int32_t *cand_id,
+                                 const int2 *cand_hdr)
 {
     const dim3 grid((Lq + 4 * LOOKUP_ROWS - 1) / (4 * LOOKUP_ROWS), B * H);
-    if (mean)
-        hipLaunchKernelGGL(prefill_lookup_kernel<true>, grid, dim3(256), 0, s, (const _Float16 *)q,
-                           (const _Float16 *)centroids, sizes, thresh, keep_mask, n_ranges, n_keys, part_sum, H, Lq, C,
-                           sm_scale);
+    if (cand_id) {
+        if (!mean || !cand_hdr) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((prefill_lookup_kernel<true, true>), grid, dim3(256), 0, s, (const _Float16 *)q,
+                           (const _Float16 *)centroids, sizes, thresh, keep_mask, n_ranges, n_keys, part_sum, cand_id,
+                           cand_hdr, H, Lq, C, sm_scale);
+    } else if (mean)
+        hipLaunchKernelGGL((prefill_lookup_kernel<true, false>), grid, dim3(256), 0, s, (const _Float16 *)q,
+                           (const _Float16 *)centroids, sizes, thresh, keep_mask, n_ranges, n_keys, part_sum,
+                           (const int32_t *)nullptr, (const int2 *)nullptr, H, Lq, C, sm_scale);
     else
-        hipLaunchKernelGGL(prefill_lookup_kernel<false>, grid, dim3(256), 0, s, (const _Float16 *)q,
-                           (const _Float16 *)centroids, sizes, thresh, keep_mask, n_ranges, n_keys, part_sum, H, Lq, C,
-                           sm_scale);
+        hipLaunchKernelGGL((prefill_lookup_kernel<false, false>), grid, dim3(256), 0, s, (const _Float16 *)q,
+                           (const _Float16 *)centroids, sizes, thresh, keep_mask, n_ranges, n_keys, part_sum,
+                           (const int32_t *)nullptr, (const int2 *)nullptr, H, Lq, C, sm_scale);
     return hipGetLastError();
 }
 

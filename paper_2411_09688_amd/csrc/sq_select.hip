@@ -314,7 +314,15 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
         for (int st = 0; st < 16; ++st) {
             const int i = st * SEL_THREADS + tid;
             idv[st] = i < n ? cid[i] : 0;
-            xv[st] = i < n ? x[i] : 0.0f;
+            if (STATS_IN && opt.mean_parts) {               // averaged scores of the candidates (parts in ascending order)
+                const float *ps = logits + row * (size_t)opt.mean_parts * C;
+                float sum = 0.0f;
+                if (i < n)
+                    for (int p = 0; p < opt.mean_parts; ++p) sum += ps[(size_t)p * C + i];
+                xv[st] = sum / opt.mean_div;
+            } else {
+                xv[st] = i < n ? x[i] : 0.0f;
+            }
         }
 #pragma unroll
         for (int st = 0; st < 16; ++st) nv[st] = st * SEL_THREADS + tid < n ? N[idv[st]] : 0;
@@ -683,7 +691,8 @@ hipError_t launch_select(const float *logits, const float *row_max, const float 
     static bool attr_set = false;   // one GPU per process in this build
     if (!attr_set) {
         const int lim = LDS_BYTES_MAX;
-        const void *fns[7] = {reinterpret_cast<const void *>(select_kernel<true, false>),
+        const void *fns[8] = {reinterpret_cast<const void *>(select_kernel<true, false, false, true>),
+                              reinterpret_cast<const void *>(select_kernel<true, false>),
                               reinterpret_cast<const void *>(select_kernel<false, false>),
                               reinterpret_cast<const void *>(select_kernel<false, true>),
                               reinterpret_cast<const void *>(select_kernel<true, true>),
@@ -705,8 +714,12 @@ hipError_t launch_select(const float *logits, const float *row_max, const float 
         return hipGetLastError();
     }
     if (opt.cand_id) {
-        if (stats_in || !opt.cand_hdr) return hipErrorInvalidValue;
-        if (schedule)
+        if ((stats_in && (!opt.mean_parts || schedule)) || !opt.cand_hdr) return hipErrorInvalidValue;
+        if (stats_in)                                       // averaged scores over the candidates (prefill rule)
+            hipLaunchKernelGGL((select_kernel<true, false, false, true>), dim3(rows), dim3(SEL_THREADS), smem, s, logits,
+                               row_max, denom, thresh, sizes, offsets, keep_mask, ranges, n_ranges, n_keys, plan, opt, H,
+                               Lq, C, U, nuc);
+        else if (schedule)
             hipLaunchKernelGGL((select_kernel<false, true, false, true>), dim3(rows), dim3(SEL_THREADS), smem, s, logits,
                                row_max, denom, thresh, sizes, offsets, keep_mask, ranges, n_ranges, n_keys, plan, opt, H,
                                Lq, C, U, nuc);
