@@ -213,7 +213,18 @@ __global__ __launch_bounds__(1024) void kmeans_scan_kernel(int32_t *__restrict__
         int total = 0;
         if (c < C) {
             int32_t *col = hist + (size_t)h * P * C + c;
-            for (int p = 0; p < P; ++p) {
+            int p = 0;
+            for (; p + 8 <= P; p += 8) {                        // eight loads in flight
+                int t8[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) t8[u] = col[(size_t)(p + u) * C];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    col[(size_t)(p + u) * C] = total;
+                    total += t8[u];
+                }
+            }
+            for (; p < P; ++p) {
                 const int t = col[(size_t)p * C];
                 col[(size_t)p * C] = total;
                 total += t;
@@ -345,7 +356,7 @@ int kmeans_part_len(int L)
 {
     const int want = (L + 63) / 64;                           // at most 64 parts per head
     const int pl = ((want + 255) / 256) * 256;
-    return pl < 1024 ? 1024 : pl;
+    return pl < 512 ? 512 : pl;
 }
 
 hipError_t launch_normalize_rows(const void *K, void *X, size_t rows, hipStream_t s)
