@@ -242,14 +242,17 @@ def test_full_size_iteration_on_sampled_keys_and_centres(sq):
             assert np.abs(cn[h][c].astype(np.float64) - ref).max() <= UNIT_ATOL
 
 
-def test_two_level_hierarchy_built_on_the_gpu_feeds_the_hierarchical_lookup(sq, oracle):
+@pytest.mark.parametrize("H,L,C2,C1,U,mix", [
+    (2, 12000, 160, 12, 40, 48),
+    (2, 32768, 1638, 328, 128, 400),       # the paper's sizing: fine centroids 5 % of the keys, coarse 1 %
+])
+def test_two_level_hierarchy_built_on_the_gpu_feeds_the_hierarchical_lookup(sq, oracle, H, L, C2, C1, U, mix):
     """Keys -> fine K-means -> K-means of the fine centroids -> nesting -> layouts, all through the C ABI; every array
     against the oracle's composition of the same steps, then sq_hier_decode_step on the result against the oracle's
     two-level lookup and sparse attention on the same arrays."""
     from test_gpu_hier import check_hier_selection
     from gpu_util import ranges_from_keep
-    H, L, C2, C1, U = 2, 12000, 160, 12, 40
-    K, V, init = wl.clustering_input(21, H, L, C2, mix=48)
+    K, V, init = wl.clustering_input(21, H, L, C2, mix=mix)
     _, _, init1 = wl.clustering_input(22, H, C2, C1)             # (only the seeding indices are used)
     i32 = lambda *s: torch.empty(s, dtype=torch.int32, device=DEV)
     f16 = lambda *s: torch.empty(s, dtype=torch.float16, device=DEV)
