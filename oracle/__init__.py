@@ -274,3 +274,24 @@ def gqa_decode(q, centroids, sizes, offsets, thresh, K_fixed, V_fixed, K_user, V
         res["out"][:, hq] = out[:, 0, 0]
         res["lse"][:, hq] = lse[:, 0, 0]
     return res
+
+
+def gqa_mean_decode(q, centroids, sizes, offsets, thresh, K_fixed, V_fixed, K_user, V_user, sm_scale, G):
+    """Grouped-query decode with ONE kept set per (sequence, K/V head): the aggregation the paper's appendix
+    ("Additional Longbench Evaluation") leaves as future work, read as "average the scores over the group": the
+    cluster scores of Eq. 1 of the G query heads that share a K/V head are averaged (the rule of Appendix D with the
+    group's heads in the place of the query tokens) and compared with T; every head of the group then attends to the
+    same kept keys plus the sequence's user keys.  q [B, Hq, d], Hq = H * G, head hq uses K/V head hq // G.
+    -> dict(mask [B,H,W] u32, n_keys [B,H] i32, out [B,Hq,d] f64, lse [B,Hq] f64)."""
+    q = _f16(q)
+    B, Hq, d = q.shape
+    H = centroids.shape[0]
+    assert Hq == H * G
+    qg = np.ascontiguousarray(q.reshape(B, H, G, d))
+    x, m, D = centroid_score(qg, centroids, sizes, sm_scale)
+    mask, ranges, n_r, n_k = select_mean(x, m, D, thresh, sizes, offsets)
+    cap = ranges.shape[2]
+    rr = np.ascontiguousarray(np.broadcast_to(ranges[:, :, None], (B, H, G, cap, 2)))
+    nn = np.ascontiguousarray(np.broadcast_to(n_r[:, :, None], (B, H, G)))
+    out, lse = sparse_attn(qg, K_fixed, V_fixed, rr, nn, K_user, V_user, sm_scale)
+    return dict(mask=mask, n_keys=n_k, out=out.reshape(B, Hq, d), lse=lse.reshape(B, Hq))

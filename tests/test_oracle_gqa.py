@@ -84,3 +84,47 @@ def test_heads_of_a_group_are_independent_and_share_only_the_kv_head():
     # selections of the two heads of a group differ (each head selects on its own)
     keep = unpack_mask(base["mask"], w.C)
     assert (keep[:, 0] != keep[:, 1]).any()
+
+
+# ---- one kept set per K/V head from scores averaged over the group --------------------------------------------------
+
+def test_group_average_keeps_what_no_single_head_would():
+    # Two query heads on one K/V head, d = 2, sm_scale = ln 2: head 0 = (1, 0), head 1 = (0, 1); clusters with
+    # centroids (3, 0) and (0, 3), two keys each.  Head 0 alone: e = (8, 1), D = 18, S = (8/18, 1/18); head 1 mirrored.
+    # With T = 0.2 each head on its own keeps ONE cluster; the group average (1/4, 1/4) keeps BOTH.
+    import oracle
+    LN2 = float(np.log(2.0))
+    q = np.array([[[1, 0], [0, 1]]], np.float16)                 # [B = 1, Hq = 2, d]
+    cent = np.array([[[3, 0], [0, 3]]], np.float16)
+    sizes, offsets = np.array([[2, 2]], np.int32), np.array([[0, 2, 4]], np.int32)
+    K = np.array([[[3, 0], [3, 0], [0, 3], [0, 3]]], np.float16)
+    V = np.array([[[1, 0], [1, 0], [0, 1], [0, 1]]], np.float16)
+    Ku = np.zeros((1, 1, 0, 2), np.float16)
+    T = np.array([0.2], np.float32)
+    own = oracle.gqa_decode(q, cent, sizes, offsets, T, K, V, Ku, Ku, LN2, 2)
+    assert own["n_keys"].tolist() == [[2, 2]] and own["mask"][0, :, 0].tolist() == [1, 2]
+    avg = oracle.gqa_mean_decode(q, cent, sizes, offsets, T, K, V, Ku, Ku, LN2, 2)
+    assert avg["n_keys"].tolist() == [[4]] and avg["mask"][0, 0, 0] == 3
+    # head 0 over all four keys: weights (8, 8, 1, 1) / 18 on values (1,0), (1,0), (0,1), (0,1)
+    np.testing.assert_allclose(avg["out"][0, 0], [16 / 18, 2 / 18], rtol=1e-6)
+    np.testing.assert_allclose(avg["out"][0, 1], [2 / 18, 16 / 18], rtol=1e-6)
+    np.testing.assert_allclose(avg["lse"][0], [np.log(18.0)] * 2, rtol=1e-6)
+
+
+def test_group_of_one_average_is_the_plain_step():
+    import oracle
+    rng = np.random.default_rng(77)
+    H, C, L, U, d = 3, 20, 200, 7, 128
+    cent = (rng.standard_normal((H, C, d)) * 0.6).astype(np.float16)
+    sizes = rng.multinomial(L, np.full(C, 1 / C), size=H).astype(np.int32)
+    offsets = np.zeros((H, C + 1), np.int32); offsets[:, 1:] = np.cumsum(sizes, 1)
+    K = rng.standard_normal((H, L, d)).astype(np.float16); V = rng.standard_normal((H, L, d)).astype(np.float16)
+    Ku = rng.standard_normal((2, H, U, d)).astype(np.float16); Vu = rng.standard_normal((2, H, U, d)).astype(np.float16)
+    q = rng.standard_normal((2, H, d)).astype(np.float16)
+    T = np.full(H, 1.0 / L, np.float32)
+    a = oracle.gqa_decode(q, cent, sizes, offsets, T, K, V, Ku, Vu, 0.3, 1)
+    b = oracle.gqa_mean_decode(q, cent, sizes, offsets, T, K, V, Ku, Vu, 0.3, 1)
+    np.testing.assert_array_equal(a["mask"], b["mask"])
+    np.testing.assert_array_equal(a["n_keys"], b["n_keys"])
+    np.testing.assert_allclose(a["out"], b["out"], rtol=0, atol=1e-12)
+    assert 0 < b["n_keys"].sum() < 2 * H * L
