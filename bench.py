@@ -375,10 +375,15 @@ def bench_gqa(args, torch, sq, wl, dev):
     shape = sq.make_shape(w.B, w.H, w.L, w.C, 1, w.U, w.sm_scale)
     ws = sq.workspace(shape, sq.SQ_CALL_GQA_DECODE_STEP, dev)
 
+    mean = args.selection == "mean"          # one kept set per K/V head from the group's averaged scores
+    entry = sq.sq_gqa_mean_decode_step if mean else sq.sq_gqa_decode_step
+    if mean:
+        ws = sq.workspace(shape, sq.SQ_CALL_GQA_MEAN_DECODE_STEP, dev)
+
     def step(i, stream_ptr):
         qi, r = i % NQ, i % R
-        sq.sq_gqa_decode_step(shape, G, Q[qi], Ce[r], sizes, offsets, thresh, Kf[r], Vf[r], Ku[r], Vu[r], out[qi],
-                              lse[qi], kmask[qi], nkeys[qi], ws)
+        entry(shape, G, Q[qi], Ce[r], sizes, offsets, thresh, Kf[r], Vf[r], Ku[r], Vu[r], out[qi], lse[qi], kmask[qi],
+              nkeys[qi], ws)
 
     eager_ms, graph_ms, ms, (n_meas, k_avg, k_min, k_max) = time_steps(step, args, torch, sq)
     used = [(args.warmup + i) % NQ for i in range(args.steps)]
@@ -395,7 +400,7 @@ def bench_gqa(args, torch, sq, wl, dev):
     tot = sel + cen + dense + meta + 2 * w.B * Hq * w.d * 2      # what the method has to move: every needed byte once
     # The library streams the union once from 8 (sequence, query head) pairs per K/V head on; with fewer, its
     # per-row kernels read a K/V head's selected keys and user keys once per query head.
-    shared = w.B * G >= 8
+    shared = mean or w.B * G >= 8
     kernel = "decode_attn_shared_kernel" if shared else "decode_attn_kernel"
     kernel_bytes = (sel + dense if shared else sel_req + dense * G) + w.B * Hq * w.d * 2
     res = base_result(args, "grouped-query decode attn µs/token + achieved HBM GB/s, 32K fixed ctx, keep 1/8, "
@@ -403,7 +408,8 @@ def bench_gqa(args, torch, sq, wl, dev):
                       graph_ms, w.B)
     res["config"] = {"workload": args.workload, "B": w.B, "H_kv": w.H, "G": G, "d": w.d, "L": w.L, "C": w.C, "U": w.U,
                      "keep_target": w.keep_frac, "keep_achieved": round(float(np.mean([nk[qi].mean() for qi in used])) / w.L, 5),
-                     "queries": NQ, "replicas": R, "entry": "sq_gqa_decode_step"}
+                     "queries": NQ, "replicas": R, "selection": args.selection,
+                     "entry": "sq_gqa_mean_decode_step" if mean else "sq_gqa_decode_step"}
     res["bytes_per_step"] = {"total": round(tot), "centroid": cen, "selected_kv": round(sel),
                              "selected_kv_requested": round(sel_req), "dense_kv": dense}
     res["hbm_frac_whole_step"] = round(tot / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)

@@ -62,7 +62,8 @@ typedef enum sq_call {
     SQ_CALL_MULTILEVEL_DECODE_STEP = 13,
     SQ_CALL_KMEANS_STEP = 14,
     SQ_CALL_CALIBRATE = 15,
-    SQ_CALL_HIER_PREFILL_MEAN_STEP = 16
+    SQ_CALL_HIER_PREFILL_MEAN_STEP = 16,
+    SQ_CALL_GQA_MEAN_DECODE_STEP = 17
 } sq_call;
 
 /*
@@ -245,6 +246,22 @@ int sq_gqa_decode_step(const sq_shape_t *shape, int32_t G, const void *q,
                        const void *K_fixed, const void *V_fixed, const void *K_user, const void *V_user,
                        void *out, float *lse, uint32_t *keep_mask, int32_t *n_keys,
                        void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Grouped-query decode with ONE kept set per (sequence, K/V head): the aggregation across the heads of a group that
+ * the paper's appendix ("Additional Longbench Evaluation") leaves as future work, read as the average: the Eq. 1
+ * scores of the G query heads that share a K/V head are averaged (Appendix D's rule with the heads in the place of
+ * the query tokens) and cluster i is kept iff the average exceeds thresh (up to the fp32 rounding of sum_i N_i * mean_i,
+ * which is 1 in exact arithmetic); every head of the group attends to those keys plus the sequence's user keys, and
+ * each kept key is read once per group.  Arguments, layouts and G as sq_gqa_decode_step; keep_mask u32
+ * [B,H*G,1,ceil(C/32)] and n_keys i32 [B,H*G,1] (optional) repeat the group's set for each of its heads.
+ * Workspace: sq_workspace_bytes(shape, SQ_CALL_GQA_MEAN_DECODE_STEP).
+ */
+int sq_gqa_mean_decode_step(const sq_shape_t *shape, int32_t G, const void *q, const void *centroids,
+                            const int32_t *sizes, const int32_t *offsets, const float *thresh,
+                            const void *K_fixed, const void *V_fixed, const void *K_user, const void *V_user,
+                            void *out, float *lse, uint32_t *keep_mask, int32_t *n_keys,
+                            void *ws, size_t ws_bytes, void *stream);
 
 /*
  * One whole prefill step with PER-QUERY selection: the lookup of sq_centroid_score + sq_select for every

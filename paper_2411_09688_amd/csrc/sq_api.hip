@@ -399,6 +399,9 @@ size_t sq_workspace_bytes(const sq_shape_t *sh, int which)
     case SQ_CALL_KMEANS_STEP:
         carve_kmeans(cv, sh);
         return cv.off;
+    case SQ_CALL_GQA_MEAN_DECODE_STEP:                // sized for the largest group
+        carve_step_shared(cv, sh, sq::SG);
+        return cv.off;
     case SQ_CALL_HIER_PREFILL_MEAN_STEP:
         carve_hier_prefill_mean(cv, sh);
         return cv.off;
@@ -557,6 +560,46 @@ int sq_gqa_decode_step(const sq_shape_t *sh, int32_t G, const void *q, const voi
     sq::Shape shp = to_shape(sh);
     shp.Lq = G;
     SQ_HIP(sq::launch_decode_attn(q, K_fixed, V_fixed, K_user, V_user, w.dec.plan, w.dec.partials, out, lse, shp, s));
+    g_err[0] = 0;
+    return SQ_OK;
+}
+
+int sq_gqa_mean_decode_step(const sq_shape_t *sh, int32_t G, const void *q, const void *centroids,
+                            const int32_t *sizes, const int32_t *offsets, const float *thresh, const void *K_fixed,
+                            const void *V_fixed, const void *K_user, const void *V_user, void *out, float *lse,
+                            uint32_t *keep_mask, int32_t *n_keys, void *ws, size_t ws_bytes, void *stream)
+{
+    if (int rc = check_shape(sh, __func__, true)) return rc;
+    if (G != 1 && G != 2 && G != 4 && G != 8 && G != 16)
+        return fail(SQ_ERR_UNSUPPORTED, "%s: G = %d query heads per K/V head; supported: 1, 2, 4, 8, 16", __func__, G);
+    SQ_REQUIRE_PTR(q);
+    SQ_REQUIRE_PTR(centroids);
+    SQ_REQUIRE_PTR(sizes);
+    SQ_REQUIRE_PTR(offsets);
+    SQ_REQUIRE_PTR(thresh);
+    SQ_REQUIRE_PTR(K_fixed);
+    SQ_REQUIRE_PTR(V_fixed);
+    if (sh->U > 0) {
+        SQ_REQUIRE_PTR(K_user);
+        SQ_REQUIRE_PTR(V_user);
+    }
+    SQ_REQUIRE_PTR(out);
+    SQ_OPTIONAL_PTR(lse);
+    SQ_OPTIONAL_PTR(keep_mask);
+    SQ_OPTIONAL_PTR(n_keys);
+    if (int rc = check_ws(__func__, sh, SQ_CALL_GQA_MEAN_DECODE_STEP, ws, ws_bytes)) return rc;
+    if (int rc = check_device(__func__)) return rc;
+    Carver cv(ws);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    SharedStepWs w = carve_step_shared(cv, sh, G);
+    SQ_HIP(sq::launch_score(q, centroids, w.logits, w.plan.total, sh->B, sh->H, G, sh->C, sh->sm_scale, s));
+    SQ_HIP(sq::launch_group_mean_logits(w.logits, sizes, sh->B * sh->H, sh->H, G, sh->C, s));
+    // The G rows of a group now select the same clusters: the union of a group of 16 rows streams each kept key once.
+    SQ_HIP(sq::launch_union_schedule(w.logits, thresh, sizes, offsets, keep_mask ? keep_mask : w.mask, w.n_ranges,
+                                     n_keys ? n_keys : w.n_keys, w.plan, sh->U, sh->B, G, sh->H, sh->C, s));
+    sq::Shape shp = to_shape(sh);
+    shp.Lq = G;
+    SQ_HIP(sq::launch_decode_attn_shared(q, K_fixed, V_fixed, K_user, V_user, w.plan, w.partials, out, lse, shp, s));
     g_err[0] = 0;
     return SQ_OK;
 }

@@ -115,6 +115,8 @@ hipError_t launch_select(const float *logits, const float *row_max, const float 
 // items of `cand` (chunks of candidate clusters), written in candidate order: logits2[row, j], cand_id[row, j].
 hipError_t launch_gather_score(const void *q, const void *centroids2, DecodePlan cand, float *logits2,
                                int32_t *cand_id, int *zero_counter, int H, int C2, float sm_scale, hipStream_t s);
+// Rows [BH, G, C] of logits -> ln of the group's averaged Eq. 1 scores, written to all G rows (in place).
+hipError_t launch_group_mean_logits(float *logits, const int32_t *sizes, int BH, int H, int G, int C, hipStream_t s);
 // Caller-style ranges [rows, range_cap, 2] -> records + header per row.
 hipError_t launch_ranges_to_rec(const int32_t *ranges, const int32_t *n_ranges, DecodePlan plan, int rows,
                                 int range_cap, hipStream_t s);

@@ -119,6 +119,61 @@ __global__ __launch_bounds__(256) void mean_score_kernel(const float *__restrict
     }
 }
 
+// Grouped-query attention with one kept set per K/V head: the scores S_i = exp(x_i - m) / D (Eq. 1) of the G query
+// heads of a (sequence, K/V head) are averaged, g ascending, and every head's logit row is replaced by
+// ln(mean score) (-inf where the mean is 0).  A selection run on such a row finds max = ln(max mean),
+// D = sum N_i mean_i / max mean, and therefore keeps cluster i iff mean_i > T * sum_j N_j mean_j, the sum being 1 up
+// to fp32 rounding: the per-row threshold rule applied to the group's averaged scores, identically for the G rows.
+__global__ __launch_bounds__(1024) void group_mean_logits_kernel(float *__restrict__ logits,
+                                                                 const int32_t *__restrict__ sizes, int H, int G, int C)
+{
+    __shared__ float s_m[SG], s_D[SG], s_red[16];
+    const int bh = blockIdx.x, h = bh % H;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const size_t row0 = (size_t)bh * G;                       // first of the G rows of this (sequence, K/V head)
+    const int32_t *N = sizes + (size_t)h * C;
+    for (int g = 0; g < G; ++g) {                             // (m, D) of Eq. 1 per query head, the whole workgroup per row
+        const float *x = logits + (row0 + g) * C;
+        float m = SQ_NEG_INF;
+        for (int i = tid; i < C; i += 1024)
+            if (N[i] > 0) m = fmaxf(m, x[i]);
+        m = wave_max(m);
+        if (lane == 0) s_red[wave] = m;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < 16; ++w) m = fmaxf(m, s_red[w]);
+        __syncthreads();                                      // s_red is reused
+        float d = 0.0f;
+        for (int i = tid; i < C; i += 1024)
+            if (N[i] > 0) d += (float)N[i] * expf(x[i] - m);
+        d = wave_sum(d);
+        if (lane == 0) s_red[wave] = d;
+        __syncthreads();
+        float Dsum = 0.0f;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) Dsum += s_red[w];
+        if (tid == 0) {
+            s_m[g] = m;
+            s_D[g] = Dsum;
+        }
+        __syncthreads();
+    }
+    for (int i = tid; i < C; i += 1024) {
+        float sum = 0.0f;
+        if (N[i] > 0)
+            for (int g = 0; g < G; ++g) sum += expf(logits[(row0 + g) * C + i] - s_m[g]) / s_D[g];
+        const float mean = sum / (float)G;
+        const float xl = mean > 0.0f ? logf(mean) : SQ_NEG_INF;
+        for (int g = 0; g < G; ++g) logits[(row0 + g) * C + i] = xl;
+    }
+}
+
+hipError_t launch_group_mean_logits(float *logits, const int32_t *sizes, int BH, int H, int G, int C, hipStream_t s)
+{
+    hipLaunchKernelGGL(group_mean_logits_kernel, dim3(BH), dim3(1024), 0, s, logits, sizes, H, G, C);
+    return hipGetLastError();
+}
+
 // Level-2 scoring of the two-level lookup (Section 3.3, Eq. 3 numerator): the fine centroids to score are
 // the children of the kept coarse clusters, listed by work items of KPC candidate clusters each (built
 // by the level-1 selection: a balanced number of centroids per workgroup, Appendix D).  A persistent

@@ -145,3 +145,82 @@ def test_group_averaged_selection_llama3_shape(sq):
     keep = got[3].mean() / w.L
     print("gqa group-averaged attention max-abs err", err, "keep", keep, flush=True)
     assert 0.02 < keep < 0.6
+
+
+# ---- one kept set per K/V head from the group's averaged scores (sq_gqa_mean_decode_step) ----------------------------
+
+def run_gqa_mean(sq, w, G, thresh):
+    dev = torch.device("cuda:0")
+    tt = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    Hq, W = w.H * G, (w.C + 31) // 32
+    shape = sq.make_shape(w.B, w.H, w.L, w.C, 1, w.U, w.sm_scale)
+    out = torch.full((w.B, Hq, 1, w.d), 7.0, dtype=torch.float16, device=dev)
+    lse = torch.zeros(w.B, Hq, 1, dtype=torch.float32, device=dev)
+    mask = torch.zeros(w.B, Hq, 1, W, dtype=torch.int32, device=dev)
+    nk = torch.zeros(w.B, Hq, 1, dtype=torch.int32, device=dev)
+    ws = sq.workspace(shape, sq.SQ_CALL_GQA_MEAN_DECODE_STEP, dev)
+    sq.sq_gqa_mean_decode_step(shape, G, tt(w.q.reshape(w.B, Hq, 1, w.d)), tt(w.centroids), tt(w.sizes), tt(w.offsets),
+                               tt(thresh), tt(w.K_fixed), tt(w.V_fixed), tt(w.K_user), tt(w.V_user), out, lse, mask, nk, ws)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()[:, :, 0], lse.cpu().numpy()[:, :, 0], mask.cpu().numpy()[:, :, 0], nk.cpu().numpy()[:, :, 0]
+
+
+def mean_against_oracle(sq, w, G, label):
+    from oracle import literal
+    from tests.test_gpu_prefill import mean_thresholds
+    th, _ = mean_thresholds(oracle, w)                           # thresholds for averaged scores (w.Lq = G "tokens")
+    out, lse, mask, nk = run_gqa_mean(sq, w, G, th)
+    q = np.ascontiguousarray(w.q.reshape(w.B, w.H * G, w.d))
+    ref = oracle.gqa_mean_decode(q, w.centroids, w.sizes, w.offsets, th, w.K_fixed, w.V_fixed, w.K_user, w.V_user,
+                                 w.sm_scale, G)
+    gk = unpack_mask(mask.view(np.uint32), w.C).reshape(w.B, w.H, G, w.C)
+    ok = unpack_mask(ref["mask"], w.C)                           # [B, H, C]
+    assert (gk == gk[:, :, :1]).all(), "the heads of a group must report one set"
+    listed = 0
+    for b, h, c in np.argwhere(gk[:, :, 0] != ok):               # disagreements must sit next to the threshold
+        sbar = literal.select_mean(w.q[b, h], w.centroids[h], w.sizes[h], th[h], w.sm_scale)[1]
+        assert literal.near_threshold(sbar[c], th[h]), (label, b, h, c, sbar[c], th[h])
+        listed += 1
+    np.testing.assert_array_equal(nk.reshape(w.B, w.H, G), np.broadcast_to((gk[:, :, 0] * w.sizes[None]).sum(-1)[..., None],
+                                                                          (w.B, w.H, G)))
+    if listed:                                                   # attention on the GPU's own (validated) set
+        ranges = np.zeros((w.B, w.H, G, w.C, 2), np.int32)
+        n_r = np.zeros((w.B, w.H, G), np.int32)
+        for b, h, g in np.ndindex(w.B, w.H, G):
+            ids = np.flatnonzero(gk[b, h, g])
+            ranges[b, h, g, :len(ids), 0] = w.offsets[h][ids]
+            ranges[b, h, g, :len(ids), 1] = w.sizes[h][ids]
+            n_r[b, h, g] = len(ids)
+        ro, rl = oracle.sparse_attn(w.q, w.K_fixed, w.V_fixed, ranges, n_r, w.K_user, w.V_user, w.sm_scale)
+        ro, rl = ro.reshape(w.B, w.H * G, w.d), rl.reshape(w.B, w.H * G)
+    else:
+        ro, rl = ref["out"], ref["lse"]
+    err = np.abs(out.astype(np.float64) - ro).max()
+    assert err <= ATTN_ATOL, f"{label}: attention max-abs error {err}"
+    fin = np.isfinite(rl)
+    assert (np.isneginf(lse) == ~fin).all()
+    np.testing.assert_allclose(lse[fin], rl[fin], atol=1e-4, rtol=1e-5)
+    return err, float(nk.mean()) / w.L
+
+
+@pytest.mark.parametrize("case", [
+    dict(G=4, B=1, H=2, L=900, C=30, U=5, keep_frac=0.3),
+    dict(G=2, B=3, H=3, L=3000, C=100, U=300, keep_frac=0.5),
+    dict(G=8, B=2, H=2, L=2000, C=50, U=0, keep_frac=0.2),
+    dict(G=16, B=2, H=2, L=1200, C=40, U=130, keep_frac=0.4),
+    dict(G=2, B=2, H=1, L=4096, C=2048, U=17, keep_frac=0.2),
+    dict(G=1, B=2, H=2, L=1000, C=33, U=9, keep_frac=0.3),
+])
+def test_gqa_mean_step_against_oracle(sq, case):
+    G = case.pop("G")
+    w = wl.make_workload("gqa_mean", Lq=G, seed=41, threads=2, **case)
+    err, keep = mean_against_oracle(sq, w, G, f"gqa-mean G{G} {case}")
+    assert 0 < keep < 1
+
+
+def test_gqa_mean_llama3_shape_32k(sq):
+    print("gqa mean 32k: generating", flush=True)
+    G = 4
+    w = wl.make_workload("gqa_avg_32k", B=1, H=8, L=32768, C=1024, Lq=G, U=512, keep_frac=1 / 8, seed=1, threads=16)
+    err, keep = mean_against_oracle(sq, w, G, "gqa-mean-32k")
+    print("gqa mean 32k attention max-abs err", err, "keep", keep, flush=True)
