@@ -85,6 +85,45 @@ __global__ __launch_bounds__(256) void row_stats_kernel(const float *__restrict_
     }
 }
 
+// The same statistics with a 1024-thread workgroup per row, for launches of few rows (decode): thread v adds clusters
+// v, v+1024, ... ascending, a butterfly inside each wave, the 16 wave sums in ascending order -- the library's one
+// summation order computed side by side instead of group after group: bit-identical to wave_row_stats.
+__global__ __launch_bounds__(1024) void row_stats_block_kernel(const float *__restrict__ logits,
+                                                               const int32_t *__restrict__ sizes,
+                                                               float *__restrict__ row_max, float *__restrict__ denom,
+                                                               int H, int Lq, int C)
+{
+    __shared__ float s_red[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int row = blockIdx.x, h = (row / Lq) % H;
+    const float *x = logits + (size_t)row * C;
+    const int32_t *N = sizes + (size_t)h * C;
+    float m = SQ_NEG_INF;
+    for (int i = tid; i < C; i += 1024)
+        if (N[i] > 0) m = fmaxf(m, x[i]);
+    m = wave_max(m);
+    if (lane == 0) s_red[wave] = m;
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < 16; ++w) m = fmaxf(m, s_red[w]);
+    __syncthreads();                                         // s_red is reused
+    float local = 0.0f;
+    for (int i = tid; i < C; i += 1024) {
+        const int Ni = N[i];
+        if (Ni > 0) local += (float)Ni * expf(x[i] - m);
+    }
+    local = wave_sum(local);
+    if (lane == 0) s_red[wave] = local;
+    __syncthreads();
+    if (tid == 0) {
+        float Dsum = 0.0f;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) Dsum += s_red[w];
+        row_max[row] = m;
+        denom[row] = Dsum;
+    }
+}
+
 // Prefill selection on averaged scores (Appendix D, "Prefill Stage"), first half: the per-token scores
 // S_i(t) = exp(x_i(t) - m(t)) / D(t) of Eq. 1 summed over a block of MEAN_ROWS query tokens of one
 // (sequence, head), t ascending, one thread per cluster (coalesced along i).  The selection kernel adds the
@@ -268,8 +307,11 @@ hipError_t launch_mean_score(const float *logits, const float *row_max, const fl
 hipError_t launch_row_stats(const float *logits, const int32_t *sizes, float *row_max, float *denom, int rows,
                             int H, int Lq, int C, hipStream_t s)
 {
-    hipLaunchKernelGGL(row_stats_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, logits, sizes, row_max, denom, rows, H,
-                       Lq, C);
+    if (rows <= 2048)                                        // few rows: a whole workgroup per row
+        hipLaunchKernelGGL(row_stats_block_kernel, dim3(rows), dim3(1024), 0, s, logits, sizes, row_max, denom, H, Lq, C);
+    else
+        hipLaunchKernelGGL(row_stats_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, logits, sizes, row_max, denom, rows,
+                           H, Lq, C);
     return hipGetLastError();
 }
 
