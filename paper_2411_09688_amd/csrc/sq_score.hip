@@ -166,44 +166,43 @@ __global__ __launch_bounds__(256) void mean_score_kernel(const float *__restrict
 __global__ __launch_bounds__(1024) void group_mean_logits_kernel(float *__restrict__ logits,
                                                                  const int32_t *__restrict__ sizes, int H, int G, int C)
 {
-    __shared__ float s_m[SG], s_D[SG], s_red[16];
+    __shared__ float s_red[SG][16], s_m[SG], s_D[SG];
     const int bh = blockIdx.x, h = bh % H;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const size_t row0 = (size_t)bh * G;                       // first of the G rows of this (sequence, K/V head)
     const int32_t *N = sizes + (size_t)h * C;
-    for (int g = 0; g < G; ++g) {                             // (m, D) of Eq. 1 per query head, the whole workgroup per row
-        const float *x = logits + (row0 + g) * C;
-        float m = SQ_NEG_INF;
-        for (int i = tid; i < C; i += 1024)
-            if (N[i] > 0) m = fmaxf(m, x[i]);
-        m = wave_max(m);
-        if (lane == 0) s_red[wave] = m;
-        __syncthreads();
-#pragma unroll
-        for (int w = 0; w < 16; ++w) m = fmaxf(m, s_red[w]);
-        __syncthreads();                                      // s_red is reused
-        float d = 0.0f;
-        for (int i = tid; i < C; i += 1024)
-            if (N[i] > 0) d += (float)N[i] * expf(x[i] - m);
-        d = wave_sum(d);
-        if (lane == 0) s_red[wave] = d;
-        __syncthreads();
+    // (m, D) of Eq. 1 for the G query heads side by side: row g is handled by the 16 / G waves w with w % G == g
+    // (G divides 16), each covering every (16 / G)-th block of 64 clusters.
+    const int g = wave % G, j = wave / G, nw = 16 / G;
+    const float *x = logits + (row0 + g) * C;
+    float m = SQ_NEG_INF;
+    for (int i = j * 64 + lane; i < C; i += 64 * nw)
+        if (N[i] > 0) m = fmaxf(m, x[i]);
+    m = wave_max(m);
+    if (lane == 0) s_red[g][j] = m;
+    __syncthreads();
+    for (int k = 0; k < nw; ++k) m = fmaxf(m, s_red[g][k]);
+    __syncthreads();                                          // s_red is reused
+    float d = 0.0f;
+    for (int i = j * 64 + lane; i < C; i += 64 * nw)
+        if (N[i] > 0) d += (float)N[i] * expf(x[i] - m);
+    d = wave_sum(d);
+    if (lane == 0) s_red[g][j] = d;
+    __syncthreads();
+    if (tid < G) {
         float Dsum = 0.0f;
-#pragma unroll
-        for (int w = 0; w < 16; ++w) Dsum += s_red[w];
-        if (tid == 0) {
-            s_m[g] = m;
-            s_D[g] = Dsum;
-        }
-        __syncthreads();
+        for (int k = 0; k < nw; ++k) Dsum += s_red[tid][k];
+        s_D[tid] = Dsum;
     }
+    if (j == 0 && lane == 0) s_m[g] = m;
+    __syncthreads();
     for (int i = tid; i < C; i += 1024) {
         float sum = 0.0f;
         if (N[i] > 0)
-            for (int g = 0; g < G; ++g) sum += expf(logits[(row0 + g) * C + i] - s_m[g]) / s_D[g];
+            for (int gg = 0; gg < G; ++gg) sum += expf(logits[(row0 + gg) * C + i] - s_m[gg]) / s_D[gg];
         const float mean = sum / (float)G;
         const float xl = mean > 0.0f ? logf(mean) : SQ_NEG_INF;
-        for (int g = 0; g < G; ++g) logits[(row0 + g) * C + i] = xl;
+        for (int gg = 0; gg < G; ++gg) logits[(row0 + gg) * C + i] = xl;
     }
 }
 
