@@ -63,7 +63,8 @@ typedef enum sq_call {
     SQ_CALL_KMEANS_STEP = 14,
     SQ_CALL_CALIBRATE = 15,
     SQ_CALL_HIER_PREFILL_MEAN_STEP = 16,
-    SQ_CALL_GQA_MEAN_DECODE_STEP = 17
+    SQ_CALL_GQA_MEAN_DECODE_STEP = 17,
+    SQ_CALL_HIER_PREFILL_STEP = 18
 } sq_call;
 
 /*
@@ -363,6 +364,22 @@ int sq_hier_prefill_mean_step(const sq_shape_t *shape, int32_t C1, const void *q
                               const int32_t *offsets2, const float *thresh2, const void *K_fixed, const void *V_fixed,
                               const void *K_user, const void *V_user, void *out, float *lse, uint32_t *keep_mask2,
                               int32_t *n_keys, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * The same with PER-QUERY selection (every query token selects for itself, as sq_prefill_step): token t keeps coarse
+ * clusters by Eq. 2 and thresh1, and fine clusters among the children of ITS kept coarse clusters by Eq. 3
+ * (normaliser over those children only) and thresh2; attention as in sq_sparse_attn_prefill with the per-token fine
+ * masks.  The fine centroids are scored densely for every token (a token's non-candidates are treated as clusters
+ * without keys), so this form saves no centroid comparisons over sq_prefill_step: it applies the hierarchical rule.
+ * keep_mask2 u32 [B,H,Lq,ceil(C/32)] and n_keys i32 [B,H,Lq] are optional outputs.  C1 <= 1024.
+ * Workspace: sq_workspace_bytes(shape, SQ_CALL_HIER_PREFILL_STEP).
+ */
+int sq_hier_prefill_step(const sq_shape_t *shape, int32_t C1, const void *q,
+                         const void *centroids1, const int32_t *sizes1, const int32_t *child_offsets,
+                         const float *thresh1, const void *centroids2, const int32_t *sizes2,
+                         const int32_t *offsets2, const float *thresh2, const void *K_fixed, const void *V_fixed,
+                         const void *K_user, const void *V_user, void *out, float *lse, uint32_t *keep_mask2,
+                         int32_t *n_keys, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Offline clustering of the fixed-context keys (Section 3.1: K-means on normalised key vectors; the centroid of a

@@ -21,14 +21,14 @@ SQ_OK, SQ_ERR_INVALID_ARG, SQ_ERR_UNSUPPORTED, SQ_ERR_WORKSPACE, SQ_ERR_HIP = 0,
 (SQ_CALL_CENTROID_SCORE, SQ_CALL_SELECT, SQ_CALL_ATTN_DECODE, SQ_CALL_ATTN_PREFILL, SQ_CALL_HIER_SELECT,
  SQ_CALL_DECODE_STEP, SQ_CALL_HIER_DECODE_STEP, SQ_CALL_SELECT_MEAN, SQ_CALL_ATTN_PREFILL_SHARED,
  SQ_CALL_PREFILL_STEP, SQ_CALL_PREFILL_MEAN_STEP, SQ_CALL_GQA_DECODE_STEP, SQ_CALL_MULTILEVEL_SELECT,
- SQ_CALL_MULTILEVEL_DECODE_STEP, SQ_CALL_KMEANS_STEP, SQ_CALL_CALIBRATE, SQ_CALL_HIER_PREFILL_MEAN_STEP, SQ_CALL_GQA_MEAN_DECODE_STEP) = range(18)
+ SQ_CALL_MULTILEVEL_DECODE_STEP, SQ_CALL_KMEANS_STEP, SQ_CALL_CALIBRATE, SQ_CALL_HIER_PREFILL_MEAN_STEP, SQ_CALL_GQA_MEAN_DECODE_STEP, SQ_CALL_HIER_PREFILL_STEP) = range(19)
 SQ_MAX_LEVELS = 4
 
 EXPORTS = ("sq_workspace_bytes", "sq_last_error", "sq_version", "sq_centroid_score", "sq_select",
            "sq_sparse_attn_decode", "sq_sparse_attn_prefill", "sq_hier_select", "sq_decode_step",
            "sq_hier_decode_step", "sq_select_mean", "sq_sparse_attn_prefill_shared", "sq_prefill_step",
            "sq_prefill_mean_step", "sq_gqa_decode_step", "sq_multilevel_select", "sq_multilevel_decode_step",
-           "sq_kmeans_normalize", "sq_kmeans_step", "sq_cluster_layout", "sq_cluster_nest", "sq_calibrate_threshold", "sq_hier_prefill_mean_step", "sq_gqa_mean_decode_step", "sq_profile_begin",
+           "sq_kmeans_normalize", "sq_kmeans_step", "sq_cluster_layout", "sq_cluster_nest", "sq_calibrate_threshold", "sq_hier_prefill_mean_step", "sq_hier_prefill_step", "sq_gqa_mean_decode_step", "sq_profile_begin",
            "sq_profile_end", "sq_probe_stream_read")
 
 
@@ -72,6 +72,7 @@ def lib() -> C.CDLL:
         L.sq_hier_select.argtypes = [sp, C.c_int32] + [vp] * 14 + [vp, sz, vp]
         L.sq_decode_step.argtypes = [sp] + [vp] * 13 + [vp, sz, vp]
         L.sq_hier_decode_step.argtypes = [sp, C.c_int32] + [vp] * 17 + [vp, sz, vp]
+        L.sq_hier_prefill_step.argtypes = [sp, C.c_int32] + [vp] * 17 + [vp, sz, vp]
         L.sq_hier_prefill_mean_step.argtypes = [sp, C.c_int32] + [vp] * 17 + [vp, sz, vp]
         L.sq_gqa_mean_decode_step.argtypes = [sp, C.c_int32] + [vp] * 13 + [vp, sz, vp]
         L.sq_gqa_decode_step.argtypes = [sp, C.c_int32] + [vp] * 13 + [vp, sz, vp]
@@ -336,15 +337,29 @@ def sq_calibrate_threshold(shape, logits, row_max, denom, sizes, target_keys, th
                                         _ptr(thresh, F32, "thresh"), *_ws_args(ws), _stream(stream)))
 
 
-def sq_hier_prefill_mean_step(shape, C1, q, centroids1, sizes1, child_offsets, thresh1, centroids2, sizes2, offsets2,
-                              thresh2, K_fixed, V_fixed, K_user, V_user, out, lse, keep_mask2, n_keys, ws, stream=None):
-    _check(lib().sq_hier_prefill_mean_step(
+def _hier_prefill(fn, shape, C1, q, centroids1, sizes1, child_offsets, thresh1, centroids2, sizes2, offsets2, thresh2,
+                  K_fixed, V_fixed, K_user, V_user, out, lse, keep_mask2, n_keys, ws, stream):
+    _check(fn(
         C.byref(shape), int(C1), _ptr(q, F16, "q"), _ptr(centroids1, F16, "centroids1"), _ptr(sizes1, I32, "sizes1"),
         _ptr(child_offsets, I32, "child_offsets"), _ptr(thresh1, F32, "thresh1"),
         _ptr(centroids2, F16, "centroids2"), _ptr(sizes2, I32, "sizes2"), _ptr(offsets2, I32, "offsets2"),
         _ptr(thresh2, F32, "thresh2"), _ptr(K_fixed, F16, "K_fixed"), _ptr(V_fixed, F16, "V_fixed"),
         _ptr(K_user, F16, "K_user"), _ptr(V_user, F16, "V_user"), _ptr(out, F16, "out"), _ptr(lse, F32, "lse"),
         _ptr(keep_mask2, I32, "keep_mask2"), _ptr(n_keys, I32, "n_keys"), *_ws_args(ws), _stream(stream)))
+
+
+def sq_hier_prefill_step(shape, C1, q, centroids1, sizes1, child_offsets, thresh1, centroids2, sizes2, offsets2, thresh2,
+                         K_fixed, V_fixed, K_user, V_user, out, lse, keep_mask2, n_keys, ws, stream=None):
+    """Per-token selection: keep_mask2 [B,H,Lq,W], n_keys [B,H,Lq]."""
+    _hier_prefill(lib().sq_hier_prefill_step, shape, C1, q, centroids1, sizes1, child_offsets, thresh1, centroids2,
+                  sizes2, offsets2, thresh2, K_fixed, V_fixed, K_user, V_user, out, lse, keep_mask2, n_keys, ws, stream)
+
+
+def sq_hier_prefill_mean_step(shape, C1, q, centroids1, sizes1, child_offsets, thresh1, centroids2, sizes2, offsets2,
+                              thresh2, K_fixed, V_fixed, K_user, V_user, out, lse, keep_mask2, n_keys, ws, stream=None):
+    """One kept set per (sequence, head): keep_mask2 [B,H,W], n_keys [B,H]."""
+    _hier_prefill(lib().sq_hier_prefill_mean_step, shape, C1, q, centroids1, sizes1, child_offsets, thresh1, centroids2,
+                  sizes2, offsets2, thresh2, K_fixed, V_fixed, K_user, V_user, out, lse, keep_mask2, n_keys, ws, stream)
 
 
 def sq_probe_stream_read(buf: torch.Tensor, sink: torch.Tensor, workgroups: int, nbytes: Optional[int] = None,

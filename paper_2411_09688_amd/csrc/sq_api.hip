@@ -311,6 +311,26 @@ PrefillMeanStepWs carve_prefill_mean_step(Carver &cv, const sq_shape_t *sh)
     return w;
 }
 
+// Workspace of the hierarchical prefill step with per-query selection: the one-level step's, plus the level-1 masks
+// and counts per token and the parent of every fine cluster.
+struct HierPrefillWs {
+    PrefillStepWs step;
+    uint32_t *mask1;
+    int32_t *nr1, *nk1, *parent;
+};
+
+HierPrefillWs carve_hier_prefill(Carver &cv, const sq_shape_t *sh)
+{
+    const size_t rows = (size_t)sh->B * sh->H * sh->Lq;
+    HierPrefillWs w{};
+    w.step = carve_prefill_step(cv, sh);
+    w.mask1 = cv.take<uint32_t>(rows * 32);                 // at most 1024 coarse clusters
+    w.nr1 = cv.take<int32_t>(rows);
+    w.nk1 = cv.take<int32_t>(rows);
+    w.parent = cv.take<int32_t>((size_t)sh->H * sh->C);
+    return w;
+}
+
 // Workspace of the hierarchical prefill step on averaged scores: the one-level step's, plus the records of the kept
 // coarse clusters' child ranges and the candidate list they expand to.
 struct HierPrefillMeanWs {
@@ -398,6 +418,9 @@ size_t sq_workspace_bytes(const sq_shape_t *sh, int which)
         return cv.off;
     case SQ_CALL_KMEANS_STEP:
         carve_kmeans(cv, sh);
+        return cv.off;
+    case SQ_CALL_HIER_PREFILL_STEP:
+        carve_hier_prefill(cv, sh);
         return cv.off;
     case SQ_CALL_GQA_MEAN_DECODE_STEP:                // sized for the largest group
         carve_step_shared(cv, sh, sq::SG);
@@ -984,6 +1007,55 @@ int sq_hier_decode_step(const sq_shape_t *sh, int32_t C1, const void *q, const v
         return rc;
     SQ_HIP(sq::launch_decode_attn(q, K_fixed, V_fixed, K_user, V_user, w.dec.plan, w.dec.partials, out, lse,
                                   to_shape(sh), s));
+    g_err[0] = 0;
+    return SQ_OK;
+}
+
+int sq_hier_prefill_step(const sq_shape_t *sh, int32_t C1, const void *q, const void *centroids1, const int32_t *sizes1,
+                         const int32_t *child_offsets, const float *thresh1, const void *centroids2,
+                         const int32_t *sizes2, const int32_t *offsets2, const float *thresh2, const void *K_fixed,
+                         const void *V_fixed, const void *K_user, const void *V_user, void *out, float *lse,
+                         uint32_t *keep_mask2, int32_t *n_keys, void *ws, size_t ws_bytes, void *stream)
+{
+    if (int rc = check_shape(sh, __func__, false)) return rc;
+    if (int rc = check_hier_args(__func__, sh, C1)) return rc;
+    if (C1 > 1024)
+        return fail(SQ_ERR_UNSUPPORTED, "%s: C1 = %d coarse clusters; per-query prefill supports at most 1024", __func__, C1);
+    SQ_REQUIRE_PTR(q);
+    SQ_REQUIRE_PTR(centroids1);
+    SQ_REQUIRE_PTR(sizes1);
+    SQ_REQUIRE_PTR(child_offsets);
+    SQ_REQUIRE_PTR(thresh1);
+    SQ_REQUIRE_PTR(centroids2);
+    SQ_REQUIRE_PTR(sizes2);
+    SQ_REQUIRE_PTR(offsets2);
+    SQ_REQUIRE_PTR(thresh2);
+    SQ_REQUIRE_PTR(K_fixed);
+    SQ_REQUIRE_PTR(V_fixed);
+    if (sh->U > 0) {
+        SQ_REQUIRE_PTR(K_user);
+        SQ_REQUIRE_PTR(V_user);
+    }
+    SQ_REQUIRE_PTR(out);
+    SQ_OPTIONAL_PTR(lse);
+    SQ_OPTIONAL_PTR(keep_mask2);
+    SQ_OPTIONAL_PTR(n_keys);
+    if (int rc = check_ws(__func__, sh, SQ_CALL_HIER_PREFILL_STEP, ws, ws_bytes)) return rc;
+    if (int rc = check_device(__func__)) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Carver cv(ws);
+    HierPrefillWs w = carve_hier_prefill(cv, sh);
+    uint32_t *mask2 = keep_mask2 ? keep_mask2 : w.step.mask;
+    // Level 1 (Eq. 2) per token over the coarse centroids; then every fine cluster's parent; then level 2 (Eq. 3) per
+    // token over the children of the coarse clusters that token kept.
+    SQ_HIP(sq::launch_prefill_lookup(q, centroids1, sizes1, thresh1, w.mask1, w.nr1, w.nk1, nullptr, false, sh->B, sh->H,
+                                     sh->Lq, C1, sh->sm_scale, s));
+    SQ_HIP(sq::launch_child_parent(child_offsets, w.parent, sh->H, C1, sh->C, s));
+    SQ_HIP(sq::launch_prefill_lookup(q, centroids2, sizes2, thresh2, mask2, w.step.n_ranges,
+                                     n_keys ? n_keys : w.step.n_keys, nullptr, false, sh->B, sh->H, sh->Lq, sh->C,
+                                     sh->sm_scale, s, nullptr, nullptr, w.parent, w.mask1, C1));
+    SQ_HIP(sq::launch_prefill_attn(q, K_fixed, V_fixed, K_user, V_user, mask2, offsets2, w.step.key_cid, w.step.blk_info,
+                                   out, lse, to_shape(sh), s));
     g_err[0] = 0;
     return SQ_OK;
 }

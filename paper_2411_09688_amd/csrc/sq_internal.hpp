@@ -68,7 +68,11 @@ __host__ __device__ inline int lookup_parts_for(int Lq) { return (Lq + LOOKUP_RO
 hipError_t launch_prefill_lookup(const void *q, const void *centroids, const int32_t *sizes, const float *thresh,
                                  uint32_t *keep_mask, int32_t *n_ranges, int32_t *n_keys, float *part_sum, bool mean,
                                  int B, int H, int Lq, int C, float sm_scale, hipStream_t s,
-                                 const int32_t *cand_id = nullptr, const int2 *cand_hdr = nullptr);
+                                 const int32_t *cand_id = nullptr, const int2 *cand_hdr = nullptr,
+                                 const int32_t *parent = nullptr, const uint32_t *mask1 = nullptr, int C1 = 0);
+// (parent [H, C] / mask1 [B*H*Lq, ceil(C1/32)] given, per-query mode: a cluster counts for a token only if the token's
+// level-1 mask holds its parent: level 2 of a hierarchical lookup with per-token candidates; C1 <= 1024.)
+hipError_t launch_child_parent(const int32_t *child_offsets, int32_t *parent, int H, int C1, int C2, hipStream_t s);
 // (cand_id [B*H, C] / cand_hdr [B*H] given, with mean: only the hdr.y candidates listed for a (sequence, head) are
 // scored, statistics over them alone, part_sum in candidate order: level 2 of a hierarchical lookup.)
 // Kept ranges (records of a plan) -> flat index lists idx [rows, L]: the key rows of the attention, or the candidate

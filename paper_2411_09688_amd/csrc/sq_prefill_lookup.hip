@@ -18,6 +18,10 @@
 //                  n candidates cand_id[bh, 0..n) of the (sequence, head) -- the children of the coarse clusters kept
 //                  one level up -- so maximum and normaliser run over the candidates only; part_sum is written in
 //                  candidate order.
+//   PARENTS == true (per-query selection) second level of a hierarchical lookup with per-token candidates: fine
+//                  cluster i counts for token t only if t kept its parent coarse cluster (bit parent[i] of the
+//                  token's level-1 mask); the others are treated like clusters without keys, so maximum,
+//                  normaliser and threshold test of Eq. 3 run over the token's candidates only.
 #include "sq_common.hpp"
 #include "sq_internal.hpp"
 
@@ -30,16 +34,21 @@ constexpr int LK_STRIDE = D + 8;             // halves per centroid row in LDS (
 struct LkStage {
     _Float16 Ct[LK_G * LK_STRIDE];
     int N[LK_G];
+    int P[LK_G];                             // parent coarse cluster (PARENTS only)
 };
 
-template <bool MEAN, bool CANDS = false>
+constexpr int LK_MAX_W1 = 32;                // level-1 mask words per token held in LDS: at most 1024 coarse clusters
+
+template <bool MEAN, bool CANDS = false, bool PARENTS = false>
 __global__ __launch_bounds__(256) void prefill_lookup_kernel(
     const _Float16 *__restrict__ q, const _Float16 *__restrict__ cent, const int32_t *__restrict__ sizes,
     const float *__restrict__ thresh, uint32_t *__restrict__ keep_mask, int32_t *__restrict__ n_ranges,
     int32_t *__restrict__ n_keys, float *__restrict__ part_sum, const int32_t *__restrict__ cand_id,
-    const int2 *__restrict__ cand_hdr, int H, int Lq, int C_all, float sm_scale)
+    const int2 *__restrict__ cand_hdr, const uint32_t *__restrict__ mask1, int W1, int H, int Lq, int C_all,
+    float sm_scale)
 {
     __shared__ __align__(16) LkStage stage[2];
+    __shared__ uint32_t s_m1[PARENTS ? 64 * LK_MAX_W1 : 1];   // level-1 masks of the workgroup's 64 tokens
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 15, kg = lane >> 4;
     const int bh = blockIdx.y, h = bh % H;
@@ -47,6 +56,14 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
     const int C = CANDS ? min(cand_hdr[bh].y, C_all) : C_all;
     if (CANDS && C <= 0) return;                            // no candidate: nothing to score (workgroup-uniform)
     const int32_t *cid = CANDS ? cand_id + (size_t)bh * C_all : nullptr;
+    const int32_t *par = PARENTS ? cand_id + (size_t)h * C_all : nullptr;     // (PARENTS: cand_id is parent [H, C])
+    if (PARENTS) {
+        for (int idx = threadIdx.x; idx < 64 * W1; idx += 256) {
+            const int t = idx / W1, w = idx - t * W1;
+            const int token = min((int)blockIdx.x * 64 + t, Lq - 1);
+            s_m1[t * W1 + w] = mask1[((size_t)bh * Lq + token) * W1 + w];
+        }
+    }
     const int q0 = (blockIdx.x * 4 + wave) * LOOKUP_ROWS;   // first token of this wave (may lie past the end)
     const int nq = q0 + col;
     const bool valid = nq < Lq;
@@ -65,7 +82,7 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
 
     // This thread's share of a group: rows i*16 + tid/16 (i = 0..3), 16-byte chunk tid%16; size of cluster tid.
     h8 pk[4];
-    int pn = 0;
+    int pn = 0, pp = 0;
     auto fetch = [&](int g) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -76,13 +93,17 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
         if (tid < LK_G) {                                                    // 0 past the last cluster
             const int c = g * LK_G + tid;
             pn = c < C ? Nh[CANDS ? min(max(cid[c], 0), C_all - 1) : c] : 0;
+            if (PARENTS) pp = c < C ? min(max(par[c], 0), W1 * 32 - 1) : 0;
         }
     };
     auto commit = [&](LkStage &st) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             *reinterpret_cast<h8 *>(st.Ct + (i * 16 + (tid >> 4)) * LK_STRIDE + (tid & 15) * 8) = pk[i];
-        if (tid < LK_G) st.N[tid] = pn;
+        if (tid < LK_G) {
+            st.N[tid] = pn;
+            if (PARENTS) st.P[tid] = pp;
+        }
     };
     // Logits of the staged group: x[u][v] = sm_scale * q . C_c, c = g*64 + u*16 + kg*4 + v, and the cluster sizes.
     auto scores = [&](const LkStage &st, float (&x)[LK_TU][4], int (&nv)[LK_TU][4]) {
@@ -99,6 +120,14 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
             nv[u][1] = n4.y;
             nv[u][2] = n4.z;
             nv[u][3] = n4.w;
+            if (PARENTS) {                                  // not a candidate of this lane's token: as if it had no keys
+                const int4 p4 = *reinterpret_cast<const int4 *>(st.P + u * 16 + kg * 4);
+                const uint32_t *mrow = s_m1 + (wave * 16 + col) * W1;
+                const int pv[4] = {p4.x, p4.y, p4.z, p4.w};
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (!((mrow[pv[v] >> 5] >> (pv[v] & 31)) & 1u)) nv[u][v] = 0;
+            }
 #pragma unroll
             for (int v = 0; v < 4; ++v) x[u][v] = acc[v] * sm_scale;
         }
@@ -206,22 +235,51 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
 hipError_t launch_prefill_lookup(const void *q, const void *centroids, const int32_t *sizes, const float *thresh,
                                  uint32_t *keep_mask, int32_t *n_ranges, int32_t *n_keys, float *part_sum, bool mean,
                                  int B, int H, int Lq, int C, float sm_scale, hipStream_t s, const int32_t *cand_id,
-                                 const int2 *cand_hdr)
+                                 const int2 *cand_hdr, const int32_t *parent, const uint32_t *mask1, int C1)
 {
     const dim3 grid((Lq + 4 * LOOKUP_ROWS - 1) / (4 * LOOKUP_ROWS), B * H);
-    if (cand_id) {
+    const uint32_t *no_mask = nullptr;
+    if (parent) {
+        if (mean || cand_id || !mask1 || C1 <= 0 || (C1 + 31) / 32 > LK_MAX_W1) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((prefill_lookup_kernel<false, false, true>), grid, dim3(256), 0, s, (const _Float16 *)q,
+                           (const _Float16 *)centroids, sizes, thresh, keep_mask, n_ranges, n_keys, part_sum, parent,
+                           (const int2 *)nullptr, mask1, (C1 + 31) / 32, H, Lq, C, sm_scale);
+    } else if (cand_id) {
         if (!mean || !cand_hdr) return hipErrorInvalidValue;
         hipLaunchKernelGGL((prefill_lookup_kernel<true, true>), grid, dim3(256), 0, s, (const _Float16 *)q,
                            (const _Float16 *)centroids, sizes, thresh, keep_mask, n_ranges, n_keys, part_sum, cand_id,
-                           cand_hdr, H, Lq, C, sm_scale);
+                           cand_hdr, no_mask, 0, H, Lq, C, sm_scale);
     } else if (mean)
         hipLaunchKernelGGL((prefill_lookup_kernel<true, false>), grid, dim3(256), 0, s, (const _Float16 *)q,
                            (const _Float16 *)centroids, sizes, thresh, keep_mask, n_ranges, n_keys, part_sum,
-                           (const int32_t *)nullptr, (const int2 *)nullptr, H, Lq, C, sm_scale);
+                           (const int32_t *)nullptr, (const int2 *)nullptr, no_mask, 0, H, Lq, C, sm_scale);
     else
         hipLaunchKernelGGL((prefill_lookup_kernel<false, false>), grid, dim3(256), 0, s, (const _Float16 *)q,
                            (const _Float16 *)centroids, sizes, thresh, keep_mask, n_ranges, n_keys, part_sum,
-                           (const int32_t *)nullptr, (const int2 *)nullptr, H, Lq, C, sm_scale);
+                           (const int32_t *)nullptr, (const int2 *)nullptr, no_mask, 0, H, Lq, C, sm_scale);
+    return hipGetLastError();
+}
+
+// parent[h, c] = the coarse cluster whose child range child_offsets[j] .. child_offsets[j+1]-1 holds fine cluster c
+// (binary search; C1 - 1 for ids past the last range).
+__global__ __launch_bounds__(256) void child_parent_kernel(const int32_t *__restrict__ child_offsets,
+                                                           int32_t *__restrict__ parent, int C1, int C2)
+{
+    const int h = blockIdx.y, c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= C2) return;
+    const int32_t *co = child_offsets + (size_t)h * (C1 + 1);
+    int lo = 0, hi = C1;                                     // invariant: co[lo] <= c (co[0] = 0), answer in [lo, hi)
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (co[mid] <= c) lo = mid;
+        else hi = mid;
+    }
+    parent[(size_t)h * C2 + c] = lo;
+}
+
+hipError_t launch_child_parent(const int32_t *child_offsets, int32_t *parent, int H, int C1, int C2, hipStream_t s)
+{
+    hipLaunchKernelGGL(child_parent_kernel, dim3((C2 + 255) / 256, H), dim3(256), 0, s, child_offsets, parent, C1, C2);
     return hipGetLastError();
 }
 
