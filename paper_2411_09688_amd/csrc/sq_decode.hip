@@ -20,6 +20,7 @@ namespace sq {
 
 constexpr int KW = KPC / 4;     // keys per wave
 constexpr int NI = KW / 4;      // loads per lane (4 rows per wave-wide load)
+constexpr int REG_RECORDS = 16; // chunks of at most this many records find their rows in registers (else through LDS)
 
 // Items per batch: the work list is cut into batches of this many consecutive items, ATTN_OVERSUB batches per
 // workgroup.  The partial kernel and the merge kernel derive it from the same two numbers.  Measured: more
@@ -56,7 +57,7 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
     // fetch.  (The grid never exceeds item_cap, so the speculative read stays inside the item array; slots
     // past the count hold stale data that is not used.)
     const int2 *it = plan.item + (size_t)blockIdx.x * ITEM_STRIDE;
-    int2 h0_next = it[0], h1_next = it[1], rec_next = it[2 + (tid < KPC ? tid : 0)];   // threads >= KPC idle here
+    int2 h0_next = it[0], h1_next = it[1], rec_next = it[2 + lane];   // every wave holds records 0..63 in its lanes
     const int total = min(*plan.total, plan.item_cap);
     const int kb = items_per_batch(total, (int)gridDim.x);
     const int n_batches = (total + kb - 1) / kb;
@@ -66,7 +67,7 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
         it = plan.item + (size_t)batch * kb * ITEM_STRIDE;
         h0_next = it[0];
         h1_next = it[1];
-        rec_next = it[2 + (tid < KPC ? tid : 0)];
+        rec_next = it[2 + lane];
     }
 
     // Running state of the current (batch, row) segment.  m is wave-uniform; l and o are this lane's
@@ -139,25 +140,53 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
             const int h = (int)(bkv % H);
             const _Float16 *Kbase, *Vbase;
             const h8 qv = *reinterpret_cast<const h8 *>(q + bh * D + p * 8);
+            // Rows of this lane's NI key slots (slot = wave * KW + i * 4 + g) and of the chunk's last valid slot.
+            // A slot lies in the last record whose position is <= the slot and reads row slot + delta.  With few
+            // records (the usual case: a chunk of 128 keys spans a handful of clusters) the records are broadcast
+            // from the wave's lanes and the rows found in registers: no LDS, no barrier on the way to the K/V loads.
+            int rows[NI], r_last;
             if (user) {
                 Kbase = Ku + (bkv * U + h1.y) * D;
                 Vbase = Vu + (bkv * U + h1.y) * D;
-                if (tid < KPC) s_rows[tid] = tid < nvalid ? tid : -1;
+#pragma unroll
+                for (int i = 0; i < NI; ++i) rows[i] = wave * KW + i * 4 + g;
+                r_last = nvalid - 1;
             } else {
                 Kbase = Kf + (size_t)h * L * D;
                 Vbase = Vf + (size_t)h * L * D;
-                chunk_rows_from_records<KPC>(rc.x, rc.y, nrec, nvalid, L, s_pos, s_delta, s_rows, tid);
+                if (nrec <= REG_RECORDS) {                  // workgroup-uniform
+                    int dl[NI], d_last;
+                    const int d0 = __builtin_amdgcn_readlane(rc.y, 0);
+#pragma unroll
+                    for (int i = 0; i < NI; ++i) dl[i] = d0;
+                    d_last = d0;
+                    for (int r = 1; r < nrec; ++r) {
+                        const int pr = __builtin_amdgcn_readlane(rc.x, r), dr = __builtin_amdgcn_readlane(rc.y, r);
+#pragma unroll
+                        for (int i = 0; i < NI; ++i)
+                            if (pr <= wave * KW + i * 4 + g) dl[i] = dr;
+                        if (pr <= nvalid - 1) d_last = dr;
+                    }
+#pragma unroll
+                    for (int i = 0; i < NI; ++i) rows[i] = max(0, min(wave * KW + i * 4 + g + dl[i], L - 1));
+                    r_last = max(0, min(nvalid - 1 + d_last, L - 1));
+                } else {
+                    const int2 rcl = plan.item[(size_t)item * ITEM_STRIDE + 2 + (tid < KPC ? tid : 0)];
+                    __syncthreads();                        // (the previous item's readers of s_rows are done)
+                    chunk_rows_from_records<KPC>(rcl.x, rcl.y, nrec, nvalid, L, s_pos, s_delta, s_rows, tid);
+                    __syncthreads();
+#pragma unroll
+                    for (int i = 0; i < NI; ++i) rows[i] = s_rows[wave * KW + i * 4 + g];
+                    r_last = s_rows[nvalid - 1];
+                }
             }
-            __syncthreads();
 
             // Issue every K and V load of this lane.
             h8 kreg[NI], vreg[NI];
-            const int r_last = s_rows[nvalid - 1];
 #pragma unroll
             for (int i = 0; i < NI; ++i) {
                 const int kl = wave * KW + i * 4 + g;
-                int r = s_rows[kl];
-                r = r < 0 ? r_last : r;                       // slots past the chunk re-read a valid row
+                const int r = kl < nvalid ? rows[i] : r_last;     // slots past the chunk re-read a valid row
                 const size_t off = (size_t)r * D + p * 8;
                 kreg[i] = *reinterpret_cast<const h8 *>(Kbase + off);
                 vreg[i] = *reinterpret_cast<const h8 *>(Vbase + off);
@@ -169,7 +198,7 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
                 const int2 *nx = plan.item + (size_t)item_nx * ITEM_STRIDE;
                 h0_next = nx[0];
                 h1_next = nx[1];
-                rec_next = nx[2 + (tid < KPC ? tid : 0)];
+                rec_next = nx[2 + lane];
             }
 
             // Scores of this lane-group's keys, folded into the running softmax.
@@ -196,7 +225,6 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
                 for (int e = 0; e < 8; ++e) o[e] += pr * (float)vreg[i][e];
             }
             m_run = m_new;
-            __syncthreads();      // s_rows is rewritten by the next item
         }
         flush(seg_first);
         batch += (int)gridDim.x;
