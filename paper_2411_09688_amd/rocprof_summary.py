@@ -22,14 +22,14 @@ def _find(d, suffix):
 
 
 def stats(d):
-    rows = list(csv.DictReader(open(_find(d, "kernel_stats.csv"))))
+    rows = [r for r in csv.DictReader(open(_find(d, "kernel_stats.csv"))) if "rocclr" not in r["Name"]]
+    # percentages over the kernels listed (the runtime's own copy kernels are left out)
+    total = sum(float(r["AverageNs"]) * int(r["Calls"]) for r in rows) or 1.0
     print(f"{'kernel':72s} {'calls':>7s} {'avg_us':>9s} {'min_us':>9s} {'max_us':>9s} {'pct':>6s}")
     for r in rows:
-        name = r["Name"]
-        if "rocclr" in name:
-            continue
-        print(f"{name[:72]:72s} {r['Calls']:>7s} {float(r['AverageNs']) / 1e3:9.2f} {float(r['MinNs']) / 1e3:9.2f} "
-              f"{float(r['MaxNs']) / 1e3:9.2f} {float(r['Percentage']):6.2f}")
+        share = 100.0 * float(r["AverageNs"]) * int(r["Calls"]) / total
+        print(f"{r['Name'][:72]:72s} {r['Calls']:>7s} {float(r['AverageNs']) / 1e3:9.2f} {float(r['MinNs']) / 1e3:9.2f} "
+              f"{float(r['MaxNs']) / 1e3:9.2f} {share:6.2f}")
 
 
 def pmc(d, counter):
