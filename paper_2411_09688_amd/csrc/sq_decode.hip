@@ -22,24 +22,43 @@ constexpr int KW = KPC / 4;     // keys per wave
 constexpr int NI = KW / 4;      // loads per lane (4 rows per wave-wide load)
 constexpr int REG_RECORDS = 16; // chunks of at most this many records find their rows in registers (else through LDS)
 
-// Items per batch: the work list is cut into batches of this many consecutive items, ATTN_OVERSUB batches per
-// workgroup.  The partial kernel and the merge kernel derive it from the same two numbers.  Measured: more
-// than one batch per workgroup buys no better balance (a step of config 2 stays within 1 %) and costs more
-// partial results to write and merge (config 5: merge 6.7 -> 14.2 us), so it is 1.
-constexpr int ATTN_OVERSUB = 1;
-__device__ __forceinline__ int items_per_batch(int total, int grid)
+// How the work list of `total` items is split over the G workgroups of the partial kernel (the merge kernel derives
+// the same numbers).  Compute units take workgroups round robin and each streams at the same rate, so what counts is
+// equal bytes per compute unit.
+//   total <= G        workgroup w takes item w;
+//   total <  2 G      workgroup w takes item w and, for w < total - G, also item G + w: with four workgroups per
+//                     compute unit that is 4 or 5 chunks each (runs of two consecutive items over total / 2
+//                     workgroups would give 4 or 6); the first item is item w itself, fetched before the count is known;
+//   otherwise         runs of kq = ceil(total / G) consecutive items (8 or 9 chunks per workgroup hardly differ, and
+//                     consecutive chunks of a row fold into one partial result).
+struct WorkSplit {
+    int kq, rem, R;                      // items per run, items past the runs, first index past the runs
+};
+__device__ __forceinline__ WorkSplit work_split(int total, int grid)
 {
-    return max(1, (total + grid * ATTN_OVERSUB - 1) / (grid * ATTN_OVERSUB));
+    WorkSplit ws;
+    if (total < 2 * grid) {
+        ws.kq = 1;
+        ws.R = min(total, grid);
+        ws.rem = total - ws.R;
+    } else {
+        ws.kq = (total + grid - 1) / grid;
+        ws.R = total;
+        ws.rem = 0;
+    }
+    return ws;
 }
+// Index (past the runs) of the extra item of workgroup w, or -1.
+__device__ __forceinline__ int extra_of(const WorkSplit &ws, int w) { return w < ws.rem ? w : -1; }
 
-// Phase 1: one work item = one chunk of up to KPC keys of one (sequence, head) row.  The grid is a fixed
-// number G of workgroups; the work list is cut into batches of kb consecutive items and workgroup w takes
-// batches w, w + G, w + 2G, ... (one batch with ATTN_OVERSUB = 1).  Every workgroup streams the same number of
-// keys whatever the selection looks like, and no workgroup is launched for chunks that do not exist.  (Handing
-// the batches out through a device-wide counter was measured too: a thousand increments of one address
-// serialise, and the step got 4 us slower.)
-// Consecutive items of one row inside a batch are folded into one running (max, sum, output) per lane, so a
-// partial result is written once per (batch, row) segment, at the index of the segment's first item.
+// Phase 1: one work item = one chunk of up to KPC keys of one (sequence, head) row.  The grid is a fixed number of
+// workgroups and the work list is split over them as described at work_split: no workgroup is launched for chunks
+// that do not exist.  (Handing items out through a device-wide counter was measured too: a thousand increments of one
+// address serialise, and the step got 4 us slower.  Several runs per workgroup buy no better balance and cost more
+// partial results to merge.)
+// Consecutive items of one row inside a run are folded into one running (max, sum, output) per lane, so a
+// partial result is written once per (run, row) segment, at the index of the segment's first item; an extra item
+// is a segment of its own.
 __global__ __launch_bounds__(256) void decode_attn_kernel(
     const _Float16 *__restrict__ q, const _Float16 *__restrict__ Kf, const _Float16 *__restrict__ Vf,
     const _Float16 *__restrict__ Ku, const _Float16 *__restrict__ Vu, DecodePlan plan,
@@ -53,24 +72,27 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
     const int g = lane >> 4, p = lane & 15;
 
     // The work list is read with as few dependent round trips as possible: the item this workgroup starts with
-    // when a batch is one item is fetched together with the item count; only a longer list costs a second
-    // fetch.  (The grid never exceeds item_cap, so the speculative read stays inside the item array; slots
+    // when the list is shorter than twice the grid is fetched together with the item count; only a longer list
+    // costs a second fetch.  (The grid never exceeds item_cap, so the speculative read stays inside the item array; slots
     // past the count hold stale data that is not used.)
     const int2 *it = plan.item + (size_t)blockIdx.x * ITEM_STRIDE;
     int2 h0_next = it[0], h1_next = it[1], rec_next = it[2 + lane];   // every wave holds records 0..63 in its lanes
     const int total = min(*plan.total, plan.item_cap);
-    const int kb = items_per_batch(total, (int)gridDim.x);
-    const int n_batches = (total + kb - 1) / kb;
-    int batch = blockIdx.x;
-    if (batch >= n_batches) return;                        // whole workgroup
-    if (kb != 1) {
-        it = plan.item + (size_t)batch * kb * ITEM_STRIDE;
+    const WorkSplit ws = work_split(total, (int)gridDim.x);
+    const int run0 = (int)blockIdx.x * ws.kq;               // this workgroup's run [run0, run0 + run_len)
+    const int run_len = run0 < ws.R ? min(ws.kq, ws.R - run0) : 0;
+    const int extra = extra_of(ws, (int)blockIdx.x);
+    const int n_my = run_len + (extra >= 0 ? 1 : 0);
+    if (n_my == 0) return;                                 // whole workgroup
+    auto item_at = [&](int j) { return j < run_len ? run0 + j : ws.R + extra; };
+    if (item_at(0) != (int)blockIdx.x) {                   // (only lists of 2 G items or more)
+        it = plan.item + (size_t)item_at(0) * ITEM_STRIDE;
         h0_next = it[0];
         h1_next = it[1];
         rec_next = it[2 + lane];
     }
 
-    // Running state of the current (batch, row) segment.  m is wave-uniform; l and o are this lane's
+    // Running state of the current (run, row) segment.  m is wave-uniform; l and o are this lane's
     // share (its 16-lane group's keys), summed over the four groups only when the segment is flushed.
     float m_run, l_run;
     float o[8];
@@ -110,18 +132,17 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
         __syncthreads();
     };
 
-    for (;;) {                                             // one batch per trip
-        int item = batch * kb;
-        const int item_end = min(item + kb, total);
+    {
         m_run = SQ_NEG_INF;
         l_run = 0.0f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[e] = 0.0f;
-        int seg_first = item;
+        int seg_first = item_at(0);
         int cur_row = h0_next.x;
-        for (; item < item_end; ++item) {
+        for (int j = 0; j < n_my; ++j) {
+            const int item = item_at(j);
             const int2 h0 = h0_next, h1 = h1_next, rc = rec_next;   // (row, keys) (records | -1, first user key)
-            if (h0.x != cur_row) {                         // workgroup-uniform: the segment of the previous row ends
+            if (h0.x != cur_row || (j == run_len && j > 0)) {   // workgroup-uniform: the previous segment ends
                 flush(seg_first);
                 m_run = SQ_NEG_INF;
                 l_run = 0.0f;
@@ -191,11 +212,10 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
                 kreg[i] = *reinterpret_cast<const h8 *>(Kbase + off);
                 vreg[i] = *reinterpret_cast<const h8 *>(Vbase + off);
             }
-            // Metadata of the next item (the batch's next one, or the first of this workgroup's next batch),
+            // Metadata of this workgroup's next item,
             // fetched behind the K/V stream.
-            const int item_nx = item + 1 < item_end ? item + 1 : (batch + (int)gridDim.x) * kb;
-            if (item_nx < total) {
-                const int2 *nx = plan.item + (size_t)item_nx * ITEM_STRIDE;
+            if (j + 1 < n_my) {
+                const int2 *nx = plan.item + (size_t)item_at(j + 1) * ITEM_STRIDE;
                 h0_next = nx[0];
                 h1_next = nx[1];
                 rec_next = nx[2 + lane];
@@ -227,8 +247,6 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
             m_run = m_new;
         }
         flush(seg_first);
-        batch += (int)gridDim.x;
-        if (batch >= n_batches) break;
     }
 }
 
@@ -243,11 +261,18 @@ __global__ __launch_bounds__(MERGE_THREADS) void decode_merge_kernel(const float
     const size_t bh = blockIdx.x;
     const int2 it = plan.row_items[bh];              // (first item, items) of this row
     const int total = min(*plan.total, plan.item_cap);
-    const int k = items_per_batch(total, attn_grid);               // items per batch of the partial kernel
-    const int n = it.y == 0 ? 0 : 1 + (it.x + it.y - 1) / k - it.x / k;
-    // The row's partials sit at item indices `first` and every multiple of k inside (first, first + items).
-    const int first = it.x, fk = first / k;
-    auto slot_ptr = [&](int c) { return partials + (size_t)(c == 0 ? first : (fk + c) * k) * PART_STRIDE; };
+    const WorkSplit ws = work_split(total, attn_grid);
+    // The row's items are [first, first + items).  Inside the runs its partials sit at `first` and at every multiple
+    // of kq inside (first, end of the row or of the runs); past the runs every item has a partial of its own.
+    const int first = it.x, last = it.x + it.y, kq = ws.kq, fk = first / kq;
+    const int e1 = min(last, ws.R);
+    const int n_run = (it.y > 0 && first < ws.R) ? 1 + (e1 - 1) / kq - fk : 0;
+    const int t0 = max(first, ws.R);
+    const int n = n_run + max(0, last - t0);
+    auto slot_ptr = [&](int c) {
+        const int idx = c >= n_run ? t0 + (c - n_run) : (c == 0 ? first : (fk + c) * kq);
+        return partials + (size_t)idx * PART_STRIDE;
+    };
     merge_row<false>(slot_ptr, n, out + bh * D, lse ? lse + bh : nullptr, s_red, threadIdx.x);
 }
 
