@@ -33,6 +33,27 @@
 
 namespace sq {
 
+// The work list of `total` items is cut into one run of consecutive items per workgroup, kq = total / G items each
+// and one more for the first total % G workgroups: every workgroup is busy, and since compute units take workgroups
+// round robin and stream at the same rate each, every compute unit gets the same number of chunks to within three.
+struct RunSplit {
+    int kq, rem;
+    __device__ __forceinline__ int start(int w) const { return w * kq + min(w, rem); }
+    __device__ __forceinline__ int owner(int x) const      // the workgroup whose run holds item x
+    {
+        const int head = rem * (kq + 1);                   // items held by the longer runs
+        return x < head ? x / (kq + 1) : rem + (x - head) / max(kq, 1);
+    }
+};
+__device__ __forceinline__ RunSplit run_split(int total, int grid)
+{
+    RunSplit rs;
+    rs.kq = total / grid;
+    rs.rem = total - rs.kq * grid;
+    return rs;
+}
+
+
 static_assert(KPC == 128 && SG == 16, "the shared-context kernel is written for 128-key chunks and 16 sequences");
 constexpr int SV_STRIDE = 40;    // halves per V^T row in LDS: 32 keys + 8 of padding (80 B)
 
@@ -75,9 +96,9 @@ __global__ __launch_bounds__(256, 3) void decode_attn_shared_kernel(
     const int j0 = wave * 32;                              // this wave's 32 key slots of every item
 
     const int total = min(plan.total[0], plan.item_cap);
-    const int ki = (total + (int)gridDim.x - 1) / (int)gridDim.x;   // items per workgroup
-    int item = blockIdx.x * ki;
-    const int item_end = min(item + ki, total);
+    const RunSplit rs = run_split(total, (int)gridDim.x);
+    int item = rs.start((int)blockIdx.x);
+    const int item_end = rs.start((int)blockIdx.x + 1);
     if (item >= item_end) return;                          // whole workgroup
 
     const float c2 = sm_scale * 1.44269504088896341f;      // exp(sm_scale * s) = exp2(c2 * s)
@@ -311,9 +332,9 @@ __global__ __launch_bounds__(MERGE_THREADS) void decode_merge_shared_kernel(cons
     const int2 it = plan.row_items[urow];            // (first item, items) of the union row
     const int rank = plan.row_rank[urow];
     const int total = min(plan.total[0], plan.item_cap);
-    const int ki = max(1, (total + attn_grid - 1) / attn_grid);    // items per attention workgroup
-    const int w_lo = it.x / ki;
-    const int n = it.y == 0 ? 0 : (it.x + it.y - 1) / ki - w_lo + 1;
+    const RunSplit rs = run_split(total, attn_grid);
+    const int w_lo = rs.owner(it.x);                 // the attention workgroups that hold the row's items
+    const int n = it.y == 0 ? 0 : rs.owner(it.x + it.y - 1) - w_lo + 1;
     auto slot_ptr = [&](int c) { return partials + ((size_t)(w_lo + c + rank) * SG + sq_) * PART_STRIDE; };
     merge_row<true>(slot_ptr, n, out + bh * D, lse ? lse + bh : nullptr, s_red, threadIdx.x);
 }
