@@ -235,6 +235,28 @@ __device__ __forceinline__ void wave_select_mask(const float *__restrict__ x, co
     }
 }
 
+// Sets bit `id` of an LDS bit mask for every lane with `keep`, called by a whole wave.  Candidates are listed in
+// ascending id order and the children of a kept cluster are consecutive, so the kept lanes of a wave usually hold
+// ids base + lane: their ballot, shifted by base % 32, IS the content of at most three mask words, written by three
+// lanes -- instead of up to 32 lanes contending for one word.  Any other pattern falls back to one atomic per lane.
+__device__ __forceinline__ void wave_mask_or(uint32_t *mask, int id, bool keep, int lane)
+{
+    const unsigned long long bal = __ballot(keep);
+    if (bal == 0ull) return;                                  // wave-uniform
+    const int first = __ffsll((long long)bal) - 1;
+    const int base = __builtin_amdgcn_readlane(id, first) - first;
+    if (__ballot(keep && id != base + lane) == 0ull) {
+        const int s = base & 31, w0 = base >> 5;              // floor division: base may be negative (unkept low lanes)
+        uint32_t v = 0u;
+        if (lane == 0) v = (uint32_t)(bal << s);
+        else if (lane == 1) v = s ? (uint32_t)(bal >> (32 - s)) : (uint32_t)(bal >> 32);
+        else if (lane == 2) v = s ? (uint32_t)(bal >> (64 - s)) : 0u;
+        if (lane < 3 && v != 0u) atomicOr(&mask[w0 + lane], v);   // (a word below 0 would hold no bit: v == 0)
+    } else if (keep) {
+        atomicOr(&mask[id >> 5], 1u << (id & 31));
+    }
+}
+
 // UNION: the row is a union row (sequence group, head) of a batched decode over a shared context.  First every
 // sequence of the group is selected by one wave of the workgroup (logits [B*H, C]; keep_mask, n_ranges, n_keys
 // are the per-sequence outputs), then cluster i is kept for the union row iff any sequence of the group kept
@@ -436,8 +458,8 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
             if (i < n) {
                 s_e[i] = __int_as_float(sv[st]);
                 if (opt.len_from_offsets) s_N[i] = idv[st] >= 0 ? lv[st] - sv[st] : 0;
-                if (CAND && idv[st] >= 0) atomicOr(&s_mask[idv[st] >> 5], 1u << (idv[st] & 31));   // mask bit by cluster id
             }
+            if (CAND) wave_mask_or(s_mask, idv[st], i < n && idv[st] >= 0, lane);   // mask bit by cluster id
         }
     }
     // Entry i of step st: kept?, first key and length of its range.
@@ -470,7 +492,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
                 if (w0 + 1 < W) keep_mask[row * W + w0 + 1] = (uint32_t)(bal >> 32);
             }
         }
-        if (CAND && !staged_ranges && keep) atomicOr(&s_mask[id_first >> 5], 1u << (id_first & 31));
+        if (CAND && !staged_ranges) wave_mask_or(s_mask, id_first, keep, lane);
     }
     __syncthreads();
     if (CAND && keep_mask)
