@@ -209,8 +209,10 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
                 const int kl = wave * KW + i * 4 + g;
                 const int r = kl < nvalid ? rows[i] : r_last;     // slots past the chunk re-read a valid row
                 const size_t off = (size_t)r * D + p * 8;
-                kreg[i] = *reinterpret_cast<const h8 *>(Kbase + off);
-                vreg[i] = *reinterpret_cast<const h8 *>(Vbase + off);
+                // (streamed once: non-temporal loads keep the rows from displacing the centroids, records and
+                // partial results that the step's other kernels find in the cache)
+                kreg[i] = __builtin_nontemporal_load(reinterpret_cast<const h8 *>(Kbase + off));
+                vreg[i] = __builtin_nontemporal_load(reinterpret_cast<const h8 *>(Vbase + off));
             }
             // Metadata of this workgroup's next item,
             // fetched behind the K/V stream.
