@@ -29,20 +29,24 @@ bool profile_pair(hipEvent_t *start, hipEvent_t *stop)
 }  // namespace sq
 
 namespace sq {
-// Plain streaming read: every lane loads 16 bytes per step, grid-stride, and folds them into one word
-// per workgroup so the loads cannot be dropped.  The ceiling an HBM-bound kernel can approach.
-__global__ __launch_bounds__(256) void stream_read_kernel(const uint4 *__restrict__ src, size_t n16,
+// Plain streaming read: every lane loads 16 bytes per step (non-temporal loads, what a kernel that reads its data
+// once would use), grid-stride, and folds them into one word per workgroup so the loads cannot be dropped.  The
+// ceiling an HBM-bound kernel can approach.
+typedef unsigned u4v __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void stream_read_kernel(const u4v *__restrict__ src, size_t n16,
                                                           unsigned *__restrict__ sink)
 {
     const size_t stride = (size_t)gridDim.x * 256;
     size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     unsigned acc = 0;
     for (; i + 3 * stride < n16; i += 4 * stride) {
-        const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        const u4v a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + stride),
+                  c = __builtin_nontemporal_load(src + i + 2 * stride), d = __builtin_nontemporal_load(src + i + 3 * stride);
         acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
     }
     for (; i < n16; i += stride) {
-        const uint4 a = src[i];
+        const u4v a = __builtin_nontemporal_load(src + i);
         acc ^= a.x ^ a.y ^ a.z ^ a.w;
     }
     if (acc == 0x9e3779b9u) sink[blockIdx.x & 255] = acc;     // practically never true; keeps the loads live
@@ -56,7 +60,7 @@ int sq_probe_stream_read(const void *buf, size_t bytes, void *sink, int workgrou
     if (!buf || !sink || bytes < 16 || workgroups <= 0 || (reinterpret_cast<uintptr_t>(buf) & 15u))
         return SQ_ERR_INVALID_ARG;
     hipLaunchKernelGGL(sq::stream_read_kernel, dim3(workgroups), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<const uint4 *>(buf), bytes / 16, static_cast<unsigned *>(sink));
+                       static_cast<const sq::u4v *>(buf), bytes / 16, static_cast<unsigned *>(sink));
     return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_HIP;
 }
 
