@@ -88,6 +88,7 @@ struct SelectOpts {
     int union_rows;                  // shared-context decode: rows are union rows (sequence group, head)
     int B;                           // shared-context decode: number of query rows that share a head's K/V (B * G)
     int G;                           // shared-context decode: query rows per (sequence, head), see shared_row
+    int replay;                      // set by launch_select: multi-step rows write their work items from the staged row
 };
 
 // Batched decode over a shared fixed context: sequences are handled in groups of SG; a "union row" is one

@@ -562,28 +562,49 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     bool have_rec = false;                                   // this thread's record of the (only) step
     int my_r = 0;
     int4 my_rec = make_int4(0, 0, 0, 0);
-    for (int st = 0; st < n_steps; ++st) {
-        const int i = st * SEL_THREADS + tid;
-        bool keep;
-        int start, len;
-        entry(st, i, keep, start, len);
-        const bool emit = keep && len > 0;
-        const unsigned long long bal_emit = __ballot(emit);
-        if (bal_emit == 0ull) continue;                  // wave-uniform
-        const int rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(bal_emit >> 32),
-                                                   __builtin_amdgcn_mbcnt_lo((uint32_t)bal_emit, 0));
-        const int kv = emit ? len : 0;
-        const int incl = wave_inclusive_scan(kv, lane);
-        if (emit) {
-            const int r = (n_steps == 1 ? pre_r : s_tcnt[st * SEL_WAVES + wave]) + rank;
-            const int kbefore = (n_steps == 1 ? pre_k : s_tkeys[st * SEL_WAVES + wave]) + incl - kv;
-            if (ranges) *reinterpret_cast<int2 *>(ranges + (row * C + r) * 2) = make_int2(start, len);
-            my_rec = make_int4(start, len, kbefore, UNION ? (int)s_set[i] : 0);
-            my_r = r;
-            have_rec = true;
-            if (plan.rec) plan.rec[row * plan.rec_cap + r] = my_rec;
+    // Walks the row's records in order: fn(r, (first key, keys, keys before, set)) for every kept entry with keys,
+    // r and the key prefix from the (step, wave) table plus a ballot and a lane scan.  Can be run more than once:
+    // the staged row stays in LDS.
+    auto for_each_record = [&](auto &&fn) {
+        for (int st = 0; st < n_steps; ++st) {
+            const int i = st * SEL_THREADS + tid;
+            bool keep;
+            int start, len;
+            entry(st, i, keep, start, len);
+            const bool emit = keep && len > 0;
+            const unsigned long long bal_emit = __ballot(emit);
+            if (bal_emit == 0ull) continue;              // wave-uniform
+            const int rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(bal_emit >> 32),
+                                                       __builtin_amdgcn_mbcnt_lo((uint32_t)bal_emit, 0));
+            const int kv = emit ? len : 0;
+            const int incl = wave_inclusive_scan(kv, lane);
+            if (emit) {
+                const int r = (n_steps == 1 ? pre_r : s_tcnt[st * SEL_WAVES + wave]) + rank;
+                const int kbefore = (n_steps == 1 ? pre_k : s_tkeys[st * SEL_WAVES + wave]) + incl - kv;
+                fn(r, make_int4(start, len, kbefore, UNION ? (int)s_set[i] : 0));
+            }
         }
-    }
+    };
+    // Rows of more than one step that schedule (opt.replay: the table below fits behind the staged row): the work
+    // items are written from two walks over the records instead of reading them back from memory.  Walk 1 (together
+    // with the outputs) notes, per chunk of KPC kept keys, the record that holds the chunk's first key (bit 31: the
+    // record begins exactly there); walk 2 copies every record into the chunks it touches.
+    const bool replay = SCHEDULE && n_steps > 1 && opt.replay;     // workgroup-uniform
+    int *s_tab = reinterpret_cast<int *>(smem + (size_t)C * 8);
+    const int n_sel = SCHEDULE ? min(base_k, plan.L) : 0;
+    const int n_fixed = (n_sel + KPC - 1) / KPC;
+    constexpr uint32_t EXACT = 0x80000000u;
+    for_each_record([&](int r, const int4 rc) {
+        if (ranges) *reinterpret_cast<int2 *>(ranges + (row * C + r) * 2) = make_int2(rc.x, rc.y);
+        my_rec = rc;
+        my_r = r;
+        have_rec = true;
+        if (plan.rec && !replay) plan.rec[row * plan.rec_cap + r] = rc;
+        if (replay) {
+            const int c_lo = (rc.z + KPC - 1) / KPC, c_hi = min((rc.z + rc.y - 1) / KPC, n_fixed - 1);
+            for (int c = c_lo; c <= c_hi; ++c) s_tab[c] = (int)((uint32_t)r | (rc.z == c * KPC ? EXACT : 0u));
+        }
+    });
     if (tid == 0) {
         if (!UNION) {                                        // a union row has no outputs of its own
             n_ranges[row] = base_r;
@@ -591,10 +612,44 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
         }
         if (plan.rec) plan.hdr[row] = make_int2(base_r, base_k);
     }
-    if (SCHEDULE) {
+    if (SCHEDULE && replay) {
+        const int n_uc = n_user_chunks * n_real;            // every real sequence of a union row has its own user keys
+        __syncthreads();                                    // the chunk table is complete
+        const int base = s_base;
+        if (tid == 0) plan.row_items[row] = make_int2(base, n_uc + n_fixed);
+        for (int c = tid; c < n_uc; c += SEL_THREADS) {
+            int2 *it = plan.item + (size_t)(base + c) * ITEM_STRIDE;
+            const int seq = UNION ? c / n_user_chunks : 0, cu = UNION ? c % n_user_chunks : c;
+            it[0] = make_int2((int)row, min(KPC, U - cu * KPC));
+            it[1] = make_int2(-1 - seq, cu * KPC);
+        }
+        for_each_record([&](int r, const int4 rc) {
+            const int c_lo = rc.z / KPC, c_hi = min((rc.z + rc.y - 1) / KPC, n_fixed - 1);
+            for (int c = c_lo; c <= c_hi; ++c) {
+                int2 *it = plan.item + (size_t)(base + n_uc + c) * ITEM_STRIDE;
+                const int pos = rc.z - c * KPC;              // negative for a record that began in an earlier chunk
+                const int first = (int)((uint32_t)s_tab[c] & ~EXACT);
+                it[2 + r - first] = make_int2(UNION ? (int)((uint32_t)max(pos, 0) | ((uint32_t)rc.w << 16)) : pos, rc.x - pos);
+            }
+        });
+        // Chunk headers.  The last record touching chunk c is the first record of chunk c+1 if that record began
+        // before the boundary, else the one before it.
+        for (int c = tid; c < n_fixed; c += SEL_THREADS) {
+            int2 *it = plan.item + (size_t)(base + n_uc + c) * ITEM_STRIDE;
+            const int first = (int)((uint32_t)s_tab[c] & ~EXACT);
+            int last;
+            if (c + 1 < n_fixed) {
+                const uint32_t t = (uint32_t)s_tab[c + 1];
+                last = (int)(t & ~EXACT) - ((t & EXACT) ? 1 : 0);
+            } else {
+                last = base_r - 1;
+            }
+            it[0] = make_int2((int)row, min(KPC, n_sel - c * KPC));
+            it[1] = make_int2(last - first + 1, 0);
+        }
+    } else if (SCHEDULE) {
         // This row's work items (their base was taken above).  The records written above are read back after
         // the barrier.
-        const int n_sel = min(base_k, plan.L);
         const int n_uc = n_user_chunks * n_real;            // every real sequence of a union row has its own user keys
         __syncthreads();                                    // every thread is done with the staged row (s_first aliases it)
         int *s_first = reinterpret_cast<int *>(smem);       // the staged logits are no longer needed
@@ -708,6 +763,12 @@ hipError_t launch_select(const float *logits, const float *row_max, const float 
     // LDS: logits + sizes of the row; reused for two ints per chunk when scheduling.
     size_t smem = (size_t)C * 8;
     if (schedule && (size_t)chunk_cap_for(plan.L) * 8 > smem) smem = (size_t)chunk_cap_for(plan.L) * 8;
+    // Rows of more than one step build their work items from the staged row when the per-chunk table fits behind it.
+    opt.replay = 0;
+    if (schedule && C > SEL_THREADS && (size_t)C * 8 + (size_t)chunk_cap_for(plan.L) * 4 <= (size_t)LDS_BYTES_MAX) {
+        opt.replay = 1;
+        if ((size_t)C * 8 + (size_t)chunk_cap_for(plan.L) * 4 > smem) smem = (size_t)C * 8 + (size_t)chunk_cap_for(plan.L) * 4;
+    }
     if (opt.union_rows && (size_t)SG * ((C + 31) / 32) * 4 > smem) smem = (size_t)SG * ((C + 31) / 32) * 4;   // the group's masks
     if (smem > (size_t)LDS_BYTES_MAX) return hipErrorInvalidValue;
     static bool attr_set = false;   // one GPU per process in this build
