@@ -195,4 +195,15 @@ __device__ __forceinline__ void wave_row_stats(const float *x, const int32_t *N,
     D_out = Dsum;
 }
 
+// A-operand of O^T += V^T P^T from a ROW-MAJOR V tile in LDS, with the CDNA4 transposing LDS read: within each
+// group of 16 lanes, lane i receives element i % 4 of the four halves addressed by lanes i/4, 4 + i/4, 8 + i/4 and
+// 12 + i/4.  With lane 4r + c of a group pointing at V[key0 + r][d0 + 4c .. +4], lane i gets V[key0 + 0..3][d0 + i]:
+// four consecutive keys of one dimension, which is what the operand wants, and no transposed copy is ever written.
+typedef __fp16 tr_h4 __attribute__((__vector_size__(4 * sizeof(__fp16))));
+__device__ __forceinline__ h4 lds_read_tr16(const _Float16 *p)
+{
+    typedef __attribute__((address_space(3))) tr_h4 *lds_ptr_t;
+    return __builtin_bit_cast(h4, __builtin_amdgcn_ds_read_tr16_b64_v4f16((lds_ptr_t)(p)));
+}
+
 }  // namespace sq

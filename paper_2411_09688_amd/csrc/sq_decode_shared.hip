@@ -13,9 +13,9 @@
 //     tiles: A = 16 keys, B = the 16 queries of the group, kept in registers per head), so K never touches LDS;
 //   * in the accumulator layout a lane owns ONE sequence (column) and a few keys, so the per-(key, sequence)
 //     ownership bit, the running maximum, the running sum and the output rescaling are per-lane scalars;
-//   * V rows are transposed through a wave-private LDS tile on the way in (keys of the 32-key step permuted so
-//     that the eight keys a lane needs are 16 contiguous bytes) and O^T += V^T P^T runs on MFMA with P^T taken
-//     from the score accumulators in place;
+//   * V rows are loaded whole (16 lanes per 256-byte row, a wave-wide load = 4 rows), stored row-major in a
+//     wave-private LDS tile and read back as V^T tiles with the transposing LDS read; O^T += V^T P^T runs on MFMA
+//     with P^T taken from the score accumulators in place;
 //   * a lane's output accumulators hold its sequence's 128 dimensions spread over the four lane groups: 32
 //     registers of state for all 16 sequences.
 //
@@ -55,7 +55,8 @@ __device__ __forceinline__ RunSplit run_split(int total, int grid)
 
 
 static_assert(KPC == 128 && SG == 16, "the shared-context kernel is written for 128-key chunks and 16 sequences");
-constexpr int SV_STRIDE = 40;    // halves per V^T row in LDS: 32 keys + 8 of padding (80 B)
+constexpr int SV_STRIDE = D + 16; // halves per V row in LDS (288 B: the transposing reads hit 32 distinct banks)
+constexpr int SK_STRIDE = D + 8;  // halves per K row in the same tile (272 B: conflict-free 16-byte reads)
 
 struct WaveLds {                 // private to one wave, except while a segment's results are combined
     int pos[KPC], delta[KPC];    // run-length records of the current item
@@ -63,9 +64,9 @@ struct WaveLds {                 // private to one wave, except while a segment'
     int rows[32];                // K/V row of the wave's key slots (-1 past the end)
     uint32_t kset[32];           // set of sequences per key slot (0 past the end)
     float ml[2 * SG];            // segment end: (m, l) of every sequence
-    _Float16 Vt[D * SV_STRIDE];  // V^T of the current 32-key step; segment end: o[SG][D] as fp32
+    _Float16 Vt[32 * SV_STRIDE]; // K rows, then V rows of the current 32-key step; segment end: o[SG][D] as fp32
 };
-static_assert(sizeof(_Float16) * D * SV_STRIDE >= sizeof(float) * SG * D, "the V^T tile doubles as the output staging");
+static_assert(sizeof(_Float16) * 32 * SV_STRIDE >= sizeof(float) * SG * D, "the V tile doubles as the output staging");
 
 // LDS traffic inside a wave needs no hardware barrier (a wave's LDS operations complete in order), only a point
 // the compiler does not move LDS accesses across.
@@ -74,14 +75,6 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-// Position of key kappa (0..31) of a step inside a V^T row: key (t*16 + g*4 + j) goes to g*8 + t*4 + j, so
-// the B operand's keys of lane group g (two accumulator tiles x 4 keys) are contiguous.
-__device__ __forceinline__ int sv_pos(int kappa)
-{
-    const int t = kappa >> 4, g = (kappa & 15) >> 2, j = kappa & 3;
-    return g * 8 + t * 4 + j;
 }
 
 __global__ __launch_bounds__(256, 3) void decode_attn_shared_kernel(
@@ -226,25 +219,18 @@ __global__ __launch_bounds__(256, 3) void decode_attn_shared_kernel(
         wave_lds_sync();
         const int r_last = S.rows[min(nvalid - j0, 32) - 1];
 
-        // ---- loads: K in A-operand layout (tile t: key t*16 + col, dims s*32 + kg*8 .. +8); V by key ----------------
-        h8 ka[2][4], vr[8];
+        // ---- loads: K in A-operand layout (tile t: key t*16 + col, dims s*32 + kg*8 .. +8); V rows whole: lane group
+        // kg takes keys kg*8 + i, 16 bytes per lane ------------------------------------------------------------------
+        h8 kr[8], vr[8];
         {
-            int rk[2];
+            const int4 rv0 = *reinterpret_cast<const int4 *>(&S.rows[kg * 8]), rv1 = *reinterpret_cast<const int4 *>(&S.rows[kg * 8 + 4]);
+            const int rv[8] = {rv0.x, rv0.y, rv0.z, rv0.w, rv1.x, rv1.y, rv1.z, rv1.w};
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const int r = S.rows[t * 16 + col];
-                rk[t] = r < 0 ? r_last : r;               // slots past the end re-read a valid row
-            }
-            const int rvv = S.rows[lane & 31];
-            const int rv = rvv < 0 ? r_last : rvv;
+            for (int i = 0; i < 8; ++i)                    // slots past the end re-read a valid row
+                kr[i] = __builtin_nontemporal_load(reinterpret_cast<const h8 *>(Kbase + (size_t)(rv[i] < 0 ? r_last : rv[i]) * 256 + col * 16));
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int s = 0; s < 4; ++s)
-                    ka[t][s] = *reinterpret_cast<const h8 *>(Kbase + (size_t)rk[t] * 256 + s * 64 + kg * 16);
-            const char *vp = Vbase + (size_t)rv * 256 + (lane >> 5) * 128;
-#pragma unroll
-            for (int c = 0; c < 8; ++c) vr[c] = *reinterpret_cast<const h8 *>(vp + c * 16);
+            for (int i = 0; i < 8; ++i)
+                vr[i] = __builtin_nontemporal_load(reinterpret_cast<const h8 *>(Vbase + (size_t)(rv[i] < 0 ? r_last : rv[i]) * 256 + col * 16));
         }
         if (item + 1 < item_end) prefetch(item + 1);
         // ownership bits of this lane's (key, sequence) pairs: element e = t*4 + v <-> key t*16 + kg*4 + v
@@ -259,6 +245,17 @@ __global__ __launch_bounds__(256, 3) void decode_attn_shared_kernel(
         }
 
         // ---- S^T = K Q^T ---------------------------------------------------------------------------------------------
+        // K rows -> the wave's LDS tile (row-major) -> A-operand layout (tile t: key t*16 + col, dims s*32 + kg*8 .. +8)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) *reinterpret_cast<h8 *>(S.Vt + (kg * 8 + i) * SK_STRIDE + col * 8) = kr[i];
+        wave_lds_sync();
+        h8 ka[2][4];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                ka[t][s] = *reinterpret_cast<const h8 *>(S.Vt + (t * 16 + col) * SK_STRIDE + s * 32 + kg * 8);
+        wave_lds_sync();                                   // the tile is free for V
         f4 sacc[2];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
@@ -268,14 +265,9 @@ __global__ __launch_bounds__(256, 3) void decode_attn_shared_kernel(
                 sacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][s], bq[s], sacc[t], 0, 0, 0);
         }
 
-        // ---- V -> wave-private LDS, transposed: lane = key (lane % 32), dims (lane / 32) * 64 + c*8 + e ------------
-        {
-            _Float16 *vt = S.Vt + (lane >> 5) * 64 * SV_STRIDE + sv_pos(lane & 31);
+        // ---- V -> wave-private LDS, row-major ----------------------------------------------------------------------
 #pragma unroll
-            for (int c = 0; c < 8; ++c)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) vt[(c * 8 + e) * SV_STRIDE] = vr[c][e];
-        }
+        for (int i = 0; i < 8; ++i) *reinterpret_cast<h8 *>(S.Vt + (kg * 8 + i) * SV_STRIDE + col * 8) = vr[i];
 
         // ---- online softmax of column `col` -----------------------------------------------------------------------
         float sv[8];
@@ -308,10 +300,13 @@ __global__ __launch_bounds__(256, 3) void decode_attn_shared_kernel(
         for (int e = 0; e < 8; ++e) bp[e] = (_Float16)sv[e];
 
         // ---- O^T += V^T P^T -----------------------------------------------------------------------------------------
-        wave_lds_sync();                                   // V^T is written
+        wave_lds_sync();                                   // V is written
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) {
-            const h8 a = *reinterpret_cast<const h8 *>(S.Vt + (dt * 16 + col) * SV_STRIDE + kg * 8);
+            // keys t*16 + kg*4 + (0..3) for t = 0, 1: the order P^T sits in the score accumulators
+            const _Float16 *vp = S.Vt + (kg * 4 + (col >> 2)) * SV_STRIDE + dt * 16 + (col & 3) * 4;
+            const h4 a0 = lds_read_tr16(vp), a1 = lds_read_tr16(vp + 16 * SV_STRIDE);
+            const h8 a = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
             o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bp, o[dt], 0, 0, 0);
         }
     }

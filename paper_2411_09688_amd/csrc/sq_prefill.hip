@@ -64,17 +64,6 @@ __global__ __launch_bounds__(256) void block_info_kernel(const int32_t *__restri
     blk_info[(size_t)h * nblk + blk] = first | (min(span, 30) << 16) | (span >= 31 ? (int)0x80000000 : 0);
 }
 
-// A-operand of O^T += V^T P^T from a ROW-MAJOR V tile in LDS, with the CDNA4 transposing LDS read: within each
-// group of 16 lanes, lane i receives element i % 4 of the four halves addressed by lanes i/4, 4 + i/4, 8 + i/4 and
-// 12 + i/4.  With lane 4r + c of a group pointing at V[key0 + r][d0 + 4c .. +4], lane i gets V[key0 + 0..3][d0 + i]:
-// four consecutive keys of one dimension, which is what the operand wants, and no transposed copy is ever written.
-typedef __fp16 tr_h4 __attribute__((__vector_size__(4 * sizeof(__fp16))));
-__device__ __forceinline__ h4 lds_read_tr16(const _Float16 *p)
-{
-    typedef __attribute__((address_space(3))) tr_h4 *lds_ptr_t;
-    return __builtin_bit_cast(h4, __builtin_amdgcn_ds_read_tr16_b64_v4f16((lds_ptr_t)(p)));
-}
-
 // Kept ranges of every (sequence, head) row -> list of key rows: record (first key, count, keys before) writes
 // key_idx[row, before + j] = first + j, clamped into the tensor.  One wave per record at a time.
 __global__ __launch_bounds__(256) void expand_ranges_kernel(DecodePlan plan, int32_t *__restrict__ key_idx, int L)

@@ -589,7 +589,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     // items are written from two walks over the records instead of reading them back from memory.  Walk 1 (together
     // with the outputs) notes, per chunk of KPC kept keys, the record that holds the chunk's first key (bit 31: the
     // record begins exactly there); walk 2 copies every record into the chunks it touches.
-    const bool replay = SCHEDULE && n_steps > 1 && opt.replay;     // workgroup-uniform
+    const bool replay = SCHEDULE && CAND && n_steps > 1 && opt.replay;     // workgroup-uniform; candidate rows only
     int *s_tab = reinterpret_cast<int *>(smem + (size_t)C * 8);
     const int n_sel = SCHEDULE ? min(base_k, plan.L) : 0;
     const int n_fixed = (n_sel + KPC - 1) / KPC;
