@@ -181,6 +181,7 @@ struct HierWs {
     float *logits1, *logits2;   // logits2 and cand_id are in candidate order: [rows, C2] with the row's candidates first
     int32_t *cand_id;
     int32_t *nr1, *nk1;
+    float2 *cand_stats;       // per candidate work item: (max, sum N exp(x - max)) of its candidates
     sq::DecodePlan cand;      // work items of candidate fine clusters (chunks of KPC clusters)
 };
 
@@ -194,6 +195,7 @@ HierWs carve_hier(Carver &cv, const sq_shape_t *sh)
     w.cand_id = cv.take<int32_t>(rows * sh->C);
     w.nr1 = cv.take<int32_t>(rows);
     w.nk1 = cv.take<int32_t>(rows);
+    w.cand_stats = cv.take<float2>(items);
     w.cand.rec_cap = sh->C;
     w.cand.L = sh->C;
     w.cand.item_cap = (int)items;
@@ -872,12 +874,16 @@ int multilevel_lookup(const char *fn, const sq_shape_t *sh, int n, const Level *
     for (int k = 1; k < n && e == hipSuccess; ++k) {
         const bool last = k == n - 1;
         sq::DecodePlan dst = last ? plan_last : nxt;
-        e = sq::launch_gather_score(q, lv[k].centroids, cur, w.logits2, w.cand_id, dst.total, sh->H, lv[k].C,
-                                    sh->sm_scale, s);
+        // (the records of `cur` were consumed when its work items were written: the array now takes the candidates')
+        e = sq::launch_gather_score(q, lv[k].centroids, cur, lv[k].sizes, lv[k].child_offsets, last ? 0 : 1, w.logits2,
+                                    w.cand_id, cur.rec, w.cand_stats, dst.total, sh->H, lv[k].C, sh->sm_scale, s);
         if (e != hipSuccess) break;
         sq::SelectOpts o{};
         o.cand_id = w.cand_id;
         o.cand_hdr = cur.hdr;
+        o.cand_rec = cur.rec;
+        o.cand_stats = w.cand_stats;
+        o.cand_items = cur.row_items;
         if (last) {
             e = sq::launch_select(w.logits2, nullptr, nullptr, false, lv[k].thresh, lv[k].sizes, lv[k].child_offsets,
                                   lv[k].mask, ranges, n_ranges, n_keys, plan_last, schedule_last, sh->U, o, rows, sh->H, 1,

@@ -89,6 +89,9 @@ struct SelectOpts {
     int B;                           // shared-context decode: number of query rows that share a head's K/V (B * G)
     int G;                           // shared-context decode: query rows per (sequence, head), see shared_row
     int replay;                      // set by launch_select: multi-step rows write their work items from the staged row
+    const int4 *cand_rec;            // level 2, optional: the candidates' records and the statistics of the work items
+    const float2 *cand_stats;        //   that listed them (see launch_gather_score), cand_items[row] = (first item,
+    const int2 *cand_items;          //   items) of the row: the row is then staged from these streams alone
 };
 
 // Batched decode over a shared fixed context: sequences are handled in groups of SG; a "union row" is one
@@ -117,9 +120,13 @@ hipError_t launch_select(const float *logits, const float *row_max, const float 
                          int32_t *ranges, int32_t *n_ranges, int32_t *n_keys, DecodePlan plan, bool schedule, int U,
                          SelectOpts opt, int rows, int H, int Lq, int C, hipStream_t s);
 // Level-2 scoring of the two-level lookup: logits of the candidate fine centroids listed by the work
-// items of `cand` (chunks of candidate clusters), written in candidate order: logits2[row, j], cand_id[row, j].
-hipError_t launch_gather_score(const void *q, const void *centroids2, DecodePlan cand, float *logits2,
-                               int32_t *cand_id, int *zero_counter, int H, int C2, float sm_scale, hipStream_t s);
+// items of `cand` (chunks of candidate clusters), written in candidate order: logits2[row, j], cand_id[row, j],
+// cand_rec[row, j] = (id, N, offsets[id], range length: N, or offsets[id + 1] - offsets[id] with len_from_offsets),
+// and per item cand_stats[item] = (max, sum N exp(x - max)) over the item's candidates with N > 0.
+hipError_t launch_gather_score(const void *q, const void *centroids2, DecodePlan cand, const int32_t *sizes2,
+                               const int32_t *offsets2, int len_from_offsets, float *logits2, int32_t *cand_id,
+                               int4 *cand_rec, float2 *cand_stats, int *zero_counter, int H, int C2, float sm_scale,
+                               hipStream_t s);
 // Rows [BH, G, C] of logits -> ln of the group's averaged Eq. 1 scores, written to all G rows (in place).
 hipError_t launch_group_mean_logits(float *logits, const int32_t *sizes, int BH, int H, int G, int C, hipStream_t s);
 // Caller-style ranges [rows, range_cap, 2] -> records + header per row.

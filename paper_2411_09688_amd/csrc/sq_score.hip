@@ -216,19 +216,29 @@ hipError_t launch_group_mean_logits(float *logits, const int32_t *sizes, int BH,
 // the children of the kept coarse clusters, listed by work items of KPC candidate clusters each (built
 // by the level-1 selection: a balanced number of centroids per workgroup, Appendix D).  A persistent
 // grid walks the items; each wave scores 16-cluster MFMA tiles of its share, gathering the centroid rows
-// by cluster id, and writes logits2[row, cluster id].
+// by cluster id.  Per candidate j of the row (candidate order) it writes the logit, the cluster id and the record
+// (id, N, first key | first child, range length) the selection needs, so that the selection -- one workgroup per
+// row -- reads three coalesced streams instead of gathering by id; per item it writes the statistics of Eq. 3's
+// denominator over the item's candidates, (m, sum N exp(x - m)) over those with N > 0, which the selection
+// merges in item order.
 __global__ __launch_bounds__(256) void gather_score_kernel(const _Float16 *__restrict__ q,
                                                            const _Float16 *__restrict__ cent2, DecodePlan cand,
+                                                           const int32_t *__restrict__ sizes2,
+                                                           const int32_t *__restrict__ offsets2, int len_from_offsets,
                                                            float *__restrict__ logits2,
-                                                           int32_t *__restrict__ cand_id,
+                                                           int32_t *__restrict__ cand_id, int4 *__restrict__ cand_rec,
+                                                           float2 *__restrict__ cand_stats,
                                                            int *__restrict__ zero_counter, int H, int C2,
                                                            float sm_scale)
 {
     __shared__ int s_pos[KPC], s_delta[KPC], s_rows[KPC];
+    __shared__ __align__(16) float s_x[KPC];
+    __shared__ float s_red[4];
     if (zero_counter && blockIdx.x == 0 && threadIdx.x == 0) zero_counter[0] = zero_counter[1] = 0;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 15, kg = lane >> 4;
     constexpr int TILES = KPC / 64;                 // 16-cluster tiles per wave
+    static_assert(KPC == 128, "two waves hold an item's candidates");
     const int total = min(*cand.total, cand.item_cap);
     for (int item = blockIdx.x; item < total; item += gridDim.x) {
         const int2 *it = cand.item + (size_t)item * ITEM_STRIDE;
@@ -255,33 +265,56 @@ __global__ __launch_bounds__(256) void gather_score_kernel(const _Float16 *__res
 #pragma unroll
             for (int s = 0; s < 4; ++s) a[t][s] = cp[s * 4 + kg];
         }
+        // the candidate's record, one candidate per thread of the first two waves (loads run under the products)
+        const int my_r = tid < KPC ? s_rows[tid] : -1;
+        int my_N = 0, my_start = 0, my_next = 0;
+        if (my_r >= 0) {
+            my_N = sizes2[(size_t)h * C2 + my_r];
+            my_start = offsets2[(size_t)h * (C2 + 1) + my_r];
+            if (len_from_offsets) my_next = offsets2[(size_t)h * (C2 + 1) + my_r + 1];
+        }
 #pragma unroll
         for (int t = 0; t < TILES; ++t) {
             f4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int s = 0; s < 4; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[t][s], bq[s], acc, 0, 0, 0);
-            if (col == 0) {
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int slot = wave * (KPC / 4) + t * 16 + kg * 4 + v;
-                    const int r = s_rows[slot];
-                    if (r >= 0 && j0 + slot < C2) {
-                        logits2[bh * (size_t)C2 + j0 + slot] = acc[v] * sm_scale;
-                        cand_id[bh * (size_t)C2 + j0 + slot] = r;
-                    }
-                }
-            }
+            if (col == 0) *reinterpret_cast<f4 *>(&s_x[wave * (KPC / 4) + t * 16 + kg * 4]) = acc * sm_scale;
         }
-        __syncthreads();                            // LDS is reused by the next item
+        __syncthreads();
+        if (wave < 2) {                             // wave-uniform
+            const float xj = s_x[tid];
+            const bool ok = my_r >= 0 && j0 + tid < C2;
+            if (ok) {
+                const size_t j = bh * (size_t)C2 + j0 + tid;
+                logits2[j] = xj;
+                cand_id[j] = my_r;
+                cand_rec[j] = make_int4(my_r, my_N, my_start, len_from_offsets ? my_next - my_start : my_N);
+            }
+            const bool live = ok && my_N > 0;
+            const float mw = wave_max(live ? xj : SQ_NEG_INF);
+            if (lane == 0) s_red[wave] = mw;
+        }
+        __syncthreads();
+        if (wave < 2) {
+            const float m = fmaxf(s_red[0], s_red[1]);
+            const bool live = my_r >= 0 && j0 + tid < C2 && my_N > 0;
+            const float sw = wave_sum(live ? __fmul_rn((float)my_N, expf(s_x[tid] - m)) : 0.0f);
+            if (lane == 0) s_red[2 + wave] = sw;
+        }
+        __syncthreads();                            // (LDS is reused by the next item)
+        if (tid == 0) cand_stats[item] = make_float2(fmaxf(s_red[0], s_red[1]), s_red[2] + s_red[3]);
     }
 }
 
-hipError_t launch_gather_score(const void *q, const void *centroids2, DecodePlan cand, float *logits2,
-                               int32_t *cand_id, int *zero_counter, int H, int C2, float sm_scale, hipStream_t s)
+hipError_t launch_gather_score(const void *q, const void *centroids2, DecodePlan cand, const int32_t *sizes2,
+                               const int32_t *offsets2, int len_from_offsets, float *logits2, int32_t *cand_id,
+                               int4 *cand_rec, float2 *cand_stats, int *zero_counter, int H, int C2, float sm_scale,
+                               hipStream_t s)
 {
     const int grid = cand.item_cap < 2048 ? cand.item_cap : 2048;
     hipLaunchKernelGGL(gather_score_kernel, dim3(grid), dim3(256), 0, s, (const _Float16 *)q,
-                       (const _Float16 *)centroids2, cand, logits2, cand_id, zero_counter, H, C2, sm_scale);
+                       (const _Float16 *)centroids2, cand, sizes2, offsets2, len_from_offsets, logits2, cand_id,
+                       cand_rec, cand_stats, zero_counter, H, C2, sm_scale);
     return hipGetLastError();
 }
 

@@ -328,6 +328,47 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
                 s_N[i] = N[i];
             }
         }
+    } else if (CAND && !STATS_IN && opt.cand_rec) {
+        // Candidates with their records and per-item statistics at hand (see launch_gather_score): the row's maximum
+        // and normaliser are merged from its items' pairs (items in ascending order), every entry is decided as its
+        // logit and record arrive, and the row is staged directly as (first key | -1, range length).
+        for (int w = tid; w < W; w += SEL_THREADS) s_mask[w] = 0u;
+        float xv[16];
+        int4 rv[16];                                        // all loads of the (up to 16) steps in flight together
+        const int4 *crec = opt.cand_rec + row * C;
+#pragma unroll
+        for (int st = 0; st < 16; ++st) {
+            const int i = st * SEL_THREADS + tid;
+            xv[st] = i < n ? x[i] : 0.0f;
+            rv[st] = i < n ? crec[i] : make_int4(0, 0, 0, 0);
+        }
+        const int2 ri = opt.cand_items[row];                // (first item, items): at most chunk_cap_for(C) <= SEL_THREADS
+        const float2 ms = tid < ri.y ? opt.cand_stats[ri.x + tid] : make_float2(SQ_NEG_INF, 0.0f);
+        float mw = wave_max(ms.x);
+        if (lane == 0) s_wred[wave] = mw;
+        __syncthreads();
+        float m = s_wred[0];
+#pragma unroll
+        for (int w = 1; w < SEL_WAVES; ++w) m = fmaxf(m, s_wred[w]);
+        __syncthreads();                                    // every wave has read the maxima: s_wred is reused
+        const float part = ms.y > 0.0f ? __fmul_rn(ms.y, expf(ms.x - m)) : 0.0f;
+        const float pw = wave_sum(part);
+        if (lane == 0) s_wred[wave] = pw;
+        __syncthreads();
+        float Dsum = 0.0f;                                  // every thread adds the wave sums in the same order
+#pragma unroll
+        for (int w = 0; w < SEL_WAVES; ++w) Dsum += s_wred[w];
+        const float thr_c = T * Dsum;
+#pragma unroll
+        for (int st = 0; st < 16; ++st) {
+            const int i = st * SEL_THREADS + tid;
+            const bool k = i < n && rv[st].y > 0 && expf(xv[st] - m) > thr_c;
+            if (i < n) {
+                s_e[i] = __int_as_float(k ? rv[st].z : -1);
+                s_N[i] = k ? rv[st].w : 0;
+            }
+            if (st * SEL_THREADS < n) wave_mask_or(s_mask, rv[st].x, k, lane);   // mask bit by cluster id
+        }
     } else if (CAND) {
         for (int w = tid; w < W; w += SEL_THREADS) s_mask[w] = 0u;
         int idv[16], nv[16];                                // all loads of the (up to 16) steps in flight together
@@ -380,8 +421,11 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
             s_N[i] = N[i];
         }
     }
+    const bool cand_fast = CAND && !STATS_IN && opt.cand_rec != nullptr;   // workgroup-uniform
     float m, thr = 0.0f;
-    if (UNION) {
+    if (cand_fast) {
+        __syncthreads();                                    // the row is staged
+    } else if (UNION) {
         if (tid == 0) s_thr = 0.0f;
     } else if (STATS_IN && opt.mean_parts) {
         if (tid == 0) s_thr = T;                            // keep iff mean score > T
@@ -438,8 +482,8 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     // Rows of more than one step: every global load of the compaction is issued here, for all (up to 16) steps at
     // once, so that no step below waits on memory.  The staged value of entry i becomes the first key of its range
     // (-1 if the cluster is dropped) and s_N[i] the range's length; a thread re-reads only entries it wrote itself.
-    const bool staged_ranges = !UNION && n_steps > 1;
-    if (staged_ranges) {
+    const bool staged_ranges = (!UNION && n_steps > 1) || cand_fast;
+    if (staged_ranges && !cand_fast) {
         int idv[16], sv[16], lv[16];
 #pragma unroll
         for (int st = 0; st < 16; ++st) {
