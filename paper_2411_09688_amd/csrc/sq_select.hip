@@ -294,6 +294,9 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     uint32_t *s_set = reinterpret_cast<uint32_t *>(s_e);   // UNION: set of sequences per cluster instead of e_i
     const int n_seq = UNION ? min(SG, opt.B - (int)(row / H) * SG) : 1;   // (virtual) sequences of this group
     const int n_real = UNION ? (n_seq + opt.G - 1) / opt.G : 1;            // real sequences: owners of user keys
+    // Candidate rows staged from records keep their entries in registers: entry st*SEL_THREADS + tid of this thread is
+    // (first key | -1 if dropped, range length).  Indexed with constants only (the step loops below are unrolled).
+    int kz[CAND ? 16 : 1], kl[CAND ? 16 : 1];
 
     if (UNION) {
         static_assert(SG == SEL_WAVES, "one wave per sequence of the group");
@@ -363,10 +366,8 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
         for (int st = 0; st < 16; ++st) {
             const int i = st * SEL_THREADS + tid;
             const bool k = i < n && rv[st].y > 0 && expf(xv[st] - m) > thr_c;
-            if (i < n) {
-                s_e[i] = __int_as_float(k ? rv[st].z : -1);
-                s_N[i] = k ? rv[st].w : 0;
-            }
+            kz[CAND ? st : 0] = k ? rv[st].z : -1;
+            kl[CAND ? st : 0] = k ? rv[st].w : 0;
             if (st * SEL_THREADS < n) wave_mask_or(s_mask, rv[st].x, k, lane);   // mask bit by cluster id
         }
     } else if (CAND) {
@@ -508,7 +509,11 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     }
     // Entry i of step st: kept?, first key and length of its range.
     auto entry = [&](int st, int i, bool &keep, int &start, int &len) {
-        if (staged_ranges) {
+        if (CAND && cand_fast) {
+            start = kz[CAND ? st : 0];
+            keep = start >= 0;
+            len = kl[CAND ? st : 0];
+        } else if (staged_ranges) {
             start = i < n ? __float_as_int(s_e[i]) : -1;
             keep = start >= 0;
             len = keep ? s_N[i] : 0;
@@ -519,7 +524,18 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
             len = opt.len_from_offsets ? (keep ? next_first - start_first : 0) : Ni;
         }
     };
-    for (int st = 0; st < n_steps; ++st) {
+    // The block-wide steps of the row.  Candidate rows: unrolled, so that `st` is a constant in the body (register
+    // entries) and the steps, which do not depend on each other, overlap.
+    auto for_steps = [&](auto &&body) {
+        if constexpr (CAND) {
+#pragma unroll
+            for (int st = 0; st < 16; ++st)
+                if (st < n_steps) body(st);              // workgroup-uniform
+        } else {
+            for (int st = 0; st < n_steps; ++st) body(st);
+        }
+    };
+    for_steps([&](int st) {
         const int i = st * SEL_THREADS + tid;
         bool keep;
         int start, len;
@@ -537,7 +553,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
             }
         }
         if (CAND && !staged_ranges) wave_mask_or(s_mask, id_first, keep, lane);
-    }
+    });
     __syncthreads();
     if (CAND && keep_mask)
         for (int w = tid; w < W; w += SEL_THREADS) keep_mask[row * W + w] = s_mask[w];
@@ -610,14 +626,14 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     // r and the key prefix from the (step, wave) table plus a ballot and a lane scan.  Can be run more than once:
     // the staged row stays in LDS.
     auto for_each_record = [&](auto &&fn) {
-        for (int st = 0; st < n_steps; ++st) {
+        for_steps([&](int st) {
             const int i = st * SEL_THREADS + tid;
             bool keep;
             int start, len;
             entry(st, i, keep, start, len);
             const bool emit = keep && len > 0;
             const unsigned long long bal_emit = __ballot(emit);
-            if (bal_emit == 0ull) continue;              // wave-uniform
+            if (bal_emit == 0ull) return;                // wave-uniform
             const int rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(bal_emit >> 32),
                                                        __builtin_amdgcn_mbcnt_lo((uint32_t)bal_emit, 0));
             const int kv = emit ? len : 0;
@@ -627,7 +643,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
                 const int kbefore = (n_steps == 1 ? pre_k : s_tkeys[st * SEL_WAVES + wave]) + incl - kv;
                 fn(r, make_int4(start, len, kbefore, UNION ? (int)s_set[i] : 0));
             }
-        }
+        });
     };
     // Rows of more than one step that schedule (opt.replay: the table below fits behind the staged row): the work
     // items are written from two walks over the records instead of reading them back from memory.  Walk 1 (together
