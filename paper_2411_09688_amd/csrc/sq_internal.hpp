@@ -89,6 +89,7 @@ struct SelectOpts {
     int B;                           // shared-context decode: number of query rows that share a head's K/V (B * G)
     int G;                           // shared-context decode: query rows per (sequence, head), see shared_row
     int replay;                      // set by launch_select: multi-step rows write their work items from the staged row
+    int masks_ready;                 // union rows: set by launch_select when the per-sequence masks are already in keep_mask
     const int4 *cand_rec;            // level 2, optional: the candidates' records and the statistics of the work items
     const float2 *cand_stats;        //   that listed them (see launch_gather_score), cand_items[row] = (first item,
     const int2 *cand_items;          //   items) of the row: the row is then staged from these streams alone

@@ -304,8 +304,12 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
         if (wave < n_seq) {
             const size_t bh = shared_row(vs0 + wave, h, H, opt.G);
             // the mask words also go to LDS ([SG][W] words at the start of the staging area: W * 32 <= C + 31)
-            wave_select_mask<false>(logits + bh * C, N, C, thresh[h], 0.0f, 0.0f, keep_mask + bh * W, n_ranges + bh,
-                                    n_keys + bh, lane, s_set + wave * W);
+            if (opt.masks_ready) {                                   // selected by a launch of its own (see launch_select)
+                for (int w = lane; w < W; w += 64) s_set[wave * W + w] = keep_mask[bh * W + w];
+            } else {
+                wave_select_mask<false>(logits + bh * C, N, C, thresh[h], 0.0f, 0.0f, keep_mask + bh * W, n_ranges + bh,
+                                        n_keys + bh, lane, s_set + wave * W);
+            }
         }
         __syncthreads();                                             // the group's masks are in LDS
         uint32_t setv[16];                                           // C <= 16 * SEL_THREADS
@@ -851,6 +855,16 @@ hipError_t launch_select(const float *logits, const float *row_max, const float 
     const int nuc = user_chunks_for(U);
     if (opt.union_rows) {
         if (!schedule || !keep_mask || !logits) return hipErrorInvalidValue;
+        // Groups of many sequences: the per-sequence selections (one wave each) would share one compute unit per
+        // union row and queue for its vector ALUs, so they get a launch of their own, four rows per workgroup
+        // across the chip (the same function, the same bits); the union kernel then reads the mask words.
+        opt.masks_ready = 0;
+        if (opt.B >= 8) {
+            const int seq_rows = opt.B * H;
+            hipLaunchKernelGGL(select_mask_kernel<false>, dim3((seq_rows + 3) / 4), dim3(256), 0, s, logits, row_max, denom,
+                               thresh, sizes, keep_mask, n_ranges, n_keys, seq_rows, H, opt.G, C);
+            opt.masks_ready = 1;
+        }
         hipLaunchKernelGGL((select_kernel<false, true, true>), dim3(rows), dim3(SEL_THREADS), smem, s, logits, row_max,
                            denom, thresh, sizes, offsets, keep_mask, ranges, n_ranges, n_keys, plan, opt, H, Lq, C, U,
                            nuc);
