@@ -314,7 +314,10 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
         __syncthreads();                                             // the group's masks are in LDS
         uint32_t setv[16];                                           // C <= 16 * SEL_THREADS
 #pragma unroll
+        for (int k = 0; k < 16; ++k) setv[k] = 0u;
+#pragma unroll
         for (int k = 0; k < 16; ++k) {
+            if (k * SEL_THREADS >= C) break;                         // (one jump past the steps the row does not have)
             const int i = k * SEL_THREADS + tid;
             uint32_t set = 0u;
             if (i < C) {
@@ -329,6 +332,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
         __syncthreads();                                             // the mask words are consumed: the area is reused
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
+            if (k * SEL_THREADS >= C) break;
             const int i = k * SEL_THREADS + tid;
             if (i < C) {
                 s_set[i] = setv[k];
