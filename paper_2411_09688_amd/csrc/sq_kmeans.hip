@@ -191,7 +191,8 @@ __global__ __launch_bounds__(256) void kmeans_hist_kernel(const int32_t *__restr
     for (int c = threadIdx.x; c < C; c += 256) s_cnt[c] = 0;
     __syncthreads();
     const int k_end = min(L, (p + 1) * PL);
-    for (int k = p * PL + threadIdx.x; k < k_end; k += 256) atomicAdd(&s_cnt[assign[(size_t)h * L + k]], 1);
+    for (int k = p * PL + threadIdx.x; k < k_end; k += 256)      // (an id out of range counts for the nearest valid one)
+        atomicAdd(&s_cnt[min(max(assign[(size_t)h * L + k], 0), C - 1)], 1);
     __syncthreads();
     int32_t *dst = hist + ((size_t)h * P + p) * C;
     for (int c = threadIdx.x; c < C; c += 256) dst[c] = s_cnt[c];
@@ -245,8 +246,7 @@ __global__ __launch_bounds__(1024) void kmeans_scan_kernel(int32_t *__restrict__
 }
 
 // Grouping, step 3: one WAVE per part walks the part's keys in index order, 64 at a time.  The lanes that hold the
-// same centre id are found in registers by electing the first unplaced lane and matching the others against its
-// id; a lane's slot is the cluster's cursor plus the number of matching lanes below it, so members appear in
+// same centre id are found in registers (a ballot per bit of the id); a lane's slot is the cluster's cursor plus the number of matching lanes below it, so members appear in
 // ascending key order inside every cluster (a stable sort).  The cursors live in LDS and are touched by this one
 // wave only, in program order (all lanes of a group read the cursor, then its last lane advances it): no atomics.
 __global__ __launch_bounds__(64) void kmeans_scatter_kernel(const int32_t *__restrict__ assign,
@@ -261,22 +261,21 @@ __global__ __launch_bounds__(64) void kmeans_scatter_kernel(const int32_t *__res
     for (int c = lane; c < C; c += 64) s_cur[c] = op[c] + hp[c];
     __syncthreads();
     const int k_end = min(L, (p + 1) * PL);
+    const int nbits = 32 - __clz(max(C - 1, 1));           // bits of a centre id
     for (int k0 = p * PL; k0 < k_end; k0 += 64) {
         const int k = k0 + lane;
         const bool valid = k < k_end;
-        const int c = valid ? assign[(size_t)h * L + k] : -1;
-        uint64_t todo = __ballot(valid);
-        int rank = 0, cnt = 0;
-        while (todo) {
-            const int leader = __ffsll((long long)todo) - 1;
-            const int cl = __builtin_amdgcn_readlane(c, leader);
-            const uint64_t m = __ballot(c == cl);
-            if (c == cl) {
-                rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-                cnt = __popcll(m);
-            }
-            todo &= ~m;
+        const int c = valid ? min(max(assign[(size_t)h * L + k], 0), C - 1) : -1;   // clamped like the counts
+        // Lanes with the same centre id, found bit by bit: a lane keeps the lanes that agree with it on every bit of
+        // the id (one ballot per bit, no data-dependent loop).
+        uint64_t m = __ballot(valid);
+        for (int b = 0; b < nbits; ++b) {                  // uniform trip count
+            const bool bit = (c >> b) & 1;
+            const uint64_t bal = __ballot(valid && bit);
+            m &= bit ? bal : ~bal;
         }
+        const int rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+        const int cnt = __popcll(m);
         if (valid) {
             const int cur = s_cur[c];
             if (rank == cnt - 1) s_cur[c] = cur + cnt;
