@@ -9,8 +9,9 @@
 // matrix-core tile, so the arithmetic runs on MFMA and the kernel stays bound by the K/V stream:
 //   * a workgroup takes a run of consecutive work items; each of its four waves owns 32 of an item's 128 key
 //     slots and works alone between segment ends (no workgroup barrier inside a union row);
-//   * K rows are loaded from global memory directly in the A-operand layout of S^T = K Q^T (16x16x32 fp16
-//     tiles: A = 16 keys, B = the 16 queries of the group, kept in registers per head), so K never touches LDS;
+//   * scores are S^T = K Q^T on 16x16x32 fp16 tiles (A = 16 keys, B = the 16 queries of the group, kept in
+//     registers per head).  K rows are loaded whole (16 lanes per 256-byte row, non-temporal: a row is needed once)
+//     and reach the A-operand layout through the wave's LDS tile (row-major store, 16-byte reads);
 //   * in the accumulator layout a lane owns ONE sequence (column) and a few keys, so the per-(key, sequence)
 //     ownership bit, the running maximum, the running sum and the output rescaling are per-lane scalars;
 //   * V rows are loaded whole (16 lanes per 256-byte row, a wave-wide load = 4 rows), stored row-major in a
@@ -219,8 +220,7 @@ __global__ __launch_bounds__(256, 3) void decode_attn_shared_kernel(
         wave_lds_sync();
         const int r_last = S.rows[min(nvalid - j0, 32) - 1];
 
-        // ---- loads: K in A-operand layout (tile t: key t*16 + col, dims s*32 + kg*8 .. +8); V rows whole: lane group
-        // kg takes keys kg*8 + i, 16 bytes per lane ------------------------------------------------------------------
+        // ---- loads: K and V rows whole: lane group kg takes keys kg*8 + i, 16 bytes per lane --------------------------
         h8 kr[8], vr[8];
         {
             const int4 rv0 = *reinterpret_cast<const int4 *>(&S.rows[kg * 8]), rv1 = *reinterpret_cast<const int4 *>(&S.rows[kg * 8 + 4]);
