@@ -43,6 +43,20 @@ __device__ __forceinline__ void merge_row(SlotPtr slot_ptr, int n, _Float16 *__r
         lsum = lsum * sc + a0.y * w0 + a1.y * w1 + a2.y * w2 + a3.y * w3;
         M = Mn;
     }
+    for (; c + MERGE_GROUPS < n; c += 2 * MERGE_GROUPS) {       // two partials in flight (rows of 33 .. 128 partials)
+        const float *p0 = slot_ptr(c), *p1 = slot_ptr(c + MERGE_GROUPS);
+        const float2 a0 = *reinterpret_cast<const float2 *>(p0), a1 = *reinterpret_cast<const float2 *>(p1);
+        f4 o0 = *reinterpret_cast<const f4 *>(p0 + 4 + quad * 4), o1 = *reinterpret_cast<const f4 *>(p1 + 4 + quad * 4);
+        if (GUARD) {
+            o0 = a0.x == SQ_NEG_INF ? zero4 : o0;
+            o1 = a1.x == SQ_NEG_INF ? zero4 : o1;
+        }
+        const float Mn = fmaxf(M, fmaxf(a0.x, a1.x));
+        const float sc = wgt(M, Mn), w0 = wgt(a0.x, Mn), w1 = wgt(a1.x, Mn);
+        acc = acc * sc + o0 * w0 + o1 * w1;
+        lsum = lsum * sc + a0.y * w0 + a1.y * w1;
+        M = Mn;
+    }
     for (; c < n; c += MERGE_GROUPS) {
         const float *p = slot_ptr(c);
         const float2 a = *reinterpret_cast<const float2 *>(p);
