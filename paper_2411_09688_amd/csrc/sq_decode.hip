@@ -10,7 +10,6 @@
 // issues all of its K and V loads before any arithmetic, so a workgroup keeps its whole chunk in
 // flight.  Scores are reduced over the 16 lanes of a row with DPP rotations; the softmax runs per
 // wave and the four wave results are combined in LDS.
-#include <stdlib.h>
 
 #include "sq_common.hpp"
 #include "sq_internal.hpp"
@@ -287,9 +286,7 @@ hipError_t launch_decode_attn(const void *q, const void *Kf, const void *Vf, con
 {
     const int G = sh.Lq;                             // query heads per K/V head (1, or the group size)
     const int rows = sh.B * sh.H * G;
-    static const int grid_env = getenv("SQ_ATTN_GRID") ? atoi(getenv("SQ_ATTN_GRID")) : 0;   // tuning knob
-    const int want = grid_env > 0 ? grid_env : ATTN_GRID;
-    const int grid = plan.item_cap < want ? plan.item_cap : want;
+    const int grid = plan.item_cap < ATTN_GRID ? plan.item_cap : ATTN_GRID;
     hipEvent_t ev0, ev1;
     if (profile_pair(&ev0, &ev1))
         hipExtLaunchKernelGGL(decode_attn_kernel, dim3(grid), dim3(256), 0, s, ev0, ev1, 0, (const _Float16 *)q,
