@@ -28,6 +28,8 @@
 // Section 4.2); the kernel walks that list 64 keys at a time, gathering K and V rows by index (the indices of
 // the block after next travel in registers ahead of the rows), with no per-query masks: only the tail of the
 // last block and the causal user keys are masked, so every executed tile is useful work.
+#include <type_traits>
+
 #include "sq_common.hpp"
 #include "sq_internal.hpp"
 
@@ -270,7 +272,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
         // cores work while `make_masks` (inlined, branch-free in the common cases) expands the visibility of this
         // lane's (query, key) pairs: msk = all ones (visible) or zero; element e = kt*4 + v <-> key kt*16 + kg*4 + v
         // of the block, query nq[qt].
-        auto block = [&](auto make_masks) {
+        auto block = [&](auto make_masks, auto masked) {   // masked: std::bool_constant (false: every pair is visible)
             // ---- S^T = K Q^T ---------------------------------------------------------------------------------
             f4 sacc[QT][4];
 #pragma unroll
@@ -288,7 +290,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
                 }
             }
             uint32_t msk[QT][16];
-            make_masks(msk);
+            if constexpr (decltype(masked)::value) make_masks(msk);
 
             // ---- online softmax per query column; P^T packed as the B operand of the next product ------------
             h8 bp[QT][2];
@@ -298,7 +300,10 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
                 float mx = SQ_NEG_INF;
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    sv[e] = select_bits(msk[qt][e], sacc[qt][e >> 2][e & 3], SQ_NEG_INF);
+                    if constexpr (decltype(masked)::value)
+                        sv[e] = select_bits(msk[qt][e], sacc[qt][e >> 2][e & 3], SQ_NEG_INF);
+                    else
+                        sv[e] = sacc[qt][e >> 2][e & 3];
                     mx = fmaxf(mx, sv[e]);
                 }
                 mx = cross16_max(mx);                       // the 4 lane groups hold the other keys of the column
@@ -345,7 +350,10 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
             }
         };
 
-        if (SHARED && !user) {
+        if (SHARED && !user && j0 + PF_BN <= n_fixed && q0 + BM <= Lq) {
+            // One kept set for every query and a full block of kept keys: nothing to hide, no mask arithmetic.
+            block([&](uint32_t (&)[QT][16]) {}, std::false_type{});
+        } else if (SHARED && !user) {
             // One kept set for every query: only slots past the kept keys (last block) are hidden.
             block([&](uint32_t (&msk)[QT][16]) {
 #pragma unroll
@@ -355,7 +363,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
                         const int j = j0 + (e >> 2) * 16 + kg * 4 + (e & 3);
                         msk[qt][e] = (j < n_fixed && nq[qt] < Lq) ? 0xffffffffu : 0u;
                     }
-            });
+            }, std::true_type{});
         } else if (!user && info >= 0) {
             // Fixed context, usual case: bit (cluster - first cluster of the block) of the query's staged window.
             const uint32_t present = (2u << ((info >> 16) & 31)) - 1u;       // local clusters that occur in the block
@@ -382,7 +390,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
 #pragma unroll
                         for (int e = 0; e < 16; ++e)
                             msk[qt][e] = (uint32_t)__builtin_amdgcn_sbfe((int)qb[qt], (uint32_t)bit[e], 1u);
-                });
+                }, std::true_type{});
             }
         } else if (!user) {
             // Fixed context, block spanning more than 31 cluster ids: look every bit up in the mask itself.
@@ -397,7 +405,10 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
                         msk[qt][e] = ok ? 0xffffffffu : 0u;
                     }
                 }
-            });
+            }, std::true_type{});
+        } else if (user && j0 + PF_BN <= U && q0 + BM <= Lq && (!causal_user || j0 + PF_BN - 1 <= q0 + wave * 16 * QT)) {
+            // A full block of user keys that every query of this wave sees (not causal, or wholly in their past).
+            block([&](uint32_t (&)[QT][16]) {}, std::false_type{});
         } else if (!causal_user || j0 <= q0 + wave * 16 * QT + 16 * QT - 1) {   // else: the block lies in every query's future
             block([&](uint32_t (&msk)[QT][16]) {
 #pragma unroll
@@ -408,7 +419,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
                         const bool ok = j < U && nq[qt] < Lq && (!causal_user || j <= nq[qt]);
                         msk[qt][e] = ok ? 0xffffffffu : 0u;
                     }
-            });
+            }, std::true_type{});
         }
 
         // ---- next block: registers -> the other LDS buffer; one barrier per block --------------------------
