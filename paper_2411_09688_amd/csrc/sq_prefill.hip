@@ -67,14 +67,16 @@ __global__ __launch_bounds__(256) void block_info_kernel(const int32_t *__restri
 }
 
 // Kept ranges of every (sequence, head) row -> list of key rows: record (first key, count, keys before) writes
-// key_idx[row, before + j] = first + j, clamped into the tensor.  One wave per record at a time.
+// key_idx[row, before + j] = first + j, clamped into the tensor.  One wave per record at a time, the records of a row
+// dealt over the gridDim.y workgroups of the row.
+constexpr int EXPAND_SLICES = 16;         // workgroups per row
 __global__ __launch_bounds__(256) void expand_ranges_kernel(DecodePlan plan, int32_t *__restrict__ key_idx, int L)
 {
     const size_t row = blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nrec = min(plan.hdr[row].x, plan.rec_cap);
     int32_t *dst = key_idx + row * (size_t)L;
-    for (int r = wave; r < nrec; r += 4) {
+    for (int r = (int)blockIdx.y * 4 + wave; r < nrec; r += 4 * (int)gridDim.y) {
         const int4 rc = plan.rec[row * plan.rec_cap + r];
         for (int j = lane; j < rc.y && rc.z + j < L; j += 64) dst[rc.z + j] = max(0, min(rc.x + j, L - 1));
     }
@@ -497,7 +499,7 @@ hipError_t launch_prefill_attn(const void *q, const void *Kf, const void *Vf, co
 
 hipError_t launch_expand_ranges(DecodePlan plan, int32_t *idx, int rows, int L, hipStream_t s)
 {
-    hipLaunchKernelGGL(expand_ranges_kernel, dim3(rows), dim3(256), 0, s, plan, idx, L);
+    hipLaunchKernelGGL(expand_ranges_kernel, dim3(rows, EXPAND_SLICES), dim3(256), 0, s, plan, idx, L);
     return hipGetLastError();
 }
 
@@ -505,7 +507,7 @@ hipError_t launch_prefill_attn_shared(const void *q, const void *Kf, const void 
                                       DecodePlan plan, int32_t *key_idx, void *out, float *lse, const Shape &sh,
                                       hipStream_t s)
 {
-    hipLaunchKernelGGL(expand_ranges_kernel, dim3(sh.B * sh.H), dim3(256), 0, s, plan, key_idx, sh.L);
+    hipLaunchKernelGGL(expand_ranges_kernel, dim3(sh.B * sh.H, EXPAND_SLICES), dim3(256), 0, s, plan, key_idx, sh.L);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return launch_prefill_kernel<true>(q, Kf, Vf, Ku, Vu, nullptr, key_idx, reinterpret_cast<const int32_t *>(plan.hdr),
