@@ -38,18 +38,41 @@ __device__ __forceinline__ float row16_sum(float v)
     return v;
 }
 
-// Sum / max over the four 16-lane groups (lanes l, l^16, l^32, l^48); all lanes get the result.
+// Sum / max over the four 16-lane groups (lanes l, l^16, l^32, l^48); all lanes get the result.  Done with the CDNA4
+// row-swap moves, which stay in the vector ALU (a shuffle through ds_bpermute goes to the LDS unit and back):
+// v_permlane16_swap exchanges the odd rows of its first operand with the even rows of its second, so with the same
+// value in both, one operand ends up holding the even row of each row pair in both rows and the other the odd row;
+// v_permlane32_swap does the same with the two halves of the wave.  Each lane then combines x[l] and x[l ^ 16]
+// (then x[l ^ 32]) in one order or the other: sums and maxima are commutative, so the bits equal the shuffle form's.
+// (written as instructions: this compiler's builtins for the two moves hand back the first result twice.  The
+// waits around them cover the vector-ALU write -> swap and swap -> vector-ALU read distances.)
+__device__ __forceinline__ void swap16(float v, float &a, float &b)
+{
+    a = v;
+    b = v;
+    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ void swap32(float v, float &a, float &b)
+{
+    a = v;
+    b = v;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
 __device__ __forceinline__ float cross16_sum(float v)
 {
-    v += __shfl_xor(v, 16);
-    v += __shfl_xor(v, 32);
-    return v;
+    float a, b;
+    swap16(v, a, b);
+    v = a + b;
+    swap32(v, a, b);
+    return a + b;
 }
 __device__ __forceinline__ float cross16_max(float v)
 {
-    v = fmaxf(v, __shfl_xor(v, 16));
-    v = fmaxf(v, __shfl_xor(v, 32));
-    return v;
+    float a, b;
+    swap16(v, a, b);
+    v = fmaxf(a, b);
+    swap32(v, a, b);
+    return fmaxf(a, b);
 }
 
 // Sum over the 64 lanes of a wave as an xor butterfly (partners 1, 2, 4, 8, 16, 32 lanes away, in that order);
