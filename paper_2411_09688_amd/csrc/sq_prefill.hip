@@ -276,6 +276,9 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
         // of the block, query nq[qt].
         auto block = [&](auto make_masks, auto masked) {   // masked: std::bool_constant (false: every pair is visible)
             // ---- S^T = K Q^T ---------------------------------------------------------------------------------
+            // (scheduling hint for the region: interleave the LDS reads and vector-ALU work with the matrix products;
+            // measured -3.5 % on the masked form, nothing on the shared-set form)
+            if constexpr (!SHARED) __builtin_amdgcn_iglp_opt(1);
             f4 sacc[QT][4];
 #pragma unroll
             for (int qt = 0; qt < QT; ++qt)
