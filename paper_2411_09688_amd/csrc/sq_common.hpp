@@ -66,6 +66,23 @@ __device__ __forceinline__ float cross16_sum(float v)
     swap32(v, a, b);
     return a + b;
 }
+// The same over integers: bitwise OR (mask words) and sum (counts).
+__device__ __forceinline__ uint32_t cross16_or(uint32_t v)
+{
+    float a, b;
+    swap16(__builtin_bit_cast(float, v), a, b);
+    v = __builtin_bit_cast(uint32_t, a) | __builtin_bit_cast(uint32_t, b);
+    swap32(__builtin_bit_cast(float, v), a, b);
+    return __builtin_bit_cast(uint32_t, a) | __builtin_bit_cast(uint32_t, b);
+}
+__device__ __forceinline__ int cross16_sum_i(int v)
+{
+    float a, b;
+    swap16(__builtin_bit_cast(float, v), a, b);
+    v = __builtin_bit_cast(int, a) + __builtin_bit_cast(int, b);
+    swap32(__builtin_bit_cast(float, v), a, b);
+    return __builtin_bit_cast(int, a) + __builtin_bit_cast(int, b);
+}
 __device__ __forceinline__ float cross16_max(float v)
 {
     float a, b;

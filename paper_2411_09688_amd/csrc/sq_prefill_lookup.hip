@@ -199,8 +199,7 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
                         keys += keep ? nv[u][v] : 0;
                     }
                     if ((t & 1) || t == nt - 1) {            // a mask word is complete
-                        word |= __shfl_xor(word, 16);
-                        word |= __shfl_xor(word, 32);
+                        word = cross16_or(word);
                         if (kg == 0 && valid) keep_mask[row * W + (t >> 1)] = word;
                         word = 0u;
                     }
@@ -221,10 +220,8 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
         __syncthreads();                                     // stage it & 1 may be overwritten; stage (it+1) & 1 is complete
     }
     if (!MEAN) {
-        cnt += __shfl_xor(cnt, 16);
-        cnt += __shfl_xor(cnt, 32);
-        keys += __shfl_xor(keys, 16);
-        keys += __shfl_xor(keys, 32);
+        cnt = cross16_sum_i(cnt);
+        keys = cross16_sum_i(keys);
         if (kg == 0 && valid) {
             n_ranges[row] = cnt;
             n_keys[row] = keys;
