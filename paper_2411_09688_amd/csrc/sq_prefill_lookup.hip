@@ -133,7 +133,7 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
         }
     };
 
-    float m = SQ_NEG_INF, Dsum = 0.0f, thr = 0.0f;
+    float m = SQ_NEG_INF, Dsum = 0.0f, thr = 0.0f, inv_D = 0.0f;
     uint32_t word = 0u;
     int cnt = 0, keys = 0;
     const int part = q0 / LOOKUP_ROWS, n_part = lookup_parts_for(Lq);
@@ -180,6 +180,7 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
                     m = M;
                 }
                 thr = thresh[h] * Dsum;
+                inv_D = valid && Dsum > 0.0f ? 1.0f / Dsum : 0.0f;   // scores of pass 2: e * (1 / D), one division per token
             }
         } else {
             // ---- pass 2: the same logits again, now as scores ---------------------------------------------------------
@@ -207,7 +208,7 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
                     float sums[4];
 #pragma unroll
                     for (int v = 0; v < 4; ++v)             // over the wave's tokens
-                        sums[v] = row16_sum(valid && Dsum > 0.0f ? e[v] / Dsum : 0.0f);
+                        sums[v] = row16_sum(e[v] * inv_D);
                     if (col == 0 && part < n_part) {
                         float *dst = part_sum + ((size_t)bh * n_part + part) * C_all + t * 16 + kg * 4;
 #pragma unroll
