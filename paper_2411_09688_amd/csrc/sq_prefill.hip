@@ -3,10 +3,10 @@
 //
 // Layout of the computation (FlashAttention-2 style: grid over heads x query blocks, loop over key blocks,
 // online softmax), written for CDNA4 matrix cores:
-//   * a workgroup = 4 waves x 16 queries (two workgroups per compute unit); all waves walk the same
-//     64-key blocks, whose K tile and transposed
-//     V tile are staged in LDS once per workgroup (two LDS buffers; the next block's global loads are issued
-//     before the current block's arithmetic and land in registers meanwhile);
+//   * a workgroup = 4 waves x 16 queries, two workgroups per compute unit (shared-set form: 8 waves, one
+//     workgroup); all waves walk the same 64-key blocks, whose K and V tiles are staged row-major in LDS once per
+//     workgroup (two LDS buffers; the next block's global loads are issued before the current block's arithmetic
+//     and land in registers meanwhile);
 //   * scores are computed TRANSPOSED, S^T = K Q^T, with 16x16x32 fp16 MFMA tiles (A = 16 keys, B = 16
 //     queries).  In the accumulator layout a lane then owns ONE query column for the whole kernel (and four
 //     keys per tile), so the running maximum, the running sum and the rescaling of the output are per-lane
@@ -83,7 +83,12 @@ __global__ __launch_bounds__(256) void expand_ranges_kernel(DecodePlan plan, int
 }
 
 constexpr int PF_QT = 1;                  // 16-query tiles per wave
-constexpr int PF_BM = 64 * PF_QT;         // queries per workgroup (4 waves)
+// Waves per workgroup (all walk the same staged key blocks).  Measured at the 32-head, 1024-token shape: the masked
+// form is fastest with 4 (1.10 ms against 1.17 with 8: the two workgroups of a compute unit cover each other's
+// barriers), the shared-set form with 8 (155 us against 171: half the global->LDS staging per product).
+constexpr int pf_waves(bool shared) { return shared ? 8 : 4; }
+constexpr int pf_bm(bool shared) { return 16 * PF_QT * pf_waves(shared); }   // queries per workgroup
+constexpr int PF_BM_MAX = pf_bm(true);
 
 struct PfStage {                          // one LDS buffer of a key block
     _Float16 K[PF_BN * PF_KS_STRIDE];
@@ -91,7 +96,7 @@ struct PfStage {                          // one LDS buffer of a key block
     int cid[PF_BN];                       // cluster of each key (0x7fffffff past the end)
     int sh[PF_BN];                        // bit of the key's cluster in the staged window: cluster - first cluster of
                                           // the block (31, a bit that is never set, for keys past the end)
-    uint32_t qbits[PF_BM];                // per query: mask bits of clusters first .. first+30, bit 31 clear
+    uint32_t qbits[PF_BM_MAX];            // per query: mask bits of clusters first .. first+30, bit 31 clear
 };
 
 // (mask & a) | (~mask & b) on the bit patterns of floats: one v_bfi_b32.
@@ -103,13 +108,16 @@ __device__ __forceinline__ float select_bits(uint32_t mask, float a, float b)
 // SHARED: key_cid is the key-row list [B*H, L] and blk_info the per-row (records, kept keys) headers; keep_mask is
 // not used.
 template <bool SHARED>
-__global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
+__global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void prefill_attn_kernel(
     const _Float16 *__restrict__ q, const _Float16 *__restrict__ Kf, const _Float16 *__restrict__ Vf,
     const _Float16 *__restrict__ Ku, const _Float16 *__restrict__ Vu, const uint32_t *__restrict__ keep_mask,
     const int32_t *__restrict__ key_cid, const int32_t *__restrict__ blk_info, _Float16 *__restrict__ out,
     float *__restrict__ lse, int B, int H, int L, int C, int Lq, int U, int causal_user, float sm_scale)
 {
-    constexpr int QT = PF_QT, BM = PF_BM;
+    constexpr int QT = PF_QT, BM = pf_bm(SHARED);
+    constexpr int PF_THREADS = 64 * pf_waves(SHARED);
+    constexpr int PF_RP = PF_THREADS / 16;    // rows of a key block the workgroup moves per pass (16 lanes per row)
+    constexpr int PF_NP = PF_BN / PF_RP;      // passes per block
     extern __shared__ __align__(16) unsigned char smem[];
     PfStage *stage = reinterpret_cast<PfStage *>(smem);   // [2]
 
@@ -166,20 +174,20 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
     const uint32_t *my_mrow = keep_mask + (row0 + min(my_q, Lq - 1)) * W;
 
     // Registers that carry the next block from global memory to LDS.
-    h8 pk[4], pv[4];
+    h8 pk[PF_NP], pv[PF_NP];
     int pcid = 0, pinfo = 0;
     uint32_t pw_lo = 0u, pw_hi = 0u;
     // Byte offset of this thread's pieces inside a 64-key block (rows of 256 B), the same for K and V: piece i =
-    // key i*16 + tid/16, 16-byte chunk tid%16.
+    // key i*PF_RP + tid/16, 16-byte chunk tid%16.
     const uint32_t k_off = (uint32_t)(tid >> 4) * 256u + (uint32_t)(tid & 15) * 16u;
     // SHARED: rows of this thread's pieces (keys i*16 + tid/16) of a fixed block; the indices of block b+2 are
     // loaded while block b is computed and used when block b+1's rows are fetched.
-    int ik_n[4] = {0, 0, 0, 0}, ik_c[4] = {0, 0, 0, 0};
+    int ik_n[PF_NP] = {}, ik_c[PF_NP] = {};
     auto fetch_idx = [&](int blk) {
         if (!SHARED || blk >= nblk_fixed) return;
         const int j0 = blk * PF_BN, last = n_fixed - 1;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) ik_n[i] = idx_bh[min(j0 + i * 16 + (tid >> 4), last)];
+        for (int i = 0; i < PF_NP; ++i) ik_n[i] = idx_bh[min(j0 + i * PF_RP + (tid >> 4), last)];
     };
     auto fetch = [&](int blk) {           // issue the global loads of block `blk`
         const bool user = blk >= nblk_fixed;
@@ -188,10 +196,10 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
         if (SHARED && !user) {            // gathered rows (slots past the kept keys repeat the last kept row)
             const char *Kb = reinterpret_cast<const char *>(Kfh), *Vb = reinterpret_cast<const char *>(Vfh);
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < PF_NP; ++i)
                 pk[i] = *reinterpret_cast<const h8 *>(Kb + (size_t)ik_c[i] * 256 + (uint32_t)(tid & 15) * 16u);
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < PF_NP; ++i)
                 pv[i] = *reinterpret_cast<const h8 *>(Vb + (size_t)ik_c[i] * 256 + (uint32_t)(tid & 15) * 16u);
             return;
         }
@@ -199,14 +207,14 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
         const char *Vb = reinterpret_cast<const char *>(user ? Vuh : Vfh) + (size_t)j0 * 256;
         if (j0 + PF_BN <= nkeys) {        // full block: uniform base + 32-bit per-thread offsets
 #pragma unroll
-            for (int i = 0; i < 4; ++i) pk[i] = *reinterpret_cast<const h8 *>(Kb + (k_off + (uint32_t)i * 4096u));
+            for (int i = 0; i < PF_NP; ++i) pk[i] = *reinterpret_cast<const h8 *>(Kb + (k_off + (uint32_t)i * (PF_RP * 256u)));
 #pragma unroll
-            for (int i = 0; i < 4; ++i) pv[i] = *reinterpret_cast<const h8 *>(Vb + (k_off + (uint32_t)i * 4096u));
+            for (int i = 0; i < PF_NP; ++i) pv[i] = *reinterpret_cast<const h8 *>(Vb + (k_off + (uint32_t)i * (PF_RP * 256u)));
         } else {                          // last block of a tensor: rows past the end re-read the last row
             const int last = nkeys - 1 - j0;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int key = min(i * 16 + (tid >> 4), last);
+            for (int i = 0; i < PF_NP; ++i) {
+                const int key = min(i * PF_RP + (tid >> 4), last);
                 pk[i] = *reinterpret_cast<const h8 *>(Kb + (uint32_t)key * 256u + (uint32_t)(tid & 15) * 16u);
                 pv[i] = *reinterpret_cast<const h8 *>(Vb + (uint32_t)key * 256u + (uint32_t)(tid & 15) * 16u);
             }
@@ -224,8 +232,8 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
     auto commit = [&](int blk, PfStage &st) {   // registers -> LDS (K rows, V rows, ids, mask bits)
         const bool user = blk >= nblk_fixed;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int key = i * 16 + (tid >> 4), chunk = tid & 15;
+        for (int i = 0; i < PF_NP; ++i) {
+            const int key = i * PF_RP + (tid >> 4), chunk = tid & 15;
             *reinterpret_cast<h8 *>(st.K + key * PF_KS_STRIDE + chunk * 8) = pk[i];
             *reinterpret_cast<h8 *>(st.V + key * PF_V_STRIDE + chunk * 8) = pv[i];
         }
@@ -244,7 +252,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(
 
     auto take_idx = [&]() {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) ik_c[i] = ik_n[i];
+        for (int i = 0; i < PF_NP; ++i) ik_c[i] = ik_n[i];
     };
     int info_cur = 0;
     if (nblk > 0) {                                       // (no kept key and no user key: nothing to stage)
@@ -469,16 +477,17 @@ hipError_t launch_prefill_kernel(const void *q, const void *Kf, const void *Vf, 
         if (e != hipSuccess) return e;
         attr_set = true;
     }
+    constexpr int PF_BM = pf_bm(SHARED), PF_THREADS = 64 * pf_waves(SHARED);
     const int units = ((sh.Lq + PF_BM - 1) / PF_BM) * sh.H * sh.B;
     dim3 grid((units + 7) / 8 * 8);
     hipEvent_t ev0, ev1;
     if (profile_pair(&ev0, &ev1))
-        hipExtLaunchKernelGGL(prefill_attn_kernel<SHARED>, grid, dim3(256), (uint32_t)smem, s, ev0, ev1, 0,
+        hipExtLaunchKernelGGL(prefill_attn_kernel<SHARED>, grid, dim3(PF_THREADS), (uint32_t)smem, s, ev0, ev1, 0,
                               (const _Float16 *)q, (const _Float16 *)Kf, (const _Float16 *)Vf, (const _Float16 *)Ku,
                               (const _Float16 *)Vu, keep_mask, key_cid, blk_info, (_Float16 *)out, lse, sh.B, sh.H, sh.L,
                               sh.C, sh.Lq, sh.U, sh.causal_user, sh.sm_scale);
     else
-        hipLaunchKernelGGL(prefill_attn_kernel<SHARED>, grid, dim3(256), smem, s, (const _Float16 *)q,
+        hipLaunchKernelGGL(prefill_attn_kernel<SHARED>, grid, dim3(PF_THREADS), smem, s, (const _Float16 *)q,
                            (const _Float16 *)Kf, (const _Float16 *)Vf, (const _Float16 *)Ku, (const _Float16 *)Vu,
                            keep_mask, key_cid, blk_info, (_Float16 *)out, lse, sh.B, sh.H, sh.L, sh.C, sh.Lq, sh.U,
                            sh.causal_user, sh.sm_scale);
