@@ -122,7 +122,8 @@ hipError_t launch_select(const float *logits, const float *row_max, const float 
                          SelectOpts opt, int rows, int H, int Lq, int C, hipStream_t s);
 // Level-2 scoring of the two-level lookup: logits of the candidate fine centroids listed by the work
 // items of `cand` (chunks of candidate clusters), written in candidate order: logits2[row, j], cand_id[row, j],
-// cand_rec[row, j] = (id, N, offsets[id], range length: N, or offsets[id + 1] - offsets[id] with len_from_offsets),
+// cand_rec[row, j] = (logit bits, id | bit 31 if N == 0, offsets[id], range length: N, or offsets[id + 1] - offsets[id]
+// with len_from_offsets),
 // and per item cand_stats[item] = (max, sum N exp(x - max)) over the item's candidates with N > 0.
 hipError_t launch_gather_score(const void *q, const void *centroids2, DecodePlan cand, const int32_t *sizes2,
                                const int32_t *offsets2, int len_from_offsets, float *logits2, int32_t *cand_id,

@@ -216,9 +216,9 @@ hipError_t launch_group_mean_logits(float *logits, const int32_t *sizes, int BH,
 // the children of the kept coarse clusters, listed by work items of KPC candidate clusters each (built
 // by the level-1 selection: a balanced number of centroids per workgroup, Appendix D).  A persistent
 // grid walks the items; each wave scores 16-cluster MFMA tiles of its share, gathering the centroid rows
-// by cluster id.  Per candidate j of the row (candidate order) it writes the logit, the cluster id and the record
-// (id, N, first key | first child, range length) the selection needs, so that the selection -- one workgroup per
-// row -- reads three coalesced streams instead of gathering by id; per item it writes the statistics of Eq. 3's
+// by cluster id.  Per candidate j of the row (candidate order) it writes the logit, the cluster id and the 16-byte
+// record (logit, id | no-keys flag, first key | first child, range length) the selection needs, so that the selection
+// -- one workgroup per row -- reads ONE coalesced stream instead of gathering by id; per item it writes the statistics of Eq. 3's
 // denominator over the item's candidates, (m, sum N exp(x - m)) over those with N > 0, which the selection
 // merges in item order.
 __global__ __launch_bounds__(256) void gather_score_kernel(const _Float16 *__restrict__ q,
@@ -288,7 +288,9 @@ __global__ __launch_bounds__(256) void gather_score_kernel(const _Float16 *__res
                 const size_t j = bh * (size_t)C2 + j0 + tid;
                 logits2[j] = xj;
                 cand_id[j] = my_r;
-                cand_rec[j] = make_int4(my_r, my_N, my_start, len_from_offsets ? my_next - my_start : my_N);
+                // (logit, id with bit 31 set for a cluster without keys, first key | first child, range length)
+                cand_rec[j] = make_int4(__float_as_int(xj), my_N > 0 ? my_r : (int)(0x80000000u | (uint32_t)my_r), my_start,
+                                        len_from_offsets ? my_next - my_start : my_N);
             }
             const bool live = ok && my_N > 0;
             const float mw = wave_max(live ? xj : SQ_NEG_INF);

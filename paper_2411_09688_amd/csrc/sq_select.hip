@@ -344,14 +344,12 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
         // and normaliser are merged from its items' pairs (items in ascending order), every entry is decided as its
         // logit and record arrive, and the row is staged directly as (first key | -1, range length).
         for (int w = tid; w < W; w += SEL_THREADS) s_mask[w] = 0u;
-        float xv[16];
-        int4 rv[16];                                        // all loads of the (up to 16) steps in flight together
-        const int4 *crec = opt.cand_rec + row * C;
+        int4 rv[16];                                        // all loads of the (up to 16) steps in flight together:
+        const int4 *crec = opt.cand_rec + row * C;          // (logit, id | bit 31 if no keys, first key, range length)
 #pragma unroll
         for (int st = 0; st < 16; ++st) {
             const int i = st * SEL_THREADS + tid;
-            xv[st] = i < n ? x[i] : 0.0f;
-            rv[st] = i < n ? crec[i] : make_int4(0, 0, 0, 0);
+            rv[st] = i < n ? crec[i] : make_int4(0, (int)0x80000000u, 0, 0);
         }
         const int2 ri = opt.cand_items[row];                // (first item, items): at most chunk_cap_for(C) <= SEL_THREADS
         const float2 ms = tid < ri.y ? opt.cand_stats[ri.x + tid] : make_float2(SQ_NEG_INF, 0.0f);
@@ -373,10 +371,10 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
 #pragma unroll
         for (int st = 0; st < 16; ++st) {
             const int i = st * SEL_THREADS + tid;
-            const bool k = i < n && rv[st].y > 0 && expf(xv[st] - m) > thr_c;
+            const bool k = i < n && rv[st].y >= 0 && expf(__int_as_float(rv[st].x) - m) > thr_c;
             kz[CAND ? st : 0] = k ? rv[st].z : -1;
             kl[CAND ? st : 0] = k ? rv[st].w : 0;
-            if (st * SEL_THREADS < n) wave_mask_or(s_mask, rv[st].x, k, lane);   // mask bit by cluster id
+            if (st * SEL_THREADS < n) wave_mask_or(s_mask, rv[st].y & 0x7fffffff, k, lane);   // mask bit by cluster id
         }
     } else if (CAND) {
         for (int w = tid; w < W; w += SEL_THREADS) s_mask[w] = 0u;
