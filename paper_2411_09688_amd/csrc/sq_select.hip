@@ -297,6 +297,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     // Candidate rows staged from records keep their entries in registers: entry st*SEL_THREADS + tid of this thread is
     // (first key | -1 if dropped, range length).  Indexed with constants only (the step loops below are unrolled).
     int kz[CAND ? 16 : 1], kl[CAND ? 16 : 1];
+    int sr[CAND ? 16 : 1], sk[CAND ? 16 : 1];              // their record index (-1: none) and key prefix, from the first walk
 
     if (UNION) {
         static_assert(SG == SEL_WAVES, "one wave per sequence of the group");
@@ -647,7 +648,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
             if (emit) {
                 const int r = (n_steps == 1 ? pre_r : s_tcnt[st * SEL_WAVES + wave]) + rank;
                 const int kbefore = (n_steps == 1 ? pre_k : s_tkeys[st * SEL_WAVES + wave]) + incl - kv;
-                fn(r, make_int4(start, len, kbefore, UNION ? (int)s_set[i] : 0));
+                fn(r, make_int4(start, len, kbefore, UNION ? (int)s_set[i] : 0), st);
             }
         });
     };
@@ -660,11 +661,19 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     const int n_sel = SCHEDULE ? min(base_k, plan.L) : 0;
     const int n_fixed = (n_sel + KPC - 1) / KPC;
     constexpr uint32_t EXACT = 0x80000000u;
-    for_each_record([&](int r, const int4 rc) {
+    if (CAND) {
+#pragma unroll
+        for (int st = 0; st < (CAND ? 16 : 1); ++st) sr[st] = -1;
+    }
+    for_each_record([&](int r, const int4 rc, int st) {
         if (ranges) *reinterpret_cast<int2 *>(ranges + (row * C + r) * 2) = make_int2(rc.x, rc.y);
         my_rec = rc;
         my_r = r;
         have_rec = true;
+        if (CAND) {                                          // (st is a constant here: the step loop is unrolled)
+            sr[CAND ? st : 0] = r;
+            sk[CAND ? st : 0] = rc.z;
+        }
         if (plan.rec && !replay) plan.rec[row * plan.rec_cap + r] = rc;
         if (replay) {
             const int c_lo = (rc.z + KPC - 1) / KPC, c_hi = min((rc.z + rc.y - 1) / KPC, n_fixed - 1);
@@ -689,7 +698,18 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
             it[0] = make_int2((int)row, min(KPC, U - cu * KPC));
             it[1] = make_int2(-1 - seq, cu * KPC);
         }
-        for_each_record([&](int r, const int4 rc) {
+        // Second walk.  Rows staged from records kept every entry's record index and key prefix in registers.
+        auto for_each_again = [&](auto &&fn) {
+            if (CAND && cand_fast) {
+                for_steps([&](int st) {
+                    if (sr[CAND ? st : 0] >= 0)
+                        fn(sr[CAND ? st : 0], make_int4(kz[CAND ? st : 0], kl[CAND ? st : 0], sk[CAND ? st : 0], 0), st);
+                });
+            } else {
+                for_each_record(fn);
+            }
+        };
+        for_each_again([&](int r, const int4 rc, int) {
             const int c_lo = rc.z / KPC, c_hi = min((rc.z + rc.y - 1) / KPC, n_fixed - 1);
             for (int c = c_lo; c <= c_hi; ++c) {
                 int2 *it = plan.item + (size_t)(base + n_uc + c) * ITEM_STRIDE;
