@@ -139,7 +139,8 @@ __global__ __launch_bounds__(256) void mean_score_kernel(const float *__restrict
     const size_t row0 = (size_t)bh * Lq + t0;
     if ((int)threadIdx.x < nt) {
         s_m[threadIdx.x] = row_max[row0 + threadIdx.x];
-        s_D[threadIdx.x] = denom[row0 + threadIdx.x];
+        const float Dt = denom[row0 + threadIdx.x];
+        s_D[threadIdx.x] = Dt > 0.0f ? 1.0f / Dt : 0.0f;     // scores are e * (1 / D): one division per token
     }
     __syncthreads();
     for (int i = threadIdx.x; i < C; i += 256) {
@@ -151,9 +152,9 @@ __global__ __launch_bounds__(256) void mean_score_kernel(const float *__restrict
 #pragma unroll
             for (int u = 0; u < 8; ++u) xv[u] = x[(size_t)(t + u) * C];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) acc += expf(xv[u] - s_m[t + u]) / s_D[t + u];
+            for (int u = 0; u < 8; ++u) acc += expf(xv[u] - s_m[t + u]) * s_D[t + u];
         }
-        for (; t < nt; ++t) acc += expf(x[(size_t)t * C] - s_m[t]) / s_D[t];
+        for (; t < nt; ++t) acc += expf(x[(size_t)t * C] - s_m[t]) * s_D[t];
         part_sum[((size_t)bh * n_part + part) * C + i] = acc;
     }
 }
@@ -175,31 +176,55 @@ __global__ __launch_bounds__(1024) void group_mean_logits_kernel(float *__restri
     // (G divides 16), each covering every (16 / G)-th block of 64 clusters.
     const int g = wave % G, j = wave / G, nw = 16 / G;
     const float *x = logits + (row0 + g) * C;
+    // This wave's entries i = j*64 + lane + k*64*nw stay in registers between the two passes when there are at most
+    // GM_REG of them per lane (rows of up to 1024 * 16 / G clusters).
+    constexpr int GM_REG = 16;
+    const bool in_regs = C <= 64 * nw * GM_REG;              // workgroup-uniform
+    float xr[GM_REG];
+    int nr[GM_REG];
     float m = SQ_NEG_INF;
-    for (int i = j * 64 + lane; i < C; i += 64 * nw)
-        if (N[i] > 0) m = fmaxf(m, x[i]);
+    if (in_regs) {
+#pragma unroll
+        for (int k = 0; k < GM_REG; ++k) {
+            const int i = j * 64 + lane + k * 64 * nw;
+            nr[k] = i < C ? N[i] : 0;
+            xr[k] = i < C ? x[i] : 0.0f;
+        }
+#pragma unroll
+        for (int k = 0; k < GM_REG; ++k)
+            if (nr[k] > 0) m = fmaxf(m, xr[k]);
+    } else {
+        for (int i = j * 64 + lane; i < C; i += 64 * nw)
+            if (N[i] > 0) m = fmaxf(m, x[i]);
+    }
     m = wave_max(m);
     if (lane == 0) s_red[g][j] = m;
     __syncthreads();
     for (int k = 0; k < nw; ++k) m = fmaxf(m, s_red[g][k]);
     __syncthreads();                                          // s_red is reused
     float d = 0.0f;
-    for (int i = j * 64 + lane; i < C; i += 64 * nw)
-        if (N[i] > 0) d += (float)N[i] * expf(x[i] - m);
+    if (in_regs) {
+#pragma unroll
+        for (int k = 0; k < GM_REG; ++k)                     // (k ascending: the same order as the loop below)
+            if (nr[k] > 0) d += (float)nr[k] * expf(xr[k] - m);
+    } else {
+        for (int i = j * 64 + lane; i < C; i += 64 * nw)
+            if (N[i] > 0) d += (float)N[i] * expf(x[i] - m);
+    }
     d = wave_sum(d);
     if (lane == 0) s_red[g][j] = d;
     __syncthreads();
     if (tid < G) {
         float Dsum = 0.0f;
         for (int k = 0; k < nw; ++k) Dsum += s_red[tid][k];
-        s_D[tid] = Dsum;
+        s_D[tid] = Dsum > 0.0f ? 1.0f / Dsum : 0.0f;         // the scores below are e * (1 / D): one division per row
     }
     if (j == 0 && lane == 0) s_m[g] = m;
     __syncthreads();
     for (int i = tid; i < C; i += 1024) {
         float sum = 0.0f;
         if (N[i] > 0)
-            for (int gg = 0; gg < G; ++gg) sum += expf(logits[(row0 + gg) * C + i] - s_m[gg]) / s_D[gg];
+            for (int gg = 0; gg < G; ++gg) sum += expf(logits[(row0 + gg) * C + i] - s_m[gg]) * s_D[gg];
         const float mean = sum / (float)G;
         const float xl = mean > 0.0f ? logf(mean) : SQ_NEG_INF;
         for (int gg = 0; gg < G; ++gg) logits[(row0 + gg) * C + i] = xl;
