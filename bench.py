@@ -402,7 +402,8 @@ def bench_gqa(args, torch, sq, wl, dev):
     # per-row kernels read a K/V head's selected keys and user keys once per query head.
     shared = mean or w.B * G >= 8
     kernel = "decode_attn_shared_kernel" if shared else "decode_attn_kernel"
-    kernel_bytes = (sel + dense if shared else sel_req + dense * G) + w.B * Hq * w.d * 2
+    # (per-row kernels: the user keys ride on the selection launch, the partial kernel reads the selected keys only)
+    kernel_bytes = (sel + dense if shared else sel_req) + w.B * Hq * w.d * 2
     res = base_result(args, "grouped-query decode attn µs/token + achieved HBM GB/s, 32K fixed ctx, keep 1/8, "
                       "32 query heads over 8 K/V heads, d=128", round(tot / (ms * 1e-3) / 1e9, 2), "GB/s", ms, eager_ms,
                       graph_ms, w.B)
@@ -599,7 +600,10 @@ def main():
         uniq_keys = (bits * w.sizes[None]).sum(axis=(1, 2))                            # [NQ]
         sel = float(np.mean([uniq_keys[qi] for qi in used])) * w.d * 2 * 2
         tot = tot - sel_requested + sel
-    kernel_bytes = sel + dense + w.B * w.H * w.d * 2           # K/V rows read by the partial kernel + q
+    # K/V rows read by the partial kernel + q.  In the fused per-row step (fewer than 8 sequences) the user keys are
+    # attended to by extra workgroups of the selection launch, so the partial kernel reads the selected keys only.
+    rider = not args.separate and w.B < 8
+    kernel_bytes = sel + (0 if rider else dense) + w.B * w.H * w.d * 2
     keep = float(np.mean([nk[qi].mean() for qi in used]) / w.L)
     tokens = w.B
 

@@ -114,6 +114,28 @@ DecodeWs carve_decode(Carver &cv, const sq_shape_t *sh, int G = 1)
     return w;
 }
 
+// The user-key rider of a decode step's selection launch (sq_user_attn.hpp): rows = B * H * G query rows, q [rows, d],
+// user keys [B * H, U, d].  Its partial results take the top rows * nuq slots of the partial buffer, which the
+// work list cannot reach once it holds no user chunks (item_cap counts them).  q == nullptr without user keys.
+sq::UserAttn make_user_rider(const sq_shape_t *sh, int G, const void *q, const void *K_user, const void *V_user,
+                             const DecodeWs &dec)
+{
+    sq::UserAttn ua{};
+    if (sh->U <= 0) return ua;
+    const int rows = sh->B * sh->H * G, nuc = sq::user_chunks_for(sh->U);
+    ua.q = static_cast<const _Float16 *>(q);
+    ua.Ku = static_cast<const _Float16 *>(K_user);
+    ua.Vu = static_cast<const _Float16 *>(V_user);
+    ua.partials = dec.partials;
+    ua.rows = rows;
+    ua.U = sh->U;
+    ua.G = G;
+    ua.nuq = nuc;
+    ua.slot_base = dec.plan.item_cap - rows * ua.nuq;
+    ua.sm_scale = sh->sm_scale;
+    return ua;
+}
+
 // Workspace of the whole decode step: logits, counts, plan, partials.
 struct StepWs {
     float *logits;
@@ -580,11 +602,13 @@ int sq_gqa_decode_step(const sq_shape_t *sh, int32_t G, const void *q, const voi
     int32_t *nk = n_keys ? n_keys : w.n_keys;
     const int rows = sh->B * sh->H * G;
     SQ_HIP(sq::launch_score(q, centroids, w.logits, w.dec.plan.total, sh->B, sh->H, G, sh->C, sh->sm_scale, s));
+    const sq::UserAttn ua = make_user_rider(sh, G, q, K_user, V_user, w.dec);
     SQ_HIP(sq::launch_select(w.logits, nullptr, nullptr, false, thresh, sizes, offsets, keep_mask, nullptr, w.n_ranges,
-                             nk, w.dec.plan, true, sh->U, sq::SelectOpts{}, rows, sh->H, G, sh->C, s));
+                             nk, w.dec.plan, true, ua.q ? 0 : sh->U, sq::SelectOpts{}, rows, sh->H, G, sh->C, s, &ua));
     sq::Shape shp = to_shape(sh);
     shp.Lq = G;
-    SQ_HIP(sq::launch_decode_attn(q, K_fixed, V_fixed, K_user, V_user, w.dec.plan, w.dec.partials, out, lse, shp, s));
+    SQ_HIP(sq::launch_decode_attn(q, K_fixed, V_fixed, K_user, V_user, w.dec.plan, w.dec.partials, out, lse, shp, s,
+                                  ua.q ? ua.slot_base : -1, ua.nuq));
     g_err[0] = 0;
     return SQ_OK;
 }
@@ -665,10 +689,11 @@ int sq_decode_step(const sq_shape_t *sh, const void *q, const void *centroids, c
     StepWs w = carve_step(cv, sh);
     int32_t *nk = n_keys ? n_keys : w.n_keys;
     SQ_HIP(sq::launch_score(q, centroids, w.logits, w.dec.plan.total, sh->B, sh->H, 1, sh->C, sh->sm_scale, s));
+    const sq::UserAttn ua = make_user_rider(sh, 1, q, K_user, V_user, w.dec);
     SQ_HIP(sq::launch_select(w.logits, nullptr, nullptr, false, thresh, sizes, offsets, keep_mask, nullptr, w.n_ranges,
-                             nk, w.dec.plan, true, sh->U, sq::SelectOpts{}, rows, sh->H, 1, sh->C, s));
+                             nk, w.dec.plan, true, ua.q ? 0 : sh->U, sq::SelectOpts{}, rows, sh->H, 1, sh->C, s, &ua));
     SQ_HIP(sq::launch_decode_attn(q, K_fixed, V_fixed, K_user, V_user, w.dec.plan, w.dec.partials, out, lse,
-                                  to_shape(sh), s));
+                                  to_shape(sh), s, ua.q ? ua.slot_base : -1, ua.nuq));
     g_err[0] = 0;
     return SQ_OK;
 }

@@ -256,7 +256,8 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
 // kernel would write back a whole L2 per workgroup and costs far more than this launch.
 __global__ __launch_bounds__(MERGE_THREADS) void decode_merge_kernel(const float *__restrict__ partials,
                                                                      DecodePlan plan, _Float16 *__restrict__ out,
-                                                                     float *__restrict__ lse, int attn_grid)
+                                                                     float *__restrict__ lse, int attn_grid,
+                                                                     int user_slot_base, int nuq)
 {
     __shared__ float s_red[MERGE_GROUPS * 130];
     const size_t bh = blockIdx.x;
@@ -269,9 +270,12 @@ __global__ __launch_bounds__(MERGE_THREADS) void decode_merge_kernel(const float
     const int e1 = min(last, ws.R);
     const int n_run = (it.y > 0 && first < ws.R) ? 1 + (e1 - 1) / kq - fk : 0;
     const int t0 = max(first, ws.R);
-    const int n = n_run + max(0, last - t0);
+    const int n_sel = n_run + max(0, last - t0);
+    // After them, the row's user-key partials when the selection launch computed those (user_slot_base >= 0).
+    const int n = n_sel + (user_slot_base >= 0 ? nuq : 0);
     auto slot_ptr = [&](int c) {
-        const int idx = c >= n_run ? t0 + (c - n_run) : (c == 0 ? first : (fk + c) * kq);
+        const int idx = c >= n_sel ? user_slot_base + (int)bh * nuq + (c - n_sel)
+                                   : (c >= n_run ? t0 + (c - n_run) : (c == 0 ? first : (fk + c) * kq));
         return partials + (size_t)idx * PART_STRIDE;
     };
     merge_row<false>(slot_ptr, n, out + bh * D, lse ? lse + bh : nullptr, s_red, threadIdx.x);
@@ -282,7 +286,7 @@ constexpr int ATTN_GRID = 256 * 4;
 
 hipError_t launch_decode_attn(const void *q, const void *Kf, const void *Vf, const void *Ku, const void *Vu,
                               DecodePlan plan, float *partials, void *out, float *lse, const Shape &sh,
-                              hipStream_t s)
+                              hipStream_t s, int user_slot_base, int nuq)
 {
     const int G = sh.Lq;                             // query heads per K/V head (1, or the group size)
     const int rows = sh.B * sh.H * G;
@@ -299,7 +303,7 @@ hipError_t launch_decode_attn(const void *q, const void *Kf, const void *Vf, con
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(decode_merge_kernel, dim3(rows), dim3(MERGE_THREADS), 0, s, partials, plan, (_Float16 *)out, lse,
-                       grid);
+                       grid, user_slot_base, nuq);
     return hipGetLastError();
 }
 

@@ -95,6 +95,16 @@ struct SelectOpts {
     const int2 *cand_items;          //   items) of the row: the row is then staged from these streams alone
 };
 
+// Dense attention over the rows' user keys as a rider on the selection launch (see sq_user_attn.hpp): q [rows, d],
+// user keys [rows / G, U, d]; row r leaves nuq = ceil(U / KPC) partial results, one per chunk of user keys, at slots
+// slot_base + r * nuq + (0 .. nuq - 1) of `partials`.  q == nullptr: none.
+struct UserAttn {
+    const _Float16 *q, *Ku, *Vu;
+    float *partials;
+    int rows, U, G, slot_base, nuq;
+    float sm_scale;
+};
+
 // Batched decode over a shared fixed context: sequences are handled in groups of SG; a "union row" is one
 // (group, head) pair and its work items cover the clusters kept by ANY sequence of the group, each key
 // carrying the set of sequences that kept it, so a key leaves HBM once per group instead of once per sequence.
@@ -119,7 +129,8 @@ constexpr int SHARED_ATTN_GRID = 256 * 3;
 hipError_t launch_select(const float *logits, const float *row_max, const float *denom, bool stats_in,
                          const float *thresh, const int32_t *sizes, const int32_t *offsets, uint32_t *keep_mask,
                          int32_t *ranges, int32_t *n_ranges, int32_t *n_keys, DecodePlan plan, bool schedule, int U,
-                         SelectOpts opt, int rows, int H, int Lq, int C, hipStream_t s);
+                         SelectOpts opt, int rows, int H, int Lq, int C, hipStream_t s,
+                         const UserAttn *user = nullptr);   // rider: only with schedule, computed statistics, plain rows
 // Level-2 scoring of the two-level lookup: logits of the candidate fine centroids listed by the work
 // items of `cand` (chunks of candidate clusters), written in candidate order: logits2[row, j], cand_id[row, j],
 // cand_rec[row, j] = (logit bits, id | bit 31 if N == 0, offsets[id], range length: N, or offsets[id + 1] - offsets[id]
@@ -136,9 +147,11 @@ hipError_t launch_ranges_to_rec(const int32_t *ranges, const int32_t *n_ranges, 
                                 int range_cap, hipStream_t s);
 // Records + headers of all rows -> work items.
 hipError_t launch_schedule(DecodePlan plan, int rows, int U, hipStream_t s);
+// user_slot_base >= 0: the rows' user keys are already in `partials` (nuq results per row from that slot on, see
+// UserAttn) and the plan holds no user chunks.
 hipError_t launch_decode_attn(const void *q, const void *Kf, const void *Vf, const void *Ku, const void *Vu,
                               DecodePlan plan, float *partials, void *out, float *lse, const Shape &sh,
-                              hipStream_t s);
+                              hipStream_t s, int user_slot_base = -1, int nuq = 0);
 
 // Shared-context decode: per-sequence selection (keep_masks, n_ranges, n_keys: [B*H] rows) and the work items of
 // every union row in one launch (needs the two counters at plan.total zeroed), and the partial + merge kernels.  partials: (SHARED_ATTN_GRID + union

@@ -16,6 +16,7 @@
 // that keep more keys get more workgroups), each carrying its own copy of the records it touches.
 #include "sq_common.hpp"
 #include "sq_internal.hpp"
+#include "sq_user_attn.hpp"
 
 namespace sq {
 
@@ -269,9 +270,18 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     const float *__restrict__ logits, const float *__restrict__ row_max, const float *__restrict__ denom,
     const float *__restrict__ thresh, const int32_t *__restrict__ sizes, const int32_t *__restrict__ offsets,
     uint32_t *__restrict__ keep_mask, int32_t *__restrict__ ranges, int32_t *__restrict__ n_ranges,
-    int32_t *__restrict__ n_keys, DecodePlan plan, SelectOpts opt, int H, int Lq, int C, int U, int n_user_chunks)
+    int32_t *__restrict__ n_keys, DecodePlan plan, SelectOpts opt, int H, int Lq, int C, int U, int n_user_chunks,
+    UserAttn ua)
 {
     extern __shared__ __align__(16) unsigned char smem[];
+    // Rider (plain scheduling rows only): the workgroups past the first ua.rows compute the rows' attention over their
+    // user keys, one chunk each, which does not depend on the selection, while the first ua.rows select.
+    if (SCHEDULE && !STATS_IN && !UNION && !CAND) {
+        if (ua.q && (int)blockIdx.x >= ua.rows) {            // workgroup-uniform
+            user_chunk_partial(ua, (int)blockIdx.x - ua.rows, reinterpret_cast<float *>(smem));
+            return;
+        }
+    }
     __shared__ float s_wred[SEL_WAVES];
     __shared__ int s_base;
     __shared__ float s_thr;
@@ -834,8 +844,9 @@ __global__ __launch_bounds__(256) void schedule_kernel(DecodePlan plan, int rows
 hipError_t launch_select(const float *logits, const float *row_max, const float *denom, bool stats_in,
                          const float *thresh, const int32_t *sizes, const int32_t *offsets, uint32_t *keep_mask,
                          int32_t *ranges, int32_t *n_ranges, int32_t *n_keys, DecodePlan plan, bool schedule, int U,
-                         SelectOpts opt, int rows, int H, int Lq, int C, hipStream_t s)
+                         SelectOpts opt, int rows, int H, int Lq, int C, hipStream_t s, const UserAttn *user)
 {
+    if (user && user->q && (!schedule || stats_in || opt.union_rows || opt.cand_id)) return hipErrorInvalidValue;
     if (!ranges && !plan.rec && !schedule && !opt.cand_id && !opt.len_from_offsets && !opt.mean_parts && keep_mask) {
         // mask and counts only (prefill): one wave per row
         if (stats_in)
@@ -889,7 +900,7 @@ hipError_t launch_select(const float *logits, const float *row_max, const float 
         }
         hipLaunchKernelGGL((select_kernel<false, true, true>), dim3(rows), dim3(SEL_THREADS), smem, s, logits, row_max,
                            denom, thresh, sizes, offsets, keep_mask, ranges, n_ranges, n_keys, plan, opt, H, Lq, C, U,
-                           nuc);
+                           nuc, UserAttn{});
         return hipGetLastError();
     }
     if (opt.cand_id) {
@@ -897,24 +908,30 @@ hipError_t launch_select(const float *logits, const float *row_max, const float 
         if (stats_in)                                       // averaged scores over the candidates (prefill rule)
             hipLaunchKernelGGL((select_kernel<true, false, false, true>), dim3(rows), dim3(SEL_THREADS), smem, s, logits,
                                row_max, denom, thresh, sizes, offsets, keep_mask, ranges, n_ranges, n_keys, plan, opt, H,
-                               Lq, C, U, nuc);
+                               Lq, C, U, nuc, UserAttn{});
         else if (schedule)
             hipLaunchKernelGGL((select_kernel<false, true, false, true>), dim3(rows), dim3(SEL_THREADS), smem, s, logits,
                                row_max, denom, thresh, sizes, offsets, keep_mask, ranges, n_ranges, n_keys, plan, opt, H,
-                               Lq, C, U, nuc);
+                               Lq, C, U, nuc, UserAttn{});
         else
             hipLaunchKernelGGL((select_kernel<false, false, false, true>), dim3(rows), dim3(SEL_THREADS), smem, s, logits,
                                row_max, denom, thresh, sizes, offsets, keep_mask, ranges, n_ranges, n_keys, plan, opt, H,
-                               Lq, C, U, nuc);
+                               Lq, C, U, nuc, UserAttn{});
         return hipGetLastError();
     }
-#define SQ_LAUNCH_SELECT(SI, SCH)                                                                               \
-    hipLaunchKernelGGL((select_kernel<SI, SCH>), dim3(rows), dim3(SEL_THREADS), smem, s, logits, row_max, denom, \
-                       thresh, sizes, offsets, keep_mask, ranges, n_ranges, n_keys, plan, opt, H, Lq, C, U, nuc)
-    if (stats_in && schedule) SQ_LAUNCH_SELECT(true, true);
-    else if (stats_in) SQ_LAUNCH_SELECT(true, false);
-    else if (schedule) SQ_LAUNCH_SELECT(false, true);
-    else SQ_LAUNCH_SELECT(false, false);
+#define SQ_LAUNCH_SELECT(SI, SCH, GRID, UA)                                                                     \
+    hipLaunchKernelGGL((select_kernel<SI, SCH>), dim3(GRID), dim3(SEL_THREADS), smem, s, logits, row_max, denom, \
+                       thresh, sizes, offsets, keep_mask, ranges, n_ranges, n_keys, plan, opt, H, Lq, C, U, nuc, UA)
+    if (stats_in && schedule) SQ_LAUNCH_SELECT(true, true, rows, UserAttn{});
+    else if (stats_in) SQ_LAUNCH_SELECT(true, false, rows, UserAttn{});
+    else if (schedule && user && user->q) {
+        // The rows' user-key attention rides along: one more workgroup per (row, user chunk), and no user chunks in the work list
+        // (the caller passes U = 0 for it).  Their partial results are staged in the dynamic LDS area.
+        if (U != 0 || user->nuq != user_chunks_for(user->U) || user->rows != rows) return hipErrorInvalidValue;
+        if (smem < (size_t)16 * PART_STRIDE * sizeof(float)) smem = (size_t)16 * PART_STRIDE * sizeof(float);
+        SQ_LAUNCH_SELECT(false, true, rows + rows * user->nuq, *user);
+    } else if (schedule) SQ_LAUNCH_SELECT(false, true, rows, UserAttn{});
+    else SQ_LAUNCH_SELECT(false, false, rows, UserAttn{});
 #undef SQ_LAUNCH_SELECT
     return hipGetLastError();
 }
