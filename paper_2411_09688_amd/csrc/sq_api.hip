@@ -874,16 +874,20 @@ struct Level {
 // work items into plan_last.
 int multilevel_lookup(const char *fn, const sq_shape_t *sh, int n, const Level *lv, const void *q, int32_t *ranges,
                       int32_t *n_ranges, int32_t *n_keys, HierWs &w, sq::DecodePlan cand_b, sq::DecodePlan plan_last,
-                      bool schedule_last, hipStream_t s)
+                      bool schedule_last, hipStream_t s, const sq::UserAttn *user = nullptr)
 {
+    // `user` (decode steps): the rows' user-key attention rides on the level-0 selection launch (see
+    // make_user_rider), and the attention work list of the last level then holds no user chunks.
+    const bool rider = user && user->q;
+    const int U_last = rider ? 0 : sh->U;
     const int rows = sh->B * sh->H;
     hipError_t e;
     if (n == 1) {
         e = sq::launch_score(q, lv[0].centroids, w.logits1, plan_last.total, sh->B, sh->H, 1, lv[0].C, sh->sm_scale, s);
         if (e == hipSuccess)
             e = sq::launch_select(w.logits1, nullptr, nullptr, false, lv[0].thresh, lv[0].sizes, lv[0].child_offsets,
-                                  lv[0].mask, ranges, n_ranges, n_keys, plan_last, schedule_last, sh->U, sq::SelectOpts{},
-                                  rows, sh->H, 1, lv[0].C, s);
+                                  lv[0].mask, ranges, n_ranges, n_keys, plan_last, schedule_last, U_last, sq::SelectOpts{},
+                                  rows, sh->H, 1, lv[0].C, s, user);
         if (e != hipSuccess) return fail(SQ_ERR_HIP, "%s: launch failed -> %s", fn, hipGetErrorString(e));
         return SQ_OK;
     }
@@ -894,7 +898,7 @@ int multilevel_lookup(const char *fn, const sq_shape_t *sh, int n, const Level *
         o.len_from_offsets = 1;
         cur.rec_cap = lv[0].C;
         e = sq::launch_select(w.logits1, nullptr, nullptr, false, lv[0].thresh, lv[0].sizes, lv[0].child_offsets,
-                              lv[0].mask, nullptr, w.nr1, w.nk1, cur, true, 0, o, rows, sh->H, 1, lv[0].C, s);
+                              lv[0].mask, nullptr, w.nr1, w.nk1, cur, true, 0, o, rows, sh->H, 1, lv[0].C, s, user);
     }
     for (int k = 1; k < n && e == hipSuccess; ++k) {
         const bool last = k == n - 1;
@@ -911,7 +915,7 @@ int multilevel_lookup(const char *fn, const sq_shape_t *sh, int n, const Level *
         o.cand_items = cur.row_items;
         if (last) {
             e = sq::launch_select(w.logits2, nullptr, nullptr, false, lv[k].thresh, lv[k].sizes, lv[k].child_offsets,
-                                  lv[k].mask, ranges, n_ranges, n_keys, plan_last, schedule_last, sh->U, o, rows, sh->H, 1,
+                                  lv[k].mask, ranges, n_ranges, n_keys, plan_last, schedule_last, U_last, o, rows, sh->H, 1,
                                   lv[k].C, s);
         } else {
             o.len_from_offsets = 1;
@@ -930,11 +934,11 @@ int hier_lookup(const char *fn, const sq_shape_t *sh, int32_t C1, const void *q,
                 const int32_t *sizes1, const int32_t *child_offsets, const float *thresh1, const void *centroids2,
                 const int32_t *sizes2, const int32_t *offsets2, const float *thresh2, uint32_t *keep_mask1,
                 uint32_t *keep_mask2, int32_t *ranges, int32_t *n_ranges, int32_t *n_keys, HierWs &w,
-                sq::DecodePlan plan2, bool schedule2, hipStream_t s)
+                sq::DecodePlan plan2, bool schedule2, hipStream_t s, const sq::UserAttn *user = nullptr)
 {
     const Level lv[2] = {{C1, centroids1, sizes1, child_offsets, thresh1, keep_mask1},
                          {sh->C, centroids2, sizes2, offsets2, thresh2, keep_mask2}};
-    return multilevel_lookup(fn, sh, 2, lv, q, ranges, n_ranges, n_keys, w, sq::DecodePlan{}, plan2, schedule2, s);
+    return multilevel_lookup(fn, sh, 2, lv, q, ranges, n_ranges, n_keys, w, sq::DecodePlan{}, plan2, schedule2, s, user);
 }
 
 // Validates a caller's level array and copies it (masks: optional host array of per-level outputs).
@@ -1032,12 +1036,13 @@ int sq_hier_decode_step(const sq_shape_t *sh, int32_t C1, const void *q, const v
     hipStream_t s = static_cast<hipStream_t>(stream);
     Carver cv(ws);
     HierStepWs w = carve_hier_step(cv, sh);
+    const sq::UserAttn ua = make_user_rider(sh, 1, q, K_user, V_user, w.dec);
     if (int rc = hier_lookup(__func__, sh, C1, q, centroids1, sizes1, child_offsets, thresh1, centroids2, sizes2,
                              offsets2, thresh2, w.mask1, keep_mask2, nullptr, w.n_ranges, n_keys ? n_keys : w.n_keys,
-                             w.hier, w.dec.plan, true, s))
+                             w.hier, w.dec.plan, true, s, &ua))
         return rc;
     SQ_HIP(sq::launch_decode_attn(q, K_fixed, V_fixed, K_user, V_user, w.dec.plan, w.dec.partials, out, lse,
-                                  to_shape(sh), s));
+                                  to_shape(sh), s, ua.q ? ua.slot_base : -1, ua.nuq));
     g_err[0] = 0;
     return SQ_OK;
 }
@@ -1201,11 +1206,12 @@ int sq_multilevel_decode_step(const sq_shape_t *sh, int32_t n_levels, const sq_l
     HierStepWs w = carve_hier_step(cv, sh);
     sq::DecodePlan cand_b = carve_cand_plan(cv, sh);
     lv[n_levels - 1].mask = keep_mask;
+    const sq::UserAttn ua = make_user_rider(sh, 1, q, K_user, V_user, w.dec);
     if (int rc = multilevel_lookup(__func__, sh, n_levels, lv, q, nullptr, w.n_ranges, n_keys ? n_keys : w.n_keys, w.hier,
-                                   cand_b, w.dec.plan, true, s))
+                                   cand_b, w.dec.plan, true, s, &ua))
         return rc;
     SQ_HIP(sq::launch_decode_attn(q, K_fixed, V_fixed, K_user, V_user, w.dec.plan, w.dec.partials, out, lse,
-                                  to_shape(sh), s));
+                                  to_shape(sh), s, ua.q ? ua.slot_base : -1, ua.nuq));
     g_err[0] = 0;
     return SQ_OK;
 }
