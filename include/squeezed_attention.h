@@ -129,6 +129,11 @@ int sq_select(const sq_shape_t *shape, const float *logits, const float *row_max
  * chunk producing a partial (max, sum, output), merged in a second phase.
  * In:  ranges i32 [B,H,1,range_cap,2] (first key, count), ascending, disjoint, within [0, L);
  *      n_ranges, n_keys i32 [B,H,1] with n_keys = sum of counts; range_cap = shape->C.
+ *      The key counts are taken from the ranges themselves: n_keys must be a valid pointer (it keeps the
+ *      argument list of sq_select's outputs) but its values are not read.
+ *      Input outside this contract never faults and is not reported: of a row, only the first range_cap ranges
+ *      and the first L listed keys are used, entries with count <= 0 are skipped, and a key row outside
+ *      [0, L) is read as the nearest row inside.
  * Out: out f16 [B,H,1,d]; lse f32 [B,H,1] = log sum exp of the scaled logits, or NULL.
  *      A query with no visible key gets out = 0 and lse = -inf.
  * Workspace: sq_workspace_bytes(shape, SQ_CALL_ATTN_DECODE).
@@ -456,8 +461,15 @@ int sq_calibrate_threshold(const sq_shape_t *shape, const float *logits, const f
                            const int32_t *sizes, int64_t target_keys, float *thresh,
                            void *ws, size_t ws_bytes, void *stream);
 
+/* ------------------------------------------------------------------------------------------------------------------
+ * MEASUREMENT HOOKS -- sq_profile_begin / sq_profile_end / sq_probe_stream_read.  Not part of the method and not
+ * part of the path's boundary: nothing above calls them and no result depends on them.  They exist so that a
+ * benchmark can time the dominant kernel and the device's streaming-read ceiling from inside its own process.
+ * They keep process-wide state and are not thread-safe.
+ * ---------------------------------------------------------------------------------------------------------------- */
+
 /*
- * Measurement hook for benchmarks (not part of the method; for callers that want a kernel's duration
+ * Measurement hook for benchmarks (for callers that want a kernel's duration
  * without an external profiler).  Between sq_profile_begin(n) and sq_profile_end(), every launch of
  * the dominant kernel of a step -- the split-KV partial-attention kernel, which reads the selected K/V rows,
  * i.e. nearly all bytes of a decode step (Section 4.2, phase 1); the attention kernel of a prefill step --

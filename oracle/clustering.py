@@ -6,8 +6,8 @@ initialisation nor the number of iterations, so the unit defined here is one Llo
 layout step; readings taken: squared Euclidean distance between unit vectors (the usual K-means objective, which
 on unit vectors orders centres like cosine similarity corrected by the centre's norm); a centre is the plain mean
 of its members' normalised vectors (not re-normalised); a centre that loses all members keeps its value; ties go
-to the lowest centre index; the centroid handed to the online path is the mean of the RAW keys of the cluster
-(Section 3.1: "the mean of all vectors in each cluster"), as in the workload generator.
+to the lowest centre index; the centroid handed to the online path is the per-cluster mean of the RAW keys
+(Section 3.1 defines a centroid as the average of its cluster's members), as in the workload generator.
 
 Pins: tests/test_oracle_clustering.py.
 """

@@ -15,7 +15,7 @@ from typing import Optional
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("SQ_LIB_PATH") or os.path.join(_PKG, "libsqueezed_attention.so")   # override: tuning builds
+LIB_PATH = os.path.join(_PKG, "libsqueezed_attention.so")
 
 SQ_OK, SQ_ERR_INVALID_ARG, SQ_ERR_UNSUPPORTED, SQ_ERR_WORKSPACE, SQ_ERR_HIP = 0, -1, -2, -3, -4
 (SQ_CALL_CENTROID_SCORE, SQ_CALL_SELECT, SQ_CALL_ATTN_DECODE, SQ_CALL_ATTN_PREFILL, SQ_CALL_HIER_SELECT,

@@ -26,18 +26,14 @@ def sources():
     return sorted(f for f in os.listdir(CSRC) if f.endswith(".hip"))
 
 
-def build_library(verbose: bool = False, defines=(), out: str = LIB) -> str:
-    """Compile every .hip file under csrc/ and link the shared library.  Always recompiles.
-
-    `defines` (e.g. ["SQ_KPC=128"]) and `out` exist for tuning experiments; the product build uses neither.
-    """
+def build_library(verbose: bool = False) -> str:
+    """Compile every .hip file under csrc/ and link the shared library.  Always recompiles."""
     os.makedirs(OBJ_DIR, exist_ok=True)
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    dflags = [f"-D{d}" for d in defines]
 
     def compile_one(src):
         obj = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
-        cmd = [hipcc, *HIPCC_FLAGS, *FILE_FLAGS.get(src, []), *dflags, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc, *HIPCC_FLAGS, *FILE_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
         if r.returncode != 0:
@@ -48,11 +44,11 @@ def build_library(verbose: bool = False, defines=(), out: str = LIB) -> str:
 
     with ThreadPoolExecutor(max_workers=4) as ex:
         objs = list(ex.map(compile_one, sources()))
-    r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *objs],
+    r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs],
                        capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stderr}")
-    return out
+    return LIB
 
 
 if __name__ == "__main__":

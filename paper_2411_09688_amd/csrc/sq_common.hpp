@@ -6,10 +6,7 @@
 namespace sq {
 
 constexpr int D = 128;            // head dimension (fp16 row = 256 B = 16 lanes x 16 B)
-#ifndef SQ_KPC
-#define SQ_KPC 128
-#endif
-constexpr int KPC = SQ_KPC;       // keys per split-KV chunk = one workgroup of 4 waves x KPC/4 keys
+constexpr int KPC = 128;          // keys per split-KV chunk = one workgroup of 4 waves x KPC/4 keys
 constexpr int PART_STRIDE = 132;  // floats per partial result: m, l, pad, pad, o[128]
 
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
@@ -191,7 +188,9 @@ __device__ __forceinline__ void chunk_rows_from_records(int rec_pos, int rec_del
 // parallel: virtual thread v (0..1023) adds clusters v, v+1024, ... in ascending order; the 64 threads of
 // each of the 16 groups are combined with an xor butterfly; the 16 group sums are added in ascending
 // order.  This function walks the 16 groups one after the other, the selection kernel computes them
-// side by side: the results are bit-identical.
+// side by side: the results are bit-identical.  Every implementation adds a term as ONE fused multiply-add
+// (__fmaf_rn(N, e, sum); a thread's first term is then the rounded product), so the bits do not depend on what the
+// compiler chooses to contract.
 __device__ __forceinline__ void wave_row_stats(const float *x, const int32_t *N, int n, int lane, float &m_out,
                                                float &D_out)
 {
@@ -226,7 +225,7 @@ __device__ __forceinline__ void wave_row_stats(const float *x, const int32_t *N,
         }
 #pragma unroll
         for (int g = 0; g < 16; ++g)
-            if (nv[g] > 0) loc[g] += (float)nv[g] * expf(xv[g] - m);
+            if (nv[g] > 0) loc[g] = __fmaf_rn((float)nv[g], expf(xv[g] - m), loc[g]);   // (fused, everywhere)
     }
     float Dsum = 0.0f;
 #pragma unroll

@@ -24,14 +24,8 @@
 namespace sq {
 
 constexpr int KM_G = 64;                     // centres per staged group
-#ifndef SQ_KM_PAD
-#define SQ_KM_PAD 8
-#endif
-constexpr int KM_STRIDE = D + SQ_KM_PAD;             // halves per centre row in LDS (272 B: conflict-free 16-B reads)
-#ifndef SQ_KM_RW
-#define SQ_KM_RW 4
-#endif
-constexpr int KM_RW = SQ_KM_RW;             // B sets (16 keys each) per wave
+constexpr int KM_STRIDE = D + 8;             // halves per centre row in LDS (272 B: conflict-free 16-B reads)
+constexpr int KM_RW = 4;                     // B sets (16 keys each) per wave
 constexpr int KM_ROWS_PER_WG = 4 * 16 * KM_RW;
 
 struct KmStage {

@@ -39,12 +39,18 @@ constexpr int PF_BN = 64;                 // keys per block
 constexpr int PF_KS_STRIDE = D + 8;       // halves per K row in LDS (272 B: conflict-free 16-B reads)
 constexpr int PF_V_STRIDE = D + 16;       // halves per V row in LDS (288 B: the transposing reads below hit 32 distinct banks)
 
-// key -> cluster id map of every head (clusters are contiguous key ranges).
+// key -> cluster id map of every head (clusters are contiguous key ranges).  Keys that no cluster covers (before
+// offsets[0] or from offsets[C] on) get the "no cluster" id 0x7fffffff, which no query keeps.
 __global__ __launch_bounds__(256) void key_cluster_kernel(const int32_t *__restrict__ offsets, int32_t *__restrict__ cid,
                                                           int C, int L)
 {
     const int h = blockIdx.y;
     const int32_t *off = offsets + (size_t)h * (C + 1);
+    if (blockIdx.x == 0) {
+        const int head = max(0, min(L, off[0])), tail = max(0, min(L, off[C]));
+        for (int j = threadIdx.x; j < head; j += 256) cid[(size_t)h * L + j] = 0x7fffffff;
+        for (int j = tail + threadIdx.x; j < L; j += 256) cid[(size_t)h * L + j] = 0x7fffffff;
+    }
     for (int c = blockIdx.x * 4 + (threadIdx.x >> 6); c < C; c += gridDim.x * 4) {
         const int a = max(0, off[c]), b = min(L, off[c + 1]);
         for (int j = a + (threadIdx.x & 63); j < b; j += 64) cid[(size_t)h * L + j] = c;
@@ -60,8 +66,8 @@ __global__ __launch_bounds__(256) void block_info_kernel(const int32_t *__restri
     const int h = blockIdx.y;
     const int blk = blockIdx.x * 256 + threadIdx.x;
     if (blk >= nblk) return;
-    const int first = min(cid[(size_t)h * L + blk * PF_BN], C - 1);
-    const int last = min(cid[(size_t)h * L + min(L, (blk + 1) * PF_BN) - 1], C - 1);
+    const int first = max(0, min(cid[(size_t)h * L + blk * PF_BN], C - 1));
+    const int last = max(first, min(cid[(size_t)h * L + min(L, (blk + 1) * PF_BN) - 1], C - 1));
     const int span = last - first;
     blk_info[(size_t)h * nblk + blk] = first | (min(span, 30) << 16) | (span >= 31 ? (int)0x80000000 : 0);
 }
@@ -241,7 +247,7 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
             const int first = pinfo & 0xffff;
             if (tid < PF_BN) {
                 st.cid[tid] = pcid;
-                st.sh[tid] = pcid == 0x7fffffff ? 31 : min(pcid - first, 31);
+                st.sh[tid] = (unsigned)(pcid - first) >= 31u ? 31 : pcid - first;   // (no cluster, or outside the window: bit 31 is never set)
             }
             if (tid < BM) {
                 const unsigned long long two = ((unsigned long long)pw_hi << 32) | pw_lo;
@@ -414,7 +420,7 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
 #pragma unroll
                     for (int e = 0; e < 16; ++e) {
                         const int c = st.cid[(e >> 2) * 16 + kg * 4 + (e & 3)];
-                        const bool ok = c < C && nq[qt] < Lq && ((mrow[c >> 5] >> (c & 31)) & 1u);
+                        const bool ok = (unsigned)c < (unsigned)C && nq[qt] < Lq && ((mrow[c >> 5] >> (c & 31)) & 1u);
                         msk[qt][e] = ok ? 0xffffffffu : 0u;
                     }
                 }

@@ -110,7 +110,7 @@ __global__ __launch_bounds__(1024) void row_stats_block_kernel(const float *__re
     float local = 0.0f;
     for (int i = tid; i < C; i += 1024) {
         const int Ni = N[i];
-        if (Ni > 0) local += (float)Ni * expf(x[i] - m);
+        if (Ni > 0) local = __fmaf_rn((float)Ni, expf(x[i] - m), local);
     }
     local = wave_sum(local);
     if (lane == 0) s_red[wave] = local;

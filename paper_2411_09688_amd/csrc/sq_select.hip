@@ -472,7 +472,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
         float local = 0.0f;
         for (int i = tid; i < n; i += SEL_THREADS) {
             const int Ni = s_N[i];
-            if (Ni > 0) local += (float)Ni * s_e[i];
+            if (Ni > 0) local = __fmaf_rn((float)Ni, s_e[i], local);
         }
         local = wave_sum(local);
         if (lane == 0) s_wred[wave] = local;

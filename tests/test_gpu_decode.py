@@ -99,6 +99,8 @@ def test_cfg2_llama7b_decode_32k(sq, oracle):
     compare_decode(oracle, w, P, oracle_one_level(oracle, w), "cfg2")
     fused_matches(sq, w, P)
     print("cfg2 keep fraction per head:", np.round(P.n_keys.cpu().numpy().ravel() / w.L, 3), flush=True)
+    # the entry point the benchmark times, at the benchmarked size, against the oracle directly
+    step_against_oracle(sq, oracle, w, "cfg2 sq_decode_step")
 
 
 def test_cfg3_batched_decode_shared_context(sq, oracle):
@@ -109,6 +111,7 @@ def test_cfg3_batched_decode_shared_context(sq, oracle):
     run_separate(sq, w, P)
     compare_decode(oracle, w, P, oracle_one_level(oracle, w), "cfg3")
     fused_matches(sq, w, P)
+    step_against_oracle(sq, oracle, w, "cfg3 sq_decode_step")
 
 
 def test_keep_all_equals_dense_attention(sq, oracle, cfg1):

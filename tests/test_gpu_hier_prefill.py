@@ -166,7 +166,7 @@ def test_hier_prefill_mean_long_context_shape(sq, oracle):
                          coarse_keep_frac=1 / 8, causal_user=True, seed=34, threads=8)
     T1, T2 = thresholds(w)
     got = run(sq, w, T1, T2)
-    gk, err = compare(oracle, w, T1, T2, got, "hier-prefill-mean-big", sample=64)
+    gk, err = compare(oracle, w, T1, T2, got, "hier-prefill-mean-big")
     print("hier prefill mean attention max-abs err", err, "keep", got[3].mean() / w.L, flush=True)
     assert 0 < gk.sum()
 
