@@ -282,7 +282,8 @@ __global__ __launch_bounds__(256, 3) void decode_attn_shared_kernel(
         mx = cross16_max(mx);                              // the 4 lane groups hold the other keys of the column
         const float m_new = fmaxf(m_run, mx);
         const float mneg = m_new == SQ_NEG_INF ? 0.0f : -m_new * c2;   // nothing seen yet: exp2(-inf) = 0
-        const float alpha = __builtin_amdgcn_exp2f(fmaf(m_run, c2, mneg));
+        // (exactly 1 while the maximum stands still: m * c2 + fl(-m * c2) is the rounding error of the product, not 0)
+        const float alpha = m_new == m_run ? 1.0f : __builtin_amdgcn_exp2f(fmaf(m_run, c2, mneg));
         float psum = 0.0f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {

@@ -328,7 +328,9 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
                 mx = cross16_max(mx);                       // the 4 lane groups hold the other keys of the column
                 const float m_new = fmaxf(m_run[qt], mx);
                 const float mneg = m_new == SQ_NEG_INF ? 0.0f : -m_new * c2;   // nothing seen yet: exp2(-inf) = 0
-                const float alpha = __builtin_amdgcn_exp2f(fmaf(m_run[qt], c2, mneg));
+                // (exactly 1 while the maximum stands still: m * c2 + fl(-m * c2) is the rounding error of the product,
+                // not 0, and a factor 1 - 6e-7 per key block would leak into the running sum and hence into lse)
+                const float alpha = m_new == m_run[qt] ? 1.0f : __builtin_amdgcn_exp2f(fmaf(m_run[qt], c2, mneg));
                 float psum = 0.0f;
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
