@@ -232,6 +232,23 @@ int sq_decode_step(const sq_shape_t *shape, const void *q,
                    void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * sq_decode_step for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and error behaviour as
+ * sq_decode_step, without the workspace: the step's intermediate state (logits, range records, work list, partial
+ * results) lives in a device array of SQ_NOALLOC_SCRATCH_BYTES that is part of the library's code object -- one copy
+ * per GPU the library runs on, held until the process ends.  The call allocates and frees nothing.  A shape whose
+ * sq_workspace_bytes(shape, SQ_CALL_DECODE_STEP) exceeds SQ_NOALLOC_SCRATCH_BYTES is rejected with SQ_ERR_WORKSPACE
+ * (the limit covers one sequence of 32 heads over a 32K-key context with 1024 clusters and 512 user keys).
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different streams or threads)
+ * race; calls enqueued one after the other on one stream do not.
+ */
+#define SQ_NOALLOC_SCRATCH_BYTES (16u << 20)
+int sq_decode_step_noalloc(const sq_shape_t *shape, const void *q,
+                           const void *centroids, const int32_t *sizes, const int32_t *offsets, const float *thresh,
+                           const void *K_fixed, const void *V_fixed, const void *K_user, const void *V_user,
+                           void *out, float *lse, uint32_t *keep_mask, int32_t *n_keys, void *stream);
+
+/*
  * One whole decode step with GROUPED-QUERY attention (Lq must be 1): G query heads of a sequence share one K/V
  * head -- its fixed-context keys, centroids, threshold and the sequence's user keys -- and every query head
  * selects its clusters independently (the setting of the appendix "Additional Longbench Evaluation": keys and

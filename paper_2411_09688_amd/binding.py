@@ -26,7 +26,7 @@ SQ_MAX_LEVELS = 4
 
 EXPORTS = ("sq_workspace_bytes", "sq_last_error", "sq_version", "sq_centroid_score", "sq_select",
            "sq_sparse_attn_decode", "sq_sparse_attn_prefill", "sq_hier_select", "sq_decode_step",
-           "sq_hier_decode_step", "sq_select_mean", "sq_sparse_attn_prefill_shared", "sq_prefill_step",
+           "sq_hier_decode_step", "sq_decode_step_noalloc", "sq_select_mean", "sq_sparse_attn_prefill_shared", "sq_prefill_step",
            "sq_prefill_mean_step", "sq_gqa_decode_step", "sq_multilevel_select", "sq_multilevel_decode_step",
            "sq_kmeans_normalize", "sq_kmeans_step", "sq_cluster_layout", "sq_cluster_nest", "sq_calibrate_threshold", "sq_hier_prefill_mean_step", "sq_hier_prefill_step", "sq_gqa_mean_decode_step", "sq_profile_begin",
            "sq_profile_end", "sq_probe_stream_read")
@@ -71,6 +71,7 @@ def lib() -> C.CDLL:
         L.sq_sparse_attn_prefill.argtypes = [sp] + [vp] * 9 + [vp, sz, vp]
         L.sq_hier_select.argtypes = [sp, C.c_int32] + [vp] * 14 + [vp, sz, vp]
         L.sq_decode_step.argtypes = [sp] + [vp] * 13 + [vp, sz, vp]
+        L.sq_decode_step_noalloc.argtypes = [sp] + [vp] * 13 + [vp]
         L.sq_hier_decode_step.argtypes = [sp, C.c_int32] + [vp] * 17 + [vp, sz, vp]
         L.sq_hier_prefill_step.argtypes = [sp, C.c_int32] + [vp] * 17 + [vp, sz, vp]
         L.sq_hier_prefill_mean_step.argtypes = [sp, C.c_int32] + [vp] * 17 + [vp, sz, vp]
@@ -238,6 +239,20 @@ def sq_decode_step(shape, q, centroids, sizes, offsets, thresh, K_fixed, V_fixed
                                 _ptr(K_user, F16, "K_user"), _ptr(V_user, F16, "V_user"), _ptr(out, F16, "out"),
                                 _ptr(lse, F32, "lse"), _ptr(keep_mask, I32, "keep_mask"), _ptr(n_keys, I32, "n_keys"),
                                 *_ws_args(ws), _stream(stream)))
+
+
+SQ_NOALLOC_SCRATCH_BYTES = 16 << 20
+
+
+def sq_decode_step_noalloc(shape, q, centroids, sizes, offsets, thresh, K_fixed, V_fixed, K_user, V_user, out, lse,
+                           keep_mask, n_keys, stream=None):
+    _check(lib().sq_decode_step_noalloc(C.byref(shape), _ptr(q, F16, "q"), _ptr(centroids, F16, "centroids"),
+                                        _ptr(sizes, I32, "sizes"), _ptr(offsets, I32, "offsets"),
+                                        _ptr(thresh, F32, "thresh"), _ptr(K_fixed, F16, "K_fixed"),
+                                        _ptr(V_fixed, F16, "V_fixed"), _ptr(K_user, F16, "K_user"),
+                                        _ptr(V_user, F16, "V_user"), _ptr(out, F16, "out"), _ptr(lse, F32, "lse"),
+                                        _ptr(keep_mask, I32, "keep_mask"), _ptr(n_keys, I32, "n_keys"),
+                                        _stream(stream)))
 
 
 def sq_gqa_decode_step(shape, G, q, centroids, sizes, offsets, thresh, K_fixed, V_fixed, K_user, V_user, out, lse,

@@ -193,6 +193,9 @@ hipError_t launch_cluster_layout(const void *K, const void *V, const int32_t *pe
 hipError_t launch_calibrate(const float *logits, const float *row_max, const float *denom, const int32_t *sizes,
                             float *S, float *thresh, int target, int B, int H, int Lq, int C, hipStream_t s);
 
+// Records the calling thread's error message (what sq_last_error returns) and hands back `code`.
+int set_error(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+
 // Measurement hook (sq_profile.hip): when enabled, hands out the next pair of events; the caller attaches them to
 // the dominant kernel's dispatch (hipExtLaunchKernelGGL), so they carry the start and end time of that kernel
 // itself rather than of marker packets around it.
