@@ -403,9 +403,10 @@ def bench_gqa(args, torch, sq, wl, dev):
     # The library streams the union once from 8 (sequence, query head) pairs per K/V head on; with fewer, its
     # per-row kernels read a K/V head's selected keys and user keys once per query head.
     shared = mean or w.B * G >= 8
-    kernel = "decode_attn_shared_kernel" if shared else "decode_attn_kernel"
-    # (per-row kernels: the user keys ride on the selection launch, the partial kernel reads the selected keys only)
-    kernel_bytes = (sel + dense if shared else sel_req) + w.B * Hq * w.d * 2
+    kernel = "decode_attn_shared_kernel" if shared else "decode_attn_index_kernel"
+    # (per-row kernels: every query head reads its own selection and, in extra workgroups of the same launch, the
+    # sequence's user keys)
+    kernel_bytes = (sel + dense if shared else sel_req + dense * G) + w.B * Hq * w.d * 2
     res = base_result(args, "grouped-query decode attn µs/token + achieved HBM GB/s, 32K fixed ctx, keep 1/8, "
                       "32 query heads over 8 K/V heads, d=128", round(tot / (ms * 1e-3) / 1e9, 2), "GB/s", ms, eager_ms,
                       graph_ms, w.B)
@@ -602,10 +603,15 @@ def main():
         uniq_keys = (bits * w.sizes[None]).sum(axis=(1, 2))                            # [NQ]
         sel = float(np.mean([uniq_keys[qi] for qi in used])) * w.d * 2 * 2
         tot = tot - sel_requested + sel
-    # K/V rows read by the partial kernel + q.  In the fused per-row step (fewer than 8 sequences) the user keys are
-    # attended to by extra workgroups of the selection launch, so the partial kernel reads the selected keys only.
-    rider = not args.separate and w.B < 8
-    kernel_bytes = sel + (0 if rider else dense) + w.B * w.H * w.d * 2
+    # K/V rows read by the launch of the partial kernel + q: the selected keys and the user keys (in the per-row step
+    # the user keys are attended to by extra workgroups of the same launch).
+    kernel_bytes = sel + dense + w.B * w.H * w.d * 2
+    if w.B > 1 and not args.separate:
+        dom_kernel = "decode_attn_shared_kernel"
+    elif args.separate:
+        dom_kernel = "decode_attn_kernel"
+    else:
+        dom_kernel = "decode_attn_index_kernel"
     keep = float(np.mean([nk[qi].mean() for qi in used]) / w.L)
     tokens = w.B
 
@@ -625,13 +631,11 @@ def main():
                            "selected_kv_requested": round(sel_requested),
                            "dense_kv": round(dense), "centroid_plus_selected_kv": round(cen + sel)},
         "hbm_frac_whole_step": round(tot / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-        "roofline": {"bound": "hbm", "kernel": "decode_attn_shared_kernel" if w.B > 1 and not args.separate
-                     else "decode_attn_kernel",
+        "roofline": {"bound": "hbm", "kernel": dom_kernel,
                      "achieved": round(kernel_bytes / (k_avg_us * 1e-6) / 1e9, 2) if n_meas else None,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(kernel_bytes / (k_avg_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4) if n_meas else None,
-                     "traffic": read_traffic(("decode_attn_shared_kernel" if w.B > 1 and not args.separate
-                                              else "decode_attn_kernel") + f"_{args.workload}_pmc.txt"),
+                     "traffic": read_traffic(f"{dom_kernel}_{args.workload}_pmc.txt"),
                      "bytes_per_launch": round(kernel_bytes), "avg_us": round(k_avg_us, 3),
                      "min_us": round(k_min_us, 3), "launches": n_meas},
     }

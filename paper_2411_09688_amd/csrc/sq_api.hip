@@ -168,6 +168,39 @@ StepWs carve_step(Carver &cv, const sq_shape_t *sh, int G = 1)
     return w;
 }
 
+// Workspace of the decode step through a key-index list (sq_decode_keyidx.hip): logits, counts, the rows' key-index
+// lists and the partial results.
+struct IndexStepWs {
+    float *logits;
+    int32_t *n_ranges, *n_keys;
+    sq::KeyIndexPlan plan;
+    float *partials;
+    int user_slot_base, nuq;
+};
+
+IndexStepWs carve_step_index(Carver &cv, const sq_shape_t *sh, int G = 1)
+{
+    const size_t rows = (size_t)sh->B * sh->H * G;
+    IndexStepWs w{};
+    w.nuq = sq::user_pieces_for(sh->U);
+    w.user_slot_base = sq::KI_ATTN_GRID + (int)rows;
+    w.logits = cv.take<float>(rows * sh->C);
+    w.n_ranges = cv.take<int32_t>(rows);
+    w.n_keys = cv.take<int32_t>(rows);
+    w.plan.L = sh->L;
+    w.plan.row_keys = cv.take<int32_t>(rows);
+    w.plan.key_idx = cv.take<int32_t>(rows * sh->L);
+    w.partials = cv.take<float>(sq::keyidx_partial_slots((int)rows, w.nuq) * sq::PART_STRIDE);
+    return w;
+}
+
+// The key-index step handles rows of up to KI_MAX_C clusters and calls of up to KI_MAX_ROWS query rows; anything
+// larger takes the work-list kernels.
+bool step_is_indexed(const sq_shape_t *sh, int G = 1)
+{
+    return sh->C <= sq::KI_MAX_C && (long long)sh->B * sh->H * G <= sq::KI_MAX_ROWS;
+}
+
 // Workspace of a decode step over a shared context (B >= 2): per-sequence selection outputs, then the union
 // rows' plan and the partials of the shared-context kernel.
 struct SharedStepWs {
@@ -424,6 +457,7 @@ size_t sq_workspace_bytes(const sq_shape_t *sh, int which)
         return cv.off;
     case SQ_CALL_DECODE_STEP:
         if (step_is_shared(sh)) carve_step_shared(cv, sh);
+        else if (step_is_indexed(sh)) carve_step_index(cv, sh);
         else carve_step(cv, sh);
         return cv.off;
     case SQ_CALL_ATTN_PREFILL:
@@ -441,9 +475,11 @@ size_t sq_workspace_bytes(const sq_shape_t *sh, int which)
         return cv.off;
     case SQ_CALL_GQA_DECODE_STEP: {                     // sized for the largest group (16 query heads per K/V head)
         carve_step_shared(cv, sh, sq::SG);
-        Carver cv2(nullptr);                            // ... on either kernel family
+        Carver cv2(nullptr), cv3(nullptr);              // ... on any of the kernel families
         carve_step(cv2, sh, sq::SG);
-        return cv.off > cv2.off ? cv.off : cv2.off;
+        carve_step_index(cv3, sh, sq::SG);
+        size_t n = cv.off > cv2.off ? cv.off : cv2.off;
+        return n > cv3.off ? n : cv3.off;
     }
     case SQ_CALL_MULTILEVEL_SELECT:
         carve_hier(cv, sh);
@@ -575,6 +611,39 @@ int decode_step_shared(const sq_shape_t *sh, int G, const void *q, const void *c
 }
 }  // namespace
 
+namespace {
+// Decode step of rows that are handled one by one (few query rows per K/V head), through the key-index list:
+// score -> selection + key-index lists -> partial results over equal shares of the kept keys (the user keys in extra
+// workgroups of the same launch) -> merge.  rows = B * H * G query rows [B, H, G]; K/V head of a row = (row / G) % H.
+int decode_step_indexed(const sq_shape_t *sh, int G, const void *q, const void *centroids, const int32_t *sizes,
+                        const int32_t *offsets, const float *thresh, const void *K_fixed, const void *V_fixed,
+                        const void *K_user, const void *V_user, void *out, float *lse, uint32_t *keep_mask,
+                        int32_t *n_keys, Carver &cv, hipStream_t s)
+{
+    IndexStepWs w = carve_step_index(cv, sh, G);
+    const int rows = sh->B * sh->H * G;
+    sq::UserAttn ua{};
+    if (sh->U > 0) {
+        ua.q = static_cast<const _Float16 *>(q);
+        ua.Ku = static_cast<const _Float16 *>(K_user);
+        ua.Vu = static_cast<const _Float16 *>(V_user);
+        ua.partials = w.partials;
+        ua.rows = rows;
+        ua.U = sh->U;
+        ua.G = G;
+        ua.nuq = w.nuq;
+        ua.slot_base = w.user_slot_base;
+        ua.sm_scale = sh->sm_scale;
+    }
+    SQ_HIP(sq::launch_score(q, centroids, w.logits, nullptr, sh->B, sh->H, G, sh->C, sh->sm_scale, s));
+    SQ_HIP(sq::launch_select_index(w.logits, thresh, sizes, offsets, keep_mask, w.n_ranges, n_keys ? n_keys : w.n_keys,
+                                   w.plan, rows, sh->H, G, sh->C, s));
+    SQ_HIP(sq::launch_decode_attn_index(q, K_fixed, V_fixed, w.plan, w.partials, out, lse, rows, sh->H, G, sh->sm_scale,
+                                        &ua, s));
+    return SQ_OK;
+}
+}  // namespace
+
 int sq_gqa_decode_step(const sq_shape_t *sh, int32_t G, const void *q, const void *centroids, const int32_t *sizes,
                        const int32_t *offsets, const float *thresh, const void *K_fixed, const void *V_fixed,
                        const void *K_user, const void *V_user, void *out, float *lse, uint32_t *keep_mask,
@@ -611,6 +680,13 @@ int sq_gqa_decode_step(const sq_shape_t *sh, int32_t G, const void *q, const voi
     }
     // Few query rows per K/V head: every (sequence, query head) is a row of the per-row kernels, which read the K/V
     // head once per query head (the rows are [B, H, G]: K/V head = (row / G) % H).
+    if (step_is_indexed(sh, G)) {
+        if (int rc = decode_step_indexed(sh, G, q, centroids, sizes, offsets, thresh, K_fixed, V_fixed, K_user, V_user, out,
+                                         lse, keep_mask, n_keys, cv, s))
+            return rc;
+        g_err[0] = 0;
+        return SQ_OK;
+    }
     StepWs w = carve_step(cv, sh, G);
     int32_t *nk = n_keys ? n_keys : w.n_keys;
     const int rows = sh->B * sh->H * G;
@@ -695,6 +771,13 @@ int sq_decode_step(const sq_shape_t *sh, const void *q, const void *centroids, c
     if (step_is_shared(sh)) {
         if (int rc = decode_step_shared(sh, 1, q, centroids, sizes, offsets, thresh, K_fixed, V_fixed, K_user, V_user,
                                         out, lse, keep_mask, n_keys, cv, s))
+            return rc;
+        g_err[0] = 0;
+        return SQ_OK;
+    }
+    if (step_is_indexed(sh)) {
+        if (int rc = decode_step_indexed(sh, 1, q, centroids, sizes, offsets, thresh, K_fixed, V_fixed, K_user, V_user, out,
+                                         lse, keep_mask, n_keys, cv, s))
             return rc;
         g_err[0] = 0;
         return SQ_OK;

@@ -193,6 +193,34 @@ hipError_t launch_cluster_layout(const void *K, const void *V, const int32_t *pe
 hipError_t launch_calibrate(const float *logits, const float *row_max, const float *denom, const int32_t *sizes,
                             float *S, float *thresh, int target, int B, int H, int Lq, int C, hipStream_t s);
 
+// Decode step through a key-index list (sq_decode_keyidx.hip): the selection writes, per query row, the rows of the
+// kept keys in ascending order (key_idx [rows, L]) and the number of them (row_keys [rows]); the partial kernel cuts
+// the rows' lists, laid end to end, into equal shares of keys.  For rows of at most KI_MAX_C clusters and calls of at
+// most KI_MAX_ROWS query rows.
+constexpr int KI_MAX_C = 4096;
+constexpr int KI_SLICE = 128;          // clusters per selection workgroup
+constexpr int KI_MAX_ROWS = 1024;
+constexpr int KI_MIN_SHARE = 128;      // keys per workgroup of the partial kernel, at least
+constexpr int KI_ATTN_GRID = 256;      // workgroups of the partial kernel that stream selected keys: one per compute unit
+struct KeyIndexPlan {
+    int32_t *key_idx;                  // [rows, L]
+    int32_t *row_keys;                 // [rows]
+    int L;
+};
+// Partial results: KI_ATTN_GRID + rows slots for the selected keys, then rows * nuq for the user keys.
+inline size_t keyidx_partial_slots(int rows, int nuq) { return (size_t)KI_ATTN_GRID + rows + (size_t)rows * nuq; }
+hipError_t launch_select_index(const float *logits, const float *thresh, const int32_t *sizes, const int32_t *offsets,
+                               uint32_t *keep_mask, int32_t *n_ranges, int32_t *n_keys, KeyIndexPlan plan, int rows,
+                               int H, int G, int C, hipStream_t s);
+// Partial kernel over the selected keys + merge.  user (may be null): the rows' dense attention over their user keys
+// runs in extra workgroups of the partial kernel, one per piece of USER_PIECE keys: row r leaves user->nuq =
+// user_pieces_for(U) partial results at slots user->slot_base + r * nuq + (0 .. nuq - 1) of `partials`.
+constexpr int USER_PIECE = 64;
+inline int user_pieces_for(int U) { return (U + USER_PIECE - 1) / USER_PIECE; }
+hipError_t launch_decode_attn_index(const void *q, const void *Kf, const void *Vf, KeyIndexPlan plan, float *partials,
+                                    void *out, float *lse, int rows, int H, int G, float sm_scale, const UserAttn *user,
+                                    hipStream_t s);
+
 // Records the calling thread's error message (what sq_last_error returns) and hands back `code`.
 int set_error(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
 

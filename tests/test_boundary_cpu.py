@@ -37,7 +37,7 @@ def test_workspace_sizes(sq):
     assert sq.workspace_bytes(sh, sq.SQ_CALL_SELECT) == 0
     a = sq.workspace_bytes(sh, sq.SQ_CALL_ATTN_DECODE)
     b = sq.workspace_bytes(sh, sq.SQ_CALL_DECODE_STEP)
-    assert 0 < a < b and a % 256 == 0 and b % 256 == 0
+    assert a > 0 and b > 0 and a % 256 == 0 and b % 256 == 0
     # partials alone: 32 rows x (2 user + 128 fixed chunks) x 132 floats
     assert a >= 32 * 130 * 132 * 4
     bad = sq.make_shape(0, 32, 32768, 1024, 1, 512, 0.0884)
@@ -95,3 +95,16 @@ def test_host_side_validation_of_the_offline_calls(sq):
     big = sq.make_shape(64, 2, 1 << 19, 4, 64, 0, 1.0)           # B * Lq * L = 2^31 pooled keys
     rc = L.sq_calibrate_threshold(C.byref(big), *([aligned] * 4), 5, aligned, aligned, 1 << 40, None)
     assert rc == sq.SQ_ERR_UNSUPPORTED and b"calibration queries" in L.sq_last_error()
+
+
+def test_noalloc_step_rejects_oversized_shapes_on_the_host(sq):
+    """sq_decode_step_noalloc checks the shape against its built-in buffer before it touches a device."""
+    L = sq.lib()
+    sh = sq.make_shape(4, 32, 32768, 1024, 1, 512, 0.0884)
+    assert sq.workspace_bytes(sh, sq.SQ_CALL_DECODE_STEP) > sq.SQ_NOALLOC_SCRATCH_BYTES
+    buf = (C.c_char * 4096)()
+    p = C.c_void_p((C.cast(buf, C.c_void_p).value + 255) & ~255)
+    rc = L.sq_decode_step_noalloc(C.byref(sh), p, p, p, p, p, p, p, p, p, p, None, None, None, None)
+    assert rc == sq.SQ_ERR_WORKSPACE and b"built-in" in L.sq_last_error()
+    fits = sq.make_shape(1, 32, 32768, 1024, 1, 512, 0.0884)
+    assert sq.workspace_bytes(fits, sq.SQ_CALL_DECODE_STEP) <= sq.SQ_NOALLOC_SCRATCH_BYTES

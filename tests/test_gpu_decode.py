@@ -63,8 +63,10 @@ def compare_decode(oracle, w, P, ref, label):
 
 
 def fused_matches(sq, w, P):
-    """sq_decode_step: the same selection as the three separate calls, bit for bit; attention equal up to the
-    rounding of a different split of the keys over workgroups (fp32 partial sums regrouped)."""
+    """sq_decode_step against the three separate calls.  The step scores the centroids with its own kernel (another
+    fp32 summation order than sq_centroid_score), so a cluster whose score sits within rounding of the threshold may be
+    decided differently: every difference must lie in the near-threshold band.  Rows with identical selections have
+    attention outputs equal up to the rounding of a different split of the keys over workgroups."""
     sh = P.shape
     out2 = torch.zeros_like(P.out); lse2 = torch.zeros_like(P.lse)
     mask2 = torch.zeros_like(P.keep_mask); nk2 = torch.zeros_like(P.n_keys)
@@ -72,9 +74,13 @@ def fused_matches(sq, w, P):
     sq.sq_decode_step(sh, P.q, P.centroids, P.sizes, P.offsets, P.thresh, P.K_fixed, P.V_fixed, P.K_user, P.V_user,
                       out2, lse2, mask2, nk2, ws)
     torch.cuda.synchronize()
-    assert torch.equal(mask2, P.keep_mask) and torch.equal(nk2, P.n_keys)
-    assert (out2.float() - P.out.float()).abs().max().item() <= 1e-3
-    torch.testing.assert_close(lse2, P.lse, atol=1e-5, rtol=1e-6)
+    g2, g1 = unpack_mask(mask2.cpu().numpy(), w.C), unpack_mask(P.keep_mask.cpu().numpy(), w.C)
+    check_selection(w, g2, g1, w.thresh, label="step vs separate calls")
+    np.testing.assert_array_equal(nk2.cpu().numpy(), (g2 * w.sizes[None, :, None, :]).sum(-1))
+    same = torch.from_numpy((g2 == g1).all(-1)).to(P.out.device)          # [B,H,1]
+    if same.any():
+        assert (out2.float() - P.out.float()).abs().amax(-1)[same].max().item() <= 1e-3
+        torch.testing.assert_close(lse2[same], P.lse[same], atol=1e-5, rtol=1e-6)
 
 
 @pytest.fixture(scope="module")
