@@ -56,14 +56,49 @@ def step_bytes(w, n_keys_per_head):
 
 
 def read_traffic(name):
-    """HBM bytes per launch of the dominant kernel from a committed rocprofv3 --pmc summary, if present."""
+    """Entries for `roofline`: HBM bytes per launch of the dominant kernel from a committed rocprofv3 --pmc summary
+    (`traffic`, None without one), the algorithmic bytes per launch OF THAT SAME RUN, and their ratio.  The counter run covers other query
+    tokens than this run, so the counter figure is only ever compared with its own run's byte count."""
     path = os.path.join(ROOT, "profiles", name)
     if not os.path.exists(path):
-        return None
+        return {"traffic": None}
+    vals = {}
     for line in open(path):
-        if line.startswith("traffic_bytes_per_launch:"):
-            return float(line.split(":", 1)[1])
-    return None
+        for key in ("traffic_bytes_per_launch", "algorithmic_bytes_per_launch"):
+            if line.startswith(key + ":"):
+                vals[key] = float(line.split(":", 1)[1])
+    t, a = vals.get("traffic_bytes_per_launch"), vals.get("algorithmic_bytes_per_launch")
+    if t is None:
+        return {"traffic": None}
+    return {"traffic": t, "traffic_run_bytes_per_launch": a, "traffic_over_run_bytes": round(t / a, 4) if a else None,
+            "traffic_source": "profiles/" + name}
+
+
+def stream_ceiling(sq, torch, dev, nbytes, reps=30):
+    """Measured on this device, in this run: bandwidth of a plain streaming read (sq_probe_stream_read, 512 workgroups,
+    non-temporal 16-byte loads) of as many bytes as the dominant kernel moves per launch, rotating through enough
+    buffers that the 256 MB last-level cache cannot serve them.  What an HBM-bound kernel of this size can approach."""
+    n = int(max(1 << 24, min(int(nbytes), 1 << 30))) & ~255
+    nbuf = max(2, min(16, -(-(3 << 28) // n)))
+    bufs = [torch.ones(n, dtype=torch.uint8, device=dev) for _ in range(nbuf)]
+    sink = torch.zeros(1024, dtype=torch.int32, device=dev)
+    for i in range(4):
+        sq.sq_probe_stream_read(bufs[i % nbuf], sink, 512, n)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for i in range(reps):
+            sq.sq_probe_stream_read(bufs[i % nbuf], sink, 512, n)
+    g.replay()
+    torch.cuda.synchronize()
+    e0.record()
+    g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / reps
+    del bufs
+    return {"stream_ceiling_GBps": round(n / us / 1e3, 1), "stream_ceiling_bytes": n, "stream_ceiling_us": round(us, 3)}
 
 
 def cpu_baseline(w_name, seed, budget_s):
@@ -217,7 +252,7 @@ def bench_prefill(args, torch, sq, wl, dev):
                        "frac": round(useful_attn / (k_avg * 1e-6) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4) if n_meas else None,
                        "executed_TFLOPs": round(executed / (k_avg * 1e-6) / 1e12, 2) if n_meas else None,
                        "executed_frac": round(executed / (k_avg * 1e-6) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4) if n_meas else None,
-                       "traffic": read_traffic(f"prefill_attn_kernel_{args.workload}_pmc.txt"),
+                       **read_traffic(f"prefill_attn_kernel_{args.workload}_pmc.txt"),
                        "flops_per_launch": useful_attn, "avg_us": round(k_avg, 2), "min_us": round(k_min, 2),
                        "launches": n_meas}
     print(json.dumps(res, ensure_ascii=False))
@@ -337,9 +372,12 @@ def bench_hier(args, torch, sq, wl, dev):
     # (the user keys are attended to by extra workgroups of the level-1 selection launch: the partial kernel reads the
     # selected keys only)
     kernel_bytes = sel + w.H * w.d * 2
-    res = base_result(args, "hierarchical decode attn µs/token + achieved HBM GB/s, 512K fixed ctx, keep 1/16",
+    res = base_result(args, f"hierarchical decode attn µs/token + achieved HBM GB/s, {w.L // 1024}K fixed ctx, "
+                      f"keep {w.keep_frac:.4g}",
                       round(tot / (ms * 1e-3) / 1e9, 2), "GB/s", ms, eager_ms, graph_ms, 1)
     res["config"] = {"workload": args.workload, "H": w.H, "d": w.d, "L": w.L, "C1": w.C1, "C2": w.C, "U": w.U,
+                     "fanout_min_max": [int(fan.min()), int(fan.max())],
+                     "candidate_fine_fraction": round(float(np.mean([ncand[qi] for qi in steps_q]) / w.H / w.C), 4),
                      "keep_achieved": round(float(np.mean([nk[qi].mean() for qi in steps_q]) / w.L), 5),
                      "queries": NQ, "entry": "sq_hier_decode_step"}
     res["bytes_per_step"] = {"total": round(tot), "coarse_centroids": coarse, "candidate_fine_centroids": round(cand),
@@ -349,11 +387,54 @@ def bench_hier(args, torch, sq, wl, dev):
                        "achieved": round(kernel_bytes / (k_avg * 1e-6) / 1e9, 2) if n_meas else None,
                        "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                        "frac": round(kernel_bytes / (k_avg * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4) if n_meas else None,
-                       "traffic": read_traffic(("decode_attn_shared_kernel" if w.B > 1 and not args.separate
+                       **read_traffic(("decode_attn_shared_kernel" if w.B > 1 and not args.separate
                                               else "decode_attn_kernel") + f"_{args.workload}_pmc.txt"),
                        "bytes_per_launch": round(kernel_bytes), "avg_us": round(k_avg, 3), "min_us": round(k_min, 3),
                        "launches": n_meas}
+    res["roofline"].update(stream_ceiling(sq, torch, dev, kernel_bytes))
+    res["lookup_us"] = hier_lookup_times(args, torch, sq, w, P, shape, Q, dev)
     print(json.dumps(res, ensure_ascii=False))
+
+
+def hier_lookup_times(args, torch, sq, w, P, shape, Q, dev, reps=100):
+    """The centroid lookup alone (no attention), as the paper compares it (appendix "Hierarchical kernel benchmarking"):
+    the two-level lookup (sq_hier_select: level-1 scores + selection, level-2 scores + selection over the children of
+    the kept coarse clusters) against the one-level lookup over ALL fine centroids (sq_centroid_score + sq_select),
+    each as one HIP-graph replay of `reps` lookups on different query tokens."""
+    NQ = Q.shape[0]
+    i32 = lambda *s: torch.zeros(s, dtype=torch.int32, device=dev)
+    m1, m2 = i32(1, w.H, (w.C1 + 31) // 32), i32(1, w.H, (w.C + 31) // 32)
+    nr, nk = i32(1, w.H, 1), i32(1, w.H, 1)
+    ws_h = sq.workspace(shape, sq.SQ_CALL_HIER_SELECT, dev)
+    logits = torch.empty(1, w.H, 1, w.C, dtype=torch.float32, device=dev)
+    rmax = torch.empty(1, w.H, 1, dtype=torch.float32, device=dev)
+    den = torch.empty_like(rmax)
+
+    def two_level(i):
+        sq.sq_hier_select(shape, w.C1, Q[i % NQ], P.centroids1, P.sizes1, P.child_offsets, P.thresh1, P.centroids, P.sizes,
+                          P.offsets, P.thresh2, m1, m2, None, nr, nk, ws_h)
+
+    def one_level(i):
+        sq.sq_centroid_score(shape, Q[i % NQ], P.centroids, P.sizes, logits, rmax, den)
+        sq.sq_select(shape, logits, rmax, den, P.thresh2, P.sizes, P.offsets, m2, None, nr, nk)
+
+    out = {}
+    for name, fn in (("two_level", two_level), ("one_level_all_fine_centroids", one_level)):
+        for i in range(5):
+            fn(i)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(reps):
+                fn(i)
+        g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        g.replay()
+        torch.cuda.synchronize()
+        out[name] = round((time.perf_counter() - t0) / reps * 1e6, 2)
+    out["two_level_over_one_level"] = round(out["two_level"] / out["one_level_all_fine_centroids"], 3)
+    return out
 
 
 def bench_gqa(args, torch, sq, wl, dev):
@@ -421,9 +502,10 @@ def bench_gqa(args, torch, sq, wl, dev):
                        "achieved": round(kernel_bytes / (k_avg * 1e-6) / 1e9, 2) if n_meas else None,
                        "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                        "frac": round(kernel_bytes / (k_avg * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4) if n_meas else None,
-                       "traffic": read_traffic(f"{kernel}_{args.workload}_pmc.txt"),
+                       **read_traffic(f"{kernel}_{args.workload}_pmc.txt"),
                        "bytes_per_launch": round(kernel_bytes), "avg_us": round(k_avg, 3), "min_us": round(k_min, 3),
                        "launches": n_meas}
+    res["roofline"].update(stream_ceiling(sq, torch, dev, kernel_bytes))
     print(json.dumps(res, ensure_ascii=False))
 
 
@@ -495,6 +577,9 @@ def main():
     ap.add_argument("--selection", choices=("per_query", "mean"), default="per_query",
                     help="prefill workloads: per-query selection, or the paper's selection on averaged scores")
     ap.add_argument("--separate", action="store_true", help="time the three separate calls instead of sq_decode_step")
+    ap.add_argument("--global-threshold", action="store_true",
+                    help="decode workloads: heads of different score skewness under ONE threshold for all heads "
+                         "(Section 3.2), so that the heads keep very different numbers of keys")
     args = ap.parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus {args.gpus} is not "
@@ -521,13 +606,13 @@ def main():
         return bench_gqa(args, torch, sq, wl, dev)
     if args.workload in wl.KMEANS_CONFIGS:
         return bench_kmeans(args, torch, sq, wl, dev)
-    cfg = wl.CONFIGS[args.workload]
+    cfg = wl.CONFIGS[args.workload] if args.workload in wl.CONFIGS else wl.HIER_SIZING_CONFIGS[args.workload]
     if cfg.get("Lq", 1) > 1:
         return bench_prefill(args, torch, sq, wl, dev)
     if cfg.get("C1", 0):
         return bench_hier(args, torch, sq, wl, dev)
-    w = wl.make_config(args.workload, seed=args.seed, threads=16)
-    wl.calibrate(w, gpu_score_fn(sq, torch, dev))
+    w = wl.make_config(args.workload, seed=args.seed, threads=16, **({"head_skew": 0.4} if args.global_threshold else {}))
+    wl.calibrate(w, gpu_score_fn(sq, torch, dev), global_threshold=args.global_threshold)
     NQ, R = args.queries, args.replicas
     tt = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
     rep = lambda a: [tt(a) for _ in range(R)]
@@ -626,6 +711,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": args.workload, "B": w.B, "H": w.H, "d": w.d, "L": w.L, "C": w.C, "U": w.U,
                    "keep_target": w.keep_frac, "keep_achieved": round(keep, 5), "queries": NQ, "replicas": R,
+                   "threshold": "one for all heads, head skew 0.4" if args.global_threshold else "per head",
+                   "keep_per_head_min_max": [round(float(np.mean([nk[qi] for qi in used], axis=(0, 1)).min() / w.L), 4),
+                                             round(float(np.mean([nk[qi] for qi in used], axis=(0, 1)).max() / w.L), 4)],
                    "entry": "3 calls" if args.separate else "sq_decode_step"},
         "bytes_per_step": {"total": round(tot), "centroid": round(cen), "selected_kv": round(sel),
                            "selected_kv_requested": round(sel_requested),
@@ -635,10 +723,11 @@ def main():
                      "achieved": round(kernel_bytes / (k_avg_us * 1e-6) / 1e9, 2) if n_meas else None,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(kernel_bytes / (k_avg_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4) if n_meas else None,
-                     "traffic": read_traffic(f"{dom_kernel}_{args.workload}_pmc.txt"),
+                     **read_traffic(f"{dom_kernel}_{args.workload}_pmc.txt"),
                      "bytes_per_launch": round(kernel_bytes), "avg_us": round(k_avg_us, 3),
                      "min_us": round(k_min_us, 3), "launches": n_meas},
     }
+    res["roofline"].update(stream_ceiling(sq, torch, dev, kernel_bytes))
     if args.cpu_seconds > 0:
         res["cpu_baseline"] = cpu_baseline(args.workload, args.seed, args.cpu_seconds)
     print(json.dumps(res, ensure_ascii=False))

@@ -380,7 +380,10 @@ __global__ __launch_bounds__(256) void decode_attn_index_kernel(
         // batch, so that waiting for them later does not wait for that batch
         nxt = next_sb();
         const bool have_n = nxt.r >= 0;
-        if (!have_n) nxt = cur;                              // (none left: a copy of `cur`, re-read, unused)
+        if (!have_n) {                                       // none left: loads that are never used re-read ONE key row
+            nxt = cur;
+            nxt.n = 1;
+        }
         fetch_rows(nxt, kr_n, qv_n);
         set_base(nxt, Kb_n, Vb_n);
         fetch_kv(Kb, Vb, kr, NB, kB, vB);

@@ -107,10 +107,10 @@ def _cluster_means(keys16: np.ndarray, sizes: np.ndarray, centres: np.ndarray) -
     return out.astype(F16)
 
 
-def _head_fixed(seed, cfg, h, L, C, d, centres=None):
+def _head_fixed(seed, cfg, h, L, C, d, centres=None, scale=1.0):
     """One head of the fixed context: centres, sizes, sorted keys, values, centroids."""
     if centres is None:
-        centres = _normal(_rng(seed, cfg, "centres", h), (C, d))
+        centres = np.float32(scale) * _normal(_rng(seed, cfg, "centres", h), (C, d))
     sizes = _rng(seed, cfg, "sizes", h).multinomial(L, np.full(C, 1.0 / C)).astype(np.int32)
     ids = np.repeat(np.arange(C, dtype=np.int32), sizes)
     rk = _rng(seed, cfg, "K_fixed", h)
@@ -136,19 +136,37 @@ def _queries(seed, cfg, tensor, h, n, centres):
 
 def make_workload(name: str, *, B: int, H: int, L: int, C: int, Lq: int, U: int,
                   keep_frac: float, d: int = 128, seed: int = 0, causal_user: bool = False,
-                  C1: int = 0, coarse_keep_frac: float = 0.0, threads: int = 8) -> Workload:
-    """Draw one workload.  `C1 > 0` makes the nested two-level mixture (C % C1 == 0)."""
+                  C1: int = 0, coarse_keep_frac: float = 0.0, threads: int = 8, head_skew: float = 0.0,
+                  variable_fanout: bool = False) -> Workload:
+    """Draw one workload.  `C1 > 0` makes the nested two-level mixture (C % C1 == 0).
+
+    `head_skew` > 0 (one-level only) makes the heads differ in how peaked their score distributions are, as the
+    heads of a model do (appendix "Attention Score Skewness"): head h draws its centres with standard deviation
+    1 + head_skew * (2 h / (H - 1) - 1), so low heads spread their estimated attention over many clusters and high
+    heads concentrate it on one.  Under ONE threshold for all heads (Section 3.2) the heads then keep very different
+    numbers of keys -- the imbalance the split-KV scheme of Section 4.2 exists for.
+
+    `variable_fanout` (two-level): every coarse cluster gets one fine cluster plus a multinomial share of the other
+    C - C1, so the fan-out varies from cluster to cluster and C need not be a multiple of C1 -- what clustering the
+    fine centroids produces (Section 3.3), e.g. the paper's sizing of fine centroids at 5 % and coarse centroids at
+    1 % or 0.5 % of the context length (Section 6, "Experimental Details")."""
     if C1:
-        assert C % C1 == 0
+        assert (variable_fanout or C % C1 == 0) and head_skew == 0.0 and C >= C1
     fan = C // C1 if C1 else 0
 
     def one_head(h):
         centres_fine = None
         if C1:
             coarse = _normal(_rng(seed, name, "coarse_centres", h), (C1, d))
-            centres_fine = (np.repeat(coarse, fan, axis=0)
+            if variable_fanout:
+                fans = 1 + _rng(seed, name, "fanout", h).multinomial(C - C1, np.full(C1, 1.0 / C1))
+            else:
+                fans = np.full(C1, fan)
+            co = np.concatenate([[0], np.cumsum(fans)]).astype(np.int32)
+            centres_fine = (np.repeat(coarse, fans, axis=0)
                             + COARSE_NOISE * _normal(_rng(seed, name, "centres", h), (C, d)))
-        centres, sizes, K, V, cent = _head_fixed(seed, name, h, L, C, d, centres_fine)
+        scale = 1.0 + head_skew * (2.0 * h / max(1, H - 1) - 1.0)
+        centres, sizes, K, V, cent = _head_fixed(seed, name, h, L, C, d, centres_fine, scale)
         qs = _queries(seed, name, "q", h, B * Lq, centres).reshape(B, Lq, d)
         qc = _queries(seed, name, "q_calib", h, N_CALIB, centres)
         ru = _rng(seed, name, "user", h)
@@ -158,9 +176,10 @@ def make_workload(name: str, *, B: int, H: int, L: int, C: int, Lq: int, U: int,
         if C1:
             # Level-1 centroid = unweighted mean of its child level-2 centroids (K-means run on
             # the level-2 centroids, Section 3.3); level-1 size = number of keys underneath.
-            c1 = cent.astype(np.float64).reshape(C1, fan, d).mean(axis=1).astype(F16)
+            c1 = (np.add.reduceat(cent.astype(np.float64), co[:-1], axis=0) / fans[:, None]).astype(F16)
             res["cent1"] = c1
-            res["sizes1"] = sizes.reshape(C1, fan).sum(axis=1).astype(np.int32)
+            res["sizes1"] = np.add.reduceat(sizes.astype(np.int64), co[:-1]).astype(np.int32)
+            res["co"] = co
         return res
 
     with ThreadPoolExecutor(max_workers=max(1, threads)) as ex:
@@ -185,7 +204,7 @@ def make_workload(name: str, *, B: int, H: int, L: int, C: int, Lq: int, U: int,
         w.coarse_keep_frac = coarse_keep_frac
         w.centroids1 = np.stack([r["cent1"] for r in heads])
         w.sizes1 = np.stack([r["sizes1"] for r in heads])
-        w.child_offsets = np.tile(np.arange(C1 + 1, dtype=np.int32) * fan, (H, 1))
+        w.child_offsets = np.stack([r["co"] for r in heads])
     return w
 
 
@@ -198,6 +217,17 @@ CONFIGS = {
                              causal_user=True),
     "cfg5_hier_decode_512k": dict(B=1, H=32, L=524288, C=16384, Lq=1, U=1024, keep_frac=1 / 16,
                                   C1=256, coarse_keep_frac=1 / 8),
+}
+
+# The paper's own sizing of the two-level hierarchy (Section 6 "Experimental Details"; appendix "Hierarchical kernel
+# benchmarking"): fine centroids at 5 % of the context length, coarse centroids at 1 % (or 0.5 %), the first level
+# pruning 50 % (or 90 %) of the coarse clusters, variable fan-out.  256K keys: 5 % of the 512K context of config 5
+# would be more fine clusters per head than the lookup kernels take (16384).
+HIER_SIZING_CONFIGS = {
+    "f3_hier_1pct_prune50_256k": dict(B=1, H=32, L=262144, C=13107, Lq=1, U=1024, keep_frac=1 / 10, C1=2621,
+                                      coarse_keep_frac=0.5, variable_fanout=True),
+    "f3_hier_05pct_prune90_256k": dict(B=1, H=32, L=262144, C=13107, Lq=1, U=1024, keep_frac=1 / 10, C1=1310,
+                                       coarse_keep_frac=0.1, variable_fanout=True),
 }
 
 # Grouped-query decode at a Llama-3.1-8B attention shape (32 query heads over 8 K/V heads, 32K fixed context): not
@@ -215,7 +245,8 @@ KMEANS_CONFIGS = {
 
 
 def make_config(name: str, seed: int = 0, threads: int = 8, **override) -> Workload:
-    kw = dict(CONFIGS[name] if name in CONFIGS else GQA_CONFIGS[name])
+    kw = dict(CONFIGS[name] if name in CONFIGS else HIER_SIZING_CONFIGS[name] if name in HIER_SIZING_CONFIGS
+              else GQA_CONFIGS[name])
     kw.update(override)
     return make_workload(name, seed=seed, threads=threads, **kw)
 
@@ -272,8 +303,12 @@ def _cut(scores: np.ndarray, weights: np.ndarray, target: float) -> float:
     return float(math.sqrt(float(s[k]) * float(max(lo, 1e-300))))
 
 
-def calibrate(w: Workload, score_fn: ScoreFn) -> Workload:
+def calibrate(w: Workload, score_fn: ScoreFn, global_threshold: bool = False) -> Workload:
     """Per-head thresholds from the calibration queries, to hit the configured key fraction.
+
+    `global_threshold` (one-level): ONE threshold for all heads, as in Section 3.2 / Appendix C -- the (S_i, N_i) of
+    every head's calibration queries are pooled and the cut keeps keep_frac of all pooled keys; every head gets that
+    value, and heads whose scores are flatter keep more keys than heads whose scores are peaked.
 
     One-level: pool (S_i, N_i) over the calibration queries, keep the highest scores until
     keep_frac of the pooled keys is covered.  Two-level: T1 keeps coarse_keep_frac of the coarse
@@ -283,10 +318,17 @@ def calibrate(w: Workload, score_fn: ScoreFn) -> Workload:
     H = w.H
     if not w.C1:
         T = np.empty(H, dtype=np.float32)
+        pooled_s, pooled_w = [], []
         for h in range(H):
             S = np.asarray(score_fn(w.q_calib[h], w.centroids[h], w.sizes[h], w.sm_scale), dtype=np.float64)
             wts = np.broadcast_to(w.sizes[h], S.shape)
-            T[h] = _cut(S.ravel(), wts.ravel(), w.keep_frac * N_CALIB * w.L)
+            if global_threshold:
+                pooled_s.append(S.ravel())
+                pooled_w.append(wts.ravel())
+            else:
+                T[h] = _cut(S.ravel(), wts.ravel(), w.keep_frac * N_CALIB * w.L)
+        if global_threshold:
+            T[:] = _cut(np.concatenate(pooled_s), np.concatenate(pooled_w), w.keep_frac * N_CALIB * w.L * H)
         w.thresh = T
         return w
     T1 = np.empty(H, dtype=np.float32)

@@ -109,6 +109,23 @@ def test_cfg2_llama7b_decode_32k(sq, oracle):
     step_against_oracle(sq, oracle, w, "cfg2 sq_decode_step")
 
 
+def test_cfg2_shape_single_global_threshold(sq, oracle):
+    """Config 2's shape with heads of different score skewness under ONE threshold for all heads (Section 3.2,
+    appendix "Attention Score Skewness"): the heads keep very different numbers of keys, which is the case the equal
+    split of the kept keys over the compute units (Section 4.2) exists for.  Whole step against the oracle."""
+    w = wl.calibrate(wl.make_config("cfg2_decode_32k", head_skew=0.4), oracle.scores, global_threshold=True)
+    assert np.ptp(w.thresh) == 0
+    step_against_oracle(sq, oracle, w, "cfg2 shape, one global threshold")
+    P = sq.upload(w)
+    ws = sq.workspace(P.shape, sq.SQ_CALL_DECODE_STEP, P.q.device)
+    sq.sq_decode_step(P.shape, P.q, P.centroids, P.sizes, P.offsets, P.thresh, P.K_fixed, P.V_fixed, P.K_user,
+                      P.V_user, P.out, P.lse, P.keep_mask, P.n_keys, ws)
+    torch.cuda.synchronize()
+    frac = P.n_keys.cpu().numpy().ravel() / w.L
+    print("global threshold: keep fraction per head", np.round(frac, 3), "overall", round(float(frac.mean()), 4), flush=True)
+    assert frac.max() > 5 * max(frac.min(), 1e-4)          # the heads do differ
+
+
 def test_cfg3_batched_decode_shared_context(sq, oracle):
     print("cfg3: generating", flush=True)
     w = wl.calibrate(wl.make_config("cfg3_batched_decode_32k"), oracle.scores)

@@ -146,3 +146,21 @@ def test_cfg5_hier_decode_512k(sq, oracle):
     P = hier_decode_and_compare(sq, oracle, w, "cfg5")
     nk = P.n_keys.cpu().numpy().ravel()
     print("cfg5 keep fraction per head:", np.round(nk / w.L, 4), "mean", nk.mean() / w.L, flush=True)
+
+
+@pytest.mark.parametrize("name", ["f3_hier_1pct_prune50_256k", "f3_hier_05pct_prune90_256k"])
+def test_paper_hierarchy_sizing_256k(sq, oracle, name):
+    """The paper's own sizing of the hierarchy (Section 6 "Experimental Details"; appendix "Hierarchical kernel
+    benchmarking"): fine centroids at 5 % of the context, coarse centroids at 1 % / 0.5 %, the first level pruning
+    50 % / 90 % of the coarse clusters, variable fan-out; 32 heads x 256K keys through sq_hier_decode_step."""
+    print(f"{name}: generating", flush=True)
+    w = wl.make_config(name, threads=16)
+    print(f"{name}: calibrating", flush=True)
+    wl.calibrate(w, oracle.scores)
+    fans = np.diff(w.child_offsets, axis=1)
+    assert fans.min() >= 1 and fans.max() > fans.min()          # the fan-out does vary
+    print(f"{name}: running", flush=True)
+    P = hier_decode_and_compare(sq, oracle, w, name)
+    nk = P.n_keys.cpu().numpy().ravel()
+    print(f"{name}: keep fraction mean {nk.mean() / w.L:.4f} (per head {np.round(nk / w.L, 3).tolist()})", flush=True)
+    assert nk.sum() > 0
