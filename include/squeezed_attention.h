@@ -257,7 +257,8 @@ int sq_decode_step_noalloc(const sq_shape_t *shape, const void *q,
  * handled like B * G sequences over a shared context: from B * G = 8 on, the union of the selections of every group
  * of 16 of them is streamed once, so a key kept by several query heads leaves HBM once; below that every pair is a
  * row of the per-sequence kernels, which read the K/V head once per query head (same kernels, arithmetic and
- * rounding as sq_decode_step; G = 1 is that call).  G must be 1, 2, 4, 8 or 16.
+ * rounding as sq_decode_step; G = 1 is that call).  1 <= G <= 16; a group size that does not divide 16 (3 or 6 query
+ * heads per K/V head) takes the per-sequence kernels at any batch size.
  * In:  q f16 [B, H*G, 1, d]; centroids, sizes, offsets, thresh, K_fixed, V_fixed per K/V head as everywhere;
  *      K_user, V_user f16 [B, H, U, d].
  * Out: out f16 [B, H*G, 1, d]; optional (NULL to skip): lse f32 [B, H*G, 1], keep_mask u32 [B, H*G, 1, ceil(C/32)],

@@ -650,8 +650,8 @@ int sq_gqa_decode_step(const sq_shape_t *sh, int32_t G, const void *q, const voi
                        int32_t *n_keys, void *ws, size_t ws_bytes, void *stream)
 {
     if (int rc = check_shape(sh, __func__, true)) return rc;
-    if (G != 1 && G != 2 && G != 4 && G != 8 && G != 16)
-        return fail(SQ_ERR_UNSUPPORTED, "%s: G = %d query heads per K/V head; supported: 1, 2, 4, 8, 16", __func__, G);
+    if (G < 1 || G > sq::SG)
+        return fail(SQ_ERR_UNSUPPORTED, "%s: G = %d query heads per K/V head; supported: 1 .. %d", __func__, G, sq::SG);
     SQ_REQUIRE_PTR(q);
     SQ_REQUIRE_PTR(centroids);
     SQ_REQUIRE_PTR(sizes);
@@ -671,7 +671,9 @@ int sq_gqa_decode_step(const sq_shape_t *sh, int32_t G, const void *q, const voi
     if (int rc = check_device(__func__)) return rc;
     Carver cv(ws);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (step_is_shared(sh, G)) {
+    // The shared-context kernels handle groups of 16 query rows and need the G rows of a sequence inside one group:
+    // group sizes that do not divide 16 (3 or 6 query heads per K/V head) take the per-row kernels at any batch.
+    if (step_is_shared(sh, G) && sq::SG % G == 0) {
         if (int rc = decode_step_shared(sh, G, q, centroids, sizes, offsets, thresh, K_fixed, V_fixed, K_user, V_user, out,
                                         lse, keep_mask, n_keys, cv, s))
             return rc;

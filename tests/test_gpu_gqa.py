@@ -74,6 +74,9 @@ def against_oracle(sq, w, G, label, thresh=None):
     dict(G=4, B=5, H=1, L=1500, C=65, U=40, keep_frac=0.25),       # 20 (sequence, head) pairs: two groups, the second partial
     dict(G=16, B=2, H=2, L=1200, C=40, U=130, keep_frac=0.4),      # a whole group per sequence; a second user chunk
     dict(G=2, B=2, H=1, L=4096, C=2048, U=17, keep_frac=0.2),      # more clusters than one selection step holds
+    dict(G=3, B=1, H=4, L=3000, C=100, U=70, keep_frac=0.3),       # 12 query heads over 4 K/V heads (does not divide 16)
+    dict(G=3, B=3, H=2, L=2000, C=64, U=0, keep_frac=0.4),         # 9 query rows per K/V head: still the per-row kernels
+    dict(G=6, B=2, H=2, L=2500, C=80, U=140, keep_frac=0.25),      # 6 query heads per K/V head, two sequences
 ])
 def test_gqa_step_against_oracle(sq, case):
     case = dict(case)
@@ -112,10 +115,10 @@ def test_group_of_one_is_sq_decode_step(sq):
 
 
 def test_unsupported_group_size_is_an_error(sq):
-    w = wl.make_workload("gqa_bad", B=1, H=1, L=256, C=8, Lq=3, U=0, keep_frac=0.5, seed=44, threads=1)
+    w = wl.make_workload("gqa_bad", B=1, H=1, L=256, C=8, Lq=17, U=0, keep_frac=0.5, seed=44, threads=1)
     w.thresh = np.full(w.H, 0.5, np.float32)
     with pytest.raises(sq.SqError) as e:
-        run_gqa(sq, w, 3)
+        run_gqa(sq, w, 17)                                   # more than 16 query heads per K/V head
     assert e.value.code == sq.SQ_ERR_UNSUPPORTED
 
 
