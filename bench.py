@@ -369,9 +369,8 @@ def bench_hier(args, torch, sq, wl, dev):
     coarse = w.H * w.C1 * w.d * 2
     dense = w.H * w.U * w.d * 4
     tot = sel + cand + coarse + dense
-    # (the user keys are attended to by extra workgroups of the level-1 selection launch: the partial kernel reads the
-    # selected keys only)
-    kernel_bytes = sel + w.H * w.d * 2
+    # (the user keys are attended to by extra workgroups of the partial kernel's launch)
+    kernel_bytes = sel + dense + w.H * w.d * 2
     res = base_result(args, f"hierarchical decode attn µs/token + achieved HBM GB/s, {w.L // 1024}K fixed ctx, "
                       f"keep {w.keep_frac:.4g}",
                       round(tot / (ms * 1e-3) / 1e9, 2), "GB/s", ms, eager_ms, graph_ms, 1)
@@ -383,12 +382,11 @@ def bench_hier(args, torch, sq, wl, dev):
     res["bytes_per_step"] = {"total": round(tot), "coarse_centroids": coarse, "candidate_fine_centroids": round(cand),
                              "selected_kv": round(sel), "dense_kv": dense}
     res["hbm_frac_whole_step"] = round(tot / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)
-    res["roofline"] = {"bound": "hbm", "kernel": "decode_attn_kernel",
+    res["roofline"] = {"bound": "hbm", "kernel": "decode_attn_index_kernel",
                        "achieved": round(kernel_bytes / (k_avg * 1e-6) / 1e9, 2) if n_meas else None,
                        "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                        "frac": round(kernel_bytes / (k_avg * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4) if n_meas else None,
-                       **read_traffic(("decode_attn_shared_kernel" if w.B > 1 and not args.separate
-                                              else "decode_attn_kernel") + f"_{args.workload}_pmc.txt"),
+                       **read_traffic(f"decode_attn_index_kernel_{args.workload}_pmc.txt"),
                        "bytes_per_launch": round(kernel_bytes), "avg_us": round(k_avg, 3), "min_us": round(k_min, 3),
                        "launches": n_meas}
     res["roofline"].update(stream_ceiling(sq, torch, dev, kernel_bytes))

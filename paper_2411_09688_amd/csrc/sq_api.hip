@@ -250,6 +250,7 @@ struct HierWs {
     int32_t *cand_id;
     int32_t *nr1, *nk1;
     float2 *cand_stats;       // per candidate work item: (max, sum N exp(x - max)) of its candidates
+    int2 *slice_cnt;          // last level: kept (clusters, keys) per slice of candidates (see launch_cand_select)
     sq::DecodePlan cand;      // work items of candidate fine clusters (chunks of KPC clusters)
 };
 
@@ -264,6 +265,7 @@ HierWs carve_hier(Carver &cv, const sq_shape_t *sh)
     w.nr1 = cv.take<int32_t>(rows);
     w.nk1 = cv.take<int32_t>(rows);
     w.cand_stats = cv.take<float2>(items);
+    w.slice_cnt = cv.take<int2>(rows * sq::cand_slices_for(sh->C));
     w.cand.rec_cap = sh->C;
     w.cand.L = sh->C;
     w.cand.item_cap = (int)items;
@@ -309,12 +311,21 @@ KmeansWs carve_kmeans(Carver &cv, const sq_shape_t *sh)
     return w;
 }
 
+// Workspace of a hierarchical decode step.  Calls of up to KI_MAX_ROWS query rows and at least two levels attend
+// through a key-index list (`indexed`: plan, partials, user slots as in IndexStepWs); others through the work-list
+// kernels (dec).
 struct HierStepWs {
     HierWs hier;
     uint32_t *mask1;
     int32_t *n_ranges, *n_keys;
+    bool indexed;
     DecodeWs dec;
+    sq::KeyIndexPlan plan;
+    float *partials;
+    int user_slot_base, nuq;
 };
+
+bool hier_step_is_indexed(const sq_shape_t *sh) { return (long long)sh->B * sh->H <= sq::KI_MAX_ROWS; }
 
 HierStepWs carve_hier_step(Carver &cv, const sq_shape_t *sh)
 {
@@ -324,8 +335,36 @@ HierStepWs carve_hier_step(Carver &cv, const sq_shape_t *sh)
     w.mask1 = cv.take<uint32_t>(rows * ((sh->C + 31) / 32));
     w.n_ranges = cv.take<int32_t>(rows);
     w.n_keys = cv.take<int32_t>(rows);
-    w.dec = carve_decode(cv, sh);
+    w.indexed = hier_step_is_indexed(sh);
+    if (w.indexed) {
+        w.nuq = sq::user_pieces_for(sh->U);
+        w.user_slot_base = sq::KI_ATTN_GRID + (int)rows;
+        w.plan.L = sh->L;
+        w.plan.row_keys = cv.take<int32_t>(rows);
+        w.plan.key_idx = cv.take<int32_t>(rows * sh->L);
+        w.partials = cv.take<float>(sq::keyidx_partial_slots((int)rows, w.nuq) * sq::PART_STRIDE);
+    }
+    w.dec = carve_decode(cv, sh);                      // (also a one-level "hierarchy" of an indexed call)
     return w;
+}
+
+// The dense attention over the user keys as extra workgroups of the key-index partial kernel.
+sq::UserAttn make_user_pieces(const sq_shape_t *sh, int G, const void *q, const void *K_user, const void *V_user,
+                              float *partials, int user_slot_base, int nuq)
+{
+    sq::UserAttn ua{};
+    if (sh->U <= 0) return ua;
+    ua.q = static_cast<const _Float16 *>(q);
+    ua.Ku = static_cast<const _Float16 *>(K_user);
+    ua.Vu = static_cast<const _Float16 *>(V_user);
+    ua.partials = partials;
+    ua.rows = sh->B * sh->H * G;
+    ua.U = sh->U;
+    ua.G = G;
+    ua.nuq = nuq;
+    ua.slot_base = user_slot_base;
+    ua.sm_scale = sh->sm_scale;
+    return ua;
 }
 
 // Workspace of the shared-set prefill attention: records of the kept ranges and the list of kept key rows.
@@ -622,19 +661,7 @@ int decode_step_indexed(const sq_shape_t *sh, int G, const void *q, const void *
 {
     IndexStepWs w = carve_step_index(cv, sh, G);
     const int rows = sh->B * sh->H * G;
-    sq::UserAttn ua{};
-    if (sh->U > 0) {
-        ua.q = static_cast<const _Float16 *>(q);
-        ua.Ku = static_cast<const _Float16 *>(K_user);
-        ua.Vu = static_cast<const _Float16 *>(V_user);
-        ua.partials = w.partials;
-        ua.rows = rows;
-        ua.U = sh->U;
-        ua.G = G;
-        ua.nuq = w.nuq;
-        ua.slot_base = w.user_slot_base;
-        ua.sm_scale = sh->sm_scale;
-    }
+    const sq::UserAttn ua = make_user_pieces(sh, G, q, K_user, V_user, w.partials, w.user_slot_base, w.nuq);
     SQ_HIP(sq::launch_score(q, centroids, w.logits, nullptr, sh->B, sh->H, G, sh->C, sh->sm_scale, s));
     SQ_HIP(sq::launch_select_index(w.logits, thresh, sizes, offsets, keep_mask, w.n_ranges, n_keys ? n_keys : w.n_keys,
                                    w.plan, rows, sh->H, G, sh->C, s));
@@ -969,10 +996,12 @@ struct Level {
 // (logits in candidate order) and selects over that list, so its maximum and normaliser run over the candidates
 // only.  The candidate work lists of consecutive levels alternate between w.cand and cand_b (a level reads one
 // while it fills the other).  The last level writes ranges / counts and, when `schedule_last`, the attention
-// work items into plan_last.
+// work items into plan_last.  klast (n >= 2): the last level is selected in slices of its candidates, many workgroups
+// per row (launch_cand_select), and leaves the rows' key-index lists in *klast (if it has any) instead of work items.
 int multilevel_lookup(const char *fn, const sq_shape_t *sh, int n, const Level *lv, const void *q, int32_t *ranges,
                       int32_t *n_ranges, int32_t *n_keys, HierWs &w, sq::DecodePlan cand_b, sq::DecodePlan plan_last,
-                      bool schedule_last, hipStream_t s, const sq::UserAttn *user = nullptr)
+                      bool schedule_last, hipStream_t s, const sq::UserAttn *user = nullptr,
+                      const sq::KeyIndexPlan *klast = nullptr)
 {
     // `user` (decode steps): the rows' user-key attention rides on the level-0 selection launch (see
     // make_user_rider), and the attention work list of the last level then holds no user chunks.
@@ -1002,9 +1031,18 @@ int multilevel_lookup(const char *fn, const sq_shape_t *sh, int n, const Level *
         const bool last = k == n - 1;
         sq::DecodePlan dst = last ? plan_last : nxt;
         // (the records of `cur` were consumed when its work items were written: the array now takes the candidates')
+        const bool sliced = last && klast;
         e = sq::launch_gather_score(q, lv[k].centroids, cur, lv[k].sizes, lv[k].child_offsets, last ? 0 : 1, w.logits2,
-                                    w.cand_id, cur.rec, w.cand_stats, dst.total, sh->H, lv[k].C, sh->sm_scale, s);
+                                    w.cand_id, cur.rec, w.cand_stats, sliced ? nullptr : dst.total, sh->H, lv[k].C,
+                                    sh->sm_scale, s, sliced ? lv[k].mask : nullptr,
+                                    (size_t)rows * ((lv[k].C + 31) / 32));
         if (e != hipSuccess) break;
+        if (sliced) {
+            const sq::CandSelect cs{cur.rec, cur.hdr, w.cand_stats, cur.row_items, w.slice_cnt};
+            e = sq::launch_cand_select(cs, lv[k].thresh, lv[k].mask, ranges, n_ranges, n_keys, *klast, rows, sh->H,
+                                       lv[k].C, s);
+            break;
+        }
         sq::SelectOpts o{};
         o.cand_id = w.cand_id;
         o.cand_hdr = cur.hdr;
@@ -1032,11 +1070,13 @@ int hier_lookup(const char *fn, const sq_shape_t *sh, int32_t C1, const void *q,
                 const int32_t *sizes1, const int32_t *child_offsets, const float *thresh1, const void *centroids2,
                 const int32_t *sizes2, const int32_t *offsets2, const float *thresh2, uint32_t *keep_mask1,
                 uint32_t *keep_mask2, int32_t *ranges, int32_t *n_ranges, int32_t *n_keys, HierWs &w,
-                sq::DecodePlan plan2, bool schedule2, hipStream_t s, const sq::UserAttn *user = nullptr)
+                sq::DecodePlan plan2, bool schedule2, hipStream_t s, const sq::UserAttn *user = nullptr,
+                const sq::KeyIndexPlan *klast = nullptr)
 {
     const Level lv[2] = {{C1, centroids1, sizes1, child_offsets, thresh1, keep_mask1},
                          {sh->C, centroids2, sizes2, offsets2, thresh2, keep_mask2}};
-    return multilevel_lookup(fn, sh, 2, lv, q, ranges, n_ranges, n_keys, w, sq::DecodePlan{}, plan2, schedule2, s, user);
+    return multilevel_lookup(fn, sh, 2, lv, q, ranges, n_ranges, n_keys, w, sq::DecodePlan{}, plan2, schedule2, s, user,
+                             klast);
 }
 
 // Validates a caller's level array and copies it (masks: optional host array of per-level outputs).
@@ -1094,9 +1134,10 @@ int sq_hier_select(const sq_shape_t *sh, int32_t C1, const void *q, const void *
     if (int rc = check_device(__func__)) return rc;
     Carver cv(ws);
     HierWs w = carve_hier(cv, sh);
+    const sq::KeyIndexPlan none{};                     // selection alone: ranges and counts, no key-index list
     if (int rc = hier_lookup(__func__, sh, C1, q, centroids1, sizes1, child_offsets, thresh1, centroids2, sizes2,
                              offsets2, thresh2, keep_mask1, keep_mask2, ranges, n_ranges, n_keys, w, sq::DecodePlan{},
-                             false, static_cast<hipStream_t>(stream)))
+                             false, static_cast<hipStream_t>(stream), nullptr, &none))
         return rc;
     g_err[0] = 0;
     return SQ_OK;
@@ -1134,6 +1175,17 @@ int sq_hier_decode_step(const sq_shape_t *sh, int32_t C1, const void *q, const v
     hipStream_t s = static_cast<hipStream_t>(stream);
     Carver cv(ws);
     HierStepWs w = carve_hier_step(cv, sh);
+    if (w.indexed) {
+        if (int rc = hier_lookup(__func__, sh, C1, q, centroids1, sizes1, child_offsets, thresh1, centroids2, sizes2,
+                                 offsets2, thresh2, w.mask1, keep_mask2, nullptr, w.n_ranges, n_keys ? n_keys : w.n_keys,
+                                 w.hier, sq::DecodePlan{}, false, s, nullptr, &w.plan))
+            return rc;
+        const sq::UserAttn ua = make_user_pieces(sh, 1, q, K_user, V_user, w.partials, w.user_slot_base, w.nuq);
+        SQ_HIP(sq::launch_decode_attn_index(q, K_fixed, V_fixed, w.plan, w.partials, out, lse, sh->B * sh->H, sh->H, 1,
+                                            sh->sm_scale, &ua, s));
+        g_err[0] = 0;
+        return SQ_OK;
+    }
     const sq::UserAttn ua = make_user_rider(sh, 1, q, K_user, V_user, w.dec);
     if (int rc = hier_lookup(__func__, sh, C1, q, centroids1, sizes1, child_offsets, thresh1, centroids2, sizes2,
                              offsets2, thresh2, w.mask1, keep_mask2, nullptr, w.n_ranges, n_keys ? n_keys : w.n_keys,
@@ -1271,8 +1323,9 @@ int sq_multilevel_select(const sq_shape_t *sh, int32_t n_levels, const sq_level_
     Carver cv(ws);
     HierWs w = carve_hier(cv, sh);
     sq::DecodePlan cand_b = carve_cand_plan(cv, sh);
+    const sq::KeyIndexPlan none{};                     // selection alone: ranges and counts, no key-index list
     if (int rc = multilevel_lookup(__func__, sh, n_levels, lv, q, ranges, n_ranges, n_keys, w, cand_b, sq::DecodePlan{},
-                                   false, static_cast<hipStream_t>(stream)))
+                                   false, static_cast<hipStream_t>(stream), nullptr, &none))
         return rc;
     g_err[0] = 0;
     return SQ_OK;
@@ -1304,6 +1357,16 @@ int sq_multilevel_decode_step(const sq_shape_t *sh, int32_t n_levels, const sq_l
     HierStepWs w = carve_hier_step(cv, sh);
     sq::DecodePlan cand_b = carve_cand_plan(cv, sh);
     lv[n_levels - 1].mask = keep_mask;
+    if (w.indexed && n_levels >= 2) {
+        if (int rc = multilevel_lookup(__func__, sh, n_levels, lv, q, nullptr, w.n_ranges, n_keys ? n_keys : w.n_keys,
+                                       w.hier, cand_b, sq::DecodePlan{}, false, s, nullptr, &w.plan))
+            return rc;
+        const sq::UserAttn ua = make_user_pieces(sh, 1, q, K_user, V_user, w.partials, w.user_slot_base, w.nuq);
+        SQ_HIP(sq::launch_decode_attn_index(q, K_fixed, V_fixed, w.plan, w.partials, out, lse, sh->B * sh->H, sh->H, 1,
+                                            sh->sm_scale, &ua, s));
+        g_err[0] = 0;
+        return SQ_OK;
+    }
     const sq::UserAttn ua = make_user_rider(sh, 1, q, K_user, V_user, w.dec);
     if (int rc = multilevel_lookup(__func__, sh, n_levels, lv, q, nullptr, w.n_ranges, n_keys ? n_keys : w.n_keys, w.hier,
                                    cand_b, w.dec.plan, true, s, &ua))

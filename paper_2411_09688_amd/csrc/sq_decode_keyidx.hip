@@ -23,6 +23,8 @@
 //   decode_merge_index_kernel  phase 2 of Section 4.2: the partial results of a row, found from the same key counts.
 //
 // No counters, no atomics, nothing to clear between steps: every buffer is written before it is read.
+#include <algorithm>
+
 #include "sq_common.hpp"
 #include "sq_internal.hpp"
 #include "sq_merge.hpp"
@@ -482,6 +484,196 @@ __global__ __launch_bounds__(MERGE_THREADS) void decode_merge_index_kernel(const
     };
     merge_row<false>(slot_ptr, n, out + (size_t)row * D, lse ? lse + row : nullptr, s_red, tid);
 }
+
+// Last level of a hierarchical lookup (Section 3.3, Eq. 3) into the same outputs.  The row's entries are its candidate
+// clusters in candidate order, each with a 16-byte record (logit, id | bit 31 if it has no keys, first key, keys), and the
+// statistics (max, sum N exp(x - max)) of every work item that scored them (see launch_gather_score).  A row can list
+// up to C candidates, so one workgroup takes a slice of CAND_SLICE of them: a quarter of its threads hold a candidate
+// each, all of them write the key-index entries (a half-wave per kept cluster; one half-wave needs about 0.2 us per
+// cluster it writes, measured, so a slice that keeps everything has 8 clusters per half-wave); the row's maximum and
+// normaliser are merged from the items' pairs by every workgroup (item v by thread v; wave sums ascending):
+// bit-identical whichever slice asks.  Two launches: the first counts the kept clusters and keys of every slice and
+// sets the mask bits (by cluster id, into a mask the scoring launch zeroed); the second, knowing the counts of the
+// slices in front of its own, writes the ranges, the key rows into the row's key-index list and (slice 0) the row's
+// counts.
+constexpr int CAND_THREADS = 1024;                               // = items of a row, at most
+constexpr int CAND_SLICE = 256;
+constexpr int CAND_WAVES = CAND_SLICE / 64;                      // waves that hold candidates
+constexpr int CAND_ITEM_WAVES = CAND_THREADS / 64;
+static_assert(CAND_SLICE == 256, "cand_slices_for counts slices of 256 candidates");
+
+template <bool EMIT>
+struct CandLds {
+    float red[CAND_ITEM_WAVES];
+    int cnt[CAND_WAVES + 1], keys[CAND_WAVES + 1], base[2];
+    int wsum[CAND_ITEM_WAVES], unit[3];
+    int4 rec[EMIT ? CAND_SLICE : 1];
+};
+
+// Slice `sl` of row `row` (n candidates), by the whole workgroup.  Leaves the LDS free for the next slice.
+template <bool EMIT>
+__device__ __forceinline__ void cand_select_slice(const CandSelect &cs, const float *__restrict__ thresh,
+                                                  uint32_t *__restrict__ keep_mask, int32_t *__restrict__ ranges,
+                                                  int32_t *__restrict__ n_ranges, int32_t *__restrict__ n_keys,
+                                                  const KeyIndexPlan &plan, int H, int C, int nsl, int row, int sl, int n,
+                                                  CandLds<EMIT> &S)
+{
+    float (&s_red)[CAND_ITEM_WAVES] = S.red;
+    int (&s_cnt)[CAND_WAVES + 1] = S.cnt, (&s_keys)[CAND_WAVES + 1] = S.keys, (&s_base)[2] = S.base;
+    int4 (&s_rec)[EMIT ? CAND_SLICE : 1] = S.rec;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int j = sl * CAND_SLICE + tid;
+    const int4 rv = tid < CAND_SLICE && j < n ? cs.rec[(size_t)row * C + j] : make_int4(0, (int)0x80000000u, 0, 0);
+    const int2 ri = n > 0 ? cs.row_items[row] : make_int2(0, 0);   // (first item, items): at most CAND_THREADS items
+    const float2 ms = tid < ri.y ? cs.stats[ri.x + tid] : make_float2(SQ_NEG_INF, 0.0f);
+    const int n_sl = (n + CAND_SLICE - 1) / CAND_SLICE;         // slices with candidates: at most 64
+    int2 sc = make_int2(0, 0);
+    if (EMIT && tid < n_sl) sc = cs.slice_cnt[(size_t)row * nsl + tid];
+    const float T = thresh[row % H];
+
+    const float mw = wave_max(ms.x);
+    if (lane == 0) s_red[wave] = mw;
+    __syncthreads();
+    float m = s_red[0];
+#pragma unroll
+    for (int w = 1; w < CAND_ITEM_WAVES; ++w) m = fmaxf(m, s_red[w]);
+    __syncthreads();                                            // s_red is reused
+    const float part = ms.y > 0.0f ? __fmul_rn(ms.y, expf(ms.x - m)) : 0.0f;
+    const float pw = wave_sum(part);
+    if (lane == 0) s_red[wave] = pw;
+    __syncthreads();
+    float Dsum = 0.0f;                                          // the 16 wave sums in ascending order, by every thread
+#pragma unroll
+    for (int w = 0; w < CAND_ITEM_WAVES; ++w) Dsum += s_red[w];
+    const bool keep = tid < CAND_SLICE && j < n && rv.y >= 0 && expf(__int_as_float(rv.x) - m) > T * Dsum;
+
+    const unsigned long long bal = __ballot(keep);
+    const int kv = keep ? rv.w : 0;
+    const int incl = wave_inclusive_scan(kv, lane);
+    if (lane == 63 && wave < CAND_WAVES) {
+        s_cnt[wave] = __popcll(bal);
+        s_keys[wave] = incl;
+    }
+    if (!EMIT && keep_mask && wave < CAND_WAVES)
+        wave_mask_or(keep_mask + (size_t)row * ((C + 31) >> 5), rv.y & 0x7fffffff, keep, lane);
+    __syncthreads();
+    if (!EMIT) {
+        if (tid == 0) {
+            int r = 0, k = 0;
+#pragma unroll
+            for (int w = 0; w < CAND_WAVES; ++w) {
+                r += s_cnt[w];
+                k += s_keys[w];
+            }
+            cs.slice_cnt[(size_t)row * nsl + sl] = make_int2(r, k);
+        }
+        __syncthreads();                                        // (the LDS is free for the next slice)
+        return;
+    }
+    if (wave == 0) {
+        // exclusive prefix of the per-wave counts; records and keys of the slices in front; the row's totals
+        const int c = lane < CAND_WAVES ? s_cnt[lane] : 0, kk = lane < CAND_WAVES ? s_keys[lane] : 0;
+        const int ci = wave_inclusive_scan(c, lane), ki = wave_inclusive_scan(kk, lane);
+        const int before_r = wave_sum_i(lane < sl ? sc.x : 0), before_k = wave_sum_i(lane < sl ? sc.y : 0);
+        const int tot_r = wave_sum_i(sc.x), tot_k = wave_sum_i(sc.y);
+        if (lane < CAND_WAVES) {
+            s_cnt[lane] = ci - c;
+            s_keys[lane] = ki - kk;
+        }
+        if (lane == 63) {
+            s_cnt[CAND_WAVES] = ci;
+            s_base[0] = before_r;
+            s_base[1] = before_k;
+            if (sl == 0) {
+                n_ranges[row] = tot_r;
+                n_keys[row] = tot_k;
+                if (plan.row_keys) plan.row_keys[row] = min(tot_k, plan.L);
+            }
+        }
+    }
+    __syncthreads();
+    if (keep) {
+        const int rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0));
+        const int r = s_cnt[wave] + rank;
+        if (ranges) *reinterpret_cast<int2 *>(ranges + ((size_t)row * C + s_base[0] + r) * 2) = make_int2(rv.z, rv.w);
+        s_rec[r] = make_int4(rv.z, kv, s_base[1] + s_keys[wave] + incl - kv, 0);
+    }
+    __syncthreads();
+    if (!plan.key_idx) return;                                  // (selection alone: no list)
+    // Key-index list: half-wave g writes the key rows of kept clusters g, g + 32, ... of the slice.
+    const int n_slice = s_cnt[CAND_WAVES];
+    int32_t *idx_row = plan.key_idx + (size_t)row * plan.L;
+    for (int c = tid >> 5; c < n_slice; c += CAND_THREADS / 32) {
+        const int4 rc = s_rec[c];
+        for (int t = tid & 31; t < rc.y && rc.z + t < plan.L; t += 32)
+            idx_row[rc.z + t] = max(0, min(rc.x + t, plan.L - 1));   // malformed offsets stay in the tensor
+    }
+    __syncthreads();                                            // (the LDS is free for the next slice)
+}
+
+// Workgroups -> slices.  compact (rows <= CAND_THREADS): a fixed grid; every workgroup reads all rows' candidate
+// counts and takes the non-empty slices u = workgroup, workgroup + grid, ... of the rows laid end to end (a row
+// without candidates counts as one slice: its counts are still written), so no workgroup is launched only to find
+// that its slice is empty.  Otherwise one workgroup per (row, slice).
+template <bool EMIT>
+__global__ __launch_bounds__(CAND_THREADS) void cand_select_kernel(CandSelect cs, const float *__restrict__ thresh,
+                                                                   uint32_t *__restrict__ keep_mask,
+                                                                   int32_t *__restrict__ ranges,
+                                                                   int32_t *__restrict__ n_ranges,
+                                                                   int32_t *__restrict__ n_keys, KeyIndexPlan plan,
+                                                                   int rows, int H, int C, int nsl, int compact)
+{
+    __shared__ CandLds<EMIT> S;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (!compact) {
+        const int row = blockIdx.x / nsl, sl = blockIdx.x - row * nsl;
+        const int n = min(cs.hdr[row].y, C);
+        if (sl * CAND_SLICE >= n && sl != 0) return;            // workgroup-uniform (slice 0 still writes the counts)
+        cand_select_slice<EMIT>(cs, thresh, keep_mask, ranges, n_ranges, n_keys, plan, H, C, nsl, row, sl, n, S);
+        return;
+    }
+    const int n_t = tid < rows ? min(cs.hdr[tid].y, C) : 0;
+    const int cnt = tid < rows ? max(1, (n_t + CAND_SLICE - 1) / CAND_SLICE) : 0;
+    const int incl = wave_inclusive_scan(cnt, lane);
+    if (lane == 63) S.wsum[wave] = incl;
+    __syncthreads();
+    int start = incl - cnt, total = 0;
+#pragma unroll
+    for (int w = 0; w < CAND_ITEM_WAVES; ++w) {
+        const int ws = S.wsum[w];
+        if (w < wave) start += ws;
+        total += ws;
+    }
+    for (int u = blockIdx.x; u < total; u += gridDim.x) {       // workgroup-uniform
+        if (u >= start && u < start + cnt) {
+            S.unit[0] = tid;
+            S.unit[1] = u - start;
+            S.unit[2] = n_t;
+        }
+        __syncthreads();
+        const int row = S.unit[0], sl = S.unit[1], n = S.unit[2];
+        cand_select_slice<EMIT>(cs, thresh, keep_mask, ranges, n_ranges, n_keys, plan, H, C, nsl, row, sl, n, S);
+    }
+}
+
+hipError_t launch_cand_select(CandSelect cs, const float *thresh, uint32_t *keep_mask, int32_t *ranges,
+                              int32_t *n_ranges, int32_t *n_keys, KeyIndexPlan plan, int rows, int H, int C, hipStream_t s)
+{
+    const int nsl = cand_slices_for(C);
+    if (nsl > 64 || chunk_cap_for(C) > CAND_ITEM_WAVES * 64) return hipErrorInvalidValue;
+    const int compact = rows <= CAND_THREADS;
+    const long long units = (long long)rows * nsl;
+    if (units > 0x7fffffffll) return hipErrorInvalidValue;
+    const int grid = compact ? (int)std::min<long long>(units, 2 * 256) : (int)units;   // compact: two per compute unit
+    hipLaunchKernelGGL(cand_select_kernel<false>, dim3(grid), dim3(CAND_THREADS), 0, s, cs, thresh, keep_mask, ranges,
+                       n_ranges, n_keys, plan, rows, H, C, nsl, compact);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(cand_select_kernel<true>, dim3(grid), dim3(CAND_THREADS), 0, s, cs, thresh, keep_mask, ranges,
+                       n_ranges, n_keys, plan, rows, H, C, nsl, compact);
+    return hipGetLastError();
+}
+
 
 hipError_t launch_select_index(const float *logits, const float *thresh, const int32_t *sizes, const int32_t *offsets,
                                uint32_t *keep_mask, int32_t *n_ranges, int32_t *n_keys, KeyIndexPlan plan, int rows,

@@ -139,7 +139,8 @@ hipError_t launch_select(const float *logits, const float *row_max, const float 
 hipError_t launch_gather_score(const void *q, const void *centroids2, DecodePlan cand, const int32_t *sizes2,
                                const int32_t *offsets2, int len_from_offsets, float *logits2, int32_t *cand_id,
                                int4 *cand_rec, float2 *cand_stats, int *zero_counter, int H, int C2, float sm_scale,
-                               hipStream_t s);
+                               hipStream_t s, uint32_t *zero_mask = nullptr, size_t zero_words = 0);
+// (zero_mask: zero_words words cleared by the launch, for the selection that follows to set bits in.)
 // Rows [BH, G, C] of logits -> ln of the group's averaged Eq. 1 scores, written to all G rows (in place).
 hipError_t launch_group_mean_logits(float *logits, const int32_t *sizes, int BH, int H, int G, int C, hipStream_t s);
 // Caller-style ranges [rows, range_cap, 2] -> records + header per row.
@@ -212,6 +213,21 @@ inline size_t keyidx_partial_slots(int rows, int nuq) { return (size_t)KI_ATTN_G
 hipError_t launch_select_index(const float *logits, const float *thresh, const int32_t *sizes, const int32_t *offsets,
                                uint32_t *keep_mask, int32_t *n_ranges, int32_t *n_keys, KeyIndexPlan plan, int rows,
                                int H, int G, int C, hipStream_t s);
+// Last level of a hierarchical lookup, selected in slices of 256 candidates per workgroup (two launches: count, then
+// write).  rec / hdr / stats / row_items: the candidates' records, per-row candidate counts (hdr[row].y), per-item
+// statistics and per-row (first item, items), as launch_gather_score leaves them; slice_cnt [rows, cand_slices_for(C)]
+// is scratch.  keep_mask (optional) must have been zeroed (launch_gather_score does it); ranges optional; plan.key_idx
+// and plan.row_keys optional (selection without attention).  C <= SELECT_MAX_C.
+struct CandSelect {
+    const int4 *rec;
+    const int2 *hdr;
+    const float2 *stats;
+    const int2 *row_items;
+    int2 *slice_cnt;
+};
+inline int cand_slices_for(int C) { return (C + 255) / 256; }
+hipError_t launch_cand_select(CandSelect cs, const float *thresh, uint32_t *keep_mask, int32_t *ranges,
+                              int32_t *n_ranges, int32_t *n_keys, KeyIndexPlan plan, int rows, int H, int C, hipStream_t s);
 // Partial kernel over the selected keys + merge.  user (may be null): the rows' dense attention over their user keys
 // runs in extra workgroups of the partial kernel, one per piece of USER_PIECE keys: row r leaves user->nuq =
 // user_pieces_for(U) partial results at slots user->slot_base + r * nuq + (0 .. nuq - 1) of `partials`.

@@ -254,12 +254,14 @@ __global__ __launch_bounds__(256) void gather_score_kernel(const _Float16 *__res
                                                            int32_t *__restrict__ cand_id, int4 *__restrict__ cand_rec,
                                                            float2 *__restrict__ cand_stats,
                                                            int *__restrict__ zero_counter, int H, int C2,
-                                                           float sm_scale)
+                                                           float sm_scale, uint32_t *__restrict__ zero_mask,
+                                                           size_t zero_words)
 {
     __shared__ int s_pos[KPC], s_delta[KPC], s_rows[KPC];
     __shared__ __align__(16) float s_x[KPC];
     __shared__ float s_red[4];
     if (zero_counter && blockIdx.x == 0 && threadIdx.x == 0) zero_counter[0] = zero_counter[1] = 0;
+    for (size_t w = (size_t)blockIdx.x * 256 + threadIdx.x; w < zero_words; w += (size_t)gridDim.x * 256) zero_mask[w] = 0u;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 15, kg = lane >> 4;
     constexpr int TILES = KPC / 64;                 // 16-cluster tiles per wave
@@ -336,12 +338,12 @@ __global__ __launch_bounds__(256) void gather_score_kernel(const _Float16 *__res
 hipError_t launch_gather_score(const void *q, const void *centroids2, DecodePlan cand, const int32_t *sizes2,
                                const int32_t *offsets2, int len_from_offsets, float *logits2, int32_t *cand_id,
                                int4 *cand_rec, float2 *cand_stats, int *zero_counter, int H, int C2, float sm_scale,
-                               hipStream_t s)
+                               hipStream_t s, uint32_t *zero_mask, size_t zero_words)
 {
     const int grid = cand.item_cap < 2048 ? cand.item_cap : 2048;
     hipLaunchKernelGGL(gather_score_kernel, dim3(grid), dim3(256), 0, s, (const _Float16 *)q,
                        (const _Float16 *)centroids2, cand, sizes2, offsets2, len_from_offsets, logits2, cand_id,
-                       cand_rec, cand_stats, zero_counter, H, C2, sm_scale);
+                       cand_rec, cand_stats, zero_counter, H, C2, sm_scale, zero_mask, zero_mask ? zero_words : 0);
     return hipGetLastError();
 }
 

@@ -236,28 +236,6 @@ __device__ __forceinline__ void wave_select_mask(const float *__restrict__ x, co
     }
 }
 
-// Sets bit `id` of an LDS bit mask for every lane with `keep`, called by a whole wave.  Candidates are listed in
-// ascending id order and the children of a kept cluster are consecutive, so the kept lanes of a wave usually hold
-// ids base + lane: their ballot, shifted by base % 32, IS the content of at most three mask words, written by three
-// lanes -- instead of up to 32 lanes contending for one word.  Any other pattern falls back to one atomic per lane.
-__device__ __forceinline__ void wave_mask_or(uint32_t *mask, int id, bool keep, int lane)
-{
-    const unsigned long long bal = __ballot(keep);
-    if (bal == 0ull) return;                                  // wave-uniform
-    const int first = __ffsll((long long)bal) - 1;
-    const int base = __builtin_amdgcn_readlane(id, first) - first;
-    if (__ballot(keep && id != base + lane) == 0ull) {
-        const int s = base & 31, w0 = base >> 5;              // floor division: base may be negative (unkept low lanes)
-        uint32_t v = 0u;
-        if (lane == 0) v = (uint32_t)(bal << s);
-        else if (lane == 1) v = s ? (uint32_t)(bal >> (32 - s)) : (uint32_t)(bal >> 32);
-        else if (lane == 2) v = s ? (uint32_t)(bal >> (64 - s)) : 0u;
-        if (lane < 3 && v != 0u) atomicOr(&mask[w0 + lane], v);   // (a word below 0 would hold no bit: v == 0)
-    } else if (keep) {
-        atomicOr(&mask[id >> 5], 1u << (id & 31));
-    }
-}
-
 // UNION: the row is a union row (sequence group, head) of a batched decode over a shared context.  First every
 // sequence of the group is selected by one wave of the workgroup (logits [B*H, C]; keep_mask, n_ranges, n_keys
 // are the per-sequence outputs), then cluster i is kept for the union row iff any sequence of the group kept
