@@ -195,35 +195,35 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
 #pragma unroll
         for (int i = 0; i < PF_NP; ++i) ik_n[i] = idx_bh[min(j0 + i * PF_RP + (tid >> 4), last)];
     };
-    auto fetch = [&](int blk) {           // issue the global loads of block `blk`
+    // The loads of the next block are issued in PF_NP pieces (one K and one V row chunk per thread each).  `aim` points
+    // them at block `blk` and issues the block's small loads (ids, mask words); `fetch_piece` is then called from inside
+    // the block body, one piece behind each step of the S^T products, so that the four waves of a workgroup do not queue
+    // at the address unit all at once while the matrix cores idle.
+    const char *nKb = reinterpret_cast<const char *>(Kfh), *nVb = reinterpret_cast<const char *>(Vfh);   // uniform bases
+    uint32_t noff[PF_NP];                 // per-thread byte offsets of the pieces, the same for K and V
+#pragma unroll
+    for (int i = 0; i < PF_NP; ++i) noff[i] = (uint32_t)(tid & 15) * 16u;
+    auto aim = [&](int blk) {
         const bool user = blk >= nblk_fixed;
         const int j0 = (user ? blk - nblk_fixed : blk) * PF_BN;
         const int nkeys = user ? U : L;
         if (SHARED && !user) {            // gathered rows (slots past the kept keys repeat the last kept row)
-            const char *Kb = reinterpret_cast<const char *>(Kfh), *Vb = reinterpret_cast<const char *>(Vfh);
+            nKb = reinterpret_cast<const char *>(Kfh);
+            nVb = reinterpret_cast<const char *>(Vfh);
 #pragma unroll
-            for (int i = 0; i < PF_NP; ++i)
-                pk[i] = *reinterpret_cast<const h8 *>(Kb + (size_t)ik_c[i] * 256 + (uint32_t)(tid & 15) * 16u);
-#pragma unroll
-            for (int i = 0; i < PF_NP; ++i)
-                pv[i] = *reinterpret_cast<const h8 *>(Vb + (size_t)ik_c[i] * 256 + (uint32_t)(tid & 15) * 16u);
+            for (int i = 0; i < PF_NP; ++i) noff[i] = (uint32_t)ik_c[i] * 256u + (uint32_t)(tid & 15) * 16u;
             return;
         }
-        const char *Kb = reinterpret_cast<const char *>(user ? Kuh : Kfh) + (size_t)j0 * 256;
-        const char *Vb = reinterpret_cast<const char *>(user ? Vuh : Vfh) + (size_t)j0 * 256;
-        if (j0 + PF_BN <= nkeys) {        // full block: uniform base + 32-bit per-thread offsets
+        nKb = reinterpret_cast<const char *>(user ? Kuh : Kfh) + (size_t)j0 * 256;
+        nVb = reinterpret_cast<const char *>(user ? Vuh : Vfh) + (size_t)j0 * 256;
+        if (j0 + PF_BN <= nkeys) {        // full block
 #pragma unroll
-            for (int i = 0; i < PF_NP; ++i) pk[i] = *reinterpret_cast<const h8 *>(Kb + (k_off + (uint32_t)i * (PF_RP * 256u)));
-#pragma unroll
-            for (int i = 0; i < PF_NP; ++i) pv[i] = *reinterpret_cast<const h8 *>(Vb + (k_off + (uint32_t)i * (PF_RP * 256u)));
+            for (int i = 0; i < PF_NP; ++i) noff[i] = k_off + (uint32_t)i * (PF_RP * 256u);
         } else {                          // last block of a tensor: rows past the end re-read the last row
             const int last = nkeys - 1 - j0;
 #pragma unroll
-            for (int i = 0; i < PF_NP; ++i) {
-                const int key = min(i * PF_RP + (tid >> 4), last);
-                pk[i] = *reinterpret_cast<const h8 *>(Kb + (uint32_t)key * 256u + (uint32_t)(tid & 15) * 16u);
-                pv[i] = *reinterpret_cast<const h8 *>(Vb + (uint32_t)key * 256u + (uint32_t)(tid & 15) * 16u);
-            }
+            for (int i = 0; i < PF_NP; ++i)
+                noff[i] = (uint32_t)min(i * PF_RP + (tid >> 4), last) * 256u + (uint32_t)(tid & 15) * 16u;
         }
         if (!user && !SHARED) {
             pinfo = binfo[blk];
@@ -234,6 +234,15 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
                 pw_hi = w0 + 1 < W ? my_mrow[w0 + 1] : 0u;
             }
         }
+    };
+    auto fetch_piece = [&](int i) {       // i: compile-time constant at every call
+        pk[i] = *reinterpret_cast<const h8 *>(nKb + noff[i]);
+        pv[i] = *reinterpret_cast<const h8 *>(nVb + noff[i]);
+    };
+    auto fetch_rest = [&](int from) {
+#pragma unroll
+        for (int i = 0; i < PF_NP; ++i)
+            if (i >= from) fetch_piece(i);
     };
     auto commit = [&](int blk, PfStage &st) {   // registers -> LDS (K rows, V rows, ids, mask bits)
         const bool user = blk >= nblk_fixed;
@@ -265,7 +274,8 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
         fetch_idx(0);
         take_idx();
         fetch_idx(1);
-        fetch(0);
+        aim(0);
+        fetch_rest(0);
         info_cur = pinfo;
         commit(0, stage[0]);
     }
@@ -276,11 +286,14 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
         const bool user = blk >= nblk_fixed;
         const int j0 = (user ? blk - nblk_fixed : blk) * PF_BN;
         const int info = info_cur;
-        if (blk + 1 < nblk) {                               // global loads of the next block run under this one
+        // The global loads of the next block run under this one.  (After the last block the pieces re-read the
+        // addresses they were last aimed at, and nothing is committed.)
+        if (blk + 1 < nblk) {
             take_idx();
-            fetch(blk + 1);
+            aim(blk + 1);
             if (blk + 2 < nblk) fetch_idx(blk + 2);
         }
+        bool fetched = false;                               // set by the block body
 
         // ---- visibility of this lane's (query, key) pairs: msk = all ones (visible) or zero ------------------
         // element e = kt*4 + v  <->  key kt*16 + kg*4 + v of the block, query nq[qt].
@@ -290,9 +303,11 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
         // of the block, query nq[qt].
         auto block = [&](auto make_masks, auto masked) {   // masked: std::bool_constant (false: every pair is visible)
             // ---- S^T = K Q^T ---------------------------------------------------------------------------------
-            // (scheduling hint for the region: interleave the LDS reads and vector-ALU work with the matrix products;
-            // measured -3.5 % on the masked form, nothing on the shared-set form)
-            if constexpr (!SHARED) __builtin_amdgcn_iglp_opt(1);
+            // (A wave that is issuing matrix products outranks one that is in its softmax: the two workgroups of a compute
+            // unit then overlap the two kinds of work instead of contending for the same pipe.  Measured on the masked
+            // form at 32 heads x 1024 tokens x 32K keys: 1110 us without, 1028 us with; the compiler's own interleaving
+            // hint for the region gave 1069 us and cannot be combined with it.  Nothing on the shared-set form.)
+            __builtin_amdgcn_s_setprio(3);
             f4 sacc[QT][4];
 #pragma unroll
             for (int qt = 0; qt < QT; ++qt)
@@ -307,7 +322,10 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
                     for (int qt = 0; qt < QT; ++qt)
                         sacc[qt][kt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bq[qt][s], sacc[qt][kt], 0, 0, 0);
                 }
+                if (s < PF_NP) fetch_piece(s);              // the next block's loads, a piece per step
             }
+            fetched = true;
+            __builtin_amdgcn_s_setprio(0);
             uint32_t msk[QT][16];
             if constexpr (decltype(masked)::value) make_masks(msk);
 
@@ -356,6 +374,7 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
             }
 
             // ---- O^T += V^T P^T ------------------------------------------------------------------------------
+            __builtin_amdgcn_s_setprio(3);
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
 #pragma unroll
@@ -369,6 +388,7 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
                         o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bp[qt][ks], o[qt][dt], 0, 0, 0);
                 }
             }
+            __builtin_amdgcn_s_setprio(0);
         };
 
         if (SHARED && !user && j0 + PF_BN <= n_fixed && q0 + BM <= Lq) {
@@ -444,6 +464,7 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
         }
 
         // ---- next block: registers -> the other LDS buffer; one barrier per block --------------------------
+        if (!fetched) fetch_rest(0);                        // (this wave skipped the block's products)
         if (blk + 1 < nblk) {
             commit(blk + 1, stage[(blk + 1) & 1]);
             info_cur = pinfo;
