@@ -81,6 +81,25 @@ def test_small_hier_select(sq, oracle, seed, H, C1, fan):
     assert t["nk"].sum() > 0
 
 
+def test_hier_select_many_rows(sq, oracle):
+    # More than 1024 (sequence, head) rows: the last level's slices are then mapped one workgroup per (row, slice)
+    # instead of being dealt over a fixed grid.  Every sequence has its own query; the high threshold at level 1
+    # leaves some rows without a single candidate (their counts must still come out as 0).
+    rng = np.random.default_rng(77)
+    H, C1 = 8, 12
+    q1, c1, N1, co, c2, N2, off2 = hier_problem(rng, H, C1, 30, 50, 128)
+    C2 = c2.shape[1]; L = int(off2[:, -1].max())
+    B = 130                                                   # 1040 rows
+    q = (rng.standard_normal((B, H, 128)) * 1.5).astype(np.float16)
+    T1 = np.full(H, 3.0 / N1.sum(1).mean(), np.float32); T2 = np.full(H, 2.0 / N2.sum(1).mean(), np.float32)
+    sm = float(np.float32(0.3))
+    ref = oracle.hier_select(q, c1, N1, co, T1, c2, N2, off2, T2, sm)
+    sh, t = run_hier_select(sq, B, H, C1, C2, L, q, c1, N1, co, T1, c2, N2, off2, T2, sm)
+    check_hier_selection(q, c1, N1, co, T1, c2, N2, off2, T2, sm, ref, t, "manyrows")
+    nk = t["nk"].cpu().numpy()
+    assert (nk == 0).any() and (nk > 0).any()
+
+
 def test_keep_all_coarse_equals_one_level_on_gpu(sq, oracle):
     # T1 < 0 keeps every coarse cluster: the candidates are then all fine clusters in order and level 2 must equal
     # the one-level selection with T2 (same logits, same rule).  The level-2 normaliser is merged from per-item sums,
