@@ -230,6 +230,19 @@ def test_shared_context_step_against_oracle(sq, oracle, case):
     step_against_oracle(sq, oracle, w, f"shared{case}")
 
 
+@pytest.mark.parametrize("case", [
+    dict(B=1, H=2, L=6000, C=4096, U=70, keep_frac=0.3),          # most clusters the key-index step takes
+    dict(B=1, H=2, L=6000, C=4100, U=70, keep_frac=0.3),          # one step past it: the work-list kernels
+    dict(B=4, H=256, L=300, C=20, U=3, keep_frac=0.4),            # 1024 query rows: the most the key-index step takes
+    dict(B=4, H=257, L=300, C=20, U=3, keep_frac=0.4),            # 1028 rows: the work-list kernels
+    dict(B=3, H=5, L=700, C=40, U=64, keep_frac=0.02),            # rows that keep (almost) nothing; one whole user piece
+    dict(B=2, H=3, L=900, C=9, U=191, keep_frac=0.95),            # rows that keep (almost) everything; ragged user pieces
+])
+def test_step_at_key_index_limits(sq, oracle, case):
+    w = wl.calibrate(wl.make_workload("limits", Lq=1, seed=21, threads=4, **case), oracle.scores)
+    step_against_oracle(sq, oracle, w, f"limits{case}")
+
+
 def test_shared_context_step_extremes(sq, oracle):
     base = dict(B=10, H=2, L=1024, C=32, Lq=1, U=33, keep_frac=0.5, seed=12, threads=2)
     # every sequence keeps everything: each key is owned by all sequences of the group
