@@ -997,7 +997,8 @@ struct Level {
 // only.  The candidate work lists of consecutive levels alternate between w.cand and cand_b (a level reads one
 // while it fills the other).  The last level writes ranges / counts and, when `schedule_last`, the attention
 // work items into plan_last.  klast (n >= 2): the last level is selected in slices of its candidates, many workgroups
-// per row (launch_cand_select), and leaves the rows' key-index lists in *klast (if it has any) instead of work items.
+// per row (launch_cand_select), and leaves the rows' key-index lists in *klast instead of work items (decode steps of at
+// most KI_MAX_ROWS rows; the lookup alone keeps one workgroup per row).
 int multilevel_lookup(const char *fn, const sq_shape_t *sh, int n, const Level *lv, const void *q, int32_t *ranges,
                       int32_t *n_ranges, int32_t *n_keys, HierWs &w, sq::DecodePlan cand_b, sq::DecodePlan plan_last,
                       bool schedule_last, hipStream_t s, const sq::UserAttn *user = nullptr,
@@ -1039,8 +1040,7 @@ int multilevel_lookup(const char *fn, const sq_shape_t *sh, int n, const Level *
         if (e != hipSuccess) break;
         if (sliced) {
             const sq::CandSelect cs{cur.rec, cur.hdr, w.cand_stats, cur.row_items, w.slice_cnt};
-            e = sq::launch_cand_select(cs, lv[k].thresh, lv[k].mask, ranges, n_ranges, n_keys, *klast, rows, sh->H,
-                                       lv[k].C, s);
+            e = sq::launch_cand_select(cs, lv[k].thresh, lv[k].mask, n_ranges, n_keys, *klast, rows, sh->H, lv[k].C, s);
             break;
         }
         sq::SelectOpts o{};
@@ -1134,10 +1134,9 @@ int sq_hier_select(const sq_shape_t *sh, int32_t C1, const void *q, const void *
     if (int rc = check_device(__func__)) return rc;
     Carver cv(ws);
     HierWs w = carve_hier(cv, sh);
-    const sq::KeyIndexPlan none{};                     // selection alone: ranges and counts, no key-index list
     if (int rc = hier_lookup(__func__, sh, C1, q, centroids1, sizes1, child_offsets, thresh1, centroids2, sizes2,
                              offsets2, thresh2, keep_mask1, keep_mask2, ranges, n_ranges, n_keys, w, sq::DecodePlan{},
-                             false, static_cast<hipStream_t>(stream), nullptr, &none))
+                             false, static_cast<hipStream_t>(stream)))
         return rc;
     g_err[0] = 0;
     return SQ_OK;
@@ -1323,9 +1322,8 @@ int sq_multilevel_select(const sq_shape_t *sh, int32_t n_levels, const sq_level_
     Carver cv(ws);
     HierWs w = carve_hier(cv, sh);
     sq::DecodePlan cand_b = carve_cand_plan(cv, sh);
-    const sq::KeyIndexPlan none{};                     // selection alone: ranges and counts, no key-index list
     if (int rc = multilevel_lookup(__func__, sh, n_levels, lv, q, ranges, n_ranges, n_keys, w, cand_b, sq::DecodePlan{},
-                                   false, static_cast<hipStream_t>(stream), nullptr, &none))
+                                   false, static_cast<hipStream_t>(stream)))
         return rc;
     g_err[0] = 0;
     return SQ_OK;

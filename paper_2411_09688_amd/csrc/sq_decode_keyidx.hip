@@ -494,8 +494,7 @@ __global__ __launch_bounds__(MERGE_THREADS) void decode_merge_index_kernel(const
 // normaliser are merged from the items' pairs by every workgroup (item v by thread v; wave sums ascending):
 // bit-identical whichever slice asks.  Two launches: the first counts the kept clusters and keys of every slice and
 // sets the mask bits (by cluster id, into a mask the scoring launch zeroed); the second, knowing the counts of the
-// slices in front of its own, writes the ranges, the key rows into the row's key-index list and (slice 0) the row's
-// counts.
+// slices in front of its own, writes the key rows into the row's key-index list and (slice 0) the row's counts.
 constexpr int CAND_THREADS = 1024;                               // = items of a row, at most
 constexpr int CAND_SLICE = 256;
 constexpr int CAND_WAVES = CAND_SLICE / 64;                      // waves that hold candidates
@@ -513,7 +512,7 @@ struct CandLds {
 // Slice `sl` of row `row` (n candidates), by the whole workgroup.  Leaves the LDS free for the next slice.
 template <bool EMIT>
 __device__ __forceinline__ void cand_select_slice(const CandSelect &cs, const float *__restrict__ thresh,
-                                                  uint32_t *__restrict__ keep_mask, int32_t *__restrict__ ranges,
+                                                  uint32_t *__restrict__ keep_mask,
                                                   int32_t *__restrict__ n_ranges, int32_t *__restrict__ n_keys,
                                                   const KeyIndexPlan &plan, int H, int C, int nsl, int row, int sl, int n,
                                                   CandLds<EMIT> &S)
@@ -587,7 +586,7 @@ __device__ __forceinline__ void cand_select_slice(const CandSelect &cs, const fl
             if (sl == 0) {
                 n_ranges[row] = tot_r;
                 n_keys[row] = tot_k;
-                if (plan.row_keys) plan.row_keys[row] = min(tot_k, plan.L);
+                plan.row_keys[row] = min(tot_k, plan.L);
             }
         }
     }
@@ -595,11 +594,9 @@ __device__ __forceinline__ void cand_select_slice(const CandSelect &cs, const fl
     if (keep) {
         const int rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0));
         const int r = s_cnt[wave] + rank;
-        if (ranges) *reinterpret_cast<int2 *>(ranges + ((size_t)row * C + s_base[0] + r) * 2) = make_int2(rv.z, rv.w);
         s_rec[r] = make_int4(rv.z, kv, s_base[1] + s_keys[wave] + incl - kv, 0);
     }
     __syncthreads();
-    if (!plan.key_idx) return;                                  // (selection alone: no list)
     // Key-index list: half-wave g writes the key rows of kept clusters g, g + 32, ... of the slice.
     const int n_slice = s_cnt[CAND_WAVES];
     int32_t *idx_row = plan.key_idx + (size_t)row * plan.L;
@@ -611,27 +608,18 @@ __device__ __forceinline__ void cand_select_slice(const CandSelect &cs, const fl
     __syncthreads();                                            // (the LDS is free for the next slice)
 }
 
-// Workgroups -> slices.  compact (rows <= CAND_THREADS): a fixed grid; every workgroup reads all rows' candidate
-// counts and takes the non-empty slices u = workgroup, workgroup + grid, ... of the rows laid end to end (a row
-// without candidates counts as one slice: its counts are still written), so no workgroup is launched only to find
-// that its slice is empty.  Otherwise one workgroup per (row, slice).
+// Workgroups -> slices (rows <= CAND_THREADS): a fixed grid; every workgroup reads all rows' candidate counts and takes
+// the non-empty slices u = workgroup, workgroup + grid, ... of the rows laid end to end (a row without candidates counts
+// as one slice: its counts are still written), so no workgroup is launched only to find that its slice is empty.
 template <bool EMIT>
 __global__ __launch_bounds__(CAND_THREADS) void cand_select_kernel(CandSelect cs, const float *__restrict__ thresh,
                                                                    uint32_t *__restrict__ keep_mask,
-                                                                   int32_t *__restrict__ ranges,
                                                                    int32_t *__restrict__ n_ranges,
                                                                    int32_t *__restrict__ n_keys, KeyIndexPlan plan,
-                                                                   int rows, int H, int C, int nsl, int compact)
+                                                                   int rows, int H, int C, int nsl)
 {
     __shared__ CandLds<EMIT> S;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (!compact) {
-        const int row = blockIdx.x / nsl, sl = blockIdx.x - row * nsl;
-        const int n = min(cs.hdr[row].y, C);
-        if (sl * CAND_SLICE >= n && sl != 0) return;            // workgroup-uniform (slice 0 still writes the counts)
-        cand_select_slice<EMIT>(cs, thresh, keep_mask, ranges, n_ranges, n_keys, plan, H, C, nsl, row, sl, n, S);
-        return;
-    }
     const int n_t = tid < rows ? min(cs.hdr[tid].y, C) : 0;
     const int cnt = tid < rows ? max(1, (n_t + CAND_SLICE - 1) / CAND_SLICE) : 0;
     const int incl = wave_inclusive_scan(cnt, lane);
@@ -652,25 +640,23 @@ __global__ __launch_bounds__(CAND_THREADS) void cand_select_kernel(CandSelect cs
         }
         __syncthreads();
         const int row = S.unit[0], sl = S.unit[1], n = S.unit[2];
-        cand_select_slice<EMIT>(cs, thresh, keep_mask, ranges, n_ranges, n_keys, plan, H, C, nsl, row, sl, n, S);
+        cand_select_slice<EMIT>(cs, thresh, keep_mask, n_ranges, n_keys, plan, H, C, nsl, row, sl, n, S);
     }
 }
 
-hipError_t launch_cand_select(CandSelect cs, const float *thresh, uint32_t *keep_mask, int32_t *ranges,
-                              int32_t *n_ranges, int32_t *n_keys, KeyIndexPlan plan, int rows, int H, int C, hipStream_t s)
+hipError_t launch_cand_select(CandSelect cs, const float *thresh, uint32_t *keep_mask, int32_t *n_ranges, int32_t *n_keys,
+                              KeyIndexPlan plan, int rows, int H, int C, hipStream_t s)
 {
     const int nsl = cand_slices_for(C);
-    if (nsl > 64 || chunk_cap_for(C) > CAND_ITEM_WAVES * 64) return hipErrorInvalidValue;
-    const int compact = rows <= CAND_THREADS;
-    const long long units = (long long)rows * nsl;
-    if (units > 0x7fffffffll) return hipErrorInvalidValue;
-    const int grid = compact ? (int)std::min<long long>(units, 2 * 256) : (int)units;   // compact: two per compute unit
-    hipLaunchKernelGGL(cand_select_kernel<false>, dim3(grid), dim3(CAND_THREADS), 0, s, cs, thresh, keep_mask, ranges,
-                       n_ranges, n_keys, plan, rows, H, C, nsl, compact);
+    if (nsl > 64 || chunk_cap_for(C) > CAND_ITEM_WAVES * 64 || rows > CAND_THREADS || !plan.key_idx || !plan.row_keys)
+        return hipErrorInvalidValue;
+    const int grid = (int)std::min<long long>((long long)rows * nsl, 2 * 256);   // two workgroups per compute unit
+    hipLaunchKernelGGL(cand_select_kernel<false>, dim3(grid), dim3(CAND_THREADS), 0, s, cs, thresh, keep_mask, n_ranges,
+                       n_keys, plan, rows, H, C, nsl);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(cand_select_kernel<true>, dim3(grid), dim3(CAND_THREADS), 0, s, cs, thresh, keep_mask, ranges,
-                       n_ranges, n_keys, plan, rows, H, C, nsl, compact);
+    hipLaunchKernelGGL(cand_select_kernel<true>, dim3(grid), dim3(CAND_THREADS), 0, s, cs, thresh, keep_mask, n_ranges,
+                       n_keys, plan, rows, H, C, nsl);
     return hipGetLastError();
 }
 

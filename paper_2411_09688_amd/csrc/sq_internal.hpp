@@ -216,8 +216,9 @@ hipError_t launch_select_index(const float *logits, const float *thresh, const i
 // Last level of a hierarchical lookup, selected in slices of 256 candidates per workgroup (two launches: count, then
 // write).  rec / hdr / stats / row_items: the candidates' records, per-row candidate counts (hdr[row].y), per-item
 // statistics and per-row (first item, items), as launch_gather_score leaves them; slice_cnt [rows, cand_slices_for(C)]
-// is scratch.  keep_mask (optional) must have been zeroed (launch_gather_score does it); ranges optional; plan.key_idx
-// and plan.row_keys optional (selection without attention).  C <= SELECT_MAX_C.
+// is scratch.  keep_mask (optional) must have been zeroed (launch_gather_score does it).  C <= SELECT_MAX_C, at most
+// 1024 rows.  (The lookup without attention, which returns ranges, keeps the one-workgroup-per-row selection: over all
+// queries of a workload its single launch is faster than these two.)
 struct CandSelect {
     const int4 *rec;
     const int2 *hdr;
@@ -226,8 +227,8 @@ struct CandSelect {
     int2 *slice_cnt;
 };
 inline int cand_slices_for(int C) { return (C + 255) / 256; }
-hipError_t launch_cand_select(CandSelect cs, const float *thresh, uint32_t *keep_mask, int32_t *ranges,
-                              int32_t *n_ranges, int32_t *n_keys, KeyIndexPlan plan, int rows, int H, int C, hipStream_t s);
+hipError_t launch_cand_select(CandSelect cs, const float *thresh, uint32_t *keep_mask, int32_t *n_ranges, int32_t *n_keys,
+                              KeyIndexPlan plan, int rows, int H, int C, hipStream_t s);
 // Partial kernel over the selected keys + merge.  user (may be null): the rows' dense attention over their user keys
 // runs in extra workgroups of the partial kernel, one per piece of USER_PIECE keys: row r leaves user->nuq =
 // user_pieces_for(U) partial results at slots user->slot_base + r * nuq + (0 .. nuq - 1) of `partials`.
