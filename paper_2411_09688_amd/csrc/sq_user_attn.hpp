@@ -1,13 +1,17 @@
 // Dense attention of one query row over its user/generated keys (Section 3.2: they are attended to densely, whatever
 // the lookup keeps), as partial results for the split-KV merge.  The user keys do not depend on the selection, so a
-// decode step computes this part in extra workgroups of the selection launch -- a launch that occupies one compute
-// unit per row and leaves the rest of the chip idle -- and the partial kernel that follows streams only the selected
-// fixed-context keys.
+// decode step computes this part in extra workgroups of a launch that leaves the memory system idle, and the partial
+// kernel's other workgroups stream only the selected fixed-context keys.  Two forms:
 //
-// One 1024-thread workgroup per (row, chunk of KPC user keys) -- a compute unit pulls ~27 GB/s at most, so the chunks
-// of a row must not share one -- with the arithmetic of the partial kernel: a wave owns 8 key slots of the chunk,
-// 16 lanes per key row, every K/V load in flight before the arithmetic.  The 16 waves' results are folded in LDS
-// into ONE partial result at slot slot_base + row * nuq + chunk (nuq = chunks per row).
+// user_chunk_partial (steps on the work-list kernels): extra workgroups of the SELECTION launch -- a launch that occupies
+// one compute unit per row and leaves the rest of the chip idle.  One 1024-thread workgroup per (row, chunk of KPC user
+// keys) -- a compute unit pulls ~27 GB/s at most, so the chunks of a row must not share one -- with the arithmetic of
+// the partial kernel: a wave owns 8 key slots of the chunk, 16 lanes per key row, every K/V load in flight before the
+// arithmetic.  The 16 waves' results are folded in LDS into ONE partial result at slot slot_base + row * nuq + chunk
+// (nuq = chunks per row).
+//
+// user_piece_partial (steps through the key-index list): extra workgroups of the PARTIAL kernel's launch, 256 threads per
+// piece of USER_PIECE keys (see there).
 #pragma once
 #include "sq_common.hpp"
 #include "sq_internal.hpp"
