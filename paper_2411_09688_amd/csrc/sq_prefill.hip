@@ -36,8 +36,15 @@
 namespace sq {
 
 constexpr int PF_BN = 64;                 // keys per block
-constexpr int PF_KS_STRIDE = D + 8;       // halves per K row in LDS (272 B: conflict-free 16-B reads)
-constexpr int PF_V_STRIDE = D + 16;       // halves per V row in LDS (288 B: the transposing reads below hit 32 distinct banks)
+// K and V tiles in LDS: unpadded rows of 256 B, filled straight from global memory by the load-to-LDS instruction
+// (global_load_lds_dwordx4: the 64 lanes of a wave write 64 x 16 contiguous bytes = four whole rows), and swizzled
+// instead of padded so that the operand reads stay free of bank conflicts: the 16-byte chunk c of row r sits at slot
+// c ^ swz(r).  The swizzle is applied on the global side (lane = slot: it fetches chunk slot ^ swz(r)).
+//   K (16-byte reads, 16 rows at one chunk index per group of lanes): swz = r % 16 -- the 16 rows land in 16 slots.
+//   V (transposing 8-byte reads, 16 rows x 32 bytes per instruction): swz = 2 * (r % 8) -- a pair of chunks stays
+//   adjacent and the 8 rows of half a wave land in 8 different pairs.
+__device__ __forceinline__ int pf_k_swz(int row) { return row & 15; }
+__device__ __forceinline__ int pf_v_swz(int row) { return (row & 7) << 1; }
 
 // key -> cluster id map of every head (clusters are contiguous key ranges).  Keys that no cluster covers (before
 // offsets[0] or from offsets[C] on) get the "no cluster" id 0x7fffffff, which no query keeps.
@@ -97,8 +104,8 @@ constexpr int pf_bm(bool shared) { return 16 * PF_QT * pf_waves(shared); }   // 
 constexpr int PF_BM_MAX = pf_bm(true);
 
 struct PfStage {                          // one LDS buffer of a key block
-    _Float16 K[PF_BN * PF_KS_STRIDE];
-    _Float16 V[PF_BN * PF_V_STRIDE];
+    _Float16 K[PF_BN * D];
+    _Float16 V[PF_BN * D];
     int cid[PF_BN];                       // cluster of each key (0x7fffffff past the end)
     int sh[PF_BN];                        // bit of the key's cluster in the staged window: cluster - first cluster of
                                           // the block (31, a bit that is never set, for keys past the end)
@@ -179,13 +186,15 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
     const int my_q = q0 + tid;
     const uint32_t *my_mrow = keep_mask + (row0 + min(my_q, Lq - 1)) * W;
 
-    // Registers that carry the next block from global memory to LDS.
-    h8 pk[PF_NP], pv[PF_NP];
+    // Registers that carry the next block's ids and mask words from global memory to LDS (its K and V rows go to LDS
+    // directly).
     int pcid = 0, pinfo = 0;
     uint32_t pw_lo = 0u, pw_hi = 0u;
-    // Byte offset of this thread's pieces inside a 64-key block (rows of 256 B), the same for K and V: piece i =
-    // key i*PF_RP + tid/16, 16-byte chunk tid%16.
-    const uint32_t k_off = (uint32_t)(tid >> 4) * 256u + (uint32_t)(tid & 15) * 16u;
+    // This thread's pieces of a 64-key block: piece i = key i*PF_RP + tid/16 (rows of 256 B), LDS slot tid%16 of that
+    // row, i.e. the 16-byte chunk (tid%16) ^ swz(row) of the row in memory; row % 16 = (tid/16) % 16 for every piece.
+    const uint32_t r_off = (uint32_t)(tid >> 4) * 256u;
+    const uint32_t k_ch = (uint32_t)((tid & 15) ^ pf_k_swz(tid >> 4)) * 16u, v_ch = (uint32_t)((tid & 15) ^ pf_v_swz(tid >> 4)) * 16u;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     // SHARED: rows of this thread's pieces (keys i*16 + tid/16) of a fixed block; the indices of block b+2 are
     // loaded while block b is computed and used when block b+1's rows are fetched.
     int ik_n[PF_NP] = {}, ik_c[PF_NP] = {};
@@ -200,9 +209,9 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
     // the block body, one piece behind each step of the S^T products, so that the four waves of a workgroup do not queue
     // at the address unit all at once while the matrix cores idle.
     const char *nKb = reinterpret_cast<const char *>(Kfh), *nVb = reinterpret_cast<const char *>(Vfh);   // uniform bases
-    uint32_t noff[PF_NP];                 // per-thread byte offsets of the pieces, the same for K and V
+    uint32_t noff[PF_NP];                 // per-thread byte offsets of the pieces' rows, the same for K and V
 #pragma unroll
-    for (int i = 0; i < PF_NP; ++i) noff[i] = (uint32_t)(tid & 15) * 16u;
+    for (int i = 0; i < PF_NP; ++i) noff[i] = 0u;
     auto aim = [&](int blk) {
         const bool user = blk >= nblk_fixed;
         const int j0 = (user ? blk - nblk_fixed : blk) * PF_BN;
@@ -211,19 +220,19 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
             nKb = reinterpret_cast<const char *>(Kfh);
             nVb = reinterpret_cast<const char *>(Vfh);
 #pragma unroll
-            for (int i = 0; i < PF_NP; ++i) noff[i] = (uint32_t)ik_c[i] * 256u + (uint32_t)(tid & 15) * 16u;
+            for (int i = 0; i < PF_NP; ++i) noff[i] = (uint32_t)ik_c[i] * 256u;
             return;
         }
         nKb = reinterpret_cast<const char *>(user ? Kuh : Kfh) + (size_t)j0 * 256;
         nVb = reinterpret_cast<const char *>(user ? Vuh : Vfh) + (size_t)j0 * 256;
         if (j0 + PF_BN <= nkeys) {        // full block
 #pragma unroll
-            for (int i = 0; i < PF_NP; ++i) noff[i] = k_off + (uint32_t)i * (PF_RP * 256u);
+            for (int i = 0; i < PF_NP; ++i) noff[i] = r_off + (uint32_t)i * (PF_RP * 256u);
         } else {                          // last block of a tensor: rows past the end re-read the last row
             const int last = nkeys - 1 - j0;
 #pragma unroll
             for (int i = 0; i < PF_NP; ++i)
-                noff[i] = (uint32_t)min(i * PF_RP + (tid >> 4), last) * 256u + (uint32_t)(tid & 15) * 16u;
+                noff[i] = (uint32_t)min(i * PF_RP + (tid >> 4), last) * 256u;
         }
         if (!user && !SHARED) {
             pinfo = binfo[blk];
@@ -235,23 +244,35 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
             }
         }
     };
-    auto fetch_piece = [&](int i) {       // i: compile-time constant at every call
-        pk[i] = *reinterpret_cast<const h8 *>(nKb + noff[i]);
-        pv[i] = *reinterpret_cast<const h8 *>(nVb + noff[i]);
+    typedef __attribute__((address_space(1))) const void *gptr_t;
+    typedef __attribute__((address_space(3))) void *lptr_t;
+    auto fetch_piece = [&](int i, PfStage &dst) {   // i: compile-time constant at every call
+        // this wave's four rows of the piece: 1 KB of the tile, lane l at byte 16 l
+        _Float16 *lk = dst.K + (i * PF_RP + wave_u * 4) * D, *lv = dst.V + (i * PF_RP + wave_u * 4) * D;
+        if constexpr (SHARED) {
+            __builtin_amdgcn_global_load_lds((gptr_t)(nKb + (noff[i] + k_ch)), (lptr_t)lk, 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(nVb + (noff[i] + v_ch)), (lptr_t)lv, 16, 0, 0);
+        } else {
+            // Written as instructions: through the builtin the compiler makes the first V read of the CURRENT buffer wait
+            // for these loads into the OTHER buffer (it cannot tell the two apart).  Masked form at 32 heads x 1024 tokens x
+            // 32K keys: 1042 us with the builtin, 825 us this way; the shared-set form, whose V reads come later, is faster
+            // with the builtin (133 against 147 us: the asm statements pin the compiler's schedule).
+            const uint32_t ak = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)(lptr_t)lk);
+            const uint32_t av = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)(lptr_t)lv);
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(ak), "v"(noff[i] + k_ch), "s"(nKb) : "m0");
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(av), "v"(noff[i] + v_ch), "s"(nVb) : "m0");
+        }
     };
-    auto fetch_rest = [&](int from) {
+    auto fetch_rest = [&](int from, PfStage &dst) {
 #pragma unroll
         for (int i = 0; i < PF_NP; ++i)
-            if (i >= from) fetch_piece(i);
+            if (i >= from) fetch_piece(i, dst);
     };
-    auto commit = [&](int blk, PfStage &st) {   // registers -> LDS (K rows, V rows, ids, mask bits)
+    // The loads to LDS are not tracked by the compiler: before the barrier that publishes a block, every wave waits
+    // for all of its outstanding memory operations itself.
+    auto loads_landed = [&]() { __builtin_amdgcn_s_waitcnt(0x0f70); };   // vmcnt(0)
+    auto commit = [&](int blk, PfStage &st) {   // registers -> LDS (ids, mask bits)
         const bool user = blk >= nblk_fixed;
-#pragma unroll
-        for (int i = 0; i < PF_NP; ++i) {
-            const int key = i * PF_RP + (tid >> 4), chunk = tid & 15;
-            *reinterpret_cast<h8 *>(st.K + key * PF_KS_STRIDE + chunk * 8) = pk[i];
-            *reinterpret_cast<h8 *>(st.V + key * PF_V_STRIDE + chunk * 8) = pv[i];
-        }
         if (!user && !SHARED) {
             const int first = pinfo & 0xffff;
             if (tid < PF_BN) {
@@ -275,10 +296,11 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
         take_idx();
         fetch_idx(1);
         aim(0);
-        fetch_rest(0);
+        fetch_rest(0, stage[0]);
         info_cur = pinfo;
         commit(0, stage[0]);
     }
+    loads_landed();
     __syncthreads();
 
     for (int blk = 0; blk < nblk; ++blk) {
@@ -317,12 +339,12 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
             for (int s = 0; s < 4; ++s) {
 #pragma unroll
                 for (int kt = 0; kt < 4; ++kt) {            // four independent accumulators in turn
-                    const h8 a = *reinterpret_cast<const h8 *>(st.K + (kt * 16 + col) * PF_KS_STRIDE + s * 32 + kg * 8);
+                    const h8 a = *reinterpret_cast<const h8 *>(st.K + (kt * 16 + col) * D + ((s * 4 + kg) ^ pf_k_swz(col)) * 8);
 #pragma unroll
                     for (int qt = 0; qt < QT; ++qt)
                         sacc[qt][kt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bq[qt][s], sacc[qt][kt], 0, 0, 0);
                 }
-                if (s < PF_NP) fetch_piece(s);              // the next block's loads, a piece per step
+                if (s < PF_NP) fetch_piece(s, stage[(blk + 1) & 1]);   // the next block's loads, a piece per step
             }
             fetched = true;
             __builtin_amdgcn_s_setprio(0);
@@ -380,8 +402,9 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
 #pragma unroll
                 for (int dt = 0; dt < 8; ++dt) {
                     // keys ks*32 + t*16 + kg*4 + (0..3) for t = 0, 1: the order P^T was packed in
-                    const _Float16 *vp = st.V + (ks * 32 + kg * 4 + (col >> 2)) * PF_V_STRIDE + dt * 16 + (col & 3) * 4;
-                    const h4 a0 = lds_read_tr16(vp), a1 = lds_read_tr16(vp + 16 * PF_V_STRIDE);
+                    const int vrow = ks * 32 + kg * 4 + (col >> 2);      // (vrow + 16 has the same swizzle)
+                    const _Float16 *vp = st.V + vrow * D + ((dt * 2 + ((col & 3) >> 1)) ^ pf_v_swz(vrow)) * 8 + (col & 1) * 4;
+                    const h4 a0 = lds_read_tr16(vp), a1 = lds_read_tr16(vp + 16 * D);
                     const h8 a = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
 #pragma unroll
                     for (int qt = 0; qt < QT; ++qt)
@@ -464,11 +487,12 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
         }
 
         // ---- next block: registers -> the other LDS buffer; one barrier per block --------------------------
-        if (!fetched) fetch_rest(0);                        // (this wave skipped the block's products)
+        if (!fetched) fetch_rest(0, stage[(blk + 1) & 1]);  // (this wave skipped the block's products)
         if (blk + 1 < nblk) {
             commit(blk + 1, stage[(blk + 1) & 1]);
             info_cur = pinfo;
         }
+        loads_landed();
         __syncthreads();
     }
 
