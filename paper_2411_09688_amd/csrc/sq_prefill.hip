@@ -5,15 +5,15 @@
 // online softmax), written for CDNA4 matrix cores:
 //   * a workgroup = 4 waves x 16 queries, two workgroups per compute unit (shared-set form: 8 waves, one
 //     workgroup); all waves walk the same 64-key blocks, whose K and V tiles are staged row-major in LDS once per
-//     workgroup (two LDS buffers; the next block's global loads are issued before the current block's arithmetic
-//     and land in registers meanwhile);
+//     workgroup (two LDS buffers; the next block's rows go from global memory straight into the other buffer with the
+//     load-to-LDS instruction, issued a piece at a time behind the steps of the current block's score products);
 //   * scores are computed TRANSPOSED, S^T = K Q^T, with 16x16x32 fp16 MFMA tiles (A = 16 keys, B = 16
 //     queries).  In the accumulator layout a lane then owns ONE query column for the whole kernel (and four
 //     keys per tile), so the running maximum, the running sum and the rescaling of the output are per-lane
 //     scalars, and P^T is repacked into the B operand of the next product in registers, with no
 //     cross-lane traffic;
 //   * O^T = V^T P^T uses A = V^T tiles read from the row-major V tile with the transposing LDS read
-//     (ds_read_b64_tr_b16), so V goes to LDS with plain 16-byte stores;
+//     (ds_read_b64_tr_b16), so V needs no transposition on its way into LDS;
 //   * the per-query keep masks are applied per (query, key): a small pre-kernel expands the cluster offsets
 //     into a key -> cluster map, each key block brings, for every query of the workgroup, the window of mask
 //     bits that covers its clusters, the bit of a (query, key) pair is spread over a word with one signed
