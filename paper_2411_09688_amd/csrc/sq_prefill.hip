@@ -303,197 +303,31 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
     loads_landed();
     __syncthreads();
 
-    for (int blk = 0; blk < nblk; ++blk) {
-        PfStage &st = stage[blk & 1];
-        const bool user = blk >= nblk_fixed;
-        const int j0 = (user ? blk - nblk_fixed : blk) * PF_BN;
-        const int info = info_cur;
-        // The global loads of the next block run under this one.  (After the last block the pieces re-read the
-        // addresses they were last aimed at, and nothing is committed.)
-        if (blk + 1 < nblk) {
-            take_idx();
-            aim(blk + 1);
-            if (blk + 2 < nblk) fetch_idx(blk + 2);
-        }
-        bool fetched = false;                               // set by the block body
-
-        // ---- visibility of this lane's (query, key) pairs: msk = all ones (visible) or zero ------------------
-        // element e = kt*4 + v  <->  key kt*16 + kg*4 + v of the block, query nq[qt].
-        // One block for the queries of this wave: the products S^T = K Q^T are issued first, so that the matrix
-        // cores work while `make_masks` (inlined, branch-free in the common cases) expands the visibility of this
-        // lane's (query, key) pairs: msk = all ones (visible) or zero; element e = kt*4 + v <-> key kt*16 + kg*4 + v
-        // of the block, query nq[qt].
-        auto block = [&](auto make_masks, auto masked) {   // masked: std::bool_constant (false: every pair is visible)
-            // ---- S^T = K Q^T ---------------------------------------------------------------------------------
-            // (A wave that is issuing matrix products outranks one that is in its softmax: the two workgroups of a compute
-            // unit then overlap the two kinds of work instead of contending for the same pipe.  Measured on the masked
-            // form at 32 heads x 1024 tokens x 32K keys: 1110 us without, 1028 us with; the compiler's own interleaving
-            // hint for the region gave 1069 us and cannot be combined with it.  Nothing on the shared-set form.)
-            __builtin_amdgcn_s_setprio(3);
-            f4 sacc[QT][4];
-#pragma unroll
-            for (int qt = 0; qt < QT; ++qt)
-#pragma unroll
-                for (int kt = 0; kt < 4; ++kt) sacc[qt][kt] = f4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-#pragma unroll
-                for (int kt = 0; kt < 4; ++kt) {            // four independent accumulators in turn
-                    const h8 a = *reinterpret_cast<const h8 *>(st.K + (kt * 16 + col) * D + ((s * 4 + kg) ^ pf_k_swz(col)) * 8);
-#pragma unroll
-                    for (int qt = 0; qt < QT; ++qt)
-                        sacc[qt][kt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bq[qt][s], sacc[qt][kt], 0, 0, 0);
-                }
-                if (s < PF_NP) fetch_piece(s, stage[(blk + 1) & 1]);   // the next block's loads, a piece per step
-            }
-            fetched = true;
-            __builtin_amdgcn_s_setprio(0);
-            uint32_t msk[QT][16];
-            if constexpr (decltype(masked)::value) make_masks(msk);
-
-            // ---- online softmax per query column; P^T packed as the B operand of the next product ------------
-            h8 bp[QT][2];
-#pragma unroll
-            for (int qt = 0; qt < QT; ++qt) {
-                float sv[16];
-                float mx = SQ_NEG_INF;
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    if constexpr (decltype(masked)::value)
-                        sv[e] = select_bits(msk[qt][e], sacc[qt][e >> 2][e & 3], SQ_NEG_INF);
-                    else
-                        sv[e] = sacc[qt][e >> 2][e & 3];
-                    mx = fmaxf(mx, sv[e]);
-                }
-                mx = cross16_max(mx);                       // the 4 lane groups hold the other keys of the column
-                const float m_new = fmaxf(m_run[qt], mx);
-                const float mneg = m_new == SQ_NEG_INF ? 0.0f : -m_new * c2;   // nothing seen yet: exp2(-inf) = 0
-                // (exactly 1 while the maximum stands still: m * c2 + fl(-m * c2) is the rounding error of the product,
-                // not 0, and a factor 1 - 6e-7 per key block would leak into the running sum and hence into lse)
-                const float alpha = m_new == m_run[qt] ? 1.0f : __builtin_amdgcn_exp2f(fmaf(m_run[qt], c2, mneg));
-                float psum = 0.0f;
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    sv[e] = __builtin_amdgcn_exp2f(fmaf(sv[e], c2, mneg));
-                    psum += sv[e];
-                }
-                m_run[qt] = m_new;
-                l_run[qt] = l_run[qt] * alpha + psum;       // per-lane partial; groups are summed at the end
-                if (__ballot(alpha != 1.0f) != 0ull) {      // the maximum rarely moves once a strong key is seen
-#pragma unroll
-                    for (int dt = 0; dt < 8; ++dt) o[qt][dt] *= alpha;
-                }
-#pragma unroll
-                for (int ks = 0; ks < 2; ++ks) {
-                    h8 bv;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        bv[j] = (_Float16)sv[(2 * ks) * 4 + j];
-                        bv[4 + j] = (_Float16)sv[(2 * ks + 1) * 4 + j];
-                    }
-                    bp[qt][ks] = bv;
-                }
-            }
-
-            // ---- O^T += V^T P^T ------------------------------------------------------------------------------
-            __builtin_amdgcn_s_setprio(3);
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-#pragma unroll
-                for (int dt = 0; dt < 8; ++dt) {
-                    // keys ks*32 + t*16 + kg*4 + (0..3) for t = 0, 1: the order P^T was packed in
-                    const int vrow = ks * 32 + kg * 4 + (col >> 2);      // (vrow + 16 has the same swizzle)
-                    const _Float16 *vp = st.V + vrow * D + ((dt * 2 + ((col & 3) >> 1)) ^ pf_v_swz(vrow)) * 8 + (col & 1) * 4;
-                    const h4 a0 = lds_read_tr16(vp), a1 = lds_read_tr16(vp + 16 * D);
-                    const h8 a = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
-#pragma unroll
-                    for (int qt = 0; qt < QT; ++qt)
-                        o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bp[qt][ks], o[qt][dt], 0, 0, 0);
-                }
-            }
-            __builtin_amdgcn_s_setprio(0);
+    // The key blocks, alternating between the two LDS buffers.  The shared-set form runs the loop unrolled over the
+    // buffers, so that which buffer is read and which is filled are compile-time constants: the compiler can then tell
+    // them apart (no wait for the loads to LDS in front of the V reads) and the swizzled operand addresses are
+    // loop-invariant -- 133 -> 117 us at 32 heads x 1024 tokens, 1/8 of 32K keys kept.  The masked form is faster as a
+    // plain loop (823 us against 896-929 us unrolled: twice the code for a body that already holds five variants of
+    // the block), so the body is kept in a file of its own and included in both loops.
+    if constexpr (SHARED) {
+        auto one_block = [&](int blk, auto par) {
+            PfStage &st = stage[par];
+            PfStage &st_next = stage[par ^ 1];
+#define PF_NEXT_STAGE st_next
+#include "sq_prefill_block.inc"
+#undef PF_NEXT_STAGE
         };
-
-        if (SHARED && !user && j0 + PF_BN <= n_fixed && q0 + BM <= Lq) {
-            // One kept set for every query and a full block of kept keys: nothing to hide, no mask arithmetic.
-            block([&](uint32_t (&)[QT][16]) {}, std::false_type{});
-        } else if (SHARED && !user) {
-            // One kept set for every query: only slots past the kept keys (last block) are hidden.
-            block([&](uint32_t (&msk)[QT][16]) {
-#pragma unroll
-                for (int qt = 0; qt < QT; ++qt)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        const int j = j0 + (e >> 2) * 16 + kg * 4 + (e & 3);
-                        msk[qt][e] = (j < n_fixed && nq[qt] < Lq) ? 0xffffffffu : 0u;
-                    }
-            }, std::true_type{});
-        } else if (!user && info >= 0) {
-            // Fixed context, usual case: bit (cluster - first cluster of the block) of the query's staged window.
-            const uint32_t present = (2u << ((info >> 16) & 31)) - 1u;       // local clusters that occur in the block
-            uint32_t qb[QT];
-            bool any = false;
-#pragma unroll
-            for (int qt = 0; qt < QT; ++qt) {
-                qb[qt] = st.qbits[wave * 16 * QT + qt * 16 + col];
-                any |= (qb[qt] & present) != 0u;
-            }
-            if (__ballot(any) != 0ull) {                    // else: none of this wave's queries kept a cluster of the block
-                block([&](uint32_t (&msk)[QT][16]) {
-                    int bit[16];
-#pragma unroll
-                    for (int kt = 0; kt < 4; ++kt) {
-                        const int4 b4 = *reinterpret_cast<const int4 *>(st.sh + kt * 16 + kg * 4);
-                        bit[kt * 4 + 0] = b4.x;
-                        bit[kt * 4 + 1] = b4.y;
-                        bit[kt * 4 + 2] = b4.z;
-                        bit[kt * 4 + 3] = b4.w;
-                    }
-#pragma unroll
-                    for (int qt = 0; qt < QT; ++qt)
-#pragma unroll
-                        for (int e = 0; e < 16; ++e)
-                            msk[qt][e] = (uint32_t)__builtin_amdgcn_sbfe((int)qb[qt], (uint32_t)bit[e], 1u);
-                }, std::true_type{});
-            }
-        } else if (!user) {
-            // Fixed context, block spanning more than 31 cluster ids: look every bit up in the mask itself.
-            block([&](uint32_t (&msk)[QT][16]) {
-#pragma unroll
-                for (int qt = 0; qt < QT; ++qt) {
-                    const uint32_t *mrow = keep_mask + (row0 + min(nq[qt], Lq - 1)) * W;
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        const int c = st.cid[(e >> 2) * 16 + kg * 4 + (e & 3)];
-                        const bool ok = (unsigned)c < (unsigned)C && nq[qt] < Lq && ((mrow[c >> 5] >> (c & 31)) & 1u);
-                        msk[qt][e] = ok ? 0xffffffffu : 0u;
-                    }
-                }
-            }, std::true_type{});
-        } else if (user && j0 + PF_BN <= U && q0 + BM <= Lq && (!causal_user || j0 + PF_BN - 1 <= q0 + wave * 16 * QT)) {
-            // A full block of user keys that every query of this wave sees (not causal, or wholly in their past).
-            block([&](uint32_t (&)[QT][16]) {}, std::false_type{});
-        } else if (!causal_user || j0 <= q0 + wave * 16 * QT + 16 * QT - 1) {   // else: the block lies in every query's future
-            block([&](uint32_t (&msk)[QT][16]) {
-#pragma unroll
-                for (int qt = 0; qt < QT; ++qt)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        const int j = j0 + (e >> 2) * 16 + kg * 4 + (e & 3);
-                        const bool ok = j < U && nq[qt] < Lq && (!causal_user || j <= nq[qt]);
-                        msk[qt][e] = ok ? 0xffffffffu : 0u;
-                    }
-            }, std::true_type{});
+        for (int blk = 0; blk < nblk; blk += 2) {
+            one_block(blk, std::integral_constant<int, 0>{});
+            if (blk + 1 < nblk) one_block(blk + 1, std::integral_constant<int, 1>{});
         }
-
-        // ---- next block: registers -> the other LDS buffer; one barrier per block --------------------------
-        if (!fetched) fetch_rest(0, stage[(blk + 1) & 1]);  // (this wave skipped the block's products)
-        if (blk + 1 < nblk) {
-            commit(blk + 1, stage[(blk + 1) & 1]);
-            info_cur = pinfo;
+    } else {
+        for (int blk = 0; blk < nblk; ++blk) {
+            PfStage &st = stage[blk & 1];
+#define PF_NEXT_STAGE stage[(blk + 1) & 1]
+#include "sq_prefill_block.inc"
+#undef PF_NEXT_STAGE
         }
-        loads_landed();
-        __syncthreads();
     }
 
     // ---- normalise and store: lane holds query column nq[qt], dims dt*16 + kg*4 + v ---------------------------
