@@ -234,7 +234,7 @@ int sq_decode_step(const sq_shape_t *shape, const void *q,
 /*
  * sq_decode_step for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and error behaviour as
- * sq_decode_step, without the workspace: the step's intermediate state (logits, range records, work list, partial
+ * sq_decode_step, without the workspace: the step's intermediate state (logits, key-index lists, partial
  * results) lives in a device array of SQ_NOALLOC_SCRATCH_BYTES that is part of the library's code object -- one copy
  * per GPU the library runs on, held until the process ends.  The call allocates and frees nothing.  A shape whose
  * sq_workspace_bytes(shape, SQ_CALL_DECODE_STEP) exceeds SQ_NOALLOC_SCRATCH_BYTES is rejected with SQ_ERR_WORKSPACE
