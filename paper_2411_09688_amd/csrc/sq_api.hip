@@ -251,6 +251,7 @@ struct HierWs {
     int32_t *nr1, *nk1;
     float2 *cand_stats;       // per candidate work item: (max, sum N exp(x - max)) of its candidates
     int2 *slice_cnt;          // last level: kept (clusters, keys) per slice of candidates (see launch_cand_select)
+    float2 *row_stat;         // last level: the rows' (maximum, T * D)
     sq::DecodePlan cand;      // work items of candidate fine clusters (chunks of KPC clusters)
 };
 
@@ -266,6 +267,7 @@ HierWs carve_hier(Carver &cv, const sq_shape_t *sh)
     w.nk1 = cv.take<int32_t>(rows);
     w.cand_stats = cv.take<float2>(items);
     w.slice_cnt = cv.take<int2>(rows * sq::cand_slices_for(sh->C));
+    w.row_stat = cv.take<float2>(rows);
     w.cand.rec_cap = sh->C;
     w.cand.L = sh->C;
     w.cand.item_cap = (int)items;
@@ -1039,7 +1041,7 @@ int multilevel_lookup(const char *fn, const sq_shape_t *sh, int n, const Level *
                                     (size_t)rows * ((lv[k].C + 31) / 32));
         if (e != hipSuccess) break;
         if (sliced) {
-            const sq::CandSelect cs{cur.rec, cur.hdr, w.cand_stats, cur.row_items, w.slice_cnt};
+            const sq::CandSelect cs{cur.rec, cur.hdr, w.cand_stats, cur.row_items, w.slice_cnt, w.row_stat};
             e = sq::launch_cand_select(cs, lv[k].thresh, lv[k].mask, n_ranges, n_keys, *klast, rows, sh->H, lv[k].C, s);
             break;
         }

@@ -523,28 +523,37 @@ __device__ __forceinline__ void cand_select_slice(const CandSelect &cs, const fl
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int j = sl * CAND_SLICE + tid;
     const int4 rv = tid < CAND_SLICE && j < n ? cs.rec[(size_t)row * C + j] : make_int4(0, (int)0x80000000u, 0, 0);
-    const int2 ri = n > 0 ? cs.row_items[row] : make_int2(0, 0);   // (first item, items): at most CAND_THREADS items
-    const float2 ms = tid < ri.y ? cs.stats[ri.x + tid] : make_float2(SQ_NEG_INF, 0.0f);
     const int n_sl = (n + CAND_SLICE - 1) / CAND_SLICE;         // slices with candidates: at most 64
     int2 sc = make_int2(0, 0);
-    if (EMIT && tid < n_sl) sc = cs.slice_cnt[(size_t)row * nsl + tid];
-    const float T = thresh[row % H];
-
-    const float mw = wave_max(ms.x);
-    if (lane == 0) s_red[wave] = mw;
-    __syncthreads();
-    float m = s_red[0];
+    float m, thr;                                               // the row's maximum and T * D
+    if constexpr (EMIT) {
+        // (the counting launch left them: the same bits, without the round trip to the items' pairs and three barriers)
+        if (tid < n_sl) sc = cs.slice_cnt[(size_t)row * nsl + tid];
+        const float2 rs = cs.row_stat[row];
+        m = rs.x;
+        thr = rs.y;
+    } else {
+        const int2 ri = n > 0 ? cs.row_items[row] : make_int2(0, 0);   // (first item, items): at most CAND_THREADS items
+        const float2 ms = tid < ri.y ? cs.stats[ri.x + tid] : make_float2(SQ_NEG_INF, 0.0f);
+        const float T = thresh[row % H];
+        const float mw = wave_max(ms.x);
+        if (lane == 0) s_red[wave] = mw;
+        __syncthreads();
+        m = s_red[0];
 #pragma unroll
-    for (int w = 1; w < CAND_ITEM_WAVES; ++w) m = fmaxf(m, s_red[w]);
-    __syncthreads();                                            // s_red is reused
-    const float part = ms.y > 0.0f ? __fmul_rn(ms.y, expf(ms.x - m)) : 0.0f;
-    const float pw = wave_sum(part);
-    if (lane == 0) s_red[wave] = pw;
-    __syncthreads();
-    float Dsum = 0.0f;                                          // the 16 wave sums in ascending order, by every thread
+        for (int w = 1; w < CAND_ITEM_WAVES; ++w) m = fmaxf(m, s_red[w]);
+        __syncthreads();                                        // s_red is reused
+        const float part = ms.y > 0.0f ? __fmul_rn(ms.y, expf(ms.x - m)) : 0.0f;
+        const float pw = wave_sum(part);
+        if (lane == 0) s_red[wave] = pw;
+        __syncthreads();
+        float Dsum = 0.0f;                                      // the 16 wave sums in ascending order, by every thread
 #pragma unroll
-    for (int w = 0; w < CAND_ITEM_WAVES; ++w) Dsum += s_red[w];
-    const bool keep = tid < CAND_SLICE && j < n && rv.y >= 0 && expf(__int_as_float(rv.x) - m) > T * Dsum;
+        for (int w = 0; w < CAND_ITEM_WAVES; ++w) Dsum += s_red[w];
+        thr = T * Dsum;
+        if (sl == 0 && tid == 0) cs.row_stat[row] = make_float2(m, thr);   // for the writing launch
+    }
+    const bool keep = tid < CAND_SLICE && j < n && rv.y >= 0 && expf(__int_as_float(rv.x) - m) > thr;
 
     const unsigned long long bal = __ballot(keep);
     const int kv = keep ? rv.w : 0;

@@ -225,6 +225,7 @@ struct CandSelect {
     const float2 *stats;
     const int2 *row_items;
     int2 *slice_cnt;
+    float2 *row_stat;                  // [rows] scratch: the row's (maximum, T * D), from the counting to the writing launch
 };
 inline int cand_slices_for(int C) { return (C + 255) / 256; }
 hipError_t launch_cand_select(CandSelect cs, const float *thresh, uint32_t *keep_mask, int32_t *n_ranges, int32_t *n_keys,
