@@ -21,8 +21,8 @@ struct Shape {
 //   total     two ints: work items of the whole call, rows that have placed their items
 //   row_rank  per row (may be null): how many rows had placed their items before this one
 //   item      per work item (= one chunk of up to KPC keys of one row) ITEM_STRIDE int2 slots:
-//             slot 0 = (row, keys in the chunk), slot 1 = (records in the chunk or -1 for a chunk of user
-//             keys, first user key), slots 2.. = the chunk's own copy of the range records it touches, as
+//             slot 0 = (row, keys in the chunk), slot 1 = (records in the chunk, position of the chunk's first key
+//             in its row's selection) or, for a chunk of user keys, (-1, first user key), slots 2.. = the chunk's own copy of the range records it touches, as
 //             (position of the record's first key relative to the chunk, fixed-context row of that key
 //             minus that position): key slot t of the chunk lies in the last record whose position is
 //             <= t and reads row t + delta.  This is the key-index tensor of Section 4.2 in run-length

@@ -269,11 +269,11 @@ __global__ __launch_bounds__(256) void gather_score_kernel(const _Float16 *__res
     const int total = min(*cand.total, cand.item_cap);
     for (int item = blockIdx.x; item < total; item += gridDim.x) {
         const int2 *it = cand.item + (size_t)item * ITEM_STRIDE;
-        const int2 h0 = it[0], h1 = it[1];          // (row, clusters in chunk) (records, -)
+        const int2 h0 = it[0], h1 = it[1];          // (row, clusters in chunk) (records, chunk's first candidate in its row)
         const int2 rc = it[2 + (tid < KPC ? tid : 0)];
         const size_t bh = (size_t)h0.x;
         const int h = (int)(bh % H);
-        const int j0 = (item - cand.row_items[bh].x) * KPC;   // this chunk's first candidate within its row
+        const int j0 = h1.y;                        // this chunk's first candidate within its row
         chunk_rows_from_records<KPC>(rc.x, rc.y, min(h1.x, KPC), h0.y, C2, s_pos, s_delta, s_rows, tid);
         __syncthreads();
         h8 bq[4];

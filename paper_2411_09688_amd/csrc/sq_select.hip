@@ -137,7 +137,7 @@ __device__ __forceinline__ void emit_row_items(const DecodePlan &plan, int row, 
             last = n_rec - 1;
         }
         it[0] = make_int2(row, min(KPC, n_sel - c * KPC));
-        it[1] = make_int2(last - s_first[c] + 1, 0);
+        it[1] = make_int2(last - s_first[c] + 1, c * KPC);   // (records, first position of the chunk in its row)
     }
 }
 
@@ -719,7 +719,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
                 last = base_r - 1;
             }
             it[0] = make_int2((int)row, min(KPC, n_sel - c * KPC));
-            it[1] = make_int2(last - first + 1, 0);
+            it[1] = make_int2(last - first + 1, c * KPC);   // (records, first position of the chunk in its row)
         }
     } else if (SCHEDULE) {
         // This row's work items (their base was taken above).  The records written above are read back after
