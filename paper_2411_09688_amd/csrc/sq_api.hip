@@ -401,7 +401,7 @@ PrefillStepWs carve_prefill_step(Carver &cv, const sq_shape_t *sh)
     w.n_ranges = cv.take<int32_t>(rows);
     w.n_keys = cv.take<int32_t>(rows);
     w.key_cid = cv.take<int32_t>((size_t)sh->H * sh->L);
-    w.blk_info = cv.take<int32_t>((size_t)sh->H * ((sh->L + 63) / 64));
+    w.blk_info = cv.take<int32_t>(sq::prefill_blk_info_ints(sh->H, sh->L));
     return w;
 }
 
@@ -503,7 +503,7 @@ size_t sq_workspace_bytes(const sq_shape_t *sh, int which)
         return cv.off;
     case SQ_CALL_ATTN_PREFILL:
         cv.take<int32_t>((size_t)sh->H * sh->L);
-        cv.take<int32_t>((size_t)sh->H * ((sh->L + 63) / 64));
+        cv.take<int32_t>(sq::prefill_blk_info_ints(sh->H, sh->L));
         return cv.off;
     case SQ_CALL_SELECT_MEAN:
         cv.take<float>((size_t)sh->B * sh->H * sq::mean_parts_for(sh->Lq) * sh->C);
@@ -845,7 +845,7 @@ int sq_sparse_attn_prefill(const sq_shape_t *sh, const void *q, const void *K_fi
     if (int rc = check_device(__func__)) return rc;
     Carver cv(ws);
     int32_t *key_cid = cv.take<int32_t>((size_t)sh->H * sh->L);
-    int32_t *blk_info = cv.take<int32_t>((size_t)sh->H * ((sh->L + 63) / 64));
+    int32_t *blk_info = cv.take<int32_t>(sq::prefill_blk_info_ints(sh->H, sh->L));
     SQ_HIP(sq::launch_prefill_attn(q, K_fixed, V_fixed, K_user, V_user, keep_mask, offsets, key_cid, blk_info, out, lse,
                                    to_shape(sh), static_cast<hipStream_t>(stream)));
     g_err[0] = 0;

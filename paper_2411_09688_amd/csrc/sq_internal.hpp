@@ -164,7 +164,13 @@ hipError_t launch_decode_attn_shared(const void *q, const void *Kf, const void *
                                      DecodePlan plan, float *partials, void *out, float *lse, const Shape &sh,
                                      hipStream_t s);
 
-// Prefill attention with per-query keep masks; key_cid [H, L] is workspace for the key -> cluster map.
+// The masked prefill's block table blk_info: an int per (head, 64-key block), then, 8-byte aligned, the 64-bit count of
+// (workgroup, block) pairs in which no query of the workgroup kept a cluster.
+__host__ __device__ inline size_t prefill_skip_count_at(int H, int L) { return ((size_t)H * ((L + 63) / 64) + 1) & ~(size_t)1; }
+inline size_t prefill_blk_info_ints(int H, int L) { return prefill_skip_count_at(H, L) + 2; }
+
+// Prefill attention with per-query keep masks; key_cid [H, L] and blk_info [prefill_blk_info_ints(H, L)] are workspace
+// (the key -> cluster map and the block table).
 hipError_t launch_prefill_attn(const void *q, const void *Kf, const void *Vf, const void *Ku, const void *Vu,
                                const uint32_t *keep_mask, const int32_t *offsets, int32_t *key_cid, int32_t *blk_info,
                                void *out, float *lse, const Shape &sh, hipStream_t s);

@@ -19,7 +19,10 @@
 //     bits that covers its clusters, the bit of a (query, key) pair is spread over a word with one signed
 //     bit-field extract and blended into the score with one bit-select, and a wave skips the products of a
 //     block none of its queries kept.  The mask arithmetic is issued behind the S^T products, in the same
-//     straight-line block, so the vector ALU works while the matrix cores do.
+//     straight-line block, so the vector ALU works while the matrix cores do;
+//   * the masked form exists twice: a kernel that walks every key block, and one that first lists, per workgroup, the
+//     blocks in which at least one of its queries kept a cluster and walks only those.  A counting launch decides which
+//     of the two does the work (see PF_LIST_MIN_SHARE).
 // The user block is causal when causal_user is set (query t sees user keys 0..t); the fixed context is
 // always fully visible.
 //
@@ -72,6 +75,8 @@ __global__ __launch_bounds__(256) void block_info_kernel(const int32_t *__restri
 {
     const int h = blockIdx.y;
     const int blk = blockIdx.x * 256 + threadIdx.x;
+    if (h == 0 && blk == 0)                              // the count of skippable (workgroup, block) pairs, behind the table
+        *reinterpret_cast<unsigned long long *>(blk_info + prefill_skip_count_at((int)gridDim.y, L)) = 0ull;
     if (blk >= nblk) return;
     const int first = max(0, min(cid[(size_t)h * L + blk * PF_BN], C - 1));
     const int last = max(first, min(cid[(size_t)h * L + min(L, (blk + 1) * PF_BN) - 1], C - 1));
@@ -93,6 +98,70 @@ __global__ __launch_bounds__(256) void expand_ranges_kernel(DecodePlan plan, int
         const int4 rc = plan.rec[row * plan.rec_cap + r];
         for (int j = lane; j < rc.y && rc.z + j < L; j += 64) dst[rc.z + j] = max(0, min(rc.x + j, L - 1));
     }
+}
+
+// Masked form, two kernels for the same work.  The plain one walks every fixed-context block (a wave still skips the
+// products of a block none of its queries kept).  The listed one first builds, in LDS, the ordered list of the blocks in
+// which at least one query of the workgroup kept a cluster and walks only those (Section 4.2: the work follows the kept
+// set, not the context length): blocks nobody kept are neither fetched nor staged nor waited for at a barrier.  Walking
+// through the list costs about 6% when nothing can be skipped (883 against 833 us at 32 heads x 1024 tokens x 32K keys,
+// 1/8 kept per query), so a counting launch in front adds up the (workgroup, block) pairs that can be skipped; both
+// kernels are then launched and each returns at once unless the count picks it (listed: an eighth of the pairs or more).
+constexpr int PF_LIST_CAP = 4096;         // blocks (256K keys); longer contexts take the plain kernel
+constexpr int PF_UMASK_WORDS = SELECT_MAX_C / 32;
+constexpr size_t PF_LIST_BYTES = PF_UMASK_WORDS * 4 + PF_LIST_CAP * 2;
+constexpr int PF_LIST_MIN_SHARE = 8;      // listed kernel iff skippable pairs * 8 >= all pairs
+
+// s_um[0..W) |= keep masks of queries q0 .. q0+bm-1 (those below Lq) of query rows row0...; s_um zeroed by the caller,
+// barrier after it by the caller.  A mask word of eight queries per item: eight independent loads, one LDS atomic.
+__device__ __forceinline__ void pf_union_mask(uint32_t *s_um, const uint32_t *__restrict__ keep_mask, size_t row0, int q0,
+                                              int bm, int Lq, int W, int tid, int threads)
+{
+    for (int idx = tid; idx < (bm / 8) * W; idx += threads) {
+        const int g = idx / W, w = idx - g * W;
+        uint32_t acc = 0u;
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            if (q0 + g * 8 + k < Lq) acc |= keep_mask[(row0 + q0 + g * 8 + k) * W + w];
+        if (acc) atomicOr(&s_um[w], acc);
+    }
+}
+
+// Does a workgroup whose queries' masks OR to s_um need the block with table entry bi?  (A block that spans more
+// cluster ids than the staged window is not decided here: needed.)
+__device__ __forceinline__ bool pf_block_needed(int bi, const uint32_t *s_um, int W)
+{
+    if (bi < 0) return true;
+    const int first = bi & 0xffff, w0 = first >> 5;
+    const unsigned long long two = ((unsigned long long)(w0 + 1 < W ? s_um[w0 + 1] : 0u) << 32) | s_um[w0];
+    const uint32_t present = (2u << ((bi >> 16) & 31)) - 1u;   // local clusters that occur in the block
+    return ((uint32_t)(two >> (first & 31)) & present) != 0u;
+}
+
+// The counting launch: one workgroup per query block of the masked kernels, *skip_count += blocks it can skip.
+__global__ __launch_bounds__(256) void prefill_need_kernel(const uint32_t *__restrict__ keep_mask,
+                                                           const int32_t *__restrict__ blk_info,
+                                                           unsigned long long *__restrict__ skip_count, int B, int H,
+                                                           int L, int C, int Lq, int bm)
+{
+    __shared__ uint32_t s_um[PF_UMASK_WORDS];
+    __shared__ int s_cnt;
+    const int tid = threadIdx.x;
+    const int nqb = (Lq + bm - 1) / bm, unit = blockIdx.x;
+    const int h = unit / (nqb * B), b = (unit / nqb) % B, q0 = (unit % nqb) * bm;
+    const int W = (C + 31) >> 5, nblk = (L + PF_BN - 1) / PF_BN;
+    const size_t row0 = ((size_t)b * H + h) * Lq;
+    for (int w = tid; w < W; w += 256) s_um[w] = 0u;
+    if (tid == 0) s_cnt = 0;
+    __syncthreads();
+    pf_union_mask(s_um, keep_mask, row0, q0, bm, Lq, W, tid, 256);
+    __syncthreads();
+    int skip = 0;
+    for (int bb = tid; bb < nblk; bb += 256) skip += pf_block_needed(blk_info[(size_t)h * nblk + bb], s_um, W) ? 0 : 1;
+    for (int o = 32; o; o >>= 1) skip += __shfl_xor(skip, o);
+    if ((tid & 63) == 0 && skip) atomicAdd(&s_cnt, skip);
+    __syncthreads();
+    if (tid == 0 && s_cnt) atomicAdd(skip_count, (unsigned long long)s_cnt);
 }
 
 constexpr int PF_QT = 1;                  // 16-query tiles per wave
@@ -120,7 +189,7 @@ __device__ __forceinline__ float select_bits(uint32_t mask, float a, float b)
 
 // SHARED: key_cid is the key-row list [B*H, L] and blk_info the per-row (records, kept keys) headers; keep_mask is
 // not used.
-template <bool SHARED>
+template <bool SHARED, bool LISTED>
 __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void prefill_attn_kernel(
     const _Float16 *__restrict__ q, const _Float16 *__restrict__ Kf, const _Float16 *__restrict__ Vf,
     const _Float16 *__restrict__ Ku, const _Float16 *__restrict__ Vu, const uint32_t *__restrict__ keep_mask,
@@ -143,6 +212,14 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
     const int per_xcd = gridDim.x >> 3;                   // grid is a multiple of 8
     const int unit = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (unit >= nqb * B * H) return;
+    if constexpr (!SHARED) {
+        // Which of the two masked kernels does the work: the listed one iff enough (workgroup, block) pairs can be skipped.
+        const int nblk_all = (L + PF_BN - 1) / PF_BN;
+        const unsigned long long skip = *reinterpret_cast<const unsigned long long *>(blk_info + prefill_skip_count_at(H, L));
+        const bool by_list = nblk_all <= PF_LIST_CAP && skip > 0ull &&
+                             skip * PF_LIST_MIN_SHARE >= (unsigned long long)(nqb * B * H) * (unsigned long long)nblk_all;
+        if (by_list != LISTED) return;
+    }
     const int h = unit / (nqb * B), b = (unit / nqb) % B;
     const int q0 = (unit % nqb) * BM;                     // first query of the workgroup
     const int W = (C + 31) >> 5;
@@ -290,15 +367,53 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
 #pragma unroll
         for (int i = 0; i < PF_NP; ++i) ik_c[i] = ik_n[i];
     };
+    // ---- listed form: the blocks this workgroup has to walk, in order ------------------------------------------------
+    // s_um = OR of the keep masks of the workgroup's queries; s_list = the fixed blocks it needs.
+    uint32_t *s_um = reinterpret_cast<uint32_t *>(smem + 2 * sizeof(PfStage));
+    uint16_t *s_list = reinterpret_cast<uint16_t *>(s_um + PF_UMASK_WORDS);
+    int n_list = nblk_fixed;
+    if constexpr (LISTED) {
+        __shared__ int s_wc[PF_THREADS / 64];
+        for (int w = tid; w < W; w += PF_THREADS) s_um[w] = 0u;
+        __syncthreads();
+        pf_union_mask(s_um, keep_mask, row0, q0, BM, Lq, W, tid, PF_THREADS);
+        __syncthreads();
+        int base = 0;
+        for (int b0 = 0; b0 < nblk_fixed; b0 += PF_THREADS) {   // in order: a ballot per wave, the waves' counts in LDS
+            const int bb = b0 + tid;
+            const bool need = bb < nblk_fixed && pf_block_needed(binfo[bb], s_um, W);
+            const unsigned long long bal = __ballot(need);
+            if (lane == 0) s_wc[wave] = __popcll(bal);
+            __syncthreads();
+            int before = 0, total = 0;
+#pragma unroll
+            for (int w = 0; w < PF_THREADS / 64; ++w) {
+                if (w < wave) before += s_wc[w];
+                total += s_wc[w];
+            }
+            if (need)
+                s_list[base + before + __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0))] = (uint16_t)bb;
+            base += total;
+            __syncthreads();
+        }
+        n_list = __builtin_amdgcn_readfirstlane(base);
+    }
+    // The blocks in walking order: the (listed) fixed blocks, then the user blocks.
+    const int n_seq = n_list + (nblk - nblk_fixed);
+    // (the same in every lane: made scalar, or every address and branch that hangs on it would be done per lane)
+    auto blk_at = [&](int i) {
+        return i < n_list ? (LISTED ? __builtin_amdgcn_readfirstlane((int)s_list[i]) : i) : nblk_fixed + (i - n_list);
+    };
+
     int info_cur = 0;
-    if (nblk > 0) {                                       // (no kept key and no user key: nothing to stage)
+    if (n_seq > 0) {                                      // (no kept key and no user key: nothing to stage)
         fetch_idx(0);
         take_idx();
         fetch_idx(1);
-        aim(0);
+        aim(blk_at(0));
         fetch_rest(0, stage[0]);
         info_cur = pinfo;
-        commit(0, stage[0]);
+        commit(blk_at(0), stage[0]);
     }
     loads_landed();
     __syncthreads();
@@ -308,25 +423,81 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
     // them apart (no wait for the loads to LDS in front of the V reads) and the swizzled operand addresses are
     // loop-invariant -- 133 -> 117 us at 32 heads x 1024 tokens, 1/8 of 32K keys kept.  The masked form is faster as a
     // plain loop (823 us against 896-929 us unrolled: twice the code for a body that already holds five variants of
-    // the block), so the body is kept in a file of its own and included in both loops.
+    // the block), so the body is kept in a file of its own and included in each loop.
     if constexpr (SHARED) {
         auto one_block = [&](int blk, auto par) {
             PfStage &st = stage[par];
             PfStage &st_next = stage[par ^ 1];
+#define PF_USER(b) ((b) >= nblk_fixed)
 #define PF_NEXT_STAGE st_next
+#define PF_HAS_NEXT (blk + 1 < nblk)
+#define PF_NEXT_BLK (blk + 1)
+#define PF_FETCH_IDX_AHEAD if (blk + 2 < nblk) fetch_idx(blk + 2)
 #include "sq_prefill_block.inc"
+#undef PF_FETCH_IDX_AHEAD
+#undef PF_NEXT_BLK
+#undef PF_HAS_NEXT
 #undef PF_NEXT_STAGE
+#undef PF_USER
         };
         for (int blk = 0; blk < nblk; blk += 2) {
             one_block(blk, std::integral_constant<int, 0>{});
             if (blk + 1 < nblk) one_block(blk + 1, std::integral_constant<int, 1>{});
         }
-    } else {
+    } else if constexpr (!LISTED) {
         for (int blk = 0; blk < nblk; ++blk) {
             PfStage &st = stage[blk & 1];
+#define PF_USER(b) ((b) >= nblk_fixed)
 #define PF_NEXT_STAGE stage[(blk + 1) & 1]
+#define PF_HAS_NEXT (blk + 1 < nblk)
+#define PF_NEXT_BLK (blk + 1)
+#define PF_FETCH_IDX_AHEAD (void)0
 #include "sq_prefill_block.inc"
+#undef PF_FETCH_IDX_AHEAD
+#undef PF_NEXT_BLK
+#undef PF_HAS_NEXT
 #undef PF_NEXT_STAGE
+#undef PF_USER
+        }
+    } else {
+        // Two loops, fixed blocks then user blocks: each then holds only its own forms of the block, and what only the
+        // other needs (base pointers, lengths) is not kept in registers through it.
+        // (The list is read two blocks ahead and made scalar only after the block: the entry heads the address chain
+        // of the next block's loads, and nothing in front of the block's own work waits for it.)
+        int blk_cur = n_list > 0 ? blk_at(0) : 0, blk_ahead = n_seq > 1 ? blk_at(1) : 0;
+        for (int it = 0; it < n_list; ++it) {
+            const int blk = blk_cur, blk_nx = blk_ahead;
+            int ahead_v = 0;
+            if (it + 2 < n_seq) ahead_v = it + 2 < n_list ? (int)s_list[it + 2] : nblk_fixed + (it + 2 - n_list);
+            PfStage &st = stage[it & 1];
+#define PF_USER(b) false
+#define PF_NEXT_STAGE stage[(it + 1) & 1]
+#define PF_HAS_NEXT (it + 1 < n_seq)
+#define PF_NEXT_BLK blk_nx
+#define PF_FETCH_IDX_AHEAD (void)0
+#include "sq_prefill_block.inc"
+#undef PF_FETCH_IDX_AHEAD
+#undef PF_NEXT_BLK
+#undef PF_HAS_NEXT
+#undef PF_NEXT_STAGE
+#undef PF_USER
+            blk_cur = blk_nx;
+            blk_ahead = __builtin_amdgcn_readfirstlane(ahead_v);
+        }
+        for (int it = n_list; it < n_seq; ++it) {
+            const int blk = nblk_fixed + (it - n_list);
+            PfStage &st = stage[it & 1];
+#define PF_USER(b) true
+#define PF_NEXT_STAGE stage[(it + 1) & 1]
+#define PF_HAS_NEXT (it + 1 < n_seq)
+#define PF_NEXT_BLK (blk + 1)
+#define PF_FETCH_IDX_AHEAD (void)0
+#include "sq_prefill_block.inc"
+#undef PF_FETCH_IDX_AHEAD
+#undef PF_NEXT_BLK
+#undef PF_HAS_NEXT
+#undef PF_NEXT_STAGE
+#undef PF_USER
         }
     }
 
@@ -351,15 +522,16 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
 
 namespace {
 
-template <bool SHARED>
+// ev0 / ev1: profiling events recorded in front of / behind the launch (either may be null).
+template <bool SHARED, bool LISTED>
 hipError_t launch_prefill_kernel(const void *q, const void *Kf, const void *Vf, const void *Ku, const void *Vu,
                                  const uint32_t *keep_mask, const int32_t *key_cid, const int32_t *blk_info, void *out,
-                                 float *lse, const Shape &sh, hipStream_t s)
+                                 float *lse, const Shape &sh, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1)
 {
-    const size_t smem = 2 * sizeof(PfStage);
+    const size_t smem = 2 * sizeof(PfStage) + (LISTED ? PF_LIST_BYTES : 0);
     static bool attr_set = false;   // one GPU per process in this build
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(prefill_attn_kernel<SHARED>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(prefill_attn_kernel<SHARED, LISTED>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -367,14 +539,13 @@ hipError_t launch_prefill_kernel(const void *q, const void *Kf, const void *Vf, 
     constexpr int PF_BM = pf_bm(SHARED), PF_THREADS = 64 * pf_waves(SHARED);
     const int units = ((sh.Lq + PF_BM - 1) / PF_BM) * sh.H * sh.B;
     dim3 grid((units + 7) / 8 * 8);
-    hipEvent_t ev0, ev1;
-    if (profile_pair(&ev0, &ev1))
-        hipExtLaunchKernelGGL(prefill_attn_kernel<SHARED>, grid, dim3(PF_THREADS), (uint32_t)smem, s, ev0, ev1, 0,
-                              (const _Float16 *)q, (const _Float16 *)Kf, (const _Float16 *)Vf, (const _Float16 *)Ku,
+    if (ev0 || ev1)
+        hipExtLaunchKernelGGL((prefill_attn_kernel<SHARED, LISTED>), grid, dim3(PF_THREADS), (uint32_t)smem, s, ev0, ev1,
+                              0, (const _Float16 *)q, (const _Float16 *)Kf, (const _Float16 *)Vf, (const _Float16 *)Ku,
                               (const _Float16 *)Vu, keep_mask, key_cid, blk_info, (_Float16 *)out, lse, sh.B, sh.H, sh.L,
                               sh.C, sh.Lq, sh.U, sh.causal_user, sh.sm_scale);
     else
-        hipLaunchKernelGGL(prefill_attn_kernel<SHARED>, grid, dim3(PF_THREADS), smem, s, (const _Float16 *)q,
+        hipLaunchKernelGGL((prefill_attn_kernel<SHARED, LISTED>), grid, dim3(PF_THREADS), smem, s, (const _Float16 *)q,
                            (const _Float16 *)Kf, (const _Float16 *)Vf, (const _Float16 *)Ku, (const _Float16 *)Vu,
                            keep_mask, key_cid, blk_info, (_Float16 *)out, lse, sh.B, sh.H, sh.L, sh.C, sh.Lq, sh.U,
                            sh.causal_user, sh.sm_scale);
@@ -393,7 +564,23 @@ hipError_t launch_prefill_attn(const void *q, const void *Kf, const void *Vf, co
                        sh.L, nblk);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return launch_prefill_kernel<false>(q, Kf, Vf, Ku, Vu, keep_mask, key_cid, blk_info, out, lse, sh, s);
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    profile_pair(&ev0, &ev1);                            // (the pair brackets both attention launches)
+    const bool may_list = nblk <= PF_LIST_CAP;           // else the count stays 0 and the plain kernel does the work
+    if (may_list) {
+        constexpr int BM = pf_bm(false);
+        const int units = ((sh.Lq + BM - 1) / BM) * sh.H * sh.B;
+        hipLaunchKernelGGL(prefill_need_kernel, dim3(units), dim3(256), 0, s, keep_mask, blk_info,
+                           reinterpret_cast<unsigned long long *>(blk_info + prefill_skip_count_at(sh.H, sh.L)), sh.B, sh.H,
+                           sh.L, sh.C, sh.Lq, BM);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    e = launch_prefill_kernel<false, false>(q, Kf, Vf, Ku, Vu, keep_mask, key_cid, blk_info, out, lse, sh, s, ev0,
+                                            may_list ? nullptr : ev1);
+    if (e != hipSuccess || !may_list) return e;
+    return launch_prefill_kernel<false, true>(q, Kf, Vf, Ku, Vu, keep_mask, key_cid, blk_info, out, lse, sh, s, nullptr,
+                                              ev1);
 }
 
 hipError_t launch_expand_ranges(DecodePlan plan, int32_t *idx, int rows, int L, hipStream_t s)
@@ -409,8 +596,10 @@ hipError_t launch_prefill_attn_shared(const void *q, const void *Kf, const void 
     hipLaunchKernelGGL(expand_ranges_kernel, dim3(sh.B * sh.H, EXPAND_SLICES), dim3(256), 0, s, plan, key_idx, sh.L);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return launch_prefill_kernel<true>(q, Kf, Vf, Ku, Vu, nullptr, key_idx, reinterpret_cast<const int32_t *>(plan.hdr),
-                                       out, lse, sh, s);
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    profile_pair(&ev0, &ev1);
+    return launch_prefill_kernel<true, false>(q, Kf, Vf, Ku, Vu, nullptr, key_idx,
+                                              reinterpret_cast<const int32_t *>(plan.hdr), out, lse, sh, s, ev0, ev1);
 }
 
 }  // namespace sq

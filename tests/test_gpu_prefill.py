@@ -91,6 +91,72 @@ def test_prefill_empty_and_keep_all(sq, oracle):
         assert np.abs(P.out[0, h, t].cpu().numpy().astype(np.float64) - ref[0]).max() <= ATTN_ATOL
 
 
+def banded_keep(w, rng, band, extra, qb=64):
+    """Keep sets that follow the query's position: the 64 queries of a query block share a band of clusters (plus
+    `extra` stray clusters per block, and a few queries that keep nothing), so most key blocks are kept by no
+    query of the block."""
+    gk = np.zeros((w.B, w.H, w.Lq, w.C), bool)
+    for b in range(w.B):
+        for h in range(w.H):
+            for g in range(0, w.Lq, qb):
+                lo = int(rng.integers(0, max(1, w.C - band)))
+                stray = rng.integers(0, w.C, size=extra)
+                for t in range(g, min(g + qb, w.Lq)):
+                    if rng.random() < 0.05:
+                        continue
+                    a = lo + int(rng.integers(0, band // 2)); e = a + int(rng.integers(1, band // 2 + 1))
+                    gk[b, h, t, a:e] = True
+                    if extra:
+                        gk[b, h, t, stray[rng.integers(0, extra)]] = True
+    return gk
+
+
+@pytest.mark.parametrize("case", [
+    dict(B=1, H=2, L=8192, C=512, Lq=200, U=64, band=48, extra=2, causal_user=True),
+    dict(B=2, H=2, L=5000, C=300, Lq=130, U=0, band=30, extra=0, causal_user=False),      # ragged, no user keys
+    dict(B=1, H=1, L=4096, C=4096, Lq=64, U=40, band=400, extra=3, causal_user=True),     # empty clusters: wide blocks
+    dict(B=1, H=2, L=40000, C=2000, Lq=100, U=30, band=150, extra=4, causal_user=True),   # 625 key blocks: the list is built in rounds
+])
+def test_prefill_masks_that_follow_position(sq, oracle, case):
+    """Explicit keep masks under which most (query block, key block) pairs hold no kept key: the kernel that walks only
+    the listed blocks does the work (its rule: an eighth of the pairs or more can be skipped)."""
+    case = dict(case); band = case.pop("band"); extra = case.pop("extra")
+    w = wl.make_workload("prefill_banded", seed=23, threads=2, keep_frac=0.1, **case)
+    rng = np.random.default_rng(5)
+    gk = banded_keep(w, rng, band, extra)
+    # share of (query block, key block) pairs without a kept key
+    nblk = (w.L + 63) // 64
+    skip = tot = 0
+    for h in range(w.H):
+        cid = np.repeat(np.arange(w.C), w.sizes[h])
+        for b in range(w.B):
+            for g in range(0, w.Lq, 64):
+                kept_keys = gk[b, h, g:g + 64].any(0)[cid]
+                need = np.add.reduceat(kept_keys, np.arange(0, w.L, 64)) > 0
+                skip += nblk - int(need.sum()); tot += nblk
+    assert skip * 8 >= tot, (skip, tot)
+    W = (w.C + 31) // 32
+    bits = np.zeros((w.B, w.H, w.Lq, W * 32), bool); bits[..., :w.C] = gk
+    words = (bits.reshape(w.B, w.H, w.Lq, W, 32) * (1 << np.arange(32, dtype=np.uint64))).sum(-1).astype(np.uint32)
+    P = sq.upload(w)
+    P.keep_mask.copy_(torch.from_numpy(words.view(np.int32)))
+    ws = sq.workspace(P.shape, sq.SQ_CALL_ATTN_PREFILL, P.q.device)
+    sq.sq_sparse_attn_prefill(P.shape, P.q, P.K_fixed, P.V_fixed, P.offsets, P.keep_mask, P.K_user, P.V_user, P.out,
+                              P.lse, ws)
+    torch.cuda.synchronize()
+    R = (w.B, w.H, w.Lq)
+    cap = int(gk.sum(-1).max()) + 1
+    ranges = np.zeros((*R, cap, 2), np.int32); n_r = np.zeros(R, np.int32)
+    for b, h, t in np.ndindex(*R):
+        ranges[b, h, t], n_r[b, h, t] = ranges_from_keep(gk[b, h, t], w.offsets[h], w.sizes[h], cap)
+    out, lse = oracle.sparse_attn(w.q, w.K_fixed, w.V_fixed, ranges, n_r, w.K_user, w.V_user, w.sm_scale,
+                                  causal_user=w.causal_user)
+    err = np.abs(P.out.cpu().numpy().astype(np.float64) - out).max()
+    assert err <= ATTN_ATOL, f"{case}: attention max-abs error {err}"
+    np.testing.assert_allclose(P.lse.cpu().numpy(), lse, atol=2e-4, rtol=1e-5)
+    print(f"banded {case}: skippable pairs {skip}/{tot}, max-abs err {err:.2e}", flush=True)
+
+
 def test_cfg4_sparse_prefill_32k(sq, oracle):
     print("cfg4: generating", flush=True)
     w = wl.calibrate(wl.make_config("cfg4_prefill_32k", threads=16), oracle.scores)
