@@ -433,7 +433,9 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
 #define PF_HAS_NEXT (blk + 1 < nblk)
 #define PF_NEXT_BLK (blk + 1)
 #define PF_FETCH_IDX_AHEAD if (blk + 2 < nblk) fetch_idx(blk + 2)
+#define PF_OPERANDS_AHEAD 0
 #include "sq_prefill_block.inc"
+#undef PF_OPERANDS_AHEAD
 #undef PF_FETCH_IDX_AHEAD
 #undef PF_NEXT_BLK
 #undef PF_HAS_NEXT
@@ -452,7 +454,9 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
 #define PF_HAS_NEXT (blk + 1 < nblk)
 #define PF_NEXT_BLK (blk + 1)
 #define PF_FETCH_IDX_AHEAD (void)0
+#define PF_OPERANDS_AHEAD 3
 #include "sq_prefill_block.inc"
+#undef PF_OPERANDS_AHEAD
 #undef PF_FETCH_IDX_AHEAD
 #undef PF_NEXT_BLK
 #undef PF_HAS_NEXT
@@ -475,7 +479,9 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
 #define PF_HAS_NEXT (it + 1 < n_seq)
 #define PF_NEXT_BLK blk_nx
 #define PF_FETCH_IDX_AHEAD (void)0
+#define PF_OPERANDS_AHEAD 3
 #include "sq_prefill_block.inc"
+#undef PF_OPERANDS_AHEAD
 #undef PF_FETCH_IDX_AHEAD
 #undef PF_NEXT_BLK
 #undef PF_HAS_NEXT
@@ -492,7 +498,9 @@ __global__ __launch_bounds__(64 * pf_waves(SHARED), 8 / pf_waves(SHARED)) void p
 #define PF_HAS_NEXT (it + 1 < n_seq)
 #define PF_NEXT_BLK (blk + 1)
 #define PF_FETCH_IDX_AHEAD (void)0
+#define PF_OPERANDS_AHEAD 3
 #include "sq_prefill_block.inc"
+#undef PF_OPERANDS_AHEAD
 #undef PF_FETCH_IDX_AHEAD
 #undef PF_NEXT_BLK
 #undef PF_HAS_NEXT
