@@ -114,16 +114,19 @@ def banded_keep(w, rng, band, extra, qb=64):
 @pytest.mark.parametrize("case", [
     dict(B=1, H=2, L=8192, C=512, Lq=200, U=64, band=48, extra=2, causal_user=True),
     dict(B=2, H=2, L=5000, C=300, Lq=130, U=0, band=30, extra=0, causal_user=False),      # ragged, no user keys
+    dict(B=1, H=2, L=5000, C=300, Lq=200, U=0, band=30, extra=0, causal_user=False, blank=(64, 128)),   # a query block with nothing to attend to
     dict(B=1, H=1, L=4096, C=4096, Lq=64, U=40, band=400, extra=3, causal_user=True),     # empty clusters: wide blocks
     dict(B=1, H=2, L=40000, C=2000, Lq=100, U=30, band=150, extra=4, causal_user=True),   # 625 key blocks: the list is built in rounds
 ])
 def test_prefill_masks_that_follow_position(sq, oracle, case):
     """Explicit keep masks under which most (query block, key block) pairs hold no kept key: the kernel that walks only
     the listed blocks does the work (its rule: an eighth of the pairs or more can be skipped)."""
-    case = dict(case); band = case.pop("band"); extra = case.pop("extra")
+    case = dict(case); band = case.pop("band"); extra = case.pop("extra"); blank = case.pop("blank", None)
     w = wl.make_workload("prefill_banded", seed=23, threads=2, keep_frac=0.1, **case)
     rng = np.random.default_rng(5)
     gk = banded_keep(w, rng, band, extra)
+    if blank:
+        gk[:, :, blank[0]:blank[1]] = False
     # share of (query block, key block) pairs without a kept key
     nblk = (w.L + 63) // 64
     skip = tot = 0
