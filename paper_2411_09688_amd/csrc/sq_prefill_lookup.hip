@@ -33,7 +33,10 @@ constexpr int LK_STRIDE = D + 8;             // halves per centroid row in LDS (
 
 struct LkStage {
     _Float16 Ct[LK_G * LK_STRIDE];
-    int N[LK_G];
+    int N[LK_G];                             // cluster sizes
+    float bias[LK_G];                        // 0 for a cluster with keys, -inf for one without (or past the end): the
+                                             // score products start from it, so such a cluster's logit is -inf and
+                                             // it drops out of maximum, normaliser and scores without a test
     int P[LK_G];                             // parent coarse cluster (PARENTS only)
 };
 
@@ -102,6 +105,7 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
             *reinterpret_cast<h8 *>(st.Ct + (i * 16 + (tid >> 4)) * LK_STRIDE + (tid & 15) * 8) = pk[i];
         if (tid < LK_G) {
             st.N[tid] = pn;
+            st.bias[tid] = pn > 0 ? 0.0f : SQ_NEG_INF;
             if (PARENTS) st.P[tid] = pp;
         }
     };
@@ -109,7 +113,7 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
     auto scores = [&](const LkStage &st, float (&x)[LK_TU][4], int (&nv)[LK_TU][4]) {
 #pragma unroll
         for (int u = 0; u < LK_TU; ++u) {
-            f4 acc = {0.f, 0.f, 0.f, 0.f};
+            f4 acc = *reinterpret_cast<const f4 *>(st.bias + u * 16 + kg * 4);
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
                 const h8 a = *reinterpret_cast<const h8 *>(st.Ct + (u * 16 + col) * LK_STRIDE + s * 32 + kg * 8);
@@ -126,14 +130,17 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
                 const int pv[4] = {p4.x, p4.y, p4.z, p4.w};
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
-                    if (!((mrow[pv[v] >> 5] >> (pv[v] & 31)) & 1u)) nv[u][v] = 0;
+                    if (!((mrow[pv[v] >> 5] >> (pv[v] & 31)) & 1u)) {
+                        nv[u][v] = 0;
+                        acc[v] = SQ_NEG_INF;
+                    }
             }
 #pragma unroll
-            for (int v = 0; v < 4; ++v) x[u][v] = acc[v] * sm_scale;
+            for (int v = 0; v < 4; ++v) x[u][v] = acc[v] * sm_scale;   // (-inf stays -inf: sm_scale > 0)
         }
     };
 
-    float m = SQ_NEG_INF, Dsum = 0.0f, thr = 0.0f, inv_D = 0.0f;
+    float m = SQ_NEG_INF, Dsum = 0.0f, thr = 0.0f, inv_D = 0.0f, m_ref = 0.0f;
     uint32_t word = 0u;
     int cnt = 0, keys = 0;
     const int part = q0 / LOOKUP_ROWS, n_part = lookup_parts_for(Lq);
@@ -154,19 +161,18 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
         scores(stage[it & 1], x, nv);
         if (it < ng) {
             // ---- pass 1: m = max over clusters with keys, D = sum N_i exp(x_i - m), per token ---------------------
+            // (a cluster without keys has x = -inf: it does not move the maximum and adds 0 * exp(-inf) = +0)
             float mt = m;
 #pragma unroll
             for (int u = 0; u < LK_TU; ++u)
 #pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    if (nv[u][v] > 0) mt = fmaxf(mt, x[u][v]);
+                for (int v = 0; v < 4; ++v) mt = fmaxf(mt, x[u][v]);
             if (mt != SQ_NEG_INF) {
                 Dsum *= __expf(m - mt);                      // m = -inf: Dsum is 0 and stays 0
 #pragma unroll
                 for (int u = 0; u < LK_TU; ++u)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v)
-                        if (nv[u][v] > 0) Dsum += (float)nv[u][v] * __expf(x[u][v] - mt);
+                    for (int v = 0; v < 4; ++v) Dsum += (float)nv[u][v] * __expf(x[u][v] - mt);
                 m = mt;
             }
             if (it == ng - 1) {                              // the four lane groups hold the other clusters of the token
@@ -181,6 +187,7 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
                 }
                 thr = thresh[h] * Dsum;
                 inv_D = valid && Dsum > 0.0f ? 1.0f / Dsum : 0.0f;   // scores of pass 2: e * (1 / D), one division per token
+                m_ref = m == SQ_NEG_INF ? 0.0f : m;          // (no cluster with keys at all: exp(-inf - 0) = 0, not NaN)
             }
         } else {
             // ---- pass 2: the same logits again, now as scores ---------------------------------------------------------
@@ -190,7 +197,7 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
                 if (t >= nt) break;                          // workgroup-uniform
                 float e[4];
 #pragma unroll
-                for (int v = 0; v < 4; ++v) e[v] = nv[u][v] > 0 ? __expf(x[u][v] - m) : 0.0f;
+                for (int v = 0; v < 4; ++v) e[v] = __expf(x[u][v] - m_ref);   // 0 for a cluster without keys
                 if (!MEAN) {
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
