@@ -33,7 +33,7 @@ constexpr int LK_STRIDE = D + 8;             // halves per centroid row in LDS (
 
 struct LkStage {
     _Float16 Ct[LK_G * LK_STRIDE];
-    int N[LK_G];                             // cluster sizes
+    float Wt[LK_G];                          // cluster sizes as floats (exact: a head has fewer than 2^24 keys)
     float bias[LK_G];                        // 0 for a cluster with keys, -inf for one without (or past the end): the
                                              // score products start from it, so such a cluster's logit is -inf and
                                              // it drops out of maximum, normaliser and scores without a test
@@ -104,13 +104,15 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
         for (int i = 0; i < 4; ++i)
             *reinterpret_cast<h8 *>(st.Ct + (i * 16 + (tid >> 4)) * LK_STRIDE + (tid & 15) * 8) = pk[i];
         if (tid < LK_G) {
-            st.N[tid] = pn;
+            st.Wt[tid] = (float)pn;
             st.bias[tid] = pn > 0 ? 0.0f : SQ_NEG_INF;
             if (PARENTS) st.P[tid] = pp;
         }
     };
-    // Logits of the staged group: x[u][v] = sm_scale * q . C_c, c = g*64 + u*16 + kg*4 + v, and the cluster sizes.
-    auto scores = [&](const LkStage &st, float (&x)[LK_TU][4], int (&nv)[LK_TU][4]) {
+    const float c2 = sm_scale * 1.44269504088896341f;
+    // Logits of the staged group in units of log 2 (the exponentials below are base-2: one instruction each):
+    // x[u][v] = sm_scale * log2(e) * q . C_c, c = g*64 + u*16 + kg*4 + v, and the cluster sizes.
+    auto scores = [&](const LkStage &st, float (&x)[LK_TU][4], float (&nv)[LK_TU][4]) {
 #pragma unroll
         for (int u = 0; u < LK_TU; ++u) {
             f4 acc = *reinterpret_cast<const f4 *>(st.bias + u * 16 + kg * 4);
@@ -119,7 +121,7 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
                 const h8 a = *reinterpret_cast<const h8 *>(st.Ct + (u * 16 + col) * LK_STRIDE + s * 32 + kg * 8);
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bq[s], acc, 0, 0, 0);
             }
-            const int4 n4 = *reinterpret_cast<const int4 *>(st.N + u * 16 + kg * 4);
+            const f4 n4 = *reinterpret_cast<const f4 *>(st.Wt + u * 16 + kg * 4);
             nv[u][0] = n4.x;
             nv[u][1] = n4.y;
             nv[u][2] = n4.z;
@@ -131,18 +133,19 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
                     if (!((mrow[pv[v] >> 5] >> (pv[v] & 31)) & 1u)) {
-                        nv[u][v] = 0;
+                        nv[u][v] = 0.0f;
                         acc[v] = SQ_NEG_INF;
                     }
             }
 #pragma unroll
-            for (int v = 0; v < 4; ++v) x[u][v] = acc[v] * sm_scale;   // (-inf stays -inf: sm_scale > 0)
+            for (int v = 0; v < 4; ++v) x[u][v] = acc[v] * c2;   // (-inf stays -inf: sm_scale > 0)
         }
     };
 
     float m = SQ_NEG_INF, Dsum = 0.0f, thr = 0.0f, inv_D = 0.0f, m_ref = 0.0f;
     uint32_t word = 0u;
-    int cnt = 0, keys = 0;
+    int cnt = 0;
+    float keys = 0.0f;                                       // (exact in fp32, like the sizes)
     const int part = q0 / LOOKUP_ROWS, n_part = lookup_parts_for(Lq);
 
     // One loop over both passes: iteration it handles group it % ng; the stream of groups never drains in between.
@@ -157,7 +160,7 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
             if (it + 2 < 2 * ng) fetch((it + 2) % ng);
         }
         float x[LK_TU][4];
-        int nv[LK_TU][4];
+        float nv[LK_TU][4];
         scores(stage[it & 1], x, nv);
         if (it < ng) {
             // ---- pass 1: m = max over clusters with keys, D = sum N_i exp(x_i - m), per token ---------------------
@@ -168,11 +171,11 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
 #pragma unroll
                 for (int v = 0; v < 4; ++v) mt = fmaxf(mt, x[u][v]);
             if (mt != SQ_NEG_INF) {
-                Dsum *= __expf(m - mt);                      // m = -inf: Dsum is 0 and stays 0
+                Dsum *= __builtin_amdgcn_exp2f(m - mt);      // m = -inf: Dsum is 0 and stays 0
 #pragma unroll
                 for (int u = 0; u < LK_TU; ++u)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) Dsum += (float)nv[u][v] * __expf(x[u][v] - mt);
+                    for (int v = 0; v < 4; ++v) Dsum += nv[u][v] * __builtin_amdgcn_exp2f(x[u][v] - mt);
                 m = mt;
             }
             if (it == ng - 1) {                              // the four lane groups hold the other clusters of the token
@@ -180,8 +183,8 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
                 for (int off = 16; off <= 32; off <<= 1) {
                     const float mo = __shfl_xor(m, off), Do = __shfl_xor(Dsum, off);
                     const float M = fmaxf(m, mo);
-                    const float wa = m == SQ_NEG_INF ? 0.0f : __expf(m - M);
-                    const float wb = mo == SQ_NEG_INF ? 0.0f : __expf(mo - M);
+                    const float wa = m == SQ_NEG_INF ? 0.0f : __builtin_amdgcn_exp2f(m - M);
+                    const float wb = mo == SQ_NEG_INF ? 0.0f : __builtin_amdgcn_exp2f(mo - M);
                     Dsum = Dsum * wa + Do * wb;
                     m = M;
                 }
@@ -197,14 +200,14 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
                 if (t >= nt) break;                          // workgroup-uniform
                 float e[4];
 #pragma unroll
-                for (int v = 0; v < 4; ++v) e[v] = __expf(x[u][v] - m_ref);   // 0 for a cluster without keys
+                for (int v = 0; v < 4; ++v) e[v] = __builtin_amdgcn_exp2f(x[u][v] - m_ref);   // 0 for a cluster without keys
                 if (!MEAN) {
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        const bool keep = nv[u][v] > 0 && e[v] > thr;
+                        const bool keep = nv[u][v] > 0.0f && e[v] > thr;
                         word |= (uint32_t)keep << ((t & 1) * 16 + kg * 4 + v);
                         cnt += keep;
-                        keys += keep ? nv[u][v] : 0;
+                        keys += keep ? nv[u][v] : 0.0f;
                     }
                     if ((t & 1) || t == nt - 1) {            // a mask word is complete
                         word = cross16_or(word);
@@ -229,10 +232,10 @@ __global__ __launch_bounds__(256) void prefill_lookup_kernel(
     }
     if (!MEAN) {
         cnt = cross16_sum_i(cnt);
-        keys = cross16_sum_i(keys);
+        const int keys_i = cross16_sum_i((int)keys);
         if (kg == 0 && valid) {
             n_ranges[row] = cnt;
-            n_keys[row] = keys;
+            n_keys[row] = keys_i;
         }
     }
 }
