@@ -150,6 +150,10 @@ int sq_sparse_attn_decode(const sq_shape_t *shape, const void *q, const void *K_
  * In:  keep_mask u32 [B,H,Lq,ceil(C/32)], offsets i32 [H,C+1].
  * Out: out f16 [B,H,Lq,d]; lse f32 [B,H,Lq] or NULL.
  * Workspace: sq_workspace_bytes(shape, SQ_CALL_ATTN_PREFILL).
+ * Cost: the keys are walked in blocks of 64 by groups of 64 consecutive query tokens.  A block in which no token of
+ * the group kept a cluster is not read at all, provided at least an eighth of all (group, block) pairs are of that
+ * kind (counted on the device from keep_mask, no host synchronisation) and L <= 262144; otherwise every group walks
+ * every block and only the matrix products of such a block are skipped.  The result does not depend on which.
  */
 int sq_sparse_attn_prefill(const sq_shape_t *shape, const void *q, const void *K_fixed, const void *V_fixed,
                            const int32_t *offsets, const uint32_t *keep_mask,
