@@ -342,6 +342,39 @@ def test_prefill_mean_step_small(sq, oracle, case):
     compare_prefill_mean(oracle, w, P, got, stats, f"prefill-mean-step{case}")
 
 
+def test_prefill_step_queries_alike_within_a_block(sq, oracle):
+    """The whole step on queries that resemble their neighbours (each block of 64 tokens shares a direction, as
+    consecutive tokens of a prompt do): the selections of a block overlap, most key blocks are kept by no token of it,
+    and the step's attention runs through the kernel that walks only the listed blocks."""
+    w = wl.make_workload("prefill_alike", seed=29, threads=2, B=1, H=2, L=8192, C=512, Lq=192, U=64, keep_frac=0.05,
+                         causal_user=True)
+    rng = np.random.default_rng(9)
+    q = w.q.astype(np.float32)
+    for h in range(w.H):
+        for g in range(0, w.Lq, 64):
+            base = q[0, h, g]                                 # the block's first token gives the direction
+            n = min(64, w.Lq - g)
+            q[0, h, g:g + n] = base[None, :] + 0.05 * np.abs(base).mean() * rng.standard_normal((n, w.d))
+    w.q = q.astype(np.float16)
+    w = wl.calibrate(w, oracle.scores)
+    # the scenario itself, from the oracle's selection: at least an eighth of the (query block, key block) pairs are empty
+    x, m, D = oracle.centroid_score(w.q, w.centroids, w.sizes, w.sm_scale)
+    mask, _, _, _ = oracle.select(x, m, D, w.thresh, w.sizes, w.offsets)
+    keep = unpack_mask(mask, w.C)
+    nblk = (w.L + 63) // 64
+    skip = tot = 0
+    for h in range(w.H):
+        cid = np.repeat(np.arange(w.C), w.sizes[h])
+        for g in range(0, w.Lq, 64):
+            need = np.add.reduceat(keep[0, h, g:g + 64].any(0)[cid], np.arange(0, w.L, 64)) > 0
+            skip += nblk - int(need.sum()); tot += nblk
+    assert skip * 8 >= tot, (skip, tot)
+    P = sq.upload(w)
+    run_prefill_step(sq, w, P)
+    err = compare_prefill(oracle, w, P, "prefill-step-alike", logits=False)
+    print(f"queries alike within a block: skippable pairs {skip}/{tot}, max-abs err {err:.2e}", flush=True)
+
+
 def test_prefill_steps_extremes_and_optional_outputs(sq, oracle):
     base = dict(B=1, H=2, L=700, C=20, Lq=40, U=40, keep_frac=0.5, causal_user=True, seed=27, threads=1)
     for T in (2.0, -1.0):                                  # nothing kept / everything kept
