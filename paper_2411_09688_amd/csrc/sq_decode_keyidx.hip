@@ -49,6 +49,33 @@ struct SelectLds {
 // logits xv[k] and sizes nv[k] of clusters v + 1024 k), then the outputs of the slice alone: its mask words, the rows of
 // its kept keys at their positions in the row's key-index list, and (slice 0) the row's counts.  start_s: first key of
 // this thread's cluster in the slice's step (waves of the slice only).  STEPS: clusters per thread the caller holds.
+// Key-index entries of the kept clusters rec[0..n) = (first key, keys, position in the row's list) of a slice: eight
+// lanes per cluster, so 8 x (waves of the workgroup) clusters are written per round.  (A wave per cluster took eight
+// rounds for a 128-cluster slice of a row that keeps everything, and the launch waited 1.6 us for that row's workgroups;
+// measured on the whole step at 32 heads x 32K keys: a wave per cluster 28.10 us, 16 lanes 27.82, 8 lanes 27.70, the
+// group width chosen by the number of clusters 27.81.)  The eight lanes write the first 64 keys of their cluster; the
+// rest of a longer cluster is written by the whole wave.  Called by every thread of the workgroup.
+constexpr int KI_WRITE_SH = 3;                                       // log2 of the lanes per cluster
+__device__ __forceinline__ void write_key_index(const int4 *rec, int n, int32_t *__restrict__ idx_row, int L, int threads)
+{
+    constexpr int LPC = 1 << KI_WRITE_SH, PER_WAVE = 64 / LPC;
+    const int lane = threadIdx.x & 63;
+    for (int c0 = (threadIdx.x >> 6) * PER_WAVE; c0 < n; c0 += (threads >> 6) * PER_WAVE) {   // (wave-uniform bounds)
+        const int c = c0 + (lane >> KI_WRITE_SH);
+        const int4 rc = c < n ? rec[c] : make_int4(0, 0, 0, 0);
+        const int head = min(rc.y, 64);
+        for (int j = lane & (LPC - 1); j < head && rc.z + j < L; j += LPC)
+            idx_row[rc.z + j] = max(0, min(rc.x + j, L - 1));        // malformed offsets stay in the tensor
+        unsigned long long big = __ballot(rc.y > 64);
+        while (big) {                                                // wave-uniform; rare
+            const int src = __builtin_ctzll(big);                    // a lane of the long cluster's group
+            big &= ~(((1ull << LPC) - 1ull) << (src & ~(LPC - 1)));
+            const int bx = __shfl(rc.x, src), by = __shfl(rc.y, src), bz = __shfl(rc.z, src);
+            for (int j = 64 + lane; j < by && bz + j < L; j += 64) idx_row[bz + j] = max(0, min(bx + j, L - 1));
+        }
+    }
+}
+
 template <int STEPS>
 __device__ __forceinline__ void select_row_slice(float (&xv)[STEPS], const int (&nv)[STEPS], int start_s, float T, int C,
                                                  int row, int sl, uint32_t *__restrict__ keep_mask,
@@ -149,13 +176,7 @@ __device__ __forceinline__ void select_row_slice(float (&xv)[STEPS], const int (
     // kept clusters of the slice: prefix of the entry after its second wave (the same step: wv_s is even) minus its own
     const int e_next = ent0 + 2;
     const int n_slice = (e_next < KI_STEPS * KI_WAVES ? S.cnt[e_next] : tot_r) - slice_r0;
-    // Key-index list: wave j writes the key rows of kept clusters j, j + 16, ... of the slice.
-    int32_t *idx_row = plan.key_idx + (size_t)row * plan.L;
-    for (int c = wave; c < n_slice; c += KI_WAVES) {
-        const int4 rc = S.rec[c];
-        for (int j = lane; j < rc.y && rc.z + j < plan.L; j += 64)
-            idx_row[rc.z + j] = max(0, min(rc.x + j, plan.L - 1));   // malformed offsets stay in the tensor
-    }
+    write_key_index(S.rec, n_slice, plan.key_idx + (size_t)row * plan.L, plan.L, KI_THREADS);
     __syncthreads();                                         // (the caller may select another row with the same LDS)
 }
 
@@ -489,8 +510,8 @@ __global__ __launch_bounds__(MERGE_THREADS) void decode_merge_index_kernel(const
 // clusters in candidate order, each with a 16-byte record (logit, id | bit 31 if it has no keys, first key, keys), and the
 // statistics (max, sum N exp(x - max)) of every work item that scored them (see launch_gather_score).  A row can list
 // up to C candidates, so one workgroup takes a slice of CAND_SLICE of them: a quarter of its threads hold a candidate
-// each, all of them write the key-index entries (a half-wave per kept cluster; one half-wave needs about 0.2 us per
-// cluster it writes, measured, so a slice that keeps everything has 8 clusters per half-wave); the row's maximum and
+// each, all of them write the key-index entries (eight lanes per kept cluster, see write_key_index: a slice that
+// keeps everything is written in two rounds); the row's maximum and
 // normaliser are merged from the items' pairs by every workgroup (item v by thread v; wave sums ascending):
 // bit-identical whichever slice asks.  Two launches: the first counts the kept clusters and keys of every slice and
 // sets the mask bits (by cluster id, into a mask the scoring launch zeroed); the second, knowing the counts of the
@@ -606,14 +627,7 @@ __device__ __forceinline__ void cand_select_slice(const CandSelect &cs, const fl
         s_rec[r] = make_int4(rv.z, kv, s_base[1] + s_keys[wave] + incl - kv, 0);
     }
     __syncthreads();
-    // Key-index list: half-wave g writes the key rows of kept clusters g, g + 32, ... of the slice.
-    const int n_slice = s_cnt[CAND_WAVES];
-    int32_t *idx_row = plan.key_idx + (size_t)row * plan.L;
-    for (int c = tid >> 5; c < n_slice; c += CAND_THREADS / 32) {
-        const int4 rc = s_rec[c];
-        for (int t = tid & 31; t < rc.y && rc.z + t < plan.L; t += 32)
-            idx_row[rc.z + t] = max(0, min(rc.x + t, plan.L - 1));   // malformed offsets stay in the tensor
-    }
+    write_key_index(s_rec, s_cnt[CAND_WAVES], plan.key_idx + (size_t)row * plan.L, plan.L, CAND_THREADS);
     __syncthreads();                                            // (the LDS is free for the next slice)
 }
 
